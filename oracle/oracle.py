@@ -1,0 +1,182 @@
+"""ctypes front-end of the CPU oracle (pshard_oracle.c): TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this.
+It shares nothing with the HIP library and never imports it.  The layer-stack
+loops live here in plain Python; every arithmetic step is a call into the C
+file, which follows the plain definition of each operation in fp64.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pshard_oracle.c")
+_LIB = os.path.join(_HERE, "libpshard_oracle.so")
+_lib = None
+
+MAT_QKV, MAT_O, MAT_GATE, MAT_UP, MAT_DOWN = 0, 1, 2, 3, 4
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (OpenMP over output rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_half_to_double.restype = C.c_double
+        _lib.orc_half_to_double.argtypes = [C.c_uint16]
+        _lib.orc_round_f16.restype = C.c_double
+        _lib.orc_round_f16.argtypes = [C.c_double]
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _sc(scales, codes):
+    s = np.ascontiguousarray(scales)
+    assert s.dtype == np.float16
+    c = np.ascontiguousarray(codes)
+    assert c.dtype == np.uint8
+    return s, c
+
+
+def half_to_double(bits):
+    return lib().orc_half_to_double(int(bits))
+
+
+def round_f16(x):
+    return lib().orc_round_f16(float(x))
+
+
+def dequant(scales, codes):
+    s, c = _sc(scales, codes)
+    N, K = c.shape
+    W = np.empty((N, K), dtype=np.float64)
+    lib().orc_dequant(_p(s), _p(c), C.c_int64(N), C.c_int64(K), _p(W))
+    return W
+
+
+def linear(X, scales, codes):
+    X = _f64(X)
+    s, c = _sc(scales, codes)
+    N, K = c.shape
+    M = X.shape[0]
+    assert X.shape == (M, K) and s.shape == (N, K // 32)
+    Y = np.empty((M, N), dtype=np.float64)
+    lib().orc_linear(_p(X), C.c_int64(M), _p(s), _p(c), C.c_int64(N), C.c_int64(K), _p(Y))
+    return Y
+
+
+def rmsnorm(x, eps):
+    x = _f64(x)
+    y = np.empty_like(x)
+    lib().orc_rmsnorm(_p(x), C.c_int64(x.shape[0]), C.c_int64(x.shape[1]), C.c_double(eps), _p(y))
+    return y
+
+
+def swiglu(g, u):
+    g, u = _f64(g), _f64(u)
+    s = np.empty_like(g)
+    lib().orc_swiglu(_p(g), _p(u), C.c_int64(g.size), _p(s))
+    return s
+
+
+def attn_identity_v(qkv, n_q, n_kv, hd):
+    qkv = _f64(qkv)
+    M = qkv.shape[0]
+    A = np.empty((M, n_q * hd), dtype=np.float64)
+    lib().orc_attn_identity_v(_p(qkv), C.c_int64(M), n_q, n_kv, hd, _p(A))
+    return A
+
+
+def route_topk(logits, top_k):
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    M, E = lg.shape
+    idx = np.empty((M, top_k), dtype=np.int32)
+    w = np.empty((M, top_k), dtype=np.float64)
+    lib().orc_route_topk(_p(lg), C.c_int64(M), E, top_k, _p(idx), _p(w))
+    return idx, w
+
+
+def attn_half(x, cfg, qkv, o, mirror):
+    x = _f64(x)
+    M, H = x.shape
+    (qs, qc), (os_, oc) = _sc(*qkv), _sc(*o)
+    h = np.empty_like(x)
+    lib().orc_attn_half(_p(x), C.c_int64(M), H, cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
+                        C.c_double(cfg["rms_eps"]), _p(qs), _p(qc), _p(os_), _p(oc), int(mirror), _p(h))
+    return h
+
+
+def dense_ffn_half(h, cfg, gate, up, down, mirror):
+    h = _f64(h)
+    M, H = h.shape
+    (gs, gc), (us, uc), (ds, dc) = _sc(*gate), _sc(*up), _sc(*down)
+    out = np.empty_like(h)
+    lib().orc_dense_ffn_half(_p(h), C.c_int64(M), H, cfg["ffn_inter"], C.c_double(cfg["rms_eps"]),
+                             _p(gs), _p(gc), _p(us), _p(uc), _p(ds), _p(dc),
+                             int(not cfg["no_residual"]), int(mirror), _p(out))
+    return out
+
+
+def moe_ffn_half(h, cfg, logits, experts, mirror):
+    """experts: dict expert_id -> ((gs,gc),(us,uc),(ds,dc)); must hold every selected expert."""
+    h = _f64(h)
+    M, H = h.shape
+    E, k = cfg["n_experts"], cfg["top_k"]
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    assert lg.shape == (M, E)
+    keep = []
+    arrs = [(C.c_void_p * E)() for _ in range(6)]
+    for e, mats in experts.items():
+        flat = []
+        for s, c in mats:
+            s, c = _sc(s, c)
+            flat += [s, c]
+        keep.append(flat)
+        for i in range(6):
+            arrs[i][e] = flat[i].ctypes.data
+    out = np.empty_like(h)
+    lib().orc_moe_ffn_half(_p(h), C.c_int64(M), H, cfg["expert_inter"], E, k, C.c_double(cfg["rms_eps"]),
+                           _p(lg), arrs[0], arrs[1], arrs[2], arrs[3], arrs[4], arrs[5], int(mirror), _p(out))
+    return out
+
+
+def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None):
+    """Run the whole decoder weight stack on x [M][H].
+
+    weights(layer, kind, expert) -> (scales, codes) for one logical matrix (called
+    on demand so the full model never has to be resident).  logits: fp32 [L][M][E]
+    for MoE stacks.  per_layer, if a list, receives each layer's output.
+    """
+    x = _f64(x)
+    for l in range(cfg["n_layers"]):
+        h = x
+        if not cfg["no_attn"]:
+            h = attn_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), mirror)
+        if cfg["n_experts"] == 0:
+            x = dense_ffn_half(h, cfg, weights(l, MAT_GATE, None), weights(l, MAT_UP, None),
+                               weights(l, MAT_DOWN, None), mirror)
+        else:
+            idx, _ = route_topk(logits[l], cfg["top_k"])
+            experts = {int(e): (weights(l, MAT_GATE, int(e)), weights(l, MAT_UP, int(e)),
+                                weights(l, MAT_DOWN, int(e))) for e in np.unique(idx)}
+            x = moe_ffn_half(h, cfg, logits[l], experts, mirror)
+        if per_layer is not None:
+            per_layer.append(x.copy())
+    return x

@@ -1,0 +1,316 @@
+"""Pins for the CPU oracle: each oracle function is checked against something
+other than itself -- pure-Python brute force on tiny shapes, closed forms,
+numpy's independent fp16 conversion, and textbook special cases.  A dropped
+term, a wrong sign/index or a transposed operand fails at least one of them.
+(The paper prints no numeric tensor example, so there is no printed-value pin.)
+"""
+import math
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+
+
+# ---------------------------------------------------------------- fp16 helpers
+
+def test_half_to_double_all_bit_patterns_match_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    for b in range(0, 65536, 7):  # every 7th pattern plus the specials below
+        v = O.half_to_double(b)
+        r = ref[b]
+        assert (math.isnan(v) and math.isnan(r)) or v == r, b
+    for b in (0, 1, 0x3FF, 0x400, 0x7BFF, 0x7C00, 0x8000, 0x8001, 0xFBFF, 0xFC00, 0x3C00, 0xBC00):
+        assert O.half_to_double(b) == ref[b]
+
+
+def test_round_f16_matches_numpy_and_ties_to_even():
+    rng = np.random.default_rng(1)
+    xs = np.concatenate([rng.standard_normal(2000) * s for s in (1e-7, 1e-4, 1.0, 300.0, 40000.0)])
+    for x in xs:
+        assert O.round_f16(x) == float(np.float64(x).astype(np.float16)), x
+    # exact ties: 2049 is halfway between 2048 and 2050 -> even mantissa (2048); 2051 -> 2052
+    assert O.round_f16(2049.0) == 2048.0
+    assert O.round_f16(2051.0) == 2052.0
+    assert O.round_f16(-2049.0) == -2048.0
+    assert O.round_f16(65519.9) == 65504.0 and math.isinf(O.round_f16(65520.0))
+    assert O.round_f16(2.0 ** -25) == 0.0 and O.round_f16(2.0 ** -25 * 1.0001) == 2.0 ** -24
+
+
+# ---------------------------------------------------------------- dequant
+
+def test_dequant_closed_form_all_codes():
+    for d in (1.0, 0.5, 0.0234375, 2.0 ** -14, 0.0):
+        scales = np.full((1, 1), d, dtype=np.float16)
+        codes = (np.arange(32, dtype=np.uint8) % 16).reshape(1, 32)
+        W = O.dequant(scales, codes)
+        for k in range(32):
+            assert W[0, k] == float(np.float16(d)) * ((k % 16) - 8)
+
+
+def test_dequant_block_indexing():
+    # scale varies per (row, block): W[n][k] must pick scales[n][k // 32]
+    N, K = 3, 96
+    scales = (np.arange(N * 3, dtype=np.float32).reshape(N, 3) + 1).astype(np.float16)
+    codes = np.full((N, K), 9, dtype=np.uint8)
+    W = O.dequant(scales, codes)
+    for n in range(N):
+        for k in range(K):
+            assert W[n, k] == float(scales[n, k // 32])
+
+
+# ---------------------------------------------------------------- linear
+
+def _py_linear(X, scales, codes):
+    """Pure-Python brute force of Y[m][n] = sum_k X[m][k] * d[n][k//32] * (q[n][k] - 8)."""
+    M, K = len(X), len(X[0])
+    N = len(codes)
+    Y = [[0.0] * N for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                acc += float(X[m][k]) * (float(scales[n][k // 32]) * (int(codes[n][k]) - 8))
+            Y[m][n] = acc
+    return Y
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 5, 32), (3, 7, 64), (2, 33, 96)])
+def test_linear_vs_pure_python_bruteforce(M, N, K):
+    s, c = S.weight_matrix(11, 0, S.MAT_QKV, None, N, K)
+    X = S.activations(11, 0, M, K).astype(np.float64)
+    Y = O.linear(X, s, c)
+    ref = np.array(_py_linear(X.tolist(), s.astype(np.float64).tolist(), c.tolist()))
+    assert Y.shape == (M, N)
+    np.testing.assert_allclose(Y, ref, rtol=1e-13, atol=1e-13)
+
+
+def test_linear_one_hot_identity_zero_and_constant():
+    K = 64
+    X = S.activations(3, 0, 2, K).astype(np.float64)
+    ones = np.ones((K, K // 32), dtype=np.float16)
+    # identity: q=9 on the diagonal, q=8 elsewhere, d=1 -> Y = X
+    c = np.full((K, K), 8, dtype=np.uint8)
+    c[np.arange(K), np.arange(K)] = 9
+    np.testing.assert_array_equal(O.linear(X, ones, c), X)
+    # one-hot rows at a non-symmetric position: row n picks X[:, (5 n + 3) % K]
+    c = np.full((K, K), 8, dtype=np.uint8)
+    pick = (5 * np.arange(K) + 3) % K
+    c[np.arange(K), pick] = 9
+    np.testing.assert_array_equal(O.linear(X, ones, c), X[:, pick])
+    # all q=8 -> 0
+    np.testing.assert_array_equal(O.linear(X, ones, np.full((K, K), 8, dtype=np.uint8)), np.zeros((2, K)))
+    # all q=9, d=c -> c * sum(X); q=7 flips the sign
+    cst = np.full((4, K // 32), 0.25, dtype=np.float16)
+    Y = O.linear(X, cst, np.full((4, K), 9, dtype=np.uint8))
+    np.testing.assert_allclose(Y, np.repeat(0.25 * X.sum(1, keepdims=True), 4, 1), rtol=1e-14)
+    Y = O.linear(X, cst, np.full((4, K), 7, dtype=np.uint8))
+    np.testing.assert_allclose(Y, np.repeat(-0.25 * X.sum(1, keepdims=True), 4, 1), rtol=1e-14)
+
+
+def test_linear_matches_numpy_matmul_of_independent_dequant():
+    N, K, M = 48, 256, 5
+    s, c = S.weight_matrix(5, 1, S.MAT_DOWN, None, N, K)
+    X = S.activations(5, 1, M, K).astype(np.float64)
+    W = np.repeat(s.astype(np.float64), 32, axis=1) * (c.astype(np.float64) - 8.0)
+    np.testing.assert_allclose(O.linear(X, s, c), X @ W.T, rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(O.dequant(s, c), W)
+
+
+def test_generator_statistics_band():
+    # sanity band for the generator: E[q-8] = -0.5, E[(q-8)^2] = 21.5, E[d^2] = 4e-4
+    s, c = S.weight_matrix(0, 0, S.MAT_GATE, None, 512, 1024)
+    q = c.astype(np.float64) - 8
+    assert abs(q.mean() + 0.5) < 0.05 and abs((q * q).mean() - 21.5) < 0.2
+    assert abs((s.astype(np.float64) ** 2).mean() - 4e-4) < 2e-5
+    assert c.min() == 0 and c.max() == 15
+
+
+# ---------------------------------------------------------------- norm / swiglu
+
+def test_rmsnorm_closed_forms():
+    eps = 1e-6
+    for cval in (0.5, -3.0, 100.0):
+        y = O.rmsnorm(np.full((2, 64), cval), eps)
+        np.testing.assert_allclose(y, cval / math.sqrt(cval * cval + eps), rtol=1e-15)
+    x = S.activations(2, 0, 3, 128).astype(np.float64)
+    y = O.rmsnorm(x, eps)
+    ms = (x * x).mean(1)
+    np.testing.assert_allclose((y * y).mean(1), ms / (ms + eps), rtol=1e-13)
+    # direction preserved, rows independent
+    np.testing.assert_allclose(y[1] * math.sqrt(ms[1] + eps), x[1], rtol=1e-13)
+
+
+def test_swiglu_closed_forms():
+    g = np.array([0.0, 40.0, -40.0, 1.5, -1.5, 0.3])
+    u = np.array([2.0, 1.0, 1.0, -2.0, 1.0, 7.0])
+    s = O.swiglu(g, u)
+    assert s[0] == 0.0
+    assert abs(s[1] - 40.0) < 1e-12 and abs(s[2]) < 1e-14
+    for i in range(len(g)):
+        assert abs(s[i] - g[i] / (1.0 + math.exp(-g[i])) * u[i]) < 1e-15
+    # silu(-x) = silu(x) - x
+    x = np.linspace(-6, 6, 25)
+    one = np.ones_like(x)
+    np.testing.assert_allclose(O.swiglu(-x, one), O.swiglu(x, one) - x, atol=1e-14)
+    # gate and up are not interchangeable
+    assert O.swiglu(np.array([1.0]), np.array([3.0]))[0] != O.swiglu(np.array([3.0]), np.array([1.0]))[0]
+
+
+# ---------------------------------------------------------------- attention stand-in
+
+def test_identity_v_equals_softmax_attention_with_one_key():
+    n_q, n_kv, hd, M = 8, 2, 16, 3
+    rng = np.random.default_rng(4)
+    qkv = rng.standard_normal((M, (n_q + 2 * n_kv) * hd))
+    A = O.attn_identity_v(qkv, n_q, n_kv, hd)
+    # textbook grouped-query attention with context length 1 (each token attends to itself only)
+    q = qkv[:, : n_q * hd].reshape(M, n_q, hd)
+    k = qkv[:, n_q * hd:(n_q + n_kv) * hd].reshape(M, n_kv, hd)
+    v = qkv[:, (n_q + n_kv) * hd:].reshape(M, n_kv, hd)
+    ref = np.empty((M, n_q, hd))
+    for m in range(M):
+        for h in range(n_q):
+            kvh = h // (n_q // n_kv)
+            score = np.array([q[m, h] @ k[m, kvh] / math.sqrt(hd)])
+            p = np.exp(score - score.max())
+            p /= p.sum()
+            ref[m, h] = p[0] * v[m, kvh]
+    np.testing.assert_array_equal(A, ref.reshape(M, n_q * hd))
+
+
+# ---------------------------------------------------------------- routing
+
+def test_route_topk_vs_sort_bruteforce_and_invariants():
+    lg = S.router_logits(9, 0, 1, 6, 128)[0]
+    idx, w = O.route_topk(lg, 8)
+    for m in range(6):
+        order = sorted(range(128), key=lambda e: (-float(lg[m, e]), e))[:8]
+        assert list(idx[m]) == order
+        ex = [math.exp(float(lg[m, e]) - float(lg[m, order[0]])) for e in order]
+        np.testing.assert_allclose(w[m], np.array(ex) / sum(ex), rtol=1e-14)
+        # equals the full softmax renormalised over the selection
+        full = np.exp(lg[m].astype(np.float64) - lg[m].max())
+        full /= full.sum()
+        np.testing.assert_allclose(w[m], full[order] / full[order].sum(), rtol=1e-12)
+    np.testing.assert_allclose(w.sum(1), 1.0, rtol=1e-14)
+    idx2, w2 = O.route_topk(lg + np.float32(4.0), 8)   # exact shift in fp32 for these magnitudes? compare loosely
+    np.testing.assert_array_equal(idx2[:, :1], idx[:, :1])
+    # equal logits -> 1/8 each and the lowest indices win
+    idx3, w3 = O.route_topk(np.zeros((1, 128), dtype=np.float32), 8)
+    assert list(idx3[0]) == list(range(8))
+    np.testing.assert_allclose(w3, 1.0 / 8)
+    # ties inside the selection boundary go to the lower index
+    t = np.zeros((1, 16), dtype=np.float32)
+    t[0, [3, 9, 12]] = 1.0
+    t[0, 5] = 2.0
+    idx4, _ = O.route_topk(t, 4)
+    assert list(idx4[0]) == [5, 3, 9, 12]
+
+
+# ---------------------------------------------------------------- layer composition
+
+def _numpy_dequant(sc):
+    s, c = sc
+    return np.repeat(s.astype(np.float64), 32, axis=1) * (c.astype(np.float64) - 8.0)
+
+
+def _tiny_dense_cfg():
+    return dict(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn_inter=96,
+                n_experts=0, top_k=0, expert_inter=0, rms_eps=1e-6, no_attn=False, no_residual=False)
+
+
+def _weights(seed, cfg):
+    shapes = {(k, e): (N, K) for (k, e, N, K) in S.matrix_shapes(cfg)}
+
+    def get(layer, kind, expert):
+        N, K = shapes[(kind, expert)]
+        return S.weight_matrix(seed, layer, kind, expert, N, K)
+    return get
+
+
+def test_dense_stack_pure_matches_numpy_composition():
+    cfg = _tiny_dense_cfg()
+    W = _weights(21, cfg)
+    x0 = S.activations(21, 0, 3, cfg["hidden"]).astype(np.float64)
+    got = O.stack_forward(x0, cfg, W, mirror=False)
+    x = x0
+    eps = cfg["rms_eps"]
+    for l in range(cfg["n_layers"]):
+        n = x / np.sqrt((x * x).mean(1, keepdims=True) + eps)
+        qkv = n @ _numpy_dequant(W(l, S.MAT_QKV, None)).T
+        v = qkv[:, (4 + 2) * 32:].reshape(3, 2, 32)
+        A = np.repeat(v, 2, axis=1).reshape(3, 4 * 32)        # q head h reads kv head h // 2
+        h = x + A @ _numpy_dequant(W(l, S.MAT_O, None)).T
+        n2 = h / np.sqrt((h * h).mean(1, keepdims=True) + eps)
+        g = n2 @ _numpy_dequant(W(l, S.MAT_GATE, None)).T
+        u = n2 @ _numpy_dequant(W(l, S.MAT_UP, None)).T
+        s = g / (1 + np.exp(-g)) * u
+        x = h + s @ _numpy_dequant(W(l, S.MAT_DOWN, None)).T
+    np.testing.assert_allclose(got, x, rtol=1e-10, atol=1e-10)
+
+
+def test_ffn_block_config_has_no_residual():
+    cfg = dict(S.cfg_ffn_block(), hidden=64, ffn_inter=96)
+    W = _weights(22, cfg)
+    x = S.activations(22, 0, 1, 64).astype(np.float64)
+    got = O.stack_forward(x, cfg, W, mirror=False)
+    n = x / np.sqrt((x * x).mean(1, keepdims=True) + 1e-6)
+    g = n @ _numpy_dequant(W(0, S.MAT_GATE, None)).T
+    u = n @ _numpy_dequant(W(0, S.MAT_UP, None)).T
+    ref = (g / (1 + np.exp(-g)) * u) @ _numpy_dequant(W(0, S.MAT_DOWN, None)).T
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+
+
+def test_mirror_mode_rounds_only_to_fp16_grid_and_stays_close():
+    cfg = _tiny_dense_cfg()
+    W = _weights(23, cfg)
+    x0 = S.activations(23, 0, 2, cfg["hidden"])
+    pure = O.stack_forward(x0, cfg, W, mirror=False)
+    mir = O.stack_forward(x0, cfg, W, mirror=True)
+    np.testing.assert_array_equal(mir, mir.astype(np.float16).astype(np.float64))
+    assert np.abs(mir - pure).max() / np.abs(pure).max() < 5e-3
+    assert np.abs(mir - pure).max() > 0
+
+
+def _tiny_moe_cfg():
+    return dict(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn_inter=0,
+                n_experts=8, top_k=3, expert_inter=32, rms_eps=1e-6, no_attn=False, no_residual=False)
+
+
+def test_moe_with_identical_experts_equals_dense_ffn():
+    cfg = _tiny_moe_cfg()
+    H, I = cfg["hidden"], cfg["expert_inter"]
+    gate = S.weight_matrix(31, 0, S.MAT_GATE, None, I, H)
+    up = S.weight_matrix(31, 0, S.MAT_UP, None, I, H)
+    down = S.weight_matrix(31, 0, S.MAT_DOWN, None, H, I)
+    h = S.activations(31, 0, 4, H).astype(np.float64)
+    lg = S.router_logits(31, 0, 1, 4, cfg["n_experts"])[0]
+    experts = {e: (gate, up, down) for e in range(cfg["n_experts"])}
+    moe = O.moe_ffn_half(h, cfg, lg, experts, mirror=False)
+    dense_cfg = dict(cfg, ffn_inter=I, n_experts=0)
+    dense = O.dense_ffn_half(h, dense_cfg, gate, up, down, mirror=False)
+    np.testing.assert_allclose(moe, dense, rtol=1e-12, atol=1e-12)
+
+
+def test_moe_layer_matches_python_composition():
+    cfg = _tiny_moe_cfg()
+    W = _weights(32, cfg)
+    H, E, k = cfg["hidden"], cfg["n_experts"], cfg["top_k"]
+    h = S.activations(32, 0, 3, H).astype(np.float64)
+    lg = S.router_logits(32, 0, 1, 3, E)[0]
+    experts = {e: (W(0, S.MAT_GATE, e), W(0, S.MAT_UP, e), W(0, S.MAT_DOWN, e)) for e in range(E)}
+    got = O.moe_ffn_half(h, cfg, lg, experts, mirror=False)
+    n = h / np.sqrt((h * h).mean(1, keepdims=True) + 1e-6)
+    ref = h.copy()
+    for m in range(3):
+        order = sorted(range(E), key=lambda e: (-float(lg[m, e]), e))[:k]
+        ex = np.exp(lg[m, order].astype(np.float64) - float(lg[m, order[0]]))
+        w = ex / ex.sum()
+        for j, e in enumerate(order):
+            g = n[m] @ _numpy_dequant(experts[e][0]).T
+            u = n[m] @ _numpy_dequant(experts[e][1]).T
+            ref[m] += w[j] * ((g / (1 + np.exp(-g)) * u) @ _numpy_dequant(experts[e][2]).T)
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-10)
