@@ -1,0 +1,268 @@
+/*
+ * pshard -- C ABI of the pipelined-sharding hot path for one MI355X (gfx950).
+ *
+ * What the library does (paper Section 3, "Pipelined Sharding", Algorithm 1 and
+ * the GPU-only plan, "Plan One"): a decoder weight stack in a 4-bit block
+ * format is cut at sub-layer granularity into shards; a planner pins shards
+ * into a fixed VRAM budget by priority (attention before FFN) and leaves the
+ * rest in pinned host memory; at run time host shards are copied on a copy
+ * stream into a double-buffered VRAM scratch while the compute stream runs the
+ * dequantising matmul kernels on the previous shard.  The method is lossless:
+ * outputs do not depend on the budget or on where a shard lives.
+ *
+ * Conventions
+ *  - every function returns 0 (PS_OK) or a negative PS_E_* code; nothing throws
+ *    or exits across the boundary; ps_last_error() gives a thread-local text.
+ *  - "host" / "device" is stated for every pointer.  The library never
+ *    allocates device memory: the caller hands one VRAM arena whose size is the
+ *    budget.  Pinned host memory for streamed shards is allocated and owned by
+ *    the library (hipHostMalloc).
+ *  - streams are hipStream_t handles passed as void*, owned by the caller,
+ *    default priority.  One ps_stack is used from one host thread at a time.
+ *
+ * Logical weight format (benchmark definition; the paper only says "q4"):
+ *  blocks of 32 weights along K, one fp16 scale d per block, one 4-bit code q
+ *  per weight, w = d * (q - 8).  At the boundary a matrix [N outputs][K inputs]
+ *  is two host arrays: scales, fp16 bits, [N][K/32]; codes, one code per byte,
+ *  [N][K].  The physical layout in VRAM / pinned memory is private.
+ *  Constraints: K % 128 == 0, K <= 16384, output rows % 16 == 0, head_dim == 128.
+ */
+#ifndef PSHARD_H
+#define PSHARD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_OK 0
+#define PS_E_ARG (-1)    /* bad argument / unsupported shape                      */
+#define PS_E_BUDGET (-2) /* budget < workspace + two minimum scratch slots        */
+#define PS_E_HIP (-3)    /* a HIP runtime call failed (text in ps_last_error)     */
+#define PS_E_STATE (-4)  /* call order violated (e.g. forward before all loads)   */
+#define PS_E_NOMEM (-5)  /* host allocation failed                                */
+
+/* logical matrices handed to ps_stack_load_matrix */
+#define PS_MAT_QKV 0
+#define PS_MAT_O 1
+#define PS_MAT_GATE 2
+#define PS_MAT_UP 3
+#define PS_MAT_DOWN 4
+
+/* shard kinds in a plan.  GATE_UP is gate and up interleaved in 16-row tiles so
+ * that one slab yields finished SwiGLU outputs; EXPERT is one whole MoE expert
+ * (its gate/up tiles followed by its down tiles), never split. */
+#define PS_SHARD_QKV 0
+#define PS_SHARD_O 1
+#define PS_SHARD_GATE_UP 2
+#define PS_SHARD_DOWN 3
+#define PS_SHARD_EXPERT 4
+
+/* priority classes, in the paper's order (Section 3, planning phase):
+ * attention, KV cache, FFN, outputs.  This build has no KV cache or output
+ * head, the values are kept so ranks compare the same way. */
+#define PS_CLASS_ATTN 0
+#define PS_CLASS_KVCACHE 1
+#define PS_CLASS_FFN 2
+#define PS_CLASS_OUTS 3
+
+#define PS_FLAG_NO_ATTN 1u     /* layers have no attention sub-layer (FFN block only) */
+#define PS_FLAG_NO_RESIDUAL 2u /* FFN output is not added to its input                */
+
+/* token tiers of the paper's tier table (Section 3, inference phase) */
+#define PS_NTIERS 11
+/* {1, 4, 16, 32, 64, 512, 1024, 2048, 4096, 8192, 16384} -- see ps_tier_tokens */
+
+typedef struct ps_model_desc {
+    uint32_t n_layers;
+    uint32_t hidden;       /* H                                                  */
+    uint32_t n_q_heads;    /* 0 with PS_FLAG_NO_ATTN                             */
+    uint32_t n_kv_heads;
+    uint32_t head_dim;     /* must be 128 when attention is present              */
+    uint32_t ffn_inter;    /* dense FFN width I, 0 for MoE                       */
+    uint32_t n_experts;    /* 0 for dense                                        */
+    uint32_t top_k;
+    uint32_t expert_inter; /* per-expert FFN width                               */
+    uint32_t flags;        /* PS_FLAG_*                                          */
+    float rms_eps;
+} ps_model_desc;
+
+/* measured (ps_profile_measure) or caller-supplied machine profile; the
+ * planner's time estimate uses nothing else (paper Section 3, timing
+ * estimation: a kernel is priced compute-bound or memory-bound). */
+typedef struct ps_profile {
+    double h2d_gbps;               /* pinned host -> device copy rate, GB/s      */
+    double gemv_gbps;              /* weight bytes/s the decode kernels sustain  */
+    double gemm_tflops[PS_NTIERS]; /* dequant-GEMM rate at each token tier       */
+    double launch_us;              /* fixed cost per kernel launch               */
+} ps_profile;
+
+typedef struct ps_shard_info {
+    uint32_t layer;
+    uint32_t kind;          /* PS_SHARD_*                                        */
+    uint32_t expert;        /* expert id, 0xFFFFFFFF if none                     */
+    uint32_t cls;           /* PS_CLASS_*                                        */
+    uint32_t tile0;         /* first 16-row tile of the slab within its matrix   */
+    uint32_t ntiles;        /* number of 16-row tiles (EXPERT: gate/up + down)   */
+    uint32_t resident;      /* 1 = pinned in VRAM, 0 = pinned host, streamed     */
+    uint32_t priority_rank; /* position in the priority order (0 = first)        */
+    uint64_t bytes;         /* packed bytes of this shard                        */
+    uint64_t offset;        /* resident: byte offset in the arena; streamed:
+                               byte offset in the library's host shard pool      */
+} ps_shard_info;
+
+typedef struct ps_plan_summary_t {
+    uint64_t budget_bytes;
+    uint64_t weight_bytes;    /* all shards                                      */
+    uint64_t resident_bytes;  /* pinned in VRAM                                  */
+    uint64_t streamed_bytes;  /* left in host memory (whole stack)               */
+    uint64_t scratch_bytes;   /* n_slots * slot_bytes                            */
+    uint64_t workspace_bytes; /* activations and tables for n_tokens             */
+    uint64_t slot_bytes;
+    uint32_t n_slots;         /* 0 or 2                                          */
+    uint32_t n_shards;
+    uint32_t n_tokens;
+    uint32_t tier;            /* index into the tier table used for the estimate */
+    double est_step_ms;       /* sum over shards of max(compute, next copy)      */
+    double est_streamed_bytes_per_step; /* expected bytes crossing PCIe per step */
+} ps_plan_summary_t;
+
+typedef struct ps_stats {
+    uint64_t resident_bytes_step; /* weight bytes read in place in the last forward */
+    uint64_t streamed_bytes_step; /* weight bytes copied H2D in the last forward    */
+    uint32_t n_copies, n_kernels;
+    /* the rest is valid only after a forward with profiling on, once complete   */
+    double copy_ms;     /* sum of copy durations on the copy stream              */
+    double compute_ms;  /* sum of kernel durations on the compute stream         */
+    double wall_ms;     /* first op start to last op end                         */
+    double overlap;     /* (copy + compute - wall) / min(copy, compute), 0 if either is 0 */
+    double h2d_gbps;    /* streamed_bytes_step / copy_ms                         */
+} ps_stats;
+
+/* one operation of an executor schedule, as plain data (see ps_schedule_*) */
+#define PS_OP_COPY 0
+#define PS_OP_KERNEL 1
+#define PS_K_RINV 0
+#define PS_K_QKV 1
+#define PS_K_O 2
+#define PS_K_GATE_UP 3
+#define PS_K_DOWN 4
+#define PS_K_ROUTE 5
+#define PS_K_EXPERT_GATE_UP 6
+#define PS_K_EXPERT_DOWN 7
+#define PS_K_COMBINE 8
+#define PS_OPF_WAIT_SLOT_FREE 1u  /* copy stream waits for slot_free[slot]        */
+#define PS_OPF_WAIT_ROUTER 2u     /* copy stream waits for router_done[layer]     */
+#define PS_OPF_RECORD_READY 4u    /* copy stream records slot_ready[slot] after   */
+#define PS_OPF_WAIT_READY 8u      /* compute stream waits for slot_ready[slot]    */
+#define PS_OPF_RECORD_FREE 16u    /* compute stream records slot_free[slot] after */
+#define PS_OPF_RECORD_ROUTER 32u  /* compute stream records router_done[layer]    */
+
+typedef struct ps_op_info {
+    uint32_t type;   /* PS_OP_*                                                  */
+    uint32_t kernel; /* PS_K_* for kernels                                       */
+    uint32_t layer;
+    uint32_t flags;  /* PS_OPF_*                                                 */
+    int32_t slot;    /* scratch slot touched, -1 if none                         */
+    uint32_t shard0; /* first plan shard this op copies / reads                  */
+    uint32_t nshards;/* number of consecutive task entries (expert batches) or 1 */
+    uint64_t slot_offset; /* byte offset inside the slot (copy destination / kernel source) */
+    uint64_t bytes;  /* weight bytes copied or read                              */
+} ps_op_info;
+
+typedef struct ps_plan ps_plan;
+typedef struct ps_schedule ps_schedule;
+typedef struct ps_stack ps_stack;
+
+/* thread-local description of the last error on this thread (never NULL) */
+const char *ps_last_error(void);
+
+/* token count of tier t (t < PS_NTIERS), and the smallest tier holding n_tokens */
+uint32_t ps_tier_tokens(uint32_t t);
+uint32_t ps_tier_for_tokens(uint32_t n_tokens);
+
+/* packed bytes of a [rows][K] matrix in the private device layout (host only) */
+uint64_t ps_packed_bytes(uint32_t rows, uint32_t K);
+
+/* Pack a whole logical matrix (host scales fp16 [rows][K/32], host codes u8 [rows][K]) into
+ * the private layout, rows in natural order; out: host, ps_packed_bytes(rows, K) bytes.
+ * Layout: 16-row tiles, each a run of scale groups of up to 8 super-blocks (128 k); a
+ * super-block is 64 lanes x 16 B, lane c*16+i = block 4*sb+c of row i, dword kk = weights
+ * 8*kk..8*kk+7 of the block, weight t in nibble (t>>1) + 4*(t&1); after a group's
+ * super-blocks come 64 lanes x 8 fp16 scales (lane c*16+i, entry s = block 4*(8g+s)+c). */
+int32_t ps_pack_matrix(const uint16_t *scales, const uint8_t *codes, uint32_t rows, uint32_t K,
+                       uint8_t *out);
+
+/* Planning phase for one token count (Algorithm 1, PlanningPhase and
+ * PinShardsToGPU; GPU-only plan).  Host only, no GPU needed.
+ *  model, profile: host, copied.  expert_freq: host [n_layers*n_experts]
+ *  selection frequencies used to rank experts (NULL: rank by layer, expert).
+ *  *out is owned by the caller until ps_plan_destroy.
+ *  PS_E_BUDGET when the budget cannot hold the workspace plus two slots. */
+int32_t ps_plan_create(const ps_model_desc *model, uint64_t vram_budget_bytes,
+                       const ps_profile *profile, uint32_t n_tokens,
+                       const float *expert_freq, ps_plan **out);
+int32_t ps_plan_summary(const ps_plan *plan, ps_plan_summary_t *out);
+/* shards are listed in execution (topological) order */
+int32_t ps_plan_get_shard(const ps_plan *plan, uint32_t i, ps_shard_info *out);
+void ps_plan_destroy(ps_plan *plan);
+
+/* The executor's op list for one forward, as plain data (host only, no GPU).
+ * router_logits: host fp32 [n_layers][n_tokens][n_experts], NULL for dense.
+ * ps_schedule_validate proves with vector clocks over the two streams that no
+ * kernel reads a slot before its copy completed and no copy overwrites a slot
+ * before its last reader finished; returns PS_E_STATE with a text otherwise. */
+int32_t ps_schedule_create(const ps_plan *plan, const float *router_logits, ps_schedule **out);
+int32_t ps_schedule_num_ops(const ps_schedule *s, uint32_t *n);
+int32_t ps_schedule_get_op(const ps_schedule *s, uint32_t i, ps_op_info *out);
+int32_t ps_schedule_validate(const ps_schedule *s);
+void ps_schedule_destroy(ps_schedule *s);
+
+/* MoE routing on the host with the same rule as the device kernel: the top_k
+ * largest fp32 logits, ties to the lower index, in descending order.
+ * logits host [n_tokens][n_experts] -> idx host [n_tokens][top_k]. */
+int32_t ps_route_host(const float *logits, uint32_t n_tokens, uint32_t n_experts,
+                      uint32_t top_k, int32_t *idx);
+
+/* Measure the machine profile on the current device (Section 3, install phase:
+ * several asynchronous launches timed together).  scratch: device, at least
+ * 256 MiB, contents destroyed.  Streams as for ps_stack_create. */
+int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
+                           void *compute_stream, void *copy_stream, ps_profile *out);
+
+/* Bind a plan to a VRAM arena (device, 256-byte aligned, arena_bytes >= the
+ * plan's budget) and two streams.  Allocates pinned host memory for the
+ * streamed shards.  The plan is copied; the arena and streams must outlive the stack. */
+int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes,
+                        void *compute_stream, void *copy_stream, ps_stack **out);
+/* Pack one logical matrix (host scales fp16 [N][K/32], host codes u8 [N][K]) into
+ * every shard that covers it: resident slabs are copied to the arena
+ * (synchronous), streamed slabs into the pinned pool.  expert: id or 0xFFFFFFFF. */
+int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_t expert,
+                             const uint16_t *scales, const uint8_t *codes);
+/* One pass over the whole stack (Algorithm 1, RunInTopologicalOrder).
+ *  x_in, x_out: device fp16 [n_tokens][hidden], caller-owned, may not alias.
+ *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.
+ * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
+int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
+/* record per-op timing events in the next forwards (adds event overhead) */
+int32_t ps_stack_set_profiling(ps_stack *st, int32_t on);
+/* blocks until both streams are idle when profiling is on */
+int32_t ps_stack_stats(ps_stack *st, ps_stats *out);
+/* device pointers into the workspace for inspection by tests (fp16 unless noted):
+ * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
+ * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k] */
+int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes);
+void ps_stack_destroy(ps_stack *st);
+
+/* Diagnostic: one v_mfma_f32_16x16x32_f16 with A = unit at (row pi, k pk) and B = unit at
+ * (k pk, column pj); out_dev: device fp32 [64 lanes][4 registers] receives the accumulator.
+ * Used by a GPU test to confirm the operand lane layout the GEMM kernel relies on.
+ * pi, pj in 0..15, pk in 0..31; asynchronous on stream. */
+int32_t ps_mfma_probe(int32_t pi, int32_t pk, int32_t pj, float *out_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSHARD_H */

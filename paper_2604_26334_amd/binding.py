@@ -1,0 +1,331 @@
+"""ctypes binding of libpshard.so: same names as include/pshard.h, argument marshalling only.
+
+The library must have been built (python -m paper_2604_26334_amd.build, or
+__graft_entry__.build()); loading fails loudly otherwise -- there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpshard.so")
+
+PS_OK, PS_E_ARG, PS_E_BUDGET, PS_E_HIP, PS_E_STATE, PS_E_NOMEM = 0, -1, -2, -3, -4, -5
+PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN = 0, 1, 2, 3, 4
+PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT = 0, 1, 2, 3, 4
+PS_CLASS_ATTN, PS_CLASS_KVCACHE, PS_CLASS_FFN, PS_CLASS_OUTS = 0, 1, 2, 3
+PS_FLAG_NO_ATTN, PS_FLAG_NO_RESIDUAL = 1, 2
+PS_NTIERS = 11
+PS_OP_COPY, PS_OP_KERNEL = 0, 1
+(PS_K_RINV, PS_K_QKV, PS_K_O, PS_K_GATE_UP, PS_K_DOWN, PS_K_ROUTE, PS_K_EXPERT_GATE_UP,
+ PS_K_EXPERT_DOWN, PS_K_COMBINE) = range(9)
+(PS_OPF_WAIT_SLOT_FREE, PS_OPF_WAIT_ROUTER, PS_OPF_RECORD_READY, PS_OPF_WAIT_READY,
+ PS_OPF_RECORD_FREE, PS_OPF_RECORD_ROUTER) = 1, 2, 4, 8, 16, 32
+NO_EXPERT = 0xFFFFFFFF
+
+
+class ps_model_desc(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
+                                          "ffn_inter", "n_experts", "top_k", "expert_inter", "flags")] + \
+               [("rms_eps", C.c_float)]
+
+
+class ps_profile(C.Structure):
+    _fields_ = [("h2d_gbps", C.c_double), ("gemv_gbps", C.c_double),
+                ("gemm_tflops", C.c_double * PS_NTIERS), ("launch_us", C.c_double)]
+
+
+class ps_shard_info(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("layer", "kind", "expert", "cls", "tile0", "ntiles", "resident",
+                                          "priority_rank")] + [("bytes", C.c_uint64), ("offset", C.c_uint64)]
+
+
+class ps_plan_summary_t(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("budget_bytes", "weight_bytes", "resident_bytes", "streamed_bytes",
+                                          "scratch_bytes", "workspace_bytes", "slot_bytes")] + \
+               [(n, C.c_uint32) for n in ("n_slots", "n_shards", "n_tokens", "tier")] + \
+               [("est_step_ms", C.c_double), ("est_streamed_bytes_per_step", C.c_double)]
+
+
+class ps_stats(C.Structure):
+    _fields_ = [("resident_bytes_step", C.c_uint64), ("streamed_bytes_step", C.c_uint64),
+                ("n_copies", C.c_uint32), ("n_kernels", C.c_uint32)] + \
+               [(n, C.c_double) for n in ("copy_ms", "compute_ms", "wall_ms", "overlap", "h2d_gbps")]
+
+
+class ps_op_info(C.Structure):
+    _fields_ = [("type", C.c_uint32), ("kernel", C.c_uint32), ("layer", C.c_uint32), ("flags", C.c_uint32),
+                ("slot", C.c_int32), ("shard0", C.c_uint32), ("nshards", C.c_uint32),
+                ("slot_offset", C.c_uint64), ("bytes", C.c_uint64)]
+
+
+EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
+           "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
+           "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
+           "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
+           "ps_stack_forward", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_debug_buffer",
+           "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix"]
+
+_lib = None
+
+
+def lib():
+    """Load libpshard.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpshard.so is not built: run `python -m paper_2604_26334_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32
+        L.ps_last_error.restype = C.c_char_p
+        L.ps_last_error.argtypes = []
+        L.ps_tier_tokens.restype = u32
+        L.ps_tier_tokens.argtypes = [u32]
+        L.ps_tier_for_tokens.restype = u32
+        L.ps_tier_for_tokens.argtypes = [u32]
+        L.ps_packed_bytes.restype = u64
+        L.ps_packed_bytes.argtypes = [u32, u32]
+        sig = {
+            "ps_plan_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), u32, vp, C.POINTER(vp)],
+            "ps_plan_summary": [vp, C.POINTER(ps_plan_summary_t)],
+            "ps_plan_get_shard": [vp, u32, C.POINTER(ps_shard_info)],
+            "ps_schedule_create": [vp, vp, C.POINTER(vp)],
+            "ps_schedule_num_ops": [vp, C.POINTER(u32)],
+            "ps_schedule_get_op": [vp, u32, C.POINTER(ps_op_info)],
+            "ps_schedule_validate": [vp],
+            "ps_route_host": [vp, u32, u32, u32, vp],
+            "ps_profile_measure": [vp, u64, vp, vp, C.POINTER(ps_profile)],
+            "ps_stack_create": [vp, vp, u64, vp, vp, C.POINTER(vp)],
+            "ps_stack_load_matrix": [vp, u32, u32, u32, vp, vp],
+            "ps_stack_forward": [vp, vp, vp, vp],
+            "ps_stack_set_profiling": [vp, i32],
+            "ps_stack_stats": [vp, C.POINTER(ps_stats)],
+            "ps_stack_debug_buffer": [vp, u32, C.POINTER(vp), C.POINTER(u64)],
+            "ps_mfma_probe": [i32, i32, i32, vp, vp],
+            "ps_pack_matrix": [vp, vp, u32, u32, vp],
+        }
+        for name, args in sig.items():
+            f = getattr(L, name)
+            f.restype = i32
+            f.argtypes = args
+        for name in ("ps_plan_destroy", "ps_schedule_destroy", "ps_stack_destroy"):
+            f = getattr(L, name)
+            f.restype = None
+            f.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+class PshardError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("pshard error %d: %s" % (code, text))
+        self.code = code
+
+
+def _check(rc):
+    if rc != PS_OK:
+        raise PshardError(rc, lib().ps_last_error().decode())
+
+
+def model_desc(cfg):
+    """ps_model_desc from a config dict (keys as in synth_inputs.cfg_*)."""
+    flags = (PS_FLAG_NO_ATTN if cfg.get("no_attn") else 0) | (PS_FLAG_NO_RESIDUAL if cfg.get("no_residual") else 0)
+    return ps_model_desc(cfg["n_layers"], cfg["hidden"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
+                         cfg["ffn_inter"], cfg["n_experts"], cfg["top_k"], cfg["expert_inter"], flags,
+                         cfg["rms_eps"])
+
+
+def make_profile(h2d_gbps=55.0, gemv_gbps=4000.0, gemm_tflops=400.0, launch_us=3.0):
+    p = ps_profile()
+    p.h2d_gbps, p.gemv_gbps, p.launch_us = h2d_gbps, gemv_gbps, launch_us
+    for t in range(PS_NTIERS):
+        p.gemm_tflops[t] = gemm_tflops[t] if hasattr(gemm_tflops, "__len__") else gemm_tflops
+    return p
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.c_void_p)
+
+
+class Plan:
+    """ps_plan_create / ps_plan_summary / ps_plan_get_shard / ps_plan_destroy."""
+
+    def __init__(self, cfg, budget_bytes, n_tokens, profile=None, expert_freq=None):
+        self.cfg = cfg
+        self.desc = model_desc(cfg)
+        self.profile = profile if profile is not None else make_profile()
+        self.h = C.c_void_p()
+        freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
+        _check(lib().ps_plan_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), int(n_tokens),
+                                    _ptr(freq), C.byref(self.h)))
+
+    def summary(self):
+        s = ps_plan_summary_t()
+        _check(lib().ps_plan_summary(self.h, C.byref(s)))
+        return s
+
+    def shards(self):
+        n = self.summary().n_shards
+        out = []
+        for i in range(n):
+            s = ps_shard_info()
+            _check(lib().ps_plan_get_shard(self.h, i, C.byref(s)))
+            out.append(s)
+        return out
+
+    def schedule(self, router_logits=None):
+        return Schedule(self, router_logits)
+
+    def close(self):
+        if self.h:
+            lib().ps_plan_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Schedule:
+    """ps_schedule_create / ps_schedule_get_op / ps_schedule_validate."""
+
+    def __init__(self, plan, router_logits=None):
+        self.h = C.c_void_p()
+        lg = None if router_logits is None else np.ascontiguousarray(router_logits, dtype=np.float32)
+        _check(lib().ps_schedule_create(plan.h, _ptr(lg), C.byref(self.h)))
+
+    def ops(self):
+        n = C.c_uint32()
+        _check(lib().ps_schedule_num_ops(self.h, C.byref(n)))
+        out = []
+        for i in range(n.value):
+            o = ps_op_info()
+            _check(lib().ps_schedule_get_op(self.h, i, C.byref(o)))
+            out.append(o)
+        return out
+
+    def validate(self):
+        _check(lib().ps_schedule_validate(self.h))
+
+    def __del__(self):
+        try:
+            if self.h:
+                lib().ps_schedule_destroy(self.h)
+        except Exception:
+            pass
+
+
+def pack_matrix(scales, codes):
+    s = np.ascontiguousarray(scales)
+    c = np.ascontiguousarray(codes)
+    assert s.dtype == np.float16 and c.dtype == np.uint8
+    rows, K = c.shape
+    out = np.empty(lib().ps_packed_bytes(rows, K), dtype=np.uint8)
+    _check(lib().ps_pack_matrix(_ptr(s), _ptr(c), rows, K, _ptr(out)))
+    return out
+
+
+def route_host(logits, top_k):
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    M, E = lg.shape
+    idx = np.empty((M, top_k), dtype=np.int32)
+    _check(lib().ps_route_host(_ptr(lg), M, E, top_k, _ptr(idx)))
+    return idx
+
+
+class Stack:
+    """ps_stack_*: binds a plan to a torch-owned VRAM arena and two torch streams."""
+
+    def __init__(self, plan, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.plan = plan
+        self.device = torch.device(device)
+        s = plan.summary()
+        self.M = s.n_tokens
+        self.H = plan.cfg["hidden"]
+        self.arena = torch.empty(int(s.budget_bytes), dtype=torch.uint8, device=self.device)
+        self.compute = torch.cuda.Stream(device=self.device)
+        self.copy = torch.cuda.Stream(device=self.device)
+        self.h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().ps_stack_create(plan.h, self.arena.data_ptr(), self.arena.numel(),
+                                         self.compute.cuda_stream, self.copy.cuda_stream, C.byref(self.h)))
+
+    def load_matrix(self, layer, mat, expert, scales, codes):
+        s = np.ascontiguousarray(scales)
+        c = np.ascontiguousarray(codes)
+        assert s.dtype == np.float16 and c.dtype == np.uint8
+        e = NO_EXPERT if expert is None else int(expert)
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_load_matrix(self.h, layer, mat, e, _ptr(s), _ptr(c)))
+
+    def forward(self, x_in, x_out, router_logits=None):
+        """x_in, x_out: torch fp16 CUDA tensors [M][H]; asynchronous on self.compute."""
+        assert x_in.dtype == self.torch.float16 and x_out.dtype == self.torch.float16
+        assert x_in.is_contiguous() and x_out.is_contiguous()
+        assert tuple(x_in.shape) == (self.M, self.H) and tuple(x_out.shape) == (self.M, self.H)
+        lg = None if router_logits is None else np.ascontiguousarray(router_logits, dtype=np.float32)
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_forward(self.h, x_in.data_ptr(), x_out.data_ptr(), _ptr(lg)))
+
+    def synchronize(self):
+        self.copy.synchronize()
+        self.compute.synchronize()
+
+    def set_profiling(self, on):
+        _check(lib().ps_stack_set_profiling(self.h, 1 if on else 0))
+
+    def stats(self):
+        s = ps_stats()
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_stats(self.h, C.byref(s)))
+        return s
+
+    def debug_buffer(self, which, dtype, shape):
+        """Copy of a workspace buffer as a numpy array (synchronises first)."""
+        self.synchronize()
+        p, n = C.c_void_p(), C.c_uint64()
+        _check(lib().ps_stack_debug_buffer(self.h, which, C.byref(p), C.byref(n)))
+        off = p.value - self.arena.data_ptr()
+        raw = self.arena[off:off + n.value].cpu().numpy()
+        return raw.view(dtype)[: int(np.prod(shape))].reshape(shape)
+
+    def close(self):
+        if self.h:
+            with self.torch.cuda.device(self.device):
+                lib().ps_stack_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def profile_measure(scratch_bytes=1 << 30, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=dev)
+    s1, s2 = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    p = ps_profile()
+    with torch.cuda.device(dev):
+        _check(lib().ps_profile_measure(scratch.data_ptr(), scratch_bytes, s1.cuda_stream, s2.cuda_stream, C.byref(p)))
+    torch.cuda.synchronize(dev)
+    return p
+
+
+def load_synthetic(stack, cfg, seed, weight_fn):
+    """Load every logical matrix of cfg into the stack; weight_fn(seed, layer, kind, expert, N, K)
+    returns (scales, codes).  Matrices are generated one at a time and dropped."""
+    import synth_inputs as S
+    for layer in range(cfg["n_layers"]):
+        for kind, expert, N, K in S.matrix_shapes(cfg):
+            sc, cd = weight_fn(seed, layer, kind, expert, N, K)
+            stack.load_matrix(layer, kind, expert, sc, cd)

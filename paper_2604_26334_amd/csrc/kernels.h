@@ -1,0 +1,61 @@
+// Launch interface between the executor (stack.hip) and the device kernels (kernels.hip).
+#pragma once
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "ps_internal.h"
+
+namespace ps {
+
+enum { GEMV_PLAIN = 0, GEMV_RESID = 1, GEMV_GATE_UP = 2, GEMV_F32 = 3 };
+enum { GEMM_PLAIN = 0, GEMM_RESID = 1, GEMM_GATE_UP = 2, GEMM_F32 = 3 };
+
+// One token.  PLAIN: out = rinv * (W x) with rinv from x's RMS; RESID: out = res + W x;
+// GATE_UP: out = silu(rinv * gate) * (rinv * up); F32: out_f32 = W x.
+struct GemvArgs {
+    const uint4 *W;       // first tile of the slab (ignored when tasks != null)
+    uint32_t nunits;      // row-tiles (GATE_UP: tile pairs) in this launch
+    uint32_t tile_u4;     // tile stride in 16-byte units
+    uint32_t nsb, ngroups, K;
+    const __half *x;      // input row
+    uint32_t x_off, x_group;   // input column map (identity: 0, 1)
+    uint32_t x_stride;    // grouped launches: elements between input rows
+    float eps;
+    const __half *res;    // RESID: residual row or null
+    __half *out;
+    float *out_f32;
+    uint32_t out_row0;    // first output element of the slab
+    uint32_t out_stride;  // grouped launches: elements between output rows
+    uint32_t top_k;
+    const DeviceTask *tasks;  // grouped (MoE) launch: one expert per blockIdx.y
+    const int32_t *pairs;
+};
+
+// M tokens on the matrix cores.  Same modes; rinv comes from a buffer.
+struct GemmArgs {
+    const uint4 *W;
+    uint32_t ntiles;      // row-tiles in this launch
+    uint32_t tile_u4, nsb;
+    uint32_t M;
+    const __half *x;
+    uint32_t x_stride, x_off, x_group;
+    const float *rinv;
+    const __half *res;
+    __half *out;
+    float *out_f32;
+    uint32_t out_stride, out_row0, top_k;
+    const DeviceTask *tasks;
+    const int32_t *pairs;
+};
+
+uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units);
+hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st);
+hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st);
+hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st);
+hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
+                        hipStream_t st);
+hipError_t launch_combine(const __half *h, const float *y, const float *w, uint32_t M, uint32_t H, uint32_t top_k,
+                          int residual, __half *out, hipStream_t st);
+hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st);
+
+}  // namespace ps

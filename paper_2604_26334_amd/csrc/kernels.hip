@@ -1,0 +1,518 @@
+// CDNA4 (gfx950) kernels of the pipelined-sharding hot path: the dequantising matmuls of
+// the decoder sub-layers with their fused RMSNorm / SwiGLU / residual steps, MoE routing and
+// the expert combine.  Weight layout: see pack.cpp.  wave64 only.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace ps {
+
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ h2_t as_h2(uint32_t v) { return __builtin_bit_cast(h2_t, v); }
+
+// 8 codes of one dword -> four fp16 pairs holding (q - 8), exact.  Codes sit in the
+// mantissa of 1024 + q (low nibbles) or 1024 + 16 q (next nibbles).
+__device__ __forceinline__ void dequant8(uint32_t v, h2_t w[4]) {
+    const h2_t k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+    const h2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const h2_t k72 = {(_Float16)72.0f, (_Float16)72.0f};
+    const uint32_t v8 = v >> 8;
+    w[0] = as_h2((v & 0x000F000Fu) | 0x64006400u) - k1032;
+    w[1] = as_h2((v & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+    w[2] = as_h2((v8 & 0x000F000Fu) | 0x64006400u) - k1032;
+    w[3] = as_h2((v8 & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+}
+
+__device__ __forceinline__ float dot8(uint32_t v, uint4 x, float acc) {
+    h2_t w[4];
+    dequant8(v, w);
+    acc = __builtin_amdgcn_fdot2(w[0], as_h2(x.x), acc, false);
+    acc = __builtin_amdgcn_fdot2(w[1], as_h2(x.y), acc, false);
+    acc = __builtin_amdgcn_fdot2(w[2], as_h2(x.z), acc, false);
+    acc = __builtin_amdgcn_fdot2(w[3], as_h2(x.w), acc, false);
+    return acc;
+}
+
+__device__ __forceinline__ float half_of(uint4 v, int s) {  // s-th fp16 of a 16-byte vector
+    const uint32_t d = (s < 2) ? v.x : (s < 4) ? v.y : (s < 6) ? v.z : v.w;
+    const uint16_t h = (s & 1) ? (uint16_t)(d >> 16) : (uint16_t)(d & 0xFFFFu);
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+__device__ __forceinline__ float sumsq8(uint4 v) {
+    float s = 0.f;
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const h2_t p = as_h2(d[i]);
+        s += (float)p.x * (float)p.x;
+        s += (float)p.y * (float)p.y;
+    }
+    return s;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+
+// source column of logical input column k: identity, or the identity-on-V attention
+// stand-in where query head h reads kv head h / group (head_dim 128)
+__device__ __forceinline__ uint32_t gather_col(uint32_t k, uint32_t x_off, uint32_t group) {
+    return x_off + ((k >> 7) / group) * 128u + (k & 127u);
+}
+
+// ------------------------------------------------------------------------------------
+// Decode kernel, one token: fused 4-bit dequant GEMV.  256 threads = 4 waves.  A "unit" is
+// one row-tile (16 outputs) or, for GATE_UP, a gate tile plus its up tile.  KSPLIT waves
+// share a unit, each taking every KSPLIT-th scale group of K; partial sums meet in LDS in
+// a fixed order, so a row's result does not depend on which slab or slot it came from.
+// x (with the RMSNorm sum of squares) is staged once per workgroup in LDS, permuted so that
+// the four 16-byte reads of a lane's block hit distinct banks.
+// ------------------------------------------------------------------------------------
+template <int MODE, int KSPLIT>
+__global__ __launch_bounds__(256) void gemv_w4_kernel(GemvArgs a) {
+    extern __shared__ uint4 lds[];
+    uint4 *lds_x = lds;                                        // K/8 chunks
+    float *red = reinterpret_cast<float *>(lds + a.K / 8);      // [4 waves][2][16] + 4
+    constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
+    constexpr int UNITS = 4 / KSPLIT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, c = lane >> 4;
+
+    const uint4 *W = a.W;
+    const __half *x = a.x;
+    uint32_t out_row_base = a.out_row0;
+    __half *out = a.out;
+    float *out_f32 = a.out_f32;
+    if (a.tasks) {  // grouped launch: blockIdx.y selects the expert
+        const DeviceTask t = a.tasks[blockIdx.y];
+        const uint32_t pair = (uint32_t)a.pairs[t.pair0];
+        if (MODE == GEMV_GATE_UP) {
+            W = reinterpret_cast<const uint4 *>(t.w_gate_up);
+            x = a.x + (size_t)(pair / a.top_k) * a.x_stride;
+            out = a.out + (size_t)pair * a.out_stride;
+        } else {
+            W = reinterpret_cast<const uint4 *>(t.w_down);
+            x = a.x + (size_t)pair * a.x_stride;
+            out_f32 = a.out_f32 + (size_t)pair * a.out_stride;
+        }
+    }
+
+    // stage x, accumulate sum of squares
+    float ss = 0.f;
+    for (uint32_t q = tid; q < a.K / 8; q += 256) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(x + gather_col(q * 8, a.x_off, a.x_group));
+        const uint32_t b = q >> 2, p = q & 3, sb = b >> 2, cc = b & 3;
+        lds_x[sb * 16 + p * 4 + cc] = v;
+        if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) ss += sumsq8(v);
+    }
+    float rinv = 1.f;
+    if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) {
+        ss = wave_sum(ss);
+        if (lane == 0) red[128 + wave] = ss;
+    }
+    __syncthreads();
+    if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) {
+        const float tot = (red[128] + red[129]) + (red[130] + red[131]);
+        rinv = rsqrtf(tot / (float)a.K + a.eps);
+    }
+
+    const uint32_t unit = blockIdx.x * UNITS + wave / KSPLIT;
+    const uint32_t kpart = wave % KSPLIT;
+    const bool active = unit < a.nunits;
+    float acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+
+    if (active) {
+        for (uint32_t g = kpart; g < a.ngroups; g += KSPLIT) {
+            const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
+            uint4 sc[NT], wq[NT][8];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const uint4 *gb = W + (size_t)(unit * NT + t) * a.tile_u4 + (size_t)g * (9 * 64);
+                sc[t] = gb[nsb_g * 64 + lane];
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    if ((uint32_t)s < nsb_g) wq[t][s] = gb[s * 64 + lane];
+            }
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                if ((uint32_t)s < nsb_g) {
+                    const uint32_t sbi = g * 8 + s;
+                    uint4 xv[4];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) xv[p] = lds_x[sbi * 16 + p * 4 + c];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        float part = 0.f;
+                        part = dot8(wq[t][s].x, xv[0], part);
+                        part = dot8(wq[t][s].y, xv[1], part);
+                        part = dot8(wq[t][s].z, xv[2], part);
+                        part = dot8(wq[t][s].w, xv[3], part);
+                        acc[t] = fmaf(half_of(sc[t], s), part, acc[t]);
+                    }
+                }
+            }
+        }
+    }
+    // the 4 lanes of a row (c = 0..3) meet, then the KSPLIT waves of a unit
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        acc[t] += __shfl_xor(acc[t], 16, 64);
+        acc[t] += __shfl_xor(acc[t], 32, 64);
+    }
+    if (KSPLIT > 1) {
+        if (c == 0) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) red[(wave * 2 + t) * 16 + i] = acc[t];
+        }
+        __syncthreads();
+        if (kpart == 0 && c == 0) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                float v = red[(wave * 2 + t) * 16 + i];
+#pragma unroll
+                for (int k = 1; k < KSPLIT; ++k) v += red[((wave + k) * 2 + t) * 16 + i];
+                acc[t] = v;
+            }
+        }
+    }
+    if (!active || kpart != 0 || c != 0) return;
+    const uint32_t row = out_row_base + unit * 16 + i;
+    if (MODE == GEMV_PLAIN) {
+        out[row] = __float2half(rinv * acc[0]);
+    } else if (MODE == GEMV_RESID) {
+        const float r = a.res ? __half2float(a.res[row]) : 0.f;
+        out[row] = __float2half(r + acc[0]);
+    } else if (MODE == GEMV_GATE_UP) {
+        out[row] = __float2half(silu(rinv * acc[0]) * (rinv * acc[NT - 1]));
+    } else {
+        out_f32[row] = acc[0];
+    }
+}
+
+template <int MODE, int KSPLIT>
+static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
+    constexpr int UNITS = 4 / KSPLIT;
+    dim3 grid((a.nunits + UNITS - 1) / UNITS, ntasks ? ntasks : 1);
+    const size_t lds = (size_t)a.K * 2 + (128 + 4) * sizeof(float);
+    hipLaunchKernelGGL((gemv_w4_kernel<MODE, KSPLIT>), grid, dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+// KSPLIT depends on the matrix (K and its total tile count) only, never on the slab, so
+// every placement adds the same partial sums in the same order.
+uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
+    if (ngroups >= 4 && total_units < 2048) return 4;
+    if (ngroups >= 2 && total_units < 4096) return 2;
+    return 1;
+}
+
+hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
+#define PS_GEMV_CASE(M)                                                   \
+    case M:                                                               \
+        if (ksplit == 4) return launch_gemv_t<M, 4>(a, ntasks, st);       \
+        if (ksplit == 2) return launch_gemv_t<M, 2>(a, ntasks, st);       \
+        return launch_gemv_t<M, 1>(a, ntasks, st);
+    switch (mode) {
+        PS_GEMV_CASE(GEMV_PLAIN)
+        PS_GEMV_CASE(GEMV_RESID)
+        PS_GEMV_CASE(GEMV_GATE_UP)
+        PS_GEMV_CASE(GEMV_F32)
+    }
+#undef PS_GEMV_CASE
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
+// rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one wave per token (used when M > 1)
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rinv_kernel(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv) {
+    const uint32_t m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (m >= M) return;
+    float ss = 0.f;
+    for (uint32_t q = lane; q < H / 8; q += 64) ss += sumsq8(*reinterpret_cast<const uint4 *>(x + (size_t)m * H + q * 8));
+    ss = wave_sum(ss);
+    if (lane == 0) rinv[m] = rsqrtf(ss / (float)H + eps);
+}
+
+hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st) {
+    hipLaunchKernelGGL(rinv_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, H, eps, rinv);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// MoE routing: per token the top_k largest fp32 logits (ties to the lower index, listed
+// in descending order) and the softmax over the selected logits.  One wave per token.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void route_kernel(const float *logits, uint32_t M, uint32_t E, uint32_t top_k,
+                                                    int32_t *idx, float *w) {
+    const uint32_t m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (m >= M) return;
+    const float *l = logits + (size_t)m * E;
+    float v[16];  // E <= 1024
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t e = r * 64 + lane;
+        v[r] = e < E ? l[e] : -INFINITY;
+    }
+    uint32_t taken = 0;  // bit r: this lane's entry r already selected
+    float sel = 0.f, lmax = 0.f;
+    for (uint32_t j = 0; j < top_k; ++j) {
+        float best = -INFINITY;
+        uint32_t be = 0xFFFFFFFFu;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t e = r * 64 + lane;
+            if (e < E && !((taken >> r) & 1u) && (be == 0xFFFFFFFFu || v[r] > best)) { best = v[r]; be = e; }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const float ob = __shfl_xor(best, o, 64);
+            const uint32_t oe = __shfl_xor(be, o, 64);
+            const bool take = (oe != 0xFFFFFFFFu) && (be == 0xFFFFFFFFu || ob > best || (ob == best && oe < be));
+            if (take) { best = ob; be = oe; }
+        }
+        if ((be & 63u) == (uint32_t)lane) taken |= 1u << (be >> 6);
+        if (j == 0) lmax = best;
+        if ((uint32_t)lane == j) sel = best;
+        if (lane == 0) idx[(size_t)m * top_k + j] = (int32_t)be;
+    }
+    const float ex = (uint32_t)lane < top_k ? __expf(sel - lmax) : 0.f;
+    const float den = wave_sum(ex);
+    if ((uint32_t)lane < top_k) w[(size_t)m * top_k + lane] = ex / den;
+}
+
+hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
+                        hipStream_t st) {
+    hipLaunchKernelGGL(route_kernel, dim3((M + 3) / 4), dim3(256), 0, st, logits, M, E, top_k, idx, w);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// MoE combine: out[m] = h[m] + sum_j w[m][j] * y[m*top_k + j], j in rank order
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(const __half *h, const float *y, const float *w, uint32_t M,
+                                                      uint32_t H, uint32_t top_k, int residual, __half *out) {
+    const size_t n = (size_t)M * H;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n; q += (size_t)gridDim.x * 256) {
+        const uint32_t m = (uint32_t)(q / H), col = (uint32_t)(q % H);
+        float s = 0.f;
+        for (uint32_t j = 0; j < top_k; ++j) s += w[(size_t)m * top_k + j] * y[((size_t)m * top_k + j) * H + col];
+        out[q] = __float2half((residual ? __half2float(h[q]) : 0.f) + s);
+    }
+}
+
+hipError_t launch_combine(const __half *h, const float *y, const float *w, uint32_t M, uint32_t H, uint32_t top_k,
+                          int residual, __half *out, hipStream_t st) {
+    const size_t n = (size_t)M * H;
+    const size_t want = (n + 255) / 256;
+    const uint32_t blocks = (uint32_t)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL(combine_kernel, dim3(blocks), dim3(256), 0, st, h, y, w, M, H, top_k, residual, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Prefill / batched-decode kernel: 4-bit dequant GEMM on the matrix cores.
+// v_mfma_f32_16x16x32_f16: A = weights (16 rows x 32 k), B = activations (32 k x 16 tokens).
+// A lane's 16 weight bytes are four A operands as they sit in memory: lane (i, c) holds
+// block 4*sb + c of row i, dword kk supplies k-slots c*8 .. c*8+7 of MFMA step kk, which
+// this kernel maps to k = 32*(4*sb + c) + 8*kk + t; the B operand follows the same map.
+// Scales are folded into the fp16 A operand ((q - 8) * d rounded to fp16).
+// 256 threads = 4 waves, each wave owns AT row-tiles and all MT tokens of the workgroup;
+// the activation tile of one super-block (MT x 128 k) is staged in LDS, 16-byte chunks
+// XOR-swizzled by token so that operand reads are conflict-free.
+// ------------------------------------------------------------------------------------
+template <int MODE, int AT, int MT>
+__global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
+    extern __shared__ uint4 lds[];
+    constexpr int NMT = MT / 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, c = lane >> 4;
+
+    const uint4 *W = a.W;
+    uint32_t ntok = a.M;           // tokens this workgroup column may touch
+    const int32_t *pairs = nullptr;
+    if (a.tasks) {
+        const DeviceTask t = a.tasks[blockIdx.z];
+        W = reinterpret_cast<const uint4 *>(MODE == GEMM_GATE_UP ? t.w_gate_up : t.w_down);
+        ntok = t.npairs;
+        pairs = a.pairs + t.pair0;
+    }
+    const uint32_t m0 = blockIdx.y * MT;
+    if (m0 >= ntok) return;
+    const uint32_t tile_base = (blockIdx.x * 4 + wave) * AT;
+
+    // token rows handled by this thread during the LDS fill: MT*16 chunks / 256 threads
+    f4_t acc[AT][NMT];
+#pragma unroll
+    for (int t = 0; t < AT; ++t)
+#pragma unroll
+        for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (uint32_t sb = 0; sb < a.nsb; ++sb) {
+        __syncthreads();
+        // fill: chunk id = tid + r*256 -> token = id / 16, u = id % 16
+#pragma unroll
+        for (int r = 0; r < MT / 16; ++r) {
+            const uint32_t id = tid + r * 256, tok = id >> 4, u = id & 15;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m0 + tok < ntok) {
+                size_t rowi = m0 + tok;
+                if (pairs) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[m0 + tok] / (int32_t)a.top_k) : (size_t)pairs[m0 + tok];
+                v = *reinterpret_cast<const uint4 *>(a.x + rowi * a.x_stride + gather_col(sb * 128 + u * 8, a.x_off, a.x_group));
+            }
+            lds[tok * 16 + (u ^ (tok & 15))] = v;
+        }
+        __syncthreads();
+        const uint32_t g = sb >> 3, s = sb & 7;
+        const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
+        h8_t A[AT][4];
+#pragma unroll
+        for (int t = 0; t < AT; ++t) {
+            if (tile_base + t < a.ntiles) {
+                const uint4 *gb = W + (size_t)(tile_base + t) * a.tile_u4 + (size_t)g * (9 * 64);
+                const uint4 wq = gb[s * 64 + lane];
+                const uint16_t dbits = reinterpret_cast<const uint16_t *>(gb + nsb_g * 64 + lane)[s];
+                const _Float16 d = __builtin_bit_cast(_Float16, dbits);
+                const h2_t dd = {d, d};
+                const uint32_t q[4] = {wq.x, wq.y, wq.z, wq.w};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    h2_t w[4];
+                    dequant8(q[kk], w);
+                    w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+                    A[t][kk] = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+                }
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) A[t][kk] = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int n = 0; n < NMT; ++n) {
+                const uint32_t tok = n * 16 + i;  // B operand: lane (j = i, c) holds token j
+                const uint4 bv = lds[tok * 16 + ((c * 4 + kk) ^ (tok & 15))];
+                const h8_t B = __builtin_bit_cast(h8_t, bv);
+#pragma unroll
+                for (int t = 0; t < AT; ++t)
+                    acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t][kk], B, acc[t][n], 0, 0, 0);
+            }
+        }
+    }
+
+    // epilogue: lane holds token j = lane & 15 of each token tile and rows 4*(lane >> 4) + r
+    const int j = lane & 15, rg = lane >> 4;
+#pragma unroll
+    for (int n = 0; n < NMT; ++n) {
+        const uint32_t tok = m0 + n * 16 + j;
+        if (tok >= ntok) continue;
+        size_t orow = tok;           // output row
+        size_t xrow = tok;           // row of rinv / residual
+        if (pairs) { orow = (size_t)pairs[tok]; xrow = orow / a.top_k; }
+        if (MODE == GEMM_GATE_UP) {
+            const float rinv = a.rinv[xrow];
+#pragma unroll
+            for (int t = 0; t < AT; t += 2) {
+                if (tile_base + t >= a.ntiles) continue;
+                const uint32_t col = a.out_row0 + ((tile_base + t) >> 1) * 16 + rg * 4;
+                __half2 o01 = __floats2half2_rn(silu(rinv * acc[t][n][0]) * (rinv * acc[t + 1][n][0]),
+                                               silu(rinv * acc[t][n][1]) * (rinv * acc[t + 1][n][1]));
+                __half2 o23 = __floats2half2_rn(silu(rinv * acc[t][n][2]) * (rinv * acc[t + 1][n][2]),
+                                               silu(rinv * acc[t][n][3]) * (rinv * acc[t + 1][n][3]));
+                __half2 *dst = reinterpret_cast<__half2 *>(a.out + orow * a.out_stride + col);
+                dst[0] = o01; dst[1] = o23;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < AT; ++t) {
+                if (tile_base + t >= a.ntiles) continue;
+                const uint32_t col = a.out_row0 + (tile_base + t) * 16 + rg * 4;
+                if (MODE == GEMM_F32) {
+                    float4 *dst = reinterpret_cast<float4 *>(a.out_f32 + orow * a.out_stride + col);
+                    *dst = make_float4(acc[t][n][0], acc[t][n][1], acc[t][n][2], acc[t][n][3]);
+                } else {
+                    float v[4];
+                    if (MODE == GEMM_PLAIN) {
+                        const float rinv = a.rinv[xrow];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = rinv * acc[t][n][r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = acc[t][n][r];
+                        if (a.res) {
+                            const __half2 *rs = reinterpret_cast<const __half2 *>(a.res + orow * a.out_stride + col);
+                            const float2 r01 = __half22float2(rs[0]), r23 = __half22float2(rs[1]);
+                            v[0] += r01.x; v[1] += r01.y; v[2] += r23.x; v[3] += r23.y;
+                        }
+                    }
+                    __half2 *dst = reinterpret_cast<__half2 *>(a.out + orow * a.out_stride + col);
+                    dst[0] = __floats2half2_rn(v[0], v[1]);
+                    dst[1] = __floats2half2_rn(v[2], v[3]);
+                }
+            }
+        }
+    }
+}
+
+template <int MODE, int AT, int MT>
+static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
+    dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : 1);
+    const size_t lds = (size_t)MT * 256;
+    hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT>), grid, dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_gemm_m(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
+    if (max_tok <= 16) return launch_gemm_t<MODE, 2, 16>(a, ntasks, max_tok, st);
+    if (max_tok <= 32) return launch_gemm_t<MODE, 2, 32>(a, ntasks, max_tok, st);
+    if (max_tok <= 64) return launch_gemm_t<MODE, 2, 64>(a, ntasks, max_tok, st);
+    return launch_gemm_t<MODE, 4, 128>(a, ntasks, max_tok, st);
+}
+
+hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
+    switch (mode) {
+        case GEMM_PLAIN: return launch_gemm_m<GEMM_PLAIN>(a, ntasks, max_tok, st);
+        case GEMM_RESID: return launch_gemm_m<GEMM_RESID>(a, ntasks, max_tok, st);
+        case GEMM_GATE_UP: return launch_gemm_m<GEMM_GATE_UP>(a, ntasks, max_tok, st);
+        case GEMM_F32: return launch_gemm_m<GEMM_F32>(a, ntasks, max_tok, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
+// Lane-layout probe for v_mfma_f32_16x16x32_f16 (in-bounds, integer-valued inputs):
+// A[i][k] = 1 if (i, k) == (pi, pk) else 0, B[k][j] = 1 if (k, j) == (pk, pj): the single
+// non-zero of C tells which lane/register holds C[pi][pj] under the layout assumed above.
+// ------------------------------------------------------------------------------------
+__global__ void mfma_probe_kernel(int pi, int pk, int pj, float *out /*[64][4]*/) {
+    const int lane = threadIdx.x & 63, i = lane & 15, c = lane >> 4;
+    h8_t A = {0, 0, 0, 0, 0, 0, 0, 0}, B = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (i == pi && c == pk / 8) A[pk % 8] = (_Float16)1.0f;
+    if (i == pj && c == pk / 8) B[pk % 8] = (_Float16)1.0f;
+    f4_t C = {0.f, 0.f, 0.f, 0.f};
+    C = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, C, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) out[lane * 4 + r] = C[r];
+}
+
+hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(1), dim3(64), 0, st, pi, pk, pj, out);
+    return hipGetLastError();
+}
+
+}  // namespace ps

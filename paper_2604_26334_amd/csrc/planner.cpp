@@ -1,0 +1,365 @@
+// Planning phase of pipelined sharding for the GPU-only plan (paper Section 3:
+// Algorithm 1 procedures PlanningPhase and PinShardsToGPU, "Plan One", and the
+// profile-based timing estimate).  Host code only; no HIP calls.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+#include "ps_internal.h"
+
+namespace ps {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+static const uint32_t kTiers[PS_NTIERS] = {1, 4, 16, 32, 64, 512, 1024, 2048, 4096, 8192, 16384};
+
+MatGeom make_geom(uint32_t rows, uint32_t K, bool paired) {
+    MatGeom g;
+    g.K = K;
+    g.rows = rows;
+    g.ntiles = rows / kTileRows;
+    g.nsb = K / kSuperK;
+    g.ngroups = (g.nsb + kGroupSb - 1) / kGroupSb;
+    g.tile_bytes = (uint64_t)(g.nsb + g.ngroups) * kSbBytes;
+    g.bytes = g.tile_bytes * g.ntiles;
+    // slabs are cut at multiples of 16 tiles (256 rows) when the matrix allows it, else
+    // at 2 tiles (one gate tile + its up tile) or 1
+    g.quantum_tiles = (g.ntiles % 16 == 0) ? 16 : (paired ? 2 : 1);
+    return g;
+}
+
+int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
+    if (!m) { set_error("model is NULL"); return PS_E_ARG; }
+    ModelGeom g;
+    g.m = *m;
+    g.has_attn = !(m->flags & PS_FLAG_NO_ATTN);
+    g.moe = m->n_experts > 0;
+    auto bad_k = [](uint32_t K) { return K == 0 || K % kSuperK != 0 || K > 16384; };
+    if (m->n_layers == 0 || bad_k(m->hidden)) {
+        set_error("hidden=%u must be a multiple of 128, <= 16384; n_layers=%u must be > 0", m->hidden, m->n_layers);
+        return PS_E_ARG;
+    }
+    if (m->hidden % kTileRows) { set_error("hidden must be a multiple of 16"); return PS_E_ARG; }
+    if (g.has_attn) {
+        if (m->head_dim != 128 || m->n_kv_heads == 0 || m->n_q_heads == 0 || m->n_q_heads % m->n_kv_heads) {
+            set_error("attention needs head_dim 128 and n_q_heads a multiple of n_kv_heads (got %u, %u, %u)",
+                      m->head_dim, m->n_q_heads, m->n_kv_heads);
+            return PS_E_ARG;
+        }
+        g.qkv_w = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+        g.attn_w = m->n_q_heads * m->head_dim;
+        if (bad_k(g.attn_w)) { set_error("n_q_heads*head_dim=%u unsupported", g.attn_w); return PS_E_ARG; }
+        g.qkv = make_geom(g.qkv_w, m->hidden, false);
+        g.o = make_geom(m->hidden, g.attn_w, false);
+    }
+    if (g.moe) {
+        if (m->ffn_inter != 0 || m->top_k == 0 || m->top_k > m->n_experts || m->top_k > 32 || m->n_experts > 1024) {
+            set_error("MoE needs ffn_inter 0, 0 < top_k <= min(n_experts, 32), n_experts <= 1024");
+            return PS_E_ARG;
+        }
+        g.ffn_i = m->expert_inter;
+    } else {
+        g.ffn_i = m->ffn_inter;
+    }
+    if (bad_k(g.ffn_i) || g.ffn_i % kTileRows) {
+        set_error("FFN width %u must be a multiple of 128 and <= 16384", g.ffn_i);
+        return PS_E_ARG;
+    }
+    g.gate_up = make_geom(2 * g.ffn_i, m->hidden, true);
+    g.down = make_geom(m->hidden, g.ffn_i, false);
+    g.expert_bytes = g.moe ? g.gate_up.bytes + g.down.bytes : 0;
+    *out = g;
+    return PS_OK;
+}
+
+Workspace make_workspace(const ModelGeom &g, uint32_t M) {
+    Workspace w;
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, kAlign); return o; };
+    const uint64_t H = g.m.hidden;
+    w.h_bytes = (uint64_t)M * H * 2;
+    w.x0 = take(w.h_bytes);
+    w.x1 = take(w.h_bytes);
+    w.h = take(w.h_bytes);
+    w.qkv_bytes = (uint64_t)M * g.qkv_w * 2;
+    w.qkv = take(w.qkv_bytes);
+    w.rinv = take((uint64_t)M * 4);
+    if (g.moe) {
+        const uint64_t P = (uint64_t)M * g.m.top_k;  // (token, rank) pairs
+        w.s_bytes = P * g.ffn_i * 2;
+        w.s = take(w.s_bytes);
+        w.y = take(P * H * 4);
+        w.ridx = take(P * 4);
+        w.rw = take(P * 4);
+        w.logits_bytes = (uint64_t)g.m.n_layers * M * g.m.n_experts * 4;
+        w.logits = take(w.logits_bytes);
+        const uint64_t tasks_per_layer = std::min<uint64_t>(g.m.n_experts, P);
+        w.tasks_bytes = (uint64_t)g.m.n_layers * tasks_per_layer * sizeof(DeviceTask);
+        w.tasks = take(w.tasks_bytes);
+        w.pairs_bytes = (uint64_t)g.m.n_layers * P * 4;
+        w.pairs = take(w.pairs_bytes);
+    } else {
+        w.s_bytes = (uint64_t)M * g.ffn_i * 2;
+        w.s = take(w.s_bytes);
+    }
+    w.total = off;
+    return w;
+}
+
+struct Cand {  // a whole matrix / expert before any split
+    Shard s;
+    uint32_t quantum_tiles;
+    uint64_t tile_bytes;
+    double freq;
+};
+
+static double shard_compute_ms(const ps_plan &p, uint64_t bytes, double tokens) {
+    // memory-bound price vs compute-bound price (roofline rule of the paper's estimator)
+    const double weights = (double)bytes / 0.5625;
+    const double t_mem = p.prof.gemv_gbps > 0 ? (double)bytes / (p.prof.gemv_gbps * 1e9) : 0;
+    const double tf = p.prof.gemm_tflops[p.tier];
+    const double t_cmp = tf > 0 ? 2.0 * tokens * weights / (tf * 1e12) : 0;
+    return (std::max(t_mem, t_cmp)) * 1e3 + p.prof.launch_us * 1e-3;
+}
+
+static void estimate(ps_plan &p, const float *freq) {
+    // Each shard's time is the larger of its compute time and the concurrent H2D copy of
+    // the next shard; shard times are summed (paper Section 3, timing estimation).  MoE
+    // expert shards are weighted by the probability that a step touches them.
+    const auto &m = p.g.m;
+    const size_t n = p.shards.size();
+    std::vector<double> prob(n, 1.0), comp(n), copy(n, 0.0);
+    for (size_t i = 0; i < n; ++i) {
+        const Shard &s = p.shards[i];
+        double tokens = p.M;
+        if (s.kind == PS_SHARD_EXPERT) {
+            double f = (double)m.top_k / m.n_experts;
+            if (freq) f = freq[(size_t)s.layer * m.n_experts + s.expert];
+            f = std::min(1.0, std::max(0.0, f));
+            prob[i] = 1.0 - std::pow(1.0 - f, (double)p.M);
+            tokens = prob[i] > 0 ? p.M * f / prob[i] : 0;
+        }
+        comp[i] = shard_compute_ms(p, s.bytes, tokens) * prob[i];
+        if (!s.resident && p.prof.h2d_gbps > 0) copy[i] = (double)s.bytes / (p.prof.h2d_gbps * 1e9) * 1e3 * prob[i];
+    }
+    double t = n ? copy[0] : 0.0, streamed = 0;
+    for (size_t i = 0; i < n; ++i) {
+        t += std::max(comp[i], i + 1 < n ? copy[i + 1] : 0.0);
+        if (!p.shards[i].resident) streamed += (double)p.shards[i].bytes * prob[i];
+    }
+    p.est_step_ms = t;
+    p.est_streamed_per_step = streamed;
+}
+
+static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                         uint32_t M, const float *freq, ps_plan *p) {
+    int32_t rc = make_model_geom(model, &p->g);
+    if (rc) return rc;
+    if (M == 0 || M > kTiers[PS_NTIERS - 1]) { set_error("n_tokens=%u out of range 1..16384", M); return PS_E_ARG; }
+    if (prof) p->prof = *prof;
+    p->budget = budget;
+    p->M = M;
+    p->tier = ps_tier_for_tokens(M);
+    p->ws = make_workspace(p->g, M);
+    const ModelGeom &g = p->g;
+    const auto &m = g.m;
+
+    // ShardIntoSubLayers: one candidate per weight matrix (dense) or per expert (MoE)
+    std::vector<Cand> cands;
+    for (uint32_t l = 0; l < m.n_layers; ++l) {
+        auto add = [&](uint32_t kind, uint32_t cls, const MatGeom &mg) {
+            Cand c{};
+            c.s.layer = l; c.s.kind = kind; c.s.cls = cls; c.s.ntiles = mg.ntiles; c.s.bytes = mg.bytes;
+            c.quantum_tiles = mg.quantum_tiles; c.tile_bytes = mg.tile_bytes; c.freq = 0;
+            cands.push_back(c);
+        };
+        if (g.has_attn) { add(PS_SHARD_QKV, PS_CLASS_ATTN, g.qkv); add(PS_SHARD_O, PS_CLASS_ATTN, g.o); }
+        if (!g.moe) { add(PS_SHARD_GATE_UP, PS_CLASS_FFN, g.gate_up); add(PS_SHARD_DOWN, PS_CLASS_FFN, g.down); }
+        else for (uint32_t e = 0; e < m.n_experts; ++e) {
+            Cand c{};
+            c.s.layer = l; c.s.kind = PS_SHARD_EXPERT; c.s.cls = PS_CLASS_FFN; c.s.expert = e;
+            c.s.ntiles = g.gate_up.ntiles + g.down.ntiles; c.s.bytes = g.expert_bytes;
+            c.quantum_tiles = 0; c.tile_bytes = 0;  // experts are never split
+            c.freq = freq ? freq[(size_t)l * m.n_experts + e] : 0.0;
+            cands.push_back(c);
+        }
+    }
+    p->weight_bytes = 0;
+    uint64_t max_unit = 0;  // smallest thing a slot must be able to hold
+    for (auto &c : cands) {
+        p->weight_bytes += c.s.bytes;
+        max_unit = std::max(max_unit, c.quantum_tiles ? c.tile_bytes * c.quantum_tiles : c.s.bytes);
+    }
+    if (p->ws.total > budget) {
+        set_error("budget %llu B < workspace %llu B for %u tokens", (unsigned long long)budget,
+                  (unsigned long long)p->ws.total, M);
+        return PS_E_BUDGET;
+    }
+
+    // SortByPriority: class first; inside a class layer order and matrix order, experts by
+    // descending frequency then (layer, expert)
+    std::vector<uint32_t> order(cands.size());
+    std::iota(order.begin(), order.end(), 0u);
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        const Cand &x = cands[a], &y = cands[b];
+        if (x.s.cls != y.s.cls) return x.s.cls < y.s.cls;
+        if (x.s.kind == PS_SHARD_EXPERT && y.s.kind == PS_SHARD_EXPERT && x.freq != y.freq) return x.freq > y.freq;
+        return a < b;  // enumeration order = (layer, matrix order / expert id)
+    });
+    for (uint32_t r = 0; r < order.size(); ++r) cands[order[r]].s.rank = r;
+
+    // DecideScratchVRAMBudget: none if everything fits, else a double buffer
+    std::vector<uint32_t> head_tiles(cands.size(), 0);  // tiles pinned per candidate
+    if (p->ws.total + p->weight_bytes <= budget) {
+        p->n_slots = 0; p->slot_bytes = 0;
+        for (size_t i = 0; i < cands.size(); ++i) head_tiles[i] = cands[i].s.ntiles;
+    } else {
+        uint64_t lo = std::min<uint64_t>(1ull << 20, budget / 8), hi = 64ull << 20;
+        uint64_t slot = std::min(std::max(budget / 16, lo), hi) / kAlign * kAlign;
+        if (slot < max_unit) slot = align_up(max_unit, kAlign);
+        p->slot_bytes = slot; p->n_slots = 2;
+        if (p->ws.total + 2 * slot > budget) {
+            set_error("budget %llu B < workspace %llu B + 2 scratch slots of %llu B",
+                      (unsigned long long)budget, (unsigned long long)p->ws.total, (unsigned long long)slot);
+            return PS_E_BUDGET;
+        }
+        // PinShardsToGPU: first fit in priority order; the first shard that does not fit
+        // is split at slab granularity and its head pinned; scanning continues
+        uint64_t remaining = budget - p->ws.total - 2 * slot;
+        bool split_done = false;
+        for (uint32_t r = 0; r < order.size(); ++r) {
+            Cand &c = cands[order[r]];
+            if (c.s.bytes <= remaining) { head_tiles[order[r]] = c.s.ntiles; remaining -= c.s.bytes; continue; }
+            if (!split_done && c.quantum_tiles) {
+                split_done = true;
+                uint64_t q = remaining / (c.tile_bytes * c.quantum_tiles);
+                head_tiles[order[r]] = (uint32_t)q * c.quantum_tiles;
+                remaining -= (uint64_t)head_tiles[order[r]] * c.tile_bytes;
+            }
+        }
+    }
+    p->scratch_off = p->ws.total;
+    p->pinned_off = p->scratch_off + (uint64_t)p->n_slots * p->slot_bytes;
+
+    // Emit shards in execution order; streamed remainders are cut into slabs that fit a slot.
+    // Arena offsets of resident shards follow priority rank so the pinned region is dense.
+    std::vector<uint64_t> res_off(cands.size(), 0);
+    {
+        uint64_t off = p->pinned_off;
+        for (uint32_t r = 0; r < order.size(); ++r) {
+            const Cand &c = cands[order[r]];
+            uint64_t b = c.quantum_tiles ? (uint64_t)head_tiles[order[r]] * c.tile_bytes
+                                         : (head_tiles[order[r]] ? c.s.bytes : 0);
+            res_off[order[r]] = off;
+            off += b;
+        }
+        if (off > budget) { set_error("internal: pinned region overflows the budget"); return PS_E_STATE; }
+    }
+    uint64_t host_off = 0;
+    p->resident_bytes = p->streamed_bytes = 0;
+    for (size_t i = 0; i < cands.size(); ++i) {
+        const Cand &c = cands[i];
+        if (!c.quantum_tiles) {  // expert: whole
+            Shard s = c.s;
+            s.resident = head_tiles[i] ? 1 : 0;
+            s.offset = s.resident ? res_off[i] : host_off;
+            if (!s.resident) host_off += s.bytes;
+            (s.resident ? p->resident_bytes : p->streamed_bytes) += s.bytes;
+            p->shards.push_back(s);
+            continue;
+        }
+        if (head_tiles[i]) {
+            Shard s = c.s;
+            s.tile0 = 0; s.ntiles = head_tiles[i]; s.bytes = (uint64_t)s.ntiles * c.tile_bytes;
+            s.resident = 1; s.offset = res_off[i];
+            p->resident_bytes += s.bytes;
+            p->shards.push_back(s);
+        }
+        uint32_t t = head_tiles[i];
+        if (t < c.s.ntiles) {
+            uint32_t per = (uint32_t)(p->slot_bytes / (c.tile_bytes * c.quantum_tiles)) * c.quantum_tiles;
+            if (per == 0) { set_error("internal: slot smaller than a slab quantum"); return PS_E_STATE; }
+            while (t < c.s.ntiles) {
+                Shard s = c.s;
+                s.tile0 = t; s.ntiles = std::min(per, c.s.ntiles - t); s.bytes = (uint64_t)s.ntiles * c.tile_bytes;
+                s.resident = 0; s.offset = host_off;
+                host_off += s.bytes;
+                p->streamed_bytes += s.bytes;
+                p->shards.push_back(s);
+                t += s.ntiles;
+            }
+        }
+    }
+    estimate(*p, freq);
+    return PS_OK;
+}
+
+}  // namespace ps
+
+extern "C" {
+
+const char *ps_last_error(void) { return ps::g_err; }
+
+uint32_t ps_tier_tokens(uint32_t t) { return t < PS_NTIERS ? ps::kTiers[t] : 0; }
+
+uint32_t ps_tier_for_tokens(uint32_t n) {
+    for (uint32_t t = 0; t < PS_NTIERS; ++t)
+        if (n <= ps::kTiers[t]) return t;
+    return PS_NTIERS - 1;
+}
+
+uint64_t ps_packed_bytes(uint32_t rows, uint32_t K) {
+    if (K == 0 || K % ps::kSuperK || rows % ps::kTileRows) return 0;
+    return ps::make_geom(rows, K, false).bytes;
+}
+
+int32_t ps_plan_create(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                       uint32_t n_tokens, const float *expert_freq, ps_plan **out) {
+    if (!out) { ps::set_error("out is NULL"); return PS_E_ARG; }
+    *out = nullptr;
+    ps_plan *p = new (std::nothrow) ps_plan();
+    if (!p) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
+    int32_t rc = ps::plan_impl(model, budget, prof, n_tokens, expert_freq, p);
+    if (rc) { delete p; return rc; }
+    *out = p;
+    return PS_OK;
+}
+
+int32_t ps_plan_summary(const ps_plan *p, ps_plan_summary_t *o) {
+    if (!p || !o) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    o->budget_bytes = p->budget;
+    o->weight_bytes = p->weight_bytes;
+    o->resident_bytes = p->resident_bytes;
+    o->streamed_bytes = p->streamed_bytes;
+    o->scratch_bytes = (uint64_t)p->n_slots * p->slot_bytes;
+    o->workspace_bytes = p->ws.total;
+    o->slot_bytes = p->slot_bytes;
+    o->n_slots = p->n_slots;
+    o->n_shards = (uint32_t)p->shards.size();
+    o->n_tokens = p->M;
+    o->tier = p->tier;
+    o->est_step_ms = p->est_step_ms;
+    o->est_streamed_bytes_per_step = p->est_streamed_per_step;
+    return PS_OK;
+}
+
+int32_t ps_plan_get_shard(const ps_plan *p, uint32_t i, ps_shard_info *o) {
+    if (!p || !o || i >= p->shards.size()) { ps::set_error("shard index out of range"); return PS_E_ARG; }
+    const ps::Shard &s = p->shards[i];
+    o->layer = s.layer; o->kind = s.kind; o->expert = s.expert; o->cls = s.cls;
+    o->tile0 = s.tile0; o->ntiles = s.ntiles; o->resident = s.resident; o->priority_rank = s.rank;
+    o->bytes = s.bytes; o->offset = s.offset;
+    return PS_OK;
+}
+
+void ps_plan_destroy(ps_plan *p) { delete p; }
+
+}  // extern "C"

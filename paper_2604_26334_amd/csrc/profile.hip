@@ -1,0 +1,114 @@
+// Machine profile for the planner's time estimate (paper Section 3, install phase: kernels
+// are timed as a batch of asynchronous launches so that the rate reflects the concurrency
+// the GPU offers).  Three kinds of numbers: pinned H2D copy rate, decode-kernel weight
+// bandwidth, dequant-GEMM rate per token tier, plus the fixed cost of a launch.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+
+#include "kernels.h"
+#include "ps_internal.h"
+
+#define PS_HIP(call)                                                                   \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess) {                                                        \
+            ps::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            rc = PS_E_HIP;                                                             \
+            goto done;                                                                 \
+        }                                                                              \
+    } while (0)
+
+extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes, void *compute_stream,
+                                      void *copy_stream, ps_profile *out) {
+    using namespace ps;
+    constexpr uint64_t kHead = 64ull << 20;   // activations / outputs live here
+    constexpr int kLaunches = 10;
+    if (!scratch_dev || !out || scratch_bytes < (256ull << 20) || (uintptr_t)scratch_dev % kAlign) {
+        set_error("profile scratch must be device memory, 256-byte aligned, >= 256 MiB");
+        return PS_E_ARG;
+    }
+    int32_t rc = PS_OK;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ps_copy = static_cast<hipStream_t>(copy_stream);
+    uint8_t *base = static_cast<uint8_t *>(scratch_dev);
+    void *host = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    float ms = 0;
+    const MatGeom mg = make_geom(2048, 4096, false);  // a 2048 x 4096 matrix, 128 tiles
+    __half *x = reinterpret_cast<__half *>(base);                         // [2048][4096] fp16 = 16 MiB
+    __half *y = reinterpret_cast<__half *>(base + (16ull << 20));         // [2048][2048] fp16 = 8 MiB
+    float *rinv = reinterpret_cast<float *>(base + (24ull << 20));
+    uint8_t *wts = base + kHead;
+    const uint64_t wbytes = scratch_bytes - kHead;
+    *out = ps_profile{};
+
+    PS_HIP(hipEventCreate(&e0));
+    PS_HIP(hipEventCreate(&e1));
+    PS_HIP(hipHostMalloc(&host, kHead, hipHostMallocDefault));
+    std::memset(host, 0x11, kHead);
+    // well-defined contents: activations 0x1111 (a small positive fp16), weights / scales likewise
+    PS_HIP(hipMemsetAsync(base, 0x11, scratch_bytes, cs));
+    PS_HIP(hipStreamSynchronize(cs));
+
+    // pinned H2D rate: 64 MiB copies back to back on the copy stream
+    PS_HIP(hipMemcpyAsync(wts, host, kHead, hipMemcpyHostToDevice, ps_copy));
+    PS_HIP(hipEventRecord(e0, ps_copy));
+    for (int i = 0; i < 8; ++i) PS_HIP(hipMemcpyAsync(wts, host, kHead, hipMemcpyHostToDevice, ps_copy));
+    PS_HIP(hipEventRecord(e1, ps_copy));
+    PS_HIP(hipEventSynchronize(e1));
+    PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+    out->h2d_gbps = 8.0 * (double)kHead / (ms * 1e-3) / 1e9;
+
+    // fixed launch cost: a trivial kernel, many launches
+    PS_HIP(launch_rinv(x, 4, 4096, 1e-6f, rinv, cs));
+    PS_HIP(hipEventRecord(e0, cs));
+    for (int i = 0; i < 50; ++i) PS_HIP(launch_rinv(x, 4, 4096, 1e-6f, rinv, cs));
+    PS_HIP(hipEventRecord(e1, cs));
+    PS_HIP(hipEventSynchronize(e1));
+    PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+    out->launch_us = ms * 1e3 / 50.0;
+
+    {   // decode kernel bandwidth: ten launches over ten different weight regions
+        const uint32_t tiles_total = (uint32_t)std::min<uint64_t>(wbytes / mg.tile_bytes, 1u << 20);
+        const uint32_t per = tiles_total / kLaunches;
+        GemvArgs a{};
+        a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K;
+        a.x = x; a.x_group = 1; a.eps = 1e-6f; a.out = y; a.nunits = per; a.top_k = 1;
+        for (int rep = 0; rep < 2; ++rep) {
+            PS_HIP(hipEventRecord(e0, cs));
+            for (int i = 0; i < kLaunches; ++i) {
+                a.W = reinterpret_cast<const uint4 *>(wts + (uint64_t)i * per * mg.tile_bytes);
+                PS_HIP(launch_gemv(GEMV_PLAIN, 1, a, 0, cs));
+            }
+            PS_HIP(hipEventRecord(e1, cs));
+            PS_HIP(hipEventSynchronize(e1));
+        }
+        PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+        const double bytes = (double)kLaunches * per * mg.tile_bytes;
+        out->gemv_gbps = bytes / (ms * 1e-3) / 1e9;
+        out->gemm_tflops[0] = 2.0 * bytes / 0.5625 / (ms * 1e-3) / 1e12;
+    }
+    for (uint32_t t = 1; t < PS_NTIERS; ++t) {  // dequant GEMM at each token tier (capped at 2048 tokens)
+        const uint32_t T = std::min(ps_tier_tokens(t), 2048u);
+        if (ps_tier_tokens(t) > 2048) { out->gemm_tflops[t] = out->gemm_tflops[t - 1]; continue; }
+        GemmArgs a{};
+        a.W = reinterpret_cast<const uint4 *>(wts); a.ntiles = mg.ntiles; a.tile_u4 = (uint32_t)(mg.tile_bytes / 16);
+        a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = 4096; a.x_group = 1; a.rinv = rinv; a.out = y;
+        a.out_stride = 2048; a.top_k = 1;
+        PS_HIP(launch_rinv(x, T, 4096, 1e-6f, rinv, cs));
+        for (int rep = 0; rep < 2; ++rep) {
+            PS_HIP(hipEventRecord(e0, cs));
+            for (int i = 0; i < kLaunches; ++i) PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
+            PS_HIP(hipEventRecord(e1, cs));
+            PS_HIP(hipEventSynchronize(e1));
+        }
+        PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+        out->gemm_tflops[t] = 2.0 * T * 2048.0 * 4096.0 * kLaunches / (ms * 1e-3) / 1e12;
+    }
+done:
+    if (host) (void)hipHostFree(host);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    return rc;
+}

@@ -1,0 +1,532 @@
+// Executor of the GPU-only plan (paper Section 3, "Plan One", and Algorithm 1's
+// SetupForSched / RunInTopologicalOrder): resident shards are computed in place, host
+// shards are copied with hipMemcpyAsync on the copy stream into a two-slot VRAM scratch
+// while the compute stream works on the other slot.  Also: weight loading (packing into
+// the private layout) and the machine-profile measurement.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <functional>
+#include <map>
+#include <thread>
+#include <tuple>
+
+#include "kernels.h"
+#include "ps_internal.h"
+
+#define PS_HIP(call)                                                                   \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess) {                                                        \
+            ps::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return PS_E_HIP;                                                           \
+        }                                                                              \
+    } while (0)
+
+struct ps_stack {
+    ps_plan plan;
+    uint8_t *arena = nullptr;
+    uint64_t arena_bytes = 0;
+    hipStream_t compute = nullptr, copy = nullptr;
+    std::vector<void *> host_chunks;          // hipHostMalloc'ed pools of streamed shards
+    std::vector<uint8_t *> shard_host;        // per shard: host image (streamed) or null
+    std::map<std::tuple<uint32_t, uint32_t, uint32_t>, std::vector<uint32_t>> cover;  // (layer, shard kind, expert)
+    std::vector<uint8_t> loaded;              // per (layer, logical matrix slot)
+    uint64_t n_loaded = 0, n_expected = 0;
+    hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> ev_router;
+    hipEvent_t ev_upload = nullptr;
+    bool upload_pending = false;
+    ps_schedule dense_sched;
+    bool have_dense_sched = false;
+    void *stage = nullptr;                    // pinned staging for resident loads
+    uint64_t stage_bytes = 0;
+    void *tables_host = nullptr;              // pinned: logits | tasks | pairs for one forward (MoE)
+    uint64_t tables_bytes = 0;
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
+    std::vector<uint8_t> prof_is_copy;
+    bool prof_valid = false;
+    ps_stats stats{};
+};
+
+namespace {
+
+using namespace ps;
+
+constexpr uint64_t kHostChunk = 1ull << 30;
+
+uint8_t *slot_ptr(const ps_stack *st, int slot) {
+    return st->arena + st->plan.scratch_off + (uint64_t)slot * st->plan.slot_bytes;
+}
+
+void parallel_for(uint32_t n, const std::function<void(uint32_t)> &fn) {
+    unsigned hw = std::thread::hardware_concurrency();
+    uint32_t nt = std::max(1u, std::min<uint32_t>(std::min<uint32_t>(hw ? hw : 4, 16), n));
+    if (nt == 1) { for (uint32_t i = 0; i < n; ++i) fn(i); return; }
+    std::atomic<uint32_t> next{0};
+    std::vector<std::thread> th;
+    for (uint32_t t = 0; t < nt; ++t)
+        th.emplace_back([&]() { for (uint32_t i; (i = next.fetch_add(1)) < n;) fn(i); });
+    for (auto &t : th) t.join();
+}
+
+const MatGeom &geom_of(const ModelGeom &g, uint32_t mat) {
+    switch (mat) {
+        case PS_MAT_QKV: return g.qkv;
+        case PS_MAT_O: return g.o;
+        case PS_MAT_DOWN: return g.down;
+        default: return g.gate_up;
+    }
+}
+
+int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __half *x_in, __half *x_out) {
+    const ps_plan &p = st->plan;
+    const ModelGeom &g = p.g;
+    const auto &m = g.m;
+    const uint32_t M = p.M, H = m.hidden, l = op.info.layer;
+    uint8_t *A = st->arena;
+    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
+    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(A + p.ws.h) : const_cast<__half *>(xin);
+    __half *qkv = reinterpret_cast<__half *>(A + p.ws.qkv);
+    __half *sbuf = reinterpret_cast<__half *>(A + p.ws.s);
+    float *rinv = reinterpret_cast<float *>(A + p.ws.rinv);
+    const bool resid = !(m.flags & PS_FLAG_NO_RESIDUAL);
+    hipStream_t cs = st->compute;
+
+    auto wptr = [&](const Op &o) -> const uint4 * {
+        const Shard &s = p.shards[o.info.shard0];
+        if (s.resident) return reinterpret_cast<const uint4 *>(A + s.offset);
+        return reinterpret_cast<const uint4 *>(slot_ptr(st, o.info.slot) + o.info.slot_offset);
+    };
+    auto gemv_base = [&](const MatGeom &mg) {
+        GemvArgs a{};
+        a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K;
+        a.x_group = 1; a.eps = m.rms_eps; a.top_k = std::max(1u, m.top_k);
+        return a;
+    };
+    auto gemm_base = [&](const MatGeom &mg) {
+        GemmArgs a{};
+        a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.M = M;
+        a.x_group = 1; a.rinv = rinv; a.top_k = std::max(1u, m.top_k);
+        return a;
+    };
+
+    switch (op.info.kernel) {
+        case PS_K_RINV:
+            PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
+            return PS_OK;
+        case PS_K_QKV: {
+            const Shard &s = p.shards[op.info.shard0];
+            if (M == 1) {
+                GemvArgs a = gemv_base(g.qkv);
+                a.W = wptr(op); a.nunits = s.ntiles; a.x = xin; a.out = qkv; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemv(GEMV_PLAIN, gemv_ksplit(g.qkv.ngroups, g.qkv.ntiles), a, 0, cs));
+            } else {
+                GemmArgs a = gemm_base(g.qkv);
+                a.W = wptr(op); a.ntiles = s.ntiles; a.x = xin; a.x_stride = H; a.out = qkv;
+                a.out_stride = g.qkv_w; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, M, cs));
+            }
+            return PS_OK;
+        }
+        case PS_K_O: {
+            const Shard &s = p.shards[op.info.shard0];
+            const uint32_t voff = (m.n_q_heads + m.n_kv_heads) * m.head_dim, grp = m.n_q_heads / m.n_kv_heads;
+            if (M == 1) {
+                GemvArgs a = gemv_base(g.o);
+                a.W = wptr(op); a.nunits = s.ntiles; a.x = qkv; a.x_off = voff; a.x_group = grp;
+                a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemv(GEMV_RESID, gemv_ksplit(g.o.ngroups, g.o.ntiles), a, 0, cs));
+            } else {
+                GemmArgs a = gemm_base(g.o);
+                a.W = wptr(op); a.ntiles = s.ntiles; a.x = qkv; a.x_stride = g.qkv_w; a.x_off = voff; a.x_group = grp;
+                a.res = xin; a.out = hbuf; a.out_stride = H; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
+            }
+            return PS_OK;
+        }
+        case PS_K_GATE_UP: {
+            const Shard &s = p.shards[op.info.shard0];
+            if (M == 1) {
+                GemvArgs a = gemv_base(g.gate_up);
+                a.W = wptr(op); a.nunits = s.ntiles / 2; a.x = hbuf; a.out = sbuf; a.out_row0 = s.tile0 / 2 * 16;
+                PS_HIP(launch_gemv(GEMV_GATE_UP, gemv_ksplit(g.gate_up.ngroups, g.gate_up.ntiles / 2), a, 0, cs));
+            } else {
+                GemmArgs a = gemm_base(g.gate_up);
+                a.W = wptr(op); a.ntiles = s.ntiles; a.x = hbuf; a.x_stride = H; a.out = sbuf;
+                a.out_stride = g.ffn_i; a.out_row0 = s.tile0 / 2 * 16;
+                PS_HIP(launch_gemm(GEMM_GATE_UP, a, 0, M, cs));
+            }
+            return PS_OK;
+        }
+        case PS_K_DOWN: {
+            const Shard &s = p.shards[op.info.shard0];
+            if (M == 1) {
+                GemvArgs a = gemv_base(g.down);
+                a.W = wptr(op); a.nunits = s.ntiles; a.x = sbuf; a.res = resid ? hbuf : nullptr;
+                a.out = xout; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemv(GEMV_RESID, gemv_ksplit(g.down.ngroups, g.down.ntiles), a, 0, cs));
+            } else {
+                GemmArgs a = gemm_base(g.down);
+                a.W = wptr(op); a.ntiles = s.ntiles; a.x = sbuf; a.x_stride = g.ffn_i;
+                a.res = resid ? hbuf : nullptr; a.out = xout; a.out_stride = H; a.out_row0 = s.tile0 * 16;
+                PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
+            }
+            return PS_OK;
+        }
+        case PS_K_ROUTE:
+            PS_HIP(launch_route(reinterpret_cast<const float *>(A + p.ws.logits) + (size_t)l * M * m.n_experts, M,
+                                m.n_experts, m.top_k, reinterpret_cast<int32_t *>(A + p.ws.ridx),
+                                reinterpret_cast<float *>(A + p.ws.rw), cs));
+            return PS_OK;
+        case PS_K_EXPERT_GATE_UP:
+        case PS_K_EXPERT_DOWN: {
+            const bool gu = op.info.kernel == PS_K_EXPERT_GATE_UP;
+            const DeviceTask *tasks = reinterpret_cast<const DeviceTask *>(A + p.ws.tasks) + op.task0;
+            const int32_t *pairs = reinterpret_cast<const int32_t *>(A + p.ws.pairs);
+            float *y = reinterpret_cast<float *>(A + p.ws.y);
+            uint32_t max_tok = 0;
+            for (uint32_t t = op.task0; t < op.task0 + op.ntasks; ++t) max_tok = std::max(max_tok, sc.tasks[t].npairs);
+            const MatGeom &mg = gu ? g.gate_up : g.down;
+            if (M == 1) {
+                GemvArgs a = gemv_base(mg);
+                a.tasks = tasks; a.pairs = pairs;
+                if (gu) { a.nunits = mg.ntiles / 2; a.x = hbuf; a.x_stride = H; a.out = sbuf; a.out_stride = g.ffn_i; }
+                else { a.nunits = mg.ntiles; a.x = sbuf; a.x_stride = g.ffn_i; a.out_f32 = y; a.out_stride = H; }
+                const uint32_t units = gu ? mg.ntiles / 2 : mg.ntiles;
+                PS_HIP(launch_gemv(gu ? GEMV_GATE_UP : GEMV_F32, gemv_ksplit(mg.ngroups, units * m.top_k), a, op.ntasks, cs));
+            } else {
+                GemmArgs a = gemm_base(mg);
+                a.tasks = tasks; a.pairs = pairs; a.ntiles = mg.ntiles;
+                if (gu) { a.x = hbuf; a.x_stride = H; a.out = sbuf; a.out_stride = g.ffn_i; }
+                else { a.x = sbuf; a.x_stride = g.ffn_i; a.out_f32 = y; a.out_stride = H; }
+                PS_HIP(launch_gemm(gu ? GEMM_GATE_UP : GEMM_F32, a, op.ntasks, max_tok, cs));
+            }
+            return PS_OK;
+        }
+        case PS_K_COMBINE:
+            PS_HIP(launch_combine(hbuf, reinterpret_cast<const float *>(A + p.ws.y),
+                                  reinterpret_cast<const float *>(A + p.ws.rw), M, H, m.top_k, resid ? 1 : 0, xout, cs));
+            return PS_OK;
+    }
+    set_error("unknown kernel id %u", op.info.kernel);
+    return PS_E_STATE;
+}
+
+int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __half *x_out) {
+    const ps_plan &p = st->plan;
+    const bool prof = st->profiling;
+    if (prof) {
+        while (st->prof_ev.size() < 2 * sc.ops.size()) {
+            hipEvent_t e;
+            PS_HIP(hipEventCreate(&e));
+            st->prof_ev.push_back(e);
+        }
+        st->prof_is_copy.assign(sc.ops.size(), 0);
+    }
+    st->prof_valid = false;
+    ps_stats &ss = st->stats;
+    ss = ps_stats{};
+    for (size_t i = 0; i < sc.ops.size(); ++i) {
+        const Op &op = sc.ops[i];
+        const ps_op_info &o = op.info;
+        if (o.type == PS_OP_COPY) {
+            if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
+            if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
+            if (prof) { PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->copy)); st->prof_is_copy[i] = 1; }
+            PS_HIP(hipMemcpyAsync(slot_ptr(st, o.slot) + o.slot_offset, st->shard_host[o.shard0], o.bytes,
+                                  hipMemcpyHostToDevice, st->copy));
+            if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->copy));
+            if (o.flags & PS_OPF_RECORD_READY) PS_HIP(hipEventRecord(st->ev_ready[o.slot], st->copy));
+            ss.streamed_bytes_step += o.bytes;
+            ss.n_copies++;
+        } else {
+            if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
+            if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
+            int32_t rc = issue_kernel(st, sc, op, x_in, x_out);
+            if (rc) return rc;
+            if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->compute));
+            if (o.flags & PS_OPF_RECORD_FREE) PS_HIP(hipEventRecord(st->ev_free[o.slot], st->compute));
+            if (o.flags & PS_OPF_RECORD_ROUTER) PS_HIP(hipEventRecord(st->ev_router[o.layer], st->compute));
+            if (o.slot < 0) ss.resident_bytes_step += o.bytes;
+            ss.n_kernels++;
+        }
+    }
+    (void)p;
+    st->prof_valid = prof;
+    return PS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes, void *compute_stream,
+                        void *copy_stream, ps_stack **out) {
+    if (!plan || !vram_arena || !out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    *out = nullptr;
+    if (arena_bytes < plan->budget) {
+        ps::set_error("arena of %llu B is smaller than the plan's budget %llu B", (unsigned long long)arena_bytes,
+                      (unsigned long long)plan->budget);
+        return PS_E_ARG;
+    }
+    if ((uintptr_t)vram_arena % ps::kAlign) { ps::set_error("arena must be 256-byte aligned"); return PS_E_ARG; }
+    if (compute_stream == copy_stream && plan->n_slots) {
+        ps::set_error("streamed shards need distinct compute and copy streams"); return PS_E_ARG;
+    }
+    ps_stack *st = new (std::nothrow) ps_stack();
+    if (!st) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
+    st->plan = *plan;
+    st->arena = static_cast<uint8_t *>(vram_arena);
+    st->arena_bytes = arena_bytes;
+    st->compute = static_cast<hipStream_t>(compute_stream);
+    st->copy = static_cast<hipStream_t>(copy_stream);
+    auto fail = [&](int32_t rc) { ps_stack_destroy(st); return rc; };
+
+    const ps_plan &p = st->plan;
+    const auto &m = p.g.m;
+    // host pools for streamed shards: chunks of at most 1 GiB, a shard never straddles chunks
+    st->shard_host.assign(p.shards.size(), nullptr);
+    {
+        std::vector<std::pair<size_t, uint64_t>> place(p.shards.size());  // chunk, offset
+        std::vector<uint64_t> chunk_bytes;
+        for (size_t i = 0; i < p.shards.size(); ++i) {
+            if (p.shards[i].resident) continue;
+            if (chunk_bytes.empty() || chunk_bytes.back() + p.shards[i].bytes > kHostChunk) chunk_bytes.push_back(0);
+            place[i] = {chunk_bytes.size() - 1, chunk_bytes.back()};
+            chunk_bytes.back() += p.shards[i].bytes;
+        }
+        for (uint64_t b : chunk_bytes) {
+            void *ptr = nullptr;
+            hipError_t e = hipHostMalloc(&ptr, b, hipHostMallocDefault);
+            if (e != hipSuccess) { ps::set_error("hipHostMalloc(%llu) failed: %s", (unsigned long long)b, hipGetErrorString(e)); return fail(PS_E_HIP); }
+            st->host_chunks.push_back(ptr);
+        }
+        for (size_t i = 0; i < p.shards.size(); ++i)
+            if (!p.shards[i].resident) st->shard_host[i] = static_cast<uint8_t *>(st->host_chunks[place[i].first]) + place[i].second;
+    }
+    for (size_t i = 0; i < p.shards.size(); ++i)
+        st->cover[std::make_tuple(p.shards[i].layer, p.shards[i].kind, p.shards[i].expert)].push_back((uint32_t)i);
+    const uint32_t per_layer = (p.g.has_attn ? 2 : 0) + 3 * (p.g.moe ? m.n_experts : 1);
+    st->n_expected = (uint64_t)per_layer * m.n_layers;
+    st->loaded.assign(st->n_expected, 0);
+
+    for (int s = 0; s < 2; ++s) {
+        if (hipEventCreateWithFlags(&st->ev_ready[s], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&st->ev_free[s], hipEventDisableTiming) != hipSuccess) {
+            ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP);
+        }
+    }
+    if (p.g.moe) {
+        st->ev_router.resize(m.n_layers);
+        for (auto &e : st->ev_router)
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
+        if (hipEventCreateWithFlags(&st->ev_upload, hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
+        st->tables_bytes = p.ws.logits_bytes + p.ws.tasks_bytes + p.ws.pairs_bytes;
+        if (hipHostMalloc(&st->tables_host, st->tables_bytes, hipHostMallocDefault) != hipSuccess) {
+            ps::set_error("hipHostMalloc for routing tables failed"); return fail(PS_E_HIP);
+        }
+    } else {
+        int32_t rc = ps::build_schedule(&st->plan, nullptr, &st->dense_sched);
+        if (rc) return fail(rc);
+        rc = ps::validate_schedule(&st->dense_sched);
+        if (rc) return fail(rc);
+        st->have_dense_sched = true;
+    }
+    st->stage_bytes = 32ull << 20;
+    if (hipHostMalloc(&st->stage, st->stage_bytes, hipHostMallocDefault) != hipSuccess) {
+        ps::set_error("hipHostMalloc for staging failed"); return fail(PS_E_HIP);
+    }
+    *out = st;
+    return PS_OK;
+}
+
+int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_t expert,
+                             const uint16_t *scales, const uint8_t *codes) {
+    if (!st || !scales || !codes) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    const ps::ModelGeom &g = p.g;
+    const auto &m = g.m;
+    if (layer >= m.n_layers || mat > PS_MAT_DOWN) { ps::set_error("bad layer/matrix id"); return PS_E_ARG; }
+    const bool is_attn = mat == PS_MAT_QKV || mat == PS_MAT_O;
+    if (is_attn && !g.has_attn) { ps::set_error("model has no attention matrices"); return PS_E_ARG; }
+    if (g.moe && !is_attn) {
+        if (expert >= m.n_experts) { ps::set_error("expert id %u out of range", expert); return PS_E_ARG; }
+    } else if (expert != ps::kNoExpert) {
+        ps::set_error("expert must be 0xFFFFFFFF for this matrix"); return PS_E_ARG;
+    }
+    uint32_t kind;
+    if (is_attn) kind = mat == PS_MAT_QKV ? PS_SHARD_QKV : PS_SHARD_O;
+    else if (g.moe) kind = PS_SHARD_EXPERT;
+    else kind = mat == PS_MAT_DOWN ? PS_SHARD_DOWN : PS_SHARD_GATE_UP;
+    auto it = st->cover.find(std::make_tuple(layer, kind, g.moe && !is_attn ? expert : ps::kNoExpert));
+    if (it == st->cover.end()) { ps::set_error("internal: no shard covers this matrix"); return PS_E_STATE; }
+    const ps::MatGeom &mg = geom_of(g, mat);
+    const bool paired = mat == PS_MAT_GATE || mat == PS_MAT_UP;
+    const uint32_t parity = mat == PS_MAT_UP ? 1 : 0;
+    const uint32_t step = paired ? 2 : 1;
+    const uint64_t pitch = mg.tile_bytes * step;
+
+    for (uint32_t si : it->second) {
+        const ps::Shard &s = p.shards[si];
+        uint32_t t0 = s.tile0, nt = s.ntiles;
+        uint64_t base_off = 0;
+        if (kind == PS_SHARD_EXPERT) {
+            t0 = 0;
+            nt = mat == PS_MAT_DOWN ? g.down.ntiles : g.gate_up.ntiles;
+            base_off = mat == PS_MAT_DOWN ? g.gate_up.bytes : 0;
+        }
+        // physical tiles t0 + parity, t0 + parity + step, ... (t0 is even for paired matrices)
+        const uint32_t count = (nt + step - 1 - parity) / step;
+        if (!s.resident) {
+            uint8_t *dst = st->shard_host[si] + base_off;
+            parallel_for(count, [&](uint32_t j) {
+                const uint32_t pt = t0 + parity + j * step;
+                ps::pack_tile(mg, scales, codes, paired ? pt / 2 : pt, dst + (uint64_t)(pt - t0) * mg.tile_bytes);
+            });
+        } else {
+            uint8_t *dst = st->arena + s.offset + base_off;
+            const uint32_t per = (uint32_t)(st->stage_bytes / mg.tile_bytes);
+            for (uint32_t j0 = 0; j0 < count; j0 += per) {
+                const uint32_t n = std::min(per, count - j0);
+                uint8_t *stg = static_cast<uint8_t *>(st->stage);
+                parallel_for(n, [&](uint32_t j) {
+                    const uint32_t pt = t0 + parity + (j0 + j) * step;
+                    ps::pack_tile(mg, scales, codes, paired ? pt / 2 : pt, stg + (uint64_t)j * mg.tile_bytes);
+                });
+                uint8_t *d = dst + (uint64_t)(parity + j0 * step) * mg.tile_bytes;
+                PS_HIP(hipMemcpy2D(d, pitch, stg, mg.tile_bytes, mg.tile_bytes, n, hipMemcpyHostToDevice));
+            }
+        }
+    }
+    const uint32_t per_layer = (g.has_attn ? 2 : 0) + 3 * (g.moe ? m.n_experts : 1);
+    uint32_t slot;
+    if (is_attn) slot = mat == PS_MAT_QKV ? 0 : 1;
+    else slot = (g.has_attn ? 2 : 0) + 3 * (g.moe ? expert : 0) + (mat - PS_MAT_GATE);
+    uint8_t &flag = st->loaded[(size_t)layer * per_layer + slot];
+    if (!flag) { flag = 1; st->n_loaded++; }
+    return PS_OK;
+}
+
+int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits) {
+    if (!st || !x_in || !x_out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (x_in == x_out) { ps::set_error("x_in and x_out may not alias"); return PS_E_ARG; }
+    if (st->n_loaded != st->n_expected) {
+        ps::set_error("forward before all matrices were loaded (%llu of %llu)", (unsigned long long)st->n_loaded,
+                      (unsigned long long)st->n_expected);
+        return PS_E_STATE;
+    }
+    const ps_plan &p = st->plan;
+    if (!p.g.moe) return run_schedule(st, st->dense_sched, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+
+    if (!router_logits) { ps::set_error("MoE forward needs host router logits"); return PS_E_ARG; }
+    ps_schedule sc;
+    int32_t rc = ps::build_schedule(&st->plan, router_logits, &sc);
+    if (rc) return rc;
+    // device tables: logits | tasks | pairs, staged in pinned memory and uploaded on the compute stream
+    if (st->upload_pending) { PS_HIP(hipEventSynchronize(st->ev_upload)); st->upload_pending = false; }
+    uint8_t *th = static_cast<uint8_t *>(st->tables_host);
+    std::memcpy(th, router_logits, p.ws.logits_bytes);
+    ps::DeviceTask *dt = reinterpret_cast<ps::DeviceTask *>(th + p.ws.logits_bytes);
+    if (sc.tasks.size() * sizeof(ps::DeviceTask) > p.ws.tasks_bytes || sc.pairs.size() * 4 > p.ws.pairs_bytes) {
+        ps::set_error("internal: routing tables exceed the workspace"); return PS_E_STATE;
+    }
+    for (size_t t = 0; t < sc.tasks.size(); ++t) {
+        const ps::TaskHost &h = sc.tasks[t];
+        const ps::Shard &s = p.shards[h.shard];
+        const uint8_t *w = s.resident ? st->arena + s.offset : slot_ptr(st, h.slot) + h.slot_offset;
+        dt[t].w_gate_up = (uint64_t)(uintptr_t)w;
+        dt[t].w_down = (uint64_t)(uintptr_t)(w + p.g.gate_up.bytes);
+        dt[t].pair0 = h.pair0; dt[t].npairs = h.npairs; dt[t].expert = h.expert; dt[t].pad = 0;
+    }
+    std::memcpy(th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.data(), sc.pairs.size() * 4);
+    PS_HIP(hipMemcpyAsync(st->arena + p.ws.logits, th, p.ws.logits_bytes, hipMemcpyHostToDevice, st->compute));
+    if (!sc.tasks.empty())
+        PS_HIP(hipMemcpyAsync(st->arena + p.ws.tasks, dt, sc.tasks.size() * sizeof(ps::DeviceTask), hipMemcpyHostToDevice, st->compute));
+    if (!sc.pairs.empty())
+        PS_HIP(hipMemcpyAsync(st->arena + p.ws.pairs, th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.size() * 4,
+                              hipMemcpyHostToDevice, st->compute));
+    PS_HIP(hipEventRecord(st->ev_upload, st->compute));
+    st->upload_pending = true;
+    return run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+}
+
+int32_t ps_stack_set_profiling(ps_stack *st, int32_t on) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    st->profiling = on != 0;
+    return PS_OK;
+}
+
+int32_t ps_stack_stats(ps_stack *st, ps_stats *out) {
+    if (!st || !out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (st->prof_valid) {
+        PS_HIP(hipStreamSynchronize(st->copy));
+        PS_HIP(hipStreamSynchronize(st->compute));
+        const size_t n = st->prof_is_copy.size();
+        double copy_ms = 0, comp_ms = 0, t_min = 0, t_max = 0;
+        bool first = true;
+        for (size_t i = 0; i < n; ++i) {
+            float dur = 0, t0 = 0;
+            PS_HIP(hipEventElapsedTime(&dur, st->prof_ev[2 * i], st->prof_ev[2 * i + 1]));
+            PS_HIP(hipEventElapsedTime(&t0, st->prof_ev[0], st->prof_ev[2 * i]));
+            (st->prof_is_copy[i] ? copy_ms : comp_ms) += dur;
+            if (first || t0 < t_min) t_min = t0;
+            if (first || t0 + dur > t_max) t_max = t0 + dur;
+            first = false;
+        }
+        ps_stats &s = st->stats;
+        s.copy_ms = copy_ms; s.compute_ms = comp_ms; s.wall_ms = t_max - t_min;
+        const double mn = std::min(copy_ms, comp_ms);
+        s.overlap = mn > 0 ? (copy_ms + comp_ms - s.wall_ms) / mn : 0.0;
+        s.h2d_gbps = copy_ms > 0 ? (double)s.streamed_bytes_step / (copy_ms * 1e-3) / 1e9 : 0.0;
+        st->prof_valid = false;
+    }
+    *out = st->stats;
+    return PS_OK;
+}
+
+int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes) {
+    if (!st || !dev_ptr || !bytes) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    const uint64_t P = (uint64_t)p.M * std::max(1u, p.g.m.top_k);
+    switch (which) {
+        case 0: *dev_ptr = st->arena + p.ws.qkv; *bytes = p.ws.qkv_bytes; return PS_OK;
+        case 1: *dev_ptr = st->arena + p.ws.h; *bytes = p.ws.h_bytes; return PS_OK;
+        case 2: *dev_ptr = st->arena + p.ws.s; *bytes = p.ws.s_bytes; return PS_OK;
+        case 3: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.ridx; *bytes = P * 4; return PS_OK;
+        case 4: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.rw; *bytes = P * 4; return PS_OK;
+    }
+    ps::set_error("no such debug buffer");
+    return PS_E_ARG;
+}
+
+void ps_stack_destroy(ps_stack *st) {
+    if (!st) return;
+    if (st->compute || st->copy) {
+        if (st->copy) (void)hipStreamSynchronize(st->copy);
+        if (st->compute) (void)hipStreamSynchronize(st->compute);
+    }
+    for (void *c : st->host_chunks) (void)hipHostFree(c);
+    if (st->stage) (void)hipHostFree(st->stage);
+    if (st->tables_host) (void)hipHostFree(st->tables_host);
+    for (int s = 0; s < 2; ++s) {
+        if (st->ev_ready[s]) (void)hipEventDestroy(st->ev_ready[s]);
+        if (st->ev_free[s]) (void)hipEventDestroy(st->ev_free[s]);
+    }
+    for (auto e : st->ev_router) if (e) (void)hipEventDestroy(e);
+    if (st->ev_upload) (void)hipEventDestroy(st->ev_upload);
+    for (auto e : st->prof_ev) (void)hipEventDestroy(e);
+    delete st;
+}
+
+int32_t ps_mfma_probe(int32_t pi, int32_t pk, int32_t pj, float *out_dev, void *stream) {
+    if (pi < 0 || pi > 15 || pj < 0 || pj > 15 || pk < 0 || pk > 31 || !out_dev) { ps::set_error("probe index out of range"); return PS_E_ARG; }
+    PS_HIP(ps::launch_mfma_probe(pi, pk, pj, out_dev, static_cast<hipStream_t>(stream)));
+    return PS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the
+same seeded inputs, plus bit-exact invariance of the output to shard placement.
+
+Tolerance (fp16 activations, fp32 accumulation): max|err| / max|ref| <= 5e-3 against the oracle
+that rounds to fp16 where the GPU stores fp16; the pure fp64 oracle is reported alongside."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from tests import harness as Hn
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def test_mfma_operand_layout_probe():
+    import ctypes as C
+    import torch
+    from paper_2604_26334_amd import binding as B
+    out = torch.zeros(64 * 4, dtype=torch.float32, device="cuda:0")
+    for pi, pk, pj in [(0, 0, 0), (5, 13, 9), (15, 31, 15), (7, 8, 2), (12, 23, 0), (3, 16, 14)]:
+        out.zero_()
+        torch.cuda.synchronize()
+        rc = B.lib().ps_mfma_probe(pi, pk, pj, out.data_ptr(), None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        c = out.cpu().numpy().reshape(64, 4)
+        nz = np.argwhere(c != 0)
+        _say("probe", (pi, pk, pj), "->", nz.tolist())
+        assert nz.tolist() == [[pj + 16 * (pi // 4), pi % 4]]
+        assert c[pj + 16 * (pi // 4), pi % 4] == 1.0
+
+
+def _check(cfg, seed, M, budgets, logits=None, tol=TOL):
+    W = Hn.WeightCache(cfg, seed)
+    x = S.activations(seed, 0, M, cfg["hidden"])
+    ref_m = O.stack_forward(x, cfg, W, logits=logits, mirror=True)
+    ref_p = O.stack_forward(x, cfg, W, logits=logits, mirror=False)
+    outs = []
+    for b in budgets:
+        _say("  budget", b, "M", M)
+        y, info = Hn.run_gpu(cfg, W, b, x, logits=logits)
+        e_m, e_p = Hn.rel_err(y, ref_m), Hn.rel_err(y, ref_p)
+        _say("    resident %d streamed %d copies %d kernels %d  err(mirror) %.3e err(pure) %.3e" % (
+            info["resident"], info["streamed"], info["stats"].n_copies, info["stats"].n_kernels, e_m, e_p))
+        assert np.isfinite(y.astype(np.float64)).all()
+        assert e_m <= tol, (b, e_m)
+        outs.append(y)
+    for y in outs[1:]:
+        np.testing.assert_array_equal(y.view(np.uint16), outs[0].view(np.uint16))
+    return outs[0]
+
+
+def _budgets(cfg, M, fracs):
+    wb, _ = Hn.total_weight_bytes(cfg)
+    from paper_2604_26334_amd import binding as B
+    ws = B.Plan(cfg, 1 << 62, M).summary().workspace_bytes
+    return [int(wb * f) + ws + 4096 for f in fracs]
+
+
+def test_ffn_block_decode_half_budget():
+    """Config 1: RMSNorm -> gate/up -> SwiGLU -> down, one token, budget = 50% of the weight bytes."""
+    cfg = S.cfg_ffn_block()
+    wb, _ = Hn.total_weight_bytes(cfg)
+    _check(cfg, 0, 1, [wb // 2, 1 << 30, wb // 3, int(wb * 0.8)])
+
+
+def test_small_dense_decode_placements():
+    cfg = Hn.small_dense_cfg(3)
+    _check(cfg, 1, 1, _budgets(cfg, 1, [1.0, 0.7, 0.45, 0.3]))
+
+
+@pytest.mark.parametrize("M", [2, 16, 37, 64, 150])
+def test_small_dense_batched_and_prefill(M):
+    cfg = Hn.small_dense_cfg(2)
+    _check(cfg, 2, M, _budgets(cfg, M, [1.0, 0.5]))
+
+
+@pytest.mark.parametrize("M", [1, 5, 16])
+def test_small_moe(M):
+    cfg = Hn.small_moe_cfg(2)
+    lg = S.router_logits(3, 0, cfg["n_layers"], M, cfg["n_experts"])
+    _check(cfg, 3, M, _budgets(cfg, M, [1.0, 0.6, 0.35]), logits=lg)

@@ -1,0 +1,274 @@
+"""CPU tests of the host side of the library: C-ABI exports, the packer's layout, the planner
+(priority order, budget, monotonicity, estimate -- paper Section 3, Algorithm 1 and the timing
+estimate) and the schedule checker.  No GPU compute is called."""
+import ctypes as C
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from paper_2604_26334_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "pshard.h")).read()
+    declared = set(re.findall(r"\b(ps_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(B.ps_model_desc) == 44
+    assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS)
+    assert C.sizeof(B.ps_shard_info) == 48
+    assert C.sizeof(B.ps_op_info) == 48
+
+
+def test_tiers_are_the_papers_set():
+    # Section 3, inference phase: J = {1, 4, 16, 32, 64, 512, 1K, 2K, 4K, 8K, 16K}
+    lines = open(os.path.join(ROOT, "tests", "golden", "token_tiers.txt")).read().splitlines()
+    want = [int(x) for ln in lines if not ln.startswith("#") for x in ln.split()]
+    got = [B.lib().ps_tier_tokens(t) for t in range(B.PS_NTIERS)]
+    assert got == want
+    assert B.lib().ps_tier_for_tokens(1) == 0 and B.lib().ps_tier_for_tokens(2) == 1
+    assert B.lib().ps_tier_for_tokens(2048) == 7 and B.lib().ps_tier_for_tokens(65) == 5
+
+
+# ------------------------------------------------------------------ packer
+
+def _unpack(img, rows, K):
+    """Decode the documented layout back to (scales, codes) with plain index arithmetic."""
+    nsb, ngroups = K // 128, (K // 128 + 7) // 8
+    tile_bytes = (nsb + ngroups) * 1024
+    codes = np.zeros((rows, K), dtype=np.uint8)
+    scales = np.zeros((rows, K // 32), dtype=np.uint16)
+    for T in range(rows // 16):
+        tile = img[T * tile_bytes:(T + 1) * tile_bytes]
+        for g in range(ngroups):
+            nsb_g = min(8, nsb - 8 * g)
+            gb = tile[g * 9 * 1024:]
+            for s in range(nsb_g):
+                dw = gb[s * 1024:(s + 1) * 1024].view(np.uint32).reshape(64, 4)
+                for lane in range(64):
+                    i, c = lane & 15, lane >> 4
+                    b = 4 * (8 * g + s) + c
+                    for kk in range(4):
+                        v = int(dw[lane, kk])
+                        for t in range(8):
+                            codes[16 * T + i, 32 * b + 8 * kk + t] = (v >> (4 * ((t >> 1) + 4 * (t & 1)))) & 15
+            sc = gb[nsb_g * 1024:(nsb_g + 1) * 1024].view(np.uint16).reshape(64, 8)
+            for lane in range(64):
+                i, c = lane & 15, lane >> 4
+                for s in range(nsb_g):
+                    scales[16 * T + i, 4 * (8 * g + s) + c] = sc[lane, s]
+    return scales, codes
+
+
+@pytest.mark.parametrize("rows,K", [(16, 128), (32, 1024), (48, 1408), (16, 2816)])
+def test_pack_layout_round_trip(rows, K):
+    sc, cd = S.weight_matrix(7, 0, S.MAT_QKV, None, rows, K)
+    img = B.pack_matrix(sc, cd)
+    assert img.size == B.lib().ps_packed_bytes(rows, K) == rows // 16 * (K // 128 + (K // 128 + 7) // 8) * 1024
+    s2, c2 = _unpack(img, rows, K)
+    np.testing.assert_array_equal(c2, cd)
+    np.testing.assert_array_equal(s2, sc.view(np.uint16))
+
+
+def test_packed_bytes_equal_algorithmic_bytes_when_k_is_a_multiple_of_1024():
+    for rows, K in [(6144, 4096), (4096, 14336), (28672, 4096)]:
+        assert B.lib().ps_packed_bytes(rows, K) * 32 == rows * K * 18   # 18 bytes per 32 weights
+
+
+# ------------------------------------------------------------------ planner
+
+def _plan(cfg, budget, M=1, **kw):
+    p = B.Plan(cfg, int(budget), M, **kw)
+    return p, p.summary(), p.shards()
+
+
+def test_budget_is_honoured_and_accounts_add_up():
+    for cfg, M, budgets in [(S.cfg_ffn_block(), 1, [2433024, 10 ** 7]),
+                            (S.cfg_dense8b(), 1, [2e9, 4e9, 8e9]), (S.cfg_dense8b(), 2048, [4e9]),
+                            (S.cfg_moe(), 16, [6e9])]:
+        for b in budgets:
+            p, s, sh = _plan(cfg, b, M)
+            assert s.workspace_bytes + s.scratch_bytes + s.resident_bytes <= s.budget_bytes
+            assert s.resident_bytes + s.streamed_bytes == s.weight_bytes
+            assert sum(x.bytes for x in sh) == s.weight_bytes
+            hi = s.workspace_bytes + s.scratch_bytes
+            for x in sh:
+                if x.resident:
+                    assert x.offset >= hi and x.offset + x.bytes <= s.budget_bytes
+                else:
+                    assert x.bytes <= s.slot_bytes
+            # resident shards do not overlap
+            iv = sorted((x.offset, x.offset + x.bytes) for x in sh if x.resident)
+            assert all(a[1] <= b_[0] for a, b_ in zip(iv, iv[1:]))
+
+
+def test_dense_8b_expected_splits():
+    _, s, _ = _plan(S.cfg_dense8b(), 4e9, 1)
+    assert s.weight_bytes == 3925868544 and s.streamed_bytes == 0 and s.n_slots == 0
+    _, s, sh = _plan(S.cfg_dense8b(), 2e9, 1)
+    attn = sum(x.bytes for x in sh if x.cls == B.PS_CLASS_ATTN)
+    assert attn == 32 * (14155776 + 9437184)
+    assert all(x.resident for x in sh if x.cls == B.PS_CLASS_ATTN)
+    assert 1.9e9 < s.streamed_bytes < 2.1e9
+    _, s, _ = _plan(S.cfg_dense8b(), 4e9, 2048)
+    assert 0 < s.streamed_bytes < 0.35e9
+
+
+def test_priority_attention_before_ffn_and_first_fit():
+    # Section 3: attention sub-layers are pinned before FFN sub-layers, dense and MoE alike
+    for cfg, b, M in [(S.cfg_dense8b(), 1.0e9, 1), (S.cfg_moe(), 6e9, 1), (S.cfg_moe(4), 0.3e9, 16)]:
+        _, s, sh = _plan(cfg, b, M)
+        attn_streamed = [x for x in sh if x.cls == B.PS_CLASS_ATTN and not x.resident]
+        ffn_resident = [x for x in sh if x.cls == B.PS_CLASS_FFN and x.resident]
+        if attn_streamed:
+            free = s.budget_bytes - s.workspace_bytes - s.scratch_bytes - s.resident_bytes
+            assert not ffn_resident or all(x.bytes > free for x in attn_streamed)
+        ranks = [x.priority_rank for x in sh if x.cls == B.PS_CLASS_ATTN]
+        assert max(ranks) < min(x.priority_rank for x in sh if x.cls == B.PS_CLASS_FFN)
+
+
+def test_streamed_bytes_monotone_in_budget():
+    # the paper's evaluation appendix: throughput rises with budget; here: streamed bytes never rise
+    cfg = S.cfg_dense8b(8)
+    prev = None
+    for b in np.linspace(0.2e9, 1.2e9, 21):
+        _, s, _ = _plan(cfg, b, 1)
+        if prev is not None:
+            assert s.streamed_bytes <= prev
+        prev = s.streamed_bytes
+    assert prev == 0
+
+
+def test_budget_too_small_is_an_error_not_a_crash():
+    with pytest.raises(B.PshardError) as e:
+        B.Plan(S.cfg_dense8b(), 10 ** 6, 1)
+    assert e.value.code == B.PS_E_BUDGET
+    with pytest.raises(B.PshardError) as e:
+        B.Plan(dict(S.cfg_dense8b(), hidden=4000), 10 ** 9, 1)
+    assert e.value.code == B.PS_E_ARG
+    with pytest.raises(B.PshardError):
+        B.Plan(S.cfg_dense8b(), 10 ** 9, 0)
+
+
+def test_expert_frequency_ranks_hot_experts_first():
+    cfg = S.cfg_moe(2)
+    rng = np.random.default_rng(0)
+    freq = rng.random((2, 128)).astype(np.float32)
+    freq *= 8 / freq.sum(1, keepdims=True)
+    p, s, sh = _plan(cfg, 0.2e9, 1, expert_freq=freq)
+    ex = [x for x in sh if x.kind == B.PS_SHARD_EXPERT]
+    res = [freq[x.layer, x.expert] for x in ex if x.resident]
+    non = [freq[x.layer, x.expert] for x in ex if not x.resident]
+    assert res and non and min(res) >= max(non)
+    # without frequencies: (layer, expert) order
+    _, _, sh2 = _plan(cfg, 0.2e9, 1)
+    ex2 = [x for x in sh2 if x.kind == B.PS_SHARD_EXPERT]
+    flags = [x.resident for x in ex2]
+    assert flags == sorted(flags, reverse=True)
+
+
+def test_estimate_is_sum_of_max_compute_next_copy_on_a_toy():
+    # Section 3, timing estimation: shard time = max(own compute, concurrent copy of the next shard);
+    # plan time = sum.  Toy: FFN block, 1 layer, hand-computed from the shard list.
+    cfg = S.cfg_ffn_block()
+    prof = B.make_profile(h2d_gbps=10.0, gemv_gbps=100.0, gemm_tflops=1000.0, launch_us=2.0)
+    p, s, sh = _plan(cfg, 2433024, 1, profile=prof)
+    comp = [x.bytes / 100e9 * 1e3 + 2e-3 for x in sh]
+    copy = [0.0 if x.resident else x.bytes / 10e9 * 1e3 for x in sh]
+    want = copy[0] + sum(max(comp[i], copy[i + 1] if i + 1 < len(sh) else 0.0) for i in range(len(sh)))
+    assert abs(s.est_step_ms - want) < 1e-9 * max(1, want)
+    # compute-bound pricing takes over when the GEMM rate is the smaller roof
+    prof2 = B.make_profile(h2d_gbps=10.0, gemv_gbps=1e6, gemm_tflops=1e-3, launch_us=0.0)
+    _, s2, sh2 = _plan(cfg, 10 ** 8, 1, profile=prof2)
+    want2 = sum(2.0 * (x.bytes / 0.5625) / 1e9 * 1e3 for x in sh2)
+    assert abs(s2.est_step_ms - want2) < 1e-6 * want2
+
+
+def test_greedy_pinning_vs_brute_force_on_few_shards():
+    # with <= 12 whole shards: the pinned set respects priority (no lower-priority shard pinned
+    # while a higher-priority one that would fit in its place is streamed) and the budget
+    cfg = dict(S.cfg_dense8b(3), hidden=512, n_q_heads=4, n_kv_heads=2, ffn_inter=1408)
+    for b in [0.6e6, 1.2e6, 2.5e6, 4e6, 9e6]:
+        try:
+            _, s, sh = _plan(cfg, b, 1)
+        except B.PshardError:
+            continue
+        cap = s.budget_bytes - s.workspace_bytes - s.scratch_bytes
+        assert s.resident_bytes <= cap
+        whole = {}
+        for x in sh:
+            whole.setdefault((x.layer, x.kind), []).append(x)
+        order = sorted(whole, key=lambda k: whole[k][0].priority_rank)
+        # replay first-fit by hand
+        rem, split = cap, False
+        for k in order:
+            tot = sum(x.bytes for x in whole[k])
+            pinned = sum(x.bytes for x in whole[k] if x.resident)
+            if tot <= rem:
+                assert pinned == tot
+                rem -= tot
+            elif not split:
+                split = True
+                assert pinned <= rem
+                rem -= pinned
+            else:
+                assert pinned == 0
+
+
+# ------------------------------------------------------------------ schedule
+
+def test_schedules_validate_and_copy_every_streamed_shard_once():
+    for cfg, b, M in [(S.cfg_ffn_block(), 2433024, 1), (S.cfg_dense8b(), 2e9, 1), (S.cfg_dense8b(4), 0.25e9, 64)]:
+        p, s, sh = _plan(cfg, b, M)
+        sc = p.schedule()
+        sc.validate()
+        ops = sc.ops()
+        copies = [o for o in ops if o.type == B.PS_OP_COPY]
+        assert sorted(o.shard0 for o in copies) == [i for i, x in enumerate(sh) if not x.resident]
+        assert sum(o.bytes for o in copies) == s.streamed_bytes
+        for o in copies:
+            assert o.slot in (0, 1) and o.slot_offset + o.bytes <= s.slot_bytes
+
+
+def test_moe_schedule_copies_only_selected_nonresident_experts_after_routing():
+    cfg = S.cfg_moe(3)
+    M = 4
+    lg = S.router_logits(1, 0, 3, M, 128)
+    p, s, sh = _plan(cfg, 0.4e9, M)
+    sc = p.schedule(lg)
+    sc.validate()
+    ops = sc.ops()
+    routed = set()
+    for l in range(3):
+        idx = B.route_host(lg[l], 8)
+        routed |= {(l, int(e)) for e in idx.ravel()}
+    want = sorted(i for i, x in enumerate(sh) if x.kind == B.PS_SHARD_EXPERT and not x.resident
+                  and (x.layer, x.expert) in routed)
+    copies = [o for o in ops if o.type == B.PS_OP_COPY and sh[o.shard0].kind == B.PS_SHARD_EXPERT]
+    assert sorted(o.shard0 for o in copies) == want
+    seen_route = set()
+    for o in ops:
+        if o.type == B.PS_OP_KERNEL and o.kernel == B.PS_K_ROUTE:
+            seen_route.add(o.layer)
+        if o.type == B.PS_OP_COPY and sh[o.shard0].kind == B.PS_SHARD_EXPERT:
+            assert o.flags & B.PS_OPF_WAIT_ROUTER and o.layer in seen_route
+
+
+def test_route_host_matches_sort_rule():
+    lg = S.router_logits(5, 0, 1, 9, 128)[0]
+    lg[0, :] = 0.0
+    lg[1, [7, 90]] = 10.0
+    idx = B.route_host(lg, 8)
+    for m in range(9):
+        assert list(idx[m]) == sorted(range(128), key=lambda e: (-float(lg[m, e]), e))[:8]
