@@ -250,6 +250,9 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
 int32_t ps_stack_set_profiling(ps_stack *st, int32_t on);
 /* blocks until both streams are idle when profiling is on */
 int32_t ps_stack_stats(ps_stack *st, ps_stats *out);
+/* start (relative to the first op) and duration in ms of op i of the last profiled forward;
+ * ops are numbered as in the schedule of the same plan.  Blocks like ps_stack_stats. */
+int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur_ms);
 /* device pointers into the workspace for inspection by tests (fp16 unless noted):
  * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
  * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k] */

@@ -64,7 +64,7 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
-           "ps_stack_forward", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_debug_buffer",
+           "ps_stack_forward", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix"]
 
 _lib = None
@@ -76,6 +76,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libpshard.so is not built: run `python -m paper_2604_26334_amd.build`")
+        # torch ships its own HIP runtime; it must be in the process before libpshard.so so
+        # that both resolve libamdhip64 to the same loaded copy (two runtimes cannot share a GPU)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32
         L.ps_last_error.restype = C.c_char_p
@@ -101,6 +104,7 @@ def lib():
             "ps_stack_forward": [vp, vp, vp, vp],
             "ps_stack_set_profiling": [vp, i32],
             "ps_stack_stats": [vp, C.POINTER(ps_stats)],
+            "ps_stack_op_time": [vp, u32, C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "ps_stack_debug_buffer": [vp, u32, C.POINTER(vp), C.POINTER(u64)],
             "ps_mfma_probe": [i32, i32, i32, vp, vp],
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
@@ -287,6 +291,16 @@ class Stack:
             _check(lib().ps_stack_stats(self.h, C.byref(s)))
         return s
 
+    def op_times(self, n_ops):
+        """[(start_ms, dur_ms)] of the last profiled forward, one per schedule op."""
+        out = []
+        a, b = C.c_double(), C.c_double()
+        with self.torch.cuda.device(self.device):
+            for i in range(n_ops):
+                _check(lib().ps_stack_op_time(self.h, i, C.byref(a), C.byref(b)))
+                out.append((a.value, b.value))
+        return out
+
     def debug_buffer(self, which, dtype, shape):
         """Copy of a workspace buffer as a numpy array (synchronises first)."""
         self.synchronize()
@@ -321,11 +335,33 @@ def profile_measure(scratch_bytes=1 << 30, device="cuda:0"):
     return p
 
 
-def load_synthetic(stack, cfg, seed, weight_fn):
-    """Load every logical matrix of cfg into the stack; weight_fn(seed, layer, kind, expert, N, K)
-    returns (scales, codes).  Matrices are generated one at a time and dropped."""
+def load_synthetic(stacks, cfg, seed, threads=8, lookahead=12, progress=None):
+    """Generate every logical matrix of cfg with synth_inputs.weight_matrix (a pool of generator
+    threads, bounded look-ahead so the whole model is never resident on the host) and load it
+    into each stack of `stacks`."""
+    import collections
+    from concurrent.futures import ThreadPoolExecutor
     import synth_inputs as S
-    for layer in range(cfg["n_layers"]):
-        for kind, expert, N, K in S.matrix_shapes(cfg):
-            sc, cd = weight_fn(seed, layer, kind, expert, N, K)
-            stack.load_matrix(layer, kind, expert, sc, cd)
+    stacks = stacks if isinstance(stacks, (list, tuple)) else [stacks]
+    todo = [(layer, kind, expert, N, K) for layer in range(cfg["n_layers"])
+            for (kind, expert, N, K) in S.matrix_shapes(cfg)]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        q = collections.deque()
+        it = iter(todo)
+
+        def submit():
+            t = next(it, None)
+            if t is not None:
+                q.append((t, ex.submit(S.weight_matrix, seed, t[0], t[1], t[2], t[3], t[4])))
+        for _ in range(lookahead):
+            submit()
+        done = 0
+        while q:
+            (layer, kind, expert, N, K), fut = q.popleft()
+            sc, cd = fut.result()
+            submit()
+            for st in stacks:
+                st.load_matrix(layer, kind, expert, sc, cd)
+            done += 1
+            if progress and (done % progress == 0 or done == len(todo)):
+                print("  loaded %d / %d matrices" % (done, len(todo)), flush=True)

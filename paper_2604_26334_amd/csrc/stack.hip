@@ -48,6 +48,7 @@ struct ps_stack {
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
     std::vector<uint8_t> prof_is_copy;
+    std::vector<double> prof_start, prof_dur;
     bool prof_valid = false;
     ps_stats stats{};
 };
@@ -467,6 +468,7 @@ int32_t ps_stack_stats(ps_stack *st, ps_stats *out) {
         PS_HIP(hipStreamSynchronize(st->copy));
         PS_HIP(hipStreamSynchronize(st->compute));
         const size_t n = st->prof_is_copy.size();
+        st->prof_start.assign(n, 0.0); st->prof_dur.assign(n, 0.0);
         double copy_ms = 0, comp_ms = 0, t_min = 0, t_max = 0;
         bool first = true;
         for (size_t i = 0; i < n; ++i) {
@@ -474,6 +476,7 @@ int32_t ps_stack_stats(ps_stack *st, ps_stats *out) {
             PS_HIP(hipEventElapsedTime(&dur, st->prof_ev[2 * i], st->prof_ev[2 * i + 1]));
             PS_HIP(hipEventElapsedTime(&t0, st->prof_ev[0], st->prof_ev[2 * i]));
             (st->prof_is_copy[i] ? copy_ms : comp_ms) += dur;
+            st->prof_start[i] = t0; st->prof_dur[i] = dur;
             if (first || t0 < t_min) t_min = t0;
             if (first || t0 + dur > t_max) t_max = t0 + dur;
             first = false;
@@ -486,6 +489,14 @@ int32_t ps_stack_stats(ps_stack *st, ps_stats *out) {
         st->prof_valid = false;
     }
     *out = st->stats;
+    return PS_OK;
+}
+
+int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur_ms) {
+    if (!st || !start_ms || !dur_ms) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (st->prof_valid) { ps_stats tmp; int32_t rc = ps_stack_stats(st, &tmp); if (rc) return rc; }
+    if (i >= st->prof_dur.size()) { ps::set_error("no profiled op %u", i); return PS_E_ARG; }
+    *start_ms = st->prof_start[i]; *dur_ms = st->prof_dur[i];
     return PS_OK;
 }
 

@@ -31,7 +31,7 @@ def weight_matrix(seed, layer, kind, expert, N, K):
     e = NO_EXPERT if expert is None else expert
     g = _gen(seed, 1, layer, kind, e)
     scales = (np.abs(g.standard_normal((N, K // BLOCK), dtype=np.float32)) * np.float32(0.02)).astype(np.float16)
-    raw = np.frombuffer(g.bytes(N * K // 2), dtype=np.uint8)
+    raw = g.bit_generator.random_raw((N * K // 2 + 7) // 8).view(np.uint8)[: N * K // 2]
     codes = np.empty(N * K, dtype=np.uint8)
     codes[0::2] = raw & 15
     codes[1::2] = raw >> 4
