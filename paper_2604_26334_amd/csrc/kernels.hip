@@ -12,7 +12,15 @@ typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef float f4_t __attribute__((ext_vector_type(4)));
 
+typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ h2_t as_h2(uint32_t v) { return __builtin_bit_cast(h2_t, v); }
+
+// streaming 16-byte load: weights are read once per step, keep them out of the way of the caches
+__device__ __forceinline__ uint4 load_stream(const uint4 *p) {
+    const u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // 8 codes of one dword -> four fp16 pairs holding (q - 8), exact.  Codes sit in the
 // mantissa of 1024 + q (low nibbles) or 1024 + 16 q (next nibbles).
@@ -70,26 +78,63 @@ __device__ __forceinline__ uint32_t gather_col(uint32_t k, uint32_t x_off, uint3
 }
 
 // ------------------------------------------------------------------------------------
-// Decode kernel, one token: fused 4-bit dequant GEMV.  256 threads = 4 waves.  A "unit" is
-// one row-tile (16 outputs) or, for GATE_UP, a gate tile plus its up tile.  KSPLIT waves
-// share a unit, each taking every KSPLIT-th scale group of K; partial sums meet in LDS in
-// a fixed order, so a row's result does not depend on which slab or slot it came from.
-// x (with the RMSNorm sum of squares) is staged once per workgroup in LDS, permuted so that
-// the four 16-byte reads of a lane's block hit distinct banks.
+// Decode kernel, one token: fused 4-bit dequant GEMV.  A "unit" is one row-tile (16 outputs)
+// or, for GATE_UP, a gate tile plus its up tile.  KSPLIT waves share a unit, wave kpart taking
+// scale groups kpart, kpart + KSPLIT, ... of K; a workgroup holds NW / KSPLIT units.
+// Each wave first issues all weight loads of its group (they do not depend on the
+// activations), then fetches only the 1024 activations of that group and spreads them to its
+// lanes through a wave-private LDS window (LDS operations of one wave execute in order, so no
+// barrier is needed).  The RMSNorm sum of squares is accumulated from the same fetch.
+// Partial sums of the KSPLIT waves meet in LDS in a fixed order behind the only barrier, so
+// a row's result does not depend on which slab or slot it came from.
 // ------------------------------------------------------------------------------------
-template <int MODE, int KSPLIT>
-__global__ __launch_bounds__(256) void gemv_w4_kernel(GemvArgs a) {
-    extern __shared__ uint4 lds[];
-    uint4 *lds_x = lds;                                        // K/8 chunks
-    float *red = reinterpret_cast<float *>(lds + a.K / 8);      // [4 waves][2][16] + 4
+template <int NT>
+struct GemvBuf {
+    uint4 sc[NT];
+    uint4 wq[NT][8];
+    uint4 xa, xb;
+};
+
+template <int NT>
+__device__ __forceinline__ void gemv_issue(GemvBuf<NT> &b, const uint4 *W, uint32_t unit, uint32_t tile_u4,
+                                           uint32_t g, uint32_t nsb_g, uint32_t K, const __half *x,
+                                           uint32_t x_off, uint32_t x_group, int lane) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint4 *gb = W + (size_t)(unit * NT + t) * tile_u4 + (size_t)g * (9 * 64);
+        b.sc[t] = load_stream(gb + nsb_g * 64 + lane);
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            if ((uint32_t)s < nsb_g) b.wq[t][s] = load_stream(gb + s * 64 + lane);
+    }
+    // this group's activations: 128 chunks of 8, lane takes chunks lane and lane + 64
+    const uint32_t k0 = g * 1024u + (uint32_t)lane * 8u, k1 = k0 + 512u;
+    b.xa = make_uint4(0, 0, 0, 0);
+    b.xb = make_uint4(0, 0, 0, 0);
+    if (k0 < K) b.xa = *reinterpret_cast<const uint4 *>(x + gather_col(k0, x_off, x_group));
+    if (k1 < K) b.xb = *reinterpret_cast<const uint4 *>(x + gather_col(k1, x_off, x_group));
+}
+
+// chunk q (0..127) of a group -> slot in the wave's LDS window: block b = q / 4, part p = q % 4,
+// super-block sb = b / 4, c = b % 4; the four lanes groups c read distinct banks for a given p
+__device__ __forceinline__ uint32_t xslot(uint32_t q) {
+    const uint32_t b = q >> 2, p = q & 3u;
+    return (b >> 2) * 16u + p * 4u + (b & 3u);
+}
+
+template <int MODE, int KSPLIT, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a) {
     constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
-    constexpr int UNITS = 4 / KSPLIT;
+    constexpr int UNITS = NW / KSPLIT;
+    constexpr bool NORM = (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP);
+    __shared__ uint4 lds_x[NW][128];       // one 2 KB window per wave
+    __shared__ float red[NW][2][16];
+    __shared__ float red_ss[NW];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, c = lane >> 4;
 
     const uint4 *W = a.W;
     const __half *x = a.x;
-    uint32_t out_row_base = a.out_row0;
     __half *out = a.out;
     float *out_f32 = a.out_f32;
     if (a.tasks) {  // grouped launch: blockIdx.y selects the expert
@@ -106,62 +151,47 @@ __global__ __launch_bounds__(256) void gemv_w4_kernel(GemvArgs a) {
         }
     }
 
-    // stage x, accumulate sum of squares
-    float ss = 0.f;
-    for (uint32_t q = tid; q < a.K / 8; q += 256) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(x + gather_col(q * 8, a.x_off, a.x_group));
-        const uint32_t b = q >> 2, p = q & 3, sb = b >> 2, cc = b & 3;
-        lds_x[sb * 16 + p * 4 + cc] = v;
-        if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) ss += sumsq8(v);
-    }
-    float rinv = 1.f;
-    if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) {
-        ss = wave_sum(ss);
-        if (lane == 0) red[128 + wave] = ss;
-    }
-    __syncthreads();
-    if (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP) {
-        const float tot = (red[128] + red[129]) + (red[130] + red[131]);
-        rinv = rsqrtf(tot / (float)a.K + a.eps);
-    }
-
     const uint32_t unit = blockIdx.x * UNITS + wave / KSPLIT;
     const uint32_t kpart = wave % KSPLIT;
     const bool active = unit < a.nunits;
     float acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+    float ss = 0.f;
+    uint4 *win = lds_x[wave];
 
-    if (active) {
-        for (uint32_t g = kpart; g < a.ngroups; g += KSPLIT) {
+    if (active && kpart < a.ngroups) {
+        GemvBuf<NT> cur, nxt;
+        uint32_t g = kpart;
+        gemv_issue<NT>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), a.K, x, a.x_off, a.x_group, lane);
+        while (true) {
             const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
-            uint4 sc[NT], wq[NT][8];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const uint4 *gb = W + (size_t)(unit * NT + t) * a.tile_u4 + (size_t)g * (9 * 64);
-                sc[t] = gb[nsb_g * 64 + lane];
-#pragma unroll
-                for (int s = 0; s < 8; ++s)
-                    if ((uint32_t)s < nsb_g) wq[t][s] = gb[s * 64 + lane];
-            }
+            const uint32_t gn = g + KSPLIT;
+            const bool more = gn < a.ngroups;
+            if (more) gemv_issue<NT>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), a.K, x, a.x_off, a.x_group, lane);
+            win[xslot(lane)] = cur.xa;
+            win[xslot(lane + 64)] = cur.xb;
+            if (NORM) ss += sumsq8(cur.xa) + sumsq8(cur.xb);
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 if ((uint32_t)s < nsb_g) {
-                    const uint32_t sbi = g * 8 + s;
                     uint4 xv[4];
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) xv[p] = lds_x[sbi * 16 + p * 4 + c];
+                    for (int p = 0; p < 4; ++p) xv[p] = win[s * 16 + p * 4 + c];
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         float part = 0.f;
-                        part = dot8(wq[t][s].x, xv[0], part);
-                        part = dot8(wq[t][s].y, xv[1], part);
-                        part = dot8(wq[t][s].z, xv[2], part);
-                        part = dot8(wq[t][s].w, xv[3], part);
-                        acc[t] = fmaf(half_of(sc[t], s), part, acc[t]);
+                        part = dot8(cur.wq[t][s].x, xv[0], part);
+                        part = dot8(cur.wq[t][s].y, xv[1], part);
+                        part = dot8(cur.wq[t][s].z, xv[2], part);
+                        part = dot8(cur.wq[t][s].w, xv[3], part);
+                        acc[t] = fmaf(half_of(cur.sc[t], s), part, acc[t]);
                     }
                 }
             }
+            if (!more) break;
+            cur = nxt;
+            g = gn;
         }
     }
     // the 4 lanes of a row (c = 0..3) meet, then the KSPLIT waves of a unit
@@ -170,24 +200,33 @@ __global__ __launch_bounds__(256) void gemv_w4_kernel(GemvArgs a) {
         acc[t] += __shfl_xor(acc[t], 16, 64);
         acc[t] += __shfl_xor(acc[t], 32, 64);
     }
+    if (NORM) ss = wave_sum(ss);
     if (KSPLIT > 1) {
         if (c == 0) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) red[(wave * 2 + t) * 16 + i] = acc[t];
+            for (int t = 0; t < NT; ++t) red[wave][t][i] = acc[t];
         }
+        if (NORM && lane == 0) red_ss[wave] = ss;
         __syncthreads();
         if (kpart == 0 && c == 0) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                float v = red[(wave * 2 + t) * 16 + i];
+                float v = red[wave][t][i];
 #pragma unroll
-                for (int k = 1; k < KSPLIT; ++k) v += red[((wave + k) * 2 + t) * 16 + i];
+                for (int k = 1; k < KSPLIT; ++k) v += red[wave + k][t][i];
                 acc[t] = v;
+            }
+            if (NORM) {
+                float v = red_ss[wave];
+#pragma unroll
+                for (int k = 1; k < KSPLIT; ++k) v += red_ss[wave + k];
+                ss = v;
             }
         }
     }
     if (!active || kpart != 0 || c != 0) return;
-    const uint32_t row = out_row_base + unit * 16 + i;
+    const float rinv = NORM ? rsqrtf(ss / (float)a.K + a.eps) : 1.f;
+    const uint32_t row = a.out_row0 + unit * 16 + i;
     if (MODE == GEMV_PLAIN) {
         out[row] = __float2half(rinv * acc[0]);
     } else if (MODE == GEMV_RESID) {
@@ -202,24 +241,26 @@ __global__ __launch_bounds__(256) void gemv_w4_kernel(GemvArgs a) {
 
 template <int MODE, int KSPLIT>
 static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
-    constexpr int UNITS = 4 / KSPLIT;
+    constexpr int NW = KSPLIT > 4 ? KSPLIT : 4;
+    constexpr int UNITS = NW / KSPLIT;
     dim3 grid((a.nunits + UNITS - 1) / UNITS, ntasks ? ntasks : 1);
-    const size_t lds = (size_t)a.K * 2 + (128 + 4) * sizeof(float);
-    hipLaunchKernelGGL((gemv_w4_kernel<MODE, KSPLIT>), grid, dim3(256), lds, st, a);
+    hipLaunchKernelGGL((gemv_w4_kernel<MODE, KSPLIT, NW>), grid, dim3(NW * 64), 0, st, a);
     return hipGetLastError();
 }
 
-// KSPLIT depends on the matrix (K and its total tile count) only, never on the slab, so
-// every placement adds the same partial sums in the same order.
+// KSPLIT depends on the matrix (K and its total unit count) only, never on the slab, so
+// every placement adds the same partial sums in the same order.  It grows until the launch
+// has about two waves per SIMD or a wave is down to one scale group.
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
-    if (ngroups >= 4 && total_units < 2048) return 4;
-    if (ngroups >= 2 && total_units < 4096) return 2;
-    return 1;
+    uint32_t ks = 1;
+    while (ks < 8 && ks * 2 <= ngroups && total_units * ks < 2048) ks *= 2;
+    return ks;
 }
 
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
 #define PS_GEMV_CASE(M)                                                   \
     case M:                                                               \
+        if (ksplit == 8) return launch_gemv_t<M, 8>(a, ntasks, st);       \
         if (ksplit == 4) return launch_gemv_t<M, 4>(a, ntasks, st);       \
         if (ksplit == 2) return launch_gemv_t<M, 2>(a, ntasks, st);       \
         return launch_gemv_t<M, 1>(a, ntasks, st);
@@ -336,8 +377,9 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // ------------------------------------------------------------------------------------
 template <int MODE, int AT, int MT>
 __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
-    extern __shared__ uint4 lds[];
+    extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
+    constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, c = lane >> 4;
 
@@ -354,62 +396,102 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
     if (m0 >= ntok) return;
     const uint32_t tile_base = (blockIdx.x * 4 + wave) * AT;
 
-    // token rows handled by this thread during the LDS fill: MT*16 chunks / 256 threads
+    // activation fill: thread moves chunk u of tokens tok0, tok0 + 16, ... of the tile
+    const uint32_t u = tid & 15, tok0 = tid >> 4;
+    const uint32_t fill_dst = tok0 * 16 + (u ^ (tok0 & 15));   // + r * 256 for token tok0 + 16 r
+    uint32_t xoff[NFILL];
+    bool xok[NFILL];
+#pragma unroll
+    for (int r = 0; r < NFILL; ++r) {
+        const uint32_t tok = m0 + tok0 + r * 16;
+        xok[r] = tok < ntok;
+        size_t rowi = xok[r] ? tok : m0;
+        if (pairs) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[rowi] / (int32_t)a.top_k) : (size_t)pairs[rowi];
+        xoff[r] = (uint32_t)(rowi * a.x_stride);
+    }
+    // weights: per tile a pointer to its first group; tiles past the slab read tile 0 (discarded)
+    const uint4 *wt[AT];
+#pragma unroll
+    for (int t = 0; t < AT; ++t) {
+        const uint32_t tile = tile_base + t < a.ntiles ? tile_base + t : 0;
+        wt[t] = W + (size_t)tile * a.tile_u4 + lane;
+    }
+
     f4_t acc[AT][NMT];
 #pragma unroll
     for (int t = 0; t < AT; ++t)
 #pragma unroll
         for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (uint32_t sb = 0; sb < a.nsb; ++sb) {
-        __syncthreads();
-        // fill: chunk id = tid + r*256 -> token = id / 16, u = id % 16
+    uint4 xr[NFILL], wq[AT], wn[AT], sc[AT];
+    auto load_x = [&](uint32_t sb) {
+        const uint32_t col = gather_col(sb * 128 + u * 8, a.x_off, a.x_group);
 #pragma unroll
-        for (int r = 0; r < MT / 16; ++r) {
-            const uint32_t id = tid + r * 256, tok = id >> 4, u = id & 15;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m0 + tok < ntok) {
-                size_t rowi = m0 + tok;
-                if (pairs) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[m0 + tok] / (int32_t)a.top_k) : (size_t)pairs[m0 + tok];
-                v = *reinterpret_cast<const uint4 *>(a.x + rowi * a.x_stride + gather_col(sb * 128 + u * 8, a.x_off, a.x_group));
-            }
-            lds[tok * 16 + (u ^ (tok & 15))] = v;
-        }
-        __syncthreads();
-        const uint32_t g = sb >> 3, s = sb & 7;
+        for (int r = 0; r < NFILL; ++r)
+            xr[r] = xok[r] ? *reinterpret_cast<const uint4 *>(a.x + xoff[r] + col) : make_uint4(0, 0, 0, 0);
+    };
+    auto store_x = [&](uint32_t stage) {
+#pragma unroll
+        for (int r = 0; r < NFILL; ++r) lds[stage * (MT * 16) + fill_dst + r * 256] = xr[r];
+    };
+
+    const uint32_t ngroups = (a.nsb + 7) / 8;
+    load_x(0);
+#pragma unroll
+    for (int t = 0; t < AT; ++t) wn[t] = load_stream(wt[t]);
+    store_x(0);
+    __syncthreads();
+
+    uint32_t sb = 0;
+    for (uint32_t g = 0; g < ngroups; ++g) {
         const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
-        h8_t A[AT][4];
 #pragma unroll
-        for (int t = 0; t < AT; ++t) {
-            if (tile_base + t < a.ntiles) {
-                const uint4 *gb = W + (size_t)(tile_base + t) * a.tile_u4 + (size_t)g * (9 * 64);
-                const uint4 wq = gb[s * 64 + lane];
-                const uint16_t dbits = reinterpret_cast<const uint16_t *>(gb + nsb_g * 64 + lane)[s];
-                const _Float16 d = __builtin_bit_cast(_Float16, dbits);
-                const h2_t dd = {d, d};
-                const uint32_t q[4] = {wq.x, wq.y, wq.z, wq.w};
+        for (int t = 0; t < AT; ++t) sc[t] = wt[t][(size_t)g * (9 * 64) + nsb_g * 64];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            if ((uint32_t)s < nsb_g) {
+                const uint32_t stage = sb & 1;
+#pragma unroll
+                for (int t = 0; t < AT; ++t) wq[t] = wn[t];
+                const bool more = sb + 1 < a.nsb;
+                if (more) {   // prefetch the next super-block: activations to registers, weights
+                    load_x(sb + 1);
+                    const uint32_t gn = (sb + 1) >> 3, sn = (sb + 1) & 7;
+#pragma unroll
+                    for (int t = 0; t < AT; ++t) wn[t] = load_stream(wt[t] + (size_t)gn * (9 * 64) + sn * 64);
+                }
+                _Float16 d[AT];
+#pragma unroll
+                for (int t = 0; t < AT; ++t) {
+                    const uint32_t dw = (s < 2) ? sc[t].x : (s < 4) ? sc[t].y : (s < 6) ? sc[t].z : sc[t].w;
+                    d[t] = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
+                }
+                const uint4 *ls = lds + stage * (MT * 16);
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    h2_t w[4];
-                    dequant8(q[kk], w);
-                    w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
-                    A[t][kk] = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+                    h8_t A[AT];
+#pragma unroll
+                    for (int t = 0; t < AT; ++t) {
+                        const uint32_t q = kk == 0 ? wq[t].x : kk == 1 ? wq[t].y : kk == 2 ? wq[t].z : wq[t].w;
+                        const h2_t dd = {d[t], d[t]};
+                        h2_t w[4];
+                        dequant8(q, w);
+                        w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+                        A[t] = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+                    }
+#pragma unroll
+                    for (int n = 0; n < NMT; ++n) {
+                        const uint32_t tok = n * 16 + i;  // B operand: lane (j = i, c) holds token j
+                        const uint4 bv = ls[tok * 16 + ((c * 4 + kk) ^ i)];
+                        const h8_t B = __builtin_bit_cast(h8_t, bv);
+#pragma unroll
+                        for (int t = 0; t < AT; ++t)
+                            acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], B, acc[t][n], 0, 0, 0);
+                    }
                 }
-            } else {
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) A[t][kk] = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            }
-        }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-            for (int n = 0; n < NMT; ++n) {
-                const uint32_t tok = n * 16 + i;  // B operand: lane (j = i, c) holds token j
-                const uint4 bv = lds[tok * 16 + ((c * 4 + kk) ^ (tok & 15))];
-                const h8_t B = __builtin_bit_cast(h8_t, bv);
-#pragma unroll
-                for (int t = 0; t < AT; ++t)
-                    acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t][kk], B, acc[t][n], 0, 0, 0);
+                if (more) store_x(stage ^ 1);
+                __syncthreads();
+                ++sb;
             }
         }
     }
@@ -471,7 +553,7 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
 template <int MODE, int AT, int MT>
 static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
     dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : 1);
-    const size_t lds = (size_t)MT * 256;
+    const size_t lds = (size_t)MT * 256 * 2;
     hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
