@@ -376,7 +376,7 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // XOR-swizzled by token so that operand reads are conflict-free.
 // ------------------------------------------------------------------------------------
 template <int MODE, int AT, int MT>
-__global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
+__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
     constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
@@ -423,7 +423,8 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
 
-    uint4 xr[NFILL], wq[AT], wn[AT], sc[AT];
+    uint4 xr[NFILL], wq[AT], wn[AT];
+    uint16_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block
     auto load_x = [&](uint32_t sb) {
         const uint32_t col = gather_col(sb * 128 + u * 8, a.x_off, a.x_group);
 #pragma unroll
@@ -438,7 +439,10 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
     const uint32_t ngroups = (a.nsb + 7) / 8;
     load_x(0);
 #pragma unroll
-    for (int t = 0; t < AT; ++t) wn[t] = load_stream(wt[t]);
+    for (int t = 0; t < AT; ++t) {
+        wn[t] = load_stream(wt[t]);
+        dn[t] = reinterpret_cast<const uint16_t *>(wt[t] + min(8u, a.nsb) * 64)[0];
+    }
     store_x(0);
     __syncthreads();
 
@@ -446,27 +450,27 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
     for (uint32_t g = 0; g < ngroups; ++g) {
         const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
 #pragma unroll
-        for (int t = 0; t < AT; ++t) sc[t] = wt[t][(size_t)g * (9 * 64) + nsb_g * 64];
-#pragma unroll
         for (int s = 0; s < 8; ++s) {
             if ((uint32_t)s < nsb_g) {
                 const uint32_t stage = sb & 1;
 #pragma unroll
-                for (int t = 0; t < AT; ++t) wq[t] = wn[t];
+                for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
                 const bool more = sb + 1 < a.nsb;
                 if (more) {   // prefetch the next super-block: activations to registers, weights
                     load_x(sb + 1);
                     const uint32_t gn = (sb + 1) >> 3, sn = (sb + 1) & 7;
+                    const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
 #pragma unroll
-                    for (int t = 0; t < AT; ++t) wn[t] = load_stream(wt[t] + (size_t)gn * (9 * 64) + sn * 64);
+                    for (int t = 0; t < AT; ++t) {
+                        const uint4 *gb = wt[t] + (size_t)gn * (9 * 64);
+                        wn[t] = load_stream(gb + sn * 64);
+                        dn[t] = reinterpret_cast<const uint16_t *>(gb + nsb_n * 64)[sn];
+                    }
                 }
                 _Float16 d[AT];
 #pragma unroll
-                for (int t = 0; t < AT; ++t) {
-                    const uint32_t dw = (s < 2) ? sc[t].x : (s < 4) ? sc[t].y : (s < 6) ? sc[t].z : sc[t].w;
-                    d[t] = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
-                }
-                const uint4 *ls = lds + stage * (MT * 16);
+                for (int t = 0; t < AT; ++t) d[t] = __builtin_bit_cast(_Float16, dq[t]);
+                const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     h8_t A[AT];
@@ -481,9 +485,7 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(GemmArgs a) {
                     }
 #pragma unroll
                     for (int n = 0; n < NMT; ++n) {
-                        const uint32_t tok = n * 16 + i;  // B operand: lane (j = i, c) holds token j
-                        const uint4 bv = ls[tok * 16 + ((c * 4 + kk) ^ i)];
-                        const h8_t B = __builtin_bit_cast(h8_t, bv);
+                        const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c * 4 + kk) ^ i)]);
 #pragma unroll
                         for (int t = 0; t < AT; ++t)
                             acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], B, acc[t][n], 0, 0, 0);

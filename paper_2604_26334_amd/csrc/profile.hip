@@ -35,10 +35,10 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
     void *host = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     float ms = 0;
-    const MatGeom mg = make_geom(2048, 4096, false);  // a 2048 x 4096 matrix, 128 tiles
+    const MatGeom mg = make_geom(8192, 4096, false);  // an 8192 x 4096 matrix, 512 tiles
     __half *x = reinterpret_cast<__half *>(base);                         // [2048][4096] fp16 = 16 MiB
-    __half *y = reinterpret_cast<__half *>(base + (16ull << 20));         // [2048][2048] fp16 = 8 MiB
-    float *rinv = reinterpret_cast<float *>(base + (24ull << 20));
+    __half *y = reinterpret_cast<__half *>(base + (16ull << 20));         // [2048][8192] fp16 = 32 MiB
+    float *rinv = reinterpret_cast<float *>(base + (56ull << 20));
     uint8_t *wts = base + kHead;
     const uint64_t wbytes = scratch_bytes - kHead;
     *out = ps_profile{};
@@ -95,7 +95,7 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
         GemmArgs a{};
         a.W = reinterpret_cast<const uint4 *>(wts); a.ntiles = mg.ntiles; a.tile_u4 = (uint32_t)(mg.tile_bytes / 16);
         a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = 4096; a.x_group = 1; a.rinv = rinv; a.out = y;
-        a.out_stride = 2048; a.top_k = 1;
+        a.out_stride = 8192; a.top_k = 1;
         PS_HIP(launch_rinv(x, T, 4096, 1e-6f, rinv, cs));
         for (int rep = 0; rep < 2; ++rep) {
             PS_HIP(hipEventRecord(e0, cs));
@@ -104,7 +104,7 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
             PS_HIP(hipEventSynchronize(e1));
         }
         PS_HIP(hipEventElapsedTime(&ms, e0, e1));
-        out->gemm_tflops[t] = 2.0 * T * 2048.0 * 4096.0 * kLaunches / (ms * 1e-3) / 1e12;
+        out->gemm_tflops[t] = 2.0 * T * 8192.0 * 4096.0 * kLaunches / (ms * 1e-3) / 1e12;
     }
 done:
     if (host) (void)hipHostFree(host);
