@@ -35,6 +35,7 @@ struct GemvArgs {
 struct GemmArgs {
     const uint4 *W;
     uint32_t ntiles;      // row-tiles in this launch
+    uint32_t total_tiles; // row-tiles of the whole matrix (picks the tile shape)
     uint32_t tile_u4, nsb;
     uint32_t M;
     const __half *x;

@@ -24,15 +24,22 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
 
 // 8 codes of one dword -> four fp16 pairs holding (q - 8), exact.  Codes sit in the
 // mantissa of 1024 + q (low nibbles) or 1024 + 16 q (next nibbles).
+// (v & mask) | magic in one VALU op: the mask rides the scalar operand slot, the magic a VGPR
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(magic));
+    return r;
+}
+
 __device__ __forceinline__ void dequant8(uint32_t v, h2_t w[4]) {
     const h2_t k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
     const h2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
     const h2_t k72 = {(_Float16)72.0f, (_Float16)72.0f};
     const uint32_t v8 = v >> 8;
-    w[0] = as_h2((v & 0x000F000Fu) | 0x64006400u) - k1032;
-    w[1] = as_h2((v & 0x00F000F0u) | 0x64006400u) * k16th - k72;
-    w[2] = as_h2((v8 & 0x000F000Fu) | 0x64006400u) - k1032;
-    w[3] = as_h2((v8 & 0x00F000F0u) | 0x64006400u) * k16th - k72;
+    w[0] = as_h2(and_or(v, 0x000F000Fu, 0x64006400u)) - k1032;
+    w[1] = as_h2(and_or(v, 0x00F000F0u, 0x64006400u)) * k16th - k72;
+    w[2] = as_h2(and_or(v8, 0x000F000Fu, 0x64006400u)) - k1032;
+    w[3] = as_h2(and_or(v8, 0x00F000F0u, 0x64006400u)) * k16th - k72;
 }
 
 __device__ __forceinline__ float dot8(uint32_t v, uint4 x, float acc) {
@@ -565,6 +572,10 @@ static hipError_t launch_gemm_m(const GemmArgs &a, uint32_t ntasks, uint32_t max
     if (max_tok <= 16) return launch_gemm_t<MODE, 2, 16>(a, ntasks, max_tok, st);
     if (max_tok <= 32) return launch_gemm_t<MODE, 2, 32>(a, ntasks, max_tok, st);
     if (max_tok <= 64) return launch_gemm_t<MODE, 2, 64>(a, ntasks, max_tok, st);
+    // narrow matrices: halve the row extent of a workgroup so that the launch still has two
+    // workgroups per CU (the choice depends on the matrix, not on the slab)
+    const uint64_t wgs = (uint64_t)((a.total_tiles + 15) / 16) * ((max_tok + 127) / 128) * (ntasks ? ntasks : 1);
+    if (wgs < 512) return launch_gemm_t<MODE, 2, 128>(a, ntasks, max_tok, st);
     return launch_gemm_t<MODE, 4, 128>(a, ntasks, max_tok, st);
 }
 

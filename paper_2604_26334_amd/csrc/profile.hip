@@ -93,7 +93,7 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
         const uint32_t T = std::min(ps_tier_tokens(t), 2048u);
         if (ps_tier_tokens(t) > 2048) { out->gemm_tflops[t] = out->gemm_tflops[t - 1]; continue; }
         GemmArgs a{};
-        a.W = reinterpret_cast<const uint4 *>(wts); a.ntiles = mg.ntiles; a.tile_u4 = (uint32_t)(mg.tile_bytes / 16);
+        a.W = reinterpret_cast<const uint4 *>(wts); a.ntiles = mg.ntiles; a.total_tiles = mg.ntiles; a.tile_u4 = (uint32_t)(mg.tile_bytes / 16);
         a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = 4096; a.x_group = 1; a.rinv = rinv; a.out = y;
         a.out_stride = 8192; a.top_k = 1;
         PS_HIP(launch_rinv(x, T, 4096, 1e-6f, rinv, cs));

@@ -111,7 +111,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     };
     auto gemm_base = [&](const MatGeom &mg) {
         GemmArgs a{};
-        a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.M = M;
+        a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.M = M; a.total_tiles = mg.ntiles;
         a.x_group = 1; a.rinv = rinv; a.top_k = std::max(1u, m.top_k);
         return a;
     };
