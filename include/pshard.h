@@ -246,6 +246,15 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
+/* Decode execution mode (default 0).  persistent = 1: when the plan is dense, one token and
+ * every shard is resident, the whole pass runs as ONE persistent kernel with grid-wide barriers
+ * between the matmuls instead of one launch each (Algorithm 1's RunInTopologicalOrder,
+ * the order and arithmetic are unchanged and results are bit-identical).  Other plans, and
+ * persistent = 0, use one launch per shard.  Not to be called while a forward is in flight. */
+int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t persistent);
+/* Block until both streams are idle; PS_E_HIP if the persistent kernel reported a barrier
+ * time-out (its bounded waits make the kernel drain instead of hanging). */
+int32_t ps_stack_sync_check(ps_stack *st);
 /* record per-op timing events in the next forwards (adds event overhead) */
 int32_t ps_stack_set_profiling(ps_stack *st, int32_t on);
 /* blocks until both streams are idle when profiling is on */
@@ -255,7 +264,9 @@ int32_t ps_stack_stats(ps_stack *st, ps_stats *out);
 int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur_ms);
 /* device pointers into the workspace for inspection by tests (fp16 unless noted):
  * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
- * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k] */
+ * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k],
+ * 5: uint32 timeline of the persistent decode kernel's last profiled pass (100 MHz ticks):
+ *    for its first and its last workgroup, [start, then per phase: items done, barrier passed] */
 int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes);
 void ps_stack_destroy(ps_stack *st);
 

@@ -11,7 +11,10 @@ LIB = os.path.join(HERE, "libpshard.so")
 BUILD = os.path.join(HERE, "_build")
 SOURCES = ["planner.cpp", "schedule.cpp", "pack.cpp", "kernels.hip", "stack.hip", "profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+# -ffp-contract=off: results must not depend on which kernel a device function was inlined into
+# (the launch-per-shard and persistent decode paths have to agree bit for bit); fused multiply-adds
+# are written out with fmaf where they are wanted
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -37,9 +37,9 @@ __device__ __forceinline__ void dequant8(uint32_t v, h2_t w[4]) {
     const h2_t k72 = {(_Float16)72.0f, (_Float16)72.0f};
     const uint32_t v8 = v >> 8;
     w[0] = as_h2(and_or(v, 0x000F000Fu, 0x64006400u)) - k1032;
-    w[1] = as_h2(and_or(v, 0x00F000F0u, 0x64006400u)) * k16th - k72;
+    w[1] = __builtin_elementwise_fma(as_h2(and_or(v, 0x00F000F0u, 0x64006400u)), k16th, -k72);
     w[2] = as_h2(and_or(v8, 0x000F000Fu, 0x64006400u)) - k1032;
-    w[3] = as_h2(and_or(v8, 0x00F000F0u, 0x64006400u)) * k16th - k72;
+    w[3] = __builtin_elementwise_fma(as_h2(and_or(v8, 0x00F000F0u, 0x64006400u)), k16th, -k72);
 }
 
 __device__ __forceinline__ float dot8(uint32_t v, uint4 x, float acc) {
@@ -76,6 +76,14 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// fp32 -> fp16 with the rounding kept as its own step: the value passes through an opaque
+// register so the compiler cannot merge the producing multiply/add into a mixed-precision
+// convert in one kernel and not in another (the decode paths must agree bit for bit)
+__device__ __forceinline__ __half to_half(float v) {
+    asm volatile("" : "+v"(v));
+    return __float2half(v);
+}
+
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
 // source column of logical input column k: identity, or the identity-on-V attention
@@ -95,6 +103,18 @@ __device__ __forceinline__ uint32_t gather_col(uint32_t k, uint32_t x_off, uint3
 // Partial sums of the KSPLIT waves meet in LDS in a fixed order behind the only barrier, so
 // a row's result does not depend on which slab or slot it came from.
 // ------------------------------------------------------------------------------------
+// Activations cross workgroups inside the persistent kernel, so there (COH) they are moved with
+// device-scope atomic loads/stores, which bypass the caches that are not coherent between the
+// chip's XCDs; no bulk cache write-back or invalidate is then needed at a grid barrier.
+template <bool COH>
+__device__ __forceinline__ uint4 load_act16(const __half *p) {
+    if (!COH) return *reinterpret_cast<const uint4 *>(p);
+    uint64_t *q = reinterpret_cast<uint64_t *>(const_cast<__half *>(p));
+    const uint64_t lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint64_t hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
 template <int NT>
 struct GemvBuf {
     uint4 sc[NT];
@@ -102,10 +122,10 @@ struct GemvBuf {
     uint4 xa, xb;
 };
 
+// weights of scale group g of a unit's NT tiles (independent of the activations)
 template <int NT>
-__device__ __forceinline__ void gemv_issue(GemvBuf<NT> &b, const uint4 *W, uint32_t unit, uint32_t tile_u4,
-                                           uint32_t g, uint32_t nsb_g, uint32_t K, const __half *x,
-                                           uint32_t x_off, uint32_t x_group, int lane) {
+__device__ __forceinline__ void gemv_issue_w(GemvBuf<NT> &b, const uint4 *W, uint32_t unit, uint32_t tile_u4,
+                                             uint32_t g, uint32_t nsb_g, int lane) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const uint4 *gb = W + (size_t)(unit * NT + t) * tile_u4 + (size_t)g * (9 * 64);
@@ -114,12 +134,17 @@ __device__ __forceinline__ void gemv_issue(GemvBuf<NT> &b, const uint4 *W, uint3
         for (int s = 0; s < 8; ++s)
             if ((uint32_t)s < nsb_g) b.wq[t][s] = load_stream(gb + s * 64 + lane);
     }
-    // this group's activations: 128 chunks of 8, lane takes chunks lane and lane + 64
+}
+
+// activations of scale group g: 128 chunks of 8, lane takes chunks lane and lane + 64
+template <int NT, bool COH>
+__device__ __forceinline__ void gemv_issue_x(GemvBuf<NT> &b, uint32_t g, uint32_t K, const __half *x,
+                                             uint32_t x_off, uint32_t x_group, int lane) {
     const uint32_t k0 = g * 1024u + (uint32_t)lane * 8u, k1 = k0 + 512u;
     b.xa = make_uint4(0, 0, 0, 0);
     b.xb = make_uint4(0, 0, 0, 0);
-    if (k0 < K) b.xa = *reinterpret_cast<const uint4 *>(x + gather_col(k0, x_off, x_group));
-    if (k1 < K) b.xb = *reinterpret_cast<const uint4 *>(x + gather_col(k1, x_off, x_group));
+    if (k0 < K) b.xa = load_act16<COH>(x + gather_col(k0, x_off, x_group));
+    if (k1 < K) b.xb = load_act16<COH>(x + gather_col(k1, x_off, x_group));
 }
 
 // chunk q (0..127) of a group -> slot in the wave's LDS window: block b = q / 4, part p = q % 4,
@@ -129,53 +154,82 @@ __device__ __forceinline__ uint32_t xslot(uint32_t q) {
     return (b >> 2) * 16u + p * 4u + (b & 3u);
 }
 
-template <int MODE, int KSPLIT, int NW>
-__global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a) {
+// LDS of one decode workgroup of NW waves: a 2 KB activation window per wave and two
+// generations of cross-wave reduction scratch (consecutive items alternate, so a fast wave
+// can never overwrite sums that a slow wave of the previous item is still reading).
+template <int NW>
+struct GemvLds {
+    uint4 x[NW][128];
+    float red[2][NW][2][16];
+    float red_ss[2][NW];
+};
+
+// One work item of the decode GEMV: the NW waves of the workgroup cover NW / ks units, ks
+// waves per unit.  `gen` selects the reduction scratch generation.
+// With use_pre, `pre` already holds (or has in flight) the weights of this wave's first group.
+// DBUF: a wave with several scale groups issues the next group's loads before computing the
+// current one (costs a second register buffer; the one-tile modes can afford it).
+struct NoPrefetch {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// after_issue() runs once this item's first loads are in flight and `pre` has been consumed:
+// the persistent kernel uses it to start the weight loads of its NEXT item, so that they
+// stream while this item waits for its activations, computes, and crosses the barrier.
+template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = (MODE == GEMV_RESID || MODE == GEMV_F32)>
+__device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, const __half *x, __half *out,
+                                          float *out_f32, uint32_t item, uint32_t ks, uint32_t gen,
+                                          GemvLds<NW> &lds, const GemvBuf<2> &pre, bool use_pre,
+                                          F after_issue = F()) {
     constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
-    constexpr int UNITS = NW / KSPLIT;
     constexpr bool NORM = (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP);
-    __shared__ uint4 lds_x[NW][128];       // one 2 KB window per wave
-    __shared__ float red[NW][2][16];
-    __shared__ float red_ss[NW];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, c = lane >> 4;
-
-    const uint4 *W = a.W;
-    const __half *x = a.x;
-    __half *out = a.out;
-    float *out_f32 = a.out_f32;
-    if (a.tasks) {  // grouped launch: blockIdx.y selects the expert
-        const DeviceTask t = a.tasks[blockIdx.y];
-        const uint32_t pair = (uint32_t)a.pairs[t.pair0];
-        if (MODE == GEMV_GATE_UP) {
-            W = reinterpret_cast<const uint4 *>(t.w_gate_up);
-            x = a.x + (size_t)(pair / a.top_k) * a.x_stride;
-            out = a.out + (size_t)pair * a.out_stride;
-        } else {
-            W = reinterpret_cast<const uint4 *>(t.w_down);
-            x = a.x + (size_t)pair * a.x_stride;
-            out_f32 = a.out_f32 + (size_t)pair * a.out_stride;
-        }
-    }
-
-    const uint32_t unit = blockIdx.x * UNITS + wave / KSPLIT;
-    const uint32_t kpart = wave % KSPLIT;
+    const uint32_t units = NW / ks;
+    const uint32_t unit = item * units + wave / ks;
+    const uint32_t kpart = wave % ks;
     const bool active = unit < a.nunits;
     float acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = 0.f;
     float ss = 0.f;
-    uint4 *win = lds_x[wave];
+    uint4 *win = lds.x[wave];
+    const uint32_t row = a.out_row0 + unit * 16 + i;
+    float resv = 0.f;   // residual of this lane's output row, fetched early (it only waits on the previous phase)
+    const bool writer = active && kpart == 0 && c == 0;
 
     if (active && kpart < a.ngroups) {
         GemvBuf<NT> cur, nxt;
         uint32_t g = kpart;
-        gemv_issue<NT>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), a.K, x, a.x_off, a.x_group, lane);
+        if (use_pre) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                cur.sc[t] = pre.sc[t];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) cur.wq[t][s] = pre.wq[t][s];
+            }
+        } else {
+            gemv_issue_w<NT>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), lane);
+        }
+        gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
+        if (MODE == GEMV_RESID && writer && a.res) {
+            if (COH) {  // written by other workgroups: read the 32-bit word holding it at device scope
+                const uint32_t wd = __hip_atomic_load(reinterpret_cast<uint32_t *>(const_cast<__half *>(a.res)) + (row >> 1),
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                resv = (float)__builtin_bit_cast(_Float16, (uint16_t)((row & 1u) ? (wd >> 16) : (wd & 0xFFFFu)));
+            } else {
+                resv = __half2float(a.res[row]);
+            }
+        }
+        after_issue();
         while (true) {
             const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
-            const uint32_t gn = g + KSPLIT;
+            const uint32_t gn = g + ks;
             const bool more = gn < a.ngroups;
-            if (more) gemv_issue<NT>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), a.K, x, a.x_off, a.x_group, lane);
+            if (DBUF && more) {
+                gemv_issue_w<NT>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
+                gemv_issue_x<NT, COH>(nxt, gn, a.K, x, a.x_off, a.x_group, lane);
+            }
             win[xslot(lane)] = cur.xa;
             win[xslot(lane + 64)] = cur.xb;
             if (NORM) ss += sumsq8(cur.xa) + sumsq8(cur.xb);
@@ -197,65 +251,101 @@ __global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a) {
                 }
             }
             if (!more) break;
-            cur = nxt;
+            if (DBUF) {
+                cur = nxt;
+            } else {
+                gemv_issue_w<NT>(cur, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
+                gemv_issue_x<NT, COH>(cur, gn, a.K, x, a.x_off, a.x_group, lane);
+            }
             g = gn;
         }
+    } else {
+        after_issue();
     }
-    // the 4 lanes of a row (c = 0..3) meet, then the KSPLIT waves of a unit
+    // the 4 lanes of a row (c = 0..3) meet, then the ks waves of a unit
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         acc[t] += __shfl_xor(acc[t], 16, 64);
         acc[t] += __shfl_xor(acc[t], 32, 64);
     }
     if (NORM) ss = wave_sum(ss);
-    if (KSPLIT > 1) {
+    if (ks > 1) {
         if (c == 0) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) red[wave][t][i] = acc[t];
+            for (int t = 0; t < NT; ++t) lds.red[gen][wave][t][i] = acc[t];
         }
-        if (NORM && lane == 0) red_ss[wave] = ss;
+        if (NORM && lane == 0) lds.red_ss[gen][wave] = ss;
         __syncthreads();
         if (kpart == 0 && c == 0) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                float v = red[wave][t][i];
-#pragma unroll
-                for (int k = 1; k < KSPLIT; ++k) v += red[wave + k][t][i];
+                float v = lds.red[gen][wave][t][i];
+                for (uint32_t k = 1; k < ks; ++k) v += lds.red[gen][wave + k][t][i];
                 acc[t] = v;
             }
             if (NORM) {
-                float v = red_ss[wave];
-#pragma unroll
-                for (int k = 1; k < KSPLIT; ++k) v += red_ss[wave + k];
+                float v = lds.red_ss[gen][wave];
+                for (uint32_t k = 1; k < ks; ++k) v += lds.red_ss[gen][wave + k];
                 ss = v;
             }
         }
     }
-    if (!active || kpart != 0 || c != 0) return;
+    if (!writer) return;
     const float rinv = NORM ? rsqrtf(ss / (float)a.K + a.eps) : 1.f;
-    const uint32_t row = a.out_row0 + unit * 16 + i;
-    if (MODE == GEMV_PLAIN) {
-        out[row] = __float2half(rinv * acc[0]);
-    } else if (MODE == GEMV_RESID) {
-        const float r = a.res ? __half2float(a.res[row]) : 0.f;
-        out[row] = __float2half(r + acc[0]);
-    } else if (MODE == GEMV_GATE_UP) {
-        out[row] = __float2half(silu(rinv * acc[0]) * (rinv * acc[NT - 1]));
-    } else {
+    if (MODE == GEMV_F32) {
         out_f32[row] = acc[0];
+        return;
+    }
+    float v;
+    if (MODE == GEMV_PLAIN) v = rinv * acc[0];
+    else if (MODE == GEMV_RESID) v = resv + acc[0];
+    else v = silu(rinv * acc[0]) * (rinv * acc[NT - 1]);
+    const __half hv = to_half(v);
+    if (COH) {  // lanes 0..15 are here: pair up and store 32-bit words at device scope
+        const uint32_t mine = __builtin_bit_cast(uint16_t, hv);
+        const uint32_t next = __shfl_down(mine, 1, 64);
+        if ((i & 1) == 0)
+            __hip_atomic_store(reinterpret_cast<uint32_t *>(out) + (row >> 1), mine | (next << 16), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        out[row] = hv;
     }
 }
 
-template <int MODE, int KSPLIT>
-static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
-    constexpr int NW = KSPLIT > 4 ? KSPLIT : 4;
-    constexpr int UNITS = NW / KSPLIT;
-    dim3 grid((a.nunits + UNITS - 1) / UNITS, ntasks ? ntasks : 1);
-    hipLaunchKernelGGL((gemv_w4_kernel<MODE, KSPLIT, NW>), grid, dim3(NW * 64), 0, st, a);
+template <int MODE, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a, uint32_t ks) {
+    __shared__ GemvLds<NW> lds;
+    const uint4 *W = a.W;
+    const __half *x = a.x;
+    __half *out = a.out;
+    float *out_f32 = a.out_f32;
+    if (a.tasks) {  // grouped launch: blockIdx.y selects the expert
+        const DeviceTask t = a.tasks[blockIdx.y];
+        const uint32_t pair = (uint32_t)a.pairs[t.pair0];
+        if (MODE == GEMV_GATE_UP) {
+            W = reinterpret_cast<const uint4 *>(t.w_gate_up);
+            x = a.x + (size_t)(pair / a.top_k) * a.x_stride;
+            out = a.out + (size_t)pair * a.out_stride;
+        } else {
+            W = reinterpret_cast<const uint4 *>(t.w_down);
+            x = a.x + (size_t)pair * a.x_stride;
+            out_f32 = a.out_f32 + (size_t)pair * a.out_stride;
+        }
+    }
+    GemvBuf<2> none;
+    gemv_item<MODE, NW, false>(a, W, x, out, out_f32, blockIdx.x, ks, 0, lds, none, false);
+}
+
+template <int MODE>
+static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ks, uint32_t ntasks, hipStream_t st) {
+    const uint32_t nw = ks > 4 ? 8 : 4, units = nw / ks;
+    dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
+    if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8>), grid, dim3(512), 0, st, a, ks);
+    else hipLaunchKernelGGL((gemv_w4_kernel<MODE, 4>), grid, dim3(256), 0, st, a, ks);
     return hipGetLastError();
 }
 
-// KSPLIT depends on the matrix (K and its total unit count) only, never on the slab, so
+// The K split depends on the matrix (K and its total unit count) only, never on the slab, so
 // every placement adds the same partial sums in the same order.  It grows until the launch
 // has about two waves per SIMD or a wave is down to one scale group.
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
@@ -265,21 +355,143 @@ uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
 }
 
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
-#define PS_GEMV_CASE(M)                                                   \
-    case M:                                                               \
-        if (ksplit == 8) return launch_gemv_t<M, 8>(a, ntasks, st);       \
-        if (ksplit == 4) return launch_gemv_t<M, 4>(a, ntasks, st);       \
-        if (ksplit == 2) return launch_gemv_t<M, 2>(a, ntasks, st);       \
-        return launch_gemv_t<M, 1>(a, ntasks, st);
+    if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return hipErrorInvalidValue;
     switch (mode) {
-        PS_GEMV_CASE(GEMV_PLAIN)
-        PS_GEMV_CASE(GEMV_RESID)
-        PS_GEMV_CASE(GEMV_GATE_UP)
-        PS_GEMV_CASE(GEMV_F32)
+        case GEMV_PLAIN: return launch_gemv_t<GEMV_PLAIN>(a, ksplit, ntasks, st);
+        case GEMV_RESID: return launch_gemv_t<GEMV_RESID>(a, ksplit, ntasks, st);
+        case GEMV_GATE_UP: return launch_gemv_t<GEMV_GATE_UP>(a, ksplit, ntasks, st);
+        case GEMV_F32: return launch_gemv_t<GEMV_F32>(a, ksplit, ntasks, st);
     }
-#undef PS_GEMV_CASE
     return hipErrorInvalidValue;
 }
+
+// ------------------------------------------------------------------------------------
+// Persistent decode kernel: one launch runs a whole list of GEMV phases (the sub-layer
+// matmuls of consecutive resident shards), one workgroup of 8 waves per CU, with a grid-wide
+// barrier between phases instead of a kernel boundary.  The barrier is a monotone counter in
+// device memory; a wait is bounded by the 100 MHz real-time clock, and on expiry an error flag
+// makes every later wait fall through, so the grid always drains.
+// ------------------------------------------------------------------------------------
+// Tree barrier: workgroups arrive in groups of 16 on their group's counter, the last of a group
+// arrives on the top counter, the last of all publishes the barrier's epoch in every group's
+// flag, and each workgroup polls only its group's flag, so no address sees more than 16
+// contending atomics.  Counters only ever grow (a barrier adds exactly the group size), so
+// "last" is a test on the value modulo the size.  Layout of `sync` (uint32, 32 words = 128 B
+// apart): [0] top counter, [32 * (1 + g)] group counter, [32 * (33 + g)] group flag, g < 32;
+// the error flag lives at word 32 * 65.
+constexpr uint32_t kSyncStride = 32, kSyncGroup = 16, kSyncErrWord = 32 * 65;
+
+__device__ __forceinline__ void grid_barrier(uint32_t *sync, uint32_t epoch) {
+    // every wave first waits until its own device-scope stores of this phase have completed
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t G = gridDim.x, grp = blockIdx.x / kSyncGroup, ngroups = (G + kSyncGroup - 1) / kSyncGroup;
+        const uint32_t gsize = min(kSyncGroup, G - grp * kSyncGroup);
+        uint32_t *err = sync + kSyncErrWord;
+        const uint32_t old = __hip_atomic_fetch_add(sync + kSyncStride * (1 + grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old % gsize == gsize - 1) {
+            const uint32_t top = __hip_atomic_fetch_add(sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (top % ngroups == ngroups - 1)
+                for (uint32_t g = 0; g < ngroups; ++g)
+                    __hip_atomic_store(sync + kSyncStride * (33 + g), epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        uint32_t *flag = sync + kSyncStride * (33 + grp);
+        const uint64_t t0 = wall_clock64();
+        while ((int32_t)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+            if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+            if (wall_clock64() - t0 > 200000000ull) {  // 2 s at 100 MHz: give up, let the grid drain
+                __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// weights of the first scale group of work item `item` of phase `ph`, for this wave
+__device__ __forceinline__ bool decode_prefetch(GemvBuf<2> &pre, const DecodePhase &ph, uint32_t item) {
+    const GemvArgs &a = ph.args;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t ks = ph.ksplit, units = 8 / ks;
+    if (item >= (a.nunits + units - 1) / units) return false;   // uniform over the workgroup
+    const uint32_t unit = item * units + wave / ks, kpart = wave % ks;
+    if (unit < a.nunits && kpart < a.ngroups) {
+        const uint32_t nsb_g = min(8u, a.nsb - kpart * 8u);
+        if (ph.mode == GEMV_GATE_UP) {
+            gemv_issue_w<2>(pre, a.W, unit, a.tile_u4, kpart, nsb_g, lane);
+        } else {
+            GemvBuf<1> one;
+            gemv_issue_w<1>(one, a.W, unit, a.tile_u4, kpart, nsb_g, lane);
+            pre.sc[0] = one.sc[0];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) pre.wq[0][s] = one.wq[0][s];
+        }
+    }
+    return true;
+}
+
+__global__ __launch_bounds__(512) void decode_persistent_kernel(const DecodePhase *phases, uint32_t nphases,
+                                                                uint32_t *sync, uint32_t epoch_base,
+                                                                const __half *x_in, __half *x_out, uint32_t *trace) {
+    __shared__ GemvLds<8> lds;
+    // optional timeline (100 MHz ticks) of the first and last workgroup: per phase the time its
+    // items were done and the time the barrier let it go
+    uint32_t *tr = (trace && threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1))
+                       ? trace + (blockIdx.x ? 2 * nphases + 2 : 0) : nullptr;
+    if (tr) tr[0] = (uint32_t)wall_clock64();
+    uint32_t gen = 0;
+    GemvBuf<2> pre;
+    bool have_pre = decode_prefetch(pre, phases[0], blockIdx.x);
+    for (uint32_t p = 0; p < nphases; ++p) {
+        const DecodePhase &ph = phases[p];
+        GemvArgs a = ph.args;
+        // activations that live in the caller's buffers are tagged rather than addressed
+        if (ph.x_tag == 1) a.x = x_in;
+        if (ph.res_tag == 1) a.res = x_in;
+        if (ph.out_tag == 2) a.out = x_out;
+        const uint32_t ks = ph.ksplit, units = 8 / ks;
+        const uint32_t nitems = (a.nunits + units - 1) / units;
+        for (uint32_t item = blockIdx.x; item < nitems; item += gridDim.x) {
+            // next item of this workgroup: in this phase, else its first item of the next phase
+            bool next_pre = false;
+            auto prefetch_next = [&]() {
+                if (item + gridDim.x < nitems) next_pre = decode_prefetch(pre, ph, item + gridDim.x);
+                else if (p + 1 < nphases) next_pre = decode_prefetch(pre, phases[p + 1], blockIdx.x);
+            };
+            switch (ph.mode) {
+                case GEMV_PLAIN:
+                    gemv_item<GEMV_PLAIN, 8, true>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
+                    break;
+                case GEMV_RESID:
+                    gemv_item<GEMV_RESID, 8, true, decltype(prefetch_next), false>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
+                    break;
+                default:
+                    gemv_item<GEMV_GATE_UP, 8, true>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
+                    break;
+            }
+            gen ^= 1;
+            have_pre = next_pre;
+        }
+        if (tr) tr[1 + 2 * p] = (uint32_t)wall_clock64();
+        if (p + 1 < nphases) {
+            if (blockIdx.x >= nitems) have_pre = decode_prefetch(pre, phases[p + 1], blockIdx.x);  // idle this phase
+            grid_barrier(sync, epoch_base + p + 1);
+        }
+        if (tr) tr[2 + 2 * p] = (uint32_t)wall_clock64();
+    }
+}
+
+hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases, uint32_t grid, uint32_t *sync,
+                                    uint32_t epoch_base, const __half *x_in, __half *x_out, uint32_t *trace,
+                                    hipStream_t st) {
+    if (grid == 0 || grid > 32 * kSyncGroup) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(decode_persistent_kernel, dim3(grid), dim3(512), 0, st, phases, nphases, sync, epoch_base, x_in,
+                       x_out, trace);
+    return hipGetLastError();
+}
+
+uint32_t decode_sync_err_offset() { return kSyncErrWord * 4; }
 
 // ------------------------------------------------------------------------------------
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one wave per token (used when M > 1)

@@ -45,6 +45,8 @@ struct ps_stack {
     uint64_t stage_bytes = 0;
     void *tables_host = nullptr;              // pinned: logits | tasks | pairs for one forward (MoE)
     uint64_t tables_bytes = 0;
+    bool persistent = false;                  // whole forward = one persistent decode kernel
+    uint32_t n_phases = 0, bar_base = 0, persistent_grid = 0;
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
     std::vector<uint8_t> prof_is_copy;
@@ -83,6 +85,51 @@ const MatGeom &geom_of(const ModelGeom &g, uint32_t mat) {
     }
 }
 
+// GEMV launch description of a dense one-token matmul op (QKV, O, GATE_UP, DOWN)
+bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __half *x_out, GemvArgs *out, int *mode,
+                     uint32_t *ks) {
+    const ps_plan &p = st->plan;
+    const ModelGeom &g = p.g;
+    const auto &m = g.m;
+    const uint32_t l = op.info.layer;
+    uint8_t *A = st->arena;
+    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
+    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(A + p.ws.h) : const_cast<__half *>(xin);
+    __half *qkv = reinterpret_cast<__half *>(A + p.ws.qkv);
+    __half *sbuf = reinterpret_cast<__half *>(A + p.ws.s);
+    const bool resid = !(m.flags & PS_FLAG_NO_RESIDUAL);
+    const Shard &s = p.shards[op.info.shard0];
+    const uint4 *W = s.resident ? reinterpret_cast<const uint4 *>(A + s.offset)
+                                : reinterpret_cast<const uint4 *>(slot_ptr(st, op.info.slot) + op.info.slot_offset);
+    const MatGeom *mg = nullptr;
+    GemvArgs a{};
+    a.x_group = 1; a.eps = m.rms_eps; a.top_k = 1; a.W = W;
+    switch (op.info.kernel) {
+        case PS_K_QKV:
+            mg = &g.qkv; *mode = GEMV_PLAIN; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
+            a.nunits = s.ntiles; a.x = xin; a.out = qkv; a.out_row0 = s.tile0 * 16;
+            break;
+        case PS_K_O:
+            mg = &g.o; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
+            a.nunits = s.ntiles; a.x = qkv; a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim;
+            a.x_group = m.n_q_heads / m.n_kv_heads; a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
+            break;
+        case PS_K_GATE_UP:
+            mg = &g.gate_up; *mode = GEMV_GATE_UP; *ks = gemv_ksplit(mg->ngroups, mg->ntiles / 2);
+            a.nunits = s.ntiles / 2; a.x = hbuf; a.out = sbuf; a.out_row0 = s.tile0 / 2 * 16;
+            break;
+        case PS_K_DOWN:
+            mg = &g.down; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
+            a.nunits = s.ntiles; a.x = sbuf; a.res = resid ? hbuf : nullptr; a.out = xout; a.out_row0 = s.tile0 * 16;
+            break;
+        default: return false;
+    }
+    a.tile_u4 = (uint32_t)(mg->tile_bytes / 16); a.nsb = mg->nsb; a.ngroups = mg->ngroups; a.K = mg->K;
+    *out = a;
+    return true;
+}
+
 int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __half *x_in, __half *x_out) {
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
@@ -116,67 +163,49 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         return a;
     };
 
+    if (M == 1 && op.info.kernel >= PS_K_QKV && op.info.kernel <= PS_K_DOWN) {
+        GemvArgs a;
+        int mode;
+        uint32_t ks;
+        dense_gemv_args(st, op, x_in, x_out, &a, &mode, &ks);
+        PS_HIP(launch_gemv(mode, ks, a, 0, cs));
+        return PS_OK;
+    }
     switch (op.info.kernel) {
         case PS_K_RINV:
             PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
             return PS_OK;
         case PS_K_QKV: {
             const Shard &s = p.shards[op.info.shard0];
-            if (M == 1) {
-                GemvArgs a = gemv_base(g.qkv);
-                a.W = wptr(op); a.nunits = s.ntiles; a.x = xin; a.out = qkv; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemv(GEMV_PLAIN, gemv_ksplit(g.qkv.ngroups, g.qkv.ntiles), a, 0, cs));
-            } else {
-                GemmArgs a = gemm_base(g.qkv);
-                a.W = wptr(op); a.ntiles = s.ntiles; a.x = xin; a.x_stride = H; a.out = qkv;
-                a.out_stride = g.qkv_w; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, M, cs));
-            }
+            GemmArgs a = gemm_base(g.qkv);
+            a.W = wptr(op); a.ntiles = s.ntiles; a.x = xin; a.x_stride = H; a.out = qkv;
+            a.out_stride = g.qkv_w; a.out_row0 = s.tile0 * 16;
+            PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, M, cs));
             return PS_OK;
         }
         case PS_K_O: {
             const Shard &s = p.shards[op.info.shard0];
-            const uint32_t voff = (m.n_q_heads + m.n_kv_heads) * m.head_dim, grp = m.n_q_heads / m.n_kv_heads;
-            if (M == 1) {
-                GemvArgs a = gemv_base(g.o);
-                a.W = wptr(op); a.nunits = s.ntiles; a.x = qkv; a.x_off = voff; a.x_group = grp;
-                a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemv(GEMV_RESID, gemv_ksplit(g.o.ngroups, g.o.ntiles), a, 0, cs));
-            } else {
-                GemmArgs a = gemm_base(g.o);
-                a.W = wptr(op); a.ntiles = s.ntiles; a.x = qkv; a.x_stride = g.qkv_w; a.x_off = voff; a.x_group = grp;
-                a.res = xin; a.out = hbuf; a.out_stride = H; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
-            }
+            GemmArgs a = gemm_base(g.o);
+            a.W = wptr(op); a.ntiles = s.ntiles; a.x = qkv; a.x_stride = g.qkv_w;
+            a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
+            a.res = xin; a.out = hbuf; a.out_stride = H; a.out_row0 = s.tile0 * 16;
+            PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
             return PS_OK;
         }
         case PS_K_GATE_UP: {
             const Shard &s = p.shards[op.info.shard0];
-            if (M == 1) {
-                GemvArgs a = gemv_base(g.gate_up);
-                a.W = wptr(op); a.nunits = s.ntiles / 2; a.x = hbuf; a.out = sbuf; a.out_row0 = s.tile0 / 2 * 16;
-                PS_HIP(launch_gemv(GEMV_GATE_UP, gemv_ksplit(g.gate_up.ngroups, g.gate_up.ntiles / 2), a, 0, cs));
-            } else {
-                GemmArgs a = gemm_base(g.gate_up);
-                a.W = wptr(op); a.ntiles = s.ntiles; a.x = hbuf; a.x_stride = H; a.out = sbuf;
-                a.out_stride = g.ffn_i; a.out_row0 = s.tile0 / 2 * 16;
-                PS_HIP(launch_gemm(GEMM_GATE_UP, a, 0, M, cs));
-            }
+            GemmArgs a = gemm_base(g.gate_up);
+            a.W = wptr(op); a.ntiles = s.ntiles; a.x = hbuf; a.x_stride = H; a.out = sbuf;
+            a.out_stride = g.ffn_i; a.out_row0 = s.tile0 / 2 * 16;
+            PS_HIP(launch_gemm(GEMM_GATE_UP, a, 0, M, cs));
             return PS_OK;
         }
         case PS_K_DOWN: {
             const Shard &s = p.shards[op.info.shard0];
-            if (M == 1) {
-                GemvArgs a = gemv_base(g.down);
-                a.W = wptr(op); a.nunits = s.ntiles; a.x = sbuf; a.res = resid ? hbuf : nullptr;
-                a.out = xout; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemv(GEMV_RESID, gemv_ksplit(g.down.ngroups, g.down.ntiles), a, 0, cs));
-            } else {
-                GemmArgs a = gemm_base(g.down);
-                a.W = wptr(op); a.ntiles = s.ntiles; a.x = sbuf; a.x_stride = g.ffn_i;
-                a.res = resid ? hbuf : nullptr; a.out = xout; a.out_stride = H; a.out_row0 = s.tile0 * 16;
-                PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
-            }
+            GemmArgs a = gemm_base(g.down);
+            a.W = wptr(op); a.ntiles = s.ntiles; a.x = sbuf; a.x_stride = g.ffn_i;
+            a.res = resid ? hbuf : nullptr; a.out = xout; a.out_stride = H; a.out_row0 = s.tile0 * 16;
+            PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
             return PS_OK;
         }
         case PS_K_ROUTE:
@@ -232,6 +261,19 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     st->prof_valid = false;
     ps_stats &ss = st->stats;
     ss = ps_stats{};
+    if (st->persistent) {   // every shard resident, one token: the whole pass is one kernel
+        if (prof) PS_HIP(hipEventRecord(st->prof_ev[0], st->compute));
+        PS_HIP(launch_decode_persistent(reinterpret_cast<const DecodePhase *>(st->arena + p.ws.phases), st->n_phases,
+                                        st->persistent_grid, reinterpret_cast<uint32_t *>(st->arena + p.ws.sync),
+                                        st->bar_base, x_in, x_out,
+                                        prof ? reinterpret_cast<uint32_t *>(st->arena + p.ws.trace) : nullptr, st->compute));
+        if (prof) PS_HIP(hipEventRecord(st->prof_ev[1], st->compute));
+        st->bar_base += st->n_phases - 1;   // barriers completed so far = epoch of the last one
+        for (const Op &op : sc.ops) ss.resident_bytes_step += op.info.bytes;
+        ss.n_kernels = 1;
+        if (prof) { st->prof_is_copy.assign(1, 0); st->prof_valid = true; }
+        return PS_OK;
+    }
     for (size_t i = 0; i < sc.ops.size(); ++i) {
         const Op &op = sc.ops[i];
         const ps_op_info &o = op.info;
@@ -257,7 +299,6 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             ss.n_kernels++;
         }
     }
-    (void)p;
     st->prof_valid = prof;
     return PS_OK;
 }
@@ -456,6 +497,63 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     return run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
 }
 
+int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t persistent) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    st->persistent = false;
+    // eligible: dense, one token, every shard resident (no copies to wait for inside the kernel)
+    if (!persistent || p.g.moe || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
+    static_assert(sizeof(ps::DecodePhase) <= ps::kPhaseBytes, "phase descriptor outgrew its workspace slot");
+    const __half *tag_in = reinterpret_cast<const __half *>(uintptr_t(0x10));
+    __half *tag_out = reinterpret_cast<__half *>(uintptr_t(0x20));
+    std::vector<ps::DecodePhase> ph;
+    for (const ps::Op &op : st->dense_sched.ops) {
+        ps::DecodePhase d{};
+        int mode = 0;
+        if (op.info.type != PS_OP_KERNEL || !dense_gemv_args(st, op, tag_in, tag_out, &d.args, &mode, &d.ksplit)) {
+            ps::set_error("internal: schedule op not expressible as a decode phase"); return PS_E_STATE;
+        }
+        d.mode = (uint32_t)mode;
+        if (d.args.x == tag_in) { d.x_tag = 1; d.args.x = nullptr; }
+        if (d.args.res == tag_in) { d.res_tag = 1; d.args.res = nullptr; }
+        if (d.args.out == tag_out) { d.out_tag = 2; d.args.out = nullptr; }
+        ph.push_back(d);
+    }
+    if (ph.empty() || ph.size() * sizeof(ps::DecodePhase) > (uint64_t)p.g.m.n_layers * 4 * ps::kPhaseBytes) {
+        ps::set_error("internal: phase list does not fit its workspace"); return PS_E_STATE;
+    }
+    int dev = 0, cus = 0;
+    PS_HIP(hipGetDevice(&dev));
+    PS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) { ps::set_error("no compute units reported"); return PS_E_HIP; }
+    PS_HIP(hipStreamSynchronize(st->compute));
+    PS_HIP(hipMemcpy(st->arena + p.ws.phases, ph.data(), ph.size() * sizeof(ps::DecodePhase), hipMemcpyHostToDevice));
+    PS_HIP(hipMemset(st->arena + p.ws.sync, 0, ps::kSyncBytes));
+    st->n_phases = (uint32_t)ph.size();
+    st->persistent_grid = (uint32_t)cus;   // one 512-thread workgroup per CU: all co-resident
+    st->bar_base = 0;
+    st->persistent = true;
+    return PS_OK;
+}
+
+int32_t ps_stack_sync_check(ps_stack *st) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    PS_HIP(hipStreamSynchronize(st->copy));
+    PS_HIP(hipStreamSynchronize(st->compute));
+    if (st->persistent) {
+        uint32_t flag = 0;
+        PS_HIP(hipMemcpy(&flag, st->arena + st->plan.ws.sync + ps::decode_sync_err_offset(), 4, hipMemcpyDeviceToHost));
+        if (flag) {
+            // leave the barrier state clean for the next forward
+            PS_HIP(hipMemset(st->arena + st->plan.ws.sync, 0, ps::kSyncBytes));
+            st->bar_base = 0;
+            ps::set_error("persistent decode kernel: a grid barrier timed out (workgroups not co-resident?)");
+            return PS_E_HIP;
+        }
+    }
+    return PS_OK;
+}
+
 int32_t ps_stack_set_profiling(ps_stack *st, int32_t on) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
     st->profiling = on != 0;
@@ -510,6 +608,7 @@ int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint
         case 2: *dev_ptr = st->arena + p.ws.s; *bytes = p.ws.s_bytes; return PS_OK;
         case 3: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.ridx; *bytes = P * 4; return PS_OK;
         case 4: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.rw; *bytes = P * 4; return PS_OK;
+        case 5: if (!p.ws.trace_bytes) break; *dev_ptr = st->arena + p.ws.trace; *bytes = p.ws.trace_bytes; return PS_OK;
     }
     ps::set_error("no such debug buffer");
     return PS_E_ARG;

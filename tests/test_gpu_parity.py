@@ -51,6 +51,12 @@ def _check(cfg, seed, M, budgets, logits=None, tol=TOL):
         assert np.isfinite(y.astype(np.float64)).all()
         assert e_m <= tol, (b, e_m)
         outs.append(y)
+        if M == 1 and info["streamed"] == 0 and not cfg["n_experts"]:
+            # the persistent one-launch decode path ran; the launch-per-shard path must agree bit for bit
+            assert info["stats"].n_kernels == 1
+            y2, info2 = Hn.run_gpu(cfg, W, b, x, logits=logits, persistent=False)
+            assert info2["stats"].n_kernels > 1
+            outs.append(y2)
     for y in outs[1:]:
         np.testing.assert_array_equal(y.view(np.uint16), outs[0].view(np.uint16))
     return outs[0]
