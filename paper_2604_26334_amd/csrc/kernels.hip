@@ -155,13 +155,17 @@ __device__ __forceinline__ uint32_t xslot(uint32_t q) {
 }
 
 // LDS of one decode workgroup of NW waves: a 2 KB activation window per wave and two
-// generations of cross-wave reduction scratch (consecutive items alternate, so a fast wave
-// can never overwrite sums that a slow wave of the previous item is still reading).
+// generations of reduction scratch (consecutive items alternate, so a fast wave can never
+// overwrite sums that a slow wave of the previous item is still reading).  The scratch holds one
+// partial sum per (unit, scale group): a row's result is the sum of its scale-group partials in
+// ascending group order, whichever wave produced which partial -- so it depends neither on the
+// K split nor on the workgroup shape, let alone on the slab or slot the weights came from.
+constexpr int kMaxGroups = 16;   // K <= 16384
 template <int NW>
 struct GemvLds {
     uint4 x[NW][128];
-    float red[2][NW][2][16];
-    float red_ss[2][NW];
+    float red[2][(NW / 2) * kMaxGroups][2][16];   // K split >= 2: at most NW / 2 units per workgroup
+    float red_ss[2][(NW / 2) * kMaxGroups];
 };
 
 // One work item of the decode GEMV: the NW waves of the workgroup cover NW / ks units, ks
@@ -176,7 +180,7 @@ struct NoPrefetch {
 // after_issue() runs once this item's first loads are in flight and `pre` has been consumed:
 // the persistent kernel uses it to start the weight loads of its NEXT item, so that they
 // stream while this item waits for its activations, computes, and crosses the barrier.
-template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = (MODE == GEMV_RESID || MODE == GEMV_F32)>
+template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16)>
 __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, const __half *x, __half *out,
                                           float *out_f32, uint32_t item, uint32_t ks, uint32_t gen,
                                           GemvLds<NW> &lds, const GemvBuf<2> &pre, bool use_pre,
@@ -232,7 +236,9 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             }
             win[xslot(lane)] = cur.xa;
             win[xslot(lane + 64)] = cur.xb;
-            if (NORM) ss += sumsq8(cur.xa) + sumsq8(cur.xb);
+            float gacc[NT];   // this scale group's partial sums
+#pragma unroll
+            for (int t = 0; t < NT; ++t) gacc[t] = 0.f;
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 if ((uint32_t)s < nsb_g) {
@@ -246,9 +252,29 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
                         part = dot8(cur.wq[t][s].y, xv[1], part);
                         part = dot8(cur.wq[t][s].z, xv[2], part);
                         part = dot8(cur.wq[t][s].w, xv[3], part);
-                        acc[t] = fmaf(half_of(cur.sc[t], s), part, acc[t]);
+                        gacc[t] = fmaf(half_of(cur.sc[t], s), part, gacc[t]);
                     }
                 }
+            }
+            // the 4 lanes of a row (c = 0..3) meet; then the group partial joins the others in group order
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                gacc[t] += __shfl_xor(gacc[t], 16, 64);
+                gacc[t] += __shfl_xor(gacc[t], 32, 64);
+            }
+            float gss = 0.f;
+            if (NORM) gss = wave_sum(sumsq8(cur.xa) + sumsq8(cur.xb));
+            if (ks == 1) {   // this wave sees the groups in ascending order: add as it goes
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] += gacc[t];
+                ss += gss;
+            } else {
+                const uint32_t slot = (wave / ks) * kMaxGroups + g;
+                if (c == 0) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) lds.red[gen][slot][t][i] = gacc[t];
+                }
+                if (NORM && lane == 0) lds.red_ss[gen][slot] = gss;
             }
             if (!more) break;
             if (DBUF) {
@@ -262,31 +288,14 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
     } else {
         after_issue();
     }
-    // the 4 lanes of a row (c = 0..3) meet, then the ks waves of a unit
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        acc[t] += __shfl_xor(acc[t], 16, 64);
-        acc[t] += __shfl_xor(acc[t], 32, 64);
-    }
-    if (NORM) ss = wave_sum(ss);
     if (ks > 1) {
-        if (c == 0) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) lds.red[gen][wave][t][i] = acc[t];
-        }
-        if (NORM && lane == 0) lds.red_ss[gen][wave] = ss;
         __syncthreads();
-        if (kpart == 0 && c == 0) {
+        if (writer) {
+            const uint32_t slot0 = (wave / ks) * kMaxGroups;
+            for (uint32_t g = 0; g < a.ngroups; ++g) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                float v = lds.red[gen][wave][t][i];
-                for (uint32_t k = 1; k < ks; ++k) v += lds.red[gen][wave + k][t][i];
-                acc[t] = v;
-            }
-            if (NORM) {
-                float v = lds.red_ss[gen][wave];
-                for (uint32_t k = 1; k < ks; ++k) v += lds.red_ss[gen][wave + k];
-                ss = v;
+                for (int t = 0; t < NT; ++t) acc[t] += lds.red[gen][slot0 + g][t][i];
+                if (NORM) ss += lds.red_ss[gen][slot0 + g];
             }
         }
     }
@@ -338,24 +347,24 @@ __global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a, uint32_t k
 
 template <int MODE>
 static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ks, uint32_t ntasks, hipStream_t st) {
-    const uint32_t nw = ks > 4 ? 8 : 4, units = nw / ks;
+    const uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4, units = nw / ks;
     dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
-    if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8>), grid, dim3(512), 0, st, a, ks);
+    if (nw == 16) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 16>), grid, dim3(1024), 0, st, a, ks);
+    else if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8>), grid, dim3(512), 0, st, a, ks);
     else hipLaunchKernelGGL((gemv_w4_kernel<MODE, 4>), grid, dim3(256), 0, st, a, ks);
     return hipGetLastError();
 }
 
-// The K split depends on the matrix (K and its total unit count) only, never on the slab, so
-// every placement adds the same partial sums in the same order.  It grows until the launch
-// has about two waves per SIMD or a wave is down to one scale group.
+// The K split is a pure performance choice (results do not depend on it): it grows until the
+// launch has about four waves per SIMD or every wave is down to one scale group.
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
     uint32_t ks = 1;
-    while (ks < 8 && ks * 2 <= ngroups && total_units * ks < 2048) ks *= 2;
+    while (ks < 16 && ks < ngroups && total_units * ks < 4096) ks *= 2;
     return ks;
 }
 
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
-    if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return hipErrorInvalidValue;
+    if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8 && ksplit != 16) return hipErrorInvalidValue;
     switch (mode) {
         case GEMV_PLAIN: return launch_gemv_t<GEMV_PLAIN>(a, ksplit, ntasks, st);
         case GEMV_RESID: return launch_gemv_t<GEMV_RESID>(a, ksplit, ntasks, st);

@@ -514,6 +514,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t persistent) {
             ps::set_error("internal: schedule op not expressible as a decode phase"); return PS_E_STATE;
         }
         d.mode = (uint32_t)mode;
+        d.ksplit = std::min(d.ksplit, 8u);   // the persistent kernel's workgroups have 8 waves
         if (d.args.x == tag_in) { d.x_tag = 1; d.args.x = nullptr; }
         if (d.args.res == tag_in) { d.res_tag = 1; d.args.res = nullptr; }
         if (d.args.out == tag_out) { d.out_tag = 2; d.args.out = nullptr; }
