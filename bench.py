@@ -90,7 +90,7 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=4, help="oracle sample size, 0 skips")
     ap.add_argument("--measure-profile", type=int, default=1)
-    ap.add_argument("--persistent", type=int, default=0, help="1: all-resident decode as one persistent kernel")
+    ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 persistent kernel, 2 HIP-graph replay")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -117,7 +117,7 @@ def main():
         plans.append(B.Plan(cfg, int(budgets[0]), args.prefill_tokens, profile=prof))
     stacks = [B.Stack(p) for p in plans]
     for st in stacks:
-        st.set_decode_mode(args.persistent)
+        st.set_decode_mode(args.decode_mode)
     t0 = time.perf_counter()
     B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8), progress=40)
     log("loaded %d stacks in %.1f s" % (len(stacks), time.perf_counter() - t0))

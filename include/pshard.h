@@ -246,12 +246,14 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
-/* Decode execution mode (default 0).  persistent = 1: when the plan is dense, one token and
- * every shard is resident, the whole pass runs as ONE persistent kernel with grid-wide barriers
- * between the matmuls instead of one launch each (Algorithm 1's RunInTopologicalOrder,
- * the order and arithmetic are unchanged and results are bit-identical).  Other plans, and
- * persistent = 0, use one launch per shard.  Not to be called while a forward is in flight. */
-int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t persistent);
+/* Decode execution mode (default 0 = one launch per shard).  Modes 1 and 2 apply only when the
+ * plan is dense, one token and every shard is resident; otherwise they fall back to mode 0.
+ *  1: the whole pass runs as ONE persistent kernel with grid-wide barriers between the matmuls;
+ *  2: the launch-per-shard kernel sequence is captured once per (x_in, x_out) pair into a HIP
+ *     graph (kernel nodes only) and replayed.
+ * Order and arithmetic are unchanged (Algorithm 1's RunInTopologicalOrder); all modes give
+ * bit-identical results.  Not to be called while a forward is in flight. */
+int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
 /* Block until both streams are idle; PS_E_HIP if the persistent kernel reported a barrier
  * time-out (its bounded waits make the kernel drain instead of hanging). */
 int32_t ps_stack_sync_check(ps_stack *st);

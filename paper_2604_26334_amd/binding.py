@@ -284,9 +284,10 @@ class Stack:
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_sync_check(self.h))
 
-    def set_decode_mode(self, persistent):
+    def set_decode_mode(self, mode):
+        """0: launch per shard, 1: persistent kernel, 2: HIP-graph replay (see pshard.h)."""
         with self.torch.cuda.device(self.device):
-            _check(lib().ps_stack_set_decode_mode(self.h, 1 if persistent else 0))
+            _check(lib().ps_stack_set_decode_mode(self.h, int(mode)))
 
     def set_profiling(self, on):
         _check(lib().ps_stack_set_profiling(self.h, 1 if on else 0))

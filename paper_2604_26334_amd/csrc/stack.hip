@@ -46,6 +46,8 @@ struct ps_stack {
     void *tables_host = nullptr;              // pinned: logits | tasks | pairs for one forward (MoE)
     uint64_t tables_bytes = 0;
     bool persistent = false;                  // whole forward = one persistent decode kernel
+    bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
+    std::map<std::pair<const void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out)
     uint32_t n_phases = 0, bar_base = 0, persistent_grid = 0;
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
@@ -274,6 +276,37 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
         if (prof) { st->prof_is_copy.assign(1, 0); st->prof_valid = true; }
         return PS_OK;
     }
+    if (st->use_graph && !prof) {
+        // Launch-bound case (every shard resident, one token): the kernel sequence is captured
+        // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
+        auto key = std::make_pair(static_cast<const void *>(x_in), static_cast<void *>(x_out));
+        auto it = st->graphs.find(key);
+        if (it == st->graphs.end()) {
+            if (st->graphs.size() >= 32) {
+                for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
+                st->graphs.clear();
+            }
+            hipGraph_t graph = nullptr;
+            PS_HIP(hipStreamBeginCapture(st->compute, hipStreamCaptureModeThreadLocal));
+            int32_t rc = PS_OK;
+            for (const Op &op : sc.ops) {
+                rc = issue_kernel(st, sc, op, x_in, x_out);
+                if (rc) break;
+            }
+            hipError_t e = hipStreamEndCapture(st->compute, &graph);
+            if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+            if (e != hipSuccess) { ps::set_error("hipStreamEndCapture failed: %s", hipGetErrorString(e)); return PS_E_HIP; }
+            hipGraphExec_t exec = nullptr;
+            e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) { ps::set_error("hipGraphInstantiate failed: %s", hipGetErrorString(e)); return PS_E_HIP; }
+            it = st->graphs.emplace(key, exec).first;
+        }
+        PS_HIP(hipGraphLaunch(it->second, st->compute));
+        for (const Op &op : sc.ops) ss.resident_bytes_step += op.info.bytes;
+        ss.n_kernels = (uint32_t)sc.ops.size();
+        return PS_OK;
+    }
     for (size_t i = 0; i < sc.ops.size(); ++i) {
         const Op &op = sc.ops[i];
         const ps_op_info &o = op.info;
@@ -497,12 +530,15 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     return run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
 }
 
-int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t persistent) {
+int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (mode < 0 || mode > 2) { ps::set_error("decode mode must be 0, 1 or 2"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
     st->persistent = false;
-    // eligible: dense, one token, every shard resident (no copies to wait for inside the kernel)
-    if (!persistent || p.g.moe || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
+    st->use_graph = false;
+    // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
+    if (mode == 0 || p.g.moe || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
+    if (mode == 2) { st->use_graph = true; return PS_OK; }
     static_assert(sizeof(ps::DecodePhase) <= ps::kPhaseBytes, "phase descriptor outgrew its workspace slot");
     const __half *tag_in = reinterpret_cast<const __half *>(uintptr_t(0x10));
     __half *tag_out = reinterpret_cast<__half *>(uintptr_t(0x20));
@@ -631,6 +667,7 @@ void ps_stack_destroy(ps_stack *st) {
     for (auto e : st->ev_router) if (e) (void)hipEventDestroy(e);
     if (st->ev_upload) (void)hipEventDestroy(st->ev_upload);
     for (auto e : st->prof_ev) (void)hipEventDestroy(e);
+    for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
     delete st;
 }
 

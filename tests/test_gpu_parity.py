@@ -54,7 +54,7 @@ def _check(cfg, seed, M, budgets, logits=None, tol=TOL):
         if M == 1 and info["streamed"] == 0 and not cfg["n_experts"]:
             # the persistent one-launch decode path ran; the launch-per-shard path must agree bit for bit
             assert info["stats"].n_kernels == 1
-            y2, info2 = Hn.run_gpu(cfg, W, b, x, logits=logits, persistent=False)
+            y2, info2 = Hn.run_gpu(cfg, W, b, x, logits=logits, mode=0)
             assert info2["stats"].n_kernels > 1
             outs.append(y2)
     for y in outs[1:]:
@@ -92,3 +92,37 @@ def test_small_moe(M):
     cfg = Hn.small_moe_cfg(2)
     lg = S.router_logits(3, 0, cfg["n_layers"], M, cfg["n_experts"])
     _check(cfg, 3, M, _budgets(cfg, M, [1.0, 0.6, 0.35]), logits=lg)
+
+
+def test_graph_replay_matches_eager_on_every_replay():
+    """HIP-graph decode mode: several replays, with eager work and synchronisation in between,
+    each compared bit for bit with the eager launch-per-shard result."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = Hn.small_dense_cfg(3)
+    W = Hn.WeightCache(cfg, 5)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    plan = B.Plan(cfg, wb + (1 << 20), 1)
+    st = B.Stack(plan)
+    for layer in range(cfg["n_layers"]):
+        for kind, expert, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, kind, expert, *W(layer, kind, expert))
+    xs = [torch.from_numpy(S.activations(5, t, 1, cfg["hidden"])).cuda() for t in range(3)]
+    eager = []
+    st.set_decode_mode(0)
+    for x in xs:
+        y = torch.empty_like(x)
+        st.forward(x, y)
+        st.synchronize()
+        eager.append(y.cpu().numpy().view(np.uint16))
+    st.set_decode_mode(2)
+    y = torch.empty_like(xs[0])
+    for rep in range(4):
+        for x, ref in zip(xs, eager):
+            y.zero_()                       # eager work between replays
+            torch.cuda.synchronize()
+            st.forward(x, y)
+            st.synchronize()
+            np.testing.assert_array_equal(y.cpu().numpy().view(np.uint16), ref)
+        (torch.ones(1 << 20, device="cuda") * 2).sum().item()
+    st.close()
