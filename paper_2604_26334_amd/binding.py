@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpshard.so")
+LIB_PATH = os.environ.get("PS_LIB", os.path.join(_HERE, "libpshard.so"))
 
 PS_OK, PS_E_ARG, PS_E_BUDGET, PS_E_HIP, PS_E_STATE, PS_E_NOMEM = 0, -1, -2, -3, -4, -5
 PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN = 0, 1, 2, 3, 4

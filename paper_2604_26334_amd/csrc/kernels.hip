@@ -6,6 +6,10 @@
 
 #include "kernels.h"
 
+#ifndef PS_GEMM_OCC
+#define PS_GEMM_OCC 2
+#endif
+
 namespace ps {
 
 typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
@@ -603,8 +607,8 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // the activation tile of one super-block (MT x 128 k) is staged in LDS, 16-byte chunks
 // XOR-swizzled by token so that operand reads are conflict-free.
 // ------------------------------------------------------------------------------------
-template <int MODE, int AT, int MT>
-__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
+template <int MODE, int AT, int MT, bool GROUPED>
+__global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
     extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
     constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
@@ -614,7 +618,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     const uint4 *W = a.W;
     uint32_t ntok = a.M;           // tokens this workgroup column may touch
     const int32_t *pairs = nullptr;
-    if (a.tasks) {
+    if (GROUPED) {
         const DeviceTask t = a.tasks[blockIdx.z];
         W = reinterpret_cast<const uint4 *>(MODE == GEMM_GATE_UP ? t.w_gate_up : t.w_down);
         ntok = t.npairs;
@@ -627,16 +631,18 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     // activation fill: thread moves chunk u of tokens tok0, tok0 + 16, ... of the tile
     const uint32_t u = tid & 15, tok0 = tid >> 4;
     const uint32_t fill_dst = tok0 * 16 + (u ^ (tok0 & 15));   // + r * 256 for token tok0 + 16 r
-    uint32_t xoff[NFILL];
-    bool xok[NFILL];
+    // row offset (elements) of the r-th token this thread moves; grouped launches look it up
+    uint32_t xoff_g[GROUPED ? NFILL : 1];
+    if (GROUPED) {
 #pragma unroll
-    for (int r = 0; r < NFILL; ++r) {
-        const uint32_t tok = m0 + tok0 + r * 16;
-        xok[r] = tok < ntok;
-        size_t rowi = xok[r] ? tok : m0;
-        if (pairs) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[rowi] / (int32_t)a.top_k) : (size_t)pairs[rowi];
-        xoff[r] = (uint32_t)(rowi * a.x_stride);
+        for (int r = 0; r < NFILL; ++r) {
+            const uint32_t tok = m0 + tok0 + r * 16;
+            size_t rowi = tok < ntok ? tok : m0;
+            rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[rowi] / (int32_t)a.top_k) : (size_t)pairs[rowi];
+            xoff_g[r] = (uint32_t)(rowi * a.x_stride);
+        }
     }
+    const uint32_t xoff0 = (m0 + tok0) * a.x_stride, xstep = 16 * a.x_stride;
     // weights: per tile a pointer to its first group; tiles past the slab read tile 0 (discarded)
     const uint4 *wt[AT];
 #pragma unroll
@@ -651,79 +657,97 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
 
-    uint4 xr[NFILL], wq[AT], wn[AT];
+    // the activation tile of the next super-block is fetched in two halves, so only half of it
+    // sits in registers at any time
+    constexpr int HA = (NFILL + 1) / 2, HB = NFILL - HA;
+    uint4 xr[HA], wq[AT], wn[AT];
     uint16_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block
-    auto load_x = [&](uint32_t sb) {
+    auto load_x = [&](uint32_t sb, int r0, int cnt) {
         const uint32_t col = gather_col(sb * 128 + u * 8, a.x_off, a.x_group);
 #pragma unroll
-        for (int r = 0; r < NFILL; ++r)
-            xr[r] = xok[r] ? *reinterpret_cast<const uint4 *>(a.x + xoff[r] + col) : make_uint4(0, 0, 0, 0);
-    };
-    auto store_x = [&](uint32_t stage) {
-#pragma unroll
-        for (int r = 0; r < NFILL; ++r) lds[stage * (MT * 16) + fill_dst + r * 256] = xr[r];
-    };
-
-    const uint32_t ngroups = (a.nsb + 7) / 8;
-    load_x(0);
-#pragma unroll
-    for (int t = 0; t < AT; ++t) {
-        wn[t] = load_stream(wt[t]);
-        dn[t] = reinterpret_cast<const uint16_t *>(wt[t] + min(8u, a.nsb) * 64)[0];
-    }
-    store_x(0);
-    __syncthreads();
-
-    uint32_t sb = 0;
-    for (uint32_t g = 0; g < ngroups; ++g) {
-        const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            if ((uint32_t)s < nsb_g) {
-                const uint32_t stage = sb & 1;
-#pragma unroll
-                for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
-                const bool more = sb + 1 < a.nsb;
-                if (more) {   // prefetch the next super-block: activations to registers, weights
-                    load_x(sb + 1);
-                    const uint32_t gn = (sb + 1) >> 3, sn = (sb + 1) & 7;
-                    const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
-#pragma unroll
-                    for (int t = 0; t < AT; ++t) {
-                        const uint4 *gb = wt[t] + (size_t)gn * (9 * 64);
-                        wn[t] = load_stream(gb + sn * 64);
-                        dn[t] = reinterpret_cast<const uint16_t *>(gb + nsb_n * 64)[sn];
-                    }
-                }
-                _Float16 d[AT];
-#pragma unroll
-                for (int t = 0; t < AT; ++t) d[t] = __builtin_bit_cast(_Float16, dq[t]);
-                const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    h8_t A[AT];
-#pragma unroll
-                    for (int t = 0; t < AT; ++t) {
-                        const uint32_t q = kk == 0 ? wq[t].x : kk == 1 ? wq[t].y : kk == 2 ? wq[t].z : wq[t].w;
-                        const h2_t dd = {d[t], d[t]};
-                        h2_t w[4];
-                        dequant8(q, w);
-                        w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
-                        A[t] = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
-                    }
-#pragma unroll
-                    for (int n = 0; n < NMT; ++n) {
-                        const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c * 4 + kk) ^ i)]);
-#pragma unroll
-                        for (int t = 0; t < AT; ++t)
-                            acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], B, acc[t][n], 0, 0, 0);
-                    }
-                }
-                if (more) store_x(stage ^ 1);
-                __syncthreads();
-                ++sb;
+        for (int r = 0; r < HA; ++r) {
+            if (r < cnt) {
+                const bool ok = m0 + tok0 + (r0 + r) * 16 < ntok;
+                const uint32_t off = GROUPED ? xoff_g[GROUPED ? r0 + r : 0] : xoff0 + (r0 + r) * xstep;
+                xr[r] = ok ? *reinterpret_cast<const uint4 *>(a.x + off + col) : make_uint4(0, 0, 0, 0);
             }
         }
+    };
+    auto store_x = [&](uint32_t stage, int r0, int cnt) {
+#pragma unroll
+        for (int r = 0; r < HA; ++r)
+            if (r < cnt) lds[stage * (MT * 16) + fill_dst + (r0 + r) * 256] = xr[r];
+    };
+
+    // scale group / slot of super-block sb, clamped to the last one (the prefetch past the end
+    // re-reads the last super-block instead of branching; nothing consumes it)
+    auto load_w = [&](uint32_t sbn) {
+        sbn = min(sbn, a.nsb - 1);
+        const uint32_t gn = sbn >> 3, sn = sbn & 7;
+        const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
+#pragma unroll
+        for (int t = 0; t < AT; ++t) {
+            const uint4 *gb = wt[t] + (size_t)gn * (9 * 64);
+            wn[t] = load_stream(gb + sn * 64);
+            dn[t] = reinterpret_cast<const uint16_t *>(gb + nsb_n * 64)[sn];
+        }
+    };
+    // A operands of MFMA step kk from raw dwords + scale: (q - 8) * d rounded to fp16
+    auto dequant_a = [&](h8_t (&A)[AT], const uint4 (&w4)[AT], const uint16_t (&ds)[AT], int kk) {
+#pragma unroll
+        for (int t = 0; t < AT; ++t) {
+            const uint32_t q = kk == 0 ? w4[t].x : kk == 1 ? w4[t].y : kk == 2 ? w4[t].z : w4[t].w;
+            const _Float16 d = __builtin_bit_cast(_Float16, ds[t]);
+            const h2_t dd = {d, d};
+            h2_t w[4];
+            dequant8(q, w);
+            w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+            A[t] = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+        }
+    };
+
+    load_x(0, 0, HA);
+    load_w(0);
+    store_x(0, 0, HA);
+    if (HB) { load_x(0, HA, HB); store_x(0, HA, HB); }
+    // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
+    // (one more operand set in registers; the 4-tile shape has no room for it)
+    constexpr bool PIPE = (AT <= 2);
+    h8_t Acur[AT], Anxt[AT];
+    if (PIPE) dequant_a(Acur, wn, dn, 0);
+    __syncthreads();
+
+    for (uint32_t sb = 0; sb < a.nsb; ++sb) {
+        const uint32_t stage = sb & 1;
+#pragma unroll
+        for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
+        const uint32_t sbn = min(sb + 1, a.nsb - 1);
+        load_x(sbn, 0, HA);   // prefetch the next super-block: first half of the activations, weights
+        load_w(sb + 1);
+        const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (!PIPE) dequant_a(Acur, wq, dq, kk);
+            else if (kk < 3) dequant_a(Anxt, wq, dq, kk + 1);
+            else dequant_a(Anxt, wn, dn, 0);
+#pragma unroll
+            for (int n = 0; n < NMT; ++n) {
+                const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c * 4 + kk) ^ i)]);
+#pragma unroll
+                for (int t = 0; t < AT; ++t)
+                    acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Acur[t], B, acc[t][n], 0, 0, 0);
+            }
+            if (PIPE) {
+#pragma unroll
+                for (int t = 0; t < AT; ++t) Acur[t] = Anxt[t];
+            }
+            if (kk == 1) {
+                store_x(stage ^ 1, 0, HA);
+                if (HB) load_x(sbn, HA, HB);
+            }
+        }
+        if (HB) store_x(stage ^ 1, HA, HB);
+        __syncthreads();
     }
 
     // epilogue: lane holds token j = lane & 15 of each token tile and rows 4*(lane >> 4) + r
@@ -784,7 +808,8 @@ template <int MODE, int AT, int MT>
 static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
     dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : 1);
     const size_t lds = (size_t)MT * 256 * 2;
-    hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT>), grid, dim3(256), lds, st, a);
+    if (ntasks) hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, true>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -793,11 +818,9 @@ static hipError_t launch_gemm_m(const GemmArgs &a, uint32_t ntasks, uint32_t max
     if (max_tok <= 16) return launch_gemm_t<MODE, 2, 16>(a, ntasks, max_tok, st);
     if (max_tok <= 32) return launch_gemm_t<MODE, 2, 32>(a, ntasks, max_tok, st);
     if (max_tok <= 64) return launch_gemm_t<MODE, 2, 64>(a, ntasks, max_tok, st);
-    // narrow matrices: halve the row extent of a workgroup so that the launch still has two
-    // workgroups per CU (the choice depends on the matrix, not on the slab)
-    const uint64_t wgs = (uint64_t)((a.total_tiles + 15) / 16) * ((max_tok + 127) / 128) * (ntasks ? ntasks : 1);
-    if (wgs < 512) return launch_gemm_t<MODE, 2, 128>(a, ntasks, max_tok, st);
-    return launch_gemm_t<MODE, 4, 128>(a, ntasks, max_tok, st);
+    // 2 row-tiles per wave leave room for the pipelined dequant at two workgroups per CU; the
+    // 4-tile shape (half the LDS operand traffic) does not fit that register budget
+    return launch_gemm_t<MODE, 2, 128>(a, ntasks, max_tok, st);
 }
 
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
