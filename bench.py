@@ -66,18 +66,85 @@ def kernel_breakdown(B, st, plan, xs, xout, reps=3):
     return {k: dict(avg_ms=v[0] / v[1], launches=v[1] // reps, bytes_per_launch=v[2] / v[1]) for k, v in acc.items()}, stats
 
 
-def cpu_baseline(cfg, seed, layers, S, O):
-    """The oracle as it stands on the host cores: `layers` layers of the stack at one token."""
-    import numpy as np
+def cpu_baseline(cfg, seed, layers, reps, S, O):
+    """The oracle as it stands on the host cores: `layers` layers of the stack, one token, `reps`
+    tokens one after the other.  Weights are generated beforehand (not timed)."""
+    from concurrent.futures import ThreadPoolExecutor
     sub = dict(cfg, n_layers=layers)
     shapes = {(k, e): (N, K) for (k, e, N, K) in S.matrix_shapes(sub)}
-    mats = {(l, k): S.weight_matrix(seed, l, k, None, *shapes[(k, None)]) for l in range(layers) for (k, _e) in shapes}
-    x = S.activations(seed, 0, 1, cfg["hidden"])
+    keys = [(l, k) for l in range(layers) for (k, _e) in shapes]
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        vals = list(ex.map(lambda lk: S.weight_matrix(seed, lk[0], lk[1], None, *shapes[(lk[1], None)]), keys))
+    mats = dict(zip(keys, vals))
     O.lib()
     t0 = time.perf_counter()
-    O.stack_forward(x, sub, lambda l, k, e: mats[(l, k)], mirror=True)
-    dt = time.perf_counter() - t0
-    return dt, os.cpu_count()
+    for r in range(reps):
+        O.stack_forward(S.activations(seed, r, 1, cfg["hidden"]), sub, lambda l, k, e: mats[(l, k)], mirror=True)
+    dt = (time.perf_counter() - t0) / reps
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dt, min(threads, os.cpu_count() or threads)
+
+
+def batched_leg(B, S, torch, cfg, seed, prof, tokens, budgets, steps):
+    """Batched decode (config 5): `tokens` tokens per step, `steps` steps of fresh activations."""
+    out = {}
+    plans = [B.Plan(cfg, int(b), tokens, profile=prof) for b in budgets]
+    stacks = [B.Stack(p) for p in plans]
+    B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8))
+    dev = stacks[0].device
+    xs = [torch.from_numpy(S.activations(seed, 200 + t, tokens, cfg["hidden"])).to(dev) for t in range(4)]
+    xo = torch.empty_like(xs[0])
+    torch.cuda.synchronize()
+    for b, plan, st in zip(budgets, plans, stacks):
+        s = plan.summary()
+        ms = time_steps(torch, st, xs, xo, steps, 3)
+        flops = 2.0 * tokens * (s.weight_bytes / 0.5625)
+        out["%g" % (b / 1e9)] = dict(budget_bytes=int(b), tokens_per_step=tokens, steps=steps, ms_per_step=ms,
+                                     tokens_per_s=tokens * 1e3 / ms, resident_bytes=s.resident_bytes,
+                                     streamed_bytes_per_step=st.stats().streamed_bytes_step,
+                                     hbm_gbps=s.weight_bytes / (ms * 1e-3) / 1e9,
+                                     frac_of_hbm_peak=s.weight_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                     tflops=flops / (ms * 1e-3) / 1e12)
+        log("batch %d, budget %.0f GB: %.3f ms/step, %.0f tok/s" % (tokens, b / 1e9, ms, tokens * 1e3 / ms))
+        st.close()
+    return out
+
+
+def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
+    """MoE stack (config 4): 48 layers, 128 experts, top-8; decode at each token count."""
+    cfg = S.cfg_moe()
+    out = {}
+    plans = [B.Plan(cfg, int(budget), m, profile=prof) for m in token_counts]
+    stacks = [B.Stack(p) for p in plans]
+    t0 = time.perf_counter()
+    B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
+    log("loaded MoE stacks in %.1f s" % (time.perf_counter() - t0))
+    dev = stacks[0].device
+    for m, plan, st in zip(token_counts, plans, stacks):
+        s = plan.summary()
+        xs = [torch.from_numpy(S.activations(seed, 300 + t, m, cfg["hidden"])).to(dev) for t in range(4)]
+        lgs = [S.router_logits(seed, 300 + t, cfg["n_layers"], m, cfg["n_experts"]) for t in range(4)]
+        xo = torch.empty_like(xs[0])
+        torch.cuda.synchronize()
+        for i in range(2):
+            st.forward(xs[i], xo, lgs[i])
+        st.synchronize()
+        streamed = 0
+        t0 = time.perf_counter()
+        for i in range(steps):
+            st.forward(xs[i % 4], xo, lgs[i % 4])
+            streamed += st.stats().streamed_bytes_step
+        st.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        out["batch_%d" % m] = dict(budget_bytes=int(budget), tokens_per_step=m, ms_per_step=ms, tokens_per_s=m * 1e3 / ms,
+                                   resident_bytes=s.resident_bytes, streamed_bytes_per_step=streamed / steps,
+                                   pcie_gbps_whole_step=streamed / steps / (ms * 1e-3) / 1e9,
+                                   frac_of_measured_h2d=(streamed / steps / (ms * 1e-3) / 1e9 / prof.h2d_gbps) if prof else None,
+                                   est_ms=s.est_step_ms)
+        log("MoE batch %d, budget %.0f GB: %.2f ms/step, %.1f tok/s, %.2f GB streamed/step" % (
+            m, budget / 1e9, ms, m * 1e3 / ms, streamed / steps / 1e9))
+        st.close()
+    return out
 
 
 def main():
@@ -88,7 +155,9 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="layers of the 8B-shaped stack (32 = the named config)")
     ap.add_argument("--budgets-gb", type=str, default="4,2,8", help="first one is the headline")
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="oracle sample size, 0 skips")
+    ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
+    ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
+    ap.add_argument("--extra", type=str, default="batch64,moe", help="further legs: batch64 (config 5), moe (config 4)")
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 persistent kernel, 2 HIP-graph replay")
     args = ap.parse_args()
@@ -180,21 +249,30 @@ def main():
                        streamed_bytes=s.streamed_bytes, est_ms=s.est_step_ms)
         log("prefill %d tokens: TTFT %.2f ms, %.1f TFLOP/s" % (Mp, ms, prefill["tflops"]))
 
+    for st in stacks:
+        st.close()
+    extra = {}
+    if "batch64" in args.extra and args.layers == 32:
+        extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128)
+    if "moe" in args.extra:
+        extra["moe_decode_6gb"] = moe_leg(B, S, torch, seed, prof, 6e9, [1, 16], 10)
+
     cpu = None
     if args.cpu_layers:
         from oracle import oracle as O
-        dt, cores = cpu_baseline(cfg, seed, args.cpu_layers, S, O)
-        cpu = dict(value=1.0 / (dt * cfg["n_layers"] / args.cpu_layers), unit="tokens/s", cores=cores, kind="oracle",
-                   sample="%d of %d layers of the same stack at one token, %.2f s, scaled to the full stack" % (
-                       args.cpu_layers, cfg["n_layers"], dt))
+        dt, cores = cpu_baseline(cfg, seed, min(args.cpu_layers, cfg["n_layers"]), args.cpu_reps, S, O)
+        nl = min(args.cpu_layers, cfg["n_layers"])
+        cpu = dict(value=1.0 / (dt * cfg["n_layers"] / nl), unit="tokens/s", cores=cores, kind="oracle",
+                   sample="%d of %d layers of the same stack, %d tokens one after the other, %.2f s per token" % (
+                       nl, cfg["n_layers"], args.cpu_reps, dt))
 
     line = dict(metric="decode tokens/s at fixed VRAM budget (batch 1)", value=head["tokens_per_s"], unit="tokens/s",
                 n_gpus=1, steps=head["steps"], warmup=args.warmup, ms_per_step=head["ms_per_token"],
-                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="w4 x f16 -> f32 accumulate",
+                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f16",
                 data="synthetic",
                 config=dict(workload="dense 8B-shaped stack, %d layers, decode batch 1, budget %g GB" % (
                     cfg["n_layers"], budgets[0] / 1e9), hidden=4096, ffn=14336, weight_bytes=plans[0].summary().weight_bytes),
-                roofline=roof, cpu_baseline=cpu, budgets=results, prefill=prefill,
+                roofline=roof, cpu_baseline=cpu, budgets=results, prefill=prefill, extra=extra,
                 profile=None if prof is None else dict(h2d_gbps=prof.h2d_gbps, gemv_gbps=prof.gemv_gbps,
                                                        launch_us=prof.launch_us, gemm_tflops=list(prof.gemm_tflops)))
     print(json.dumps(line))

@@ -45,6 +45,8 @@ struct GemmArgs {
     __half *out;
     float *out_f32;
     uint32_t out_stride, out_row0, top_k;
+    uint32_t sb_per_part;  // split-K: super-blocks per blockIdx.z part (0 = whole K in one part)
+    uint32_t part_stride;  // split-K: elements between the fp32 partial planes
     const DeviceTask *tasks;
     const int32_t *pairs;
 };
@@ -65,6 +67,10 @@ hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases,
 uint32_t decode_sync_err_offset();
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st);
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st);
+// sums `parts` fp32 partial planes [M][ncols_phys] in ascending order and applies the mode's epilogue
+hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
+                                  uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,
+                                  uint32_t out_stride, uint32_t out_row0, hipStream_t st);
 hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st);
 hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
                         hipStream_t st);

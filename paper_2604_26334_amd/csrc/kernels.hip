@@ -4,6 +4,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 #ifndef PS_GEMM_OCC
@@ -706,10 +708,16 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
         }
     };
 
-    load_x(0, 0, HA);
-    load_w(0);
+    // split-K: this workgroup covers super-blocks [sb_begin, sb_end) and writes an fp32 partial plane
+    uint32_t sb_begin = 0, sb_end = a.nsb;
+    if (!GROUPED && a.sb_per_part) {
+        sb_begin = blockIdx.z * a.sb_per_part;
+        sb_end = min(a.nsb, sb_begin + a.sb_per_part);
+    }
+    load_x(sb_begin, 0, HA);
+    load_w(sb_begin);
     store_x(0, 0, HA);
-    if (HB) { load_x(0, HA, HB); store_x(0, HA, HB); }
+    if (HB) { load_x(sb_begin, HA, HB); store_x(0, HA, HB); }
     // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
     // (one more operand set in registers; the 4-tile shape has no room for it)
     constexpr bool PIPE = (AT <= 2);
@@ -717,11 +725,11 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
     if (PIPE) dequant_a(Acur, wn, dn, 0);
     __syncthreads();
 
-    for (uint32_t sb = 0; sb < a.nsb; ++sb) {
-        const uint32_t stage = sb & 1;
+    for (uint32_t sb = sb_begin; sb < sb_end; ++sb) {
+        const uint32_t stage = (sb - sb_begin) & 1;
 #pragma unroll
         for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
-        const uint32_t sbn = min(sb + 1, a.nsb - 1);
+        const uint32_t sbn = min(sb + 1, sb_end - 1);
         load_x(sbn, 0, HA);   // prefetch the next super-block: first half of the activations, weights
         load_w(sb + 1);
         const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
@@ -778,7 +786,8 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
                 if (tile_base + t >= a.ntiles) continue;
                 const uint32_t col = a.out_row0 + (tile_base + t) * 16 + rg * 4;
                 if (MODE == GEMM_F32) {
-                    float4 *dst = reinterpret_cast<float4 *>(a.out_f32 + orow * a.out_stride + col);
+                    float *plane = a.out_f32 + ((!GROUPED && a.sb_per_part) ? (size_t)blockIdx.z * a.part_stride : 0);
+                    float4 *dst = reinterpret_cast<float4 *>(plane + orow * a.out_stride + col);
                     *dst = make_float4(acc[t][n][0], acc[t][n][1], acc[t][n][2], acc[t][n][3]);
                 } else {
                     float v[4];
@@ -806,7 +815,8 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
 
 template <int MODE, int AT, int MT>
 static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
-    dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : 1);
+    const uint32_t parts = (!ntasks && a.sb_per_part) ? (a.nsb + a.sb_per_part - 1) / a.sb_per_part : 1;
+    dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : parts);
     const size_t lds = (size_t)MT * 256 * 2;
     if (ntasks) hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, true>), grid, dim3(256), lds, st, a);
     else hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, false>), grid, dim3(256), lds, st, a);
@@ -831,6 +841,55 @@ hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t ma
         case GEMM_F32: return launch_gemm_m<GEMM_F32>(a, ntasks, max_tok, st);
     }
     return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
+// Split-K epilogue (batched decode): out = epilogue(sum over parts, ascending, of the fp32
+// partial planes).  One thread per output element; GATE_UP pairs a gate column with the up
+// column 16 physical columns further on.
+// ------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float *partial, uint32_t parts, uint32_t part_stride,
+                                                              uint32_t M, uint32_t ncols_phys, const float *rinv,
+                                                              const __half *res, __half *out, uint32_t out_stride,
+                                                              uint32_t out_row0) {
+    const uint32_t ncols = MODE == GEMM_GATE_UP ? ncols_phys / 2 : ncols_phys;
+    const size_t n = (size_t)M * ncols;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n; q += (size_t)gridDim.x * 256) {
+        const uint32_t m = (uint32_t)(q / ncols), j = (uint32_t)(q % ncols);
+        const uint32_t c0 = MODE == GEMM_GATE_UP ? (j >> 4) * 32 + (j & 15) : j;
+        const float *p0 = partial + (size_t)m * ncols_phys + c0;
+        float v = 0.f, u = 0.f;
+        for (uint32_t p = 0; p < parts; ++p) {
+            v += p0[(size_t)p * part_stride];
+            if (MODE == GEMM_GATE_UP) u += p0[(size_t)p * part_stride + 16];
+        }
+        float r;
+        if (MODE == GEMM_PLAIN) r = rinv[m] * v;
+        else if (MODE == GEMM_RESID) r = (res ? __half2float(res[(size_t)m * out_stride + out_row0 + j]) : 0.f) + v;
+        else { const float ri = rinv[m]; r = silu(ri * v) * (ri * u); }
+        out[(size_t)m * out_stride + out_row0 + j] = to_half(r);
+    }
+}
+
+hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
+                                  uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,
+                                  uint32_t out_stride, uint32_t out_row0, hipStream_t st) {
+    const size_t n = (size_t)M * ncols_phys;
+    const uint32_t blocks = (uint32_t)std::min<size_t>((n + 255) / 256, 2048);
+    switch (mode) {
+        case GEMM_PLAIN:
+            hipLaunchKernelGGL(splitk_epilogue_kernel<GEMM_PLAIN>, dim3(blocks), dim3(256), 0, st, partial, parts, part_stride, M, ncols_phys, rinv, res, out, out_stride, out_row0);
+            break;
+        case GEMM_RESID:
+            hipLaunchKernelGGL(splitk_epilogue_kernel<GEMM_RESID>, dim3(blocks), dim3(256), 0, st, partial, parts, part_stride, M, ncols_phys, rinv, res, out, out_stride, out_row0);
+            break;
+        case GEMM_GATE_UP:
+            hipLaunchKernelGGL(splitk_epilogue_kernel<GEMM_GATE_UP>, dim3(blocks), dim3(256), 0, st, partial, parts, part_stride, M, ncols_phys, rinv, res, out, out_stride, out_row0);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------

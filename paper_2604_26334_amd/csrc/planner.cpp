@@ -80,6 +80,15 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
     return PS_OK;
 }
 
+uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M) {
+    if (M < 2 || M > 64) return 0;
+    const uint32_t wgs = (mg.ntiles + 7) / 8;          // workgroups of 8 row-tiles over N
+    if (wgs >= 320) return 0;
+    uint32_t parts = std::min(std::min(mg.nsb, 8u), (384u + wgs - 1) / wgs);
+    if (parts <= 1) return 0;
+    return (mg.nsb + parts - 1) / parts;
+}
+
 Workspace make_workspace(const ModelGeom &g, uint32_t M) {
     Workspace w;
     uint64_t off = 0;
@@ -116,6 +125,13 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M) {
         w.s_bytes = (uint64_t)M * g.ffn_i * 2;
         w.s = take(w.s_bytes);
     }
+    uint64_t pb = 0;   // fp32 partial planes of the split-K batched-decode GEMMs (attention matrices; dense FFN)
+    for (const MatGeom *mg : {&g.qkv, &g.o, &g.gate_up, &g.down}) {
+        if (!mg->ntiles || (g.moe && (mg == &g.gate_up || mg == &g.down))) continue;
+        const uint32_t per = gemm_sb_per_part(*mg, M);
+        if (per) pb = std::max<uint64_t>(pb, (uint64_t)((mg->nsb + per - 1) / per) * M * mg->rows * 4);
+    }
+    if (pb) w.partial = take(pb);
     w.total = off;
     return w;
 }

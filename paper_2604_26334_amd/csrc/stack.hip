@@ -173,6 +173,21 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         PS_HIP(launch_gemv(mode, ks, a, 0, cs));
         return PS_OK;
     }
+    // batched decode (2..64 tokens) of a narrow matrix: split K over blockIdx.z into fp32 partial
+    // planes, then one epilogue kernel sums them in order and applies the mode's epilogue
+    auto run_gemm = [&](int mode, GemmArgs a, const MatGeom &mg) -> int32_t {
+        const uint32_t per = gemm_sb_per_part(mg, M);
+        if (!per) { PS_HIP(launch_gemm(mode, a, 0, M, cs)); return PS_OK; }
+        GemmArgs pa = a;
+        float *partial = reinterpret_cast<float *>(A + p.ws.partial);
+        const uint32_t ncols = a.ntiles * 16;
+        pa.out_f32 = partial; pa.out = nullptr; pa.out_stride = ncols; pa.out_row0 = 0;
+        pa.sb_per_part = per; pa.part_stride = M * ncols;
+        PS_HIP(launch_gemm(GEMM_F32, pa, 0, M, cs));
+        PS_HIP(launch_splitk_epilogue(mode, partial, (mg.nsb + per - 1) / per, pa.part_stride, M, ncols, rinv, a.res,
+                                      a.out, a.out_stride, a.out_row0, cs));
+        return PS_OK;
+    };
     switch (op.info.kernel) {
         case PS_K_RINV:
             PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
@@ -182,8 +197,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             GemmArgs a = gemm_base(g.qkv);
             a.W = wptr(op); a.ntiles = s.ntiles; a.x = xin; a.x_stride = H; a.out = qkv;
             a.out_stride = g.qkv_w; a.out_row0 = s.tile0 * 16;
-            PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, M, cs));
-            return PS_OK;
+            return run_gemm(GEMM_PLAIN, a, g.qkv);
         }
         case PS_K_O: {
             const Shard &s = p.shards[op.info.shard0];
@@ -191,24 +205,21 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             a.W = wptr(op); a.ntiles = s.ntiles; a.x = qkv; a.x_stride = g.qkv_w;
             a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
             a.res = xin; a.out = hbuf; a.out_stride = H; a.out_row0 = s.tile0 * 16;
-            PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
-            return PS_OK;
+            return run_gemm(GEMM_RESID, a, g.o);
         }
         case PS_K_GATE_UP: {
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.gate_up);
             a.W = wptr(op); a.ntiles = s.ntiles; a.x = hbuf; a.x_stride = H; a.out = sbuf;
             a.out_stride = g.ffn_i; a.out_row0 = s.tile0 / 2 * 16;
-            PS_HIP(launch_gemm(GEMM_GATE_UP, a, 0, M, cs));
-            return PS_OK;
+            return run_gemm(GEMM_GATE_UP, a, g.gate_up);
         }
         case PS_K_DOWN: {
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.down);
             a.W = wptr(op); a.ntiles = s.ntiles; a.x = sbuf; a.x_stride = g.ffn_i;
             a.res = resid ? hbuf : nullptr; a.out = xout; a.out_stride = H; a.out_row0 = s.tile0 * 16;
-            PS_HIP(launch_gemm(GEMM_RESID, a, 0, M, cs));
-            return PS_OK;
+            return run_gemm(GEMM_RESID, a, g.down);
         }
         case PS_K_ROUTE:
             PS_HIP(launch_route(reinterpret_cast<const float *>(A + p.ws.logits) + (size_t)l * M * m.n_experts, M,
