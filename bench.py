@@ -147,6 +147,19 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
     return out
 
 
+def measured_traffic(tag):
+    """HBM bytes per launch of the named kernel from the committed rocprofv3 PMC summary
+    (profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt); None if the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "dense8b_decode_prefill_pmc_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch %s:" % tag):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +172,8 @@ def main():
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
     ap.add_argument("--extra", type=str, default="batch64,moe", help="further legs: batch64 (config 5), moe (config 4)")
     ap.add_argument("--measure-profile", type=int, default=1)
+    ap.add_argument("--calibrate-copy", type=int, default=0,
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 persistent kernel, 2 HIP-graph replay")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -175,6 +190,13 @@ def main():
     cfg = S.cfg_dense8b(args.layers)
     budgets = [float(b) * 1e9 for b in args.budgets_gb.split(",")]
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     prof = None
     if args.measure_profile:
         prof = B.profile_measure(1 << 30)
@@ -231,7 +253,8 @@ def main():
     elif gu:
         ach = gu["bytes_per_launch"] / (gu["avg_ms"] * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel="gemv_w4_kernel<GATE_UP>", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=ach / HBM_PEAK_GBS, traffic=None, bytes_per_launch=gu["bytes_per_launch"],
+                    frac=ach / HBM_PEAK_GBS, traffic=measured_traffic("gemv_gate_up"),
+                    bytes_per_launch=gu["bytes_per_launch"],
                     avg_launch_us=gu["avg_ms"] * 1e3)
 
     prefill = None
