@@ -264,6 +264,12 @@ int32_t ps_stack_stats(ps_stack *st, ps_stats *out);
 /* start (relative to the first op) and duration in ms of op i of the last profiled forward;
  * ops are numbered as in the schedule of the same plan.  Blocks like ps_stack_stats. */
 int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur_ms);
+/* Time one kernel kind in isolation (measurement aid): every resident op of kind `kernel`
+ * (PS_K_*) of a dense stack is launched back to back, `reps` passes after one warm-up pass,
+ * between two events on the compute stream; *avg_launch_ms = elapsed / launches.  The
+ * activations are whatever the workspace holds, the outputs go to the workspace.  Blocks. */
+int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, double *avg_launch_ms,
+                             uint32_t *launches);
 /* device pointers into the workspace for inspection by tests (fp16 unless noted):
  * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
  * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k],

@@ -64,7 +64,7 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
-           "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_debug_buffer",
+           "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix"]
 
 _lib = None
@@ -107,6 +107,7 @@ def lib():
             "ps_stack_sync_check": [vp],
             "ps_stack_stats": [vp, C.POINTER(ps_stats)],
             "ps_stack_op_time": [vp, u32, C.POINTER(C.c_double), C.POINTER(C.c_double)],
+            "ps_stack_time_kernel": [vp, u32, u32, C.POINTER(C.c_double), C.POINTER(u32)],
             "ps_stack_debug_buffer": [vp, u32, C.POINTER(vp), C.POINTER(u64)],
             "ps_mfma_probe": [i32, i32, i32, vp, vp],
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
@@ -308,6 +309,13 @@ class Stack:
                 out.append((a.value, b.value))
         return out
 
+    def time_kernel(self, kernel, reps=5):
+        """(avg ms per launch, launches per pass) of one kernel kind launched back to back."""
+        ms, n = C.c_double(), C.c_uint32()
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_time_kernel(self.h, kernel, reps, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
     def debug_buffer(self, which, dtype, shape):
         """Copy of a workspace buffer as a numpy array (synchronises first)."""
         self.synchronize()
@@ -371,4 +379,5 @@ def load_synthetic(stacks, cfg, seed, threads=8, lookahead=12, progress=None):
                 st.load_matrix(layer, kind, expert, sc, cd)
             done += 1
             if progress and (done % progress == 0 or done == len(todo)):
-                print("  loaded %d / %d matrices" % (done, len(todo)), flush=True)
+                import sys
+                print("  loaded %d / %d matrices" % (done, len(todo)), file=sys.stderr, flush=True)

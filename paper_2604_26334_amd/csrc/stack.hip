@@ -646,6 +646,42 @@ int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur
     return PS_OK;
 }
 
+int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, double *avg_launch_ms, uint32_t *launches) {
+    if (!st || !avg_launch_ms || !launches || reps == 0) { ps::set_error("bad argument"); return PS_E_ARG; }
+    if (!st->have_dense_sched || st->n_loaded != st->n_expected) { ps::set_error("needs a loaded dense stack"); return PS_E_STATE; }
+    const ps_plan &p = st->plan;
+    // activations: the workspace ping-pong buffers stand in for the caller's tensors
+    const __half *xin = reinterpret_cast<const __half *>(st->arena + p.ws.x0);
+    __half *xout = reinterpret_cast<__half *>(st->arena + p.ws.x1);
+    hipEvent_t e0, e1;
+    PS_HIP(hipEventCreate(&e0));
+    PS_HIP(hipEventCreate(&e1));
+    uint32_t n = 0;
+    int32_t rc = PS_OK;
+    for (uint32_t r = 0; r <= reps && rc == PS_OK; ++r) {   // pass 0 warms up
+        if (r == 1) { if (hipEventRecord(e0, st->compute) != hipSuccess) rc = PS_E_HIP; n = 0; }
+        for (const ps::Op &op : st->dense_sched.ops) {
+            if (op.info.type != PS_OP_KERNEL || op.info.kernel != kernel || op.info.slot >= 0) continue;
+            rc = issue_kernel(st, st->dense_sched, op, xin, xout);
+            if (rc) break;
+            ++n;
+        }
+    }
+    float ms = 0;
+    if (rc == PS_OK && (hipEventRecord(e1, st->compute) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                        hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) {
+        ps::set_error("event timing failed");
+        rc = PS_E_HIP;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    if (n == 0) { ps::set_error("no resident op of kernel kind %u", kernel); return PS_E_ARG; }
+    *avg_launch_ms = (double)ms / n;
+    *launches = n / reps;
+    return PS_OK;
+}
+
 int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes) {
     if (!st || !dev_ptr || !bytes) { ps::set_error("NULL argument"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
