@@ -254,6 +254,10 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
  * Order and arithmetic are unchanged (Algorithm 1's RunInTopologicalOrder); all modes give
  * bit-identical results.  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
+/* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
+ * the copy stream pulls all of them from the pinned pool (one launch per slot fill);
+ * gather = 0: one hipMemcpyAsync per expert.  Dense slabs always use hipMemcpyAsync. */
+int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather);
 /* Block until both streams are idle; PS_E_HIP if the persistent kernel reported a barrier
  * time-out (its bounded waits make the kernel drain instead of hanging). */
 int32_t ps_stack_sync_check(ps_stack *st);

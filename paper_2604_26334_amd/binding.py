@@ -64,7 +64,7 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
-           "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
+           "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix"]
 
 _lib = None
@@ -105,6 +105,7 @@ def lib():
             "ps_stack_set_profiling": [vp, i32],
             "ps_stack_set_decode_mode": [vp, i32],
             "ps_stack_sync_check": [vp],
+            "ps_stack_set_copy_mode": [vp, i32],
             "ps_stack_stats": [vp, C.POINTER(ps_stats)],
             "ps_stack_op_time": [vp, u32, C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "ps_stack_time_kernel": [vp, u32, u32, C.POINTER(C.c_double), C.POINTER(u32)],
@@ -284,6 +285,9 @@ class Stack:
     def synchronize(self):
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_sync_check(self.h))
+
+    def set_copy_mode(self, gather):
+        _check(lib().ps_stack_set_copy_mode(self.h, 1 if gather else 0))
 
     def set_decode_mode(self, mode):
         """0: launch per shard, 1: persistent kernel, 2: HIP-graph replay (see pshard.h)."""

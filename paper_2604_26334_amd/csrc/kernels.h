@@ -59,6 +59,15 @@ struct DecodePhase {
     uint32_t mode, ksplit, x_tag, res_tag, out_tag, pad[3];
 };
 
+// one host->device copy of a gathered batch: n16 16-byte units from pinned host memory to VRAM
+struct CopyDesc {
+    uint64_t src, dst;
+    uint32_t n16, pad0, pad1, pad2;
+};
+// one launch copies `n` shards (descs may live in pinned host memory): the GPU pulls them over
+// PCIe itself, which avoids the per-call cost of many small hipMemcpyAsync
+hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st);
+
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units);
 // sync: kSyncBytes of zero-initialised device memory; epoch_base: barriers completed so far
 hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases, uint32_t grid, uint32_t *sync,

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "kernels.h"
 
@@ -841,6 +842,33 @@ hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t ma
         case GEMM_F32: return launch_gemm_m<GEMM_F32>(a, ntasks, max_tok, st);
     }
     return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
+// Gathered host->device copy: blockIdx.y selects the shard, the 16 workgroups of a shard
+// stride through it in 16-byte units (each wave moves 1 KB contiguous per step).
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs) {
+    const CopyDesc d = descs[blockIdx.y];
+    const u4_t *src = reinterpret_cast<const u4_t *>(d.src);
+    u4_t *dst = reinterpret_cast<u4_t *>(d.dst);
+    const uint32_t stride = gridDim.x * 256;
+    uint32_t idx = blockIdx.x * 256 + threadIdx.x;
+    for (; idx + 7 * stride < d.n16; idx += 8 * stride) {
+        u4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + idx + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) dst[idx + u * stride] = v[u];
+    }
+    for (; idx < d.n16; idx += stride) dst[idx] = __builtin_nontemporal_load(src + idx);
+}
+
+hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    static const int wgs = [] { const char *e = getenv("PS_GATHER_WGS"); int v = e ? atoi(e) : 8; return v > 0 && v <= 256 ? v : 8; }();
+    hipLaunchKernelGGL(h2d_gather_kernel, dim3(wgs, n), dim3(256), 0, st, descs);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------

@@ -37,13 +37,17 @@ struct ps_stack {
     uint64_t n_loaded = 0, n_expected = 0;
     hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     std::vector<hipEvent_t> ev_router;
-    hipEvent_t ev_upload = nullptr;
-    bool upload_pending = false;
+    hipEvent_t ev_upload[2] = {nullptr, nullptr};   // per table buffer: its uploads / gathers are done
+    bool upload_pending[2] = {false, false};
+    uint32_t table_idx = 0;                   // table buffer of the current forward
+    bool gather_copy = true;                  // expert batches: one gather kernel instead of one memcpy each
+    uint64_t descs_off = 0;                   // offset of the copy descriptors in a table buffer
+    uint32_t n_descs = 0;                     // descriptors written in the current forward
     ps_schedule dense_sched;
     bool have_dense_sched = false;
     void *stage = nullptr;                    // pinned staging for resident loads
     uint64_t stage_bytes = 0;
-    void *tables_host = nullptr;              // pinned: logits | tasks | pairs for one forward (MoE)
+    void *tables_host[2] = {nullptr, nullptr};   // pinned: logits | tasks | pairs | copy descriptors of one forward (MoE)
     uint64_t tables_bytes = 0;
     bool persistent = false;                  // whole forward = one persistent decode kernel
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
@@ -325,12 +329,40 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
             if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
             if (prof) { PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->copy)); st->prof_is_copy[i] = 1; }
-            PS_HIP(hipMemcpyAsync(slot_ptr(st, o.slot) + o.slot_offset, st->shard_host[o.shard0], o.bytes,
-                                  hipMemcpyHostToDevice, st->copy));
+            size_t last = i;
+            if (st->gather_copy && p.shards[o.shard0].kind == PS_SHARD_EXPERT && st->tables_host[0]) {
+                // the rest of this slot fill follows in the op list: one gather launch for all of it
+                ps::CopyDesc *descs = reinterpret_cast<ps::CopyDesc *>(
+                    static_cast<uint8_t *>(st->tables_host[st->table_idx]) + st->descs_off) + st->n_descs;
+                uint32_t n = 0;
+                for (size_t j = i; j < sc.ops.size(); ++j) {
+                    const ps_op_info &c = sc.ops[j].info;
+                    if (c.type != PS_OP_COPY || c.slot != o.slot || (j > i && (c.flags & PS_OPF_WAIT_SLOT_FREE))) break;
+                    descs[n].src = (uint64_t)(uintptr_t)st->shard_host[c.shard0];
+                    descs[n].dst = (uint64_t)(uintptr_t)(slot_ptr(st, c.slot) + c.slot_offset);
+                    descs[n].n16 = (uint32_t)(c.bytes / 16);
+                    ++n;
+                    last = j;
+                    ss.streamed_bytes_step += c.bytes;
+                    ss.n_copies++;
+                    if (prof && j > i) {   // the batch's time is booked on its first op
+                        PS_HIP(hipEventRecord(st->prof_ev[2 * j], st->copy));
+                        PS_HIP(hipEventRecord(st->prof_ev[2 * j + 1], st->copy));
+                        st->prof_is_copy[j] = 1;
+                    }
+                    if (c.flags & PS_OPF_RECORD_READY) break;
+                }
+                st->n_descs += n;
+                PS_HIP(launch_h2d_gather(descs, n, st->copy));
+            } else {
+                PS_HIP(hipMemcpyAsync(slot_ptr(st, o.slot) + o.slot_offset, st->shard_host[o.shard0], o.bytes,
+                                      hipMemcpyHostToDevice, st->copy));
+                ss.streamed_bytes_step += o.bytes;
+                ss.n_copies++;
+            }
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->copy));
-            if (o.flags & PS_OPF_RECORD_READY) PS_HIP(hipEventRecord(st->ev_ready[o.slot], st->copy));
-            ss.streamed_bytes_step += o.bytes;
-            ss.n_copies++;
+            if (sc.ops[last].info.flags & PS_OPF_RECORD_READY) PS_HIP(hipEventRecord(st->ev_ready[o.slot], st->copy));
+            i = last;
         } else {
             if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
@@ -411,10 +443,13 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         st->ev_router.resize(m.n_layers);
         for (auto &e : st->ev_router)
             if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
-        if (hipEventCreateWithFlags(&st->ev_upload, hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
-        st->tables_bytes = p.ws.logits_bytes + p.ws.tasks_bytes + p.ws.pairs_bytes;
-        if (hipHostMalloc(&st->tables_host, st->tables_bytes, hipHostMallocDefault) != hipSuccess) {
-            ps::set_error("hipHostMalloc for routing tables failed"); return fail(PS_E_HIP);
+        st->descs_off = ps::align_up(p.ws.logits_bytes + p.ws.tasks_bytes + p.ws.pairs_bytes, 256);
+        st->tables_bytes = st->descs_off + (p.ws.tasks_bytes / sizeof(ps::DeviceTask)) * sizeof(ps::CopyDesc);
+        for (int b = 0; b < 2; ++b) {
+            if (hipEventCreateWithFlags(&st->ev_upload[b], hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
+            if (hipHostMalloc(&st->tables_host[b], st->tables_bytes, hipHostMallocDefault) != hipSuccess) {
+                ps::set_error("hipHostMalloc for routing tables failed"); return fail(PS_E_HIP);
+            }
         }
     } else {
         int32_t rc = ps::build_schedule(&st->plan, nullptr, &st->dense_sched);
@@ -514,8 +549,12 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     int32_t rc = ps::build_schedule(&st->plan, router_logits, &sc);
     if (rc) return rc;
     // device tables: logits | tasks | pairs, staged in pinned memory and uploaded on the compute stream
-    if (st->upload_pending) { PS_HIP(hipEventSynchronize(st->ev_upload)); st->upload_pending = false; }
-    uint8_t *th = static_cast<uint8_t *>(st->tables_host);
+    // two table buffers alternate, so the host can prepare a forward while the previous one runs
+    st->table_idx ^= 1;
+    const uint32_t tb = st->table_idx;
+    if (st->upload_pending[tb]) { PS_HIP(hipEventSynchronize(st->ev_upload[tb])); st->upload_pending[tb] = false; }
+    st->n_descs = 0;
+    uint8_t *th = static_cast<uint8_t *>(st->tables_host[tb]);
     std::memcpy(th, router_logits, p.ws.logits_bytes);
     ps::DeviceTask *dt = reinterpret_cast<ps::DeviceTask *>(th + p.ws.logits_bytes);
     if (sc.tasks.size() * sizeof(ps::DeviceTask) > p.ws.tasks_bytes || sc.pairs.size() * 4 > p.ws.pairs_bytes) {
@@ -536,9 +575,13 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     if (!sc.pairs.empty())
         PS_HIP(hipMemcpyAsync(st->arena + p.ws.pairs, th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.size() * 4,
                               hipMemcpyHostToDevice, st->compute));
-    PS_HIP(hipEventRecord(st->ev_upload, st->compute));
-    st->upload_pending = true;
-    return run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+    rc = run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+    // the buffer is free again once the uploads (compute stream) and the gathers (copy stream) are done
+    PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[0], 0));
+    PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[1], 0));
+    PS_HIP(hipEventRecord(st->ev_upload[tb], st->compute));
+    st->upload_pending[tb] = true;
+    return rc;
 }
 
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
@@ -581,6 +624,12 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     st->persistent_grid = (uint32_t)cus;   // one 512-thread workgroup per CU: all co-resident
     st->bar_base = 0;
     st->persistent = true;
+    return PS_OK;
+}
+
+int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    st->gather_copy = gather != 0;
     return PS_OK;
 }
 
@@ -706,13 +755,13 @@ void ps_stack_destroy(ps_stack *st) {
     }
     for (void *c : st->host_chunks) (void)hipHostFree(c);
     if (st->stage) (void)hipHostFree(st->stage);
-    if (st->tables_host) (void)hipHostFree(st->tables_host);
+    for (int b = 0; b < 2; ++b) if (st->tables_host[b]) (void)hipHostFree(st->tables_host[b]);
     for (int s = 0; s < 2; ++s) {
         if (st->ev_ready[s]) (void)hipEventDestroy(st->ev_ready[s]);
         if (st->ev_free[s]) (void)hipEventDestroy(st->ev_free[s]);
     }
     for (auto e : st->ev_router) if (e) (void)hipEventDestroy(e);
-    if (st->ev_upload) (void)hipEventDestroy(st->ev_upload);
+    for (int b = 0; b < 2; ++b) if (st->ev_upload[b]) (void)hipEventDestroy(st->ev_upload[b]);
     for (auto e : st->prof_ev) (void)hipEventDestroy(e);
     for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
     delete st;
