@@ -610,6 +610,19 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // the activation tile of one super-block (MT x 128 k) is staged in LDS, 16-byte chunks
 // XOR-swizzled by token so that operand reads are conflict-free.
 // ------------------------------------------------------------------------------------
+// LDS column of activation chunk u (k = 8u .. 8u+7 of a super-block) within its token's 16-chunk
+// row, before the XOR with the token index: MFMA step kk of lane group c consumes chunk 4c + kk,
+// kept at column c + 4kk so that the four lane groups of one read touch adjacent columns (measured:
+// the 4c + kk order costs 1.5x the LDS cycles of this one)
+__device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) | (u >> 2); }
+
+// raw buffer descriptor over the whole 32-bit offset range from `base` (offsets are validated on the
+// host); loads through it take a 32-bit lane offset plus a scalar offset
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
+}
+constexpr int kAuxNt = 2;   // non-temporal: streamed weights are not worth keeping in cache
+
 template <int MODE, int AT, int MT, bool GROUPED>
 __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
     extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
@@ -633,26 +646,29 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
 
     // activation fill: thread moves chunk u of tokens tok0, tok0 + 16, ... of the tile
     const uint32_t u = tid & 15, tok0 = tid >> 4;
-    const uint32_t fill_dst = tok0 * 16 + (u ^ (tok0 & 15));   // + r * 256 for token tok0 + 16 r
-    // row offset (elements) of the r-th token this thread moves; grouped launches look it up
-    uint32_t xoff_g[GROUPED ? NFILL : 1];
-    if (GROUPED) {
+    const uint32_t fill_dst = tok0 * 16 + (lds_col(u) ^ (tok0 & 15));   // + r * 256 for token tok0 + 16 r
+    // byte offset of chunk u in the row of the r-th token this thread moves (grouped launches look
+    // the row up); tokens past the end re-read the last valid row: their MFMA columns are never
+    // stored, and the fill needs neither a branch nor zeros.  Addresses are a uniform base plus
+    // these 32-bit offsets, so the loop does no 64-bit vector arithmetic.
+    uint32_t xoff[NFILL];
 #pragma unroll
-        for (int r = 0; r < NFILL; ++r) {
-            const uint32_t tok = m0 + tok0 + r * 16;
-            size_t rowi = tok < ntok ? tok : m0;
-            rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[rowi] / (int32_t)a.top_k) : (size_t)pairs[rowi];
-            xoff_g[r] = (uint32_t)(rowi * a.x_stride);
-        }
+    for (int r = 0; r < NFILL; ++r) {
+        const uint32_t tok = min(m0 + tok0 + r * 16, ntok - 1);
+        size_t rowi = tok;
+        if (GROUPED) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[tok] / (int32_t)a.top_k) : (size_t)pairs[tok];
+        xoff[r] = (uint32_t)((rowi * a.x_stride + u * 8) * sizeof(__half));
     }
-    const uint32_t xoff0 = (m0 + tok0) * a.x_stride, xstep = 16 * a.x_stride;
-    // weights: per tile a pointer to its first group; tiles past the slab read tile 0 (discarded)
-    const uint4 *wt[AT];
+    // weights: 32-bit byte offset of the lane's 16 bytes in its tiles' first super-block; tiles past
+    // the slab read tile 0 (discarded)
+    uint32_t woff[AT];
 #pragma unroll
     for (int t = 0; t < AT; ++t) {
         const uint32_t tile = tile_base + t < a.ntiles ? tile_base + t : 0;
-        wt[t] = W + (size_t)tile * a.tile_u4 + lane;
+        woff[t] = (tile * a.tile_u4 + lane) * 16u;
     }
+    // buffer addressing: uniform part of an address in a scalar offset, lane part in xoff / woff
+    const __amdgpu_buffer_rsrc_t xbuf = make_rsrc(a.x), wbuf = make_rsrc(W);
 
     f4_t acc[AT][NMT];
 #pragma unroll
@@ -664,17 +680,12 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
     // sits in registers at any time
     constexpr int HA = (NFILL + 1) / 2, HB = NFILL - HA;
     uint4 xr[HA], wq[AT], wn[AT];
-    uint16_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block
+    uint32_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block (fp16 bits)
     auto load_x = [&](uint32_t sb, int r0, int cnt) {
-        const uint32_t col = gather_col(sb * 128 + u * 8, a.x_off, a.x_group);
+        const uint32_t xs = gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half);
 #pragma unroll
-        for (int r = 0; r < HA; ++r) {
-            if (r < cnt) {
-                const bool ok = m0 + tok0 + (r0 + r) * 16 < ntok;
-                const uint32_t off = GROUPED ? xoff_g[GROUPED ? r0 + r : 0] : xoff0 + (r0 + r) * xstep;
-                xr[r] = ok ? *reinterpret_cast<const uint4 *>(a.x + off + col) : make_uint4(0, 0, 0, 0);
-            }
-        }
+        for (int r = 0; r < HA; ++r)
+            if (r < cnt) xr[r] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xbuf, xoff[r0 + r], xs, 0));
     };
     auto store_x = [&](uint32_t stage, int r0, int cnt) {
 #pragma unroll
@@ -688,19 +699,19 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
         sbn = min(sbn, a.nsb - 1);
         const uint32_t gn = sbn >> 3, sn = sbn & 7;
         const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
+        const uint32_t gb = gn * (9 * 1024);
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
-            const uint4 *gb = wt[t] + (size_t)gn * (9 * 64);
-            wn[t] = load_stream(gb + sn * 64);
-            dn[t] = reinterpret_cast<const uint16_t *>(gb + nsb_n * 64)[sn];
+            wn[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, woff[t], gb + sn * 1024, kAuxNt));
+            dn[t] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, woff[t], gb + nsb_n * 1024 + sn * 2, 0);
         }
     };
     // A operands of MFMA step kk from raw dwords + scale: (q - 8) * d rounded to fp16
-    auto dequant_a = [&](h8_t (&A)[AT], const uint4 (&w4)[AT], const uint16_t (&ds)[AT], int kk) {
+    auto dequant_a = [&](h8_t (&A)[AT], const uint4 (&w4)[AT], const uint32_t (&ds)[AT], int kk) {
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
             const uint32_t q = kk == 0 ? w4[t].x : kk == 1 ? w4[t].y : kk == 2 ? w4[t].z : w4[t].w;
-            const _Float16 d = __builtin_bit_cast(_Float16, ds[t]);
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)ds[t]);
             const h2_t dd = {d, d};
             h2_t w[4];
             dequant8(q, w);
@@ -733,15 +744,23 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
         const uint32_t sbn = min(sb + 1, sb_end - 1);
         load_x(sbn, 0, HA);   // prefetch the next super-block: first half of the activations, weights
         load_w(sb + 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
         const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (!PIPE) dequant_a(Acur, wq, dq, kk);
             else if (kk < 3) dequant_a(Anxt, wq, dq, kk + 1);
-            else dequant_a(Anxt, wn, dn, 0);
+            else {
+                // the prefetched weights become visible to the compiler only here, so nothing derived
+                // from them is scheduled (and waited for) earlier in the iteration
+#pragma unroll
+                for (int t = 0; t < AT; ++t)
+                    asm volatile("" : "+v"(wn[t].x), "+v"(wn[t].y), "+v"(wn[t].z), "+v"(wn[t].w), "+v"(dn[t]));
+                dequant_a(Anxt, wn, dn, 0);
+            }
 #pragma unroll
             for (int n = 0; n < NMT; ++n) {
-                const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c * 4 + kk) ^ i)]);
+                const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + kk * 4) ^ i)]);
 #pragma unroll
                 for (int t = 0; t < AT; ++t)
                     acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Acur[t], B, acc[t][n], 0, 0, 0);
@@ -753,6 +772,7 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
             if (kk == 1) {
                 store_x(stage ^ 1, 0, HA);
                 if (HB) load_x(sbn, HA, HB);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if (HB) store_x(stage ^ 1, HA, HB);
@@ -835,6 +855,9 @@ static hipError_t launch_gemm_m(const GemmArgs &a, uint32_t ntasks, uint32_t max
 }
 
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
+    // the kernel addresses weights and activations as a uniform base plus 32-bit byte offsets
+    if ((uint64_t)a.ntiles * a.tile_u4 * 16u > 0xFFFFFFFFull || (uint64_t)a.M * (a.top_k ? a.top_k : 1u) * a.x_stride * 2u > 0xFFFFFFFFull)
+        return hipErrorInvalidValue;
     switch (mode) {
         case GEMM_PLAIN: return launch_gemm_m<GEMM_PLAIN>(a, ntasks, max_tok, st);
         case GEMM_RESID: return launch_gemm_m<GEMM_RESID>(a, ntasks, max_tok, st);
@@ -868,6 +891,112 @@ hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st) 
     if (n == 0) return hipSuccess;
     static const int wgs = [] { const char *e = getenv("PS_GATHER_WGS"); int v = e ? atoi(e) : 8; return v > 0 && v <= 256 ? v : 8; }();
     hipLaunchKernelGGL(h2d_gather_kernel, dim3(wgs, n), dim3(256), 0, st, descs);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Batched-decode kernel (2..64 tokens), HBM-bound: one workgroup of 8 waves owns 8 row-tiles
+// (one per wave) x ONE scale group of K (1024 k) x all tokens.  Like the one-token kernel, a wave
+// issues all its weight loads up front (8 super-blocks + scales); meanwhile the workgroup stages
+// the MT x 1024 activation tile of its scale group in LDS once (swizzled as in the prefill
+// kernel); after the single barrier every wave runs its 8 x 4 MFMA steps without further
+// synchronisation and writes its 16 x MT fp32 partial block to the scale group's plane.
+// The planes are summed in ascending group order by splitk_epilogue_kernel.
+// ------------------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs a) {
+    extern __shared__ uint4 lds[];                 // 8 sub-tiles (one per super-block) of MT x 16 chunks
+    constexpr int NMT = MT / 16;
+    constexpr int NCH = MT * 16 * 8 / 512;         // 16-byte chunks each thread stages (MT / 4)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, c = lane >> 4;
+    const uint32_t g = blockIdx.y;
+    const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
+    const uint32_t tile = blockIdx.x * 8 + wave;
+    const bool active = tile < a.ntiles;
+
+    // weights first: they do not depend on the activations
+    const uint4 *gb = a.W + (size_t)(active ? tile : 0) * a.tile_u4 + (size_t)g * (9 * 64) + lane;
+    uint4 wq[8];
+    const uint4 sc = load_stream(gb + nsb_g * 64);
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        if ((uint32_t)s < nsb_g) wq[s] = load_stream(gb + s * 64);
+
+    // activation tile: chunk id = tid + r * 512 -> sub-tile sbl = id / (MT * 16), token, chunk u
+#pragma unroll
+    for (int r0 = 0; r0 < NCH; r0 += 8) {
+        uint4 xr[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (r0 + r < NCH) {
+                const uint32_t id = tid + (r0 + r) * 512;
+                const uint32_t sbl = id / (MT * 16), rem = id % (MT * 16), tok = rem >> 4, u = rem & 15;
+                xr[r] = make_uint4(0, 0, 0, 0);
+                if (sbl < nsb_g && tok < a.M)
+                    xr[r] = *reinterpret_cast<const uint4 *>(a.x + (size_t)tok * a.x_stride +
+                                                             gather_col((g * 8 + sbl) * 128 + u * 8, a.x_off, a.x_group));
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (r0 + r < NCH) {
+                const uint32_t id = tid + (r0 + r) * 512;
+                const uint32_t sbl = id / (MT * 16), rem = id % (MT * 16), tok = rem >> 4, u = rem & 15;
+                lds[sbl * (MT * 16) + tok * 16 + (lds_col(u) ^ (tok & 15))] = xr[r];
+            }
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    f4_t acc[NMT];
+#pragma unroll
+    for (int n = 0; n < NMT; ++n) acc[n] = f4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if ((uint32_t)s < nsb_g) {
+            const uint32_t dw = (s < 2) ? sc.x : (s < 4) ? sc.y : (s < 6) ? sc.z : sc.w;
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
+            const h2_t dd = {d, d};
+            const uint4 *ls = lds + s * (MT * 16) + i * 16;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const uint32_t q = kk == 0 ? wq[s].x : kk == 1 ? wq[s].y : kk == 2 ? wq[s].z : wq[s].w;
+                h2_t w[4];
+                dequant8(q, w);
+                w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+                const h8_t A = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+#pragma unroll
+                for (int n = 0; n < NMT; ++n) {
+                    const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + kk * 4) ^ i)]);
+                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, acc[n], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // lane holds token j = lane & 15 of each token tile and rows 4 * (lane >> 4) + r of the row-tile
+    float *plane = a.out_f32 + (size_t)g * a.part_stride;
+#pragma unroll
+    for (int n = 0; n < NMT; ++n) {
+        const uint32_t tok = n * 16 + i;
+        if (tok < a.M)
+            *reinterpret_cast<float4 *>(plane + (size_t)tok * a.out_stride + tile * 16 + c * 4) =
+                make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
+    }
+}
+
+hipError_t launch_gemm_skinny(const GemmArgs &a, hipStream_t st) {
+    if (a.M < 1 || a.M > 64) return hipErrorInvalidValue;
+    dim3 grid((a.ntiles + 7) / 8, (a.nsb + 7) / 8);
+    if (a.M <= 16) hipLaunchKernelGGL(gemm_skinny_kernel<16>, grid, dim3(512), 16 * 2048, st, a);
+    else if (a.M <= 32) hipLaunchKernelGGL(gemm_skinny_kernel<32>, grid, dim3(512), 32 * 2048, st, a);
+    else {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_skinny_kernel<64>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 2048);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(gemm_skinny_kernel<64>, grid, dim3(512), 64 * 2048, st, a);
+    }
     return hipGetLastError();
 }
 

@@ -82,14 +82,8 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
 }
 
 uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M) {
-    if (M < 2 || M > 64) return 0;
-    const uint32_t wgs = (mg.ntiles + 7) / 8;          // workgroups of 8 row-tiles over N
-    static const uint32_t target = [] { const char *e = getenv("PS_SPLITK_TARGET"); return e ? (uint32_t)atoi(e) : 384u; }();
-    static const uint32_t cap = [] { const char *e = getenv("PS_SPLITK_CAP"); return e ? (uint32_t)atoi(e) : 8u; }();
-    if (wgs >= target) return 0;
-    uint32_t parts = std::min(std::min(mg.nsb, cap), (target + wgs - 1) / wgs);
-    if (parts <= 1) return 0;
-    return (mg.nsb + parts - 1) / parts;
+    (void)mg;
+    return (M >= 2 && M <= 64) ? kGroupSb : 0;   // batched decode: one scale group of K per part
 }
 
 Workspace make_workspace(const ModelGeom &g, uint32_t M) {
