@@ -621,6 +621,15 @@ __device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
 }
+typedef __attribute__((address_space(3))) void lds_void;
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at dst + 16 l
+// (dst is wave-uniform), without passing through registers.  The host pass has no such builtin and
+// only needs the kernel's signature.
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_void *dst, uint32_t voff, uint32_t soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, voff, soff, 0, 0);
+#endif
+}
 constexpr int kAuxNt = 2;   // non-temporal: streamed weights are not worth keeping in cache
 
 template <int MODE, int AT, int MT, bool GROUPED>
@@ -644,13 +653,15 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
     if (m0 >= ntok) return;
     const uint32_t tile_base = (blockIdx.x * 4 + wave) * AT;
 
-    // activation fill: thread moves chunk u of tokens tok0, tok0 + 16, ... of the tile
-    const uint32_t u = tid & 15, tok0 = tid >> 4;
-    const uint32_t fill_dst = tok0 * 16 + (lds_col(u) ^ (tok0 & 15));   // + r * 256 for token tok0 + 16 r
-    // byte offset of chunk u in the row of the r-th token this thread moves (grouped launches look
-    // the row up); tokens past the end re-read the last valid row: their MFMA columns are never
-    // stored, and the fill needs neither a branch nor zeros.  Addresses are a uniform base plus
-    // these 32-bit offsets, so the loop does no 64-bit vector arithmetic.
+    // activation fill, global memory straight into LDS (buffer_load ... lds): round r of a wave
+    // writes 64 consecutive 16-byte slots, i.e. thread tid fills slot tid & 15 of token
+    // tok0 + 16 r, tok0 = tid >> 4, and therefore fetches the chunk that belongs there,
+    // u = lds_col(slot ^ (tok0 & 15)) (lds_col is its own inverse).
+    // xoff: byte offset of that chunk in the token's row (grouped launches look the row up);
+    // tokens past the end re-read the last valid row: their MFMA columns are never stored, and the
+    // fill needs neither a branch nor zeros.  Addresses are a uniform base plus these 32-bit
+    // offsets, so the loop does no 64-bit vector arithmetic.
+    const uint32_t tok0 = tid >> 4, u = lds_col((tid & 15) ^ (tok0 & 15));
     uint32_t xoff[NFILL];
 #pragma unroll
     for (int r = 0; r < NFILL; ++r) {
@@ -659,6 +670,7 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
         if (GROUPED) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[tok] / (int32_t)a.top_k) : (size_t)pairs[tok];
         xoff[r] = (uint32_t)((rowi * a.x_stride + u * 8) * sizeof(__half));
     }
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // weights: 32-bit byte offset of the lane's 16 bytes in its tiles' first super-block; tiles past
     // the slab read tile 0 (discarded)
     uint32_t woff[AT];
@@ -676,21 +688,13 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
 
-    // the activation tile of the next super-block is fetched in two halves, so only half of it
-    // sits in registers at any time
-    constexpr int HA = (NFILL + 1) / 2, HB = NFILL - HA;
-    uint4 xr[HA], wq[AT], wn[AT];
+    uint4 wq[AT], wn[AT];
     uint32_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block (fp16 bits)
-    auto load_x = [&](uint32_t sb, int r0, int cnt) {
+    auto fill_x = [&](uint32_t sb, uint32_t stage) {
         const uint32_t xs = gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half);
 #pragma unroll
-        for (int r = 0; r < HA; ++r)
-            if (r < cnt) xr[r] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xbuf, xoff[r0 + r], xs, 0));
-    };
-    auto store_x = [&](uint32_t stage, int r0, int cnt) {
-#pragma unroll
-        for (int r = 0; r < HA; ++r)
-            if (r < cnt) lds[stage * (MT * 16) + fill_dst + (r0 + r) * 256] = xr[r];
+        for (int r = 0; r < NFILL; ++r)
+            load_to_lds16(xbuf, (lds_void *)(lds + stage * (MT * 16) + r * 256 + wave_u * 64), xoff[r], xs);
     };
 
     // scale group / slot of super-block sb, clamped to the last one (the prefetch past the end
@@ -726,15 +730,14 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
         sb_begin = blockIdx.z * a.sb_per_part;
         sb_end = min(a.nsb, sb_begin + a.sb_per_part);
     }
-    load_x(sb_begin, 0, HA);
+    fill_x(sb_begin, 0);
     load_w(sb_begin);
-    store_x(0, 0, HA);
-    if (HB) { load_x(sb_begin, HA, HB); store_x(0, HA, HB); }
     // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
     // (one more operand set in registers; the 4-tile shape has no room for it)
     constexpr bool PIPE = (AT <= 2);
     h8_t Acur[AT], Anxt[AT];
     if (PIPE) dequant_a(Acur, wn, dn, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS fill has landed
     __syncthreads();
 
     for (uint32_t sb = sb_begin; sb < sb_end; ++sb) {
@@ -742,40 +745,56 @@ __global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
         const uint32_t sbn = min(sb + 1, sb_end - 1);
-        load_x(sbn, 0, HA);   // prefetch the next super-block: first half of the activations, weights
+        // prefetch the next super-block: activations into the other stage (every wave left it at
+        // the barrier that ended the previous iteration), then the weights
+        fill_x(sbn, stage ^ 1);
         load_w(sb + 1);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
         const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
+        // B operands are read one MFMA step ahead, so the LDS latency hides behind a step's MFMAs
+        h8_t Bc[NMT], Bn[NMT];
+#pragma unroll
+        for (int n = 0; n < NMT; ++n) Bc[n] = __builtin_bit_cast(h8_t, ls[n * 256 + (c ^ i)]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) {
+#pragma unroll
+                for (int n = 0; n < NMT; ++n) Bn[n] = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + (kk + 1) * 4) ^ i)]);
+                __builtin_amdgcn_sched_barrier(0);   // or the scheduler sinks each read next to its MFMA
+            }
             if (!PIPE) dequant_a(Acur, wq, dq, kk);
             else if (kk < 3) dequant_a(Anxt, wq, dq, kk + 1);
             else {
                 // the prefetched weights become visible to the compiler only here, so nothing derived
                 // from them is scheduled (and waited for) earlier in the iteration
 #pragma unroll
-                for (int t = 0; t < AT; ++t)
-                    asm volatile("" : "+v"(wn[t].x), "+v"(wn[t].y), "+v"(wn[t].z), "+v"(wn[t].w), "+v"(dn[t]));
+                for (int t = 0; t < AT; ++t) {
+                    uint4 w;
+                    uint32_t d;
+                    asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8\n\tv_mov_b32 %4, %9"
+                                 : "=&v"(w.x), "=&v"(w.y), "=&v"(w.z), "=&v"(w.w), "=&v"(d)
+                                 : "v"(wn[t].x), "v"(wn[t].y), "v"(wn[t].z), "v"(wn[t].w), "v"(dn[t]));
+                    wn[t] = w;
+                    dn[t] = d;
+                }
                 dequant_a(Anxt, wn, dn, 0);
             }
 #pragma unroll
             for (int n = 0; n < NMT; ++n) {
-                const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + kk * 4) ^ i)]);
 #pragma unroll
                 for (int t = 0; t < AT; ++t)
-                    acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Acur[t], B, acc[t][n], 0, 0, 0);
+                    acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Acur[t], Bc[n], acc[t][n], 0, 0, 0);
             }
             if (PIPE) {
 #pragma unroll
                 for (int t = 0; t < AT; ++t) Acur[t] = Anxt[t];
             }
-            if (kk == 1) {
-                store_x(stage ^ 1, 0, HA);
-                if (HB) load_x(sbn, HA, HB);
-                __builtin_amdgcn_sched_barrier(0);
+            if (kk < 3) {
+#pragma unroll
+                for (int n = 0; n < NMT; ++n) Bc[n] = Bn[n];
             }
         }
-        if (HB) store_x(stage ^ 1, HA, HB);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
 
