@@ -76,9 +76,6 @@ hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases,
 uint32_t decode_sync_err_offset();
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st);
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st);
-// batched decode (<= 64 tokens): fp32 partial plane per scale group of K (a.out_f32, a.part_stride,
-// a.out_stride = columns of a plane); the caller runs launch_splitk_epilogue over (nsb + 7) / 8 planes
-hipError_t launch_gemm_skinny(const GemmArgs &a, hipStream_t st);
 // sums `parts` fp32 partial planes [M][ncols_phys] in ascending order and applies the mode's epilogue
 hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
                                   uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,

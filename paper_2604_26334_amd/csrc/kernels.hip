@@ -9,10 +9,6 @@
 
 #include "kernels.h"
 
-#ifndef PS_GEMM_OCC
-#define PS_GEMM_OCC 2
-#endif
-
 namespace ps {
 
 typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
@@ -633,7 +629,7 @@ __device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_v
 constexpr int kAuxNt = 2;   // non-temporal: streamed weights are not worth keeping in cache
 
 template <int MODE, int AT, int MT, bool GROUPED>
-__global__ __launch_bounds__(256, PS_GEMM_OCC) void gemm_w4_kernel(GemmArgs a) {
+__global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmArgs a) {
     extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
     constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
@@ -887,7 +883,7 @@ hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t ma
 }
 
 // ------------------------------------------------------------------------------------
-// Gathered host->device copy: blockIdx.y selects the shard, the 16 workgroups of a shard
+// Gathered host->device copy: blockIdx.y selects the shard, the workgroups of a shard
 // stride through it in 16-byte units (each wave moves 1 KB contiguous per step).
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs) {
@@ -908,114 +904,9 @@ __global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs) 
 
 hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
-    static const int wgs = [] { const char *e = getenv("PS_GATHER_WGS"); int v = e ? atoi(e) : 8; return v > 0 && v <= 256 ? v : 8; }();
-    hipLaunchKernelGGL(h2d_gather_kernel, dim3(wgs, n), dim3(256), 0, st, descs);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------
-// Batched-decode kernel (2..64 tokens), HBM-bound: one workgroup of 8 waves owns 8 row-tiles
-// (one per wave) x ONE scale group of K (1024 k) x all tokens.  Like the one-token kernel, a wave
-// issues all its weight loads up front (8 super-blocks + scales); meanwhile the workgroup stages
-// the MT x 1024 activation tile of its scale group in LDS once (swizzled as in the prefill
-// kernel); after the single barrier every wave runs its 8 x 4 MFMA steps without further
-// synchronisation and writes its 16 x MT fp32 partial block to the scale group's plane.
-// The planes are summed in ascending group order by splitk_epilogue_kernel.
-// ------------------------------------------------------------------------------------
-template <int MT>
-__global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs a) {
-    extern __shared__ uint4 lds[];                 // 8 sub-tiles (one per super-block) of MT x 16 chunks
-    constexpr int NMT = MT / 16;
-    constexpr int NCH = MT * 16 * 8 / 512;         // 16-byte chunks each thread stages (MT / 4)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i = lane & 15, c = lane >> 4;
-    const uint32_t g = blockIdx.y;
-    const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
-    const uint32_t tile = blockIdx.x * 8 + wave;
-    const bool active = tile < a.ntiles;
-
-    // weights first: they do not depend on the activations
-    const uint4 *gb = a.W + (size_t)(active ? tile : 0) * a.tile_u4 + (size_t)g * (9 * 64) + lane;
-    uint4 wq[8];
-    const uint4 sc = load_stream(gb + nsb_g * 64);
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-        if ((uint32_t)s < nsb_g) wq[s] = load_stream(gb + s * 64);
-
-    // activation tile: chunk id = tid + r * 512 -> sub-tile sbl = id / (MT * 16), token, chunk u
-#pragma unroll
-    for (int r0 = 0; r0 < NCH; r0 += 8) {
-        uint4 xr[8];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            if (r0 + r < NCH) {
-                const uint32_t id = tid + (r0 + r) * 512;
-                const uint32_t sbl = id / (MT * 16), rem = id % (MT * 16), tok = rem >> 4, u = rem & 15;
-                xr[r] = make_uint4(0, 0, 0, 0);
-                if (sbl < nsb_g && tok < a.M)
-                    xr[r] = *reinterpret_cast<const uint4 *>(a.x + (size_t)tok * a.x_stride +
-                                                             gather_col((g * 8 + sbl) * 128 + u * 8, a.x_off, a.x_group));
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            if (r0 + r < NCH) {
-                const uint32_t id = tid + (r0 + r) * 512;
-                const uint32_t sbl = id / (MT * 16), rem = id % (MT * 16), tok = rem >> 4, u = rem & 15;
-                lds[sbl * (MT * 16) + tok * 16 + (lds_col(u) ^ (tok & 15))] = xr[r];
-            }
-        }
-    }
-    __syncthreads();
-    if (!active) return;
-
-    f4_t acc[NMT];
-#pragma unroll
-    for (int n = 0; n < NMT; ++n) acc[n] = f4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        if ((uint32_t)s < nsb_g) {
-            const uint32_t dw = (s < 2) ? sc.x : (s < 4) ? sc.y : (s < 6) ? sc.z : sc.w;
-            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
-            const h2_t dd = {d, d};
-            const uint4 *ls = lds + s * (MT * 16) + i * 16;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const uint32_t q = kk == 0 ? wq[s].x : kk == 1 ? wq[s].y : kk == 2 ? wq[s].z : wq[s].w;
-                h2_t w[4];
-                dequant8(q, w);
-                w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
-                const h8_t A = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
-#pragma unroll
-                for (int n = 0; n < NMT; ++n) {
-                    const h8_t B = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + kk * 4) ^ i)]);
-                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, acc[n], 0, 0, 0);
-                }
-            }
-        }
-    }
-    // lane holds token j = lane & 15 of each token tile and rows 4 * (lane >> 4) + r of the row-tile
-    float *plane = a.out_f32 + (size_t)g * a.part_stride;
-#pragma unroll
-    for (int n = 0; n < NMT; ++n) {
-        const uint32_t tok = n * 16 + i;
-        if (tok < a.M)
-            *reinterpret_cast<float4 *>(plane + (size_t)tok * a.out_stride + tile * 16 + c * 4) =
-                make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
-    }
-}
-
-hipError_t launch_gemm_skinny(const GemmArgs &a, hipStream_t st) {
-    if (a.M < 1 || a.M > 64) return hipErrorInvalidValue;
-    dim3 grid((a.ntiles + 7) / 8, (a.nsb + 7) / 8);
-    if (a.M <= 16) hipLaunchKernelGGL(gemm_skinny_kernel<16>, grid, dim3(512), 16 * 2048, st, a);
-    else if (a.M <= 32) hipLaunchKernelGGL(gemm_skinny_kernel<32>, grid, dim3(512), 32 * 2048, st, a);
-    else {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_skinny_kernel<64>),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 2048);
-        if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL(gemm_skinny_kernel<64>, grid, dim3(512), 64 * 2048, st, a);
-    }
+    // 8 workgroups per shard: enough outstanding reads to fill the PCIe link, few enough to leave the
+    // CUs to the compute stream
+    hipLaunchKernelGGL(h2d_gather_kernel, dim3(8, n), dim3(256), 0, st, descs);
     return hipGetLastError();
 }
 

@@ -82,8 +82,15 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
 }
 
 uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M) {
-    (void)mg;
-    return (M >= 2 && M <= 64) ? kGroupSb : 0;   // batched decode: one scale group of K per part
+    if (M < 2 || M > 64) return 0;
+    // batched decode: with few tokens a matrix has too few 8-tile workgroups to fill 256 CUs, so K is
+    // split until about one workgroup per CU exists (measured: more parts only add partial-plane
+    // traffic); at most 8 parts
+    const uint32_t wgs = (mg.ntiles + 7) / 8;
+    if (wgs >= 256) return 0;
+    const uint32_t parts = std::min(std::min(mg.nsb, 8u), (256u + wgs - 1) / wgs);
+    if (parts <= 1) return 0;
+    return (mg.nsb + parts - 1) / parts;
 }
 
 Workspace make_workspace(const ModelGeom &g, uint32_t M) {

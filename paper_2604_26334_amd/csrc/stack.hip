@@ -187,7 +187,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         const uint32_t ncols = a.ntiles * 16;
         pa.out_f32 = partial; pa.out = nullptr; pa.out_stride = ncols; pa.out_row0 = 0;
         pa.sb_per_part = per; pa.part_stride = M * ncols;
-        PS_HIP(launch_gemm_skinny(pa, cs));
+        PS_HIP(launch_gemm(GEMM_F32, pa, 0, M, cs));
         PS_HIP(launch_splitk_epilogue(mode, partial, (mg.nsb + per - 1) / per, pa.part_stride, M, ncols, rinv, a.res,
                                       a.out, a.out_stride, a.out_row0, cs));
         return PS_OK;
