@@ -45,14 +45,19 @@ __device__ __forceinline__ void dequant8(uint32_t v, h2_t w[4]) {
     w[3] = __builtin_elementwise_fma(as_h2(and_or(v8, 0x00F000F0u, 0x64006400u)), k16th, -k72);
 }
 
-__device__ __forceinline__ float dot8(uint32_t v, uint4 x, float acc) {
-    h2_t w[4];
-    dequant8(v, w);
-    acc = __builtin_amdgcn_fdot2(w[0], as_h2(x.x), acc, false);
-    acc = __builtin_amdgcn_fdot2(w[1], as_h2(x.y), acc, false);
-    acc = __builtin_amdgcn_fdot2(w[2], as_h2(x.z), acc, false);
-    acc = __builtin_amdgcn_fdot2(w[3], as_h2(x.w), acc, false);
-    return acc;
+// Decode dot product of 8 codes with 8 activations WITHOUT removing the code offsets: the fp16
+// patterns 1024 + q (codes 0, 1, 4, 5 of the dword) and 1024 + 16 q (codes 2, 3, 6, 7) go straight
+// into the fp32 dot-product accumulators lo / hi.  With S_lo, S_hi the sums of the activations at
+// those positions, sum((q - 8) x) = lo + hi / 16 - 1032 S_lo - 72 S_hi; the two S terms depend on
+// the activations only and are shared by every row (see gemv_item).  Saves the four packed
+// subtract / multiply-add operations per dword; the fp32 accumulators carry terms near 1024 |x|,
+// which costs about 1e-4 of a block's sum in relative accuracy.
+__device__ __forceinline__ void dot8_raw(uint32_t v, uint4 x, float &lo, float &hi) {
+    const uint32_t v8 = v >> 8;
+    lo = __builtin_amdgcn_fdot2(as_h2(and_or(v, 0x000F000Fu, 0x64006400u)), as_h2(x.x), lo, false);
+    hi = __builtin_amdgcn_fdot2(as_h2(and_or(v, 0x00F000F0u, 0x64006400u)), as_h2(x.y), hi, false);
+    lo = __builtin_amdgcn_fdot2(as_h2(and_or(v8, 0x000F000Fu, 0x64006400u)), as_h2(x.z), lo, false);
+    hi = __builtin_amdgcn_fdot2(as_h2(and_or(v8, 0x00F000F0u, 0x64006400u)), as_h2(x.w), hi, false);
 }
 
 __device__ __forceinline__ float half_of(uint4 v, int s) {  // s-th fp16 of a 16-byte vector
@@ -88,6 +93,22 @@ __device__ __forceinline__ __half to_half(float v) {
 }
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+
+// raw buffer descriptor over the whole 32-bit offset range from `base` (offsets are validated on the
+// host); loads through it take a 32-bit lane offset plus a scalar offset
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
+}
+typedef __attribute__((address_space(3))) void lds_void;
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at dst + 16 l
+// (dst is wave-uniform), without passing through registers.  The host pass has no such builtin and
+// only needs the kernel's signature.
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_void *dst, uint32_t voff, uint32_t soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, voff, soff, 0, 0);
+#endif
+}
+constexpr int kAuxNt = 2;   // non-temporal: streamed weights are not worth keeping in cache
 
 // source column of logical input column k: identity, or the identity-on-V attention
 // stand-in where query head h reads kv head h / group (head_dim 128)
@@ -125,17 +146,25 @@ struct GemvBuf {
     uint4 xa, xb;
 };
 
-// weights of scale group g of a unit's NT tiles (independent of the activations)
+// weights of scale group g of a unit's NT tiles (independent of the activations).  unit, g and
+// nsb_g are the same for the whole wave, so their share of the address is kept in scalar registers
+// and the loads take (descriptor, lane offset, scalar offset): no per-lane address arithmetic.
 template <int NT>
 __device__ __forceinline__ void gemv_issue_w(GemvBuf<NT> &b, const uint4 *W, uint32_t unit, uint32_t tile_u4,
                                              uint32_t g, uint32_t nsb_g, int lane) {
+    const __amdgpu_buffer_rsrc_t wb = make_rsrc(W);
+    const uint32_t tile_b = tile_u4 * 16u;
+    const uint32_t base = __builtin_amdgcn_readfirstlane(unit * NT * tile_b + g * (9u * 1024u));
+    const uint32_t nsb_u = __builtin_amdgcn_readfirstlane(nsb_g);
+    const uint32_t voff = (uint32_t)lane * 16u;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const uint4 *gb = W + (size_t)(unit * NT + t) * tile_u4 + (size_t)g * (9 * 64);
-        b.sc[t] = load_stream(gb + nsb_g * 64 + lane);
+        const uint32_t tb = base + t * tile_b;
+        b.sc[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, tb + nsb_u * 1024u, kAuxNt));
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-            if ((uint32_t)s < nsb_g) b.wq[t][s] = load_stream(gb + s * 64 + lane);
+            if ((uint32_t)s < nsb_u)
+                b.wq[t][s] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, tb + s * 1024u, kAuxNt));
     }
 }
 
@@ -169,6 +198,7 @@ struct GemvLds {
     uint4 x[NW][128];
     float red[2][(NW / 2) * kMaxGroups][2][16];   // K split >= 2: at most NW / 2 units per workgroup
     float red_ss[2][(NW / 2) * kMaxGroups];
+    float corr[NW][32];   // per wave: code-offset corrections of the current scale group
 };
 
 // One work item of the decode GEMV: the NW waves of the workgroup cover NW / ks units, ks
@@ -239,6 +269,24 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             }
             win[xslot(lane)] = cur.xa;
             win[xslot(lane + 64)] = cur.xb;
+            // code-offset corrections (see dot8_raw): lane (c, i) sums the activations of super-block
+            // i % 8, lane group c, that meet low-pattern and high-pattern codes; 1032 S_lo + 72 S_hi
+            // goes through LDS and each lane picks up the term of its c per super-block
+            {
+                const uint32_t *wp = reinterpret_cast<const uint32_t *>(win) + ((i & 7) * 16 + c) * 4;
+                const h2_t one = {(_Float16)1.0f, (_Float16)1.0f};
+                float sl = 0.f, sh = 0.f;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint4 xq = *reinterpret_cast<const uint4 *>(wp + p * 16);
+                    sl = __builtin_amdgcn_fdot2(as_h2(xq.x), one, sl, false);
+                    sh = __builtin_amdgcn_fdot2(as_h2(xq.y), one, sh, false);
+                    sl = __builtin_amdgcn_fdot2(as_h2(xq.z), one, sl, false);
+                    sh = __builtin_amdgcn_fdot2(as_h2(xq.w), one, sh, false);
+                }
+                if (i < 8) lds.corr[wave][c * 8 + i] = fmaf(72.0f, sh, 1032.0f * sl);
+            }
+            const float *corr = &lds.corr[wave][c * 8];
             float gacc[NT];   // this scale group's partial sums
 #pragma unroll
             for (int t = 0; t < NT; ++t) gacc[t] = 0.f;
@@ -250,11 +298,12 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
                     for (int p = 0; p < 4; ++p) xv[p] = win[s * 16 + p * 4 + c];
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
-                        float part = 0.f;
-                        part = dot8(cur.wq[t][s].x, xv[0], part);
-                        part = dot8(cur.wq[t][s].y, xv[1], part);
-                        part = dot8(cur.wq[t][s].z, xv[2], part);
-                        part = dot8(cur.wq[t][s].w, xv[3], part);
+                        float lo = 0.f, hi = 0.f;
+                        dot8_raw(cur.wq[t][s].x, xv[0], lo, hi);
+                        dot8_raw(cur.wq[t][s].y, xv[1], lo, hi);
+                        dot8_raw(cur.wq[t][s].z, xv[2], lo, hi);
+                        dot8_raw(cur.wq[t][s].w, xv[3], lo, hi);
+                        const float part = fmaf(hi, 0.0625f, lo) - corr[s];
                         gacc[t] = fmaf(half_of(cur.sc[t], s), part, gacc[t]);
                     }
                 }
@@ -325,7 +374,7 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
 }
 
 template <int MODE, int NW>
-__global__ __launch_bounds__(NW * 64) void gemv_w4_kernel(GemvArgs a, uint32_t ks) {
+__global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_t ks) {   // 4 waves per SIMD: at most 128 VGPRs
     __shared__ GemvLds<NW> lds;
     const uint4 *W = a.W;
     const __half *x = a.x;
@@ -368,6 +417,8 @@ uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units) {
 
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st) {
     if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8 && ksplit != 16) return hipErrorInvalidValue;
+    // weights are addressed as a uniform base plus 32-bit byte offsets
+    if ((uint64_t)a.nunits * (mode == GEMV_GATE_UP ? 2u : 1u) * a.tile_u4 * 16u > 0xFFFFFFFFull) return hipErrorInvalidValue;
     switch (mode) {
         case GEMV_PLAIN: return launch_gemv_t<GEMV_PLAIN>(a, ksplit, ntasks, st);
         case GEMV_RESID: return launch_gemv_t<GEMV_RESID>(a, ksplit, ntasks, st);
@@ -611,22 +662,6 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // kept at column c + 4kk so that the four lane groups of one read touch adjacent columns (measured:
 // the 4c + kk order costs 1.5x the LDS cycles of this one)
 __device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) | (u >> 2); }
-
-// raw buffer descriptor over the whole 32-bit offset range from `base` (offsets are validated on the
-// host); loads through it take a 32-bit lane offset plus a scalar offset
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
-}
-typedef __attribute__((address_space(3))) void lds_void;
-// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at dst + 16 l
-// (dst is wave-uniform), without passing through registers.  The host pass has no such builtin and
-// only needs the kernel's signature.
-__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_void *dst, uint32_t voff, uint32_t soff) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, voff, soff, 0, 0);
-#endif
-}
-constexpr int kAuxNt = 2;   // non-temporal: streamed weights are not worth keeping in cache
 
 template <int MODE, int AT, int MT, bool GROUPED>
 __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmArgs a) {
