@@ -149,22 +149,29 @@ struct GemvBuf {
 // weights of scale group g of a unit's NT tiles (independent of the activations).  unit, g and
 // nsb_g are the same for the whole wave, so their share of the address is kept in scalar registers
 // and the loads take (descriptor, lane offset, scalar offset): no per-lane address arithmetic.
-template <int NT>
+template <int NT, bool FULLG = false>
 __device__ __forceinline__ void gemv_issue_w(GemvBuf<NT> &b, const uint4 *W, uint32_t unit, uint32_t tile_u4,
                                              uint32_t g, uint32_t nsb_g, int lane) {
     const __amdgpu_buffer_rsrc_t wb = make_rsrc(W);
     const uint32_t tile_b = tile_u4 * 16u;
     const uint32_t base = __builtin_amdgcn_readfirstlane(unit * NT * tile_b + g * (9u * 1024u));
-    const uint32_t nsb_u = __builtin_amdgcn_readfirstlane(nsb_g);
+    // FULLG: every scale group has its 8 super-blocks, so the number of loads in flight is a
+    // compile-time fact and the compiler can wait for exactly the load a dot product needs
+    const uint32_t nsb_u = FULLG ? 8u : __builtin_amdgcn_readfirstlane(nsb_g);
     const uint32_t voff = (uint32_t)lane * 16u;
+    // issue order = consumption order (loads return in order): scales, then super-block by
+    // super-block across the tiles, so the dot products of a super-block can start while the later
+    // ones are still in flight
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const uint32_t tb = base + t * tile_b;
-        b.sc[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, tb + nsb_u * 1024u, kAuxNt));
+    for (int t = 0; t < NT; ++t)
+        b.sc[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, base + t * tile_b + nsb_u * 1024u, kAuxNt));
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-            if ((uint32_t)s < nsb_u)
-                b.wq[t][s] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, tb + s * 1024u, kAuxNt));
+    for (int s = 0; s < 8; ++s) {
+        if (FULLG || (uint32_t)s < nsb_u) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                b.wq[t][s] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wb, voff, base + t * tile_b + s * 1024u, kAuxNt));
+        }
     }
 }
 
@@ -213,7 +220,8 @@ struct NoPrefetch {
 // after_issue() runs once this item's first loads are in flight and `pre` has been consumed:
 // the persistent kernel uses it to start the weight loads of its NEXT item, so that they
 // stream while this item waits for its activations, computes, and crosses the barrier.
-template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16)>
+template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16),
+          bool FULLG = false>
 __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, const __half *x, __half *out,
                                           float *out_f32, uint32_t item, uint32_t ks, uint32_t gen,
                                           GemvLds<NW> &lds, const GemvBuf<2> &pre, bool use_pre,
@@ -245,10 +253,12 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
 #pragma unroll
                 for (int s = 0; s < 8; ++s) cur.wq[t][s] = pre.wq[t][s];
             }
+            gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
         } else {
-            gemv_issue_w<NT>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), lane);
+            // activations first: they are ready (and cached), and nothing can be computed before them
+            gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
+            gemv_issue_w<NT, FULLG>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), lane);
         }
-        gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
         if (MODE == GEMV_RESID && writer && a.res) {
             if (COH) {  // written by other workgroups: read the 32-bit word holding it at device scope
                 const uint32_t wd = __hip_atomic_load(reinterpret_cast<uint32_t *>(const_cast<__half *>(a.res)) + (row >> 1),
@@ -260,12 +270,12 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
         }
         after_issue();
         while (true) {
-            const uint32_t nsb_g = min(8u, a.nsb - g * 8u);
+            const uint32_t nsb_g = FULLG ? 8u : min(8u, a.nsb - g * 8u);
             const uint32_t gn = g + ks;
             const bool more = gn < a.ngroups;
             if (DBUF && more) {
-                gemv_issue_w<NT>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
                 gemv_issue_x<NT, COH>(nxt, gn, a.K, x, a.x_off, a.x_group, lane);
+                gemv_issue_w<NT, FULLG>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
             }
             win[xslot(lane)] = cur.xa;
             win[xslot(lane + 64)] = cur.xb;
@@ -292,7 +302,7 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             for (int t = 0; t < NT; ++t) gacc[t] = 0.f;
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                if ((uint32_t)s < nsb_g) {
+                if (FULLG || (uint32_t)s < nsb_g) {
                     uint4 xv[4];
 #pragma unroll
                     for (int p = 0; p < 4; ++p) xv[p] = win[s * 16 + p * 4 + c];
@@ -332,8 +342,8 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             if (DBUF) {
                 cur = nxt;
             } else {
-                gemv_issue_w<NT>(cur, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
                 gemv_issue_x<NT, COH>(cur, gn, a.K, x, a.x_off, a.x_group, lane);
+                gemv_issue_w<NT, FULLG>(cur, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
             }
             g = gn;
         }
@@ -373,7 +383,7 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
     }
 }
 
-template <int MODE, int NW>
+template <int MODE, int NW, bool FULLG>
 __global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_t ks) {   // 4 waves per SIMD: at most 128 VGPRs
     __shared__ GemvLds<NW> lds;
     const uint4 *W = a.W;
@@ -394,17 +404,23 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_
         }
     }
     GemvBuf<2> none;
-    gemv_item<MODE, NW, false>(a, W, x, out, out_f32, blockIdx.x, ks, 0, lds, none, false);
+    gemv_item<MODE, NW, false, NoPrefetch, ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), FULLG>(
+        a, W, x, out, out_f32, blockIdx.x, ks, 0, lds, none, false);
+}
+
+template <int MODE, bool FULLG>
+static hipError_t launch_gemv_f(const GemvArgs &a, uint32_t ks, uint32_t ntasks, hipStream_t st) {
+    const uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4, units = nw / ks;
+    dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
+    if (nw == 16) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 16, FULLG>), grid, dim3(1024), 0, st, a, ks);
+    else if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8, FULLG>), grid, dim3(512), 0, st, a, ks);
+    else hipLaunchKernelGGL((gemv_w4_kernel<MODE, 4, FULLG>), grid, dim3(256), 0, st, a, ks);
+    return hipGetLastError();
 }
 
 template <int MODE>
 static hipError_t launch_gemv_t(const GemvArgs &a, uint32_t ks, uint32_t ntasks, hipStream_t st) {
-    const uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4, units = nw / ks;
-    dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
-    if (nw == 16) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 16>), grid, dim3(1024), 0, st, a, ks);
-    else if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8>), grid, dim3(512), 0, st, a, ks);
-    else hipLaunchKernelGGL((gemv_w4_kernel<MODE, 4>), grid, dim3(256), 0, st, a, ks);
-    return hipGetLastError();
+    return (a.nsb % 8 == 0) ? launch_gemv_f<MODE, true>(a, ks, ntasks, st) : launch_gemv_f<MODE, false>(a, ks, ntasks, st);
 }
 
 // The K split is a pure performance choice (results do not depend on it): it grows until the
