@@ -147,6 +147,44 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
     return out
 
 
+def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
+    """Token-tier table + PickTier + chunked prefill: plan every tier under `budget`, pick the tier for a
+    prompt of `tokens` tokens, and time the chunked prefill with the picked tier and its two neighbours
+    (estimate against measurement for each)."""
+    table = B.TierTable(cfg, int(budget), profile=prof)
+    choice = table.pick(tokens)
+    ents = table.entries()
+    cand = [t for t in (choice.tier - 1, choice.tier, choice.tier + 1)
+            if 0 <= t < B.PS_NTIERS and ents[t].feasible and ents[t].tier_tokens >= 64]
+    stacks = [B.Stack(table.plan(t)) for t in cand]
+    B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8))
+    dev = stacks[0].device
+    x = torch.from_numpy(S.activations(seed, 400, tokens, cfg["hidden"])).to(dev)
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    out = dict(budget_bytes=int(budget), tokens=tokens, picked_tier_tokens=choice.tier_tokens, tiers={})
+    for t, st in zip(cand, stacks):
+        e = ents[t]
+        B.chunked_forward(st, x, y)
+        st.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            trips = B.chunked_forward(st, x, y)
+        st.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        out["tiers"]["%d" % e.tier_tokens] = dict(trips=trips, ttft_ms=ms, est_ms=trips * e.summary.est_step_ms,
+                                                  resident_bytes=e.summary.resident_bytes,
+                                                  workspace_bytes=e.summary.workspace_bytes)
+        log("prefill %d tokens, budget %.0f GB, tier %d x %d trips: TTFT %.1f ms (estimate %.1f ms)%s" % (
+            tokens, budget / 1e9, e.tier_tokens, trips, ms, trips * e.summary.est_step_ms,
+            "  <- picked" if t == choice.tier else ""))
+        st.close()
+    best = min(out["tiers"], key=lambda k: out["tiers"][k]["ttft_ms"])
+    out["measured_best_tier_tokens"] = int(best)
+    return out
+
+
 def measured_traffic(tag):
     """HBM bytes per launch of the named kernel from the committed rocprofv3 PMC summary
     (profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt); None if the summary is absent."""
@@ -170,7 +208,8 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
-    ap.add_argument("--extra", type=str, default="batch64,moe", help="further legs: batch64 (config 5), moe (config 4)")
+    ap.add_argument("--extra", type=str, default="batch64,moe,tiers",
+                    help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB)")
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -281,6 +320,8 @@ def main():
     extra = {}
     if "batch64" in args.extra and args.layers == 32:
         extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128)
+    if "tiers" in args.extra and args.layers == 32:
+        extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
     if "moe" in args.extra:
         extra["moe_decode_6gb"] = moe_leg(B, S, torch, seed, prof, 6e9, [1, 16], 10)
 

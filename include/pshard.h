@@ -208,6 +208,42 @@ int32_t ps_plan_summary(const ps_plan *plan, ps_plan_summary_t *out);
 int32_t ps_plan_get_shard(const ps_plan *plan, uint32_t i, ps_shard_info *out);
 void ps_plan_destroy(ps_plan *plan);
 
+/* Token-tier table (Algorithm 1, the loop over tiers, and Section 3, inference phase).
+ * ps_tier_table_create runs the planning phase once per tier of the set J =
+ * {1, 4, 16, 32, 64, 512, 1K, 2K, 4K, 8K, 16K} under one budget: a lower tier has a smaller
+ * workspace, so it pins more shards.  A tier whose workspace plus two minimum slots does not fit
+ * the budget is recorded as infeasible (it is not an error).  Host only, no GPU needed.
+ * Arguments as for ps_plan_create; *out is owned by the caller until ps_tier_table_destroy. */
+typedef struct ps_tier_table ps_tier_table;
+typedef struct ps_tier_entry {
+    uint32_t tier;             /* index into J                                            */
+    uint32_t tier_tokens;      /* tokens one trip through this tier's schedule processes  */
+    int32_t feasible;          /* 0: the budget cannot hold this tier's workspace + slots */
+    uint32_t pad;
+    ps_plan_summary_t summary; /* valid when feasible                                     */
+} ps_tier_entry;
+/* PickTier: the feasible tier t minimising ceil(new_tokens / tier_tokens[t]) * est_step_ms[t];
+ * among equal products the lowest tier wins.  The chosen tier's token count is also the chunk
+ * size of a chunked prefill: `iterations` trips through its schedule, the last one padded. */
+typedef struct ps_tier_choice {
+    uint32_t tier;
+    uint32_t tier_tokens;
+    uint32_t iterations;       /* ceil(new_tokens / tier_tokens)                          */
+    uint32_t pad;
+    double est_iter_ms;        /* the tier's est_step_ms                                  */
+    double est_total_ms;       /* iterations * est_iter_ms                                */
+} ps_tier_choice;
+int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t vram_budget_bytes,
+                             const ps_profile *profile, const float *expert_freq,
+                             ps_tier_table **out);
+int32_t ps_tier_table_entry(const ps_tier_table *table, uint32_t tier, ps_tier_entry *out);
+/* the plan of a feasible tier, owned by the table (valid until ps_tier_table_destroy);
+ * ps_stack_create copies it.  PS_E_ARG for an infeasible tier. */
+int32_t ps_tier_table_plan(const ps_tier_table *table, uint32_t tier, const ps_plan **out);
+/* PS_E_ARG when new_tokens is 0; PS_E_BUDGET when no tier is feasible. */
+int32_t ps_tier_pick(const ps_tier_table *table, uint32_t new_tokens, ps_tier_choice *out);
+void ps_tier_table_destroy(ps_tier_table *table);
+
 /* The executor's op list for one forward, as plain data (host only, no GPU).
  * router_logits: host fp32 [n_layers][n_tokens][n_experts], NULL for dense.
  * ps_schedule_validate proves with vector clocks over the two streams that no

@@ -180,3 +180,25 @@ def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None):
         if per_layer is not None:
             per_layer.append(x.copy())
     return x
+
+
+TIER_TOKENS = (1, 4, 16, 32, 64, 512, 1024, 2048, 4096, 8192, 16384)   # the tier set of Section 3
+
+
+def pick_tier(est_ms, new_tokens, tier_tokens=TIER_TOKENS):
+    """PickTier (Section 3, inference phase), written out: over the tiers that have a schedule
+    (est_ms[t] is not None), the one minimising ceil(new_tokens / tier_tokens[t]) * est_ms[t];
+    among equal products the lowest tier.  Returns (tier, iterations, total_ms).
+    Exact: the products are compared as rationals, not as rounded floats."""
+    from fractions import Fraction
+    best = None
+    for t, (tok, est) in enumerate(zip(tier_tokens, est_ms)):
+        if est is None:
+            continue
+        iters = -(-int(new_tokens) // tok)
+        total = iters * Fraction(est)
+        if best is None or total < best[2]:
+            best = (t, iters, total)
+    if best is None:
+        raise ValueError("no tier has a schedule")
+    return best[0], best[1], float(best[2])

@@ -48,6 +48,16 @@ class ps_plan_summary_t(C.Structure):
                [("est_step_ms", C.c_double), ("est_streamed_bytes_per_step", C.c_double)]
 
 
+class ps_tier_entry(C.Structure):
+    _fields_ = [("tier", C.c_uint32), ("tier_tokens", C.c_uint32), ("feasible", C.c_int32), ("pad", C.c_uint32),
+                ("summary", ps_plan_summary_t)]
+
+
+class ps_tier_choice(C.Structure):
+    _fields_ = [("tier", C.c_uint32), ("tier_tokens", C.c_uint32), ("iterations", C.c_uint32), ("pad", C.c_uint32),
+                ("est_iter_ms", C.c_double), ("est_total_ms", C.c_double)]
+
+
 class ps_stats(C.Structure):
     _fields_ = [("resident_bytes_step", C.c_uint64), ("streamed_bytes_step", C.c_uint64),
                 ("n_copies", C.c_uint32), ("n_kernels", C.c_uint32)] + \
@@ -65,7 +75,8 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
-           "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix"]
+           "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
+           "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy"]
 
 _lib = None
 
@@ -112,12 +123,16 @@ def lib():
             "ps_stack_debug_buffer": [vp, u32, C.POINTER(vp), C.POINTER(u64)],
             "ps_mfma_probe": [i32, i32, i32, vp, vp],
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
+            "ps_tier_table_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, C.POINTER(vp)],
+            "ps_tier_table_entry": [vp, u32, C.POINTER(ps_tier_entry)],
+            "ps_tier_table_plan": [vp, u32, C.POINTER(vp)],
+            "ps_tier_pick": [vp, u32, C.POINTER(ps_tier_choice)],
         }
         for name, args in sig.items():
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = args
-        for name in ("ps_plan_destroy", "ps_schedule_destroy", "ps_stack_destroy"):
+        for name in ("ps_plan_destroy", "ps_schedule_destroy", "ps_stack_destroy", "ps_tier_table_destroy"):
             f = getattr(L, name)
             f.restype = None
             f.argtypes = [vp]
@@ -244,6 +259,90 @@ def route_host(logits, top_k):
     idx = np.empty((M, top_k), dtype=np.int32)
     _check(lib().ps_route_host(_ptr(lg), M, E, top_k, _ptr(idx)))
     return idx
+
+
+class _TierPlan(Plan):
+    """A plan owned by a tier table: same queries as Plan, never destroyed from here."""
+
+    def __init__(self, table, handle):
+        self.cfg, self.desc, self.profile = table.cfg, table.desc, table.profile
+        self.h = handle
+        self._table = table   # keeps the owner alive
+
+    def close(self):
+        self.h = C.c_void_p()
+
+
+class TierTable:
+    """ps_tier_table_*: one plan per token tier under one budget, and PickTier."""
+
+    def __init__(self, cfg, budget_bytes, profile=None, expert_freq=None):
+        self.cfg = cfg
+        self.desc = model_desc(cfg)
+        self.profile = profile if profile is not None else make_profile()
+        self.h = C.c_void_p()
+        freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
+        _check(lib().ps_tier_table_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), _ptr(freq),
+                                          C.byref(self.h)))
+
+    def entry(self, tier):
+        e = ps_tier_entry()
+        _check(lib().ps_tier_table_entry(self.h, int(tier), C.byref(e)))
+        return e
+
+    def entries(self):
+        return [self.entry(t) for t in range(PS_NTIERS)]
+
+    def plan(self, tier):
+        h = C.c_void_p()
+        _check(lib().ps_tier_table_plan(self.h, int(tier), C.byref(h)))
+        return _TierPlan(self, h)
+
+    def pick(self, new_tokens):
+        c = ps_tier_choice()
+        _check(lib().ps_tier_pick(self.h, int(new_tokens), C.byref(c)))
+        return c
+
+    def close(self):
+        if self.h:
+            lib().ps_tier_table_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def chunked_forward(stack, x_in, x_out, router_logits=None):
+    """Run n = x_in.shape[0] tokens through a stack planned for T = stack.M tokens as ceil(n / T)
+    trips through its schedule (chunked prefill with the tier size as chunk size).  Only slices and
+    pads: full chunks are passed in place, the last partial chunk goes through zero-padded T-row
+    buffers.  Asynchronous on stack.compute like Stack.forward."""
+    torch = stack.torch
+    n, T = int(x_in.shape[0]), stack.M
+    assert tuple(x_in.shape) == (n, stack.H) and tuple(x_out.shape) == (n, stack.H)
+    lg = None if router_logits is None else np.ascontiguousarray(router_logits, dtype=np.float32)
+    for r0 in range(0, n, T):
+        r1 = min(r0 + T, n)
+        l = None
+        if lg is not None:
+            l = np.zeros((lg.shape[0], T, lg.shape[2]), dtype=np.float32)
+            l[:, :r1 - r0] = lg[:, r0:r1]
+        if r1 - r0 == T:
+            stack.forward(x_in[r0:r1], x_out[r0:r1], l)
+            continue
+        with torch.cuda.stream(stack.compute):
+            xi = torch.zeros((T, stack.H), dtype=torch.float16, device=stack.device)
+            xo = torch.empty_like(xi)
+            xi[:r1 - r0].copy_(x_in[r0:r1])
+        stack.forward(xi, xo, l)
+        with torch.cuda.stream(stack.compute):
+            x_out[r0:r1].copy_(xo[:r1 - r0])
+            xi.record_stream(stack.compute)
+            xo.record_stream(stack.compute)
+    return (n + T - 1) // T
 
 
 class Stack:

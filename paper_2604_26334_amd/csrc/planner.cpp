@@ -388,4 +388,59 @@ int32_t ps_plan_get_shard(const ps_plan *p, uint32_t i, ps_shard_info *o) {
 
 void ps_plan_destroy(ps_plan *p) { delete p; }
 
+int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                             const float *expert_freq, ps_tier_table **out) {
+    if (!out) { ps::set_error("out is NULL"); return PS_E_ARG; }
+    *out = nullptr;
+    ps_tier_table *tb = new (std::nothrow) ps_tier_table();
+    if (!tb) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
+    for (uint32_t t = 0; t < PS_NTIERS; ++t) {
+        ps_plan *p = new (std::nothrow) ps_plan();
+        if (!p) { delete tb; ps::set_error("out of host memory"); return PS_E_NOMEM; }
+        const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, p);
+        if (rc == PS_OK) { tb->plans[t] = p; continue; }
+        delete p;
+        if (rc != PS_E_BUDGET) { delete tb; return rc; }   // a bad model or profile fails every tier
+    }
+    *out = tb;
+    return PS_OK;
+}
+
+int32_t ps_tier_table_entry(const ps_tier_table *tb, uint32_t tier, ps_tier_entry *o) {
+    if (!tb || !o || tier >= PS_NTIERS) { ps::set_error("bad tier table argument"); return PS_E_ARG; }
+    std::memset(o, 0, sizeof *o);
+    o->tier = tier;
+    o->tier_tokens = ps::kTiers[tier];
+    o->feasible = tb->plans[tier] ? 1 : 0;
+    return o->feasible ? ps_plan_summary(tb->plans[tier], &o->summary) : PS_OK;
+}
+
+int32_t ps_tier_table_plan(const ps_tier_table *tb, uint32_t tier, const ps_plan **out) {
+    if (!tb || !out || tier >= PS_NTIERS) { ps::set_error("bad tier table argument"); return PS_E_ARG; }
+    if (!tb->plans[tier]) { ps::set_error("tier %u (%u tokens) does not fit the budget", tier, ps::kTiers[tier]); return PS_E_ARG; }
+    *out = tb->plans[tier];
+    return PS_OK;
+}
+
+int32_t ps_tier_pick(const ps_tier_table *tb, uint32_t new_tokens, ps_tier_choice *o) {
+    if (!tb || !o) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (new_tokens == 0) { ps::set_error("new_tokens is 0"); return PS_E_ARG; }
+    bool found = false;
+    double best = 0;
+    for (uint32_t t = 0; t < PS_NTIERS; ++t) {
+        if (!tb->plans[t]) continue;
+        const uint32_t iters = (new_tokens + ps::kTiers[t] - 1) / ps::kTiers[t];
+        const double total = (double)iters * tb->plans[t]->est_step_ms;
+        if (found && !(total < best)) continue;   // ties keep the lower tier
+        found = true;
+        best = total;
+        o->tier = t; o->tier_tokens = ps::kTiers[t]; o->iterations = iters; o->pad = 0;
+        o->est_iter_ms = tb->plans[t]->est_step_ms; o->est_total_ms = total;
+    }
+    if (!found) { ps::set_error("no token tier fits the budget"); return PS_E_BUDGET; }
+    return PS_OK;
+}
+
+void ps_tier_table_destroy(ps_tier_table *tb) { delete tb; }
+
 }  // extern "C"

@@ -95,6 +95,11 @@ struct ps_plan {
     double est_step_ms = 0, est_streamed_per_step = 0;
 };
 
+struct ps_tier_table {
+    ps_plan *plans[PS_NTIERS] = {};   // null: infeasible under this budget
+    ~ps_tier_table() { for (ps_plan *p : plans) delete p; }
+};
+
 struct ps_schedule {
     std::vector<ps::Op> ops;
     std::vector<ps::TaskHost> tasks;

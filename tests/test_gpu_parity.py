@@ -126,3 +126,49 @@ def test_graph_replay_matches_eager_on_every_replay():
             np.testing.assert_array_equal(y.cpu().numpy().view(np.uint16), ref)
         (torch.ones(1 << 20, device="cuda") * 2).sum().item()
     st.close()
+
+
+@pytest.mark.parametrize("kind", ["dense", "moe"])
+def test_chunked_prefill_through_the_tier_table(kind):
+    """Tier table + PickTier + chunked prefill (Section 3, inference phase): a prompt of n tokens runs
+    as ceil(n / T) trips through the schedule of the picked tier T (last trip zero-padded); every row
+    against the oracle, for the picked tier and for two forced ones."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    n = 150
+    if kind == "dense":
+        cfg, logits = Hn.small_dense_cfg(2), None
+    else:
+        cfg = Hn.small_moe_cfg(2)
+        logits = S.router_logits(3, 0, cfg["n_layers"], n, cfg["n_experts"])
+    W = Hn.WeightCache(cfg, 7)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    ws64 = B.Plan(cfg, 1 << 62, 64).summary().workspace_bytes
+    table = B.TierTable(cfg, int(wb * 0.6) + ws64)
+    choice = table.pick(n)
+    _say("picked tier", choice.tier_tokens, "x", choice.iterations, "est %.3f ms" % choice.est_total_ms)
+    x = S.activations(7, 0, n, cfg["hidden"])
+    ref = O.stack_forward(x, cfg, W, logits=logits, mirror=True)
+    tiers = sorted({choice.tier, 2, 4})            # picked, 16 and 64 tokens per trip
+    streamed = []
+    for t in tiers:
+        e = table.entry(t)
+        assert e.feasible
+        streamed.append(e.summary.streamed_bytes)
+        st = B.Stack(table.plan(t))
+        for layer in range(cfg["n_layers"]):
+            for k, ex, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, ex, *W(layer, k, ex))
+        xin = torch.from_numpy(x).cuda()
+        xout = torch.zeros_like(xin)
+        torch.cuda.synchronize()
+        trips = B.chunked_forward(st, xin, xout, logits)
+        st.synchronize()
+        assert trips == -(-n // e.tier_tokens)
+        got = xout.cpu().numpy()
+        err = Hn.rel_err(got, ref)
+        _say("tier", e.tier_tokens, "trips", trips, "rel err %.2e" % err)
+        assert np.isfinite(got).all() and err <= TOL
+        st.close()
+    # the larger tier's workspace displaces pinned shards, the smaller tier pins more (or all)
+    assert streamed[-1] > 0 and streamed == sorted(streamed)

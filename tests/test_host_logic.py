@@ -272,3 +272,56 @@ def test_route_host_matches_sort_rule():
     idx = B.route_host(lg, 8)
     for m in range(9):
         assert list(idx[m]) == sorted(range(128), key=lambda e: (-float(lg[m, e]), e))[:8]
+
+
+# ------------------------------------------------------------------ token-tier table, PickTier
+
+def test_tier_table_plans_every_tier_and_smaller_tiers_pin_more():
+    cfg = S.cfg_dense8b(32)
+    tb = B.TierTable(cfg, int(2e9))
+    ents = tb.entries()
+    assert [e.tier_tokens for e in ents] == [B.lib().ps_tier_tokens(t) for t in range(B.PS_NTIERS)]
+    assert all(e.feasible for e in ents)
+    for e in ents:
+        assert e.summary.n_tokens == e.tier_tokens and e.summary.budget_bytes == int(2e9)
+        one = B.Plan(cfg, int(2e9), e.tier_tokens).summary()     # same as planning that tier alone
+        assert (one.resident_bytes, one.workspace_bytes, one.est_step_ms) == \
+               (e.summary.resident_bytes, e.summary.workspace_bytes, e.summary.est_step_ms)
+    res = [e.summary.resident_bytes for e in ents]
+    assert all(a >= b for a, b in zip(res, res[1:])) and res[0] > res[-1]   # Section 3: lower tiers pin more
+    p = tb.plan(5)
+    assert p.summary().n_tokens == 512 and len(p.shards()) == ents[5].summary.n_shards
+
+
+def test_tier_table_marks_tiers_that_do_not_fit():
+    cfg = S.cfg_dense8b(32)
+    tb = B.TierTable(cfg, int(3e8))
+    feas = [e.feasible for e in tb.entries()]
+    assert feas[0] == 1 and feas[-1] == 0 and feas == sorted(feas, reverse=True)
+    with pytest.raises(B.PshardError):
+        tb.plan(B.PS_NTIERS - 1)
+    c = tb.pick(16384)          # must fall back to a feasible tier and iterate
+    assert tb.entry(c.tier).feasible and c.iterations == -(-16384 // c.tier_tokens)
+    none = B.TierTable(cfg, 1000)
+    assert not any(e.feasible for e in none.entries())
+    with pytest.raises(B.PshardError) as ei:
+        none.pick(1)
+    assert ei.value.code == B.PS_E_BUDGET
+    with pytest.raises(B.PshardError):
+        tb.pick(0)
+
+
+def test_pick_tier_matches_the_definition():
+    from oracle import oracle as O
+    rng = np.random.default_rng(5)
+    for cfg, budgets in ((S.cfg_dense8b(32), (3e8, 2e9, 4e9)), (S.cfg_moe(4), (3e8, 2e9))):
+        for budget in budgets:
+            for gemm in (50.0, 400.0, 1000.0):
+                tb = B.TierTable(cfg, int(budget), profile=B.make_profile(gemm_tflops=gemm))
+                est = [e.summary.est_step_ms if e.feasible else None for e in tb.entries()]
+                for n in [1, 2, 4, 5, 63, 64, 65, 100, 512, 2048, 3000, 16384, 50000] + list(rng.integers(1, 40000, 20)):
+                    c = tb.pick(int(n))
+                    t, iters, total = O.pick_tier(est, int(n))
+                    assert (c.tier, c.iterations) == (t, iters), (budget, gemm, n)
+                    assert c.tier_tokens == O.TIER_TOKENS[t] and c.est_iter_ms == est[t]
+                    assert c.est_total_ms == pytest.approx(total, rel=1e-12)

@@ -5,6 +5,7 @@ term, a wrong sign/index or a transposed operand fails at least one of them.
 (The paper prints no numeric tensor example, so there is no printed-value pin.)
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -314,3 +315,52 @@ def test_moe_layer_matches_python_composition():
             u = n[m] @ _numpy_dequant(experts[e][1]).T
             ref[m] += w[j] * ((g / (1 + np.exp(-g)) * u) @ _numpy_dequant(experts[e][2]).T)
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-10)
+
+
+# ------------------------------------------------------------------ PickTier
+
+def _golden_pick_cases():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "pick_tier_example.txt")
+    est, cases = None, []
+    for ln in open(path).read().splitlines():
+        f = ln.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "est":
+            est = [float(v) for v in f[1:]]
+        elif f[0] == "case":
+            cases.append((int(f[1]), int(f[2]), int(f[3]), float(f[4])))
+    return est, cases
+
+
+def test_pick_tier_hand_worked_example():
+    est, cases = _golden_pick_cases()
+    assert len(est) == len(O.TIER_TOKENS) and len(cases) >= 6
+    for tokens, want_tok, want_iters, want_ms in cases:
+        t, iters, total = O.pick_tier(est, tokens)
+        assert (O.TIER_TOKENS[t], iters, total) == (want_tok, want_iters, want_ms), tokens
+
+
+def test_pick_tier_closed_forms_and_ties():
+    J = O.TIER_TOKENS
+    # the same time for every tier: only the trip count matters -> the smallest tier that holds
+    # all tokens in one trip (ties go to the lowest tier); beyond the largest tier, the largest
+    for n in (1, 2, 4, 5, 17, 64, 65, 513, 16384):
+        t, iters, total = O.pick_tier([5.0] * len(J), n)
+        assert J[t] == min(T for T in J if T >= n) and iters == 1 and total == 5.0
+    t, iters, _ = O.pick_tier([5.0] * len(J), 16385)
+    assert (J[t], iters) == (16384, 2)
+    # time exactly proportional to the tier size: total = a * (tokens padded up to a multiple of the
+    # tier) >= a * tokens, with equality for every tier that divides the token count -> tier 1
+    for n in (1, 7, 64, 100, 4096):
+        t, iters, total = O.pick_tier([0.25 * T for T in J], n)
+        assert (J[t], iters, total) == (1, n, 0.25 * n)
+    # a fixed cost per trip on top makes the lowest-padding LARGE tier win: tokens = 1024 exactly
+    t, iters, total = O.pick_tier([10.0 + 0.25 * T for T in J], 1024)
+    assert (J[t], iters, total) == (1024, 1, 266.0)
+    # tiers without a schedule are skipped; none at all is an error
+    est = [None] * len(J)
+    est[3], est[6] = 1.0, 20.0
+    assert O.pick_tier(est, 40)[:2] == (3, 2) and O.pick_tier(est, 4000)[:2] == (6, 4)
+    with pytest.raises(ValueError):
+        O.pick_tier([None] * len(J), 5)
