@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <cstdlib>
 
 #include "kernels.h"
@@ -679,9 +680,12 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // the 4c + kk order costs 1.5x the LDS cycles of this one)
 __device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) | (u >> 2); }
 
+// super-blocks of lookahead of the GEMM's prefetch ring (see the kernel): 2 for the few-token tiles
+constexpr int gemm_depth(int MT) { return MT <= 64 ? 2 : 1; }
+
 template <int MODE, int AT, int MT, bool GROUPED>
-__global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmArgs a) {
-    extern __shared__ uint4 lds[];                 // two stages of MT x 16 chunks
+__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
+    extern __shared__ uint4 lds[];                 // gemm_depth(MT) + 1 stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
     constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -735,8 +739,17 @@ __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmAr
 #pragma unroll
         for (int n = 0; n < NMT; ++n) acc[t][n] = f4_t{0.f, 0.f, 0.f, 0.f};
 
-    uint4 wq[AT], wn[AT];
-    uint32_t dq[AT], dn[AT];   // this / next super-block's scale of the lane's block (fp16 bits)
+    // Prefetch ring: DEPTH super-blocks are in flight ahead of the one being multiplied, in R =
+    // DEPTH + 1 weight register sets and LDS stages.  With few tokens an iteration is shorter than
+    // the memory latency, so one super-block of lookahead leaves the loop waiting on its loads.
+    constexpr int DEPTH = gemm_depth(MT), R = DEPTH + 1;
+    constexpr int LPI = NFILL + 2 * AT;          // loads one prefetch issues per lane
+    // one super-block of weights of the wave's tiles: the lane's 16 code bytes, and the dword that
+    // holds its block's fp16 scale (sh = 0 / 16: which half; the same for the whole workgroup).  The
+    // scale is fetched as a whole dword so that no 16-bit zero-extension is applied to the load's
+    // result the moment it is issued (which would wait for it there).
+    struct Wset { uint4 q[AT]; uint32_t d[AT]; uint32_t sh; };
+    Wset wr[R];
     auto fill_x = [&](uint32_t sb, uint32_t stage) {
         const uint32_t xs = gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half);
 #pragma unroll
@@ -744,25 +757,40 @@ __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmAr
             load_to_lds16(xbuf, (lds_void *)(lds + stage * (MT * 16) + r * 256 + wave_u * 64), xoff[r], xs);
     };
 
-    // scale group / slot of super-block sb, clamped to the last one (the prefetch past the end
+    // scale group / slot of super-block sb, clamped to the last one (a prefetch past the end
     // re-reads the last super-block instead of branching; nothing consumes it)
-    auto load_w = [&](uint32_t sbn) {
+    auto load_w = [&](uint32_t sbn, Wset &w) {
         sbn = min(sbn, a.nsb - 1);
         const uint32_t gn = sbn >> 3, sn = sbn & 7;
         const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
         const uint32_t gb = gn * (9 * 1024);
+        w.sh = (sn & 1) * 16;
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
-            wn[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, woff[t], gb + sn * 1024, kAuxNt));
-            dn[t] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, woff[t], gb + nsb_n * 1024 + sn * 2, 0);
+            w.q[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, woff[t], gb + sn * 1024, kAuxNt));
+            w.d[t] = __builtin_amdgcn_raw_buffer_load_b32(wbuf, woff[t], gb + nsb_n * 1024 + (sn >> 1) * 4, 0);
+        }
+    };
+    // prefetched weights become visible to the compiler only where this is called, so nothing
+    // derived from them is scheduled (and waited for) earlier
+    auto arrive_w = [&](Wset &w) {
+#pragma unroll
+        for (int t = 0; t < AT; ++t) {
+            uint4 q;
+            uint32_t d;
+            asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8\n\tv_mov_b32 %4, %9"
+                         : "=&v"(q.x), "=&v"(q.y), "=&v"(q.z), "=&v"(q.w), "=&v"(d)
+                         : "v"(w.q[t].x), "v"(w.q[t].y), "v"(w.q[t].z), "v"(w.q[t].w), "v"(w.d[t]));
+            w.q[t] = q;
+            w.d[t] = d;
         }
     };
     // A operands of MFMA step kk from raw dwords + scale: (q - 8) * d rounded to fp16
-    auto dequant_a = [&](h8_t (&A)[AT], const uint4 (&w4)[AT], const uint32_t (&ds)[AT], int kk) {
+    auto dequant_a = [&](h8_t (&A)[AT], const Wset &ws, int kk) {
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
-            const uint32_t q = kk == 0 ? w4[t].x : kk == 1 ? w4[t].y : kk == 2 ? w4[t].z : w4[t].w;
-            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)ds[t]);
+            const uint32_t q = kk == 0 ? ws.q[t].x : kk == 1 ? ws.q[t].y : kk == 2 ? ws.q[t].z : ws.q[t].w;
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(ws.d[t] >> ws.sh));
             const h2_t dd = {d, d};
             h2_t w[4];
             dequant8(q, w);
@@ -777,27 +805,31 @@ __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmAr
         sb_begin = blockIdx.z * a.sb_per_part;
         sb_end = min(a.nsb, sb_begin + a.sb_per_part);
     }
-    fill_x(sb_begin, 0);
-    load_w(sb_begin);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        fill_x(min(sb_begin + d, sb_end - 1), d);
+        load_w(sb_begin + d, wr[d]);
+    }
     // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
     // (one more operand set in registers; the 4-tile shape has no room for it)
     constexpr bool PIPE = (AT <= 2);
     h8_t Acur[AT], Anxt[AT];
-    if (PIPE) dequant_a(Acur, wn, dn, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS fill has landed
-    __syncthreads();
+    arrive_w(wr[0]);
+    if (PIPE) dequant_a(Acur, wr[0], 0);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LPI) : "memory");   // the first LDS fill has landed
+    __builtin_amdgcn_s_barrier();
 
-    for (uint32_t sb = sb_begin; sb < sb_end; ++sb) {
-        const uint32_t stage = (sb - sb_begin) & 1;
-#pragma unroll
-        for (int t = 0; t < AT; ++t) { wq[t] = wn[t]; dq[t] = dn[t]; }
-        const uint32_t sbn = min(sb + 1, sb_end - 1);
-        // prefetch the next super-block: activations into the other stage (every wave left it at
-        // the barrier that ended the previous iteration), then the weights
-        fill_x(sbn, stage ^ 1);
-        load_w(sb + 1);
+    // one super-block: U = its position in the ring (compile-time, so every register set and LDS
+    // stage below is addressed statically and nothing is copied when the ring turns)
+    auto step = [&](uint32_t sb, auto U) {
+        constexpr int u = decltype(U)::value;
+        constexpr int un = (u + 1) % R, up = (u + DEPTH) % R;   // next super-block's slot, the slot to refill
+        // prefetch super-block sb + DEPTH: activations into the stage every wave left at the
+        // barrier that ended the previous step, weights into the register set used then
+        fill_x(min(sb + DEPTH, sb_end - 1), up);
+        load_w(sb + DEPTH, wr[up]);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
-        const uint4 *ls = lds + stage * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
+        const uint4 *ls = lds + u * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
         // B operands are read one MFMA step ahead, so the LDS latency hides behind a step's MFMAs
         h8_t Bc[NMT], Bn[NMT];
 #pragma unroll
@@ -809,22 +841,11 @@ __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmAr
                 for (int n = 0; n < NMT; ++n) Bn[n] = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + (kk + 1) * 4) ^ i)]);
                 __builtin_amdgcn_sched_barrier(0);   // or the scheduler sinks each read next to its MFMA
             }
-            if (!PIPE) dequant_a(Acur, wq, dq, kk);
-            else if (kk < 3) dequant_a(Anxt, wq, dq, kk + 1);
+            if (!PIPE) dequant_a(Acur, wr[u], kk);
+            else if (kk < 3) dequant_a(Anxt, wr[u], kk + 1);
             else {
-                // the prefetched weights become visible to the compiler only here, so nothing derived
-                // from them is scheduled (and waited for) earlier in the iteration
-#pragma unroll
-                for (int t = 0; t < AT; ++t) {
-                    uint4 w;
-                    uint32_t d;
-                    asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8\n\tv_mov_b32 %4, %9"
-                                 : "=&v"(w.x), "=&v"(w.y), "=&v"(w.z), "=&v"(w.w), "=&v"(d)
-                                 : "v"(wn[t].x), "v"(wn[t].y), "v"(wn[t].z), "v"(wn[t].w), "v"(dn[t]));
-                    wn[t] = w;
-                    dn[t] = d;
-                }
-                dequant_a(Anxt, wn, dn, 0);
+                arrive_w(wr[un]);
+                dequant_a(Anxt, wr[un], 0);
             }
 #pragma unroll
             for (int n = 0; n < NMT; ++n) {
@@ -841,8 +862,25 @@ __global__ __launch_bounds__(256, (MT <= 64 ? 4 : 2)) void gemm_w4_kernel(GemmAr
                 for (int n = 0; n < NMT; ++n) Bc[n] = Bn[n];
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        // super-block sb + 1's activations have landed once all but the later prefetches are done.
+        // A bare barrier: __syncthreads() carries a fence that makes the compiler wait for EVERY
+        // LDS-direct load in flight, i.e. also for the deeper prefetches.  What must be ordered
+        // here is ordered by hand: this wave's fill of the next stage is complete (vmcnt), and
+        // its LDS reads of the current stage were consumed by the MFMAs above.
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LPI) : "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+    // whole turns of the ring, then the remaining steps (no exit from inside a turn: the ring is back
+    // in phase at the loop's back edge, so no register set is live across it in another slot)
+    uint32_t sb = sb_begin;
+    for (; sb + R <= sb_end; sb += R) {
+        step(sb, std::integral_constant<int, 0>{});
+        step(sb + 1, std::integral_constant<int, 1>{});
+        if constexpr (R > 2) step(sb + 2, std::integral_constant<int, 2>{});
+    }
+    if (sb < sb_end) step(sb, std::integral_constant<int, 0>{});
+    if constexpr (R > 2) {
+        if (sb + 1 < sb_end) step(sb + 1, std::integral_constant<int, 1>{});
     }
 
     // epilogue: lane holds token j = lane & 15 of each token tile and rows 4*(lane >> 4) + r
@@ -904,7 +942,7 @@ template <int MODE, int AT, int MT>
 static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
     const uint32_t parts = (!ntasks && a.sb_per_part) ? (a.nsb + a.sb_per_part - 1) / a.sb_per_part : 1;
     dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : parts);
-    const size_t lds = (size_t)MT * 256 * 2;
+    const size_t lds = (size_t)MT * 256 * (gemm_depth(MT) + 1);
     if (ntasks) hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, true>), grid, dim3(256), lds, st, a);
     else hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
