@@ -123,6 +123,36 @@ def attn_half(x, cfg, qkv, o, mirror):
     return h
 
 
+def attn_decode(q, K, V, n_q, n_kv, hd):
+    """Softmax attention of one token: q [n_q*hd], K, V [n_kv][T][hd] -> A [n_q*hd] (fp64)."""
+    q, K, V = _f64(q).reshape(-1), _f64(K), _f64(V)
+    T = K.shape[1]
+    assert K.shape == (n_kv, T, hd) and V.shape == K.shape and q.size == n_q * hd
+    A = np.empty(n_q * hd, dtype=np.float64)
+    lib().orc_attn_decode(_p(q), _p(K), _p(V), C.c_int64(T), n_q, n_kv, hd, _p(A))
+    return A
+
+
+def attn_kv_half(x, cfg, qkv, o, Kc, Vc, ctx, mirror):
+    """Attention half at one new token with ctx cached positions.  Kc, Vc: float16 [n_kv][cap][hd];
+    row ctx of every head is left as it was (the new rows are returned, as stored, in k_new, v_new)."""
+    x = _f64(x)
+    assert x.shape[0] == 1
+    H = x.shape[1]
+    n_q, n_kv, hd = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    (qs, qc), (os_, oc) = _sc(*qkv), _sc(*o)
+    Kb = np.ascontiguousarray(Kc, dtype=np.float16).view(np.uint16)
+    Vb = np.ascontiguousarray(Vc, dtype=np.float16).view(np.uint16)
+    cap = Kb.shape[1]
+    assert Kb.shape == (n_kv, cap, hd) and Vb.shape == Kb.shape and 0 <= ctx < cap
+    h = np.empty_like(x)
+    k_new = np.empty((n_kv, hd), dtype=np.float64)
+    v_new = np.empty((n_kv, hd), dtype=np.float64)
+    lib().orc_attn_kv_half(_p(x), H, n_q, n_kv, hd, C.c_double(cfg["rms_eps"]), _p(qs), _p(qc), _p(os_), _p(oc),
+                           _p(Kb), _p(Vb), C.c_int64(cap), C.c_int64(ctx), int(mirror), _p(k_new), _p(v_new), _p(h))
+    return h, k_new, v_new
+
+
 def dense_ffn_half(h, cfg, gate, up, down, mirror):
     h = _f64(h)
     M, H = h.shape
@@ -157,17 +187,25 @@ def moe_ffn_half(h, cfg, logits, experts, mirror):
     return out
 
 
-def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None):
+def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None, kv=None, ctx=0, new_rows=None):
     """Run the whole decoder weight stack on x [M][H].
 
     weights(layer, kind, expert) -> (scales, codes) for one logical matrix (called
     on demand so the full model never has to be resident).  logits: fp32 [L][M][E]
     for MoE stacks.  per_layer, if a list, receives each layer's output.
+    kv: None (attention = identity on V) or kv(layer) -> (K, V) float16 [n_kv][cap][hd] caches holding
+    ctx earlier positions: one new token attends over them and itself; new_rows, if a list, receives
+    each layer's (k_new, v_new).
     """
     x = _f64(x)
     for l in range(cfg["n_layers"]):
         h = x
-        if not cfg["no_attn"]:
+        if not cfg["no_attn"] and kv is not None:
+            Kc, Vc = kv(l)
+            h, kn, vn = attn_kv_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), Kc, Vc, ctx, mirror)
+            if new_rows is not None:
+                new_rows.append((kn, vn))
+        elif not cfg["no_attn"]:
             h = attn_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), mirror)
         if cfg["n_experts"] == 0:
             x = dense_ffn_half(h, cfg, weights(l, MAT_GATE, None), weights(l, MAT_UP, None),

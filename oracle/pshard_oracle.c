@@ -162,6 +162,76 @@ void orc_attn_half(const double *x, int64_t M, int H, int n_q, int n_kv, int hd,
     free(n); free(qkv); free(A);
 }
 
+/* ---- decode attention over a KV cache (one new token) -----------------------
+ * q [n_q][hd]; K, V [n_kv][T][hd] hold T positions (the cache plus the new token's own row, last).
+ * Head h attends with kv head floor(h / (n_q / n_kv)): scores s_j = (q_h . K_j) / sqrt(hd),
+ * p = softmax(s) over the T positions, A_h = sum_j p_j V_j.  Plain definition, fp64, the usual
+ * max subtraction so exp cannot overflow.  No positional encoding is applied. */
+
+void orc_attn_decode(const double *q, const double *K, const double *V, int64_t T,
+                     int n_q, int n_kv, int hd, double *A) {
+    int group = n_q / n_kv;
+    double *s = (double *)malloc(sizeof(double) * (size_t)T);
+    for (int h = 0; h < n_q; ++h) {
+        const double *Kg = K + (int64_t)(h / group) * T * hd, *Vg = V + (int64_t)(h / group) * T * hd;
+        double mx = -INFINITY, den = 0.0;
+        for (int64_t j = 0; j < T; ++j) {
+            double d = 0.0;
+            for (int e = 0; e < hd; ++e) d += q[(int64_t)h * hd + e] * Kg[j * hd + e];
+            s[j] = d / sqrt((double)hd);
+            if (s[j] > mx) mx = s[j];
+        }
+        for (int64_t j = 0; j < T; ++j) { s[j] = exp(s[j] - mx); den += s[j]; }
+        for (int e = 0; e < hd; ++e) {
+            double o = 0.0;
+            for (int64_t j = 0; j < T; ++j) o += s[j] / den * Vg[j * hd + e];
+            A[(int64_t)h * hd + e] = o;
+        }
+    }
+    free(s);
+}
+
+/* attention half of a decoder layer at one new token with a KV cache of C earlier positions:
+ * qkv = Linear_QKV(RMSNorm(x)); the token's own K and V rows (as stored: fp16 when mirror) join the
+ * cache as position C; h = x + Linear_O(Attention(q, K[0..C], V[0..C])).
+ * Kc, Vc: fp16 bit patterns [n_kv][cap][hd], cap > C; row C of every head is written. */
+
+void orc_attn_kv_half(const double *x, int H, int n_q, int n_kv, int hd, double eps,
+                      const uint16_t *qkv_s, const uint8_t *qkv_c,
+                      const uint16_t *o_s, const uint8_t *o_c,
+                      uint16_t *Kc, uint16_t *Vc, int64_t cap, int64_t C, int mirror,
+                      double *k_new, double *v_new, double *h) {
+    int64_t qkv_w = (int64_t)(n_q + 2 * n_kv) * hd, a_w = (int64_t)n_q * hd, T = C + 1;
+    double *n = (double *)malloc(sizeof(double) * (size_t)H);
+    double *qkv = (double *)malloc(sizeof(double) * (size_t)qkv_w);
+    double *A = (double *)malloc(sizeof(double) * (size_t)a_w);
+    double *K = (double *)malloc(sizeof(double) * (size_t)(n_kv * T * hd));
+    double *V = (double *)malloc(sizeof(double) * (size_t)(n_kv * T * hd));
+    orc_rmsnorm(x, 1, H, eps, n);
+    orc_linear(n, 1, qkv_s, qkv_c, qkv_w, H, qkv);
+    round_all(qkv, qkv_w, mirror);
+    for (int g = 0; g < n_kv; ++g) {
+        for (int64_t j = 0; j < C; ++j)
+            for (int e = 0; e < hd; ++e) {
+                K[((int64_t)g * T + j) * hd + e] = orc_half_to_double(Kc[((int64_t)g * cap + j) * hd + e]);
+                V[((int64_t)g * T + j) * hd + e] = orc_half_to_double(Vc[((int64_t)g * cap + j) * hd + e]);
+            }
+        for (int e = 0; e < hd; ++e) {
+            double kn = qkv[(int64_t)(n_q + g) * hd + e], vn = qkv[(int64_t)(n_q + n_kv + g) * hd + e];
+            K[((int64_t)g * T + C) * hd + e] = kn;
+            V[((int64_t)g * T + C) * hd + e] = vn;
+            k_new[(int64_t)g * hd + e] = kn;
+            v_new[(int64_t)g * hd + e] = vn;
+        }
+    }
+    orc_attn_decode(qkv, K, V, T, n_q, n_kv, hd, A);
+    round_all(A, a_w, mirror);
+    orc_linear(A, 1, o_s, o_c, H, a_w, h);
+    for (int64_t i = 0; i < H; ++i) h[i] += x[i];
+    round_all(h, H, mirror);
+    free(n); free(qkv); free(A); free(K); free(V);
+}
+
 /* ---- one gated FFN on already-normalised input n [M][H] --------------------
  * y = Linear_down(SwiGLU(Linear_gate(n), Linear_up(n))), y [M][H] not rounded */
 

@@ -364,3 +364,85 @@ def test_pick_tier_closed_forms_and_ties():
     assert O.pick_tier(est, 40)[:2] == (3, 2) and O.pick_tier(est, 4000)[:2] == (6, 4)
     with pytest.raises(ValueError):
         O.pick_tier([None] * len(J), 5)
+
+
+# ------------------------------------------------------------------ decode attention over a KV cache
+
+def test_attn_decode_closed_forms():
+    rng = np.random.default_rng(11)
+    n_q, n_kv, hd, T = 4, 2, 128, 9
+    q = rng.standard_normal(n_q * hd)
+    K = rng.standard_normal((n_kv, T, hd))
+    V = rng.standard_normal((n_kv, T, hd))
+    # a single position: weight 1 -> the value row of the head's kv head (the identity-on-V stand-in)
+    A1 = O.attn_decode(q, K[:, :1], V[:, :1], n_q, n_kv, hd)
+    qkv = np.concatenate([q, K[:, 0].reshape(-1), V[:, 0].reshape(-1)])[None, :]
+    np.testing.assert_array_equal(A1, O.attn_identity_v(qkv, n_q, n_kv, hd)[0])
+    # equal keys: every score equal -> uniform weights -> the mean of the values
+    Ke = np.repeat(K[:, :1], T, axis=1)
+    Au = O.attn_decode(q, Ke, V, n_q, n_kv, hd).reshape(n_q, hd)
+    for h in range(n_q):
+        np.testing.assert_allclose(Au[h], V[h // 2].mean(axis=0), rtol=0, atol=1e-12)
+    # one key aligned with a huge query: its weight -> 1 (the others underflow to 0 exactly)
+    qb = np.zeros((n_q, hd)); qb[:, 0] = 1e4
+    Kb = np.zeros((n_kv, T, hd)); Kb[:, 5, 0] = 1.0
+    Ab = O.attn_decode(qb, Kb, V, n_q, n_kv, hd).reshape(n_q, hd)
+    for h in range(n_q):
+        np.testing.assert_array_equal(Ab[h], V[h // 2, 5])
+    # scaling by 1/sqrt(hd): with hd-dimensional unit keys e_0 and q = sqrt(hd) * ln(3) * e_0 against a zero
+    # key, the weights are 3/4 and 1/4
+    K2 = np.zeros((n_kv, 2, hd)); K2[:, 0, 0] = 1.0
+    q2 = np.zeros((n_q, hd)); q2[:, 0] = math.sqrt(hd) * math.log(3.0)
+    A2 = O.attn_decode(q2, K2, V[:, :2], n_q, n_kv, hd).reshape(n_q, hd)
+    for h in range(n_q):
+        np.testing.assert_allclose(A2[h], 0.75 * V[h // 2, 0] + 0.25 * V[h // 2, 1], rtol=1e-13, atol=1e-13)
+
+
+def test_attn_decode_vs_scipy_softmax_and_invariances():
+    from scipy.special import softmax
+    rng = np.random.default_rng(12)
+    for n_q, n_kv, hd, T in ((4, 2, 128, 37), (8, 1, 128, 5), (2, 2, 128, 64)):
+        q = rng.standard_normal(n_q * hd)
+        K = rng.standard_normal((n_kv, T, hd))
+        V = rng.standard_normal((n_kv, T, hd))
+        A = O.attn_decode(q, K, V, n_q, n_kv, hd).reshape(n_q, hd)
+        g = n_q // n_kv
+        for h in range(n_q):
+            p = softmax(K[h // g] @ q.reshape(n_q, hd)[h] / math.sqrt(hd))
+            np.testing.assert_allclose(A[h], p @ V[h // g], rtol=1e-12, atol=1e-13)
+        perm = rng.permutation(T)       # attention does not depend on the order of the positions
+        np.testing.assert_allclose(O.attn_decode(q, K[:, perm], V[:, perm], n_q, n_kv, hd).reshape(n_q, hd), A,
+                                   rtol=1e-12, atol=1e-13)
+        Vs = V + 2.5                    # weights sum to 1: shifting every value shifts the output
+        np.testing.assert_allclose(O.attn_decode(q, K, Vs, n_q, n_kv, hd).reshape(n_q, hd), A + 2.5, rtol=1e-12, atol=1e-12)
+
+
+def test_attn_kv_half_composition_and_empty_cache():
+    cfg = dict(n_layers=1, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_inter=256, n_experts=0,
+               top_k=0, expert_inter=0, rms_eps=1e-6, no_attn=False, no_residual=False)
+    H, n_q, n_kv, hd = 256, 4, 2, 128
+    qkv = S.weight_matrix(3, 0, S.MAT_QKV, None, (n_q + 2 * n_kv) * hd, H)
+    o = S.weight_matrix(3, 0, S.MAT_O, None, H, n_q * hd)
+    x = S.activations(3, 0, 1, H)
+    rng = np.random.default_rng(13)
+    cap, ctx = 12, 7
+    Kc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    Vc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    # empty cache: the token attends to itself only -> identical to the identity-on-V half
+    for mirror in (False, True):
+        h0, _, _ = O.attn_kv_half(x, cfg, qkv, o, Kc, Vc, 0, mirror)
+        np.testing.assert_array_equal(h0, O.attn_half(x, cfg, qkv, o, mirror))
+    # ctx positions: the composition of the separately pinned pieces
+    h, kn, vn = O.attn_kv_half(x, cfg, qkv, o, Kc, Vc, ctx, False)
+    y = O.linear(O.rmsnorm(x, cfg["rms_eps"]), *qkv)[0]
+    np.testing.assert_array_equal(kn.reshape(-1), y[n_q * hd:(n_q + n_kv) * hd])
+    np.testing.assert_array_equal(vn.reshape(-1), y[(n_q + n_kv) * hd:])
+    K = np.concatenate([Kc[:, :ctx].astype(np.float64), kn[:, None, :]], axis=1)
+    V = np.concatenate([Vc[:, :ctx].astype(np.float64), vn[:, None, :]], axis=1)
+    A = O.attn_decode(y[:n_q * hd], K, V, n_q, n_kv, hd)
+    np.testing.assert_allclose(h[0], x[0].astype(np.float64) + O.linear(A[None, :], *o)[0], rtol=1e-13, atol=1e-13)
+    # rows at and beyond ctx are never read
+    Kd, Vd = Kc.copy(), Vc.copy()
+    Kd[:, ctx:] = 9.0; Vd[:, ctx:] = -9.0
+    h2, _, _ = O.attn_kv_half(x, cfg, qkv, o, Kd, Vd, ctx, False)
+    np.testing.assert_array_equal(h2, h)
