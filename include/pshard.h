@@ -58,6 +58,7 @@ extern "C" {
 #define PS_SHARD_GATE_UP 2
 #define PS_SHARD_DOWN 3
 #define PS_SHARD_EXPERT 4
+#define PS_SHARD_KV 5 /* K and V cache of one kv head of one layer (field `expert` = kv head) */
 
 /* priority classes, in the paper's order (Section 3, planning phase):
  * attention, KV cache, FFN, outputs.  This build has no KV cache or output
@@ -86,6 +87,9 @@ typedef struct ps_model_desc {
     uint32_t expert_inter; /* per-expert FFN width                               */
     uint32_t flags;        /* PS_FLAG_*                                          */
     float rms_eps;
+    uint32_t kv_context;   /* 0: attention is the identity on V (no cache).  > 0: decode attention over
+                              a KV cache with room for kv_context positions per kv head (one new
+                              token per forward; plans for more than one token are rejected)        */
 } ps_model_desc;
 
 /* measured (ps_profile_measure) or caller-supplied machine profile; the
@@ -152,6 +156,8 @@ typedef struct ps_stats {
 #define PS_K_EXPERT_GATE_UP 6
 #define PS_K_EXPERT_DOWN 7
 #define PS_K_COMBINE 8
+#define PS_K_ATTN 9          /* decode attention over a run of kv-head cache shards          */
+#define PS_K_ATTN_COMBINE 10 /* merge the position chunks, add the new token, append its rows */
 #define PS_OPF_WAIT_SLOT_FREE 1u  /* copy stream waits for slot_free[slot]        */
 #define PS_OPF_WAIT_ROUTER 2u     /* copy stream waits for router_done[layer]     */
 #define PS_OPF_RECORD_READY 4u    /* copy stream records slot_ready[slot] after   */
@@ -277,6 +283,17 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
  * (synchronous), streamed slabs into the pinned pool.  expert: id or 0xFFFFFFFF. */
 int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_t expert,
                              const uint16_t *scales, const uint8_t *codes);
+/* KV cache (priority class "KV cache", Section 3 planning phase; only with kv_context > 0).
+ * ps_stack_load_kv fills positions [0, n_pos) of one kv head of one layer from host fp16
+ * K, V [n_pos][head_dim] (copied; synchronous) into that shard's home: the arena if the plan pinned
+ * it, the pinned host pool otherwise.  ps_stack_set_context sets how many cached positions the next
+ * forward attends over (context < kv_context); that forward appends the new token's K and V rows at
+ * position `context` of every head's home, so consecutive decode steps pass context, context + 1, ...
+ * Attention (no positional encoding): scores q.K_j / sqrt(head_dim) over the cached positions and the
+ * token itself, softmax, weighted sum of V; query head h uses kv head h / (n_q / n_kv). */
+int32_t ps_stack_load_kv(ps_stack *st, uint32_t layer, uint32_t kv_head, const uint16_t *k_rows,
+                         const uint16_t *v_rows, uint32_t n_pos);
+int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
 /* One pass over the whole stack (Algorithm 1, RunInTopologicalOrder).
  *  x_in, x_out: device fp16 [n_tokens][hidden], caller-owned, may not alias.
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.

@@ -13,13 +13,13 @@ LIB_PATH = os.environ.get("PS_LIB", os.path.join(_HERE, "libpshard.so"))
 
 PS_OK, PS_E_ARG, PS_E_BUDGET, PS_E_HIP, PS_E_STATE, PS_E_NOMEM = 0, -1, -2, -3, -4, -5
 PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN = 0, 1, 2, 3, 4
-PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT = 0, 1, 2, 3, 4
+PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT, PS_SHARD_KV = 0, 1, 2, 3, 4, 5
 PS_CLASS_ATTN, PS_CLASS_KVCACHE, PS_CLASS_FFN, PS_CLASS_OUTS = 0, 1, 2, 3
 PS_FLAG_NO_ATTN, PS_FLAG_NO_RESIDUAL = 1, 2
 PS_NTIERS = 11
 PS_OP_COPY, PS_OP_KERNEL = 0, 1
 (PS_K_RINV, PS_K_QKV, PS_K_O, PS_K_GATE_UP, PS_K_DOWN, PS_K_ROUTE, PS_K_EXPERT_GATE_UP,
- PS_K_EXPERT_DOWN, PS_K_COMBINE) = range(9)
+ PS_K_EXPERT_DOWN, PS_K_COMBINE, PS_K_ATTN, PS_K_ATTN_COMBINE) = range(11)
 (PS_OPF_WAIT_SLOT_FREE, PS_OPF_WAIT_ROUTER, PS_OPF_RECORD_READY, PS_OPF_WAIT_READY,
  PS_OPF_RECORD_FREE, PS_OPF_RECORD_ROUTER) = 1, 2, 4, 8, 16, 32
 NO_EXPERT = 0xFFFFFFFF
@@ -28,7 +28,7 @@ NO_EXPERT = 0xFFFFFFFF
 class ps_model_desc(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
                                           "ffn_inter", "n_experts", "top_k", "expert_inter", "flags")] + \
-               [("rms_eps", C.c_float)]
+               [("rms_eps", C.c_float), ("kv_context", C.c_uint32)]
 
 
 class ps_profile(C.Structure):
@@ -76,7 +76,7 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
-           "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy"]
+           "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context"]
 
 _lib = None
 
@@ -127,6 +127,8 @@ def lib():
             "ps_tier_table_entry": [vp, u32, C.POINTER(ps_tier_entry)],
             "ps_tier_table_plan": [vp, u32, C.POINTER(vp)],
             "ps_tier_pick": [vp, u32, C.POINTER(ps_tier_choice)],
+            "ps_stack_load_kv": [vp, u32, u32, vp, vp, u32],
+            "ps_stack_set_context": [vp, u32],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -156,7 +158,7 @@ def model_desc(cfg):
     flags = (PS_FLAG_NO_ATTN if cfg.get("no_attn") else 0) | (PS_FLAG_NO_RESIDUAL if cfg.get("no_residual") else 0)
     return ps_model_desc(cfg["n_layers"], cfg["hidden"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
                          cfg["ffn_inter"], cfg["n_experts"], cfg["top_k"], cfg["expert_inter"], flags,
-                         cfg["rms_eps"])
+                         cfg["rms_eps"], int(cfg.get("kv_context", 0)))
 
 
 def make_profile(h2d_gbps=55.0, gemv_gbps=4000.0, gemm_tflops=400.0, launch_us=3.0):
@@ -371,6 +373,17 @@ class Stack:
         e = NO_EXPERT if expert is None else int(expert)
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_load_matrix(self.h, layer, mat, e, _ptr(s), _ptr(c)))
+
+    def load_kv(self, layer, kv_head, K, V):
+        """K, V: float16 [n_pos][head_dim] rows of one kv head's cache (positions 0 .. n_pos - 1)."""
+        k = np.ascontiguousarray(K, dtype=np.float16)
+        v = np.ascontiguousarray(V, dtype=np.float16)
+        assert k.shape == v.shape and k.ndim == 2
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_load_kv(self.h, int(layer), int(kv_head), _ptr(k), _ptr(v), k.shape[0]))
+
+    def set_context(self, context):
+        _check(lib().ps_stack_set_context(self.h, int(context)))
 
     def forward(self, x_in, x_out, router_logits=None):
         """x_in, x_out: torch fp16 CUDA tensors [M][H]; asynchronous on self.compute."""

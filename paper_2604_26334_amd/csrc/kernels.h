@@ -83,6 +83,26 @@ hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts
 hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st);
 hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
                         hipStream_t st);
+// Decode attention over a KV cache, one new token.  A cache shard of one kv head is K rows
+// [cap][128] followed by V rows [cap][128], fp16; `nheads` shards lie head_stride bytes apart from
+// kv (kv heads head0 .. head0 + nheads - 1).  Each workgroup covers one kv head x one chunk of 256
+// cached positions for the head's `group` query heads and writes, per query head and chunk, the
+// chunk's score maximum, sum of weights and 128 weighted value sums (fp32) to
+// part[(q_head * chunk_cap + chunk) * 130].  ctx = cached positions (nothing is launched for 0).
+struct AttnArgs {
+    const __half *kv;
+    uint64_t head_stride;
+    uint32_t cap, ctx, head0, nheads, group, chunk_cap;
+    const __half *q;      // the token's QKV row: query head h at [h * 128]
+    float *part;
+};
+hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st);
+// Merge the chunks of every query head in ascending order with the token's own position (score
+// q.k_new / sqrt(128), value v_new), write the attention output (fp16 [n_q * 128]) and append the
+// token's K and V rows at position ctx of each kv head's cache home (home[g] = address of that
+// head's K row 0, device memory or device-visible pinned host memory).
+hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
+                               uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st);
 hipError_t launch_combine(const __half *h, const float *y, const float *w, uint32_t M, uint32_t H, uint32_t top_k,
                           int residual, __half *out, hipStream_t st);
 hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st);

@@ -641,6 +641,176 @@ hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t to
 }
 
 // ------------------------------------------------------------------------------------
+// Decode attention over a KV cache (one new token; softmax(q.K / sqrt(d)) V, no positional
+// encoding).  HBM-bound on the cache bytes: a workgroup streams 256 positions of one kv head
+// (64 KB of K, then 64 KB of V) once for all G query heads that share it.
+// 16 lanes hold one position (8 dims each), so a wave load covers 4 whole rows (1 KB contiguous).
+// Pass 1: scores of the chunk -> LDS; chunk maximum per query head.  Pass 2: p = exp(s - max),
+// sum of p and p-weighted V sums.  Chunks are merged by attn_combine_kernel in chunk order, so the
+// result does not depend on where the cache shard lives.
+// ------------------------------------------------------------------------------------
+constexpr int kAttnPos = 256;   // positions per workgroup (4 waves x 16 steps x 4 positions)
+
+template <int G>
+__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
+    __shared__ float sc[G][kAttnPos];
+    __shared__ float red[4][G][128];
+    __shared__ float redl[4][G];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dl = lane & 15, pg = lane >> 4;
+    const uint32_t chunk = blockIdx.x, hk = blockIdx.y;               // kv head within this launch
+    const __half *K = reinterpret_cast<const __half *>(reinterpret_cast<const char *>(a.kv) + (size_t)hk * a.head_stride);
+    const __half *V = K + (size_t)a.cap * 128;
+    const uint32_t q0 = (a.head0 + hk) * G;                           // first query head of this kv head
+    const float scale = 0.08838834764831845f;                         // 1 / sqrt(128)
+
+    uint4 qv[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) qv[h] = *reinterpret_cast<const uint4 *>(a.q + (size_t)(q0 + h) * 128 + dl * 8);
+
+    const uint32_t base = chunk * kAttnPos + wave * 64;
+    // pass 1: scores
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const uint32_t j = base + it * 4 + pg;
+        uint4 kv = make_uint4(0, 0, 0, 0);
+        if (j < a.ctx) kv = load_stream(reinterpret_cast<const uint4 *>(K + (size_t)j * 128 + dl * 8));
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float d = 0.f;
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].x), as_h2(kv.x), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].y), as_h2(kv.y), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kv.z), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kv.w), d, false);
+            d += __shfl_xor(d, 1, 64);
+            d += __shfl_xor(d, 2, 64);
+            d += __shfl_xor(d, 4, 64);
+            d += __shfl_xor(d, 8, 64);
+            if (dl == 0) sc[h][wave * 64 + it * 4 + pg] = j < a.ctx ? d * scale : -INFINITY;
+        }
+    }
+    __syncthreads();
+    // chunk maximum per query head (every wave computes it for itself; the first position of a
+    // launched chunk is always valid, so the maximum is finite)
+    float mx[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float v = fmaxf(fmaxf(sc[h][lane], sc[h][lane + 64]), fmaxf(sc[h][lane + 128], sc[h][lane + 192]));
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+        mx[h] = v;
+    }
+    // pass 2: weights and weighted values
+    float l[G], o[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
+    }
+#pragma unroll 2
+    for (int it = 0; it < 16; ++it) {
+        const uint32_t j = base + it * 4 + pg;
+        uint4 vv = make_uint4(0, 0, 0, 0);
+        if (j < a.ctx) vv = load_stream(reinterpret_cast<const uint4 *>(V + (size_t)j * 128 + dl * 8));
+        float vf[8];
+        const uint32_t vd[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const h2_t pr = as_h2(vd[e]);
+            vf[2 * e] = (float)pr.x;
+            vf[2 * e + 1] = (float)pr.y;
+        }
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float p = __expf(sc[h][wave * 64 + it * 4 + pg] - mx[h]);   // exp(-inf) = 0 past the end
+            l[h] += p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
+        }
+    }
+    // the 4 position groups of a wave meet, then the 4 waves through LDS, in fixed order
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        l[h] += __shfl_xor(l[h], 16, 64);
+        l[h] += __shfl_xor(l[h], 32, 64);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            o[h][e] += __shfl_xor(o[h][e], 16, 64);
+            o[h][e] += __shfl_xor(o[h][e], 32, 64);
+        }
+        if (pg == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[wave][h][dl * 8 + e] = o[h][e];
+            if (dl == 0) redl[wave][h] = l[h];
+        }
+    }
+    __syncthreads();
+    for (int t = tid; t < G * 128; t += 256) {
+        const int h = t >> 7, d = t & 127;
+        float *dst = a.part + ((size_t)(q0 + h) * a.chunk_cap + chunk) * 130;
+        dst[2 + d] = ((red[0][h][d] + red[1][h][d]) + red[2][h][d]) + red[3][h][d];
+        if (d == 0) {
+            dst[0] = mx[h];   // the same in every wave
+            dst[1] = ((redl[0][h] + redl[1][h]) + redl[2][h]) + redl[3][h];
+        }
+    }
+}
+
+hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
+    if (a.ctx == 0 || a.nheads == 0) return hipSuccess;
+    dim3 grid((a.ctx + kAttnPos - 1) / kAttnPos, a.nheads);
+    if (grid.x > a.chunk_cap) return hipErrorInvalidValue;
+    switch (a.group) {
+        case 1: hipLaunchKernelGGL(attn_decode_kernel<1>, grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL(attn_decode_kernel<2>, grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL(attn_decode_kernel<4>, grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL(attn_decode_kernel<8>, grid, dim3(256), 0, st, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// one workgroup of 128 threads per query head, thread d owns dimension d
+__global__ __launch_bounds__(128) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx,
+                                                           uint32_t cap, const __half *qkv, uint32_t n_q, uint32_t n_kv,
+                                                           const uint64_t *home, __half *out) {
+    __shared__ float dots[2];
+    const uint32_t h = blockIdx.x, d = threadIdx.x, group = n_q / n_kv, g = h / group;
+    const float kn = __half2float(qkv[(size_t)(n_q + g) * 128 + d]);
+    const float vn = __half2float(qkv[(size_t)(n_q + n_kv + g) * 128 + d]);
+    // the token's own score
+    float dot = wave_sum(__half2float(qkv[(size_t)h * 128 + d]) * kn);
+    if ((d & 63) == 0) dots[d >> 6] = dot;
+    __syncthreads();
+    const float s_self = (dots[0] + dots[1]) * 0.08838834764831845f;
+    const uint32_t nchunks = (ctx + kAttnPos - 1) / kAttnPos;
+    const float *ph = part + (size_t)h * chunk_cap * 130;
+    float mx = s_self;
+    for (uint32_t c = 0; c < nchunks; ++c) mx = fmaxf(mx, ph[(size_t)c * 130]);
+    float w = __expf(s_self - mx);
+    float L = w, o = w * vn;
+    for (uint32_t c = 0; c < nchunks; ++c) {
+        w = __expf(ph[(size_t)c * 130] - mx);
+        L = fmaf(w, ph[(size_t)c * 130 + 1], L);
+        o = fmaf(w, ph[(size_t)c * 130 + 2 + d], o);
+    }
+    out[(size_t)h * 128 + d] = to_half(o / L);
+    if (h % group == 0) {   // append the token's rows to the cache home of kv head g
+        __half *Kh = reinterpret_cast<__half *>(home[g]);
+        Kh[(size_t)ctx * 128 + d] = qkv[(size_t)(n_q + g) * 128 + d];
+        Kh[((size_t)cap + ctx) * 128 + d] = qkv[(size_t)(n_q + n_kv + g) * 128 + d];
+    }
+}
+
+hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
+                               uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st) {
+    if (ctx >= cap || n_kv == 0 || n_q % n_kv) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(128), 0, st, part, chunk_cap, ctx, cap, qkv, n_q, n_kv, home, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
 // MoE combine: out[m] = h[m] + sum_j w[m][j] * y[m*top_k + j], j in rank order
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const __half *h, const float *y, const float *w, uint32_t M,

@@ -60,6 +60,12 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
         if (bad_k(g.attn_w)) { set_error("n_q_heads*head_dim=%u unsupported", g.attn_w); return PS_E_ARG; }
         g.qkv = make_geom(g.qkv_w, m->hidden, false);
         g.o = make_geom(m->hidden, g.attn_w, false);
+        g.kv = m->kv_context > 0;
+        if (m->kv_context > (1u << 20)) { set_error("kv_context=%u too large", m->kv_context); return PS_E_ARG; }
+        g.kv_shard_bytes = (uint64_t)m->kv_context * m->head_dim * 2 * 2;   // K rows then V rows, fp16
+    } else if (m->kv_context) {
+        set_error("kv_context needs attention layers");
+        return PS_E_ARG;
     }
     if (g.moe) {
         if (m->ffn_inter != 0 || m->top_k == 0 || m->top_k > m->n_experts || m->top_k > 32 || m->n_experts > 1024) {
@@ -136,6 +142,13 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M) {
         if (per) pb = std::max<uint64_t>(pb, (uint64_t)((mg->nsb + per - 1) / per) * M * mg->rows * 4);
     }
     if (pb) w.partial = take(pb);
+    if (g.kv) {
+        w.attn = take((uint64_t)g.attn_w * 2);
+        // per query head and 256-position chunk: running maximum, sum of weights, 128 weighted sums
+        const uint64_t chunks = (g.m.kv_context + kAttnChunk - 1) / kAttnChunk;
+        w.apart = take((uint64_t)g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
+        w.kvhome = take((uint64_t)g.m.n_layers * g.m.n_kv_heads * 8);
+    }
     w.total = off;
     return w;
 }
@@ -190,6 +203,7 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
     int32_t rc = make_model_geom(model, &p->g);
     if (rc) return rc;
     if (M == 0 || M > kTiers[PS_NTIERS - 1]) { set_error("n_tokens=%u out of range 1..16384", M); return PS_E_ARG; }
+    if (p->g.kv && M != 1) { set_error("attention over a KV cache is built for one token per step (got %u)", M); return PS_E_ARG; }
     if (prof) p->prof = *prof;
     p->budget = budget;
     p->M = M;
@@ -207,7 +221,17 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
             c.quantum_tiles = mg.quantum_tiles; c.tile_bytes = mg.tile_bytes; c.freq = 0;
             cands.push_back(c);
         };
-        if (g.has_attn) { add(PS_SHARD_QKV, PS_CLASS_ATTN, g.qkv); add(PS_SHARD_O, PS_CLASS_ATTN, g.o); }
+        if (g.has_attn) {
+            add(PS_SHARD_QKV, PS_CLASS_ATTN, g.qkv);
+            if (g.kv) for (uint32_t h = 0; h < m.n_kv_heads; ++h) {   // one whole shard per kv head
+                Cand c{};
+                c.s.layer = l; c.s.kind = PS_SHARD_KV; c.s.cls = PS_CLASS_KVCACHE; c.s.expert = h;
+                c.s.ntiles = 0; c.s.bytes = g.kv_shard_bytes;
+                c.quantum_tiles = 0; c.tile_bytes = 0; c.freq = 0;
+                cands.push_back(c);
+            }
+            add(PS_SHARD_O, PS_CLASS_ATTN, g.o);
+        }
         if (!g.moe) { add(PS_SHARD_GATE_UP, PS_CLASS_FFN, g.gate_up); add(PS_SHARD_DOWN, PS_CLASS_FFN, g.down); }
         else for (uint32_t e = 0; e < m.n_experts; ++e) {
             Cand c{};
@@ -243,10 +267,10 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
     for (uint32_t r = 0; r < order.size(); ++r) cands[order[r]].s.rank = r;
 
     // DecideScratchVRAMBudget: none if everything fits, else a double buffer
-    std::vector<uint32_t> head_tiles(cands.size(), 0);  // tiles pinned per candidate
+    std::vector<uint32_t> head_tiles(cands.size(), 0);  // tiles pinned per candidate (whole shards: 0 or 1)
     if (p->ws.total + p->weight_bytes <= budget) {
         p->n_slots = 0; p->slot_bytes = 0;
-        for (size_t i = 0; i < cands.size(); ++i) head_tiles[i] = cands[i].s.ntiles;
+        for (size_t i = 0; i < cands.size(); ++i) head_tiles[i] = cands[i].quantum_tiles ? cands[i].s.ntiles : 1;
     } else {
         uint64_t lo = std::min<uint64_t>(1ull << 20, budget / 8), hi = 64ull << 20;
         uint64_t slot = std::min(std::max(budget / 16, lo), hi) / kAlign * kAlign;
@@ -263,7 +287,7 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
         bool split_done = false;
         for (uint32_t r = 0; r < order.size(); ++r) {
             Cand &c = cands[order[r]];
-            if (c.s.bytes <= remaining) { head_tiles[order[r]] = c.s.ntiles; remaining -= c.s.bytes; continue; }
+            if (c.s.bytes <= remaining) { head_tiles[order[r]] = c.quantum_tiles ? c.s.ntiles : 1; remaining -= c.s.bytes; continue; }
             if (!split_done && c.quantum_tiles) {
                 split_done = true;
                 uint64_t q = remaining / (c.tile_bytes * c.quantum_tiles);
@@ -397,6 +421,8 @@ int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t budget, const 
     for (uint32_t t = 0; t < PS_NTIERS; ++t) {
         ps_plan *p = new (std::nothrow) ps_plan();
         if (!p) { delete tb; ps::set_error("out of host memory"); return PS_E_NOMEM; }
+        // attention over a KV cache is built for one token per step: only that tier has a schedule
+        if (model && model->kv_context && t > 0) { delete p; continue; }
         const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, p);
         if (rc == PS_OK) { tb->plans[t] = p; continue; }
         delete p;

@@ -94,6 +94,36 @@ struct Builder {
         }
     }
 
+    // KV-cache shards of a layer (one per kv head, consecutive): one attention launch per run of
+    // shards that sit next to each other -- pinned neighbours in the arena, or one slot fill
+    void add_kv_kernels(uint32_t layer, size_t &si) {
+        KernelItem cur;
+        bool open = false;
+        uint64_t next_off = 0;   // where the next shard must start to extend the open launch
+        while (si < p->shards.size() && p->shards[si].layer == layer && p->shards[si].kind == PS_SHARD_KV) {
+            const Shard &s = p->shards[si];
+            int batch = -1;
+            uint64_t off = s.offset;
+            if (!s.resident) off = stage((uint32_t)si, layer, false, &batch);
+            if (open && cur.batch == batch && off == next_off) {
+                cur.op.info.nshards++;
+                cur.op.info.bytes += s.bytes;
+            } else {
+                if (open) kernels.push_back(cur);
+                cur = KernelItem();
+                cur.op = kernel_op(PS_K_ATTN, layer);
+                cur.op.info.shard0 = (uint32_t)si;
+                cur.op.info.bytes = s.bytes;
+                cur.batch = batch;
+                if (batch >= 0) { cur.op.info.slot = batch % 2; cur.op.info.slot_offset = off; }
+                open = true;
+            }
+            next_off = off + s.bytes;
+            ++si;
+        }
+        if (open) kernels.push_back(cur);
+    }
+
     // sub: which half of the layer a RINV op serves (0 = attention input, 1 = FFN input)
     void add_plain(uint32_t kernel, uint32_t layer, uint32_t flags = 0, uint32_t sub = 0) {
         KernelItem k;
@@ -133,6 +163,10 @@ struct Builder {
             if (g.has_attn) {
                 if (M > 1) add_plain(PS_K_RINV, l);
                 add_matrix_kernels(PS_K_QKV, l, PS_SHARD_QKV, si);
+                if (g.kv) {
+                    add_kv_kernels(l, si);
+                    add_plain(PS_K_ATTN_COMBINE, l);
+                }
                 add_matrix_kernels(PS_K_O, l, PS_SHARD_O, si);
             }
             if (M > 1) add_plain(PS_K_RINV, l, 0, 1);
@@ -304,9 +338,13 @@ int32_t validate_schedule(const ps_schedule *s) {
                         return PS_E_STATE;
                     }
             } else if (o.slot >= 0 && o.nshards) {
-                if (!check_read(o.shard0, o.slot, o.slot_offset)) {
-                    set_error("op %zu: kernel reads shard %u before its copy completed", i, o.shard0);
-                    return PS_E_STATE;
+                uint64_t off = o.slot_offset;   // a run of shards lies back to back in the slot
+                for (uint32_t k = 0; k < o.nshards; ++k) {
+                    if (!check_read(o.shard0 + k, o.slot, off)) {
+                        set_error("op %zu: kernel reads shard %u before its copy completed", i, o.shard0 + k);
+                        return PS_E_STATE;
+                    }
+                    off += s->shard_bytes[o.shard0 + k];
                 }
             }
             ++ncomp;

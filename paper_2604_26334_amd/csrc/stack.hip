@@ -53,6 +53,9 @@ struct ps_stack {
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
     std::map<std::pair<const void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out)
     uint32_t n_phases = 0, bar_base = 0, persistent_grid = 0;
+    uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
+    hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
+    bool step_pending = false;
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
     std::vector<uint8_t> prof_is_copy;
@@ -118,8 +121,12 @@ bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __hal
             break;
         case PS_K_O:
             mg = &g.o; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
-            a.nunits = s.ntiles; a.x = qkv; a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim;
-            a.x_group = m.n_q_heads / m.n_kv_heads; a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
+            a.nunits = s.ntiles; a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
+            if (g.kv) {   // the attention output
+                a.x = reinterpret_cast<const __half *>(A + p.ws.attn);
+            } else {      // identity on V, read in place from the QKV row
+                a.x = qkv; a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
+            }
             break;
         case PS_K_GATE_UP:
             mg = &g.gate_up; *mode = GEMV_GATE_UP; *ks = gemv_ksplit(mg->ngroups, mg->ntiles / 2);
@@ -225,6 +232,24 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             a.res = resid ? hbuf : nullptr; a.out = xout; a.out_stride = H; a.out_row0 = s.tile0 * 16;
             return run_gemm(GEMM_RESID, a, g.down);
         }
+        case PS_K_ATTN: {
+            const Shard &s = p.shards[op.info.shard0];
+            AttnArgs a{};
+            a.kv = reinterpret_cast<const __half *>(wptr(op));
+            a.head_stride = g.kv_shard_bytes; a.cap = m.kv_context; a.ctx = st->ctx;
+            a.head0 = s.expert; a.nheads = op.info.nshards; a.group = m.n_q_heads / m.n_kv_heads;
+            a.chunk_cap = (m.kv_context + kAttnChunk - 1) / kAttnChunk;
+            a.q = qkv; a.part = reinterpret_cast<float *>(A + p.ws.apart);
+            PS_HIP(launch_attn_decode(a, cs));
+            return PS_OK;
+        }
+        case PS_K_ATTN_COMBINE:
+            PS_HIP(launch_attn_combine(reinterpret_cast<const float *>(A + p.ws.apart),
+                                       (m.kv_context + kAttnChunk - 1) / kAttnChunk, st->ctx, m.kv_context, qkv,
+                                       m.n_q_heads, m.n_kv_heads,
+                                       reinterpret_cast<const uint64_t *>(A + p.ws.kvhome) + (size_t)l * m.n_kv_heads,
+                                       reinterpret_cast<__half *>(A + p.ws.attn), cs));
+            return PS_OK;
         case PS_K_ROUTE:
             PS_HIP(launch_route(reinterpret_cast<const float *>(A + p.ws.logits) + (size_t)l * M * m.n_experts, M,
                                 m.n_experts, m.top_k, reinterpret_cast<int32_t *>(A + p.ws.ridx),
@@ -462,6 +487,20 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     if (hipHostMalloc(&st->stage, st->stage_bytes, hipHostMallocDefault) != hipSuccess) {
         ps::set_error("hipHostMalloc for staging failed"); return fail(PS_E_HIP);
     }
+    if (p.g.kv) {
+        // home of every kv head's cache: where its rows live between steps (arena or pinned pool)
+        std::vector<uint64_t> home((size_t)m.n_layers * m.n_kv_heads, 0);
+        for (size_t i = 0; i < p.shards.size(); ++i) {
+            const ps::Shard &s = p.shards[i];
+            if (s.kind != PS_SHARD_KV) continue;
+            home[(size_t)s.layer * m.n_kv_heads + s.expert] =
+                (uint64_t)(uintptr_t)(s.resident ? st->arena + s.offset : st->shard_host[i]);
+        }
+        if (hipMemcpy(st->arena + p.ws.kvhome, home.data(), home.size() * 8, hipMemcpyHostToDevice) != hipSuccess ||
+            hipEventCreateWithFlags(&st->ev_step, hipEventDisableTiming) != hipSuccess) {
+            ps::set_error("KV cache set-up failed"); return fail(PS_E_HIP);
+        }
+    }
     *out = st;
     return PS_OK;
 }
@@ -533,6 +572,46 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
     return PS_OK;
 }
 
+int32_t ps_stack_load_kv(ps_stack *st, uint32_t layer, uint32_t kv_head, const uint16_t *k_rows,
+                         const uint16_t *v_rows, uint32_t n_pos) {
+    if (!st || (n_pos && (!k_rows || !v_rows))) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    const auto &m = p.g.m;
+    if (!p.g.kv) { ps::set_error("this stack has no KV cache (kv_context is 0)"); return PS_E_STATE; }
+    if (layer >= m.n_layers || kv_head >= m.n_kv_heads || n_pos > m.kv_context) {
+        ps::set_error("KV load out of range (layer %u, head %u, %u positions)", layer, kv_head, n_pos);
+        return PS_E_ARG;
+    }
+    auto it = st->cover.find(std::make_tuple(layer, (uint32_t)PS_SHARD_KV, kv_head));
+    if (it == st->cover.end() || it->second.size() != 1) { ps::set_error("internal: no cache shard"); return PS_E_STATE; }
+    const uint32_t si = it->second[0];
+    const ps::Shard &s = p.shards[si];
+    const size_t row_bytes = (size_t)m.head_dim * 2, vbase = (size_t)m.kv_context * row_bytes;
+    if (n_pos == 0) return PS_OK;
+    PS_HIP(hipStreamSynchronize(st->compute));
+    if (st->copy) PS_HIP(hipStreamSynchronize(st->copy));
+    if (s.resident) {
+        PS_HIP(hipMemcpy(st->arena + s.offset, k_rows, n_pos * row_bytes, hipMemcpyHostToDevice));
+        PS_HIP(hipMemcpy(st->arena + s.offset + vbase, v_rows, n_pos * row_bytes, hipMemcpyHostToDevice));
+    } else {
+        std::memcpy(st->shard_host[si], k_rows, n_pos * row_bytes);
+        std::memcpy(st->shard_host[si] + vbase, v_rows, n_pos * row_bytes);
+    }
+    return PS_OK;
+}
+
+int32_t ps_stack_set_context(ps_stack *st, uint32_t context) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (!st->plan.g.kv) { ps::set_error("this stack has no KV cache (kv_context is 0)"); return PS_E_STATE; }
+    if (context >= st->plan.g.m.kv_context) {
+        ps::set_error("context %u needs a cache of at least %u positions (kv_context is %u)", context, context + 1,
+                      st->plan.g.m.kv_context);
+        return PS_E_ARG;
+    }
+    st->ctx = context;
+    return PS_OK;
+}
+
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits) {
     if (!st || !x_in || !x_out) { ps::set_error("NULL argument"); return PS_E_ARG; }
     if (x_in == x_out) { ps::set_error("x_in and x_out may not alias"); return PS_E_ARG; }
@@ -542,7 +621,16 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
         return PS_E_STATE;
     }
     const ps_plan &p = st->plan;
-    if (!p.g.moe) return run_schedule(st, st->dense_sched, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+    if (p.g.kv) {
+        if (st->ctx >= p.g.m.kv_context) { ps::set_error("context %u leaves no room in a cache of %u positions", st->ctx, p.g.m.kv_context); return PS_E_STATE; }
+        // this step's cache copies read rows the previous step appended from the compute stream
+        if (st->step_pending) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_step, 0));
+    }
+    if (!p.g.moe) {
+        const int32_t rc = run_schedule(st, st->dense_sched, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
+        if (rc == PS_OK && p.g.kv) { PS_HIP(hipEventRecord(st->ev_step, st->compute)); st->step_pending = true; }
+        return rc;
+    }
 
     if (!router_logits) { ps::set_error("MoE forward needs host router logits"); return PS_E_ARG; }
     ps_schedule sc;
@@ -591,7 +679,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     st->persistent = false;
     st->use_graph = false;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
-    if (mode == 0 || p.g.moe || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
+    if (mode == 0 || p.g.moe || p.g.kv || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
     if (mode == 2) { st->use_graph = true; return PS_OK; }
     static_assert(sizeof(ps::DecodePhase) <= ps::kPhaseBytes, "phase descriptor outgrew its workspace slot");
     const __half *tag_in = reinterpret_cast<const __half *>(uintptr_t(0x10));
@@ -761,6 +849,7 @@ void ps_stack_destroy(ps_stack *st) {
         if (st->ev_free[s]) (void)hipEventDestroy(st->ev_free[s]);
     }
     for (auto e : st->ev_router) if (e) (void)hipEventDestroy(e);
+    if (st->ev_step) (void)hipEventDestroy(st->ev_step);
     for (int b = 0; b < 2; ++b) if (st->ev_upload[b]) (void)hipEventDestroy(st->ev_upload[b]);
     for (auto e : st->prof_ev) (void)hipEventDestroy(e);
     for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);

@@ -44,6 +44,16 @@ def activations(seed, step, M, H):
     return g.standard_normal((M, H), dtype=np.float32).astype(np.float16)
 
 
+def kv_cache(seed, layer, n_kv, n_pos, head_dim=128):
+    """Synthetic KV cache of one layer: (K, V) fp16 [n_kv][n_pos][head_dim], N(0,1) entries (keys of
+    unit variance per dimension give scores q.k / sqrt(d) of order |q|, i.e. a softmax that is
+    neither flat nor one-hot for the normalised queries of this stack)."""
+    g = _gen(seed, 5, layer)
+    K = g.standard_normal((n_kv, n_pos, head_dim), dtype=np.float32).astype(np.float16)
+    V = g.standard_normal((n_kv, n_pos, head_dim), dtype=np.float32).astype(np.float16)
+    return K, V
+
+
 def router_logits(seed, step, L, M, E, bias_seed=None):
     """fp32 N(0,1) router logits [L][M][E].  With bias_seed, a fixed
     per-(layer, expert) N(0,1) bias is added so that some experts are hot."""

@@ -172,3 +172,78 @@ def test_chunked_prefill_through_the_tier_table(kind):
         st.close()
     # the larger tier's workspace displaces pinned shards, the smaller tier pins more (or all)
     assert streamed[-1] > 0 and streamed == sorted(streamed)
+
+
+def _kv_cfg(n_layers, cap):
+    return dict(Hn.small_dense_cfg(n_layers), kv_context=cap)
+
+
+@pytest.mark.parametrize("ctx0", [0, 1, 255, 256, 700])
+def test_decode_attention_over_kv_cache(ctx0):
+    """KV cache as a shard class + real decode attention: three consecutive decode steps at context
+    ctx0, ctx0 + 1, ctx0 + 2 (each step attends over the rows the earlier ones appended), every step
+    against the oracle, bit-identical across cache placements (all pinned / some streamed / all
+    streamed), appended rows checked through the next step's result."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    steps = 3
+    cfg = _kv_cfg(3, ctx0 + steps + 5)
+    W = Hn.WeightCache(cfg, 9)
+    n_kv, hd, L = cfg["n_kv_heads"], cfg["head_dim"], cfg["n_layers"]
+    caches = [S.kv_cache(9, l, n_kv, ctx0, hd) for l in range(L)]
+    xs = [S.activations(9, t, 1, cfg["hidden"]) for t in range(steps)]
+    # oracle: its own copy of the caches, rows appended as stored (fp16)
+    oK = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    oV = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    for l in range(L):
+        oK[l][:, :ctx0], oV[l][:, :ctx0] = caches[l]
+    refs = []
+    for t in range(steps):
+        rows = []
+        refs.append(O.stack_forward(xs[t], cfg, W, mirror=True, kv=lambda l: (oK[l], oV[l]), ctx=ctx0 + t, new_rows=rows))
+        for l, (kn, vn) in enumerate(rows):
+            oK[l][:, ctx0 + t], oV[l][:, ctx0 + t] = kn.astype(np.float16), vn.astype(np.float16)
+    full = B.Plan(cfg, 1 << 40, 1)
+    sh = full.shards()
+    attn_b = sum(s.bytes for s in sh if s.kind in (B.PS_SHARD_QKV, B.PS_SHARD_O))
+    kv_b = sum(s.bytes for s in sh if s.kind == B.PS_SHARD_KV)
+    wsb, allb = full.summary().workspace_bytes, full.summary().weight_bytes
+    slot = B.Plan(cfg, wsb + allb - 4096, 1).summary().slot_bytes
+    budgets = [wsb + allb + 4096, wsb + 2 * slot + 4096]
+    n_pinned = lambda b: sum(s.resident for s in B.Plan(cfg, b, 1).shards() if s.kind == B.PS_SHARD_KV)
+    for k in range(1, 40):      # a budget in between that pins some of the cache shards but not all
+        b = budgets[1] + (budgets[0] - budgets[1]) * k // 40
+        if 0 < n_pinned(b) < L * n_kv:
+            budgets.insert(1, b)
+            break
+    outs = []
+    for b in budgets:
+        plan = B.Plan(cfg, b, 1)
+        kvs = [s for s in plan.shards() if s.kind == B.PS_SHARD_KV]
+        _say("budget", b, "cache shards pinned", sum(s.resident for s in kvs), "of", len(kvs))
+        st = B.Stack(plan)
+        for layer in range(L):
+            for k, ex, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, ex, *W(layer, k, ex))
+            for g in range(n_kv):
+                st.load_kv(layer, g, caches[layer][0][g], caches[layer][1][g])
+        got = []
+        for t in range(steps):
+            xin = torch.from_numpy(xs[t]).cuda()
+            xout = torch.empty_like(xin)
+            st.set_context(ctx0 + t)
+            st.forward(xin, xout)
+            st.synchronize()
+            got.append(xout.cpu().numpy())
+            err = Hn.rel_err(got[-1], refs[t])
+            _say("  step", t, "ctx", ctx0 + t, "rel err %.2e" % err)
+            assert np.isfinite(got[-1]).all() and err <= TOL
+        outs.append(got)
+        st.close()
+    pinned = [sum(s.resident for s in B.Plan(cfg, b, 1).shards() if s.kind == B.PS_SHARD_KV) for b in budgets]
+    assert pinned[0] == L * n_kv
+    if ctx0 >= 255:     # caches big enough that the budgets are three different placements
+        assert len(budgets) == 3 and pinned[-1] == 0 and 0 < pinned[1] < L * n_kv
+    for got in outs[1:]:
+        for a, b in zip(got, outs[0]):
+            np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(B.ps_model_desc) == 44
+    assert C.sizeof(B.ps_model_desc) == 48
     assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS)
     assert C.sizeof(B.ps_shard_info) == 48
     assert C.sizeof(B.ps_op_info) == 48
@@ -325,3 +325,59 @@ def test_pick_tier_matches_the_definition():
                     assert (c.tier, c.iterations) == (t, iters), (budget, gemm, n)
                     assert c.tier_tokens == O.TIER_TOKENS[t] and c.est_iter_ms == est[t]
                     assert c.est_total_ms == pytest.approx(total, rel=1e-12)
+
+
+# ------------------------------------------------------------------ KV cache as a shard class
+
+def _kv_cfg(n_layers=3, ctx=700):
+    return dict(n_layers=n_layers, hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_inter=1408,
+                n_experts=0, top_k=0, expert_inter=0, rms_eps=1e-6, no_attn=False, no_residual=False, kv_context=ctx)
+
+
+def test_kv_cache_shards_rank_between_attention_and_ffn():
+    # Section 3, planning phase: priority attention > KV cache > FFN > outputs
+    cfg = _kv_cfg()
+    full = B.Plan(cfg, 1 << 40, 1)
+    sh = full.shards()
+    kv = [s for s in sh if s.kind == B.PS_SHARD_KV]
+    assert len(kv) == cfg["n_layers"] * cfg["n_kv_heads"]
+    assert all(s.bytes == cfg["kv_context"] * 128 * 2 * 2 and s.cls == B.PS_CLASS_KVCACHE for s in kv)
+    rank = lambda kind: [s.priority_rank for s in sh if s.kind == kind]
+    assert max(rank(B.PS_SHARD_QKV) + rank(B.PS_SHARD_O)) < min(rank(B.PS_SHARD_KV))
+    assert max(rank(B.PS_SHARD_KV)) < min(rank(B.PS_SHARD_GATE_UP) + rank(B.PS_SHARD_DOWN))
+    # execution order inside a layer: QKV, the kv heads, O, gate/up, down
+    kinds = [s.kind for s in sh if s.layer == 1]
+    first = {k: kinds.index(k) for k in set(kinds)}
+    assert first[B.PS_SHARD_QKV] < first[B.PS_SHARD_KV] < first[B.PS_SHARD_O] < first[B.PS_SHARD_GATE_UP]
+    # a budget that holds attention and part of the caches: caches fill before any FFN shard is pinned
+    attn = sum(s.bytes for s in sh if s.kind in (B.PS_SHARD_QKV, B.PS_SHARD_O))
+    kvb = sum(s.bytes for s in kv)
+    ws = full.summary().workspace_bytes
+    slot = B.Plan(cfg, ws + attn + kvb, 1).summary().slot_bytes       # what two scratch slots take here
+    plan = B.Plan(cfg, ws + attn + kvb // 2 + 2 * slot + 4096, 1)
+    got = plan.shards()
+    res_kv = [s for s in got if s.kind == B.PS_SHARD_KV and s.resident]
+    assert 0 < len(res_kv) < len(kv)
+    assert all(s.resident for s in got if s.kind in (B.PS_SHARD_QKV, B.PS_SHARD_O))
+    big_ffn = [s for s in got if s.kind in (B.PS_SHARD_GATE_UP, B.PS_SHARD_DOWN) and s.resident and s.bytes > kv[0].bytes]
+    assert not big_ffn     # first fit: only FFN slabs smaller than the cache shard that missed may slip in
+    sched = plan.schedule()
+    sched.validate()
+    ops = sched.ops()
+    attn_ops = [o for o in ops if o.type == B.PS_OP_KERNEL and o.kernel == B.PS_K_ATTN]
+    comb_ops = [o for o in ops if o.type == B.PS_OP_KERNEL and o.kernel == B.PS_K_ATTN_COMBINE]
+    assert len(comb_ops) == cfg["n_layers"] and sum(o.nshards for o in attn_ops) == len(kv)
+    copied = [o.shard0 for o in ops if o.type == B.PS_OP_COPY]
+    assert sorted(copied) == [i for i, s in enumerate(got) if not s.resident]
+
+
+def test_kv_cache_plans_are_one_token_only():
+    cfg = _kv_cfg()
+    with pytest.raises(B.PshardError):
+        B.Plan(cfg, 1 << 40, 16)
+    tb = B.TierTable(cfg, 1 << 40)
+    assert [e.feasible for e in tb.entries()] == [1] + [0] * (B.PS_NTIERS - 1)
+    assert tb.pick(1).tier == 0
+    bad = dict(cfg, no_attn=True)
+    with pytest.raises(B.PshardError):
+        B.Plan(bad, 1 << 40, 1)
