@@ -185,6 +185,47 @@ def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
     return out
 
 
+def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps):
+    """Decode at a context of `context` cached positions: the KV cache is a shard class of its own
+    (pinned after the attention weights, before the FFN), attention is real softmax attention."""
+    kcfg = dict(cfg, kv_context=context + 64)
+    plans = [B.Plan(kcfg, int(b), 1, profile=prof) for b in budgets]
+    stacks = [B.Stack(p) for p in plans]
+    B.load_synthetic(stacks, kcfg, seed, threads=min(16, os.cpu_count() or 8))
+    K, V = S.kv_cache(seed, 0, kcfg["n_kv_heads"], context, kcfg["head_dim"])   # same contents in every layer
+    for st in stacks:
+        for layer in range(kcfg["n_layers"]):
+            for g in range(kcfg["n_kv_heads"]):
+                st.load_kv(layer, g, K[g], V[g])
+    dev = stacks[0].device
+    xs = [torch.from_numpy(S.activations(seed, 500 + t, 1, kcfg["hidden"])).to(dev) for t in range(4)]
+    xo = torch.empty_like(xs[0])
+    kv_bytes_layer = context * kcfg["n_kv_heads"] * kcfg["head_dim"] * 2 * 2
+    out = {}
+    for b, plan, st in zip(budgets, plans, stacks):
+        s = plan.summary()
+        st.set_context(context)            # every timed step attends over the same `context` positions
+        n = steps if s.streamed_bytes == 0 else max(3, min(steps, 10))
+        ms = time_steps(torch, st, xs, xo, n, 2)
+        kb, stats = kernel_breakdown(B, st, plan, xs, xo)
+        at = kb.get(("kernel", B.PS_K_ATTN))
+        kv_res = sum(sh.bytes for sh in plan.shards() if sh.kind == B.PS_SHARD_KV and sh.resident)
+        r = dict(budget_bytes=int(b), context=context, ms_per_token=ms, tokens_per_s=1e3 / ms,
+                 resident_bytes=s.resident_bytes, kv_cache_bytes=kv_bytes_layer * kcfg["n_layers"],
+                 kv_cache_resident_bytes=kv_res, streamed_bytes_per_token=stats.streamed_bytes_step, est_ms=s.est_step_ms)
+        if at:   # launches of one layer cover all its kv heads when they sit together
+            per_layer_ms = at["avg_ms"] * at["launches"] / kcfg["n_layers"]
+            r["attn_ms_per_layer"] = per_layer_ms
+            r["attn_kv_gbps"] = kv_bytes_layer / (per_layer_ms * 1e-3) / 1e9
+            r["attn_frac_of_hbm_peak"] = r["attn_kv_gbps"] / HBM_PEAK_GBS
+        out["%g" % (b / 1e9)] = r
+        log("context %d, budget %.0f GB: %.3f ms/token, %.1f tok/s, cache %.2f of %.2f GB pinned, %.2f GB streamed/token%s" % (
+            context, b / 1e9, ms, 1e3 / ms, kv_res / 1e9, r["kv_cache_bytes"] / 1e9, stats.streamed_bytes_step / 1e9,
+            (", attention %.1f us/layer = %.0f GB/s" % (r["attn_ms_per_layer"] * 1e3, r["attn_kv_gbps"])) if at else ""))
+        st.close()
+    return out
+
+
 def measured_traffic(tag):
     """HBM bytes per launch of the named kernel from the committed rocprofv3 PMC summary
     (profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt); None if the summary is absent."""
@@ -208,8 +249,9 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
-    ap.add_argument("--extra", type=str, default="batch64,moe,tiers",
-                    help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB)")
+    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv",
+                    help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
+                         "kv (decode over a 16K-position KV cache)")
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -322,6 +364,8 @@ def main():
         extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128)
     if "tiers" in args.extra and args.layers == 32:
         extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
+    if "kv" in args.extra and args.layers == 32:
+        extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50)
     if "moe" in args.extra:
         extra["moe_decode_6gb"] = moe_leg(B, S, torch, seed, prof, 6e9, [1, 16], 10)
 

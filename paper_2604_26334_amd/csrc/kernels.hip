@@ -649,7 +649,17 @@ hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t to
 // sum of p and p-weighted V sums.  Chunks are merged by attn_combine_kernel in chunk order, so the
 // result does not depend on where the cache shard lives.
 // ------------------------------------------------------------------------------------
-constexpr int kAttnPos = 256;   // positions per workgroup (4 waves x 16 steps x 4 positions)
+constexpr int kAttnPos = kAttnChunk;      // positions per workgroup: 4 waves x kAttnIts steps x 4 positions
+constexpr int kAttnIts = kAttnPos / 16;
+
+// sum over each row of 16 lanes, result in every lane of the row (DPP: no LDS traffic)
+__device__ __forceinline__ float row16_sum(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));   // quad_perm 1,0,3,2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));   // quad_perm 2,3,0,1
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));  // row_mirror
+    return v;
+}
 
 template <int G>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
@@ -664,29 +674,39 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
     const uint32_t q0 = (a.head0 + hk) * G;                           // first query head of this kv head
     const float scale = 0.08838834764831845f;                         // 1 / sqrt(128)
 
+    // all of the wave's cache rows are requested up front (K chunks, then V chunks):
+    // the V rows stream in while the scores are computed
+    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / 4);
+    uint4 kq[kAttnIts], vq[kAttnIts];
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it) {
+        const uint32_t j = base + it * 4 + pg;
+        kq[it] = make_uint4(0, 0, 0, 0);
+        if (j < a.ctx) kq[it] = load_stream(reinterpret_cast<const uint4 *>(K + (size_t)j * 128 + dl * 8));
+    }
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it) {
+        const uint32_t j = base + it * 4 + pg;
+        vq[it] = make_uint4(0, 0, 0, 0);
+        if (j < a.ctx) vq[it] = load_stream(reinterpret_cast<const uint4 *>(V + (size_t)j * 128 + dl * 8));
+    }
     uint4 qv[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) qv[h] = *reinterpret_cast<const uint4 *>(a.q + (size_t)(q0 + h) * 128 + dl * 8);
 
-    const uint32_t base = chunk * kAttnPos + wave * 64;
-    // pass 1: scores
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
+    // pass 1: scores (the 16 lanes of a position meet through DPP row operations)
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it) {
         const uint32_t j = base + it * 4 + pg;
-        uint4 kv = make_uint4(0, 0, 0, 0);
-        if (j < a.ctx) kv = load_stream(reinterpret_cast<const uint4 *>(K + (size_t)j * 128 + dl * 8));
 #pragma unroll
         for (int h = 0; h < G; ++h) {
             float d = 0.f;
-            d = __builtin_amdgcn_fdot2(as_h2(qv[h].x), as_h2(kv.x), d, false);
-            d = __builtin_amdgcn_fdot2(as_h2(qv[h].y), as_h2(kv.y), d, false);
-            d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kv.z), d, false);
-            d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kv.w), d, false);
-            d += __shfl_xor(d, 1, 64);
-            d += __shfl_xor(d, 2, 64);
-            d += __shfl_xor(d, 4, 64);
-            d += __shfl_xor(d, 8, 64);
-            if (dl == 0) sc[h][wave * 64 + it * 4 + pg] = j < a.ctx ? d * scale : -INFINITY;
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].x), as_h2(kq[it].x), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].y), as_h2(kq[it].y), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kq[it].z), d, false);
+            d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kq[it].w), d, false);
+            d = row16_sum(d);
+            if (dl == 0) sc[h][wave * (kAttnPos / 4) + it * 4 + pg] = j < a.ctx ? d * scale : -INFINITY;
         }
     }
     __syncthreads();
@@ -695,12 +715,20 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
     float mx[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        float v = fmaxf(fmaxf(sc[h][lane], sc[h][lane + 64]), fmaxf(sc[h][lane + 128], sc[h][lane + 192]));
+        float v = sc[h][lane];
+#pragma unroll
+        for (int r = 64; r < kAttnPos; r += 64) v = fmaxf(v, sc[h][lane + r]);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
         mx[h] = v;
     }
-    // pass 2: weights and weighted values
+    // weights of the chunk's positions, once per position (thread t owns position t), back into LDS
+    __syncthreads();   // every wave has read the scores it needs for the maximum
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+        if (tid < kAttnPos) sc[h][tid] = __expf(sc[h][tid] - mx[h]);   // exp(-inf) = 0 past the end
+    __syncthreads();
+    // pass 2: sums of weights and weighted values
     float l[G], o[G][8];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -708,13 +736,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
     }
-#pragma unroll 2
-    for (int it = 0; it < 16; ++it) {
-        const uint32_t j = base + it * 4 + pg;
-        uint4 vv = make_uint4(0, 0, 0, 0);
-        if (j < a.ctx) vv = load_stream(reinterpret_cast<const uint4 *>(V + (size_t)j * 128 + dl * 8));
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it) {
         float vf[8];
-        const uint32_t vd[4] = {vv.x, vv.y, vv.z, vv.w};
+        const uint32_t vd[4] = {vq[it].x, vq[it].y, vq[it].z, vq[it].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const h2_t pr = as_h2(vd[e]);
@@ -723,7 +748,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            const float p = __expf(sc[h][wave * 64 + it * 4 + pg] - mx[h]);   // exp(-inf) = 0 past the end
+            const float p = sc[h][wave * (kAttnPos / 4) + it * 4 + pg];
             l[h] += p;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
@@ -771,30 +796,56 @@ hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// one workgroup of 128 threads per query head, thread d owns dimension d
+// one workgroup of 128 threads per query head.  The chunk maxima and weights are handled chunk-
+// parallel (thread t takes chunks t, t + 128, ...), then thread d sums dimension d over the chunks
+// in ascending order with the weights from LDS, so no load waits for an earlier one.
+constexpr uint32_t kAttnMaxChunks = 4096;   // 1M positions
+
+__device__ __forceinline__ float block128_reduce(float v, float *scratch, bool is_max) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float u = __shfl_xor(v, o, 64);
+        v = is_max ? fmaxf(v, u) : v + u;
+    }
+    __syncthreads();                       // scratch may still be read from the previous reduction
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return is_max ? fmaxf(scratch[0], scratch[1]) : scratch[0] + scratch[1];
+}
+
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx,
                                                            uint32_t cap, const __half *qkv, uint32_t n_q, uint32_t n_kv,
                                                            const uint64_t *home, __half *out) {
-    __shared__ float dots[2];
+    __shared__ float scratch[2];
+    __shared__ float wbuf[kAttnMaxChunks];
     const uint32_t h = blockIdx.x, d = threadIdx.x, group = n_q / n_kv, g = h / group;
     const float kn = __half2float(qkv[(size_t)(n_q + g) * 128 + d]);
     const float vn = __half2float(qkv[(size_t)(n_q + n_kv + g) * 128 + d]);
     // the token's own score
-    float dot = wave_sum(__half2float(qkv[(size_t)h * 128 + d]) * kn);
-    if ((d & 63) == 0) dots[d >> 6] = dot;
-    __syncthreads();
-    const float s_self = (dots[0] + dots[1]) * 0.08838834764831845f;
+    const float s_self = block128_reduce(__half2float(qkv[(size_t)h * 128 + d]) * kn, scratch, false) * 0.08838834764831845f;
     const uint32_t nchunks = (ctx + kAttnPos - 1) / kAttnPos;
     const float *ph = part + (size_t)h * chunk_cap * 130;
-    float mx = s_self;
-    for (uint32_t c = 0; c < nchunks; ++c) mx = fmaxf(mx, ph[(size_t)c * 130]);
-    float w = __expf(s_self - mx);
-    float L = w, o = w * vn;
-    for (uint32_t c = 0; c < nchunks; ++c) {
-        w = __expf(ph[(size_t)c * 130] - mx);
-        L = fmaf(w, ph[(size_t)c * 130 + 1], L);
-        o = fmaf(w, ph[(size_t)c * 130 + 2 + d], o);
+    float mloc = s_self;
+    for (uint32_t c = d; c < nchunks; c += 128) mloc = fmaxf(mloc, ph[(size_t)c * 130]);
+    const float mx = block128_reduce(mloc, scratch, true);
+    float lloc = 0.f;
+    for (uint32_t c = d; c < nchunks; c += 128) {
+        const float w = __expf(ph[(size_t)c * 130] - mx);
+        wbuf[c] = w;
+        lloc = fmaf(w, ph[(size_t)c * 130 + 1], lloc);
     }
+    const float w_self = __expf(s_self - mx);
+    const float L = block128_reduce(lloc, scratch, false) + w_self;   // also publishes wbuf
+    float o = w_self * vn;
+    uint32_t c = 0;
+    for (; c + 8 <= nchunks; c += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = ph[(size_t)(c + u) * 130 + 2 + d];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) o = fmaf(wbuf[c + u], v[u], o);
+    }
+    for (; c < nchunks; ++c) o = fmaf(wbuf[c], ph[(size_t)c * 130 + 2 + d], o);
     out[(size_t)h * 128 + d] = to_half(o / L);
     if (h % group == 0) {   // append the token's rows to the cache home of kv head g
         __half *Kh = reinterpret_cast<__half *>(home[g]);
@@ -805,7 +856,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *part, ui
 
 hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
                                uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st) {
-    if (ctx >= cap || n_kv == 0 || n_q % n_kv) return hipErrorInvalidValue;
+    if (ctx >= cap || n_kv == 0 || n_q % n_kv || (ctx + kAttnPos - 1) / kAttnPos > kAttnMaxChunks) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(128), 0, st, part, chunk_cap, ctx, cap, qkv, n_q, n_kv, home, out);
     return hipGetLastError();
 }

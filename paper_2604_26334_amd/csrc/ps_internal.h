@@ -18,7 +18,7 @@ constexpr uint32_t kGroupSb = 8;         // super-blocks per scale group
 constexpr uint64_t kSbBytes = 1024;      // 16 rows x 128 k x 4 bit
 constexpr uint64_t kAlign = 256;
 constexpr uint64_t kPhaseBytes = 256;
-constexpr uint32_t kAttnChunk = 256;    // cached positions one attention workgroup covers
+constexpr uint32_t kAttnChunk = 128;    // cached positions one attention workgroup covers (multiple of 64)
 constexpr uint64_t kSyncBytes = 16384;   // tree-barrier counters, flags and error word, 128 B apart    // upper bound of one persistent-kernel phase descriptor
 
 void set_error(const char *fmt, ...);
