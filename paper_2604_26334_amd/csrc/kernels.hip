@@ -796,12 +796,13 @@ hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// one workgroup of 128 threads per query head.  The chunk maxima and weights are handled chunk-
-// parallel (thread t takes chunks t, t + 128, ...), then thread d sums dimension d over the chunks
-// in ascending order with the weights from LDS, so no load waits for an earlier one.
-constexpr uint32_t kAttnMaxChunks = 4096;   // 1M positions
+// one workgroup of 512 threads per query head.  The chunk maxima and weights are handled chunk-
+// parallel (thread t takes chunks t, t + 512, ...); then four groups of 128 threads each sum one
+// quarter of the chunks (thread d of a group owns dimension d, loads 16 at a time so none waits for
+// an earlier one) and the four quarter sums meet in fixed order.
+constexpr uint32_t kAttnMaxChunks = 8192;   // 1M positions
 
-__device__ __forceinline__ float block128_reduce(float v, float *scratch, bool is_max) {
+__device__ __forceinline__ float block512_reduce(float v, float *scratch, bool is_max) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
         const float u = __shfl_xor(v, o, 64);
@@ -810,42 +811,54 @@ __device__ __forceinline__ float block128_reduce(float v, float *scratch, bool i
     __syncthreads();                       // scratch may still be read from the previous reduction
     if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
-    return is_max ? fmaxf(scratch[0], scratch[1]) : scratch[0] + scratch[1];
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
+    return r;
 }
 
-__global__ __launch_bounds__(128) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx,
+__global__ __launch_bounds__(512) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx,
                                                            uint32_t cap, const __half *qkv, uint32_t n_q, uint32_t n_kv,
                                                            const uint64_t *home, __half *out) {
-    __shared__ float scratch[2];
+    __shared__ float scratch[8];
     __shared__ float wbuf[kAttnMaxChunks];
-    const uint32_t h = blockIdx.x, d = threadIdx.x, group = n_q / n_kv, g = h / group;
+    __shared__ float osum[4][128];
+    const uint32_t h = blockIdx.x, tid = threadIdx.x, d = tid & 127, grp = tid >> 7;
+    const uint32_t group = n_q / n_kv, g = h / group;
     const float kn = __half2float(qkv[(size_t)(n_q + g) * 128 + d]);
     const float vn = __half2float(qkv[(size_t)(n_q + n_kv + g) * 128 + d]);
-    // the token's own score
-    const float s_self = block128_reduce(__half2float(qkv[(size_t)h * 128 + d]) * kn, scratch, false) * 0.08838834764831845f;
+    // the token's own score (every group of 128 threads holds the 128 products once)
+    const float s_self = block512_reduce(grp == 0 ? __half2float(qkv[(size_t)h * 128 + d]) * kn : 0.f, scratch, false) *
+                         0.08838834764831845f;
     const uint32_t nchunks = (ctx + kAttnPos - 1) / kAttnPos;
     const float *ph = part + (size_t)h * chunk_cap * 130;
     float mloc = s_self;
-    for (uint32_t c = d; c < nchunks; c += 128) mloc = fmaxf(mloc, ph[(size_t)c * 130]);
-    const float mx = block128_reduce(mloc, scratch, true);
+    for (uint32_t c = tid; c < nchunks; c += 512) mloc = fmaxf(mloc, ph[(size_t)c * 130]);
+    const float mx = block512_reduce(mloc, scratch, true);
     float lloc = 0.f;
-    for (uint32_t c = d; c < nchunks; c += 128) {
+    for (uint32_t c = tid; c < nchunks; c += 512) {
         const float w = __expf(ph[(size_t)c * 130] - mx);
         wbuf[c] = w;
         lloc = fmaf(w, ph[(size_t)c * 130 + 1], lloc);
     }
     const float w_self = __expf(s_self - mx);
-    const float L = block128_reduce(lloc, scratch, false) + w_self;   // also publishes wbuf
-    float o = w_self * vn;
-    uint32_t c = 0;
-    for (; c + 8 <= nchunks; c += 8) {
-        float v[8];
+    const float L = block512_reduce(lloc, scratch, false) + w_self;   // also publishes wbuf
+    // quarter q of the chunks: [q * per, min((q + 1) * per, nchunks))
+    const uint32_t per = (nchunks + 3) / 4, c1 = min(nchunks, (grp + 1) * per);
+    uint32_t c = min(nchunks, grp * per);
+    float o = 0.f;
+    for (; c + 16 <= c1; c += 16) {
+        float v[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = ph[(size_t)(c + u) * 130 + 2 + d];
+        for (int u = 0; u < 16; ++u) v[u] = ph[(size_t)(c + u) * 130 + 2 + d];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) o = fmaf(wbuf[c + u], v[u], o);
+        for (int u = 0; u < 16; ++u) o = fmaf(wbuf[c + u], v[u], o);
     }
-    for (; c < nchunks; ++c) o = fmaf(wbuf[c], ph[(size_t)c * 130 + 2 + d], o);
+    for (; c < c1; ++c) o = fmaf(wbuf[c], ph[(size_t)c * 130 + 2 + d], o);
+    osum[grp][d] = o;
+    __syncthreads();
+    if (grp != 0) return;
+    o = fmaf(w_self, vn, ((osum[0][d] + osum[1][d]) + osum[2][d]) + osum[3][d]);
     out[(size_t)h * 128 + d] = to_half(o / L);
     if (h % group == 0) {   // append the token's rows to the cache home of kv head g
         __half *Kh = reinterpret_cast<__half *>(home[g]);
@@ -857,7 +870,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *part, ui
 hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
                                uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st) {
     if (ctx >= cap || n_kv == 0 || n_q % n_kv || (ctx + kAttnPos - 1) / kAttnPos > kAttnMaxChunks) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(128), 0, st, part, chunk_cap, ctx, cap, qkv, n_q, n_kv, home, out);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(512), 0, st, part, chunk_cap, ctx, cap, qkv, n_q, n_kv, home, out);
     return hipGetLastError();
 }
 
