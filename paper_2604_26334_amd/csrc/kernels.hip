@@ -662,10 +662,9 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 template <int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
-    __shared__ float sc[G][kAttnPos];
+__global__ __launch_bounds__(256, 4) void attn_decode_kernel(AttnArgs a) {
     __shared__ float red[4][G][128];
-    __shared__ float redl[4][G];
+    __shared__ float redm[4][G], redl[4][G];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int dl = lane & 15, pg = lane >> 4;
     const uint32_t chunk = blockIdx.x, hk = blockIdx.y;               // kv head within this launch
@@ -674,27 +673,33 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
     const uint32_t q0 = (a.head0 + hk) * G;                           // first query head of this kv head
     const float scale = 0.08838834764831845f;                         // 1 / sqrt(128)
 
-    // all of the wave's cache rows are requested up front (K chunks, then V chunks):
-    // the V rows stream in while the scores are computed
-    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / 4);
-    uint4 kq[kAttnIts], vq[kAttnIts];
-#pragma unroll
-    for (int it = 0; it < kAttnIts; ++it) {
-        const uint32_t j = base + it * 4 + pg;
-        kq[it] = make_uint4(0, 0, 0, 0);
-        if (j < a.ctx) kq[it] = load_stream(reinterpret_cast<const uint4 *>(K + (size_t)j * 128 + dl * 8));
-    }
-#pragma unroll
-    for (int it = 0; it < kAttnIts; ++it) {
-        const uint32_t j = base + it * 4 + pg;
-        vq[it] = make_uint4(0, 0, 0, 0);
-        if (j < a.ctx) vq[it] = load_stream(reinterpret_cast<const uint4 *>(V + (size_t)j * 128 + dl * 8));
-    }
+    // the queries first (loads return in order: issued last they would arrive last, and the scores
+    // could not start before every cache row had arrived)
     uint4 qv[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) qv[h] = *reinterpret_cast<const uint4 *>(a.q + (size_t)(q0 + h) * 128 + dl * 8);
-
-    // pass 1: scores (the 16 lanes of a position meet through DPP row operations)
+    // all of the wave's cache rows are requested up front (K chunks, then V chunks):
+    // the V rows stream in while the scores are computed
+    // Buffer loads bounded to the ctx valid rows: a row past the end reads as zeros, so the loads
+    // need no branch (a branch per load would also make the compiler wait for each load at once)
+    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / 4);
+    const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)(a.ctx * 256u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)(a.ctx * 256u), 0x00020000);
+    const uint32_t voff = (uint32_t)pg * 256u + (uint32_t)dl * 16u;
+    const uint32_t soff = __builtin_amdgcn_readfirstlane(base * 256u);
+    uint4 kq[kAttnIts], vq[kAttnIts];
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it)
+        kq[it] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(kb, voff, soff + it * 1024, kAuxNt));
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it)
+        vq[it] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, voff, soff + it * 1024, kAuxNt));
+    // A wave works alone until the very end (no workgroup barrier between the passes): scores of its
+    // positions stay in registers (the 16 lanes of a position meet through DPP row operations and
+    // all hold the score), its own maximum, its own weights and sums.
+    float sc[kAttnIts][G], mx[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) mx[h] = -INFINITY;
 #pragma unroll
     for (int it = 0; it < kAttnIts; ++it) {
         const uint32_t j = base + it * 4 + pg;
@@ -705,30 +710,17 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
             d = __builtin_amdgcn_fdot2(as_h2(qv[h].y), as_h2(kq[it].y), d, false);
             d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kq[it].z), d, false);
             d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kq[it].w), d, false);
-            d = row16_sum(d);
-            if (dl == 0) sc[h][wave * (kAttnPos / 4) + it * 4 + pg] = j < a.ctx ? d * scale : -INFINITY;
+            const float r = row16_sum(d) * scale;      // outside any branch: every lane takes part
+            sc[it][h] = j < a.ctx ? r : -INFINITY;
+            mx[h] = fmaxf(mx[h], sc[it][h]);
         }
     }
-    __syncthreads();
-    // chunk maximum per query head (every wave computes it for itself; the first position of a
-    // launched chunk is always valid, so the maximum is finite)
-    float mx[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        float v = sc[h][lane];
-#pragma unroll
-        for (int r = 64; r < kAttnPos; r += 64) v = fmaxf(v, sc[h][lane + r]);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-        mx[h] = v;
+    for (int h = 0; h < G; ++h) {   // the wave's 4 position groups
+        mx[h] = fmaxf(mx[h], __shfl_xor(mx[h], 16, 64));
+        mx[h] = fmaxf(mx[h], __shfl_xor(mx[h], 32, 64));
     }
-    // weights of the chunk's positions, once per position (thread t owns position t), back into LDS
-    __syncthreads();   // every wave has read the scores it needs for the maximum
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-        if (tid < kAttnPos) sc[h][tid] = __expf(sc[h][tid] - mx[h]);   // exp(-inf) = 0 past the end
-    __syncthreads();
-    // pass 2: sums of weights and weighted values
+    // a wave whose positions all lie past the end has maximum -inf: its weights must be 0, not NaN
     float l[G], o[G][8];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -748,13 +740,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            const float p = sc[h][wave * (kAttnPos / 4) + it * 4 + pg];
+            const float p = sc[it][h] == -INFINITY ? 0.f : __expf(sc[it][h] - mx[h]);
             l[h] += p;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
         }
     }
-    // the 4 position groups of a wave meet, then the 4 waves through LDS, in fixed order
+    // the 4 position groups of a wave meet; then the 4 waves through LDS, rescaled to the chunk
+    // maximum, in fixed order
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         l[h] += __shfl_xor(l[h], 16, 64);
@@ -767,17 +760,22 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
         if (pg == 0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) red[wave][h][dl * 8 + e] = o[h][e];
-            if (dl == 0) redl[wave][h] = l[h];
+            if (dl == 0) { redl[wave][h] = l[h]; redm[wave][h] = mx[h]; }
         }
     }
     __syncthreads();
     for (int t = tid; t < G * 128; t += 256) {
         const int h = t >> 7, d = t & 127;
+        // wave 0's first position is always valid in a launched chunk, so the chunk maximum is finite
+        const float m = fmaxf(fmaxf(redm[0][h], redm[1][h]), fmaxf(redm[2][h], redm[3][h]));
+        float w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] = redm[k][h] == -INFINITY ? 0.f : __expf(redm[k][h] - m);
         float *dst = a.part + ((size_t)(q0 + h) * a.chunk_cap + chunk) * 130;
-        dst[2 + d] = ((red[0][h][d] + red[1][h][d]) + red[2][h][d]) + red[3][h][d];
+        dst[2 + d] = fmaf(w[3], red[3][h][d], fmaf(w[2], red[2][h][d], fmaf(w[1], red[1][h][d], w[0] * red[0][h][d])));
         if (d == 0) {
-            dst[0] = mx[h];   // the same in every wave
-            dst[1] = ((redl[0][h] + redl[1][h]) + redl[2][h]) + redl[3][h];
+            dst[0] = m;
+            dst[1] = fmaf(w[3], redl[3][h], fmaf(w[2], redl[2][h], fmaf(w[1], redl[1][h], w[0] * redl[0][h])));
         }
     }
 }
