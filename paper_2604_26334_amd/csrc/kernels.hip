@@ -1098,8 +1098,9 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
         // A bare barrier: __syncthreads() carries a fence that makes the compiler wait for EVERY
         // LDS-direct load in flight, i.e. also for the deeper prefetches.  What must be ordered
         // here is ordered by hand: this wave's fill of the next stage is complete (vmcnt), and
-        // its LDS reads of the current stage were consumed by the MFMAs above.
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LPI) : "memory");
+        // its LDS reads of the current stage, which the next step's fill overwrites, have
+        // returned (lgkmcnt).
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DEPTH - 1) * LPI) : "memory");
         __builtin_amdgcn_s_barrier();
     };
     // whole turns of the ring, then the remaining steps (no exit from inside a turn: the ring is back

@@ -102,3 +102,65 @@ def test_moe_decode_at_6gb(M):
     _say()
     cfg = S.cfg_moe()
     _run(cfg, 0, M, [6e9], logits_fn=lambda step: S.router_logits(0, step, cfg["n_layers"], M, cfg["n_experts"]))
+
+
+def test_dense8b_decode_over_a_4k_kv_cache():
+    """The 8B-shaped stack with real decode attention over 4096 cached positions per kv head (the KV
+    cache planned as its own shard class), two consecutive steps, all pinned / FFN streamed / cache
+    partly streamed: against the oracle and bit-identical across the three placements."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    _say()
+    ctx, steps = 4096, 2
+    cfg = dict(S.cfg_dense8b(), kv_context=ctx + 8)
+    L, n_kv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
+    t0 = time.time()
+    caches = [S.kv_cache(0, l, n_kv, ctx, hd) for l in range(L)]
+    oK = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    oV = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    for l in range(L):
+        oK[l][:, :ctx], oV[l][:, :ctx] = caches[l]
+    W = Hn.WeightCache(cfg, 0, keep=False)
+    xs, refs = [], []
+    step = 0
+    while len(xs) < steps and step < 12:       # activation draws whose oracle result stays finite
+        x = S.activations(0, step, 1, cfg["hidden"])
+        step += 1
+        rows = []
+        ref = O.stack_forward(x, cfg, W, mirror=True, kv=lambda l: (oK[l], oV[l]), ctx=ctx + len(xs), new_rows=rows)
+        if not np.isfinite(ref).all():
+            continue
+        for l, (kn, vn) in enumerate(rows):
+            oK[l][:, ctx + len(xs)], oV[l][:, ctx + len(xs)] = kn.astype(np.float16), vn.astype(np.float16)
+        xs.append(x)
+        refs.append(ref)
+    assert len(xs) == steps
+    _say("  oracle: %d steps at context %d in %.1f s" % (steps, ctx, time.time() - t0))
+    budgets = [8e9, 3e9, 1.0e9]
+    plans = [B.Plan(cfg, int(b), 1) for b in budgets]
+    stacks = [B.Stack(p) for p in plans]
+    B.load_synthetic(stacks, cfg, 0, threads=16, progress=2000)
+    outs = []
+    for p, st in zip(plans, stacks):
+        kvs = [s for s in p.shards() if s.kind == B.PS_SHARD_KV]
+        for l in range(L):
+            for g in range(n_kv):
+                st.load_kv(l, g, caches[l][0][g], caches[l][1][g])
+        got = []
+        for t in range(steps):
+            xin = torch.from_numpy(xs[t]).to(st.device)
+            xout = torch.empty_like(xin)
+            st.set_context(ctx + t)
+            st.forward(xin, xout)
+            st.synchronize()
+            got.append(xout.cpu().numpy())
+            err = Hn.rel_err(got[-1], refs[t])
+            _say("  budget %.1f GB (cache shards pinned %d of %d, %.2f GB streamed/step), step %d: max|err|/max|ref| = %.3e" % (
+                p.summary().budget_bytes / 1e9, sum(s.resident for s in kvs), len(kvs),
+                st.stats().streamed_bytes_step / 1e9, t, err))
+            assert np.isfinite(got[-1]).all() and err <= TOL
+        outs.append(got)
+        st.close()
+    for got in outs[1:]:
+        for a, b in zip(got, outs[0]):
+            np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
