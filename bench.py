@@ -46,13 +46,6 @@ def kernel_breakdown(B, st, plan, xs, xout, reps=3):
         st.forward(xs[r % len(xs)], xout)
         st.synchronize()
         stats = st.stats()
-        if stats.n_kernels == 1 and len(ops) > 1:   # persistent decode: the whole pass is one kernel
-            if r > 0:
-                a = acc.setdefault(("persistent", 0), [0.0, 0, 0])
-                a[0] += st.op_times(1)[0][1]
-                a[1] += 1
-                a[2] += stats.resident_bytes_step
-            continue
         times = st.op_times(len(ops))
         if r == 0:
             continue  # first profiled pass creates the events
@@ -255,7 +248,7 @@ def main():
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 persistent kernel, 2 HIP-graph replay")
+    ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 HIP-graph replay")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -325,13 +318,7 @@ def main():
     # dominant kernel of the headline run: the fused gate/up + SwiGLU GEMV (54% of the bytes)
     gu = head["kernels"].get("kernel_%d" % B.PS_K_GATE_UP)
     roof = None
-    pk = head["kernels"].get("persistent_0")
-    if pk:   # one persistent kernel reads every weight byte of the stack once per token
-        ach = pk["bytes_per_launch"] / (pk["avg_ms"] * 1e-3) / 1e9
-        roof = dict(bound="hbm", kernel="decode_persistent_kernel", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=ach / HBM_PEAK_GBS, traffic=None, bytes_per_launch=pk["bytes_per_launch"],
-                    avg_launch_us=pk["avg_ms"] * 1e3)
-    elif gu:
+    if gu:
         # the kernel's own launch duration: its 32 launches (one per layer, different weights each) back
         # to back between two events, so the event bracket's dispatch gap is amortised away
         iso_ms, iso_n = stacks[0].time_kernel(B.PS_K_GATE_UP, 10)

@@ -299,20 +299,17 @@ int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
-/* Decode execution mode (default 0 = one launch per shard).  Modes 1 and 2 apply only when the
- * plan is dense, one token and every shard is resident; otherwise they fall back to mode 0.
- *  1: the whole pass runs as ONE persistent kernel with grid-wide barriers between the matmuls;
- *  2: the launch-per-shard kernel sequence is captured once per (x_in, x_out) pair into a HIP
- *     graph (kernel nodes only) and replayed.
- * Order and arithmetic are unchanged (Algorithm 1's RunInTopologicalOrder); all modes give
- * bit-identical results.  Not to be called while a forward is in flight. */
+/* Decode execution mode.  0 (default): one launch per shard.  1: applies when the plan is dense,
+ * one token, no KV cache and every shard resident (otherwise mode 0 runs): the launch-per-shard
+ * kernel sequence is captured once per (x_in, x_out) pair into a HIP graph (kernel nodes only) and
+ * replayed.  Order and arithmetic are unchanged (Algorithm 1's RunInTopologicalOrder); both modes
+ * give bit-identical results.  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
 /* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
  * the copy stream pulls all of them from the pinned pool (one launch per slot fill);
  * gather = 0: one hipMemcpyAsync per expert.  Dense slabs always use hipMemcpyAsync. */
 int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather);
-/* Block until both streams are idle; PS_E_HIP if the persistent kernel reported a barrier
- * time-out (its bounded waits make the kernel drain instead of hanging). */
+/* Block until both streams are idle; PS_E_HIP if either reports an error. */
 int32_t ps_stack_sync_check(ps_stack *st);
 /* record per-op timing events in the next forwards (adds event overhead) */
 int32_t ps_stack_set_profiling(ps_stack *st, int32_t on);
@@ -329,9 +326,7 @@ int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, doubl
                              uint32_t *launches);
 /* device pointers into the workspace for inspection by tests (fp16 unless noted):
  * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
- * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k],
- * 5: uint32 timeline of the persistent decode kernel's last profiled pass (100 MHz ticks):
- *    for its first and its last workgroup, [start, then per phase: items done, barrier passed] */
+ * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k] */
 int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes);
 void ps_stack_destroy(ps_stack *st);
 

@@ -12,7 +12,7 @@ BUILD = os.path.join(HERE, "_build")
 SOURCES = ["planner.cpp", "schedule.cpp", "pack.cpp", "kernels.hip", "stack.hip", "profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: results must not depend on which kernel a device function was inlined into
-# (the launch-per-shard and persistent decode paths have to agree bit for bit); fused multiply-adds
+# (the one-token kernel variants have to agree bit for bit on every placement); fused multiply-adds
 # are written out with fmaf where they are wanted
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

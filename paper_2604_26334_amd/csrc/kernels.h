@@ -51,14 +51,6 @@ struct GemmArgs {
     const int32_t *pairs;
 };
 
-// One phase of the persistent decode kernel: a GEMV launch description plus its K split.
-// Pointers into the caller's x_in / x_out change per forward, so they are tagged:
-// x_tag / res_tag == 1: the caller's input; out_tag == 2: the caller's output.
-struct DecodePhase {
-    GemvArgs args;
-    uint32_t mode, ksplit, x_tag, res_tag, out_tag, pad[3];
-};
-
 // one host->device copy of a gathered batch: n16 16-byte units from pinned host memory to VRAM
 struct CopyDesc {
     uint64_t src, dst;
@@ -69,11 +61,6 @@ struct CopyDesc {
 hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st);
 
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units);
-// sync: kSyncBytes of zero-initialised device memory; epoch_base: barriers completed so far
-hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases, uint32_t grid, uint32_t *sync,
-                                    uint32_t epoch_base, const __half *x_in, __half *x_out, uint32_t *trace,
-                                    hipStream_t st);
-uint32_t decode_sync_err_offset();
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st);
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st);
 // sums `parts` fp32 partial planes [M][ncols_phys] in ascending order and applies the mode's epilogue

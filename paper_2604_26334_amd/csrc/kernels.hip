@@ -128,18 +128,6 @@ __device__ __forceinline__ uint32_t gather_col(uint32_t k, uint32_t x_off, uint3
 // Partial sums of the KSPLIT waves meet in LDS in a fixed order behind the only barrier, so
 // a row's result does not depend on which slab or slot it came from.
 // ------------------------------------------------------------------------------------
-// Activations cross workgroups inside the persistent kernel, so there (COH) they are moved with
-// device-scope atomic loads/stores, which bypass the caches that are not coherent between the
-// chip's XCDs; no bulk cache write-back or invalidate is then needed at a grid barrier.
-template <bool COH>
-__device__ __forceinline__ uint4 load_act16(const __half *p) {
-    if (!COH) return *reinterpret_cast<const uint4 *>(p);
-    uint64_t *q = reinterpret_cast<uint64_t *>(const_cast<__half *>(p));
-    const uint64_t lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const uint64_t hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
-}
-
 template <int NT>
 struct GemvBuf {
     uint4 sc[NT];
@@ -177,14 +165,14 @@ __device__ __forceinline__ void gemv_issue_w(GemvBuf<NT> &b, const uint4 *W, uin
 }
 
 // activations of scale group g: 128 chunks of 8, lane takes chunks lane and lane + 64
-template <int NT, bool COH>
+template <int NT>
 __device__ __forceinline__ void gemv_issue_x(GemvBuf<NT> &b, uint32_t g, uint32_t K, const __half *x,
                                              uint32_t x_off, uint32_t x_group, int lane) {
     const uint32_t k0 = g * 1024u + (uint32_t)lane * 8u, k1 = k0 + 512u;
     b.xa = make_uint4(0, 0, 0, 0);
     b.xb = make_uint4(0, 0, 0, 0);
-    if (k0 < K) b.xa = load_act16<COH>(x + gather_col(k0, x_off, x_group));
-    if (k1 < K) b.xb = load_act16<COH>(x + gather_col(k1, x_off, x_group));
+    if (k0 < K) b.xa = *reinterpret_cast<const uint4 *>(x + gather_col(k0, x_off, x_group));
+    if (k1 < K) b.xb = *reinterpret_cast<const uint4 *>(x + gather_col(k1, x_off, x_group));
 }
 
 // chunk q (0..127) of a group -> slot in the wave's LDS window: block b = q / 4, part p = q % 4,
@@ -194,9 +182,8 @@ __device__ __forceinline__ uint32_t xslot(uint32_t q) {
     return (b >> 2) * 16u + p * 4u + (b & 3u);
 }
 
-// LDS of one decode workgroup of NW waves: a 2 KB activation window per wave and two
-// generations of reduction scratch (consecutive items alternate, so a fast wave can never
-// overwrite sums that a slow wave of the previous item is still reading).  The scratch holds one
+// LDS of one decode workgroup of NW waves: a 2 KB activation window per wave and the reduction
+// scratch.  The scratch holds one
 // partial sum per (unit, scale group): a row's result is the sum of its scale-group partials in
 // ascending group order, whichever wave produced which partial -- so it depends neither on the
 // K split nor on the workgroup shape, let alone on the slab or slot the weights came from.
@@ -204,29 +191,18 @@ constexpr int kMaxGroups = 16;   // K <= 16384
 template <int NW>
 struct GemvLds {
     uint4 x[NW][128];
-    float red[2][(NW / 2) * kMaxGroups][2][16];   // K split >= 2: at most NW / 2 units per workgroup
-    float red_ss[2][(NW / 2) * kMaxGroups];
+    float red[(NW / 2) * kMaxGroups][2][16];   // K split >= 2: at most NW / 2 units per workgroup
+    float red_ss[(NW / 2) * kMaxGroups];
     float corr[NW][32];   // per wave: code-offset corrections of the current scale group
 };
 
 // One work item of the decode GEMV: the NW waves of the workgroup cover NW / ks units, ks
-// waves per unit.  `gen` selects the reduction scratch generation.
-// With use_pre, `pre` already holds (or has in flight) the weights of this wave's first group.
+// waves per unit.
 // DBUF: a wave with several scale groups issues the next group's loads before computing the
 // current one (costs a second register buffer; the one-tile modes can afford it).
-struct NoPrefetch {
-    __device__ __forceinline__ void operator()() const {}
-};
-
-// after_issue() runs once this item's first loads are in flight and `pre` has been consumed:
-// the persistent kernel uses it to start the weight loads of its NEXT item, so that they
-// stream while this item waits for its activations, computes, and crosses the barrier.
-template <int MODE, int NW, bool COH, class F = NoPrefetch, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16),
-          bool FULLG = false>
+template <int MODE, int NW, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), bool FULLG = false>
 __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, const __half *x, __half *out,
-                                          float *out_f32, uint32_t item, uint32_t ks, uint32_t gen,
-                                          GemvLds<NW> &lds, const GemvBuf<2> &pre, bool use_pre,
-                                          F after_issue = F()) {
+                                          float *out_f32, uint32_t item, uint32_t ks, GemvLds<NW> &lds) {
     constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
     constexpr bool NORM = (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -247,35 +223,16 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
     if (active && kpart < a.ngroups) {
         GemvBuf<NT> cur, nxt;
         uint32_t g = kpart;
-        if (use_pre) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                cur.sc[t] = pre.sc[t];
-#pragma unroll
-                for (int s = 0; s < 8; ++s) cur.wq[t][s] = pre.wq[t][s];
-            }
-            gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
-        } else {
-            // activations first: they are ready (and cached), and nothing can be computed before them
-            gemv_issue_x<NT, COH>(cur, g, a.K, x, a.x_off, a.x_group, lane);
-            gemv_issue_w<NT, FULLG>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), lane);
-        }
-        if (MODE == GEMV_RESID && writer && a.res) {
-            if (COH) {  // written by other workgroups: read the 32-bit word holding it at device scope
-                const uint32_t wd = __hip_atomic_load(reinterpret_cast<uint32_t *>(const_cast<__half *>(a.res)) + (row >> 1),
-                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                resv = (float)__builtin_bit_cast(_Float16, (uint16_t)((row & 1u) ? (wd >> 16) : (wd & 0xFFFFu)));
-            } else {
-                resv = __half2float(a.res[row]);
-            }
-        }
-        after_issue();
+        // activations first: they are ready (and cached), and nothing can be computed before them
+        gemv_issue_x<NT>(cur, g, a.K, x, a.x_off, a.x_group, lane);
+        gemv_issue_w<NT, FULLG>(cur, W, unit, a.tile_u4, g, min(8u, a.nsb - g * 8u), lane);
+        if (MODE == GEMV_RESID && writer && a.res) resv = __half2float(a.res[row]);
         while (true) {
             const uint32_t nsb_g = FULLG ? 8u : min(8u, a.nsb - g * 8u);
             const uint32_t gn = g + ks;
             const bool more = gn < a.ngroups;
             if (DBUF && more) {
-                gemv_issue_x<NT, COH>(nxt, gn, a.K, x, a.x_off, a.x_group, lane);
+                gemv_issue_x<NT>(nxt, gn, a.K, x, a.x_off, a.x_group, lane);
                 gemv_issue_w<NT, FULLG>(nxt, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
             }
             win[xslot(lane)] = cur.xa;
@@ -335,21 +292,19 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
                 const uint32_t slot = (wave / ks) * kMaxGroups + g;
                 if (c == 0) {
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) lds.red[gen][slot][t][i] = gacc[t];
+                    for (int t = 0; t < NT; ++t) lds.red[slot][t][i] = gacc[t];
                 }
-                if (NORM && lane == 0) lds.red_ss[gen][slot] = gss;
+                if (NORM && lane == 0) lds.red_ss[slot] = gss;
             }
             if (!more) break;
             if (DBUF) {
                 cur = nxt;
             } else {
-                gemv_issue_x<NT, COH>(cur, gn, a.K, x, a.x_off, a.x_group, lane);
+                gemv_issue_x<NT>(cur, gn, a.K, x, a.x_off, a.x_group, lane);
                 gemv_issue_w<NT, FULLG>(cur, W, unit, a.tile_u4, gn, min(8u, a.nsb - gn * 8u), lane);
             }
             g = gn;
         }
-    } else {
-        after_issue();
     }
     if (ks > 1) {
         __syncthreads();
@@ -357,8 +312,8 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             const uint32_t slot0 = (wave / ks) * kMaxGroups;
             for (uint32_t g = 0; g < a.ngroups; ++g) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] += lds.red[gen][slot0 + g][t][i];
-                if (NORM) ss += lds.red_ss[gen][slot0 + g];
+                for (int t = 0; t < NT; ++t) acc[t] += lds.red[slot0 + g][t][i];
+                if (NORM) ss += lds.red_ss[slot0 + g];
             }
         }
     }
@@ -372,16 +327,7 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
     if (MODE == GEMV_PLAIN) v = rinv * acc[0];
     else if (MODE == GEMV_RESID) v = resv + acc[0];
     else v = silu(rinv * acc[0]) * (rinv * acc[NT - 1]);
-    const __half hv = to_half(v);
-    if (COH) {  // lanes 0..15 are here: pair up and store 32-bit words at device scope
-        const uint32_t mine = __builtin_bit_cast(uint16_t, hv);
-        const uint32_t next = __shfl_down(mine, 1, 64);
-        if ((i & 1) == 0)
-            __hip_atomic_store(reinterpret_cast<uint32_t *>(out) + (row >> 1), mine | (next << 16), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-        out[row] = hv;
-    }
+    out[row] = to_half(v);
 }
 
 template <int MODE, int NW, bool FULLG>
@@ -404,9 +350,7 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_
             out_f32 = a.out_f32 + (size_t)pair * a.out_stride;
         }
     }
-    GemvBuf<2> none;
-    gemv_item<MODE, NW, false, NoPrefetch, ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), FULLG>(
-        a, W, x, out, out_f32, blockIdx.x, ks, 0, lds, none, false);
+    gemv_item<MODE, NW, ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), FULLG>(a, W, x, out, out_f32, blockIdx.x, ks, lds);
 }
 
 template <int MODE, bool FULLG>
@@ -444,134 +388,6 @@ hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t nt
     }
     return hipErrorInvalidValue;
 }
-
-// ------------------------------------------------------------------------------------
-// Persistent decode kernel: one launch runs a whole list of GEMV phases (the sub-layer
-// matmuls of consecutive resident shards), one workgroup of 8 waves per CU, with a grid-wide
-// barrier between phases instead of a kernel boundary.  The barrier is a monotone counter in
-// device memory; a wait is bounded by the 100 MHz real-time clock, and on expiry an error flag
-// makes every later wait fall through, so the grid always drains.
-// ------------------------------------------------------------------------------------
-// Tree barrier: workgroups arrive in groups of 16 on their group's counter, the last of a group
-// arrives on the top counter, the last of all publishes the barrier's epoch in every group's
-// flag, and each workgroup polls only its group's flag, so no address sees more than 16
-// contending atomics.  Counters only ever grow (a barrier adds exactly the group size), so
-// "last" is a test on the value modulo the size.  Layout of `sync` (uint32, 32 words = 128 B
-// apart): [0] top counter, [32 * (1 + g)] group counter, [32 * (33 + g)] group flag, g < 32;
-// the error flag lives at word 32 * 65.
-constexpr uint32_t kSyncStride = 32, kSyncGroup = 16, kSyncErrWord = 32 * 65;
-
-__device__ __forceinline__ void grid_barrier(uint32_t *sync, uint32_t epoch) {
-    // every wave first waits until its own device-scope stores of this phase have completed
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t G = gridDim.x, grp = blockIdx.x / kSyncGroup, ngroups = (G + kSyncGroup - 1) / kSyncGroup;
-        const uint32_t gsize = min(kSyncGroup, G - grp * kSyncGroup);
-        uint32_t *err = sync + kSyncErrWord;
-        const uint32_t old = __hip_atomic_fetch_add(sync + kSyncStride * (1 + grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old % gsize == gsize - 1) {
-            const uint32_t top = __hip_atomic_fetch_add(sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (top % ngroups == ngroups - 1)
-                for (uint32_t g = 0; g < ngroups; ++g)
-                    __hip_atomic_store(sync + kSyncStride * (33 + g), epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        uint32_t *flag = sync + kSyncStride * (33 + grp);
-        const uint64_t t0 = wall_clock64();
-        while ((int32_t)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
-            if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            if (wall_clock64() - t0 > 200000000ull) {  // 2 s at 100 MHz: give up, let the grid drain
-                __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// weights of the first scale group of work item `item` of phase `ph`, for this wave
-__device__ __forceinline__ bool decode_prefetch(GemvBuf<2> &pre, const DecodePhase &ph, uint32_t item) {
-    const GemvArgs &a = ph.args;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t ks = ph.ksplit, units = 8 / ks;
-    if (item >= (a.nunits + units - 1) / units) return false;   // uniform over the workgroup
-    const uint32_t unit = item * units + wave / ks, kpart = wave % ks;
-    if (unit < a.nunits && kpart < a.ngroups) {
-        const uint32_t nsb_g = min(8u, a.nsb - kpart * 8u);
-        if (ph.mode == GEMV_GATE_UP) {
-            gemv_issue_w<2>(pre, a.W, unit, a.tile_u4, kpart, nsb_g, lane);
-        } else {
-            GemvBuf<1> one;
-            gemv_issue_w<1>(one, a.W, unit, a.tile_u4, kpart, nsb_g, lane);
-            pre.sc[0] = one.sc[0];
-#pragma unroll
-            for (int s = 0; s < 8; ++s) pre.wq[0][s] = one.wq[0][s];
-        }
-    }
-    return true;
-}
-
-__global__ __launch_bounds__(512) void decode_persistent_kernel(const DecodePhase *phases, uint32_t nphases,
-                                                                uint32_t *sync, uint32_t epoch_base,
-                                                                const __half *x_in, __half *x_out, uint32_t *trace) {
-    __shared__ GemvLds<8> lds;
-    // optional timeline (100 MHz ticks) of the first and last workgroup: per phase the time its
-    // items were done and the time the barrier let it go
-    uint32_t *tr = (trace && threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1))
-                       ? trace + (blockIdx.x ? 2 * nphases + 2 : 0) : nullptr;
-    if (tr) tr[0] = (uint32_t)wall_clock64();
-    uint32_t gen = 0;
-    GemvBuf<2> pre;
-    bool have_pre = decode_prefetch(pre, phases[0], blockIdx.x);
-    for (uint32_t p = 0; p < nphases; ++p) {
-        const DecodePhase &ph = phases[p];
-        GemvArgs a = ph.args;
-        // activations that live in the caller's buffers are tagged rather than addressed
-        if (ph.x_tag == 1) a.x = x_in;
-        if (ph.res_tag == 1) a.res = x_in;
-        if (ph.out_tag == 2) a.out = x_out;
-        const uint32_t ks = ph.ksplit, units = 8 / ks;
-        const uint32_t nitems = (a.nunits + units - 1) / units;
-        for (uint32_t item = blockIdx.x; item < nitems; item += gridDim.x) {
-            // next item of this workgroup: in this phase, else its first item of the next phase
-            bool next_pre = false;
-            auto prefetch_next = [&]() {
-                if (item + gridDim.x < nitems) next_pre = decode_prefetch(pre, ph, item + gridDim.x);
-                else if (p + 1 < nphases) next_pre = decode_prefetch(pre, phases[p + 1], blockIdx.x);
-            };
-            switch (ph.mode) {
-                case GEMV_PLAIN:
-                    gemv_item<GEMV_PLAIN, 8, true>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
-                    break;
-                case GEMV_RESID:
-                    gemv_item<GEMV_RESID, 8, true, decltype(prefetch_next), false>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
-                    break;
-                default:
-                    gemv_item<GEMV_GATE_UP, 8, true>(a, a.W, a.x, a.out, nullptr, item, ks, gen, lds, pre, have_pre, prefetch_next);
-                    break;
-            }
-            gen ^= 1;
-            have_pre = next_pre;
-        }
-        if (tr) tr[1 + 2 * p] = (uint32_t)wall_clock64();
-        if (p + 1 < nphases) {
-            if (blockIdx.x >= nitems) have_pre = decode_prefetch(pre, phases[p + 1], blockIdx.x);  // idle this phase
-            grid_barrier(sync, epoch_base + p + 1);
-        }
-        if (tr) tr[2 + 2 * p] = (uint32_t)wall_clock64();
-    }
-}
-
-hipError_t launch_decode_persistent(const DecodePhase *phases, uint32_t nphases, uint32_t grid, uint32_t *sync,
-                                    uint32_t epoch_base, const __half *x_in, __half *x_out, uint32_t *trace,
-                                    hipStream_t st) {
-    if (grid == 0 || grid > 32 * kSyncGroup) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(decode_persistent_kernel, dim3(grid), dim3(512), 0, st, phases, nphases, sync, epoch_base, x_in,
-                       x_out, trace);
-    return hipGetLastError();
-}
-
-uint32_t decode_sync_err_offset() { return kSyncErrWord * 4; }
 
 // ------------------------------------------------------------------------------------
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one wave per token (used when M > 1)

@@ -111,12 +111,6 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M) {
     w.qkv_bytes = (uint64_t)M * g.qkv_w * 2;
     w.qkv = take(w.qkv_bytes);
     w.rinv = take((uint64_t)M * 4);
-    w.sync = take(kSyncBytes);  // grid-barrier counter and error flag of the persistent decode kernel
-    if (M == 1 && !g.moe) {
-        w.phases = take((uint64_t)g.m.n_layers * 4 * kPhaseBytes);
-        w.trace_bytes = ((uint64_t)g.m.n_layers * 4 * 2 + 2) * 2 * 4;  // two workgroups' phase timelines
-        w.trace = take(w.trace_bytes);
-    }
     if (g.moe) {
         const uint64_t P = (uint64_t)M * g.m.top_k;  // (token, rank) pairs
         w.s_bytes = P * g.ffn_i * 2;

@@ -17,9 +17,7 @@ constexpr uint32_t kSuperK = 128;        // k extent of one super-block (4 block
 constexpr uint32_t kGroupSb = 8;         // super-blocks per scale group
 constexpr uint64_t kSbBytes = 1024;      // 16 rows x 128 k x 4 bit
 constexpr uint64_t kAlign = 256;
-constexpr uint64_t kPhaseBytes = 256;
 constexpr uint32_t kAttnChunk = 128;    // cached positions one attention workgroup covers (multiple of 64)
-constexpr uint64_t kSyncBytes = 16384;   // tree-barrier counters, flags and error word, 128 B apart    // upper bound of one persistent-kernel phase descriptor
 
 void set_error(const char *fmt, ...);
 
@@ -47,9 +45,8 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out);
 // Activation / table workspace at the head of the arena, sized for M tokens.
 struct Workspace {
     uint64_t x0 = 0, x1 = 0, h = 0, qkv = 0, s = 0, y = 0, rinv = 0, ridx = 0, rw = 0,
-             logits = 0, tasks = 0, pairs = 0, phases = 0, sync = 0, trace = 0, partial = 0,
+             logits = 0, tasks = 0, pairs = 0, partial = 0,
              attn = 0, apart = 0, kvhome = 0, total = 0;   // attention output, chunk partials, cache home table
-    uint64_t trace_bytes = 0;
     uint64_t qkv_bytes = 0, h_bytes = 0, s_bytes = 0, tasks_bytes = 0, pairs_bytes = 0, logits_bytes = 0;
 };
 Workspace make_workspace(const ModelGeom &g, uint32_t M);

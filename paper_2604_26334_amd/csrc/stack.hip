@@ -49,10 +49,8 @@ struct ps_stack {
     uint64_t stage_bytes = 0;
     void *tables_host[2] = {nullptr, nullptr};   // pinned: logits | tasks | pairs | copy descriptors of one forward (MoE)
     uint64_t tables_bytes = 0;
-    bool persistent = false;                  // whole forward = one persistent decode kernel
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
     std::map<std::pair<const void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out)
-    uint32_t n_phases = 0, bar_base = 0, persistent_grid = 0;
     uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
     hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
     bool step_pending = false;
@@ -303,19 +301,6 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     st->prof_valid = false;
     ps_stats &ss = st->stats;
     ss = ps_stats{};
-    if (st->persistent) {   // every shard resident, one token: the whole pass is one kernel
-        if (prof) PS_HIP(hipEventRecord(st->prof_ev[0], st->compute));
-        PS_HIP(launch_decode_persistent(reinterpret_cast<const DecodePhase *>(st->arena + p.ws.phases), st->n_phases,
-                                        st->persistent_grid, reinterpret_cast<uint32_t *>(st->arena + p.ws.sync),
-                                        st->bar_base, x_in, x_out,
-                                        prof ? reinterpret_cast<uint32_t *>(st->arena + p.ws.trace) : nullptr, st->compute));
-        if (prof) PS_HIP(hipEventRecord(st->prof_ev[1], st->compute));
-        st->bar_base += st->n_phases - 1;   // barriers completed so far = epoch of the last one
-        for (const Op &op : sc.ops) ss.resident_bytes_step += op.info.bytes;
-        ss.n_kernels = 1;
-        if (prof) { st->prof_is_copy.assign(1, 0); st->prof_valid = true; }
-        return PS_OK;
-    }
     if (st->use_graph && !prof) {
         // Launch-bound case (every shard resident, one token): the kernel sequence is captured
         // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
@@ -674,44 +659,10 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
 
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
-    if (mode < 0 || mode > 2) { ps::set_error("decode mode must be 0, 1 or 2"); return PS_E_ARG; }
+    if (mode < 0 || mode > 1) { ps::set_error("decode mode must be 0 or 1"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
-    st->persistent = false;
-    st->use_graph = false;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
-    if (mode == 0 || p.g.moe || p.g.kv || p.M != 1 || p.n_slots != 0 || !st->have_dense_sched) return PS_OK;
-    if (mode == 2) { st->use_graph = true; return PS_OK; }
-    static_assert(sizeof(ps::DecodePhase) <= ps::kPhaseBytes, "phase descriptor outgrew its workspace slot");
-    const __half *tag_in = reinterpret_cast<const __half *>(uintptr_t(0x10));
-    __half *tag_out = reinterpret_cast<__half *>(uintptr_t(0x20));
-    std::vector<ps::DecodePhase> ph;
-    for (const ps::Op &op : st->dense_sched.ops) {
-        ps::DecodePhase d{};
-        int mode = 0;
-        if (op.info.type != PS_OP_KERNEL || !dense_gemv_args(st, op, tag_in, tag_out, &d.args, &mode, &d.ksplit)) {
-            ps::set_error("internal: schedule op not expressible as a decode phase"); return PS_E_STATE;
-        }
-        d.mode = (uint32_t)mode;
-        d.ksplit = std::min(d.ksplit, 8u);   // the persistent kernel's workgroups have 8 waves
-        if (d.args.x == tag_in) { d.x_tag = 1; d.args.x = nullptr; }
-        if (d.args.res == tag_in) { d.res_tag = 1; d.args.res = nullptr; }
-        if (d.args.out == tag_out) { d.out_tag = 2; d.args.out = nullptr; }
-        ph.push_back(d);
-    }
-    if (ph.empty() || ph.size() * sizeof(ps::DecodePhase) > (uint64_t)p.g.m.n_layers * 4 * ps::kPhaseBytes) {
-        ps::set_error("internal: phase list does not fit its workspace"); return PS_E_STATE;
-    }
-    int dev = 0, cus = 0;
-    PS_HIP(hipGetDevice(&dev));
-    PS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    if (cus <= 0) { ps::set_error("no compute units reported"); return PS_E_HIP; }
-    PS_HIP(hipStreamSynchronize(st->compute));
-    PS_HIP(hipMemcpy(st->arena + p.ws.phases, ph.data(), ph.size() * sizeof(ps::DecodePhase), hipMemcpyHostToDevice));
-    PS_HIP(hipMemset(st->arena + p.ws.sync, 0, ps::kSyncBytes));
-    st->n_phases = (uint32_t)ph.size();
-    st->persistent_grid = (uint32_t)cus;   // one 512-thread workgroup per CU: all co-resident
-    st->bar_base = 0;
-    st->persistent = true;
+    st->use_graph = mode == 1 && !p.g.moe && !p.g.kv && p.M == 1 && p.n_slots == 0 && st->have_dense_sched;
     return PS_OK;
 }
 
@@ -725,17 +676,6 @@ int32_t ps_stack_sync_check(ps_stack *st) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
     PS_HIP(hipStreamSynchronize(st->copy));
     PS_HIP(hipStreamSynchronize(st->compute));
-    if (st->persistent) {
-        uint32_t flag = 0;
-        PS_HIP(hipMemcpy(&flag, st->arena + st->plan.ws.sync + ps::decode_sync_err_offset(), 4, hipMemcpyDeviceToHost));
-        if (flag) {
-            // leave the barrier state clean for the next forward
-            PS_HIP(hipMemset(st->arena + st->plan.ws.sync, 0, ps::kSyncBytes));
-            st->bar_base = 0;
-            ps::set_error("persistent decode kernel: a grid barrier timed out (workgroups not co-resident?)");
-            return PS_E_HIP;
-        }
-    }
     return PS_OK;
 }
 
@@ -829,7 +769,6 @@ int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint
         case 2: *dev_ptr = st->arena + p.ws.s; *bytes = p.ws.s_bytes; return PS_OK;
         case 3: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.ridx; *bytes = P * 4; return PS_OK;
         case 4: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.rw; *bytes = P * 4; return PS_OK;
-        case 5: if (!p.ws.trace_bytes) break; *dev_ptr = st->arena + p.ws.trace; *bytes = p.ws.trace_bytes; return PS_OK;
     }
     ps::set_error("no such debug buffer");
     return PS_E_ARG;

@@ -41,7 +41,7 @@ def total_weight_bytes(cfg):
     return p.summary().weight_bytes, p.summary().workspace_bytes
 
 
-def run_gpu(cfg, weights, budget, x_np, logits=None, expert_freq=None, steps=1, profile=None, mode=1):
+def run_gpu(cfg, weights, budget, x_np, logits=None, expert_freq=None, steps=1, profile=None, mode=0):
     """Plan for budget, load, run one forward per x in x_np (list) -> list of fp16 numpy outputs."""
     import torch
     from paper_2604_26334_amd import binding as B
