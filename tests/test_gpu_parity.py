@@ -245,3 +245,60 @@ def test_decode_attention_over_kv_cache(ctx0):
     for got in outs[1:]:
         for a, b in zip(got, outs[0]):
             np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_error_paths_return_codes_and_leave_the_stack_usable():
+    """Misuse through the C ABI: every case returns an error code with a text, none faults, and the
+    stack still computes the right result afterwards."""
+    import ctypes as C
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = Hn.small_dense_cfg(2)
+    W = Hn.WeightCache(cfg, 4)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    plan = B.Plan(cfg, wb + (1 << 20), 1)
+    L = B.lib()
+    arena = torch.empty(int(plan.summary().budget_bytes) // 2, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p()
+    assert L.ps_stack_create(plan.h, arena.data_ptr(), arena.numel(), None, None, C.byref(h)) == B.PS_E_ARG   # arena < budget
+    assert b"arena" in L.ps_last_error()
+    assert L.ps_stack_create(plan.h, None, 0, None, None, C.byref(h)) == B.PS_E_ARG
+    st = B.Stack(plan)
+    x = torch.from_numpy(S.activations(4, 0, 1, cfg["hidden"])).cuda()
+    y = torch.empty_like(x)
+    with pytest.raises(B.PshardError) as e:            # forward before the weights are loaded
+        st.forward(x, y)
+    assert e.value.code == B.PS_E_STATE
+    for layer in range(cfg["n_layers"]):
+        for k, ex, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, k, ex, *W(layer, k, ex))
+    sc, cd = W(0, S.MAT_QKV, None)
+    for bad in ((9, S.MAT_QKV), (0, 17)):               # layer / matrix kind out of range
+        with pytest.raises(B.PshardError) as e:
+            st.load_matrix(bad[0], bad[1], None, sc, cd)
+        assert e.value.code == B.PS_E_ARG
+    assert L.ps_stack_forward(st.h, x.data_ptr(), x.data_ptr(), None) == B.PS_E_ARG      # aliasing
+    assert L.ps_stack_forward(st.h, None, y.data_ptr(), None) == B.PS_E_ARG
+    with pytest.raises(B.PshardError) as e:            # no KV cache in this stack
+        st.set_context(3)
+    assert e.value.code == B.PS_E_STATE
+    with pytest.raises(B.PshardError):
+        st.load_kv(0, 0, np.zeros((4, 128), np.float16), np.zeros((4, 128), np.float16))
+    with pytest.raises(B.PshardError):
+        st.set_decode_mode(7)
+    st.forward(x, y)
+    st.synchronize()
+    ref = O.stack_forward(S.activations(4, 0, 1, cfg["hidden"]), cfg, W, mirror=True)
+    assert Hn.rel_err(y.cpu().numpy(), ref) <= TOL
+    st.close()
+    # KV stack: context must leave room for the new row; more positions than the cache holds are refused
+    kcfg = dict(cfg, kv_context=16)
+    kst = B.Stack(B.Plan(kcfg, 1 << 26, 1))
+    with pytest.raises(B.PshardError) as e:
+        kst.set_context(16)
+    assert e.value.code == B.PS_E_ARG
+    with pytest.raises(B.PshardError):
+        kst.load_kv(0, 0, np.zeros((17, 128), np.float16), np.zeros((17, 128), np.float16))
+    with pytest.raises(B.PshardError):
+        kst.load_kv(0, 5, np.zeros((4, 128), np.float16), np.zeros((4, 128), np.float16))
+    kst.close()
