@@ -220,6 +220,16 @@ def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None, kv=
     return x
 
 
+def output_head(x, cfg, head, mirror=True):
+    """Output projection after the last layer (the "outputs" entry of the priority list, Section 3
+    planning phase): logits = Linear_head(RMSNorm(x)), x [M][H] the stack's final hidden state,
+    head = (scales, codes) of the [vocab][H] matrix.  mirror rounds the logits to fp16, as stored."""
+    y = linear(rmsnorm(x, cfg["rms_eps"]), *head)
+    if mirror:
+        y = y.astype(np.float16).astype(np.float64)
+    return y
+
+
 TIER_TOKENS = (1, 4, 16, 32, 64, 512, 1024, 2048, 4096, 8192, 16384)   # the tier set of Section 3
 
 

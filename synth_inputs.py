@@ -17,6 +17,7 @@ BLOCK = 32
 
 # matrix kinds; numeric values match the C header's PS_MAT_* constants
 MAT_QKV, MAT_O, MAT_GATE, MAT_UP, MAT_DOWN = 0, 1, 2, 3, 4
+MAT_OUT = 5   # output head, addressed as a matrix of layer n_layers
 NO_EXPERT = 0xFFFF
 
 
@@ -36,6 +37,11 @@ def weight_matrix(seed, layer, kind, expert, N, K):
     codes[0::2] = raw & 15
     codes[1::2] = raw >> 4
     return scales, codes.reshape(N, K)
+
+
+def head_matrix(seed, cfg):
+    """(scales, codes) of the output head [vocab][hidden], drawn like every other weight matrix."""
+    return weight_matrix(seed, cfg["n_layers"], MAT_OUT, None, cfg["vocab"], cfg["hidden"])
 
 
 def activations(seed, step, M, H):

@@ -446,3 +446,49 @@ def test_attn_kv_half_composition_and_empty_cache():
     Kd[:, ctx:] = 9.0; Vd[:, ctx:] = -9.0
     h2, _, _ = O.attn_kv_half(x, cfg, qkv, o, Kd, Vd, ctx, False)
     np.testing.assert_array_equal(h2, h)
+
+
+# ---------------------------------------------------------------- output head
+
+def test_output_head_closed_forms():
+    """logits = W_out RMSNorm(x): cases whose value is known without running the formula."""
+    H, V = 128, 48
+    cfg = dict(rms_eps=0.0)
+    sc, co = S.weight_matrix(11, 0, S.MAT_OUT, None, V, H)
+    Wd = O.dequant(sc, co)
+    # a one-hot hidden state of any size selects sqrt(H) * one column of W (with its sign):
+    # fails for a transposed operand, a missing norm, or a norm over the wrong axis
+    for j, a in ((0, 3.0), (77, -0.25), (127, 1e3)):
+        x = np.zeros((1, H)); x[0, j] = a
+        np.testing.assert_allclose(O.output_head(x, cfg, (sc, co), mirror=False)[0],
+                                   math.copysign(math.sqrt(H), a) * Wd[:, j], rtol=1e-13)
+    # constant hidden state, constant matrix: K * d * (q - 8) * sign(c)
+    d = np.full((V, H // 32), 0.5, dtype=np.float16)
+    q = np.full((V, H), 11, dtype=np.uint8)
+    for cval in (2.0, -7.0):
+        y = O.output_head(np.full((2, H), cval), cfg, (d, q), mirror=False)
+        np.testing.assert_allclose(y, math.copysign(H * 0.5 * 3, cval), rtol=1e-13)
+    # without eps the logits do not depend on the scale of x; rows are independent
+    x = S.activations(12, 0, 3, H).astype(np.float64)
+    y = O.output_head(x, cfg, (sc, co), mirror=False)
+    np.testing.assert_allclose(O.output_head(x * 37.5, cfg, (sc, co), mirror=False), y, rtol=1e-12)
+    np.testing.assert_allclose(O.output_head(x[1:2], cfg, (sc, co), mirror=False)[0], y[1], rtol=1e-13)
+    # the row of W most aligned with x wins the argmax once it is planted there
+    sc2, co2 = sc.copy(), co.copy()
+    sc2[5] = np.float16(0.05)
+    co2[5] = np.where(x[0] > 0, 15, 0).astype(np.uint8)   # sign pattern of x, largest magnitude
+    assert int(np.argmax(O.output_head(x[:1], cfg, (sc2, co2), mirror=False)[0])) == 5
+    # eps enters as in RMSNorm: x = c * ones gives c / sqrt(c^2 + eps) per element
+    y = O.output_head(np.full((1, H), 0.5), dict(rms_eps=0.75), (d, q), mirror=False)
+    np.testing.assert_allclose(y, H * 1.5 * 0.5 / math.sqrt(0.25 + 0.75), rtol=1e-13)
+
+
+def test_output_head_mirror_rounds_logits_to_fp16_only():
+    H, V = 256, 64
+    cfg = dict(rms_eps=1e-6)
+    head = S.weight_matrix(13, 2, S.MAT_OUT, None, V, H)
+    x = S.activations(14, 0, 4, H)
+    pure = O.output_head(x, cfg, head, mirror=False)
+    mir = O.output_head(x, cfg, head, mirror=True)
+    assert np.array_equal(mir, pure.astype(np.float16).astype(np.float64))
+    assert np.abs(mir - pure).max() <= np.abs(pure).max() * 2.0 ** -11
