@@ -219,6 +219,43 @@ def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps):
     return out
 
 
+def head_leg(B, S, torch, cfg, seed, prof, vocab, budgets, steps):
+    """Decode with the output head (final RMSNorm + projection to `vocab` logits, lowest priority
+    class): at a budget that holds everything it is one more resident GEMV, at a tight one it is the
+    first thing the planner streams."""
+    hcfg = dict(cfg, vocab=vocab)
+    plans = [B.Plan(hcfg, int(b), 1, profile=prof) for b in budgets]
+    stacks = [B.Stack(p) for p in plans]
+    B.load_synthetic(stacks, hcfg, seed, threads=min(16, os.cpu_count() or 8))
+    dev = stacks[0].device
+    xs = [torch.from_numpy(S.activations(seed, 700 + t, 1, hcfg["hidden"])).to(dev) for t in range(4)]
+    xo = torch.empty_like(xs[0])
+    logits = torch.empty(vocab, dtype=torch.float16, device=dev)
+    out = {}
+    for b, plan, st in zip(budgets, plans, stacks):
+        s = plan.summary()
+        st.set_logits_out(logits, 0, 1)
+        n = steps if s.streamed_bytes == 0 else max(3, min(steps, 10))
+        ms = time_steps(torch, st, xs, xo, n, 2)
+        kb, stats = kernel_breakdown(B, st, plan, xs, xo)
+        hk = kb[("kernel", B.PS_K_OUT)]
+        head_bytes = sum(sh.bytes for sh in plan.shards() if sh.kind == B.PS_SHARD_OUT)
+        head_res = sum(sh.bytes for sh in plan.shards() if sh.kind == B.PS_SHARD_OUT and sh.resident)
+        head_ms = hk["avg_ms"] * hk["launches"]
+        r = dict(budget_bytes=int(b), vocab=vocab, ms_per_token=ms, tokens_per_s=1e3 / ms, head_bytes=head_bytes,
+                 head_resident_bytes=head_res, streamed_bytes_per_token=stats.streamed_bytes_step,
+                 head_kernel_ms=head_ms, head_launches=hk["launches"], est_ms=s.est_step_ms)
+        if head_res == head_bytes:
+            r["head_gbps"] = head_bytes / (head_ms * 1e-3) / 1e9
+            r["head_frac_of_hbm_peak"] = r["head_gbps"] / HBM_PEAK_GBS
+        out["%g" % (b / 1e9)] = r
+        log("output head %d, budget %.0f GB: %.3f ms/token, head %.2f of %.2f GB pinned, head kernels %.1f us in %d launches%s, %.2f GB streamed/token" % (
+            vocab, b / 1e9, ms, head_res / 1e9, head_bytes / 1e9, head_ms * 1e3, hk["launches"],
+            (" = %.0f GB/s" % r["head_gbps"]) if "head_gbps" in r else "", stats.streamed_bytes_step / 1e9))
+        st.close()
+    return out
+
+
 def measured_traffic(tag):
     """HBM bytes per launch of the named kernel from the committed rocprofv3 PMC summary
     (profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt); None if the summary is absent."""
@@ -242,9 +279,9 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
-    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv",
+    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv,head",
                     help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
-                         "kv (decode over a 16K-position KV cache)")
+                         "kv (decode over a 16K-position KV cache), head (decode with a 128256-row output head)")
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -353,6 +390,8 @@ def main():
         extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
     if "kv" in args.extra and args.layers == 32:
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50)
+    if "head" in args.extra and args.layers == 32:
+        extra["decode_output_head_128k"] = head_leg(B, S, torch, cfg, seed, prof, 128256, [8e9, 4e9], 100)
     if "moe" in args.extra:
         extra["moe_decode_6gb"] = moe_leg(B, S, torch, seed, prof, 6e9, [1, 16], 10)
 

@@ -49,6 +49,7 @@ extern "C" {
 #define PS_MAT_GATE 2
 #define PS_MAT_UP 3
 #define PS_MAT_DOWN 4
+#define PS_MAT_OUT 5 /* output head [vocab][hidden], loaded with layer = n_layers */
 
 /* shard kinds in a plan.  GATE_UP is gate and up interleaved in 16-row tiles so
  * that one slab yields finished SwiGLU outputs; EXPERT is one whole MoE expert
@@ -59,6 +60,7 @@ extern "C" {
 #define PS_SHARD_DOWN 3
 #define PS_SHARD_EXPERT 4
 #define PS_SHARD_KV 5 /* K and V cache of one kv head of one layer (field `expert` = kv head) */
+#define PS_SHARD_OUT 6 /* N-slab of the output head (class "outputs"); layer field = n_layers */
 
 /* priority classes, in the paper's order (Section 3, planning phase):
  * attention, KV cache, FFN, outputs.  This build has no KV cache or output
@@ -90,6 +92,10 @@ typedef struct ps_model_desc {
     uint32_t kv_context;   /* 0: attention is the identity on V (no cache).  > 0: decode attention over
                               a KV cache with room for kv_context positions per kv head (one new
                               token per forward; plans for more than one token are rejected)        */
+    uint32_t vocab;        /* 0: no output head.  > 0 (multiple of 16): after the last layer the final
+                              hidden state is RMS-normalised and projected to `vocab` logits by one
+                              more 4-bit matrix, whose shards form the lowest priority class
+                              ("outputs", Section 3 planning phase)                                  */
 } ps_model_desc;
 
 /* measured (ps_profile_measure) or caller-supplied machine profile; the
@@ -158,6 +164,7 @@ typedef struct ps_stats {
 #define PS_K_COMBINE 8
 #define PS_K_ATTN 9          /* decode attention over a run of kv-head cache shards          */
 #define PS_K_ATTN_COMBINE 10 /* merge the position chunks, add the new token, append its rows */
+#define PS_K_OUT 11          /* output head: logits = W_out RMSNorm(x_final)                   */
 #define PS_OPF_WAIT_SLOT_FREE 1u  /* copy stream waits for slot_free[slot]        */
 #define PS_OPF_WAIT_ROUTER 2u     /* copy stream waits for router_done[layer]     */
 #define PS_OPF_RECORD_READY 4u    /* copy stream records slot_ready[slot] after   */
@@ -294,6 +301,18 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
 int32_t ps_stack_load_kv(ps_stack *st, uint32_t layer, uint32_t kv_head, const uint16_t *k_rows,
                          const uint16_t *v_rows, uint32_t n_pos);
 int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
+/* Output head (models with vocab > 0; Section 3 planning phase lists the outputs as the last
+ * priority class).  Chooses what the following ps_stack_forward calls compute after the last layer:
+ *   rows == 0         nothing: the head's kernels and the copies of its streamed shards are left
+ *                     out (the state after ps_stack_create; e.g. all but the last prefill chunk);
+ *   rows == 1         logits of token `first_token` only (0 <= first_token < n_tokens), written to
+ *                     logits_dev[0 .. vocab): fused RMSNorm + GEMV, whatever the plan's n_tokens;
+ *   rows == n_tokens  logits of every token, logits_dev[n_tokens][vocab] (first_token must be 0).
+ * logits = W_out * RMSNorm(x_out row), fp32 accumulation, stored fp16.  logits_dev: device memory,
+ * caller-owned, 16-byte aligned, must stay valid for every forward until changed, and must not
+ * overlap the arena, x_in or x_out.  PS_E_STATE if the model has no head, PS_E_ARG for any other
+ * rows / first_token. */
+int32_t ps_stack_set_logits_out(ps_stack *st, void *logits_dev, uint32_t first_token, uint32_t rows);
 /* One pass over the whole stack (Algorithm 1, RunInTopologicalOrder).
  *  x_in, x_out: device fp16 [n_tokens][hidden], caller-owned, may not alias.
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.

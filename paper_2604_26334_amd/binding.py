@@ -12,14 +12,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("PS_LIB", os.path.join(_HERE, "libpshard.so"))
 
 PS_OK, PS_E_ARG, PS_E_BUDGET, PS_E_HIP, PS_E_STATE, PS_E_NOMEM = 0, -1, -2, -3, -4, -5
-PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN = 0, 1, 2, 3, 4
-PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT, PS_SHARD_KV = 0, 1, 2, 3, 4, 5
+PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN, PS_MAT_OUT = 0, 1, 2, 3, 4, 5
+PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT, PS_SHARD_KV, PS_SHARD_OUT = 0, 1, 2, 3, 4, 5, 6
 PS_CLASS_ATTN, PS_CLASS_KVCACHE, PS_CLASS_FFN, PS_CLASS_OUTS = 0, 1, 2, 3
 PS_FLAG_NO_ATTN, PS_FLAG_NO_RESIDUAL = 1, 2
 PS_NTIERS = 11
 PS_OP_COPY, PS_OP_KERNEL = 0, 1
 (PS_K_RINV, PS_K_QKV, PS_K_O, PS_K_GATE_UP, PS_K_DOWN, PS_K_ROUTE, PS_K_EXPERT_GATE_UP,
- PS_K_EXPERT_DOWN, PS_K_COMBINE, PS_K_ATTN, PS_K_ATTN_COMBINE) = range(11)
+ PS_K_EXPERT_DOWN, PS_K_COMBINE, PS_K_ATTN, PS_K_ATTN_COMBINE, PS_K_OUT) = range(12)
 (PS_OPF_WAIT_SLOT_FREE, PS_OPF_WAIT_ROUTER, PS_OPF_RECORD_READY, PS_OPF_WAIT_READY,
  PS_OPF_RECORD_FREE, PS_OPF_RECORD_ROUTER) = 1, 2, 4, 8, 16, 32
 NO_EXPERT = 0xFFFFFFFF
@@ -28,7 +28,7 @@ NO_EXPERT = 0xFFFFFFFF
 class ps_model_desc(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
                                           "ffn_inter", "n_experts", "top_k", "expert_inter", "flags")] + \
-               [("rms_eps", C.c_float), ("kv_context", C.c_uint32)]
+               [("rms_eps", C.c_float), ("kv_context", C.c_uint32), ("vocab", C.c_uint32)]
 
 
 class ps_profile(C.Structure):
@@ -76,7 +76,8 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
-           "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context"]
+           "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
+           "ps_stack_set_logits_out"]
 
 _lib = None
 
@@ -129,6 +130,7 @@ def lib():
             "ps_tier_pick": [vp, u32, C.POINTER(ps_tier_choice)],
             "ps_stack_load_kv": [vp, u32, u32, vp, vp, u32],
             "ps_stack_set_context": [vp, u32],
+            "ps_stack_set_logits_out": [vp, vp, u32, u32],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -158,7 +160,7 @@ def model_desc(cfg):
     flags = (PS_FLAG_NO_ATTN if cfg.get("no_attn") else 0) | (PS_FLAG_NO_RESIDUAL if cfg.get("no_residual") else 0)
     return ps_model_desc(cfg["n_layers"], cfg["hidden"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
                          cfg["ffn_inter"], cfg["n_experts"], cfg["top_k"], cfg["expert_inter"], flags,
-                         cfg["rms_eps"], int(cfg.get("kv_context", 0)))
+                         cfg["rms_eps"], int(cfg.get("kv_context", 0)), int(cfg.get("vocab", 0)))
 
 
 def make_profile(h2d_gbps=55.0, gemv_gbps=4000.0, gemm_tflops=400.0, launch_us=3.0):
@@ -317,11 +319,12 @@ class TierTable:
             pass
 
 
-def chunked_forward(stack, x_in, x_out, router_logits=None):
+def chunked_forward(stack, x_in, x_out, router_logits=None, logits_out=None):
     """Run n = x_in.shape[0] tokens through a stack planned for T = stack.M tokens as ceil(n / T)
     trips through its schedule (chunked prefill with the tier size as chunk size).  Only slices and
     pads: full chunks are passed in place, the last partial chunk goes through zero-padded T-row
-    buffers.  Asynchronous on stack.compute like Stack.forward."""
+    buffers.  logits_out (fp16 [vocab], models with an output head): the head runs on the last trip
+    only, for the last real token.  Asynchronous on stack.compute like Stack.forward."""
     torch = stack.torch
     n, T = int(x_in.shape[0]), stack.M
     assert tuple(x_in.shape) == (n, stack.H) and tuple(x_out.shape) == (n, stack.H)
@@ -332,6 +335,8 @@ def chunked_forward(stack, x_in, x_out, router_logits=None):
         if lg is not None:
             l = np.zeros((lg.shape[0], T, lg.shape[2]), dtype=np.float32)
             l[:, :r1 - r0] = lg[:, r0:r1]
+        if logits_out is not None:
+            stack.set_logits_out(logits_out if r1 == n else None, n - 1 - r0 if r1 == n else 0, 1 if r1 == n else 0)
         if r1 - r0 == T:
             stack.forward(x_in[r0:r1], x_out[r0:r1], l)
             continue
@@ -384,6 +389,14 @@ class Stack:
 
     def set_context(self, context):
         _check(lib().ps_stack_set_context(self.h, int(context)))
+
+    def set_logits_out(self, logits, first_token=0, rows=1):
+        """logits: torch fp16 CUDA tensor of rows * vocab elements (kept alive by the caller), or None
+        with rows = 0 to leave the output head out of the following forwards."""
+        if rows:
+            assert logits.dtype == self.torch.float16 and logits.is_contiguous()
+            assert logits.numel() == rows * self.plan.cfg["vocab"]
+        _check(lib().ps_stack_set_logits_out(self.h, logits.data_ptr() if rows else None, int(first_token), int(rows)))
 
     def forward(self, x_in, x_out, router_logits=None):
         """x_in, x_out: torch fp16 CUDA tensors [M][H]; asynchronous on self.compute."""
@@ -476,6 +489,8 @@ def load_synthetic(stacks, cfg, seed, threads=8, lookahead=12, progress=None):
     stacks = stacks if isinstance(stacks, (list, tuple)) else [stacks]
     todo = [(layer, kind, expert, N, K) for layer in range(cfg["n_layers"])
             for (kind, expert, N, K) in S.matrix_shapes(cfg)]
+    if cfg.get("vocab"):   # output head: a matrix of the layer after the last
+        todo.append((cfg["n_layers"], S.MAT_OUT, None, cfg["vocab"], cfg["hidden"]))
     with ThreadPoolExecutor(max_workers=threads) as ex:
         q = collections.deque()
         it = iter(todo)

@@ -83,6 +83,11 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
     g.gate_up = make_geom(2 * g.ffn_i, m->hidden, true);
     g.down = make_geom(m->hidden, g.ffn_i, false);
     g.expert_bytes = g.moe ? g.gate_up.bytes + g.down.bytes : 0;
+    if (m->vocab) {
+        if (m->vocab % kTileRows || m->vocab > (1u << 20)) { set_error("vocab=%u must be a multiple of 16, <= 2^20", m->vocab); return PS_E_ARG; }
+        g.head = make_geom(m->vocab, m->hidden, false);
+        if (g.head.bytes > 0xFFFFFFFFull) { set_error("output head too large"); return PS_E_ARG; }
+    }
     *out = g;
     return PS_OK;
 }
@@ -130,7 +135,7 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M) {
         w.s = take(w.s_bytes);
     }
     uint64_t pb = 0;   // fp32 partial planes of the split-K batched-decode GEMMs (attention matrices; dense FFN)
-    for (const MatGeom *mg : {&g.qkv, &g.o, &g.gate_up, &g.down}) {
+    for (const MatGeom *mg : {&g.qkv, &g.o, &g.gate_up, &g.down, &g.head}) {
         if (!mg->ntiles || (g.moe && (mg == &g.gate_up || mg == &g.down))) continue;
         const uint32_t per = gemm_sb_per_part(*mg, M);
         if (per) pb = std::max<uint64_t>(pb, (uint64_t)((mg->nsb + per - 1) / per) * M * mg->rows * 4);
@@ -235,6 +240,12 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
             c.freq = freq ? freq[(size_t)l * m.n_experts + e] : 0.0;
             cands.push_back(c);
         }
+    }
+    if (m.vocab) {   // the output head, after the last layer, lowest priority class
+        Cand c{};
+        c.s.layer = m.n_layers; c.s.kind = PS_SHARD_OUT; c.s.cls = PS_CLASS_OUTS; c.s.ntiles = g.head.ntiles;
+        c.s.bytes = g.head.bytes; c.quantum_tiles = g.head.quantum_tiles; c.tile_bytes = g.head.tile_bytes; c.freq = 0;
+        cands.push_back(c);
     }
     p->weight_bytes = 0;
     uint64_t max_unit = 0;  // smallest thing a slot must be able to hold

@@ -37,7 +37,7 @@ struct ModelGeom {
     bool has_attn = false, moe = false, kv = false;   // kv: real attention over a KV cache
     uint64_t kv_shard_bytes = 0;                      // K + V of one kv head at full capacity
     uint32_t qkv_w = 0, attn_w = 0, ffn_i = 0;
-    MatGeom qkv, o, gate_up, down;  // gate_up/down are per expert for MoE
+    MatGeom qkv, o, gate_up, down, head;  // gate_up/down are per expert for MoE; head: output projection
     uint64_t expert_bytes = 0;
 };
 int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out);

@@ -206,6 +206,10 @@ struct Builder {
             batch_open = false;
             add_plain(PS_K_COMBINE, l);
         }
+        if (m.vocab) {   // output head on the final hidden state (its own RMS factor when several tokens)
+            if (M > 1) add_plain(PS_K_RINV, m.n_layers, 0, 2);
+            add_matrix_kernels(PS_K_OUT, m.n_layers, PS_SHARD_OUT, si);
+        }
         if (si != p->shards.size()) { set_error("internal: schedule did not consume every shard"); return PS_E_STATE; }
 
         // wait/record flags on kernels, batch boundaries

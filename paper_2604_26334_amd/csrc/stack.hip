@@ -50,7 +50,9 @@ struct ps_stack {
     void *tables_host[2] = {nullptr, nullptr};   // pinned: logits | tasks | pairs | copy descriptors of one forward (MoE)
     uint64_t tables_bytes = 0;
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
-    std::map<std::pair<const void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out)
+    std::map<std::tuple<const void *, void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out, logits)
+    __half *logits = nullptr;                 // output head: caller's logits buffer
+    uint32_t head_rows = 0, head_row0 = 0;    // 0: head skipped, 1: token head_row0 only, n_tokens: every token
     uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
     hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
     bool step_pending = false;
@@ -88,6 +90,7 @@ const MatGeom &geom_of(const ModelGeom &g, uint32_t mat) {
         case PS_MAT_QKV: return g.qkv;
         case PS_MAT_O: return g.o;
         case PS_MAT_DOWN: return g.down;
+        case PS_MAT_OUT: return g.head;
         default: return g.gate_up;
     }
 }
@@ -174,6 +177,15 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         return a;
     };
 
+    if (op.info.kernel == PS_K_OUT && st->head_rows == 1) {
+        // logits of one token: fused RMSNorm + GEMV over its row of the final hidden state
+        const Shard &s = p.shards[op.info.shard0];
+        GemvArgs a = gemv_base(g.head);
+        a.top_k = 1; a.W = wptr(op); a.nunits = s.ntiles; a.x = x_out + (size_t)st->head_row0 * H;
+        a.out = st->logits; a.out_row0 = s.tile0 * 16;
+        PS_HIP(launch_gemv(GEMV_PLAIN, gemv_ksplit(g.head.ngroups, g.head.ntiles), a, 0, cs));
+        return PS_OK;
+    }
     if (M == 1 && op.info.kernel >= PS_K_QKV && op.info.kernel <= PS_K_DOWN) {
         GemvArgs a;
         int mode;
@@ -199,8 +211,16 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     };
     switch (op.info.kernel) {
         case PS_K_RINV:
-            PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
+            if (op.info.shard0 == 2) PS_HIP(launch_rinv(x_out, M, H, m.rms_eps, rinv, cs));   // output head
+            else PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
             return PS_OK;
+        case PS_K_OUT: {   // every token's logits (head_rows == M > 1)
+            const Shard &s = p.shards[op.info.shard0];
+            GemmArgs a = gemm_base(g.head);
+            a.W = wptr(op); a.ntiles = s.ntiles; a.x = x_out; a.x_stride = H; a.out = st->logits;
+            a.out_stride = m.vocab; a.out_row0 = s.tile0 * 16;
+            return run_gemm(GEMM_PLAIN, a, g.head);
+        }
         case PS_K_QKV: {
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.qkv);
@@ -287,6 +307,16 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     return PS_E_STATE;
 }
 
+// Ops of the output head (layer index n_layers) that this forward leaves out: all of them, copies
+// included, when no logits are asked for; the RMS factors of every token when only one token's
+// is.  The head's slot fills hold head shards only and nothing follows them, so leaving a fill out
+// together with its kernels keeps every event wait paired with the record it was built for.
+bool skip_head_op(const ps_stack *st, const Op &op) {
+    if (op.info.layer != st->plan.g.m.n_layers) return false;
+    if (st->head_rows == 0) return true;
+    return st->head_rows == 1 && op.info.type == PS_OP_KERNEL && op.info.kernel == PS_K_RINV;
+}
+
 int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __half *x_out) {
     const ps_plan &p = st->plan;
     const bool prof = st->profiling;
@@ -304,7 +334,8 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     if (st->use_graph && !prof) {
         // Launch-bound case (every shard resident, one token): the kernel sequence is captured
         // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
-        auto key = std::make_pair(static_cast<const void *>(x_in), static_cast<void *>(x_out));
+        auto key = std::make_tuple(static_cast<const void *>(x_in), static_cast<void *>(x_out),
+                                   static_cast<void *>(st->head_rows ? st->logits : nullptr));
         auto it = st->graphs.find(key);
         if (it == st->graphs.end()) {
             if (st->graphs.size() >= 32) {
@@ -315,6 +346,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             PS_HIP(hipStreamBeginCapture(st->compute, hipStreamCaptureModeThreadLocal));
             int32_t rc = PS_OK;
             for (const Op &op : sc.ops) {
+                if (skip_head_op(st, op)) continue;
                 rc = issue_kernel(st, sc, op, x_in, x_out);
                 if (rc) break;
             }
@@ -328,13 +360,20 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             it = st->graphs.emplace(key, exec).first;
         }
         PS_HIP(hipGraphLaunch(it->second, st->compute));
-        for (const Op &op : sc.ops) ss.resident_bytes_step += op.info.bytes;
-        ss.n_kernels = (uint32_t)sc.ops.size();
+        for (const Op &op : sc.ops)
+            if (!skip_head_op(st, op)) { ss.resident_bytes_step += op.info.bytes; ss.n_kernels++; }
         return PS_OK;
     }
     for (size_t i = 0; i < sc.ops.size(); ++i) {
         const Op &op = sc.ops[i];
         const ps_op_info &o = op.info;
+        if (skip_head_op(st, op)) {
+            if (prof) {   // keeps one (empty) interval per op
+                PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
+                PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->compute));
+            }
+            continue;
+        }
         if (o.type == PS_OP_COPY) {
             if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
             if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
@@ -440,7 +479,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     for (size_t i = 0; i < p.shards.size(); ++i)
         st->cover[std::make_tuple(p.shards[i].layer, p.shards[i].kind, p.shards[i].expert)].push_back((uint32_t)i);
     const uint32_t per_layer = (p.g.has_attn ? 2 : 0) + 3 * (p.g.moe ? m.n_experts : 1);
-    st->n_expected = (uint64_t)per_layer * m.n_layers;
+    st->n_expected = (uint64_t)per_layer * m.n_layers + (m.vocab ? 1 : 0);
     st->loaded.assign(st->n_expected, 0);
 
     for (int s = 0; s < 2; ++s) {
@@ -496,19 +535,23 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
     const ps_plan &p = st->plan;
     const ps::ModelGeom &g = p.g;
     const auto &m = g.m;
-    if (layer >= m.n_layers || mat > PS_MAT_DOWN) { ps::set_error("bad layer/matrix id"); return PS_E_ARG; }
+    const bool is_head = mat == PS_MAT_OUT;
+    if (is_head ? (!m.vocab || layer != m.n_layers) : (layer >= m.n_layers || mat > PS_MAT_DOWN)) {
+        ps::set_error("bad layer/matrix id"); return PS_E_ARG;
+    }
     const bool is_attn = mat == PS_MAT_QKV || mat == PS_MAT_O;
     if (is_attn && !g.has_attn) { ps::set_error("model has no attention matrices"); return PS_E_ARG; }
-    if (g.moe && !is_attn) {
+    if (g.moe && !is_attn && !is_head) {
         if (expert >= m.n_experts) { ps::set_error("expert id %u out of range", expert); return PS_E_ARG; }
     } else if (expert != ps::kNoExpert) {
         ps::set_error("expert must be 0xFFFFFFFF for this matrix"); return PS_E_ARG;
     }
     uint32_t kind;
     if (is_attn) kind = mat == PS_MAT_QKV ? PS_SHARD_QKV : PS_SHARD_O;
+    else if (is_head) kind = PS_SHARD_OUT;
     else if (g.moe) kind = PS_SHARD_EXPERT;
     else kind = mat == PS_MAT_DOWN ? PS_SHARD_DOWN : PS_SHARD_GATE_UP;
-    auto it = st->cover.find(std::make_tuple(layer, kind, g.moe && !is_attn ? expert : ps::kNoExpert));
+    auto it = st->cover.find(std::make_tuple(layer, kind, kind == PS_SHARD_EXPERT ? expert : ps::kNoExpert));
     if (it == st->cover.end()) { ps::set_error("internal: no shard covers this matrix"); return PS_E_STATE; }
     const ps::MatGeom &mg = geom_of(g, mat);
     const bool paired = mat == PS_MAT_GATE || mat == PS_MAT_UP;
@@ -550,7 +593,8 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
     }
     const uint32_t per_layer = (g.has_attn ? 2 : 0) + 3 * (g.moe ? m.n_experts : 1);
     uint32_t slot;
-    if (is_attn) slot = mat == PS_MAT_QKV ? 0 : 1;
+    if (is_head) slot = 0;   // the one entry after the last layer's
+    else if (is_attn) slot = mat == PS_MAT_QKV ? 0 : 1;
     else slot = (g.has_attn ? 2 : 0) + 3 * (g.moe ? expert : 0) + (mat - PS_MAT_GATE);
     uint8_t &flag = st->loaded[(size_t)layer * per_layer + slot];
     if (!flag) { flag = 1; st->n_loaded++; }
@@ -594,6 +638,25 @@ int32_t ps_stack_set_context(ps_stack *st, uint32_t context) {
         return PS_E_ARG;
     }
     st->ctx = context;
+    return PS_OK;
+}
+
+int32_t ps_stack_set_logits_out(ps_stack *st, void *logits_dev, uint32_t first_token, uint32_t rows) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    if (!p.g.m.vocab) { ps::set_error("this stack has no output head (vocab is 0)"); return PS_E_STATE; }
+    if (rows != 0 && rows != 1 && rows != p.M) {
+        ps::set_error("logits rows must be 0, 1 or the plan's %u tokens (got %u)", p.M, rows); return PS_E_ARG;
+    }
+    if (rows && (first_token >= p.M || (rows == p.M && first_token != 0))) {
+        ps::set_error("logits of tokens %u..%u asked from a plan of %u tokens", first_token, first_token + rows - 1, p.M);
+        return PS_E_ARG;
+    }
+    if (rows && !logits_dev) { ps::set_error("logits buffer is NULL"); return PS_E_ARG; }
+    if (rows && (uintptr_t)logits_dev % 16) { ps::set_error("logits buffer must be 16-byte aligned"); return PS_E_ARG; }
+    st->logits = rows ? static_cast<__half *>(logits_dev) : nullptr;
+    st->head_rows = rows;
+    st->head_row0 = rows ? first_token : 0;
     return PS_OK;
 }
 
@@ -726,6 +789,7 @@ int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur
 int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, double *avg_launch_ms, uint32_t *launches) {
     if (!st || !avg_launch_ms || !launches || reps == 0) { ps::set_error("bad argument"); return PS_E_ARG; }
     if (!st->have_dense_sched || st->n_loaded != st->n_expected) { ps::set_error("needs a loaded dense stack"); return PS_E_STATE; }
+    if (kernel == PS_K_OUT && !st->head_rows) { ps::set_error("timing the output head needs a logits buffer"); return PS_E_STATE; }
     const ps_plan &p = st->plan;
     // activations: the workspace ping-pong buffers stand in for the caller's tensors
     const __half *xin = reinterpret_cast<const __half *>(st->arena + p.ws.x0);

@@ -164,3 +164,55 @@ def test_dense8b_decode_over_a_4k_kv_cache():
     for got in outs[1:]:
         for a, b in zip(got, outs[0]):
             np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_full_vocabulary_output_head_decode_and_prefill():
+    """Two 8B-shaped layers and a 128256-row output head (8016 row tiles).  One token: all logits
+    against the oracle, head pinned / split / streamed in slabs.  2048 tokens: every token's logits
+    are computed; three sampled tokens are compared over the whole vocabulary."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = dict(S.cfg_dense8b(2), vocab=128256)
+    seed = 17
+    W = Hn.WeightCache(cfg, seed, keep=True)
+    head = S.head_matrix(seed, cfg)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    for M, rows, fracs in ((1, [0], (1.0, 0.75, 0.3)), (2048, [0, 1033, 2047], (1.0, 0.4))):
+        x = S.activations(seed, 2, M, cfg["hidden"])     # a draw whose sampled rows stay inside fp16 (see _run)
+        ref_x = O.stack_forward(x[rows], cfg, W, mirror=True)
+        assert np.isfinite(ref_x).all()
+        ref_l = O.output_head(ref_x, cfg, head, mirror=True)
+        ws = B.Plan(cfg, 1 << 40, M).summary().workspace_bytes
+        first = None
+        for f in fracs:
+            plan = B.Plan(cfg, int(full.weight_bytes * f) + ws + (1 << 20), M)
+            st = B.Stack(plan)
+            B.load_synthetic(st, cfg, seed, threads=16)
+            hs = [s for s in plan.shards() if s.kind == B.PS_SHARD_OUT]
+            xin = torch.from_numpy(x).to(st.device)
+            xout = torch.empty_like(xin)
+            logits = torch.zeros((M, cfg["vocab"]), dtype=torch.float16, device=st.device)
+            st.set_logits_out(logits, 0, M)
+            torch.cuda.synchronize()
+            st.forward(xin, xout)
+            st.synchronize()
+            lo = logits[rows].cpu().numpy()
+            xo = xout[rows].cpu().numpy()
+            alone = O.output_head(xo, cfg, head, mirror=True)
+            e2e, e1 = Hn.rel_err(lo, ref_l), Hn.rel_err(lo, alone)
+            _say("  M %d frac %.2f: head shards %d (%d pinned), streamed/step %.3f GB, err end-to-end %.3e, head alone %.3e" % (
+                M, f, len(hs), sum(1 for s in hs if s.resident), st.stats().streamed_bytes_step / 1e9, e2e, e1))
+            assert e2e <= TOL and e1 <= TOL
+            assert [int(np.argmax(r.astype(np.float64))) for r in lo] == [int(np.argmax(r)) for r in alone]
+            if M > 1:   # one-token request on the same stack: same token, GEMV instead of GEMM
+                one = torch.zeros(cfg["vocab"], dtype=torch.float16, device=st.device)
+                st.set_logits_out(one, rows[1], 1)
+                st.forward(xin, xout)
+                st.synchronize()
+                assert Hn.rel_err(one.cpu().numpy(), alone[1]) <= TOL
+            if first is None:
+                first = lo
+            else:
+                np.testing.assert_array_equal(lo.view(np.uint16), first.view(np.uint16))
+            st.close()
+            plan.close()

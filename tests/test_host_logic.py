@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(B.ps_model_desc) == 48
+    assert C.sizeof(B.ps_model_desc) == 52
     assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS)
     assert C.sizeof(B.ps_shard_info) == 48
     assert C.sizeof(B.ps_op_info) == 48
@@ -381,3 +381,69 @@ def test_kv_cache_plans_are_one_token_only():
     bad = dict(cfg, no_attn=True)
     with pytest.raises(B.PshardError):
         B.Plan(bad, 1 << 40, 1)
+
+
+# ---------------------------------------------------------------- output head ("outputs" class)
+
+def _head_cfg(vocab=1040, **kw):
+    return dict(_kv_cfg(**kw), kv_context=0, vocab=vocab)
+
+
+def test_output_head_is_the_lowest_priority_class_and_runs_last():
+    # Section 3, planning phase: priority attention > KV cache > FFN > outputs
+    cfg = _head_cfg(vocab=8192)   # the head is the largest matrix: a small shortfall costs only head slabs
+    full = B.Plan(cfg, 1 << 40, 1)
+    sh = full.shards()
+    out = [s for s in sh if s.kind == B.PS_SHARD_OUT]
+    assert len(out) == 1 and out[0].cls == B.PS_CLASS_OUTS and out[0].layer == cfg["n_layers"]
+    assert out[0].bytes == B.lib().ps_packed_bytes(cfg["vocab"], cfg["hidden"])
+    assert out[0].priority_rank == len(sh) - 1 and sh[-1].kind == B.PS_SHARD_OUT
+    base = B.Plan(dict(cfg, vocab=0), 1 << 40, 1).summary()
+    assert full.summary().weight_bytes == base.weight_bytes + out[0].bytes
+    # a budget just short of everything: head slabs are what gets streamed, nothing else
+    need = full.summary().workspace_bytes + full.summary().weight_bytes
+    lo = None
+    for budget in range(need - 1, need // 2, -4096):
+        try:
+            lo = B.Plan(cfg, budget, 1)
+        except B.PshardError:
+            continue
+        if lo.summary().n_slots:
+            break
+    streamed = [s for s in lo.shards() if not s.resident]
+    assert streamed and all(s.kind == B.PS_SHARD_OUT for s in streamed)
+    ops = lo.schedule().ops()
+    assert lo.schedule().validate() is None
+    kern = [o for o in ops if o.type == B.PS_OP_KERNEL]
+    head = [o for o in kern if o.kernel == B.PS_K_OUT]
+    assert head and all(o.layer == cfg["n_layers"] for o in head)
+    assert kern.index(head[0]) == len(kern) - len(head)          # nothing after the head's kernels
+    tiles = sum(lo.shards()[o.shard0].ntiles for o in head)
+    assert tiles == cfg["vocab"] // 16
+    # several tokens: the head gets its own RMS factors right before it
+    ops16 = [o for o in B.Plan(cfg, 1 << 40, 16).schedule().ops() if o.type == B.PS_OP_KERNEL]
+    i = [o.kernel for o in ops16].index(B.PS_K_OUT)
+    assert ops16[i - 1].kernel == B.PS_K_RINV and ops16[i - 1].layer == cfg["n_layers"]
+
+
+def test_output_head_streams_through_the_slots_when_nothing_is_pinned():
+    cfg = _head_cfg(vocab=4096)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    tight = B.Plan(cfg, full.workspace_bytes + full.weight_bytes // 6, 1)
+    sched = tight.schedule()
+    assert sched.validate() is None
+    ops = sched.ops()
+    copies = [o for o in ops if o.type == B.PS_OP_COPY and o.layer == cfg["n_layers"]]
+    kern = [o for o in ops if o.type == B.PS_OP_KERNEL and o.kernel == B.PS_K_OUT]
+    assert copies and sum(o.bytes for o in copies) == sum(o.bytes for o in kern if o.slot >= 0)
+    moe = dict(S.cfg_moe(2), n_experts=8, top_k=2, vocab=2048)
+    lg = S.router_logits(1, 0, 2, 4, 8)
+    pm = B.Plan(moe, 1 << 40, 4)
+    assert pm.shards()[-1].kind == B.PS_SHARD_OUT
+    assert pm.schedule(lg).validate() is None
+
+
+def test_output_head_argument_checks():
+    for vocab in (1000, 8, (1 << 20) + 16):
+        with pytest.raises(B.PshardError):
+            B.Plan(_head_cfg(vocab=vocab), 1 << 40, 1)
