@@ -63,12 +63,20 @@ extern "C" {
 #define PS_SHARD_OUT 6 /* N-slab of the output head (class "outputs"); layer field = n_layers */
 
 /* priority classes, in the paper's order (Section 3, planning phase):
- * attention, KV cache, FFN, outputs.  This build has no KV cache or output
- * head, the values are kept so ranks compare the same way. */
+ * attention, KV cache, FFN, outputs. */
 #define PS_CLASS_ATTN 0
 #define PS_CLASS_KVCACHE 1
 #define PS_CLASS_FFN 2
 #define PS_CLASS_OUTS 3
+
+/* where the shards that are not pinned run (Section 3, the three schedule plans) */
+#define PS_PLAN_GPU_ONLY 0 /* Plan One: all on the GPU, streamed through the VRAM scratch double buffer */
+#define PS_PLAN_STATIC 1   /* Plan Two: unpinned FFN / output shards stay in system memory and run on
+                              the CPU; only activations cross PCIe; no scratch unless an attention or
+                              cache shard is unpinned                                                 */
+#define PS_PLAN_DYNAMIC 2  /* Plan Three: each unpinned FFN / output matrix is split, part streamed to
+                              the GPU and part run on the CPU at the same time                        */
+#define PS_PLAN_AUTO 3     /* HeuristicSplit: build all three, keep the one with the lowest estimate  */
 
 #define PS_FLAG_NO_ATTN 1u     /* layers have no attention sub-layer (FFN block only) */
 #define PS_FLAG_NO_RESIDUAL 2u /* FFN output is not added to its input                */
@@ -106,6 +114,16 @@ typedef struct ps_profile {
     double gemv_gbps;              /* weight bytes/s the decode kernels sustain  */
     double gemm_tflops[PS_NTIERS]; /* dequant-GEMM rate at each token tier       */
     double launch_us;              /* fixed cost per kernel launch               */
+    /* CPU back-end (plans Two and Three); cpu_gbps == 0 means "no CPU back-end": such plans are
+     * rejected and PS_PLAN_AUTO keeps Plan One */
+    double cpu_gbps;               /* packed weight bytes/s of the CPU kernel, one token, alone     */
+    double cpu_gbps_busy;          /* the same while H2D weight copies run (shared memory controller;
+                                      Section 3, Plan Three); 0: use cpu_gbps                        */
+    double h2d_gbps_busy;          /* H2D copy rate while the CPU kernel runs; 0: use h2d_gbps      */
+    double cpu_tokens_free;        /* tokens up to which the CPU kernel stays memory-bound: its time
+                                      is priced bytes / rate * max(1, n_tokens / cpu_tokens_free)    */
+    double cpu_sync_us;            /* fixed cost of one CPU shard: activations to the host, wake-up,
+                                      result back                                                    */
 } ps_profile;
 
 typedef struct ps_shard_info {
@@ -115,7 +133,8 @@ typedef struct ps_shard_info {
     uint32_t cls;           /* PS_CLASS_*                                        */
     uint32_t tile0;         /* first 16-row tile of the slab within its matrix   */
     uint32_t ntiles;        /* number of 16-row tiles (EXPERT: gate/up + down)   */
-    uint32_t resident;      /* 1 = pinned in VRAM, 0 = pinned host, streamed     */
+    uint32_t resident;      /* 1 = pinned in VRAM; 0 = in pinned host memory, streamed to the
+                               scratch before each use; 2 = in pinned host memory, run on the CPU */
     uint32_t priority_rank; /* position in the priority order (0 = first)        */
     uint64_t bytes;         /* packed bytes of this shard                        */
     uint64_t offset;        /* resident: byte offset in the arena; streamed:
@@ -136,6 +155,13 @@ typedef struct ps_plan_summary_t {
     uint32_t tier;            /* index into the tier table used for the estimate */
     double est_step_ms;       /* sum over shards of max(compute, next copy)      */
     double est_streamed_bytes_per_step; /* expected bytes crossing PCIe per step */
+    uint64_t cpu_bytes;       /* shards run on the CPU (subset of streamed_bytes' complement: counted
+                                 in neither resident_bytes nor streamed_bytes)                       */
+    uint32_t plan_kind;       /* PS_PLAN_GPU_ONLY / STATIC / DYNAMIC: what this plan is              */
+    uint32_t pad;
+    double cpu_fraction;      /* Plan Three: share of each unpinned FFN / output matrix on the CPU   */
+    double est_kind_ms[3];    /* PS_PLAN_AUTO: the estimate of each of the three plans, < 0 where a
+                                 plan could not be built; otherwise only [plan_kind] is filled       */
 } ps_plan_summary_t;
 
 typedef struct ps_stats {
@@ -148,11 +174,22 @@ typedef struct ps_stats {
     double wall_ms;     /* first op start to last op end                         */
     double overlap;     /* (copy + compute - wall) / min(copy, compute), 0 if either is 0 */
     double h2d_gbps;    /* streamed_bytes_step / copy_ms                         */
+    uint64_t cpu_bytes_step; /* weight bytes read by the CPU back-end in the last forward           */
+    double cpu_ms;      /* host time inside the CPU kernel in the last forward (always valid)       */
+    double cpu_wait_ms; /* host time waiting for activations to arrive from the GPU (always valid)  */
 } ps_stats;
 
 /* one operation of an executor schedule, as plain data (see ps_schedule_*) */
 #define PS_OP_COPY 0
 #define PS_OP_KERNEL 1
+#define PS_OP_CPU 2   /* one shard computed by the CPU back-end (kernel = the sub-layer, PS_K_*), its
+                         result uploaded on the compute stream; the host blocks while it computes   */
+#define PS_OP_FETCH 3 /* compute stream copies the activation buffers in `buffers` to the host and the
+                         host waits for them: issued before the GPU kernels of a matrix that also has
+                         a CPU shard, so both sides then work on the matrix at the same time        */
+#define PS_BUF_H 1u   /* FFN input (the attention half's output)     */
+#define PS_BUF_S 2u   /* SwiGLU output (the down projection's input) */
+#define PS_BUF_X 4u   /* final hidden state (the output head's input) */
 #define PS_K_RINV 0
 #define PS_K_QKV 1
 #define PS_K_O 2
@@ -180,6 +217,7 @@ typedef struct ps_op_info {
     int32_t slot;    /* scratch slot touched, -1 if none                         */
     uint32_t shard0; /* first plan shard this op copies / reads                  */
     uint32_t nshards;/* number of consecutive task entries (expert batches) or 1 */
+    uint32_t buffers;/* PS_BUF_*: FETCH copies these to the host, CPU reads these there */
     uint64_t slot_offset; /* byte offset inside the slot (copy destination / kernel source) */
     uint64_t bytes;  /* weight bytes copied or read                              */
 } ps_op_info;
@@ -216,6 +254,17 @@ int32_t ps_pack_matrix(const uint16_t *scales, const uint8_t *codes, uint32_t ro
 int32_t ps_plan_create(const ps_model_desc *model, uint64_t vram_budget_bytes,
                        const ps_profile *profile, uint32_t n_tokens,
                        const float *expert_freq, ps_plan **out);
+/* The same for one of the three schedule plans of Section 3 (kind = PS_PLAN_*), or, with
+ * PS_PLAN_AUTO, HeuristicSplit: all three are built and the one with the lowest estimated time
+ * is returned (its summary lists the three estimates).  Plans Two and Three place the unpinned
+ * parts of dense FFN matrices and of the output head on the CPU back-end (attention matrices, KV
+ * caches and MoE experts always run on the GPU); Plan Three chooses the CPU share of each such
+ * matrix, one value for the whole plan, that minimises the estimate.  They need a profile with
+ * cpu_gbps > 0 and a host CPU the back-end supports (PS_E_STATE otherwise; PS_PLAN_AUTO then
+ * returns Plan One). */
+int32_t ps_plan_create_kind(const ps_model_desc *model, uint64_t vram_budget_bytes,
+                            const ps_profile *profile, uint32_t n_tokens,
+                            const float *expert_freq, uint32_t kind, ps_plan **out);
 int32_t ps_plan_summary(const ps_plan *plan, ps_plan_summary_t *out);
 /* shards are listed in execution (topological) order */
 int32_t ps_plan_get_shard(const ps_plan *plan, uint32_t i, ps_shard_info *out);
@@ -313,6 +362,18 @@ int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
  * overlap the arena, x_in or x_out.  PS_E_STATE if the model has no head, PS_E_ARG for any other
  * rows / first_token. */
 int32_t ps_stack_set_logits_out(ps_stack *st, void *logits_dev, uint32_t first_token, uint32_t rows);
+/* The CPU back-end's matrix kernel on its own (host pointers only; for tests and for measuring
+ * the CPU rate): `packed` is ps_pack_matrix's image of a [rows][K] matrix; x fp16 [n_tokens][K];
+ * out fp16 [n_tokens][rows] (mode 2: [n_tokens][rows / 2]).  mode 0: out = W RMSNorm(x);
+ * mode 1: out = W x + res (res fp16 [n_tokens][rows] or NULL); mode 2: the matrix holds gate and
+ * up row-tiles alternately (16 gate rows, 16 up rows, ...) and out = SiLU(g) * u of
+ * g, u = W RMSNorm(x).  fp32 accumulation, n_tokens <= 64, 1 <= threads <= 64.
+ * PS_E_STATE if the CPU lacks AVX-512 / F16C. */
+int32_t ps_cpu_matmul(const uint8_t *packed, uint32_t rows, uint32_t K, int32_t mode, const uint16_t *x,
+                      uint32_t n_tokens, float eps, const uint16_t *res, uint16_t *out, uint32_t threads);
+/* Worker threads of the CPU back-end (plans with CPU shards), 1..64; default min(hardware
+ * threads, 16).  PS_E_STATE if the plan has no CPU shard. */
+int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads);
 /* One pass over the whole stack (Algorithm 1, RunInTopologicalOrder).
  *  x_in, x_out: device fp16 [n_tokens][hidden], caller-owned, may not alias.
  *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.

@@ -16,8 +16,10 @@ PS_MAT_QKV, PS_MAT_O, PS_MAT_GATE, PS_MAT_UP, PS_MAT_DOWN, PS_MAT_OUT = 0, 1, 2,
 PS_SHARD_QKV, PS_SHARD_O, PS_SHARD_GATE_UP, PS_SHARD_DOWN, PS_SHARD_EXPERT, PS_SHARD_KV, PS_SHARD_OUT = 0, 1, 2, 3, 4, 5, 6
 PS_CLASS_ATTN, PS_CLASS_KVCACHE, PS_CLASS_FFN, PS_CLASS_OUTS = 0, 1, 2, 3
 PS_FLAG_NO_ATTN, PS_FLAG_NO_RESIDUAL = 1, 2
+PS_PLAN_GPU_ONLY, PS_PLAN_STATIC, PS_PLAN_DYNAMIC, PS_PLAN_AUTO = 0, 1, 2, 3
+PS_OP_COPY, PS_OP_KERNEL, PS_OP_CPU, PS_OP_FETCH = 0, 1, 2, 3
+PS_BUF_H, PS_BUF_S, PS_BUF_X = 1, 2, 4
 PS_NTIERS = 11
-PS_OP_COPY, PS_OP_KERNEL = 0, 1
 (PS_K_RINV, PS_K_QKV, PS_K_O, PS_K_GATE_UP, PS_K_DOWN, PS_K_ROUTE, PS_K_EXPERT_GATE_UP,
  PS_K_EXPERT_DOWN, PS_K_COMBINE, PS_K_ATTN, PS_K_ATTN_COMBINE, PS_K_OUT) = range(12)
 (PS_OPF_WAIT_SLOT_FREE, PS_OPF_WAIT_ROUTER, PS_OPF_RECORD_READY, PS_OPF_WAIT_READY,
@@ -33,7 +35,8 @@ class ps_model_desc(C.Structure):
 
 class ps_profile(C.Structure):
     _fields_ = [("h2d_gbps", C.c_double), ("gemv_gbps", C.c_double),
-                ("gemm_tflops", C.c_double * PS_NTIERS), ("launch_us", C.c_double)]
+                ("gemm_tflops", C.c_double * PS_NTIERS), ("launch_us", C.c_double)] + \
+               [(n, C.c_double) for n in ("cpu_gbps", "cpu_gbps_busy", "h2d_gbps_busy", "cpu_tokens_free", "cpu_sync_us")]
 
 
 class ps_shard_info(C.Structure):
@@ -45,7 +48,9 @@ class ps_plan_summary_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("budget_bytes", "weight_bytes", "resident_bytes", "streamed_bytes",
                                           "scratch_bytes", "workspace_bytes", "slot_bytes")] + \
                [(n, C.c_uint32) for n in ("n_slots", "n_shards", "n_tokens", "tier")] + \
-               [("est_step_ms", C.c_double), ("est_streamed_bytes_per_step", C.c_double)]
+               [("est_step_ms", C.c_double), ("est_streamed_bytes_per_step", C.c_double),
+                ("cpu_bytes", C.c_uint64), ("plan_kind", C.c_uint32), ("pad", C.c_uint32),
+                ("cpu_fraction", C.c_double), ("est_kind_ms", C.c_double * 3)]
 
 
 class ps_tier_entry(C.Structure):
@@ -61,12 +66,13 @@ class ps_tier_choice(C.Structure):
 class ps_stats(C.Structure):
     _fields_ = [("resident_bytes_step", C.c_uint64), ("streamed_bytes_step", C.c_uint64),
                 ("n_copies", C.c_uint32), ("n_kernels", C.c_uint32)] + \
-               [(n, C.c_double) for n in ("copy_ms", "compute_ms", "wall_ms", "overlap", "h2d_gbps")]
+               [(n, C.c_double) for n in ("copy_ms", "compute_ms", "wall_ms", "overlap", "h2d_gbps")] + \
+               [("cpu_bytes_step", C.c_uint64), ("cpu_ms", C.c_double), ("cpu_wait_ms", C.c_double)]
 
 
 class ps_op_info(C.Structure):
     _fields_ = [("type", C.c_uint32), ("kernel", C.c_uint32), ("layer", C.c_uint32), ("flags", C.c_uint32),
-                ("slot", C.c_int32), ("shard0", C.c_uint32), ("nshards", C.c_uint32),
+                ("slot", C.c_int32), ("shard0", C.c_uint32), ("nshards", C.c_uint32), ("buffers", C.c_uint32),
                 ("slot_offset", C.c_uint64), ("bytes", C.c_uint64)]
 
 
@@ -77,7 +83,7 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
            "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
-           "ps_stack_set_logits_out"]
+           "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads"]
 
 _lib = None
 
@@ -103,6 +109,8 @@ def lib():
         L.ps_packed_bytes.argtypes = [u32, u32]
         sig = {
             "ps_plan_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), u32, vp, C.POINTER(vp)],
+            "ps_plan_create_kind": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), u32, vp, u32, C.POINTER(vp)],
+            "ps_stack_set_cpu_threads": [vp, u32],
             "ps_plan_summary": [vp, C.POINTER(ps_plan_summary_t)],
             "ps_plan_get_shard": [vp, u32, C.POINTER(ps_shard_info)],
             "ps_schedule_create": [vp, vp, C.POINTER(vp)],
@@ -131,6 +139,7 @@ def lib():
             "ps_stack_load_kv": [vp, u32, u32, vp, vp, u32],
             "ps_stack_set_context": [vp, u32],
             "ps_stack_set_logits_out": [vp, vp, u32, u32],
+            "ps_cpu_matmul": [vp, u32, u32, i32, vp, u32, C.c_float, vp, vp, u32],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -163,9 +172,12 @@ def model_desc(cfg):
                          cfg["rms_eps"], int(cfg.get("kv_context", 0)), int(cfg.get("vocab", 0)))
 
 
-def make_profile(h2d_gbps=55.0, gemv_gbps=4000.0, gemm_tflops=400.0, launch_us=3.0):
+def make_profile(h2d_gbps=55.0, gemv_gbps=4000.0, gemm_tflops=400.0, launch_us=3.0, cpu_gbps=0.0,
+                 cpu_gbps_busy=0.0, h2d_gbps_busy=0.0, cpu_tokens_free=4.0, cpu_sync_us=30.0):
     p = ps_profile()
     p.h2d_gbps, p.gemv_gbps, p.launch_us = h2d_gbps, gemv_gbps, launch_us
+    p.cpu_gbps, p.cpu_gbps_busy, p.h2d_gbps_busy = cpu_gbps, cpu_gbps_busy, h2d_gbps_busy
+    p.cpu_tokens_free, p.cpu_sync_us = cpu_tokens_free, cpu_sync_us
     for t in range(PS_NTIERS):
         p.gemm_tflops[t] = gemm_tflops[t] if hasattr(gemm_tflops, "__len__") else gemm_tflops
     return p
@@ -180,14 +192,19 @@ def _ptr(a):
 class Plan:
     """ps_plan_create / ps_plan_summary / ps_plan_get_shard / ps_plan_destroy."""
 
-    def __init__(self, cfg, budget_bytes, n_tokens, profile=None, expert_freq=None):
+    def __init__(self, cfg, budget_bytes, n_tokens, profile=None, expert_freq=None, kind=None):
+        """kind: None (ps_plan_create: Plan One) or PS_PLAN_* (ps_plan_create_kind)."""
         self.cfg = cfg
         self.desc = model_desc(cfg)
         self.profile = profile if profile is not None else make_profile()
         self.h = C.c_void_p()
         freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
-        _check(lib().ps_plan_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), int(n_tokens),
-                                    _ptr(freq), C.byref(self.h)))
+        if kind is None:
+            _check(lib().ps_plan_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), int(n_tokens),
+                                        _ptr(freq), C.byref(self.h)))
+        else:
+            _check(lib().ps_plan_create_kind(C.byref(self.desc), int(budget_bytes), C.byref(self.profile),
+                                             int(n_tokens), _ptr(freq), int(kind), C.byref(self.h)))
 
     def summary(self):
         s = ps_plan_summary_t()
@@ -389,6 +406,9 @@ class Stack:
 
     def set_context(self, context):
         _check(lib().ps_stack_set_context(self.h, int(context)))
+
+    def set_cpu_threads(self, threads):
+        _check(lib().ps_stack_set_cpu_threads(self.h, int(threads)))
 
     def set_logits_out(self, logits, first_token=0, rows=1):
         """logits: torch fp16 CUDA tensor of rows * vocab elements (kept alive by the caller), or None

@@ -159,6 +159,12 @@ struct Cand {  // a whole matrix / expert before any split
     double freq;
 };
 
+// shards that a CPU plan may leave in system memory: dense FFN matrices and the output head (the
+// low end of the priority list); attention matrices, caches and experts always run on the GPU
+static bool cpu_eligible(const Shard &s) {
+    return s.kind == PS_SHARD_GATE_UP || s.kind == PS_SHARD_DOWN || s.kind == PS_SHARD_OUT;
+}
+
 static double shard_compute_ms(const ps_plan &p, uint64_t bytes, double tokens) {
     // memory-bound price vs compute-bound price (roofline rule of the paper's estimator)
     const double weights = (double)bytes / 0.5625;
@@ -171,12 +177,24 @@ static double shard_compute_ms(const ps_plan &p, uint64_t bytes, double tokens) 
 static void estimate(ps_plan &p, const float *freq) {
     // Each shard's time is the larger of its compute time and the concurrent H2D copy of
     // the next shard; shard times are summed (paper Section 3, timing estimation).  MoE
-    // expert shards are weighted by the probability that a step touches them.
+    // expert shards are weighted by the probability that a step touches them.  The CPU part of a
+    // matrix runs beside the GPU's work on the same matrix: the matrix costs the larger of the two.
+    // When both the CPU and PCIe pull on system memory, both are priced at their contended rates.
     const auto &m = p.g.m;
     const size_t n = p.shards.size();
-    std::vector<double> prob(n, 1.0), comp(n), copy(n, 0.0);
+    bool any_cpu = false, any_stream = false;
+    for (const Shard &s : p.shards) { any_cpu |= s.resident == 2; any_stream |= s.resident == 0; }
+    const bool contend = any_cpu && any_stream;
+    const double h2d = contend && p.prof.h2d_gbps_busy > 0 ? p.prof.h2d_gbps_busy : p.prof.h2d_gbps;
+    const double cpu = contend && p.prof.cpu_gbps_busy > 0 ? p.prof.cpu_gbps_busy : p.prof.cpu_gbps;
+    std::vector<double> prob(n, 1.0), comp(n, 0.0), copy(n, 0.0);
     for (size_t i = 0; i < n; ++i) {
         const Shard &s = p.shards[i];
+        if (s.resident == 2) {
+            const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, p.M / p.prof.cpu_tokens_free) : 1.0;
+            comp[i] = (cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0) + p.prof.cpu_sync_us * 1e-3;
+            continue;
+        }
         double tokens = p.M;
         if (s.kind == PS_SHARD_EXPERT) {
             double f = (double)m.top_k / m.n_experts;
@@ -186,28 +204,49 @@ static void estimate(ps_plan &p, const float *freq) {
             tokens = prob[i] > 0 ? p.M * f / prob[i] : 0;
         }
         comp[i] = shard_compute_ms(p, s.bytes, tokens) * prob[i];
-        if (!s.resident && p.prof.h2d_gbps > 0) copy[i] = (double)s.bytes / (p.prof.h2d_gbps * 1e9) * 1e3 * prob[i];
+        if (!s.resident && h2d > 0) copy[i] = (double)s.bytes / (h2d * 1e9) * 1e3 * prob[i];
     }
-    double t = n ? copy[0] : 0.0, streamed = 0;
-    for (size_t i = 0; i < n; ++i) {
-        t += std::max(comp[i], i + 1 < n ? copy[i + 1] : 0.0);
-        if (!p.shards[i].resident) streamed += (double)p.shards[i].bytes * prob[i];
+    std::vector<size_t> gpu;   // the GPU's shards, in order
+    for (size_t i = 0; i < n; ++i) if (p.shards[i].resident != 2) gpu.push_back(i);
+    std::vector<double> tg(n, 0.0);
+    for (size_t j = 0; j < gpu.size(); ++j) tg[gpu[j]] = std::max(comp[gpu[j]], j + 1 < gpu.size() ? copy[gpu[j + 1]] : 0.0);
+    double t = gpu.empty() ? 0.0 : copy[gpu[0]], streamed = 0;
+    for (size_t i = 0; i < n;) {   // one matrix (or expert, or cache head) at a time
+        size_t j = i;
+        double t_gpu = 0, t_cpu = 0;
+        while (j < n && p.shards[j].layer == p.shards[i].layer && p.shards[j].kind == p.shards[i].kind &&
+               p.shards[j].expert == p.shards[i].expert) {
+            if (p.shards[j].resident == 2) t_cpu += comp[j]; else t_gpu += tg[j];
+            if (!p.shards[j].resident) streamed += (double)p.shards[j].bytes * prob[j];
+            ++j;
+        }
+        t += std::max(t_gpu, t_cpu);
+        i = j;
     }
     p.est_step_ms = t;
     p.est_streamed_per_step = streamed;
 }
 
-static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
-                         uint32_t M, const float *freq, ps_plan *p) {
+// One plan of the given kind.  cpu_frac: Plan Three's share of each unpinned CPU-eligible matrix
+// that stays on the CPU (ignored otherwise).
+static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_profile *prof, uint32_t M,
+                          const float *freq, uint32_t kind, double cpu_frac, ps_plan *p) {
     int32_t rc = make_model_geom(model, &p->g);
     if (rc) return rc;
     if (M == 0 || M > kTiers[PS_NTIERS - 1]) { set_error("n_tokens=%u out of range 1..16384", M); return PS_E_ARG; }
     if (p->g.kv && M != 1) { set_error("attention over a KV cache is built for one token per step (got %u)", M); return PS_E_ARG; }
     if (prof) p->prof = *prof;
+    if (kind != PS_PLAN_GPU_ONLY && !(p->prof.cpu_gbps > 0)) {
+        set_error("plans with CPU shards need a profile with cpu_gbps > 0"); return PS_E_STATE;
+    }
+    if (kind != PS_PLAN_GPU_ONLY && M > 64) { set_error("the CPU back-end takes at most 64 tokens (got %u)", M); return PS_E_ARG; }
     p->budget = budget;
     p->M = M;
+    p->kind = kind;
+    p->cpu_frac = kind == PS_PLAN_DYNAMIC ? std::min(1.0, std::max(0.0, cpu_frac)) : (kind == PS_PLAN_STATIC ? 1.0 : 0.0);
     p->tier = ps_tier_for_tokens(M);
     p->ws = make_workspace(p->g, M);
+    p->shards.clear();
     const ModelGeom &g = p->g;
     const auto &m = g.m;
 
@@ -271,24 +310,11 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
     });
     for (uint32_t r = 0; r < order.size(); ++r) cands[order[r]].s.rank = r;
 
-    // DecideScratchVRAMBudget: none if everything fits, else a double buffer
+    // PinShardsToGPU: first fit in priority order; the first shard that does not fit
+    // is split at slab granularity and its head pinned; scanning continues
     std::vector<uint32_t> head_tiles(cands.size(), 0);  // tiles pinned per candidate (whole shards: 0 or 1)
-    if (p->ws.total + p->weight_bytes <= budget) {
-        p->n_slots = 0; p->slot_bytes = 0;
-        for (size_t i = 0; i < cands.size(); ++i) head_tiles[i] = cands[i].quantum_tiles ? cands[i].s.ntiles : 1;
-    } else {
-        uint64_t lo = std::min<uint64_t>(1ull << 20, budget / 8), hi = 64ull << 20;
-        uint64_t slot = std::min(std::max(budget / 16, lo), hi) / kAlign * kAlign;
-        if (slot < max_unit) slot = align_up(max_unit, kAlign);
-        p->slot_bytes = slot; p->n_slots = 2;
-        if (p->ws.total + 2 * slot > budget) {
-            set_error("budget %llu B < workspace %llu B + 2 scratch slots of %llu B",
-                      (unsigned long long)budget, (unsigned long long)p->ws.total, (unsigned long long)slot);
-            return PS_E_BUDGET;
-        }
-        // PinShardsToGPU: first fit in priority order; the first shard that does not fit
-        // is split at slab granularity and its head pinned; scanning continues
-        uint64_t remaining = budget - p->ws.total - 2 * slot;
+    auto pin = [&](uint64_t remaining) {
+        std::fill(head_tiles.begin(), head_tiles.end(), 0u);
         bool split_done = false;
         for (uint32_t r = 0; r < order.size(); ++r) {
             Cand &c = cands[order[r]];
@@ -300,12 +326,38 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
                 remaining -= (uint64_t)head_tiles[order[r]] * c.tile_bytes;
             }
         }
+    };
+    auto fully_pinned = [&](size_t i) { return head_tiles[i] == (cands[i].quantum_tiles ? cands[i].s.ntiles : 1u); };
+
+    // DecideScratchVRAMBudget: none if everything fits, else a double buffer.  Plan Two gives the
+    // scratch to the pinned region when every shard that must run on the GPU can be pinned.
+    bool need_slots = p->ws.total + p->weight_bytes > budget;
+    if (need_slots && kind == PS_PLAN_STATIC) {
+        pin(budget - p->ws.total);
+        need_slots = false;
+        for (size_t i = 0; i < cands.size(); ++i) need_slots |= !fully_pinned(i) && !cpu_eligible(cands[i].s);
+    }
+    if (!need_slots) {
+        p->n_slots = 0; p->slot_bytes = 0;
+        pin(budget - p->ws.total);
+    } else {
+        uint64_t lo = std::min<uint64_t>(1ull << 20, budget / 8), hi = 64ull << 20;
+        uint64_t slot = std::min(std::max(budget / 16, lo), hi) / kAlign * kAlign;
+        if (slot < max_unit) slot = align_up(max_unit, kAlign);
+        p->slot_bytes = slot; p->n_slots = 2;
+        if (p->ws.total + 2 * slot > budget) {
+            set_error("budget %llu B < workspace %llu B + 2 scratch slots of %llu B",
+                      (unsigned long long)budget, (unsigned long long)p->ws.total, (unsigned long long)slot);
+            return PS_E_BUDGET;
+        }
+        pin(budget - p->ws.total - 2 * slot);
     }
     p->scratch_off = p->ws.total;
     p->pinned_off = p->scratch_off + (uint64_t)p->n_slots * p->slot_bytes;
 
-    // Emit shards in execution order; streamed remainders are cut into slabs that fit a slot.
-    // Arena offsets of resident shards follow priority rank so the pinned region is dense.
+    // Emit shards in execution order; streamed remainders are cut into slabs that fit a slot; the
+    // CPU's part of a matrix is its tail, one shard.  Arena offsets of resident shards follow
+    // priority rank so the pinned region is dense.
     std::vector<uint64_t> res_off(cands.size(), 0);
     {
         uint64_t off = p->pinned_off;
@@ -319,10 +371,10 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
         if (off > budget) { set_error("internal: pinned region overflows the budget"); return PS_E_STATE; }
     }
     uint64_t host_off = 0;
-    p->resident_bytes = p->streamed_bytes = 0;
+    p->resident_bytes = p->streamed_bytes = p->cpu_bytes = 0;
     for (size_t i = 0; i < cands.size(); ++i) {
         const Cand &c = cands[i];
-        if (!c.quantum_tiles) {  // expert: whole
+        if (!c.quantum_tiles) {  // expert or cache head: whole
             Shard s = c.s;
             s.resident = head_tiles[i] ? 1 : 0;
             s.offset = s.resident ? res_off[i] : host_off;
@@ -339,12 +391,20 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
             p->shards.push_back(s);
         }
         uint32_t t = head_tiles[i];
-        if (t < c.s.ntiles) {
+        uint32_t cpu_tiles = 0;   // tail of the unpinned remainder that stays on the CPU, in slab quanta
+        if (t < c.s.ntiles && p->cpu_frac > 0 && cpu_eligible(c.s)) {
+            const uint32_t quanta = (c.s.ntiles - t) / c.quantum_tiles;
+            cpu_tiles = std::min(quanta, (uint32_t)std::lround(p->cpu_frac * quanta)) * c.quantum_tiles;
+            if (!p->n_slots) cpu_tiles = c.s.ntiles - t;   // nowhere to stream to
+        }
+        const uint32_t t_end = c.s.ntiles - cpu_tiles;
+        if (t < t_end) {
+            if (!p->n_slots) { set_error("internal: streamed shard without scratch"); return PS_E_STATE; }
             uint32_t per = (uint32_t)(p->slot_bytes / (c.tile_bytes * c.quantum_tiles)) * c.quantum_tiles;
             if (per == 0) { set_error("internal: slot smaller than a slab quantum"); return PS_E_STATE; }
-            while (t < c.s.ntiles) {
+            while (t < t_end) {
                 Shard s = c.s;
-                s.tile0 = t; s.ntiles = std::min(per, c.s.ntiles - t); s.bytes = (uint64_t)s.ntiles * c.tile_bytes;
+                s.tile0 = t; s.ntiles = std::min(per, t_end - t); s.bytes = (uint64_t)s.ntiles * c.tile_bytes;
                 s.resident = 0; s.offset = host_off;
                 host_off += s.bytes;
                 p->streamed_bytes += s.bytes;
@@ -352,8 +412,56 @@ static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_p
                 t += s.ntiles;
             }
         }
+        if (cpu_tiles) {
+            Shard s = c.s;
+            s.tile0 = t_end; s.ntiles = cpu_tiles; s.bytes = (uint64_t)cpu_tiles * c.tile_bytes;
+            s.resident = 2; s.offset = host_off;
+            host_off += s.bytes;
+            p->cpu_bytes += s.bytes;
+            p->shards.push_back(s);
+        }
     }
     estimate(*p, freq);
+    for (double &e : p->est_kind) e = -1.0;
+    p->est_kind[kind] = p->est_step_ms;
+    return PS_OK;
+}
+
+// Plan Three: one CPU share for the whole plan, the best of a grid by the estimate
+static int32_t build_dynamic(const ps_model_desc *model, uint64_t budget, const ps_profile *prof, uint32_t M,
+                             const float *freq, ps_plan *p) {
+    double best_f = -1, best_ms = 0;
+    for (int k = 1; k <= 19; ++k) {
+        ps_plan trial;
+        const int32_t rc = build_plan(model, budget, prof, M, freq, PS_PLAN_DYNAMIC, k * 0.05, &trial);
+        if (rc) return rc;
+        if (best_f < 0 || trial.est_step_ms < best_ms) { best_f = k * 0.05; best_ms = trial.est_step_ms; }
+    }
+    return build_plan(model, budget, prof, M, freq, PS_PLAN_DYNAMIC, best_f, p);
+}
+
+static int32_t plan_impl(const ps_model_desc *model, uint64_t budget, const ps_profile *prof, uint32_t M,
+                         const float *freq, uint32_t kind, ps_plan *p) {
+    if (kind == PS_PLAN_GPU_ONLY || kind == PS_PLAN_STATIC) return build_plan(model, budget, prof, M, freq, kind, 0.0, p);
+    if (kind == PS_PLAN_DYNAMIC) return build_dynamic(model, budget, prof, M, freq, p);
+    if (kind != PS_PLAN_AUTO) { set_error("unknown plan kind %u", kind); return PS_E_ARG; }
+    // HeuristicSplit: all three, the lowest estimate wins; a plan that cannot be built drops out
+    int32_t rc = build_plan(model, budget, prof, M, freq, PS_PLAN_GPU_ONLY, 0.0, p);
+    if (rc) return rc;
+    double est[3] = {p->est_step_ms, -1.0, -1.0};
+    const bool cpu_ok = prof && prof->cpu_gbps > 0 && M <= 64;
+    if (cpu_ok) {
+        ps_plan st, dy;
+        if (build_plan(model, budget, prof, M, freq, PS_PLAN_STATIC, 0.0, &st) == PS_OK) {
+            est[1] = st.est_step_ms;
+            if (st.est_step_ms < p->est_step_ms) *p = st;
+        }
+        if (build_dynamic(model, budget, prof, M, freq, &dy) == PS_OK) {
+            est[2] = dy.est_step_ms;
+            if (dy.est_step_ms < p->est_step_ms) *p = dy;
+        }
+    }
+    for (int k = 0; k < 3; ++k) p->est_kind[k] = est[k];
     return PS_OK;
 }
 
@@ -382,7 +490,19 @@ int32_t ps_plan_create(const ps_model_desc *model, uint64_t budget, const ps_pro
     *out = nullptr;
     ps_plan *p = new (std::nothrow) ps_plan();
     if (!p) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
-    int32_t rc = ps::plan_impl(model, budget, prof, n_tokens, expert_freq, p);
+    int32_t rc = ps::plan_impl(model, budget, prof, n_tokens, expert_freq, PS_PLAN_GPU_ONLY, p);
+    if (rc) { delete p; return rc; }
+    *out = p;
+    return PS_OK;
+}
+
+int32_t ps_plan_create_kind(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                            uint32_t n_tokens, const float *expert_freq, uint32_t kind, ps_plan **out) {
+    if (!out) { ps::set_error("out is NULL"); return PS_E_ARG; }
+    *out = nullptr;
+    ps_plan *p = new (std::nothrow) ps_plan();
+    if (!p) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
+    int32_t rc = ps::plan_impl(model, budget, prof, n_tokens, expert_freq, kind, p);
     if (rc) { delete p; return rc; }
     *out = p;
     return PS_OK;
@@ -403,6 +523,11 @@ int32_t ps_plan_summary(const ps_plan *p, ps_plan_summary_t *o) {
     o->tier = p->tier;
     o->est_step_ms = p->est_step_ms;
     o->est_streamed_bytes_per_step = p->est_streamed_per_step;
+    o->cpu_bytes = p->cpu_bytes;
+    o->plan_kind = p->kind;
+    o->pad = 0;
+    o->cpu_fraction = p->cpu_frac;
+    for (int k = 0; k < 3; ++k) o->est_kind_ms[k] = p->est_kind[k];
     return PS_OK;
 }
 
@@ -428,7 +553,7 @@ int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t budget, const 
         if (!p) { delete tb; ps::set_error("out of host memory"); return PS_E_NOMEM; }
         // attention over a KV cache is built for one token per step: only that tier has a schedule
         if (model && model->kv_context && t > 0) { delete p; continue; }
-        const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, p);
+        const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, PS_PLAN_GPU_ONLY, p);
         if (rc == PS_OK) { tb->plans[t] = p; continue; }
         delete p;
         if (rc != PS_E_BUDGET) { delete tb; return rc; }   // a bad model or profile fails every tier

@@ -5,8 +5,13 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstring>
+#include <memory>
+#include <thread>
+#include <vector>
 
+#include "cpu_backend.h"
 #include "kernels.h"
 #include "ps_internal.h"
 
@@ -32,7 +37,7 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
     int32_t rc = PS_OK;
     hipStream_t cs = static_cast<hipStream_t>(compute_stream), ps_copy = static_cast<hipStream_t>(copy_stream);
     uint8_t *base = static_cast<uint8_t *>(scratch_dev);
-    void *host = nullptr;
+    void *host = nullptr, *cpu_img = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     float ms = 0;
     const MatGeom mg = make_geom(8192, 4096, false);  // an 8192 x 4096 matrix, 512 tiles
@@ -106,7 +111,74 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
         PS_HIP(hipEventElapsedTime(&ms, e0, e1));
         out->gemm_tflops[t] = 2.0 * T * 8192.0 * 4096.0 * kLaunches / (ms * 1e-3) / 1e12;
     }
+    if (cpu_backend_supported()) {
+        // CPU back-end (plans Two and Three): its rate over a packed image far larger than the
+        // caches, alone and while H2D copies pull on the same memory, the copy rate meanwhile, the
+        // token count up to which it stays memory-bound, and the fixed cost of one CPU shard
+        constexpr uint64_t kImage = 512ull << 20;
+        auto now = [] { return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+        PS_HIP(hipHostMalloc(&cpu_img, kImage, hipHostMallocDefault));
+        std::memset(cpu_img, 0x11, kImage);
+        const unsigned hw = std::thread::hardware_concurrency();
+        std::unique_ptr<CpuPool> pool(new CpuPool(std::min(hw ? hw : 4u, 16u)));
+        std::vector<float> scratch(cpu_scratch_floats(16, 4096));
+        std::vector<uint16_t> xh(16 * 4096, 0x1111), yh((size_t)16 * (kImage / mg.tile_bytes) * 16);
+        CpuMatArgs a;
+        a.W = static_cast<const uint8_t *>(cpu_img); a.ntiles = (uint32_t)(kImage / mg.tile_bytes); a.tile_bytes = mg.tile_bytes;
+        a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K; a.M = 1; a.x = xh.data(); a.x_stride = 4096;
+        a.mode = CPU_PLAIN; a.eps = 1e-6f; a.out = yh.data(); a.out_stride = a.ntiles * 16; a.out_col0 = 0;
+        const double image_bytes = (double)a.ntiles * mg.tile_bytes;
+        cpu_matmul_w4(a, *pool, scratch.data());   // warm-up: pages touched, workers awake
+        double t0 = now();
+        for (int r = 0; r < 3; ++r) cpu_matmul_w4(a, *pool, scratch.data());
+        out->cpu_gbps = 3.0 * image_bytes / (now() - t0) / 1e9;
+        {   // tokens the kernel takes before it turns compute-bound: 16 tokens against 1 on 1/8 of the image
+            CpuMatArgs b = a;
+            b.ntiles = a.ntiles / 8; b.out_stride = b.ntiles * 16;
+            t0 = now();
+            cpu_matmul_w4(b, *pool, scratch.data());
+            const double t1 = now() - t0;
+            b.M = 16;
+            t0 = now();
+            cpu_matmul_w4(b, *pool, scratch.data());
+            const double t16 = now() - t0;
+            out->cpu_tokens_free = t16 > t1 ? std::max(1.0, 16.0 * t1 / t16) : 64.0;
+        }
+        {   // both at once: 24 copies of 64 MiB on the copy stream, the CPU kernel looping until they end
+            PS_HIP(hipEventRecord(e0, ps_copy));
+            for (int i = 0; i < 24; ++i) PS_HIP(hipMemcpyAsync(wts, host, kHead, hipMemcpyHostToDevice, ps_copy));
+            PS_HIP(hipEventRecord(e1, ps_copy));
+            t0 = now();
+            int passes = 0;
+            double t_in = 0;   // CPU time that ended while the copies were still running
+            while (hipEventQuery(e1) == hipErrorNotReady) {
+                cpu_matmul_w4(a, *pool, scratch.data());
+                ++passes;
+                if (hipEventQuery(e1) == hipErrorNotReady) t_in = now() - t0; else if (passes > 1) --passes;
+            }
+            PS_HIP(hipEventSynchronize(e1));
+            PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+            out->h2d_gbps_busy = 24.0 * (double)kHead / (ms * 1e-3) / 1e9;
+            out->cpu_gbps_busy = (passes > 0 && t_in > 0) ? passes * image_bytes / t_in / 1e9 : out->cpu_gbps;
+        }
+        {   // one CPU shard's fixed cost: 8 KB down, wait, a 16-tile job, 8 KB up
+            CpuMatArgs b = a;
+            b.ntiles = 16; b.out_stride = 256;
+            const int n = 20;
+            PS_HIP(hipStreamSynchronize(cs));
+            t0 = now();
+            for (int i = 0; i < n; ++i) {
+                PS_HIP(hipMemcpyAsync(host, x, 8192, hipMemcpyDeviceToHost, cs));
+                PS_HIP(hipStreamSynchronize(cs));
+                cpu_matmul_w4(b, *pool, scratch.data());
+                PS_HIP(hipMemcpy2DAsync(y, 8192, host, 8192, 512, 1, hipMemcpyHostToDevice, cs));
+            }
+            PS_HIP(hipStreamSynchronize(cs));
+            out->cpu_sync_us = (now() - t0) / n * 1e6;
+        }
+    }
 done:
+    if (cpu_img) (void)hipHostFree(cpu_img);
     if (host) (void)hipHostFree(host);
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);

@@ -56,7 +56,7 @@ uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M);
 
 struct Shard {
     uint32_t layer = 0, kind = 0, expert = kNoExpert, cls = 0, tile0 = 0, ntiles = 0;
-    uint32_t resident = 0, rank = 0;
+    uint32_t resident = 0, rank = 0;   // resident: 1 pinned in VRAM, 0 streamed, 2 run on the CPU
     uint64_t bytes = 0, offset = 0;
 };
 
@@ -91,8 +91,11 @@ struct ps_plan {
     uint64_t slot_bytes = 0, scratch_off = 0, pinned_off = 0;
     uint32_t n_slots = 0;
     std::vector<ps::Shard> shards;  // execution order
-    uint64_t weight_bytes = 0, resident_bytes = 0, streamed_bytes = 0;
+    uint64_t weight_bytes = 0, resident_bytes = 0, streamed_bytes = 0, cpu_bytes = 0;
     double est_step_ms = 0, est_streamed_per_step = 0;
+    uint32_t kind = PS_PLAN_GPU_ONLY;   // which of the three schedule plans this is
+    double cpu_frac = 0;                // Plan Three: CPU share of each unpinned eligible matrix
+    double est_kind[3] = {-1, -1, -1};  // estimates per plan kind (all three after HeuristicSplit)
 };
 
 struct ps_tier_table {

@@ -47,6 +47,7 @@ struct Builder {
     std::vector<KernelItem> kernels;
     std::vector<Batch> batches;
     bool batch_open = false;
+    bool host_has_h = false;   // the host copy of the FFN input is current (same layer, fetched once)
 
     static Op kernel_op(uint32_t kernel, uint32_t layer) {
         Op o;
@@ -78,20 +79,56 @@ struct Builder {
         return off;
     }
 
-    void add_matrix_kernels(uint32_t kernel, uint32_t layer, uint32_t kind, size_t &si) {
-        while (si < p->shards.size() && p->shards[si].layer == layer && p->shards[si].kind == kind) {
-            const Shard &s = p->shards[si];
-            KernelItem k;
-            k.op = kernel_op(kernel, layer);
-            k.op.info.shard0 = (uint32_t)si;
-            k.op.info.bytes = s.bytes;
-            if (!s.resident) {
-                k.op.info.slot_offset = stage((uint32_t)si, layer, false, &k.batch);
-                k.op.info.slot = k.batch % 2;
-            }
-            kernels.push_back(k);
-            ++si;
+    // activation buffers the CPU back-end reads for a sub-layer
+    uint32_t cpu_inputs(uint32_t kernel) const {
+        const bool resid = !(p->g.m.flags & PS_FLAG_NO_RESIDUAL);
+        switch (kernel) {
+            case PS_K_GATE_UP: return PS_BUF_H;
+            case PS_K_DOWN: return PS_BUF_S | (resid ? PS_BUF_H : 0u);
+            case PS_K_OUT: return PS_BUF_X;
         }
+        return 0;
+    }
+
+    // One matrix: its GPU shards (pinned head, streamed slabs), then its CPU shard if the plan left
+    // one in system memory.  The activations the CPU needs are fetched before the GPU kernels are
+    // launched, so the GPU works through its slabs while the host computes its rows.
+    void add_matrix_kernels(uint32_t kernel, uint32_t layer, uint32_t kind, size_t &si) {
+        size_t end = si;
+        bool any_cpu = false;
+        while (end < p->shards.size() && p->shards[end].layer == layer && p->shards[end].kind == kind) {
+            any_cpu |= p->shards[end].resident == 2;
+            ++end;
+        }
+        if (any_cpu) {
+            uint32_t need = cpu_inputs(kernel);
+            if (host_has_h) need &= ~PS_BUF_H;
+            if (need) {
+                KernelItem f;
+                f.op = kernel_op(kernel, layer);
+                f.op.info.type = PS_OP_FETCH; f.op.info.nshards = 0; f.op.info.buffers = need;
+                kernels.push_back(f);
+            }
+            if (cpu_inputs(kernel) & PS_BUF_H) host_has_h = true;
+        }
+        for (int pass = 0; pass < 2; ++pass)
+            for (size_t i = si; i < end; ++i) {
+                const Shard &s = p->shards[i];
+                if ((s.resident == 2) != (pass == 1)) continue;
+                KernelItem k;
+                k.op = kernel_op(kernel, layer);
+                k.op.info.shard0 = (uint32_t)i;
+                k.op.info.bytes = s.bytes;
+                if (s.resident == 2) {
+                    k.op.info.type = PS_OP_CPU;
+                    k.op.info.buffers = cpu_inputs(kernel);
+                } else if (!s.resident) {
+                    k.op.info.slot_offset = stage((uint32_t)i, layer, false, &k.batch);
+                    k.op.info.slot = k.batch % 2;
+                }
+                kernels.push_back(k);
+            }
+        si = end;
     }
 
     // KV-cache shards of a layer (one per kv head, consecutive): one attention launch per run of
@@ -160,6 +197,7 @@ struct Builder {
         std::vector<int32_t> idx((size_t)M * std::max(1u, m.top_k));
         size_t si = 0;
         for (uint32_t l = 0; l < m.n_layers; ++l) {
+            host_has_h = false;
             if (g.has_attn) {
                 if (M > 1) add_plain(PS_K_RINV, l);
                 add_matrix_kernels(PS_K_QKV, l, PS_SHARD_QKV, si);
@@ -287,6 +325,8 @@ int32_t validate_schedule(const ps_schedule *s) {
     struct Read { uint64_t off, bytes; int64_t comp_pos; };
     std::vector<std::vector<Read>> reads(2);                // kernel reads since the region was written
     auto overlap = [](uint64_t a0, uint64_t ab, uint64_t b0, uint64_t bb) { return a0 < b0 + bb && b0 < a0 + ab; };
+    uint32_t host_valid = 0;      // activation buffers whose host copy is current (PS_BUF_*)
+    uint32_t host_layer = ~0u;
 
     for (size_t i = 0; i < n; ++i) {
         const Op &op = s->ops[i];
@@ -318,6 +358,26 @@ int32_t validate_schedule(const ps_schedule *s) {
             end[i] = c; copy_tail = c;
             if (o.flags & PS_OPF_RECORD_READY) { ev_ready[o.slot] = c; has_ready[o.slot] = 1; }
         } else {
+            // host copies of activations: fetched on the compute stream (the host waits), stale once
+            // the layer moves on or a later op rewrites the buffer; a CPU shard reads only current ones
+            if (o.layer != host_layer) { host_valid = 0; host_layer = o.layer; }
+            if (o.type == PS_OP_FETCH) {
+                if (!o.buffers || o.slot >= 0) { set_error("op %zu: malformed fetch", i); return PS_E_STATE; }
+                host_valid |= o.buffers;
+            } else if (o.type == PS_OP_CPU) {
+                if (o.slot >= 0 || (o.flags & (PS_OPF_WAIT_READY | PS_OPF_RECORD_FREE))) {
+                    set_error("op %zu: a CPU shard does not touch the scratch slots", i); return PS_E_STATE;
+                }
+                if (o.buffers & ~host_valid) {
+                    set_error("op %zu: CPU shard reads activations (mask %u) that were not fetched (have %u)", i, o.buffers, host_valid);
+                    return PS_E_STATE;
+                }
+            }
+            if (o.type != PS_OP_FETCH) {
+                if (o.kernel == PS_K_O || o.kernel == PS_K_COMBINE) host_valid &= ~PS_BUF_H;
+                if (o.kernel == PS_K_GATE_UP || o.kernel == PS_K_EXPERT_GATE_UP) host_valid &= ~PS_BUF_S;
+                if (o.kernel == PS_K_DOWN || o.kernel == PS_K_COMBINE) host_valid &= ~PS_BUF_X;
+            }
             Clock c = comp_tail;
             if (o.flags & PS_OPF_WAIT_READY) {
                 if (o.slot < 0 || !has_ready[o.slot]) { set_error("op %zu: waits for a slot never filled", i); return PS_E_STATE; }

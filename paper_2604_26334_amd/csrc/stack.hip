@@ -9,10 +9,13 @@
 #include <atomic>
 #include <cstring>
 #include <functional>
+#include <chrono>
 #include <map>
+#include <memory>
 #include <thread>
 #include <tuple>
 
+#include "cpu_backend.h"
 #include "kernels.h"
 #include "ps_internal.h"
 
@@ -51,6 +54,12 @@ struct ps_stack {
     uint64_t tables_bytes = 0;
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
     std::map<std::tuple<const void *, void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out, logits)
+    // CPU back-end (plans with shards left in system memory): worker threads, pinned host copies of
+    // the activations it reads (FFN input, SwiGLU output, final hidden state) and of what it writes
+    std::unique_ptr<ps::CpuPool> pool;
+    uint16_t *host_h = nullptr, *host_s = nullptr, *host_x = nullptr, *host_out = nullptr;
+    std::vector<float> cpu_scratch;
+    bool out_upload_pending = false;          // host_out is still being read by an upload
     __half *logits = nullptr;                 // output head: caller's logits buffer
     uint32_t head_rows = 0, head_row0 = 0;    // 0: head skipped, 1: token head_row0 only, n_tokens: every token
     uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
@@ -110,7 +119,7 @@ bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __hal
     __half *sbuf = reinterpret_cast<__half *>(A + p.ws.s);
     const bool resid = !(m.flags & PS_FLAG_NO_RESIDUAL);
     const Shard &s = p.shards[op.info.shard0];
-    const uint4 *W = s.resident ? reinterpret_cast<const uint4 *>(A + s.offset)
+    const uint4 *W = s.resident == 1 ? reinterpret_cast<const uint4 *>(A + s.offset)
                                 : reinterpret_cast<const uint4 *>(slot_ptr(st, op.info.slot) + op.info.slot_offset);
     const MatGeom *mg = nullptr;
     GemvArgs a{};
@@ -161,7 +170,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
 
     auto wptr = [&](const Op &o) -> const uint4 * {
         const Shard &s = p.shards[o.info.shard0];
-        if (s.resident) return reinterpret_cast<const uint4 *>(A + s.offset);
+        if (s.resident == 1) return reinterpret_cast<const uint4 *>(A + s.offset);
         return reinterpret_cast<const uint4 *>(slot_ptr(st, o.info.slot) + o.info.slot_offset);
     };
     auto gemv_base = [&](const MatGeom &mg) {
@@ -307,6 +316,83 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     return PS_E_STATE;
 }
 
+double now_ms() {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+// FETCH: the activation buffers a CPU shard reads go to their pinned host copies on the compute
+// stream, and the host waits for them (this also retires every earlier upload from host_out).
+int32_t issue_fetch(ps_stack *st, const Op &op, const __half *x_in, __half *x_out) {
+    const ps_plan &p = st->plan;
+    const ModelGeom &g = p.g;
+    const uint32_t M = p.M, H = g.m.hidden, l = op.info.layer;
+    uint8_t *A = st->arena;
+    const double t0 = now_ms();
+    if (op.info.buffers & PS_BUF_H) {
+        const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+        const void *src = g.has_attn ? static_cast<const void *>(A + p.ws.h) : static_cast<const void *>(xin);
+        PS_HIP(hipMemcpyAsync(st->host_h, src, (size_t)M * H * 2, hipMemcpyDeviceToHost, st->compute));
+    }
+    if (op.info.buffers & PS_BUF_S)
+        PS_HIP(hipMemcpyAsync(st->host_s, A + p.ws.s, (size_t)M * g.ffn_i * 2, hipMemcpyDeviceToHost, st->compute));
+    if (op.info.buffers & PS_BUF_X) {
+        // the head reads every token's final state, or only the requested token's row
+        const size_t row0 = st->head_rows == 1 ? st->head_row0 : 0, rows = st->head_rows == 1 ? 1 : M;
+        PS_HIP(hipMemcpyAsync(st->host_x, x_out + row0 * H, rows * H * 2, hipMemcpyDeviceToHost, st->compute));
+    }
+    PS_HIP(hipStreamSynchronize(st->compute));
+    st->out_upload_pending = false;
+    st->stats.cpu_wait_ms += now_ms() - t0;
+    return PS_OK;
+}
+
+// CPU: one shard on the CPU back-end, straight from its packed image in the pinned host pool; the
+// finished columns are uploaded on the compute stream, in order with the GPU's work on them.
+int32_t issue_cpu(ps_stack *st, const Op &op, __half *x_out) {
+    const ps_plan &p = st->plan;
+    const ModelGeom &g = p.g;
+    const auto &m = g.m;
+    const uint32_t M = p.M, H = m.hidden, l = op.info.layer;
+    uint8_t *A = st->arena;
+    const Shard &s = p.shards[op.info.shard0];
+    if (st->out_upload_pending) { PS_HIP(hipStreamSynchronize(st->compute)); st->out_upload_pending = false; }
+    CpuMatArgs a;
+    a.W = st->shard_host[op.info.shard0];
+    a.ntiles = s.ntiles; a.M = M; a.eps = m.rms_eps; a.out = st->host_out;
+    __half *dst = nullptr;       // device buffer the columns go to
+    const MatGeom *mg = nullptr;
+    switch (op.info.kernel) {
+        case PS_K_GATE_UP:
+            mg = &g.gate_up; a.mode = CPU_GATE_UP; a.x = st->host_h; a.x_stride = H;
+            a.out_stride = g.ffn_i; a.out_col0 = s.tile0 / 2 * 16;
+            dst = reinterpret_cast<__half *>(A + p.ws.s);
+            break;
+        case PS_K_DOWN:
+            mg = &g.down; a.mode = CPU_RESID; a.x = st->host_s; a.x_stride = g.ffn_i;
+            a.res = (m.flags & PS_FLAG_NO_RESIDUAL) ? nullptr : st->host_h;
+            a.out_stride = H; a.out_col0 = s.tile0 * 16;
+            dst = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
+            break;
+        case PS_K_OUT:
+            mg = &g.head; a.mode = CPU_PLAIN; a.x = st->host_x; a.x_stride = H;
+            if (st->head_rows == 1) a.M = 1;
+            a.out_stride = m.vocab; a.out_col0 = s.tile0 * 16;
+            dst = st->logits;
+            break;
+        default: set_error("kernel %u has no CPU form", op.info.kernel); return PS_E_STATE;
+    }
+    a.tile_bytes = mg->tile_bytes; a.nsb = mg->nsb; a.ngroups = mg->ngroups; a.K = mg->K;
+    const uint32_t ncols = (a.mode == CPU_GATE_UP ? s.ntiles / 2 : s.ntiles) * 16;
+    const double t0 = now_ms();
+    cpu_matmul_w4(a, *st->pool, st->cpu_scratch.data());
+    st->stats.cpu_ms += now_ms() - t0;
+    st->stats.cpu_bytes_step += s.bytes;
+    PS_HIP(hipMemcpy2DAsync(dst + a.out_col0, (size_t)a.out_stride * 2, st->host_out + a.out_col0, (size_t)a.out_stride * 2,
+                            (size_t)ncols * 2, a.M, hipMemcpyHostToDevice, st->compute));
+    st->out_upload_pending = true;
+    return PS_OK;
+}
+
 // Ops of the output head (layer index n_layers) that this forward leaves out: all of them, copies
 // included, when no logits are asked for; the RMS factors of every token when only one token's
 // is.  The head's slot fills hold head shards only and nothing follows them, so leaving a fill out
@@ -415,13 +501,16 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
         } else {
             if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
-            int32_t rc = issue_kernel(st, sc, op, x_in, x_out);
+            int32_t rc = o.type == PS_OP_FETCH ? issue_fetch(st, op, x_in, x_out)
+                         : o.type == PS_OP_CPU ? issue_cpu(st, op, x_out) : issue_kernel(st, sc, op, x_in, x_out);
             if (rc) return rc;
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->compute));
             if (o.flags & PS_OPF_RECORD_FREE) PS_HIP(hipEventRecord(st->ev_free[o.slot], st->compute));
             if (o.flags & PS_OPF_RECORD_ROUTER) PS_HIP(hipEventRecord(st->ev_router[o.layer], st->compute));
-            if (o.slot < 0) ss.resident_bytes_step += o.bytes;
-            ss.n_kernels++;
+            if (o.type == PS_OP_KERNEL) {
+                if (o.slot < 0) ss.resident_bytes_step += o.bytes;
+                ss.n_kernels++;
+            }
         }
     }
     st->prof_valid = prof;
@@ -462,7 +551,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         std::vector<std::pair<size_t, uint64_t>> place(p.shards.size());  // chunk, offset
         std::vector<uint64_t> chunk_bytes;
         for (size_t i = 0; i < p.shards.size(); ++i) {
-            if (p.shards[i].resident) continue;
+            if (p.shards[i].resident == 1) continue;
             if (chunk_bytes.empty() || chunk_bytes.back() + p.shards[i].bytes > kHostChunk) chunk_bytes.push_back(0);
             place[i] = {chunk_bytes.size() - 1, chunk_bytes.back()};
             chunk_bytes.back() += p.shards[i].bytes;
@@ -474,7 +563,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
             st->host_chunks.push_back(ptr);
         }
         for (size_t i = 0; i < p.shards.size(); ++i)
-            if (!p.shards[i].resident) st->shard_host[i] = static_cast<uint8_t *>(st->host_chunks[place[i].first]) + place[i].second;
+            if (p.shards[i].resident != 1) st->shard_host[i] = static_cast<uint8_t *>(st->host_chunks[place[i].first]) + place[i].second;
     }
     for (size_t i = 0; i < p.shards.size(); ++i)
         st->cover[std::make_tuple(p.shards[i].layer, p.shards[i].kind, p.shards[i].expert)].push_back((uint32_t)i);
@@ -506,6 +595,23 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         rc = ps::validate_schedule(&st->dense_sched);
         if (rc) return fail(rc);
         st->have_dense_sched = true;
+    }
+    if (p.cpu_bytes) {
+        if (!ps::cpu_backend_supported()) { ps::set_error("the CPU back-end needs AVX-512 (F, BW, VL, DQ) and F16C"); return fail(PS_E_STATE); }
+        const uint32_t H = m.hidden, I = p.g.ffn_i;
+        const size_t widest = std::max<size_t>(std::max(H, I), m.vocab);
+        void *bufs[4] = {};
+        const size_t sizes[4] = {(size_t)p.M * H * 2, (size_t)p.M * I * 2, (size_t)p.M * H * 2, (size_t)p.M * widest * 2};
+        for (int b = 0; b < 4; ++b)
+            if (hipHostMalloc(&bufs[b], sizes[b], hipHostMallocDefault) != hipSuccess) {
+                for (int c = 0; c < b; ++c) (void)hipHostFree(bufs[c]);
+                ps::set_error("hipHostMalloc for the CPU back-end's activation copies failed"); return fail(PS_E_HIP);
+            }
+        st->host_h = static_cast<uint16_t *>(bufs[0]); st->host_s = static_cast<uint16_t *>(bufs[1]);
+        st->host_x = static_cast<uint16_t *>(bufs[2]); st->host_out = static_cast<uint16_t *>(bufs[3]);
+        st->cpu_scratch.resize(ps::cpu_scratch_floats(p.M, std::max(H, I)));
+        const unsigned hw = std::thread::hardware_concurrency();
+        st->pool.reset(new ps::CpuPool(std::min(hw ? hw : 4u, 16u)));
     }
     st->stage_bytes = 32ull << 20;
     if (hipHostMalloc(&st->stage, st->stage_bytes, hipHostMallocDefault) != hipSuccess) {
@@ -570,7 +676,7 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
         }
         // physical tiles t0 + parity, t0 + parity + step, ... (t0 is even for paired matrices)
         const uint32_t count = (nt + step - 1 - parity) / step;
-        if (!s.resident) {
+        if (s.resident != 1) {
             uint8_t *dst = st->shard_host[si] + base_off;
             parallel_for(count, [&](uint32_t j) {
                 const uint32_t pt = t0 + parity + j * step;
@@ -660,6 +766,13 @@ int32_t ps_stack_set_logits_out(ps_stack *st, void *logits_dev, uint32_t first_t
     return PS_OK;
 }
 
+int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads) {
+    if (!st || threads == 0 || threads > 64) { ps::set_error("threads must be 1..64"); return PS_E_ARG; }
+    if (!st->plan.cpu_bytes) { ps::set_error("this plan has no CPU shard"); return PS_E_STATE; }
+    st->pool.reset(new ps::CpuPool(threads));
+    return PS_OK;
+}
+
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits) {
     if (!st || !x_in || !x_out) { ps::set_error("NULL argument"); return PS_E_ARG; }
     if (x_in == x_out) { ps::set_error("x_in and x_out may not alias"); return PS_E_ARG; }
@@ -725,7 +838,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (mode < 0 || mode > 1) { ps::set_error("decode mode must be 0 or 1"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
-    st->use_graph = mode == 1 && !p.g.moe && !p.g.kv && p.M == 1 && p.n_slots == 0 && st->have_dense_sched;
+    st->use_graph = mode == 1 && !p.g.moe && !p.g.kv && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
     return PS_OK;
 }
 
@@ -846,6 +959,7 @@ void ps_stack_destroy(ps_stack *st) {
     }
     for (void *c : st->host_chunks) (void)hipHostFree(c);
     if (st->stage) (void)hipHostFree(st->stage);
+    for (uint16_t *b : {st->host_h, st->host_s, st->host_x, st->host_out}) if (b) (void)hipHostFree(b);
     for (int b = 0; b < 2; ++b) if (st->tables_host[b]) (void)hipHostFree(st->tables_host[b]);
     for (int s = 0; s < 2; ++s) {
         if (st->ev_ready[s]) (void)hipEventDestroy(st->ev_ready[s]);

@@ -1,0 +1,114 @@
+"""GPU parity of the plans that leave shards in system memory and run them on the CPU (Section 3,
+Plan Two "static" and Plan Three "dynamic", and HeuristicSplit's choice among the three): the
+whole stack through the C ABI against the CPU oracle at max|err| / max|ref| <= 5e-3.  Rows computed
+by the CPU back-end and by a GPU kernel sum in different orders, so across plan kinds outputs
+agree to the tolerance, not bit for bit; one plan kind run twice must repeat its bits."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from tests import harness as Hn
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _prof(B):
+    return B.make_profile(h2d_gbps=50.0, gemv_gbps=4000.0, cpu_gbps=200.0, cpu_gbps_busy=150.0, h2d_gbps_busy=45.0,
+                          cpu_tokens_free=4.0, cpu_sync_us=0.5)
+
+
+def _run(cfg, W, head, budget, kind, xs, rows=None, threads=None):
+    import torch
+    from paper_2604_26334_amd import binding as B
+    M = xs[0].shape[0]
+    plan = B.Plan(cfg, int(budget), M, profile=_prof(B), kind=kind)
+    st = B.Stack(plan)
+    if threads and plan.summary().cpu_bytes:
+        st.set_cpu_threads(threads)
+    for layer in range(cfg["n_layers"]):
+        for k, e, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, k, e, *W(layer, k, e))
+    if head is not None:
+        st.load_matrix(cfg["n_layers"], S.MAT_OUT, None, *head)
+    outs = []
+    for x in xs:
+        xin = torch.from_numpy(np.ascontiguousarray(x)).to(st.device)
+        xout = torch.empty_like(xin)
+        lo = None
+        if head is not None:
+            lo = torch.zeros((rows if rows else 1, cfg["vocab"]), dtype=torch.float16, device=st.device)
+            st.set_logits_out(lo, 0 if rows == M else M - 1, rows if rows else 1)
+        torch.cuda.synchronize()
+        st.forward(xin, xout)
+        st.synchronize()
+        outs.append((xout.cpu().numpy(), None if lo is None else lo.cpu().numpy()))
+    s, stats = plan.summary(), st.stats()
+    st.close()
+    plan.close()
+    return outs, s, stats
+
+
+@pytest.mark.parametrize("M", [1, 3, 16])
+def test_static_and_dynamic_plans_match_the_oracle(M):
+    from paper_2604_26334_amd import binding as B
+    cfg = dict(Hn.small_dense_cfg(3), vocab=1040)
+    seed = 60 + M
+    W = Hn.WeightCache(cfg, seed)
+    head = S.head_matrix(seed, cfg)
+    xs = [S.activations(seed, t, M, cfg["hidden"]) for t in range(2)]
+    refs = []
+    for x in xs:
+        rx = O.stack_forward(x, cfg, W, mirror=True)
+        refs.append((rx, O.output_head(rx, cfg, head, mirror=True)))
+    full = B.Plan(cfg, 1 << 40, M).summary()
+    for frac in (0.6, 0.25):
+        budget = full.workspace_bytes + int(full.weight_bytes * frac)
+        for kind in (B.PS_PLAN_GPU_ONLY, B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC, B.PS_PLAN_AUTO):
+            outs, s, stats = _run(cfg, W, head, budget, kind, xs, rows=M)
+            _say("  M %d frac %.2f kind %d -> plan %d: pinned %d streamed %d cpu %d (share %.2f), step: %d B on the CPU in %.2f ms, waited %.2f ms" % (
+                M, frac, kind, s.plan_kind, s.resident_bytes, s.streamed_bytes, s.cpu_bytes, s.cpu_fraction,
+                stats.cpu_bytes_step, stats.cpu_ms, stats.cpu_wait_ms))
+            if kind in (B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC):
+                assert s.cpu_bytes > 0 and stats.cpu_bytes_step == s.cpu_bytes
+            for (xo, lo), (rx, rl) in zip(outs, refs):
+                e_x, e_l = Hn.rel_err(xo, rx), Hn.rel_err(lo, rl)
+                _say("      err x %.3e logits %.3e" % (e_x, e_l))
+                assert np.isfinite(xo.astype(np.float64)).all() and e_x <= TOL and e_l <= TOL
+            if kind == B.PS_PLAN_STATIC:   # same plan, other thread counts: same bits
+                again, _, _ = _run(cfg, W, head, budget, kind, xs, rows=M, threads=3)
+                for (xo, lo), (xo2, lo2) in zip(outs, again):
+                    np.testing.assert_array_equal(xo.view(np.uint16), xo2.view(np.uint16))
+                    np.testing.assert_array_equal(lo.view(np.uint16), lo2.view(np.uint16))
+
+
+def test_cpu_plans_on_the_ffn_block_and_last_token_logits():
+    """No attention, no residual (the FFN input is the caller's tensor); and a head that serves one
+    token of a 16-token plan from the CPU."""
+    from paper_2604_26334_amd import binding as B
+    cfg = S.cfg_ffn_block()
+    W = Hn.WeightCache(cfg, 7)
+    x = S.activations(7, 0, 1, cfg["hidden"])
+    ref = O.stack_forward(x, cfg, W, mirror=True)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    for kind in (B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC):
+        outs, s, stats = _run(cfg, W, None, full.workspace_bytes + full.weight_bytes // 2, kind, [x])
+        e = Hn.rel_err(outs[0][0], ref)
+        _say("  ffn block kind %d: cpu %d B of %d, err %.3e" % (kind, s.cpu_bytes, s.weight_bytes, e))
+        assert s.cpu_bytes > 0 and e <= TOL
+    cfg = dict(Hn.small_dense_cfg(2), vocab=2064)
+    W = Hn.WeightCache(cfg, 8)
+    head = S.head_matrix(8, cfg)
+    x = S.activations(8, 0, 16, cfg["hidden"])
+    rx = O.stack_forward(x, cfg, W, mirror=True)
+    rl = O.output_head(rx[15:], cfg, head, mirror=True)
+    full = B.Plan(cfg, 1 << 40, 16).summary()
+    outs, s, stats = _run(cfg, W, head, full.workspace_bytes + full.weight_bytes // 3, B.PS_PLAN_STATIC, [x], rows=None)
+    e_x, e_l = Hn.rel_err(outs[0][0], rx), Hn.rel_err(outs[0][1], rl)
+    _say("  last token of 16 from a CPU head: err x %.3e logits %.3e" % (e_x, e_l))
+    assert e_x <= TOL and e_l <= TOL

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.ps_model_desc) == 52
-    assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS)
+    assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS + 5)
     assert C.sizeof(B.ps_shard_info) == 48
     assert C.sizeof(B.ps_op_info) == 48
 
@@ -447,3 +447,137 @@ def test_output_head_argument_checks():
     for vocab in (1000, 8, (1 << 20) + 16):
         with pytest.raises(B.PshardError):
             B.Plan(_head_cfg(vocab=vocab), 1 << 40, 1)
+
+
+# ---------------------------------------------------------------- the three schedule plans (Section 3)
+
+def _cpu_prof(**kw):
+    d = dict(h2d_gbps=50.0, gemv_gbps=4000.0, cpu_gbps=200.0, cpu_gbps_busy=150.0, h2d_gbps_busy=45.0,
+             cpu_tokens_free=4.0, cpu_sync_us=20.0)
+    d.update(kw)
+    return B.make_profile(**d)
+
+
+def _plans(cfg, budget, M=1, prof=None):
+    prof = prof or _cpu_prof()
+    return {k: B.Plan(cfg, budget, M, profile=prof, kind=k) for k in (B.PS_PLAN_GPU_ONLY, B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC)}
+
+
+def test_static_plan_keeps_unpinned_ffn_on_the_cpu_and_needs_no_scratch():
+    # Plan Two: the unpinned low-priority sub-layers stay in system memory and run on the CPU
+    cfg = _head_cfg(vocab=2048)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 2
+    pl = _plans(cfg, budget)
+    g, s = pl[B.PS_PLAN_GPU_ONLY].summary(), pl[B.PS_PLAN_STATIC].summary()
+    assert s.plan_kind == B.PS_PLAN_STATIC and s.n_slots == 0 and s.scratch_bytes == 0 and s.streamed_bytes == 0
+    assert s.cpu_bytes > 0 and s.resident_bytes + s.cpu_bytes == s.weight_bytes
+    assert s.resident_bytes > g.resident_bytes            # the scratch went to the pinned region
+    sh = pl[B.PS_PLAN_STATIC].shards()
+    cpu = [x for x in sh if x.resident == 2]
+    assert cpu and all(x.kind in (B.PS_SHARD_GATE_UP, B.PS_SHARD_DOWN, B.PS_SHARD_OUT) for x in cpu)
+    # priority: whatever is on the CPU ranks below everything pinned whole
+    whole = {}
+    for x in sh:
+        whole.setdefault((x.layer, x.kind), []).append(x)
+    pinned_whole = [v[0].priority_rank for v in whole.values() if all(y.resident == 1 for y in v)]
+    assert max(pinned_whole) < min(x.priority_rank for x in cpu) or len(cpu) == 0
+    # every matrix is covered exactly once: pinned head then CPU tail
+    for (layer, kind), v in whole.items():
+        assert [y.tile0 for y in v] == [sum(z.ntiles for z in v[:i]) for i in range(len(v))]
+        assert [y.resident for y in v] in ([1], [2], [1, 2])
+    sched = pl[B.PS_PLAN_STATIC].schedule()
+    assert sched.validate() is None
+    ops = sched.ops()
+    assert not [o for o in ops if o.type == B.PS_OP_COPY]
+    ncpu = [o for o in ops if o.type == B.PS_OP_CPU]
+    assert len(ncpu) == len(cpu) and sum(o.bytes for o in ncpu) == s.cpu_bytes
+    for i, o in enumerate(ops):
+        if o.type != B.PS_OP_CPU:
+            continue
+        # the activations were fetched before the GPU's kernels of the same matrix were launched
+        j = i
+        while j > 0 and ops[j - 1].layer == o.layer and ops[j - 1].kernel == o.kernel and ops[j - 1].type == B.PS_OP_KERNEL:
+            j -= 1
+        want = {B.PS_K_GATE_UP: B.PS_BUF_H, B.PS_K_DOWN: B.PS_BUF_S | B.PS_BUF_H, B.PS_K_OUT: B.PS_BUF_X}[o.kernel]
+        assert o.buffers == want
+        if ops[j - 1].type == B.PS_OP_FETCH and ops[j - 1].kernel == o.kernel:
+            assert ops[j - 1].buffers & want
+
+
+def test_dynamic_plan_splits_unpinned_matrices_between_pcie_and_cpu():
+    # Plan Three: fewer sub-layers on the CPU, the rest time-share the scratch double buffer
+    cfg = _kv_cfg(n_layers=4, ctx=0)
+    cfg = dict(cfg, kv_context=0)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 3
+    pl = _plans(cfg, budget, prof=_cpu_prof(cpu_sync_us=0.5))   # matrices of under 1 MB: keep the fixed cost small too
+    d = pl[B.PS_PLAN_DYNAMIC].summary()
+    s = pl[B.PS_PLAN_STATIC].summary()
+    assert d.n_slots == 2 and d.cpu_bytes > 0 and d.streamed_bytes > 0
+    assert s.streamed_bytes == 0 and d.cpu_bytes < d.weight_bytes - d.resident_bytes   # only part of the unpinned bytes
+    assert d.resident_bytes + d.streamed_bytes + d.cpu_bytes == d.weight_bytes
+    assert 0.0 < d.cpu_fraction < 1.0
+    # with the CPU three times as fast as PCIe, most of the unpinned bytes are the CPU's
+    assert d.cpu_bytes > d.streamed_bytes
+    sh = pl[B.PS_PLAN_DYNAMIC].shards()
+    by = {}
+    for x in sh:
+        by.setdefault((x.layer, x.kind), []).append(x)
+    for v in by.values():   # pinned head, streamed slabs, CPU tail, contiguous
+        res = [y.resident for y in v]
+        assert res == sorted(res, key=lambda r: {1: 0, 0: 1, 2: 2}[r])
+        assert [y.tile0 for y in v] == [sum(z.ntiles for z in v[:i]) for i in range(len(v))]
+    sched = pl[B.PS_PLAN_DYNAMIC].schedule()
+    assert sched.validate() is None
+    ops = sched.ops()
+    assert [o for o in ops if o.type == B.PS_OP_COPY] and [o for o in ops if o.type == B.PS_OP_CPU]
+    # a slower CPU gets a smaller share
+    slow = B.Plan(cfg, budget, 1, profile=_cpu_prof(cpu_gbps=60.0, cpu_gbps_busy=40.0, cpu_sync_us=0.5), kind=B.PS_PLAN_DYNAMIC).summary()
+    assert slow.cpu_fraction < d.cpu_fraction
+
+
+def test_heuristic_split_returns_the_plan_with_the_lowest_estimate():
+    cfg = _kv_cfg(n_layers=4, ctx=0)
+    cfg = dict(cfg, kv_context=0)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 3
+    for prof in (_cpu_prof(), _cpu_prof(cpu_gbps=10.0, cpu_gbps_busy=8.0), _cpu_prof(cpu_gbps=2000.0, cpu_gbps_busy=2000.0)):
+        pl = _plans(cfg, budget, prof=prof)
+        est = [pl[k].summary().est_step_ms for k in range(3)]
+        auto = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_AUTO).summary()
+        assert list(auto.est_kind_ms) == pytest.approx(est)
+        assert auto.plan_kind == int(np.argmin(est)) and auto.est_step_ms == pytest.approx(min(est))
+    # a CPU far slower than PCIe: Plan One; everything fits: nothing to split, Plan One as well
+    assert B.Plan(cfg, budget, 1, profile=_cpu_prof(cpu_gbps=5.0, cpu_gbps_busy=5.0), kind=B.PS_PLAN_AUTO).summary().plan_kind == B.PS_PLAN_GPU_ONLY
+    roomy = B.Plan(cfg, 1 << 40, 1, profile=_cpu_prof(), kind=B.PS_PLAN_AUTO).summary()
+    assert roomy.plan_kind == B.PS_PLAN_GPU_ONLY and roomy.cpu_bytes == 0
+    # prefill-sized tiers never go to the CPU back-end; no CPU rate in the profile: Plan One only
+    big = B.Plan(cfg, budget * 4, 512, profile=_cpu_prof(), kind=B.PS_PLAN_AUTO).summary()
+    assert big.plan_kind == B.PS_PLAN_GPU_ONLY and list(big.est_kind_ms)[1:] == [-1.0, -1.0]
+    none = B.Plan(cfg, budget, 1, kind=B.PS_PLAN_AUTO).summary()
+    assert none.plan_kind == B.PS_PLAN_GPU_ONLY
+    with pytest.raises(B.PshardError):
+        B.Plan(cfg, budget, 1, kind=B.PS_PLAN_STATIC)          # default profile has no CPU rate
+    with pytest.raises(B.PshardError):
+        B.Plan(cfg, budget, 1, profile=_cpu_prof(), kind=7)
+
+
+def test_cpu_plan_estimates_follow_the_papers_rule():
+    """A matrix costs max(GPU side, CPU side); the CPU side is bytes / rate (+ fixed cost), slower
+    beyond cpu_tokens_free tokens; contended rates apply only when a plan both streams and computes."""
+    cfg = _kv_cfg(n_layers=2, ctx=0)
+    cfg = dict(cfg, kv_context=0)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 2
+    prof = _cpu_prof(cpu_sync_us=0.0, launch_us=0.0, gemv_gbps=1e9)       # GPU side ~ free
+    s = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_STATIC).summary()
+    assert s.est_step_ms == pytest.approx(s.cpu_bytes / 200e9 * 1e3, rel=1e-3)
+    s16 = B.Plan(cfg, budget + (1 << 20), 16, profile=prof, kind=B.PS_PLAN_STATIC).summary()
+    assert s16.est_step_ms >= s16.cpu_bytes / 200e9 * 1e3 * 4 * 0.999
+    d = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_DYNAMIC)
+    ds = d.summary()
+    # lower bound: both resources busy the whole time at their contended rates
+    lo = max(ds.cpu_bytes / 150e9, ds.streamed_bytes / 45e9) * 1e3
+    assert ds.est_step_ms >= lo * 0.999
+    assert ds.est_step_ms <= (ds.cpu_bytes / 150e9 + ds.streamed_bytes / 45e9) * 1e3 * 1.001
