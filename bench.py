@@ -256,6 +256,39 @@ def head_leg(B, S, torch, cfg, seed, prof, vocab, budgets, steps):
     return out
 
 
+def plans_leg(B, S, torch, cfg, seed, prof, budget, tokens, steps):
+    """The three schedule plans at one tight budget: all on the GPU through the scratch double buffer,
+    unpinned FFN on the CPU, a split of both; and which one HeuristicSplit picks from its estimates."""
+    names = {B.PS_PLAN_GPU_ONLY: "gpu_only", B.PS_PLAN_STATIC: "static", B.PS_PLAN_DYNAMIC: "dynamic"}
+    out = {}
+    for M in tokens:
+        plans = {k: B.Plan(cfg, int(budget), M, profile=prof, kind=k) for k in names}
+        auto = B.Plan(cfg, int(budget), M, profile=prof, kind=B.PS_PLAN_AUTO).summary()
+        stacks = {k: B.Stack(p) for k, p in plans.items()}
+        B.load_synthetic(list(stacks.values()), cfg, seed, threads=min(16, os.cpu_count() or 8))
+        dev = stacks[B.PS_PLAN_GPU_ONLY].device
+        xs = [torch.from_numpy(S.activations(seed, 900 + t, M, cfg["hidden"])).to(dev) for t in range(4)]
+        xo = torch.empty_like(xs[0])
+        r = dict(budget_bytes=int(budget), tokens=M, picked=names[auto.plan_kind])
+        for k, st in stacks.items():
+            s = plans[k].summary()
+            ms = time_steps(torch, st, xs, xo, steps, 2)
+            stats = st.stats()
+            r[names[k]] = dict(ms_per_step=ms, tokens_per_s=M * 1e3 / ms, est_ms=s.est_step_ms, resident_bytes=s.resident_bytes,
+                               streamed_bytes=s.streamed_bytes, cpu_bytes=s.cpu_bytes, cpu_fraction=s.cpu_fraction,
+                               cpu_ms=stats.cpu_ms, cpu_wait_ms=stats.cpu_wait_ms,
+                               cpu_gbps=(stats.cpu_bytes_step / (stats.cpu_ms * 1e-3) / 1e9) if stats.cpu_ms else None)
+            log("plans at %.0f GB, %d token(s), %s: %.2f ms/step (estimate %.2f), pinned %.2f GB, streamed %.2f GB, on the CPU %.2f GB%s" % (
+                budget / 1e9, M, names[k], ms, s.est_step_ms, s.resident_bytes / 1e9, s.streamed_bytes / 1e9, s.cpu_bytes / 1e9,
+                (" at %.0f GB/s inside the kernel, %.2f ms waiting for the GPU" % (r[names[k]]["cpu_gbps"], stats.cpu_wait_ms)) if stats.cpu_ms else ""))
+            st.close()
+        best = min(names.values(), key=lambda n: r[n]["ms_per_step"])
+        r["measured_best"] = best
+        log("plans at %.0f GB, %d token(s): HeuristicSplit picks %s, measured best %s" % (budget / 1e9, M, r["picked"], best))
+        out["%d" % M] = r
+    return out
+
+
 def measured_traffic(tag):
     """HBM bytes per launch of the named kernel from the committed rocprofv3 PMC summary
     (profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt); None if the summary is absent."""
@@ -279,9 +312,10 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
-    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv,head",
+    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv,head,plans",
                     help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
-                         "kv (decode over a 16K-position KV cache), head (decode with a 128256-row output head)")
+                         "kv (decode over a 16K-position KV cache), head (decode with a 128256-row output head), "
+                         "plans (GPU-only / static / dynamic plan and HeuristicSplit's pick at 2 GB)")
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -313,6 +347,8 @@ def main():
         prof = B.profile_measure(1 << 30)
         log("profile: h2d %.1f GB/s, gemv %.0f GB/s, launch %.2f us, gemm TFLOP/s %s" % (
             prof.h2d_gbps, prof.gemv_gbps, prof.launch_us, ["%.0f" % v for v in prof.gemm_tflops]))
+        log("profile, CPU back-end: %.0f GB/s alone, %.0f GB/s beside H2D copies (which then run at %.1f GB/s), memory-bound up to %.1f tokens, %.0f us per CPU shard" % (
+            prof.cpu_gbps, prof.cpu_gbps_busy, prof.h2d_gbps_busy, prof.cpu_tokens_free, prof.cpu_sync_us))
 
     plans = [B.Plan(cfg, int(b), 1, profile=prof) for b in budgets]
     if args.prefill_tokens:
@@ -392,6 +428,8 @@ def main():
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50)
     if "head" in args.extra and args.layers == 32:
         extra["decode_output_head_128k"] = head_leg(B, S, torch, cfg, seed, prof, 128256, [8e9, 4e9], 100)
+    if "plans" in args.extra and args.layers == 32 and prof is not None and prof.cpu_gbps > 0:
+        extra["schedule_plans_2gb"] = plans_leg(B, S, torch, cfg, seed, prof, 2e9, [1, 16], 8)
     if "moe" in args.extra:
         extra["moe_decode_6gb"] = moe_leg(B, S, torch, seed, prof, 6e9, [1, 16], 10)
 
@@ -412,7 +450,10 @@ def main():
                     cfg["n_layers"], budgets[0] / 1e9), hidden=4096, ffn=14336, weight_bytes=plans[0].summary().weight_bytes),
                 roofline=roof, cpu_baseline=cpu, budgets=results, prefill=prefill, extra=extra,
                 profile=None if prof is None else dict(h2d_gbps=prof.h2d_gbps, gemv_gbps=prof.gemv_gbps,
-                                                       launch_us=prof.launch_us, gemm_tflops=list(prof.gemm_tflops)))
+                                                       launch_us=prof.launch_us, gemm_tflops=list(prof.gemm_tflops),
+                                                       cpu_gbps=prof.cpu_gbps, cpu_gbps_busy=prof.cpu_gbps_busy,
+                                                       h2d_gbps_busy=prof.h2d_gbps_busy, cpu_tokens_free=prof.cpu_tokens_free,
+                                                       cpu_sync_us=prof.cpu_sync_us))
     print(json.dumps(line))
 
 

@@ -37,12 +37,19 @@ def _pick_step(cfg, seed, M, logits_fn, rows):
     raise AssertionError("no activation draw with a finite oracle row")
 
 
-def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, threads=16):
+def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, threads=16, kinds=None):
+    """kinds: one schedule-plan kind per budget (None: Plan One everywhere).  Plans with CPU shards
+    sum some rows in another order, so they are held to the tolerance, not to identical bits."""
     import torch
     from paper_2604_26334_amd import binding as B
     rows = np.arange(M) if sample_rows is None else np.asarray(sample_rows)
     step, logits, ref = _pick_step(cfg, seed, M, logits_fn, rows)
-    plans = [B.Plan(cfg, int(b), M) for b in budgets]
+    if kinds is None:
+        plans = [B.Plan(cfg, int(b), M) for b in budgets]
+    else:
+        prof = B.make_profile(h2d_gbps=55.0, gemv_gbps=5000.0, cpu_gbps=150.0, cpu_gbps_busy=150.0, h2d_gbps_busy=55.0,
+                              cpu_tokens_free=2.5, cpu_sync_us=45.0)
+        plans = [B.Plan(cfg, int(b), M, profile=prof, kind=k) for b, k in zip(budgets, kinds)]
     stacks = [B.Stack(p) for p in plans]
     t0 = time.time()
     B.load_synthetic(stacks, cfg, seed, threads=threads, progress=2000)
@@ -57,15 +64,20 @@ def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, t
         st.forward(xin, xout, logits)
         st.synchronize()
         s = p.summary()
-        _say("  budget %.1f GB: resident %.3f GB, streamed/step %.3f GB, %d copies, %d kernels, first step %.1f ms" % (
-            s.budget_bytes / 1e9, s.resident_bytes / 1e9, st.stats().streamed_bytes_step / 1e9,
-            st.stats().n_copies, st.stats().n_kernels, (time.time() - t0) * 1e3))
+        _say("  budget %.1f GB, plan %d: resident %.3f GB, streamed/step %.3f GB, on the CPU %.3f GB, %d copies, %d kernels, first step %.1f ms" % (
+            s.budget_bytes / 1e9, s.plan_kind, s.resident_bytes / 1e9, st.stats().streamed_bytes_step / 1e9,
+            st.stats().cpu_bytes_step / 1e9, st.stats().n_copies, st.stats().n_kernels, (time.time() - t0) * 1e3))
         outs.append(xout.cpu().numpy())
     for st in stacks:
         st.close()
-    for y in outs[1:]:
-        np.testing.assert_array_equal(y.view(np.uint16), outs[0].view(np.uint16))
-    y = outs[0][rows].astype(np.float64)
+    for y in outs:
+        _compare(y, ref, rows, exact_to=outs[0] if kinds is None else None)
+
+
+def _compare(out, ref, rows, exact_to=None):
+    if exact_to is not None:
+        np.testing.assert_array_equal(out.view(np.uint16), exact_to.view(np.uint16))
+    y = out[rows].astype(np.float64)
     # The synthetic weights have a non-zero mean (E[q - 8] = -0.5), which drives the fp16
     # residual stream of some tokens past 65504 within a few layers: the oracle (rounding to
     # fp16 where the GPU stores fp16) and the GPU then both hold inf/NaN in those token rows.
@@ -83,6 +95,13 @@ def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, t
 def test_dense8b_decode_budgets_2_4_gb():
     _say()
     _run(S.cfg_dense8b(), 0, 1, [4e9, 2e9])
+
+
+def test_dense8b_decode_cpu_plans_at_2gb():
+    """Plans Two and Three and HeuristicSplit's pick on the full 8B-shaped stack, one token, 2 GB."""
+    from paper_2604_26334_amd import binding as B
+    _say()
+    _run(S.cfg_dense8b(), 0, 1, [2e9, 2e9, 2e9], kinds=[B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC, B.PS_PLAN_AUTO])
 
 
 def test_dense8b_prefill_2048_at_4gb():
