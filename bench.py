@@ -107,13 +107,23 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
     """MoE stack (config 4): 48 layers, 128 experts, top-8; decode at each token count."""
     cfg = S.cfg_moe()
     out = {}
-    plans = [B.Plan(cfg, int(budget), m, profile=prof) for m in token_counts]
+    names = ["gpu_only", "static", "dynamic"]
+    plans, tags = [], []
+    for m in token_counts:
+        plans.append(B.Plan(cfg, int(budget), m, profile=prof))
+        tags.append((m, "batch_%d" % m))
+        if prof is not None and prof.cpu_gbps > 0:   # HeuristicSplit's pick, if it is not Plan One again
+            auto = B.Plan(cfg, int(budget), m, profile=prof, kind=B.PS_PLAN_AUTO)
+            log("MoE batch %d: HeuristicSplit estimates %s -> %s" % (m, ["%.1f" % e for e in auto.summary().est_kind_ms], names[auto.summary().plan_kind]))
+            if auto.summary().plan_kind != B.PS_PLAN_GPU_ONLY:
+                plans.append(auto)
+                tags.append((m, "batch_%d_%s" % (m, names[auto.summary().plan_kind])))
     stacks = [B.Stack(p) for p in plans]
     t0 = time.perf_counter()
     B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
     log("loaded MoE stacks in %.1f s" % (time.perf_counter() - t0))
     dev = stacks[0].device
-    for m, plan, st in zip(token_counts, plans, stacks):
+    for (m, tag), plan, st in zip(tags, plans, stacks):
         s = plan.summary()
         xs = [torch.from_numpy(S.activations(seed, 300 + t, m, cfg["hidden"])).to(dev) for t in range(4)]
         lgs = [S.router_logits(seed, 300 + t, cfg["n_layers"], m, cfg["n_experts"]) for t in range(4)]
@@ -122,20 +132,25 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
         for i in range(2):
             st.forward(xs[i], xo, lgs[i])
         st.synchronize()
-        streamed = 0
+        streamed = on_cpu = 0
+        cpu_ms = 0.0
         t0 = time.perf_counter()
         for i in range(steps):
             st.forward(xs[i % 4], xo, lgs[i % 4])
-            streamed += st.stats().streamed_bytes_step
+            stt = st.stats()
+            streamed += stt.streamed_bytes_step
+            on_cpu += stt.cpu_bytes_step
+            cpu_ms += stt.cpu_ms
         st.synchronize()
         ms = (time.perf_counter() - t0) / steps * 1e3
-        out["batch_%d" % m] = dict(budget_bytes=int(budget), tokens_per_step=m, ms_per_step=ms, tokens_per_s=m * 1e3 / ms,
-                                   resident_bytes=s.resident_bytes, streamed_bytes_per_step=streamed / steps,
-                                   pcie_gbps_whole_step=streamed / steps / (ms * 1e-3) / 1e9,
-                                   frac_of_measured_h2d=(streamed / steps / (ms * 1e-3) / 1e9 / prof.h2d_gbps) if prof else None,
-                                   est_ms=s.est_step_ms)
-        log("MoE batch %d, budget %.0f GB: %.2f ms/step, %.1f tok/s, %.2f GB streamed/step" % (
-            m, budget / 1e9, ms, m * 1e3 / ms, streamed / steps / 1e9))
+        out[tag] = dict(budget_bytes=int(budget), tokens_per_step=m, ms_per_step=ms, tokens_per_s=m * 1e3 / ms,
+                        plan=names[s.plan_kind], resident_bytes=s.resident_bytes, streamed_bytes_per_step=streamed / steps,
+                        cpu_bytes_per_step=on_cpu / steps, cpu_ms_per_step=cpu_ms / steps,
+                        pcie_gbps_whole_step=streamed / steps / (ms * 1e-3) / 1e9,
+                        frac_of_measured_h2d=(streamed / steps / (ms * 1e-3) / 1e9 / prof.h2d_gbps) if prof else None,
+                        est_ms=s.est_step_ms)
+        log("MoE batch %d, budget %.0f GB, plan %s: %.2f ms/step (estimate %.2f), %.1f tok/s, %.2f GB streamed/step, %.2f GB/step on the CPU in %.2f ms" % (
+            m, budget / 1e9, names[s.plan_kind], ms, s.est_step_ms, m * 1e3 / ms, streamed / steps / 1e9, on_cpu / steps / 1e9, cpu_ms / steps))
         st.close()
     return out
 

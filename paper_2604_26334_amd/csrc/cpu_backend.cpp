@@ -177,22 +177,21 @@ PS_AVX512 void tile_dot(const uint8_t *tile, uint32_t nsb, uint32_t ngroups, con
 inline float silu(float v) { return v / (1.0f + std::exp(-v)); }
 
 template <int TOK>
-PS_AVX512 void run_units(const CpuMatArgs &a, uint32_t u0, uint32_t u1, uint32_t m0, const float *xp, const float *rinv) {
+PS_AVX512 void run_unit(const CpuMatArgs &a, uint32_t u, uint32_t m0, const float *xp, const float *rinv) {
     const bool gu = a.mode == CPU_GATE_UP;
     float g[16 * TOK], up[16 * TOK];
-    for (uint32_t u = u0; u < u1; ++u) {
-        const uint8_t *t0 = a.W + (size_t)u * (gu ? 2 : 1) * a.tile_bytes;
-        tile_dot<TOK>(t0, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, g);
-        if (gu) tile_dot<TOK>(t0 + a.tile_bytes, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, up);
-        for (int m = 0; m < TOK; ++m) {
-            const size_t row = (size_t)(m0 + m) * a.out_stride + a.out_col0 + (size_t)u * 16u;
-            for (int i = 0; i < 16; ++i) {
-                float v = g[i * TOK + m];
-                if (a.mode == CPU_PLAIN) v = rinv[m0 + m] * v;
-                else if (gu) v = silu(rinv[m0 + m] * v) * (rinv[m0 + m] * up[i * TOK + m]);
-                else if (a.res) v += half_to_float(a.res[row + i]);
-                a.out[row + i] = float_to_half(v);
-            }
+    const uint8_t *t0 = a.W + (size_t)u * (gu ? 2 : 1) * a.tile_bytes;
+    tile_dot<TOK>(t0, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, g);
+    if (gu) tile_dot<TOK>(t0 + a.tile_bytes, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, up);
+    for (int m = 0; m < TOK; ++m) {
+        const size_t row = (size_t)(m0 + m) * a.out_stride + a.out_col0 + (size_t)u * 16u;
+        for (int i = 0; i < 16; ++i) {
+            float v = g[i * TOK + m];
+            if (a.mode == CPU_F32) { a.out_f32[row + i] = v; continue; }
+            if (a.mode == CPU_PLAIN) v = rinv[m0 + m] * v;
+            else if (gu) v = silu(rinv[m0 + m] * v) * (rinv[m0 + m] * up[i * TOK + m]);
+            else if (a.res) v += half_to_float(a.res[row + i]);
+            a.out[row + i] = float_to_half(v);
         }
     }
 }
@@ -201,12 +200,12 @@ PS_AVX512 void run_units(const CpuMatArgs &a, uint32_t u0, uint32_t u1, uint32_t
 
 size_t cpu_scratch_floats(uint32_t M, uint32_t K) { return (size_t)M * K + M + 64; }
 
-PS_AVX512 void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch) {
-    const uint32_t units = a.mode == CPU_GATE_UP ? a.ntiles / 2 : a.ntiles;
-    if (!units || !a.M) return;
-    // activations once per call: fp32, in the order the kernel dequantises a block; RMS factors
+uint32_t cpu_units(const CpuMatArgs &a) { return a.mode == CPU_GATE_UP ? a.ntiles / 2 : a.ntiles; }
+
+// activations once per call: fp32, in the order the kernel dequantises a block; RMS factors
+PS_AVX512 void cpu_prepare(const CpuMatArgs &a, float *scratch) {
     float *xp = scratch, *rinv = scratch + (size_t)a.M * a.K;
-    const bool norm = a.mode != CPU_RESID;
+    const bool norm = a.mode == CPU_PLAIN || a.mode == CPU_GATE_UP;
     for (uint32_t m = 0; m < a.M; ++m) {
         const uint16_t *x = a.x + (size_t)m * a.x_stride;
         float *o = xp + (size_t)m * a.K;
@@ -219,13 +218,27 @@ PS_AVX512 void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch)
             }
         rinv[m] = norm ? 1.0f / std::sqrt((float)(ss / a.K) + a.eps) : 1.0f;
     }
+}
+
+// units [u0, u1) for every token: a tile is read from memory once and stays in cache for the
+// token passes over it
+PS_AVX512 void cpu_run_units(const CpuMatArgs &a, uint32_t u0, uint32_t u1, const float *scratch) {
+    const float *xp = scratch, *rinv = scratch + (size_t)a.M * a.K;
+    for (uint32_t u = u0; u < u1; ++u) {
+        uint32_t m = 0;
+        for (; m + 4 <= a.M; m += 4) run_unit<4>(a, u, m, xp, rinv);
+        for (; m + 2 <= a.M; m += 2) run_unit<2>(a, u, m, xp, rinv);
+        for (; m < a.M; ++m) run_unit<1>(a, u, m, xp, rinv);
+    }
+}
+
+void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch) {
+    const uint32_t units = cpu_units(a);
+    if (!units || !a.M) return;
+    cpu_prepare(a, scratch);
     const uint32_t jobs = std::min(units, pool.size() * 2u);   // two ranges per thread evens out stragglers
     pool.run(jobs, [&](uint32_t j) {
-        const uint32_t u0 = (uint32_t)((uint64_t)units * j / jobs), u1 = (uint32_t)((uint64_t)units * (j + 1) / jobs);
-        uint32_t m = 0;
-        for (; m + 4 <= a.M; m += 4) run_units<4>(a, u0, u1, m, xp, rinv);
-        for (; m + 2 <= a.M; m += 2) run_units<2>(a, u0, u1, m, xp, rinv);
-        for (; m < a.M; ++m) run_units<1>(a, u0, u1, m, xp, rinv);
+        cpu_run_units(a, (uint32_t)((uint64_t)units * j / jobs), (uint32_t)((uint64_t)units * (j + 1) / jobs), scratch);
     });
 }
 

@@ -13,7 +13,7 @@
 
 namespace ps {
 
-enum { CPU_PLAIN = 0, CPU_RESID = 1, CPU_GATE_UP = 2 };   // epilogues, as the GPU kernels' modes
+enum { CPU_PLAIN = 0, CPU_RESID = 1, CPU_GATE_UP = 2, CPU_F32 = 3 };   // epilogues, as the GPU kernels' modes
 
 // Worker threads that run one indexed job at a time.  run(n, fn) calls fn(0..n-1) once each,
 // the caller taking part, and returns when all are done.  Workers spin briefly between jobs of one
@@ -51,6 +51,7 @@ struct CpuMatArgs {
     float eps = 0.f;
     const uint16_t *res = nullptr;  // RESID: fp16 [M][out_stride] added to the result (may be null)
     uint16_t *out = nullptr;        // fp16 [M][out_stride]; this shard writes columns out_col0 ..
+    float *out_f32 = nullptr;       // CPU_F32: raw fp32 sums instead (expert down projection)
     uint32_t out_stride = 0, out_col0 = 0;
 };
 
@@ -60,5 +61,11 @@ bool cpu_backend_supported();
 // scratch: at least cpu_scratch_floats(M, K) floats, reused between calls.
 size_t cpu_scratch_floats(uint32_t M, uint32_t K);
 void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch);
+// The same in two steps, for callers that spread several small matrices over one pool.run:
+// cpu_prepare once per matrix (its own scratch), then cpu_run_units over any split of
+// [0, cpu_units(a)) from any thread.
+uint32_t cpu_units(const CpuMatArgs &a);
+void cpu_prepare(const CpuMatArgs &a, float *scratch);
+void cpu_run_units(const CpuMatArgs &a, uint32_t u0, uint32_t u1, const float *scratch);
 
 }  // namespace ps

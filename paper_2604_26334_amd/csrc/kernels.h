@@ -83,6 +83,8 @@ struct AttnArgs {
     const __half *q;      // the token's QKV row: query head h at [h * 128]
     float *part;
 };
+// dst[idx[r]][0..H) = src[r][0..H) for r < n (fp32 rows; H a multiple of 4; idx values are row numbers of dst)
+hipError_t launch_scatter_rows(const float *src, const int32_t *idx, uint32_t n, uint32_t H, float *dst, hipStream_t st);
 hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st);
 // Merge the chunks of every query head in ascending order with the token's own position (score
 // q.k_new / sqrt(128), value v_new), write the attention output (fp16 [n_q * 128]) and append the

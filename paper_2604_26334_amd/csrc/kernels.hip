@@ -1049,6 +1049,23 @@ hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st) 
 }
 
 // ------------------------------------------------------------------------------------
+// Rows computed on the host (experts run by the CPU back-end) land in one contiguous upload;
+// this puts each where the combine step expects it: dst row idx[r] = src row r.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const float *src, const int32_t *idx, uint32_t H, float *dst) {
+    const float4 *s4 = reinterpret_cast<const float4 *>(src + (size_t)blockIdx.x * H);
+    float4 *d4 = reinterpret_cast<float4 *>(dst + (size_t)idx[blockIdx.x] * H);
+    for (uint32_t j = threadIdx.x; j < H / 4; j += 256) d4[j] = s4[j];
+}
+
+hipError_t launch_scatter_rows(const float *src, const int32_t *idx, uint32_t n, uint32_t H, float *dst, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    if (H % 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3(n), dim3(256), 0, st, src, idx, H, dst);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
 // Split-K epilogue (batched decode): out = epilogue(sum over parts, ascending, of the fp32
 // partial planes).  One thread per output element; GATE_UP pairs a gate column with the up
 // column 16 physical columns further on.

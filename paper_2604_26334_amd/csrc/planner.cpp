@@ -104,7 +104,7 @@ uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M) {
     return (mg.nsb + parts - 1) / parts;
 }
 
-Workspace make_workspace(const ModelGeom &g, uint32_t M) {
+Workspace make_workspace(const ModelGeom &g, uint32_t M, bool cpu_experts) {
     Workspace w;
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, kAlign); return o; };
@@ -130,6 +130,8 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M) {
         w.tasks = take(w.tasks_bytes);
         w.pairs_bytes = (uint64_t)g.m.n_layers * P * 4;
         w.pairs = take(w.pairs_bytes);
+        // landing area of the experts computed on the CPU: fp32 rows [P][H], then their pair indices
+        if (cpu_experts) w.cpu_y = take(P * H * 4 + P * 4);
     } else {
         w.s_bytes = (uint64_t)M * g.ffn_i * 2;
         w.s = take(w.s_bytes);
@@ -159,10 +161,10 @@ struct Cand {  // a whole matrix / expert before any split
     double freq;
 };
 
-// shards that a CPU plan may leave in system memory: dense FFN matrices and the output head (the
-// low end of the priority list); attention matrices, caches and experts always run on the GPU
+// shards that a CPU plan may leave in system memory: FFN matrices, whole experts and the output
+// head (the low end of the priority list); attention matrices and caches always run on the GPU
 static bool cpu_eligible(const Shard &s) {
-    return s.kind == PS_SHARD_GATE_UP || s.kind == PS_SHARD_DOWN || s.kind == PS_SHARD_OUT;
+    return s.kind == PS_SHARD_GATE_UP || s.kind == PS_SHARD_DOWN || s.kind == PS_SHARD_OUT || s.kind == PS_SHARD_EXPERT;
 }
 
 static double shard_compute_ms(const ps_plan &p, uint64_t bytes, double tokens) {
@@ -190,18 +192,23 @@ static void estimate(ps_plan &p, const float *freq) {
     std::vector<double> prob(n, 1.0), comp(n, 0.0), copy(n, 0.0);
     for (size_t i = 0; i < n; ++i) {
         const Shard &s = p.shards[i];
-        if (s.resident == 2) {
-            const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, p.M / p.prof.cpu_tokens_free) : 1.0;
+        double tokens = p.M;
+        if (s.resident == 2 && s.kind != PS_SHARD_EXPERT) {
+            const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, tokens / p.prof.cpu_tokens_free) : 1.0;
             comp[i] = (cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0) + p.prof.cpu_sync_us * 1e-3;
             continue;
         }
-        double tokens = p.M;
         if (s.kind == PS_SHARD_EXPERT) {
             double f = (double)m.top_k / m.n_experts;
             if (freq) f = freq[(size_t)s.layer * m.n_experts + s.expert];
             f = std::min(1.0, std::max(0.0, f));
             prob[i] = 1.0 - std::pow(1.0 - f, (double)p.M);
             tokens = prob[i] > 0 ? p.M * f / prob[i] : 0;
+        }
+        if (s.resident == 2) {   // an expert on the CPU: touched with probability prob, by `tokens` tokens
+            const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, tokens / p.prof.cpu_tokens_free) : 1.0;
+            comp[i] = (cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0) * prob[i];
+            continue;
         }
         comp[i] = shard_compute_ms(p, s.bytes, tokens) * prob[i];
         if (!s.resident && h2d > 0) copy[i] = (double)s.bytes / (h2d * 1e9) * 1e3 * prob[i];
@@ -212,14 +219,17 @@ static void estimate(ps_plan &p, const float *freq) {
     for (size_t j = 0; j < gpu.size(); ++j) tg[gpu[j]] = std::max(comp[gpu[j]], j + 1 < gpu.size() ? copy[gpu[j + 1]] : 0.0);
     double t = gpu.empty() ? 0.0 : copy[gpu[0]], streamed = 0;
     for (size_t i = 0; i < n;) {   // one matrix (or expert, or cache head) at a time
+        // the experts of a layer form one group: the CPU's run beside the GPU's, one hand-over per layer
         size_t j = i;
         double t_gpu = 0, t_cpu = 0;
+        const bool experts = p.shards[i].kind == PS_SHARD_EXPERT;
         while (j < n && p.shards[j].layer == p.shards[i].layer && p.shards[j].kind == p.shards[i].kind &&
-               p.shards[j].expert == p.shards[i].expert) {
+               (experts || p.shards[j].expert == p.shards[i].expert)) {
             if (p.shards[j].resident == 2) t_cpu += comp[j]; else t_gpu += tg[j];
             if (!p.shards[j].resident) streamed += (double)p.shards[j].bytes * prob[j];
             ++j;
         }
+        if (experts && t_cpu > 0) t_cpu += p.prof.cpu_sync_us * 1e-3;
         t += std::max(t_gpu, t_cpu);
         i = j;
     }
@@ -245,7 +255,7 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
     p->kind = kind;
     p->cpu_frac = kind == PS_PLAN_DYNAMIC ? std::min(1.0, std::max(0.0, cpu_frac)) : (kind == PS_PLAN_STATIC ? 1.0 : 0.0);
     p->tier = ps_tier_for_tokens(M);
-    p->ws = make_workspace(p->g, M);
+    p->ws = make_workspace(p->g, M, kind != PS_PLAN_GPU_ONLY);
     p->shards.clear();
     const ModelGeom &g = p->g;
     const auto &m = g.m;
@@ -370,16 +380,26 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
         }
         if (off > budget) { set_error("internal: pinned region overflows the budget"); return PS_E_STATE; }
     }
+    // unpinned experts: the share cpu_frac at the cold end of the priority order stays on the CPU
+    std::vector<char> expert_on_cpu(cands.size(), 0);
+    if (p->cpu_frac > 0 && g.moe) {
+        std::vector<uint32_t> un;
+        for (uint32_t r = 0; r < order.size(); ++r)
+            if (cands[order[r]].s.kind == PS_SHARD_EXPERT && !head_tiles[order[r]]) un.push_back(order[r]);
+        const size_t n_cpu = p->n_slots ? std::min(un.size(), (size_t)std::lround(p->cpu_frac * un.size())) : un.size();
+        for (size_t k = un.size() - n_cpu; k < un.size(); ++k) expert_on_cpu[un[k]] = 1;
+    }
     uint64_t host_off = 0;
     p->resident_bytes = p->streamed_bytes = p->cpu_bytes = 0;
     for (size_t i = 0; i < cands.size(); ++i) {
         const Cand &c = cands[i];
         if (!c.quantum_tiles) {  // expert or cache head: whole
             Shard s = c.s;
-            s.resident = head_tiles[i] ? 1 : 0;
-            s.offset = s.resident ? res_off[i] : host_off;
-            if (!s.resident) host_off += s.bytes;
-            (s.resident ? p->resident_bytes : p->streamed_bytes) += s.bytes;
+            s.resident = head_tiles[i] ? 1 : (expert_on_cpu[i] ? 2 : 0);
+            s.offset = s.resident == 1 ? res_off[i] : host_off;
+            if (s.resident != 1) host_off += s.bytes;
+            (s.resident == 1 ? p->resident_bytes : s.resident == 2 ? p->cpu_bytes : p->streamed_bytes) += s.bytes;
+            if (!s.resident && !p->n_slots) { set_error("internal: streamed shard without scratch"); return PS_E_STATE; }
             p->shards.push_back(s);
             continue;
         }

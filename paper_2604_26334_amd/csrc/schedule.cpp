@@ -219,7 +219,7 @@ struct Builder {
             // shards of this layer's experts are consecutive: si + e
             const size_t e0 = si;
             si += m.n_experts;
-            std::vector<TaskHost> resident, streamed;
+            std::vector<TaskHost> resident, streamed, on_cpu;
             for (uint32_t e = 0; e < m.n_experts; ++e) {
                 TaskHost t;
                 t.shard = (uint32_t)(e0 + e); t.expert = e; t.pair0 = (uint32_t)out->pairs.size();
@@ -227,7 +227,14 @@ struct Builder {
                     if (idx[q] == (int32_t)e) out->pairs.push_back((int32_t)q);
                 t.npairs = (uint32_t)out->pairs.size() - t.pair0;
                 if (!t.npairs) continue;
-                (p->shards[t.shard].resident ? resident : streamed).push_back(t);
+                const uint32_t where = p->shards[t.shard].resident;
+                (where == 1 ? resident : where == 2 ? on_cpu : streamed).push_back(t);
+            }
+            if (!on_cpu.empty()) {   // the FFN input goes to the host before the GPU's experts are launched
+                KernelItem f;
+                f.op = kernel_op(PS_K_EXPERT_GATE_UP, l);
+                f.op.info.type = PS_OP_FETCH; f.op.info.nshards = 0; f.op.info.buffers = PS_BUF_H;
+                kernels.push_back(f);
             }
             add_expert_launch(l, resident, -1);
             std::vector<TaskHost> cur;
@@ -242,6 +249,16 @@ struct Builder {
             }
             add_expert_launch(l, cur, cur_batch);
             batch_open = false;
+            if (!on_cpu.empty()) {   // one host step for all of the layer's CPU experts, beside the GPU's launches
+                KernelItem k;
+                k.op = kernel_op(PS_K_EXPERT_GATE_UP, l);
+                k.op.info.type = PS_OP_CPU; k.op.info.buffers = PS_BUF_H;
+                k.op.info.shard0 = on_cpu[0].shard; k.op.info.nshards = (uint32_t)on_cpu.size();
+                k.op.task0 = (uint32_t)out->tasks.size(); k.op.ntasks = (uint32_t)on_cpu.size();
+                for (auto &t : on_cpu) k.op.info.bytes += p->shards[t.shard].bytes;
+                out->tasks.insert(out->tasks.end(), on_cpu.begin(), on_cpu.end());
+                kernels.push_back(k);
+            }
             add_plain(PS_K_COMBINE, l);
         }
         if (m.vocab) {   // output head on the final hidden state (its own RMS factor when several tokens)

@@ -59,6 +59,7 @@ struct ps_stack {
     std::unique_ptr<ps::CpuPool> pool;
     uint16_t *host_h = nullptr, *host_s = nullptr, *host_x = nullptr, *host_out = nullptr;
     std::vector<float> cpu_scratch;
+    std::vector<uint16_t> cpu_xg, cpu_sg;     // MoE: the CPU experts' gathered inputs and SwiGLU outputs, per pair
     bool out_upload_pending = false;          // host_out is still being read by an upload
     __half *logits = nullptr;                 // output head: caller's logits buffer
     uint32_t head_rows = 0, head_row0 = 0;    // 0: head skipped, 1: token head_row0 only, n_tokens: every token
@@ -348,7 +349,75 @@ int32_t issue_fetch(ps_stack *st, const Op &op, const __half *x_in, __half *x_ou
 
 // CPU: one shard on the CPU back-end, straight from its packed image in the pinned host pool; the
 // finished columns are uploaded on the compute stream, in order with the GPU's work on them.
-int32_t issue_cpu(ps_stack *st, const Op &op, __half *x_out) {
+// The CPU's experts of one MoE layer: for every such expert its routed (token, rank) pairs go
+// through gate/up + SwiGLU and the down projection on the host; all experts share two passes over
+// the worker pool.  The fp32 result rows travel in one upload, followed by their pair numbers, and
+// a scatter kernel puts them where the combine step reads them.
+int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
+    const ps_plan &p = st->plan;
+    const ModelGeom &g = p.g;
+    const auto &m = g.m;
+    const uint32_t H = m.hidden, I = g.ffn_i, P = p.M * m.top_k;
+    if (st->out_upload_pending) { PS_HIP(hipStreamSynchronize(st->compute)); st->out_upload_pending = false; }
+    std::vector<CpuMatArgs> gu(op.ntasks), dn(op.ntasks);
+    std::vector<size_t> scr(op.ntasks + 1, 0);
+    float *yrows = reinterpret_cast<float *>(st->host_out);
+    uint32_t row = 0;
+    uint64_t bytes = 0;
+    for (uint32_t k = 0; k < op.ntasks; ++k) {
+        const TaskHost &t = sc.tasks[op.task0 + k];
+        if (row + t.npairs > P) { set_error("internal: CPU expert pairs exceed the workspace"); return PS_E_STATE; }
+        for (uint32_t q = 0; q < t.npairs; ++q) {
+            const int32_t pair = sc.pairs[t.pair0 + q];
+            if (pair < 0 || (uint32_t)pair >= P) { set_error("internal: pair index out of range"); return PS_E_STATE; }
+            std::memcpy(st->cpu_xg.data() + (size_t)(row + q) * H, st->host_h + (size_t)(pair / m.top_k) * H, (size_t)H * 2);
+            reinterpret_cast<int32_t *>(yrows + (size_t)P * H)[row + q] = pair;
+        }
+        CpuMatArgs a;
+        a.W = st->shard_host[t.shard]; a.ntiles = g.gate_up.ntiles; a.tile_bytes = g.gate_up.tile_bytes;
+        a.nsb = g.gate_up.nsb; a.ngroups = g.gate_up.ngroups; a.K = H; a.M = t.npairs; a.eps = m.rms_eps;
+        a.mode = CPU_GATE_UP; a.x = st->cpu_xg.data() + (size_t)row * H; a.x_stride = H;
+        a.out = st->cpu_sg.data() + (size_t)row * I; a.out_stride = I; a.out_col0 = 0;
+        gu[k] = a;
+        CpuMatArgs b;
+        b.W = st->shard_host[t.shard] + g.gate_up.bytes; b.ntiles = g.down.ntiles; b.tile_bytes = g.down.tile_bytes;
+        b.nsb = g.down.nsb; b.ngroups = g.down.ngroups; b.K = I; b.M = t.npairs; b.mode = CPU_F32;
+        b.x = a.out; b.x_stride = I; b.out_f32 = yrows + (size_t)row * H; b.out_stride = H; b.out_col0 = 0;
+        dn[k] = b;
+        scr[k + 1] = scr[k] + cpu_scratch_floats(t.npairs, std::max(H, I));
+        row += t.npairs;
+        bytes += p.shards[t.shard].bytes;
+    }
+    if (st->cpu_scratch.size() < scr[op.ntasks]) st->cpu_scratch.resize(scr[op.ntasks]);
+    const double t0 = now_ms();
+    for (int phase = 0; phase < 2; ++phase) {
+        std::vector<CpuMatArgs> &mats = phase ? dn : gu;
+        // units of all experts in one job list; about two jobs per thread
+        uint32_t total = 0;
+        for (auto &a : mats) { cpu_prepare(a, st->cpu_scratch.data() + scr[&a - mats.data()]); total += cpu_units(a); }
+        const uint32_t per = std::max(1u, total / (st->pool->size() * 2u));
+        struct Job { uint32_t mat, u0, u1; };
+        std::vector<Job> jobs;
+        for (uint32_t k = 0; k < mats.size(); ++k)
+            for (uint32_t u = 0, n = cpu_units(mats[k]); u < n; u += per) jobs.push_back(Job{k, u, std::min(n, u + per)});
+        st->pool->run((uint32_t)jobs.size(), [&](uint32_t j) {
+            cpu_run_units(mats[jobs[j].mat], jobs[j].u0, jobs[j].u1, st->cpu_scratch.data() + scr[jobs[j].mat]);
+        });
+    }
+    st->stats.cpu_ms += now_ms() - t0;
+    st->stats.cpu_bytes_step += bytes;
+    // rows, then (at the fixed offset P * H floats) their pair numbers
+    uint8_t *land = st->arena + p.ws.cpu_y;
+    PS_HIP(hipMemcpyAsync(land, yrows, (size_t)row * H * 4, hipMemcpyHostToDevice, st->compute));
+    PS_HIP(hipMemcpyAsync(land + (size_t)P * H * 4, yrows + (size_t)P * H, (size_t)row * 4, hipMemcpyHostToDevice, st->compute));
+    PS_HIP(launch_scatter_rows(reinterpret_cast<const float *>(land), reinterpret_cast<const int32_t *>(land + (size_t)P * H * 4), row, H,
+                               reinterpret_cast<float *>(st->arena + p.ws.y), st->compute));
+    st->out_upload_pending = true;
+    return PS_OK;
+}
+
+int32_t issue_cpu(ps_stack *st, const ps_schedule &sc, const Op &op, __half *x_out) {
+    if (op.info.kernel == PS_K_EXPERT_GATE_UP) return issue_cpu_experts(st, sc, op);
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
     const auto &m = g.m;
@@ -502,7 +571,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
             int32_t rc = o.type == PS_OP_FETCH ? issue_fetch(st, op, x_in, x_out)
-                         : o.type == PS_OP_CPU ? issue_cpu(st, op, x_out) : issue_kernel(st, sc, op, x_in, x_out);
+                         : o.type == PS_OP_CPU ? issue_cpu(st, sc, op, x_out) : issue_kernel(st, sc, op, x_in, x_out);
             if (rc) return rc;
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->compute));
             if (o.flags & PS_OPF_RECORD_FREE) PS_HIP(hipEventRecord(st->ev_free[o.slot], st->compute));
@@ -600,8 +669,12 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         if (!ps::cpu_backend_supported()) { ps::set_error("the CPU back-end needs AVX-512 (F, BW, VL, DQ) and F16C"); return fail(PS_E_STATE); }
         const uint32_t H = m.hidden, I = p.g.ffn_i;
         const size_t widest = std::max<size_t>(std::max(H, I), m.vocab);
+        const size_t P = (size_t)p.M * std::max(1u, m.top_k);
         void *bufs[4] = {};
-        const size_t sizes[4] = {(size_t)p.M * H * 2, (size_t)p.M * I * 2, (size_t)p.M * H * 2, (size_t)p.M * widest * 2};
+        // host_out doubles as the CPU experts' landing image: fp32 rows [P][H], then P pair numbers
+        const size_t sizes[4] = {(size_t)p.M * H * 2, (size_t)p.M * I * 2, (size_t)p.M * H * 2,
+                                 std::max((size_t)p.M * widest * 2, p.g.moe ? P * H * 4 + P * 4 : 0)};
+        if (p.g.moe) { st->cpu_xg.resize(P * H); st->cpu_sg.resize(P * I); }
         for (int b = 0; b < 4; ++b)
             if (hipHostMalloc(&bufs[b], sizes[b], hipHostMallocDefault) != hipSuccess) {
                 for (int c = 0; c < b; ++c) (void)hipHostFree(bufs[c]);
@@ -812,7 +885,8 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     for (size_t t = 0; t < sc.tasks.size(); ++t) {
         const ps::TaskHost &h = sc.tasks[t];
         const ps::Shard &s = p.shards[h.shard];
-        const uint8_t *w = s.resident ? st->arena + s.offset : slot_ptr(st, h.slot) + h.slot_offset;
+        // (experts run by the CPU are never launched on the GPU: their entries only keep the table dense)
+        const uint8_t *w = s.resident == 1 ? st->arena + s.offset : s.resident == 2 ? st->arena : slot_ptr(st, h.slot) + h.slot_offset;
         dt[t].w_gate_up = (uint64_t)(uintptr_t)w;
         dt[t].w_down = (uint64_t)(uintptr_t)(w + p.g.gate_up.bytes);
         dt[t].pair0 = h.pair0; dt[t].npairs = h.npairs; dt[t].expert = h.expert; dt[t].pad = 0;

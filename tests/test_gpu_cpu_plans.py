@@ -112,3 +112,43 @@ def test_cpu_plans_on_the_ffn_block_and_last_token_logits():
     e_x, e_l = Hn.rel_err(outs[0][0], rx), Hn.rel_err(outs[0][1], rl)
     _say("  last token of 16 from a CPU head: err x %.3e logits %.3e" % (e_x, e_l))
     assert e_x <= TOL and e_l <= TOL
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_moe_experts_on_the_cpu_match_the_oracle(M):
+    """Unpinned experts run by the CPU back-end (static), or split between PCIe and the CPU (dynamic)."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = Hn.small_moe_cfg(3)
+    seed = 80 + M
+    W = Hn.WeightCache(cfg, seed)
+    steps = 3
+    xs = [S.activations(seed, t, M, cfg["hidden"]) for t in range(steps)]
+    lgs = [S.router_logits(seed, t, cfg["n_layers"], M, cfg["n_experts"]) for t in range(steps)]
+    refs = [O.stack_forward(x, cfg, W, logits=lg, mirror=True) for x, lg in zip(xs, lgs)]
+    full = B.Plan(cfg, 1 << 40, M).summary()
+    for frac in (0.6, 0.2):
+        budget = full.workspace_bytes + int(full.weight_bytes * frac) + 65536
+        for kind in (B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC, B.PS_PLAN_AUTO):
+            plan = B.Plan(cfg, budget, M, profile=_prof(B), kind=kind)
+            st = B.Stack(plan)
+            for layer in range(cfg["n_layers"]):
+                for k, e, N, K in S.matrix_shapes(cfg):
+                    st.load_matrix(layer, k, e, *W(layer, k, e))
+            s = plan.summary()
+            cpu_seen = 0
+            for x, lg, ref in zip(xs, lgs, refs):
+                xin = torch.from_numpy(x).to(st.device)
+                xout = torch.empty_like(xin)
+                torch.cuda.synchronize()
+                st.forward(xin, xout, lg)
+                st.synchronize()
+                e = Hn.rel_err(xout.cpu().numpy(), ref)
+                cpu_seen += st.stats().cpu_bytes_step
+                assert e <= TOL, (M, frac, kind, e)
+            _say("  MoE M %d frac %.1f kind %d -> plan %d: pinned %d streamed %d cpu %d; %d B went through the CPU in %d steps, last err %.3e" % (
+                M, frac, kind, s.plan_kind, s.resident_bytes, s.streamed_bytes, s.cpu_bytes, cpu_seen, steps, e))
+            if kind == B.PS_PLAN_STATIC:
+                assert s.cpu_bytes > 0 and cpu_seen > 0
+            st.close()
+            plan.close()

@@ -123,6 +123,16 @@ def test_moe_decode_at_6gb(M):
     _run(cfg, 0, M, [6e9], logits_fn=lambda step: S.router_logits(0, step, cfg["n_layers"], M, cfg["n_experts"]))
 
 
+@pytest.mark.parametrize("M", [1, 16])
+def test_moe_decode_with_cpu_experts_at_6gb(M):
+    """The full MoE stack with its unpinned experts on the CPU back-end (Plan Two) and split (Plan Three)."""
+    from paper_2604_26334_amd import binding as B
+    _say()
+    cfg = S.cfg_moe()
+    _run(cfg, 0, M, [6e9, 6e9], logits_fn=lambda step: S.router_logits(0, step, cfg["n_layers"], M, cfg["n_experts"]),
+         kinds=[B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC])
+
+
 def test_dense8b_decode_over_a_4k_kv_cache():
     """The 8B-shaped stack with real decode attention over 4096 cached positions per kv head (the KV
     cache planned as its own shard class), two consecutive steps, all pinned / FFN streamed / cache

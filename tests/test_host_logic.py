@@ -581,3 +581,42 @@ def test_cpu_plan_estimates_follow_the_papers_rule():
     lo = max(ds.cpu_bytes / 150e9, ds.streamed_bytes / 45e9) * 1e3
     assert ds.est_step_ms >= lo * 0.999
     assert ds.est_step_ms <= (ds.cpu_bytes / 150e9 + ds.streamed_bytes / 45e9) * 1e3 * 1.001
+
+
+def test_cpu_plans_put_cold_unpinned_experts_on_the_cpu():
+    cfg = dict(S.cfg_moe(3), n_experts=16, top_k=4)
+    M = 4
+    lg = S.router_logits(3, 0, 3, M, 16)
+    full = B.Plan(cfg, 1 << 40, M).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 2
+    freq = np.random.default_rng(0).random((3, 16)).astype(np.float32)
+    prof = _cpu_prof(cpu_sync_us=0.5)
+    st = B.Plan(cfg, budget, M, profile=prof, expert_freq=freq, kind=B.PS_PLAN_STATIC)
+    s = st.summary()
+    sh = st.shards()
+    ex = [x for x in sh if x.kind == B.PS_SHARD_EXPERT]
+    assert s.n_slots == 0 and s.streamed_bytes == 0 and s.cpu_bytes == sum(x.bytes for x in ex if x.resident == 2) > 0
+    assert all(x.resident == 1 for x in sh if x.kind != B.PS_SHARD_EXPERT)
+    # the pinned experts are the frequent ones
+    assert min(freq[x.layer, x.expert] for x in ex if x.resident == 1) >= max(freq[x.layer, x.expert] for x in ex if x.resident == 2)
+    sched = st.schedule(lg)
+    assert sched.validate() is None
+    ops = sched.ops()
+    assert not [o for o in ops if o.type == B.PS_OP_COPY]
+    for layer in range(3):
+        kinds = [(o.type, o.kernel) for o in ops if o.layer == layer]
+        if (B.PS_OP_CPU, B.PS_K_EXPERT_GATE_UP) in kinds:
+            i_f, i_c = kinds.index((B.PS_OP_FETCH, B.PS_K_EXPERT_GATE_UP)), kinds.index((B.PS_OP_CPU, B.PS_K_EXPERT_GATE_UP))
+            i_r, i_m = kinds.index((B.PS_OP_KERNEL, B.PS_K_ROUTE)), kinds.index((B.PS_OP_KERNEL, B.PS_K_COMBINE))
+            assert i_r < i_f < i_c < i_m
+            gpu = [i for i, k in enumerate(kinds) if k == (B.PS_OP_KERNEL, B.PS_K_EXPERT_GATE_UP)]
+            assert all(i_f < i < i_c for i in gpu)     # the GPU's experts are in flight while the host computes
+    dy = B.Plan(cfg, budget, M, profile=prof, expert_freq=freq, kind=B.PS_PLAN_DYNAMIC)
+    d = dy.summary()
+    assert d.n_slots == 2 and d.cpu_bytes > 0 and d.resident_bytes + d.streamed_bytes + d.cpu_bytes == d.weight_bytes
+    dex = [x for x in dy.shards() if x.kind == B.PS_SHARD_EXPERT]
+    if d.streamed_bytes:   # streamed experts outrank the CPU's
+        assert max(x.priority_rank for x in dex if x.resident == 0) < min(x.priority_rank for x in dex if x.resident == 2)
+    assert dy.schedule(lg).validate() is None
+    auto = B.Plan(cfg, budget, M, profile=prof, expert_freq=freq, kind=B.PS_PLAN_AUTO).summary()
+    assert auto.est_step_ms == pytest.approx(min(e for e in auto.est_kind_ms if e >= 0))
