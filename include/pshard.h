@@ -277,6 +277,8 @@ void ps_plan_destroy(ps_plan *plan);
  * the budget is recorded as infeasible (it is not an error).  Host only, no GPU needed.
  * Arguments as for ps_plan_create; *out is owned by the caller until ps_tier_table_destroy. */
 typedef struct ps_tier_table ps_tier_table;
+/* (ps_tier_table_create_kind, below, lets every tier of at most 64 tokens be planned as one of
+ * the CPU plans or by HeuristicSplit, as Algorithm 1 does per tier; larger tiers keep Plan One) */
 typedef struct ps_tier_entry {
     uint32_t tier;             /* index into J                                            */
     uint32_t tier_tokens;      /* tokens one trip through this tier's schedule processes  */
@@ -298,6 +300,9 @@ typedef struct ps_tier_choice {
 int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t vram_budget_bytes,
                              const ps_profile *profile, const float *expert_freq,
                              ps_tier_table **out);
+int32_t ps_tier_table_create_kind(const ps_model_desc *model, uint64_t vram_budget_bytes,
+                                  const ps_profile *profile, const float *expert_freq,
+                                  uint32_t kind, ps_tier_table **out);
 int32_t ps_tier_table_entry(const ps_tier_table *table, uint32_t tier, ps_tier_entry *out);
 /* the plan of a feasible tier, owned by the table (valid until ps_tier_table_destroy);
  * ps_stack_create copies it.  PS_E_ARG for an infeasible tier. */

@@ -83,7 +83,8 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
            "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
-           "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads"]
+           "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads",
+           "ps_tier_table_create_kind"]
 
 _lib = None
 
@@ -133,6 +134,7 @@ def lib():
             "ps_mfma_probe": [i32, i32, i32, vp, vp],
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
             "ps_tier_table_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, C.POINTER(vp)],
+            "ps_tier_table_create_kind": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, u32, C.POINTER(vp)],
             "ps_tier_table_entry": [vp, u32, C.POINTER(ps_tier_entry)],
             "ps_tier_table_plan": [vp, u32, C.POINTER(vp)],
             "ps_tier_pick": [vp, u32, C.POINTER(ps_tier_choice)],
@@ -297,14 +299,18 @@ class _TierPlan(Plan):
 class TierTable:
     """ps_tier_table_*: one plan per token tier under one budget, and PickTier."""
 
-    def __init__(self, cfg, budget_bytes, profile=None, expert_freq=None):
+    def __init__(self, cfg, budget_bytes, profile=None, expert_freq=None, kind=None):
         self.cfg = cfg
         self.desc = model_desc(cfg)
         self.profile = profile if profile is not None else make_profile()
         self.h = C.c_void_p()
         freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
-        _check(lib().ps_tier_table_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), _ptr(freq),
-                                          C.byref(self.h)))
+        if kind is None:
+            _check(lib().ps_tier_table_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), _ptr(freq),
+                                              C.byref(self.h)))
+        else:
+            _check(lib().ps_tier_table_create_kind(C.byref(self.desc), int(budget_bytes), C.byref(self.profile),
+                                                   _ptr(freq), int(kind), C.byref(self.h)))
 
     def entry(self, tier):
         e = ps_tier_entry()

@@ -564,7 +564,13 @@ void ps_plan_destroy(ps_plan *p) { delete p; }
 
 int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
                              const float *expert_freq, ps_tier_table **out) {
+    return ps_tier_table_create_kind(model, budget, prof, expert_freq, PS_PLAN_GPU_ONLY, out);
+}
+
+int32_t ps_tier_table_create_kind(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                                  const float *expert_freq, uint32_t kind, ps_tier_table **out) {
     if (!out) { ps::set_error("out is NULL"); return PS_E_ARG; }
+    if (kind > PS_PLAN_AUTO) { ps::set_error("unknown plan kind %u", kind); return PS_E_ARG; }
     *out = nullptr;
     ps_tier_table *tb = new (std::nothrow) ps_tier_table();
     if (!tb) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
@@ -573,7 +579,9 @@ int32_t ps_tier_table_create(const ps_model_desc *model, uint64_t budget, const 
         if (!p) { delete tb; ps::set_error("out of host memory"); return PS_E_NOMEM; }
         // attention over a KV cache is built for one token per step: only that tier has a schedule
         if (model && model->kv_context && t > 0) { delete p; continue; }
-        const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, PS_PLAN_GPU_ONLY, p);
+        // the CPU back-end takes at most 64 tokens: larger tiers keep Plan One whatever was asked for
+        const uint32_t k = ps::kTiers[t] > 64 ? (uint32_t)PS_PLAN_GPU_ONLY : kind;
+        const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, k, p);
         if (rc == PS_OK) { tb->plans[t] = p; continue; }
         delete p;
         if (rc != PS_E_BUDGET) { delete tb; return rc; }   // a bad model or profile fails every tier

@@ -620,3 +620,28 @@ def test_cpu_plans_put_cold_unpinned_experts_on_the_cpu():
     assert dy.schedule(lg).validate() is None
     auto = B.Plan(cfg, budget, M, profile=prof, expert_freq=freq, kind=B.PS_PLAN_AUTO).summary()
     assert auto.est_step_ms == pytest.approx(min(e for e in auto.est_kind_ms if e >= 0))
+
+
+def test_tier_table_plans_each_small_tier_with_heuristic_split():
+    # Algorithm 1: for every tier, HeuristicSplit; the CPU back-end serves tiers of at most 64 tokens
+    cfg = _kv_cfg(n_layers=4, ctx=0)
+    cfg = dict(cfg, kv_context=0)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 3 + (1 << 20)
+    prof = _cpu_prof(cpu_sync_us=0.5)
+    tb = B.TierTable(cfg, budget, profile=prof, kind=B.PS_PLAN_AUTO)
+    base = B.TierTable(cfg, budget, profile=prof)
+    for e, b in zip(tb.entries(), base.entries()):
+        assert e.feasible == b.feasible
+        if not e.feasible:
+            continue
+        if e.tier_tokens > 64:
+            assert e.summary.plan_kind == B.PS_PLAN_GPU_ONLY and e.summary.est_step_ms == b.summary.est_step_ms
+        else:
+            want = B.Plan(cfg, budget, e.tier_tokens, profile=prof, kind=B.PS_PLAN_AUTO).summary()
+            assert e.summary.plan_kind == want.plan_kind and e.summary.est_step_ms == pytest.approx(want.est_step_ms)
+            assert e.summary.est_step_ms <= b.summary.est_step_ms * (1 + 1e-12)
+    assert tb.entry(0).summary.plan_kind != B.PS_PLAN_GPU_ONLY        # one token, CPU 4x PCIe: a CPU plan wins
+    assert tb.pick(1).est_total_ms <= base.pick(1).est_total_ms
+    with pytest.raises(B.PshardError):
+        B.TierTable(cfg, budget, profile=prof, kind=9)
