@@ -250,3 +250,51 @@ def pick_tier(est_ms, new_tokens, tier_tokens=TIER_TOKENS):
     if best is None:
         raise ValueError("no tier has a schedule")
     return best[0], best[1], float(best[2])
+
+
+# ---- profile database (Section 3, profiler-based timing estimation) -----------------------------
+
+OPK_GEMV, OPK_GEMM, OPK_CPU, OPK_H2D = 0, 1, 2, 3
+
+
+def op_work(op, quant, n, k, m):
+    """(floating point operations, bytes moved) of one benchmarked operation: a [n][k] block-format
+    matrix (quant bits per weight plus one fp16 scale per 32 weights) times m fp16 activation rows,
+    or, for a copy, n bytes."""
+    if op == OPK_H2D:
+        return 0.0, float(n)
+    flops = 2.0 * n * k * m
+    nbytes = n * k * (quant / 8.0 + 2.0 / 32.0) + 2.0 * m * (k + n)
+    return flops, nbytes
+
+
+def profile_estimate(entries, bandwidth_gbps, op, quant, threads, n, k, m):
+    """Time estimate of one kernel from a profile database, as the paper's estimator does it.
+
+    entries: list of (op, quant, threads, n, k, m, ms).  Returns (ms, match) with match
+    'exact' (same op, quantisation, thread count and dimensions: the entry's own rate),
+    'neighbour' (same op, quantisation and thread count, other dimensions: the entry nearest in
+    the space of dimensions gives the FLOPS roof of a roofline whose memory roof is
+    bandwidth_gbps; the kernel is priced compute-bound or memory-bound by where its arithmetic
+    intensity falls), or 'none' (no entry of that op, quantisation and thread count: skipped, 0 ms).
+    Distance: Euclidean in (log2 n, log2 k, log2 m); equal distances keep the earlier entry.
+    A copy has no FLOPS: its rate in bytes/s takes that place."""
+    import math
+    flops, nbytes = op_work(op, quant, n, k, m)
+    same = [e for e in entries if e[0] == op and e[1] == quant and e[2] == threads]
+    for e in same:
+        if (e[3], e[4], e[5]) == (n, k, m):
+            return float(e[6]), "exact"
+    if not same:
+        return 0.0, "none"
+    def dist(e):
+        return math.sqrt(sum((math.log2(a) - math.log2(b)) ** 2 for a, b in zip((e[3], e[4], e[5]), (n, k, m))))
+    best = min(same, key=dist)      # min keeps the first of equal keys
+    e_flops, e_bytes = op_work(best[0], best[1], best[3], best[4], best[5])
+    if op == OPK_H2D:
+        return nbytes / (e_bytes / best[6]), "neighbour"
+    roof_flops = e_flops / (best[6] * 1e-3)             # flop/s of the neighbour
+    roof_bw = bandwidth_gbps * 1e9
+    if flops / nbytes >= roof_flops / roof_bw:          # right of the ridge: compute-bound
+        return flops / roof_flops * 1e3, "neighbour"
+    return nbytes / roof_bw * 1e3, "neighbour"

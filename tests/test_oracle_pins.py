@@ -492,3 +492,43 @@ def test_output_head_mirror_rounds_logits_to_fp16_only():
     mir = O.output_head(x, cfg, head, mirror=True)
     assert np.array_equal(mir, pure.astype(np.float16).astype(np.float64))
     assert np.abs(mir - pure).max() <= np.abs(pure).max() * 2.0 ** -11
+
+
+# ---------------------------------------------------------------- profile database estimate
+
+def _profile_golden():
+    ent, qs = [], []
+    for ln in open(os.path.join(os.path.dirname(__file__), "golden", "profile_db_example.txt")):
+        f = ln.split()
+        if not f or f[0] == "#":
+            continue
+        if f[0] == "E":
+            ent.append(tuple(int(v) for v in f[1:7]) + (float(f[7]),))
+        else:
+            qs.append((float(f[1]), tuple(int(v) for v in f[2:8]), float(f[9]), f[10]))
+    return ent, qs
+
+
+def test_profile_estimate_hand_worked_examples():
+    ent, qs = _profile_golden()
+    assert len(ent) == 5 and len(qs) == 7
+    for bw, q, want_ms, want_match in qs:
+        ms, match = O.profile_estimate(ent, bw, *q)
+        assert match == want_match, (q, match)
+        assert ms == pytest.approx(want_ms, rel=1e-9), (q, ms)
+
+
+def test_profile_estimate_properties():
+    ent = [(O.OPK_GEMM, 4, 0, 4096, 4096, 512, 2.0), (O.OPK_GEMM, 4, 0, 4096, 4096, 16, 0.3)]
+    # compute-bound side: time scales with the work, at the neighbour's rate
+    t1, _ = O.profile_estimate(ent, 1e9, O.OPK_GEMM, 4, 0, 8192, 4096, 512)
+    t2, _ = O.profile_estimate(ent, 1e9, O.OPK_GEMM, 4, 0, 16384, 4096, 512)
+    assert t2 == pytest.approx(2 * t1) and t1 == pytest.approx(4.0)
+    # memory-bound side: bytes over the bandwidth, whatever the neighbour's time
+    t3, _ = O.profile_estimate(ent, 100.0, O.OPK_GEMM, 4, 0, 8192, 4096, 2)
+    assert t3 == pytest.approx((8192 * 4096 * 0.5625 + 2 * 2 * (4096 + 8192)) / 100e9 * 1e3)
+    # the order of the entries does not matter unless two are equally near
+    t4, _ = O.profile_estimate(ent[::-1], 1e9, O.OPK_GEMM, 4, 0, 8192, 4096, 512)
+    assert t4 == t1
+    # work of an operation: one multiply-add per weight and token; 4.5 bits per weight
+    assert O.op_work(O.OPK_GEMV, 4, 4096, 4096, 1) == (2.0 * 4096 * 4096, 4096 * 4096 * 0.5625 + 2 * 8192)
