@@ -276,6 +276,11 @@ def plans_leg(B, S, torch, cfg, seed, prof, budget, tokens, steps):
     unpinned FFN on the CPU, a split of both; and which one HeuristicSplit picks from its estimates."""
     names = {B.PS_PLAN_GPU_ONLY: "gpu_only", B.PS_PLAN_STATIC: "static", B.PS_PLAN_DYNAMIC: "dynamic"}
     out = {}
+    # the same three plans priced from a profile database filled by the install-phase benchmark suite
+    db = B.ProfileDB()
+    t0 = time.perf_counter()
+    db.measure(cfg)
+    log("profile database: %d entries measured in %.1f s" % (len(db.entries()), time.perf_counter() - t0))
     for M in tokens:
         plans = {k: B.Plan(cfg, int(budget), M, profile=prof, kind=k) for k in names}
         auto = B.Plan(cfg, int(budget), M, profile=prof, kind=B.PS_PLAN_AUTO).summary()
@@ -284,7 +289,9 @@ def plans_leg(B, S, torch, cfg, seed, prof, budget, tokens, steps):
         dev = stacks[B.PS_PLAN_GPU_ONLY].device
         xs = [torch.from_numpy(S.activations(seed, 900 + t, M, cfg["hidden"])).to(dev) for t in range(4)]
         xo = torch.empty_like(xs[0])
-        r = dict(budget_bytes=int(budget), tokens=M, picked=names[auto.plan_kind])
+        auto_db = B.Plan(cfg, int(budget), M, profile=prof, kind=B.PS_PLAN_AUTO, db=db).summary()
+        r = dict(budget_bytes=int(budget), tokens=M, picked=names[auto.plan_kind], picked_with_database=names[auto_db.plan_kind],
+                 est_ms_with_database={names[k]: auto_db.est_kind_ms[k] for k in names})
         for k, st in stacks.items():
             s = plans[k].summary()
             ms = time_steps(torch, st, xs, xo, steps, 2)
@@ -299,7 +306,9 @@ def plans_leg(B, S, torch, cfg, seed, prof, budget, tokens, steps):
             st.close()
         best = min(names.values(), key=lambda n: r[n]["ms_per_step"])
         r["measured_best"] = best
-        log("plans at %.0f GB, %d token(s): HeuristicSplit picks %s, measured best %s" % (budget / 1e9, M, r["picked"], best))
+        log("plans at %.0f GB, %d token(s): HeuristicSplit picks %s (priced from the database: %s, estimates %s), measured best %s" % (
+            budget / 1e9, M, r["picked"], r["picked_with_database"],
+            {n: round(v, 2) for n, v in r["est_ms_with_database"].items()}, best))
         out["%d" % M] = r
     return out
 

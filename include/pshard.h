@@ -334,6 +334,68 @@ int32_t ps_route_host(const float *logits, uint32_t n_tokens, uint32_t n_experts
 int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
                            void *compute_stream, void *copy_stream, ps_profile *out);
 
+/* Profile database (Section 3, profiler-based timing estimation).  One entry per benchmarked
+ * kernel: operation, quantisation level (bits per weight, 0 for copies), CPU thread count (0 for
+ * GPU operations), dimensions (n output rows, k reduction length, m tokens; a copy: n = bytes,
+ * k = m = 1) and the measured time of one call.  ps_profile_db_estimate prices a kernel the way the
+ * paper does: an entry with the same operation, quantisation, thread count and dimensions gives
+ * its own time (PS_MATCH_EXACT); otherwise the entry of the same operation, quantisation and thread
+ * count nearest in the space of dimensions (Euclidean in log2 n, log2 k, log2 m; the earlier entry
+ * on a tie) gives the FLOPS roof of a roofline whose memory roof is bandwidth_gbps, and the kernel
+ * costs flops / roof if its arithmetic intensity lies right of the ridge, bytes / bandwidth if left
+ * (PS_MATCH_NEIGHBOUR; for a copy the neighbour's byte rate is used); with no such entry the kernel
+ * is skipped (PS_MATCH_NONE, 0 ms).  flops = 2 n k m; bytes = n k (quant / 8 + 1 / 16) + 2 m (k + n).
+ * Host only.  A database handed to ps_plan_create_db is copied. */
+#define PS_OPK_GEMV 0 /* GPU dequant GEMV, one token            */
+#define PS_OPK_GEMM 1 /* GPU dequant MFMA GEMM, several tokens  */
+#define PS_OPK_CPU 2  /* CPU back-end matmul                    */
+#define PS_OPK_H2D 3  /* pinned host -> device copy             */
+#define PS_MATCH_NONE 0
+#define PS_MATCH_EXACT 1
+#define PS_MATCH_NEIGHBOUR 2
+typedef struct ps_profile_db ps_profile_db;
+typedef struct ps_prof_entry {
+    uint32_t op, quant, threads, pad;
+    uint64_t n, k, m;
+    double ms;
+} ps_prof_entry;
+typedef struct ps_prof_estimate {
+    double ms;             /* estimated time of one call, 0 if skipped                     */
+    double flops, bytes;   /* work of the priced kernel                                    */
+    uint32_t match;        /* PS_MATCH_*                                                   */
+    uint32_t compute_bound;/* neighbour match: which side of the ridge                     */
+    int32_t neighbour;     /* index of the entry used, -1 if none                          */
+    uint32_t pad;
+} ps_prof_estimate;
+int32_t ps_profile_db_create(ps_profile_db **out);
+void ps_profile_db_destroy(ps_profile_db *db);
+/* add one entry (an entry with the same key is replaced) */
+int32_t ps_profile_db_add(ps_profile_db *db, const ps_prof_entry *entry);
+int32_t ps_profile_db_count(const ps_profile_db *db, uint32_t *n);
+int32_t ps_profile_db_get(const ps_profile_db *db, uint32_t i, ps_prof_entry *out);
+int32_t ps_profile_db_estimate(const ps_profile_db *db, double bandwidth_gbps, uint32_t op, uint32_t quant,
+                               uint32_t threads, uint64_t n, uint64_t k, uint64_t m, ps_prof_estimate *out);
+/* text file, one entry per line: op quant threads n k m ms */
+int32_t ps_profile_db_save(const ps_profile_db *db, const char *path);
+int32_t ps_profile_db_load(ps_profile_db *db, const char *path);
+/* Install phase: run the benchmark suite for a model on the current device and add its entries:
+ * every weight matrix of the model (QKV, O, gate/up, down or the expert pair, output head) as a
+ * GEMV at one token and as a GEMM at the tiers up to 2048 tokens, each timed as ten asynchronous
+ * launches together; pinned H2D copies of 1 to 64 MiB; and, where the CPU back-end is supported,
+ * the FFN / expert / head matrices on it at 1, 4, 16 and 64 tokens (threads = the worker count
+ * used, min(hardware threads, 16)).  scratch, streams: as for ps_profile_measure, scratch at least
+ * 768 MiB. */
+int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc *model, void *scratch_dev,
+                              uint64_t scratch_bytes, void *compute_stream, void *copy_stream);
+/* ps_plan_create_kind with shard times taken from a profile database: each shard's matmul is
+ * priced by ps_profile_db_estimate (memory roof: the profile's gemv_gbps for GPU kernels, cpu_gbps
+ * for the CPU back-end), copies by the H2D entries; what the database skips falls back to the
+ * profile's rates.  The profile still supplies the contention factors (the ratio of its busy to
+ * alone rates scales the database's CPU and copy times) and the fixed cost per CPU shard. */
+int32_t ps_plan_create_db(const ps_model_desc *model, uint64_t vram_budget_bytes, const ps_profile *profile,
+                          const ps_profile_db *db, uint32_t n_tokens, const float *expert_freq, uint32_t kind,
+                          ps_plan **out);
+
 /* Bind a plan to a VRAM arena (device, 256-byte aligned, arena_bytes >= the
  * plan's budget) and two streams.  Allocates pinned host memory for the
  * streamed shards.  The plan is copied; the arena and streams must outlive the stack. */

@@ -19,6 +19,8 @@ PS_FLAG_NO_ATTN, PS_FLAG_NO_RESIDUAL = 1, 2
 PS_PLAN_GPU_ONLY, PS_PLAN_STATIC, PS_PLAN_DYNAMIC, PS_PLAN_AUTO = 0, 1, 2, 3
 PS_OP_COPY, PS_OP_KERNEL, PS_OP_CPU, PS_OP_FETCH = 0, 1, 2, 3
 PS_BUF_H, PS_BUF_S, PS_BUF_X = 1, 2, 4
+PS_OPK_GEMV, PS_OPK_GEMM, PS_OPK_CPU, PS_OPK_H2D = 0, 1, 2, 3
+PS_MATCH_NONE, PS_MATCH_EXACT, PS_MATCH_NEIGHBOUR = 0, 1, 2
 PS_NTIERS = 11
 (PS_K_RINV, PS_K_QKV, PS_K_O, PS_K_GATE_UP, PS_K_DOWN, PS_K_ROUTE, PS_K_EXPERT_GATE_UP,
  PS_K_EXPERT_DOWN, PS_K_COMBINE, PS_K_ATTN, PS_K_ATTN_COMBINE, PS_K_OUT) = range(12)
@@ -53,6 +55,16 @@ class ps_plan_summary_t(C.Structure):
                 ("cpu_fraction", C.c_double), ("est_kind_ms", C.c_double * 3)]
 
 
+class ps_prof_entry(C.Structure):
+    _fields_ = [("op", C.c_uint32), ("quant", C.c_uint32), ("threads", C.c_uint32), ("pad", C.c_uint32),
+                ("n", C.c_uint64), ("k", C.c_uint64), ("m", C.c_uint64), ("ms", C.c_double)]
+
+
+class ps_prof_estimate(C.Structure):
+    _fields_ = [("ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double), ("match", C.c_uint32),
+                ("compute_bound", C.c_uint32), ("neighbour", C.c_int32), ("pad", C.c_uint32)]
+
+
 class ps_tier_entry(C.Structure):
     _fields_ = [("tier", C.c_uint32), ("tier_tokens", C.c_uint32), ("feasible", C.c_int32), ("pad", C.c_uint32),
                 ("summary", ps_plan_summary_t)]
@@ -84,7 +96,9 @@ EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_b
            "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
            "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
            "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads",
-           "ps_tier_table_create_kind"]
+           "ps_tier_table_create_kind", "ps_profile_db_create", "ps_profile_db_destroy", "ps_profile_db_add",
+           "ps_profile_db_count", "ps_profile_db_get", "ps_profile_db_estimate", "ps_profile_db_save",
+           "ps_profile_db_load", "ps_profile_db_measure", "ps_plan_create_db"]
 
 _lib = None
 
@@ -136,6 +150,15 @@ def lib():
             "ps_tier_table_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, C.POINTER(vp)],
             "ps_tier_table_create_kind": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, u32, C.POINTER(vp)],
             "ps_tier_table_entry": [vp, u32, C.POINTER(ps_tier_entry)],
+            "ps_profile_db_create": [C.POINTER(vp)],
+            "ps_profile_db_add": [vp, C.POINTER(ps_prof_entry)],
+            "ps_profile_db_count": [vp, C.POINTER(u32)],
+            "ps_profile_db_get": [vp, u32, C.POINTER(ps_prof_entry)],
+            "ps_profile_db_estimate": [vp, C.c_double, u32, u32, u32, u64, u64, u64, C.POINTER(ps_prof_estimate)],
+            "ps_profile_db_save": [vp, C.c_char_p],
+            "ps_profile_db_load": [vp, C.c_char_p],
+            "ps_profile_db_measure": [vp, C.POINTER(ps_model_desc), vp, u64, vp, vp],
+            "ps_plan_create_db": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, u32, vp, u32, C.POINTER(vp)],
             "ps_tier_table_plan": [vp, u32, C.POINTER(vp)],
             "ps_tier_pick": [vp, u32, C.POINTER(ps_tier_choice)],
             "ps_stack_load_kv": [vp, u32, u32, vp, vp, u32],
@@ -147,7 +170,7 @@ def lib():
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = args
-        for name in ("ps_plan_destroy", "ps_schedule_destroy", "ps_stack_destroy", "ps_tier_table_destroy"):
+        for name in ("ps_plan_destroy", "ps_schedule_destroy", "ps_stack_destroy", "ps_tier_table_destroy", "ps_profile_db_destroy"):
             f = getattr(L, name)
             f.restype = None
             f.argtypes = [vp]
@@ -194,14 +217,18 @@ def _ptr(a):
 class Plan:
     """ps_plan_create / ps_plan_summary / ps_plan_get_shard / ps_plan_destroy."""
 
-    def __init__(self, cfg, budget_bytes, n_tokens, profile=None, expert_freq=None, kind=None):
-        """kind: None (ps_plan_create: Plan One) or PS_PLAN_* (ps_plan_create_kind)."""
+    def __init__(self, cfg, budget_bytes, n_tokens, profile=None, expert_freq=None, kind=None, db=None):
+        """kind: None (ps_plan_create: Plan One) or PS_PLAN_* (ps_plan_create_kind); db: a ProfileDB whose
+        entries price the shards (ps_plan_create_db)."""
         self.cfg = cfg
         self.desc = model_desc(cfg)
         self.profile = profile if profile is not None else make_profile()
         self.h = C.c_void_p()
         freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
-        if kind is None:
+        if db is not None:
+            _check(lib().ps_plan_create_db(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), db.h,
+                                           int(n_tokens), _ptr(freq), int(kind or 0), C.byref(self.h)))
+        elif kind is None:
             _check(lib().ps_plan_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), int(n_tokens),
                                         _ptr(freq), C.byref(self.h)))
         else:
@@ -294,6 +321,64 @@ class _TierPlan(Plan):
 
     def close(self):
         self.h = C.c_void_p()
+
+
+class ProfileDB:
+    """ps_profile_db_*: benchmarked kernels and the paper's look-up rule (exact, nearest neighbour, skip)."""
+
+    def __init__(self):
+        self.h = C.c_void_p()
+        _check(lib().ps_profile_db_create(C.byref(self.h)))
+
+    def add(self, op, quant, threads, n, k, m, ms):
+        e = ps_prof_entry(op, quant, threads, 0, n, k, m, ms)
+        _check(lib().ps_profile_db_add(self.h, C.byref(e)))
+
+    def entries(self):
+        n = C.c_uint32()
+        _check(lib().ps_profile_db_count(self.h, C.byref(n)))
+        out = []
+        for i in range(n.value):
+            e = ps_prof_entry()
+            _check(lib().ps_profile_db_get(self.h, i, C.byref(e)))
+            out.append((e.op, e.quant, e.threads, e.n, e.k, e.m, e.ms))
+        return out
+
+    def estimate(self, bandwidth_gbps, op, quant, threads, n, k, m):
+        r = ps_prof_estimate()
+        _check(lib().ps_profile_db_estimate(self.h, float(bandwidth_gbps), op, quant, threads, n, k, m, C.byref(r)))
+        return r
+
+    def save(self, path):
+        _check(lib().ps_profile_db_save(self.h, str(path).encode()))
+
+    def load(self, path):
+        _check(lib().ps_profile_db_load(self.h, str(path).encode()))
+
+    def measure(self, cfg, scratch_bytes=1 << 30, device="cuda:0"):
+        """Run the benchmark suite for cfg on the device (allocates a torch scratch buffer and two streams)."""
+        import torch
+        dev = torch.device(device)
+        desc = model_desc(cfg)
+        with torch.cuda.device(dev):
+            scratch = torch.empty(int(scratch_bytes), dtype=torch.uint8, device=dev)
+            cs, cp = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+            torch.cuda.synchronize()
+            _check(lib().ps_profile_db_measure(self.h, C.byref(desc), scratch.data_ptr(), scratch.numel(),
+                                               cs.cuda_stream, cp.cuda_stream))
+            torch.cuda.synchronize()
+        del scratch
+
+    def close(self):
+        if self.h:
+            lib().ps_profile_db_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class TierTable:

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 ROOT = os.path.dirname(HERE)
 LIB = os.environ.get("PS_LIB_OUT", os.path.join(HERE, "libpshard.so"))
 BUILD = os.path.join(HERE, "_build")
-SOURCES = ["planner.cpp", "schedule.cpp", "pack.cpp", "cpu_backend.cpp", "kernels.hip", "stack.hip", "profile.hip"]
+SOURCES = ["planner.cpp", "schedule.cpp", "pack.cpp", "cpu_backend.cpp", "profile_db.cpp", "kernels.hip", "stack.hip", "profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: results must not depend on which kernel a device function was inlined into
 # (the one-token kernel variants have to agree bit for bit on every placement); fused multiply-adds

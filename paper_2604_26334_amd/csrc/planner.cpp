@@ -190,12 +190,56 @@ static void estimate(ps_plan &p, const float *freq) {
     const double h2d = contend && p.prof.h2d_gbps_busy > 0 ? p.prof.h2d_gbps_busy : p.prof.h2d_gbps;
     const double cpu = contend && p.prof.cpu_gbps_busy > 0 ? p.prof.cpu_gbps_busy : p.prof.cpu_gbps;
     std::vector<double> prob(n, 1.0), comp(n, 0.0), copy(n, 0.0);
+    // With a profile database a shard's matmuls are looked up there (exact match, nearest neighbour
+    // with a roofline, or skipped); a shard the database cannot price keeps the profile's rates.
+    const ModelGeom &g = p.g;
+    auto db_matmuls = [&](const Shard &s, double tokens, bool on_cpu, double *ms) -> bool {
+        if (!p.db) return false;
+        const uint64_t mt = (uint64_t)std::max(1.0, std::round(tokens));
+        struct { uint64_t n, k; } mats[2];
+        int nm = 1;
+        switch (s.kind) {
+            case PS_SHARD_QKV: mats[0] = {(uint64_t)s.ntiles * 16, m.hidden}; break;
+            case PS_SHARD_O: mats[0] = {(uint64_t)s.ntiles * 16, g.attn_w}; break;
+            case PS_SHARD_GATE_UP: mats[0] = {(uint64_t)s.ntiles * 16, m.hidden}; break;
+            case PS_SHARD_DOWN: mats[0] = {(uint64_t)s.ntiles * 16, g.ffn_i}; break;
+            case PS_SHARD_OUT: mats[0] = {(uint64_t)s.ntiles * 16, m.hidden}; break;
+            case PS_SHARD_EXPERT: mats[0] = {2ull * g.ffn_i, m.hidden}; mats[1] = {m.hidden, g.ffn_i}; nm = 2; break;
+            default: return false;
+        }
+        const uint32_t op = on_cpu ? PS_OPK_CPU : (mt == 1 ? PS_OPK_GEMV : PS_OPK_GEMM);
+        const double bw = on_cpu ? p.prof.cpu_gbps : p.prof.gemv_gbps;
+        if (!(bw > 0)) return false;
+        double t = 0;
+        for (int q = 0; q < nm; ++q) {
+            ps_prof_estimate e;
+            db_estimate(p.db.get(), bw, op, 4, on_cpu ? p.db_threads : 0, mats[q].n, mats[q].k, mt, &e);
+            if (e.match == PS_MATCH_NONE) return false;
+            t += e.ms;
+        }
+        if (on_cpu && contend && p.prof.cpu_gbps_busy > 0 && p.prof.cpu_gbps > 0) t *= p.prof.cpu_gbps / p.prof.cpu_gbps_busy;
+        *ms = t;
+        return true;
+    };
+    auto copy_ms = [&](uint64_t bytes) -> double {
+        if (p.db) {
+            ps_prof_estimate e;
+            db_estimate(p.db.get(), 1.0, PS_OPK_H2D, 0, 0, bytes, 1, 1, &e);
+            if (e.match != PS_MATCH_NONE) {
+                const double scale = contend && p.prof.h2d_gbps_busy > 0 && p.prof.h2d_gbps > 0 ? p.prof.h2d_gbps / p.prof.h2d_gbps_busy : 1.0;
+                return e.ms * scale;
+            }
+        }
+        return h2d > 0 ? (double)bytes / (h2d * 1e9) * 1e3 : 0.0;
+    };
     for (size_t i = 0; i < n; ++i) {
         const Shard &s = p.shards[i];
         double tokens = p.M;
         if (s.resident == 2 && s.kind != PS_SHARD_EXPERT) {
             const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, tokens / p.prof.cpu_tokens_free) : 1.0;
-            comp[i] = (cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0) + p.prof.cpu_sync_us * 1e-3;
+            double t;
+            if (!db_matmuls(s, tokens, true, &t)) t = cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0;
+            comp[i] = t + p.prof.cpu_sync_us * 1e-3;
             continue;
         }
         if (s.kind == PS_SHARD_EXPERT) {
@@ -207,11 +251,15 @@ static void estimate(ps_plan &p, const float *freq) {
         }
         if (s.resident == 2) {   // an expert on the CPU: touched with probability prob, by `tokens` tokens
             const double slow = p.prof.cpu_tokens_free > 0 ? std::max(1.0, tokens / p.prof.cpu_tokens_free) : 1.0;
-            comp[i] = (cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0) * prob[i];
+            double t;
+            if (!db_matmuls(s, tokens, true, &t)) t = cpu > 0 ? (double)s.bytes / (cpu * 1e9) * 1e3 * slow : 0.0;
+            comp[i] = t * prob[i];
             continue;
         }
-        comp[i] = shard_compute_ms(p, s.bytes, tokens) * prob[i];
-        if (!s.resident && h2d > 0) copy[i] = (double)s.bytes / (h2d * 1e9) * 1e3 * prob[i];
+        double t;
+        if (!db_matmuls(s, tokens, false, &t)) t = shard_compute_ms(p, s.bytes, tokens);
+        comp[i] = t * prob[i];
+        if (!s.resident) copy[i] = copy_ms(s.bytes) * prob[i];
     }
     std::vector<size_t> gpu;   // the GPU's shards, in order
     for (size_t i = 0; i < n; ++i) if (p.shards[i].resident != 2) gpu.push_back(i);
@@ -239,10 +287,16 @@ static void estimate(ps_plan &p, const float *freq) {
 
 // One plan of the given kind.  cpu_frac: Plan Three's share of each unpinned CPU-eligible matrix
 // that stays on the CPU (ignored otherwise).
+// the database the plans of the current ps_plan_create_db call are estimated with
+static thread_local std::shared_ptr<const ps_profile_db> t_db;
+
 static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_profile *prof, uint32_t M,
                           const float *freq, uint32_t kind, double cpu_frac, ps_plan *p) {
     int32_t rc = make_model_geom(model, &p->g);
     if (rc) return rc;
+    p->db = t_db;
+    p->db_threads = 0;
+    if (p->db) for (const ps_prof_entry &e : p->db->entries) if (e.op == PS_OPK_CPU) p->db_threads = std::max(p->db_threads, e.threads);
     if (M == 0 || M > kTiers[PS_NTIERS - 1]) { set_error("n_tokens=%u out of range 1..16384", M); return PS_E_ARG; }
     if (p->g.kv && M != 1) { set_error("attention over a KV cache is built for one token per step (got %u)", M); return PS_E_ARG; }
     if (prof) p->prof = *prof;
@@ -526,6 +580,15 @@ int32_t ps_plan_create_kind(const ps_model_desc *model, uint64_t budget, const p
     if (rc) { delete p; return rc; }
     *out = p;
     return PS_OK;
+}
+
+int32_t ps_plan_create_db(const ps_model_desc *model, uint64_t budget, const ps_profile *prof, const ps_profile_db *db,
+                          uint32_t n_tokens, const float *expert_freq, uint32_t kind, ps_plan **out) {
+    if (!db) { ps::set_error("profile database is NULL"); return PS_E_ARG; }
+    ps::t_db = std::make_shared<const ps_profile_db>(*db);
+    const int32_t rc = ps_plan_create_kind(model, budget, prof, n_tokens, expert_freq, kind, out);
+    ps::t_db.reset();
+    return rc;
 }
 
 int32_t ps_plan_summary(const ps_plan *p, ps_plan_summary_t *o) {

@@ -184,3 +184,141 @@ done:
     if (e1) (void)hipEventDestroy(e1);
     return rc;
 }
+
+extern "C" int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc *model, void *scratch_dev,
+                                         uint64_t scratch_bytes, void *compute_stream, void *copy_stream) {
+    using namespace ps;
+    constexpr uint64_t kX = 64ull << 20, kY = 64ull << 20, kHeadRoom = 132ull << 20;   // activations, outputs, rinv
+    constexpr uint32_t kMaxRows = 16384, kMaxTok = 2048;
+    constexpr int kLaunches = 10;
+    if (!db || !model || !scratch_dev || scratch_bytes < (768ull << 20) || (uintptr_t)scratch_dev % kAlign) {
+        set_error("profile database scratch must be device memory, 256-byte aligned, >= 768 MiB");
+        return PS_E_ARG;
+    }
+    ModelGeom g;
+    int32_t rc = make_model_geom(model, &g);
+    if (rc) return rc;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), cp = static_cast<hipStream_t>(copy_stream);
+    uint8_t *base = static_cast<uint8_t *>(scratch_dev);
+    __half *x = reinterpret_cast<__half *>(base);
+    __half *y = reinterpret_cast<__half *>(base + kX);
+    float *rinv = reinterpret_cast<float *>(base + kX + kY);
+    uint8_t *wts = base + kHeadRoom;
+    const uint64_t wbytes = scratch_bytes - kHeadRoom;
+    void *host = nullptr, *cpu_img = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    float ms = 0;
+    auto add = [&](uint32_t op, uint32_t threads, uint64_t n, uint64_t k, uint64_t m, double t_ms) {
+        ps_prof_entry e{};
+        e.op = op; e.quant = op == PS_OPK_H2D ? 0 : 4; e.threads = threads; e.n = n; e.k = k; e.m = m; e.ms = t_ms;
+        return ps_profile_db_add(db, &e);
+    };
+    // the model's distinct weight matrices (rows capped: a larger one is priced from its nearest entry)
+    struct Mat { uint32_t rows, K; bool cpu; };
+    std::vector<Mat> mats;
+    auto push = [&](const MatGeom &mg, bool cpu) {
+        if (!mg.ntiles) return;
+        const uint32_t rows = std::min(mg.rows, kMaxRows);
+        for (const Mat &o : mats) if (o.rows == rows && o.K == mg.K) return;
+        mats.push_back(Mat{rows, mg.K, cpu});
+    };
+    push(g.qkv, false); push(g.o, false); push(g.gate_up, true); push(g.down, true); push(g.head, true);
+
+    PS_HIP(hipEventCreate(&e0));
+    PS_HIP(hipEventCreate(&e1));
+    PS_HIP(hipHostMalloc(&host, 64ull << 20, hipHostMallocDefault));
+    std::memset(host, 0x11, 64ull << 20);
+    PS_HIP(hipMemsetAsync(base, 0x11, scratch_bytes, cs));
+    PS_HIP(hipStreamSynchronize(cs));
+
+    for (uint64_t mib : {1ull, 4ull, 16ull, 64ull}) {   // pinned H2D copies, eight timed together
+        const uint64_t bytes = mib << 20;
+        PS_HIP(hipMemcpyAsync(wts, host, bytes, hipMemcpyHostToDevice, cp));
+        PS_HIP(hipEventRecord(e0, cp));
+        for (int i = 0; i < 8; ++i) PS_HIP(hipMemcpyAsync(wts + (uint64_t)i * bytes, host, bytes, hipMemcpyHostToDevice, cp));
+        PS_HIP(hipEventRecord(e1, cp));
+        PS_HIP(hipEventSynchronize(e1));
+        PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+        rc = add(PS_OPK_H2D, 0, bytes, 1, 1, ms / 8.0);
+        if (rc) goto done;
+    }
+    PS_HIP(hipMemsetAsync(wts, 0x11, wbytes, cs));
+    for (const Mat &mt : mats) {
+        const MatGeom mg = make_geom(mt.rows, mt.K, false);
+        const uint32_t fit = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(kLaunches, wbytes / mg.bytes));
+        {   // one token: ten launches over different copies of the matrix
+            GemvArgs a{};
+            a.tile_u4 = (uint32_t)(mg.tile_bytes / 16); a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K;
+            a.x = x; a.x_group = 1; a.eps = 1e-6f; a.out = y; a.nunits = mg.ntiles; a.top_k = 1;
+            const uint32_t ks = gemv_ksplit(mg.ngroups, mg.ntiles);
+            for (int rep = 0; rep < 2; ++rep) {
+                PS_HIP(hipEventRecord(e0, cs));
+                for (int i = 0; i < kLaunches; ++i) {
+                    a.W = reinterpret_cast<const uint4 *>(wts + (uint64_t)(i % fit) * mg.bytes);
+                    PS_HIP(launch_gemv(GEMV_PLAIN, ks, a, 0, cs));
+                }
+                PS_HIP(hipEventRecord(e1, cs));
+                PS_HIP(hipEventSynchronize(e1));
+            }
+            PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+            rc = add(PS_OPK_GEMV, 0, mt.rows, mt.K, 1, ms / kLaunches);
+            if (rc) goto done;
+        }
+        for (uint32_t t = 1; t < PS_NTIERS && ps_tier_tokens(t) <= kMaxTok; ++t) {
+            const uint32_t T = ps_tier_tokens(t);
+            GemmArgs a{};
+            a.ntiles = mg.ntiles; a.total_tiles = mg.ntiles; a.tile_u4 = (uint32_t)(mg.tile_bytes / 16);
+            a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = mt.K; a.x_group = 1; a.rinv = rinv; a.out = y;
+            a.out_stride = mt.rows; a.top_k = 1;
+            PS_HIP(launch_rinv(x, T, mt.K, 1e-6f, rinv, cs));
+            for (int rep = 0; rep < 2; ++rep) {
+                PS_HIP(hipEventRecord(e0, cs));
+                for (int i = 0; i < kLaunches; ++i) {
+                    a.W = reinterpret_cast<const uint4 *>(wts + (uint64_t)(i % fit) * mg.bytes);
+                    PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
+                }
+                PS_HIP(hipEventRecord(e1, cs));
+                PS_HIP(hipEventSynchronize(e1));
+            }
+            PS_HIP(hipEventElapsedTime(&ms, e0, e1));
+            rc = add(PS_OPK_GEMM, 0, mt.rows, mt.K, T, ms / kLaunches);
+            if (rc) goto done;
+        }
+    }
+    if (cpu_backend_supported()) {
+        constexpr uint64_t kImage = 512ull << 20;
+        auto now = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+        PS_HIP(hipHostMalloc(&cpu_img, kImage, hipHostMallocDefault));
+        std::memset(cpu_img, 0x11, kImage);
+        const unsigned hw = std::thread::hardware_concurrency();
+        std::unique_ptr<CpuPool> pool(new CpuPool(std::min(hw ? hw : 4u, 16u)));
+        std::vector<float> scratch(cpu_scratch_floats(64, 16384));
+        std::vector<uint16_t> xh((size_t)64 * 16384, 0x1111), yh((size_t)64 * kMaxRows);
+        for (const Mat &mt : mats) {
+            if (!mt.cpu) continue;
+            const MatGeom mg = make_geom(mt.rows, mt.K, false);
+            const uint32_t fit = (uint32_t)std::max<uint64_t>(1, kImage / mg.bytes);
+            for (uint32_t T : {1u, 4u, 16u, 64u}) {
+                CpuMatArgs a;
+                a.ntiles = mg.ntiles; a.tile_bytes = mg.tile_bytes; a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K;
+                a.M = T; a.x = xh.data(); a.x_stride = mt.K; a.mode = CPU_PLAIN; a.eps = 1e-6f; a.out = yh.data();
+                a.out_stride = mt.rows; a.out_col0 = 0;
+                const int reps = T <= 4 ? 4 : 2;
+                double t0 = 0;
+                for (int r = -1; r < reps; ++r) {          // pass -1 warms up; each pass reads another copy of the matrix
+                    if (r == 0) t0 = now();
+                    a.W = static_cast<const uint8_t *>(cpu_img) + (uint64_t)((r + 1) % fit) * mg.bytes;
+                    cpu_matmul_w4(a, *pool, scratch.data());
+                }
+                rc = add(PS_OPK_CPU, pool->size(), mt.rows, mt.K, T, (now() - t0) / reps);
+                if (rc) goto done;
+            }
+        }
+    }
+done:
+    if (cpu_img) (void)hipHostFree(cpu_img);
+    if (host) (void)hipHostFree(host);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    return rc;
+}

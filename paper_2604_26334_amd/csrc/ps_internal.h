@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -96,6 +97,12 @@ struct ps_plan {
     uint32_t kind = PS_PLAN_GPU_ONLY;   // which of the three schedule plans this is
     double cpu_frac = 0;                // Plan Three: CPU share of each unpinned eligible matrix
     double est_kind[3] = {-1, -1, -1};  // estimates per plan kind (all three after HeuristicSplit)
+    std::shared_ptr<const ps_profile_db> db;   // optional: shard times come from here
+    uint32_t db_threads = 0;                   // thread count of the database's CPU entries
+};
+
+struct ps_profile_db {
+    std::vector<ps_prof_entry> entries;
 };
 
 struct ps_tier_table {
@@ -113,6 +120,9 @@ struct ps_schedule {
 };
 
 namespace ps {
+void op_work(uint32_t op, uint32_t quant, uint64_t n, uint64_t k, uint64_t m, double *flops, double *bytes);
+int32_t db_estimate(const ps_profile_db *db, double bandwidth_gbps, uint32_t op, uint32_t quant, uint32_t threads,
+                    uint64_t n, uint64_t k, uint64_t m, ps_prof_estimate *out);
 int32_t build_schedule(const ps_plan *plan, const float *router_logits, ps_schedule *out);
 int32_t validate_schedule(const ps_schedule *s);
 void route_host(const float *logits, uint32_t M, uint32_t E, uint32_t k, int32_t *idx);

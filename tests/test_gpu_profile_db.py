@@ -1,0 +1,73 @@
+"""The install-phase benchmark suite that fills the profile database (Section 3: kernels timed as
+a batch of asynchronous launches), and plans priced from it, on the GPU."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from tests import harness as Hn
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def test_benchmark_suite_fills_the_database_and_prices_a_plan():
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = dict(Hn.small_dense_cfg(2), vocab=2064)
+    H, I = cfg["hidden"], cfg["ffn_inter"]
+    db = B.ProfileDB()
+    db.measure(cfg, scratch_bytes=768 << 20)
+    ent = db.entries()
+    _say("  %d entries" % len(ent))
+    assert all(e[6] > 0 and np.isfinite(e[6]) for e in ent)
+    shapes = {((cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * 128, H), (H, cfg["n_q_heads"] * 128), (2 * I, H), (H, I), (2064, H)}
+    gemv = {(e[3], e[4]) for e in ent if e[0] == B.PS_OPK_GEMV}
+    assert gemv == shapes
+    tiers = sorted({e[5] for e in ent if e[0] == B.PS_OPK_GEMM})
+    assert tiers == [4, 16, 32, 64, 512, 1024, 2048]
+    assert len([e for e in ent if e[0] == B.PS_OPK_GEMM]) == len(shapes) * len(tiers)
+    assert sorted(e[3] for e in ent if e[0] == B.PS_OPK_H2D) == [1 << 20, 4 << 20, 16 << 20, 64 << 20]
+    cpu = [e for e in ent if e[0] == B.PS_OPK_CPU]
+    if cpu:   # hosts with AVX-512: the FFN and head matrices at four token counts, one thread count
+        assert {(e[3], e[4]) for e in cpu} == {(2 * I, H), (H, I), (2064, H)} and len({e[2] for e in cpu}) == 1
+        assert sorted({e[5] for e in cpu}) == [1, 4, 16, 64]
+    # larger copies are not slower per byte; the 64 MiB copy runs at a plausible PCIe rate
+    h2d = {e[3]: e[6] for e in ent if e[0] == B.PS_OPK_H2D}
+    rate = (64 << 20) / (h2d[64 << 20] * 1e-3) / 1e9
+    _say("  H2D 64 MiB: %.1f GB/s; GEMV %s" % (rate, {(e[3], e[4]): round(e[6] * 1e3, 1) for e in ent if e[0] == B.PS_OPK_GEMV}))
+    assert 5.0 < rate < 200.0
+    # the model's own shapes are exact matches; a slab of one is a neighbour
+    r = db.estimate(5000.0, B.PS_OPK_GEMV, 4, 0, 2 * I, H, 1)
+    assert r.match == B.PS_MATCH_EXACT
+    r2 = db.estimate(5000.0, B.PS_OPK_GEMV, 4, 0, I, H, 1)
+    assert r2.match == B.PS_MATCH_NEIGHBOUR and 0 < r2.ms < r.ms * 10     # (kernels this small are launch-bound)
+    # a plan priced from the database runs like any other
+    prof = B.make_profile(h2d_gbps=rate, gemv_gbps=5000.0, cpu_gbps=150.0 if cpu else 0.0, cpu_sync_us=40.0)
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 2
+    kinds = [B.PS_PLAN_GPU_ONLY] + ([B.PS_PLAN_AUTO] if cpu else [])
+    W = Hn.WeightCache(cfg, 21)
+    head = S.head_matrix(21, cfg)
+    x = S.activations(21, 0, 1, H)
+    ref = O.stack_forward(x, cfg, W, mirror=True)
+    for kind in kinds:
+        plan = B.Plan(cfg, budget, 1, profile=prof, kind=kind, db=db)
+        s = plan.summary()
+        _say("  kind %d -> plan %d, estimate %.3f ms (estimates per kind %s)" % (kind, s.plan_kind, s.est_step_ms, [round(v, 3) for v in s.est_kind_ms]))
+        assert s.est_step_ms > 0
+        st = B.Stack(plan)
+        for layer in range(cfg["n_layers"]):
+            for k, e, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, e, *W(layer, k, e))
+        st.load_matrix(cfg["n_layers"], S.MAT_OUT, None, *head)
+        xin = torch.from_numpy(x).to(st.device)
+        xout = torch.empty_like(xin)
+        st.forward(xin, xout)
+        st.synchronize()
+        assert Hn.rel_err(xout.cpu().numpy(), ref) <= 5e-3
+        st.close()
+        plan.close()

@@ -645,3 +645,97 @@ def test_tier_table_plans_each_small_tier_with_heuristic_split():
     assert tb.pick(1).est_total_ms <= base.pick(1).est_total_ms
     with pytest.raises(B.PshardError):
         B.TierTable(cfg, budget, profile=prof, kind=9)
+
+
+# ---------------------------------------------------------------- profile database (Section 3)
+
+def _golden_db():
+    from tests.test_oracle_pins import _profile_golden
+    ent, qs = _profile_golden()
+    db = B.ProfileDB()
+    for e in ent:
+        db.add(*e)
+    return db, ent, qs
+
+
+def test_profile_db_lookup_matches_the_papers_rule():
+    from oracle import oracle as O
+    db, ent, qs = _golden_db()
+    assert db.entries() == ent
+    names = {B.PS_MATCH_NONE: "none", B.PS_MATCH_EXACT: "exact", B.PS_MATCH_NEIGHBOUR: "neighbour"}
+    for bw, q, want_ms, want_match in qs:           # the hand-worked examples
+        r = db.estimate(bw, *q)
+        assert names[r.match] == want_match and r.ms == pytest.approx(want_ms, rel=1e-9)
+    rng = np.random.default_rng(5)                  # and a seeded sweep against the oracle
+    ent2 = []
+    db2 = B.ProfileDB()
+    for _ in range(40):
+        e = (int(rng.integers(0, 3)), 4, int(rng.choice([0, 8, 16])), int(2 ** rng.integers(4, 15)), int(128 * rng.integers(1, 64)),
+             int(rng.choice([1, 4, 16, 64, 512])), float(rng.uniform(0.01, 5.0)))
+        if any(o[:6] == e[:6] for o in ent2):
+            continue
+        ent2.append(e)
+        db2.add(*e)
+    for _ in range(300):
+        q = (int(rng.integers(0, 3)), 4, int(rng.choice([0, 8, 16])), int(16 * rng.integers(1, 2000)), int(128 * rng.integers(1, 64)),
+             int(rng.integers(1, 600)))
+        bw = float(rng.choice([0.5, 50.0, 5000.0]))
+        want_ms, want_match = O.profile_estimate(ent2, bw, *q)
+        r = db2.estimate(bw, *q)
+        assert names[r.match] == want_match and r.ms == pytest.approx(want_ms, rel=1e-9), q
+    for e in ent2[:5]:
+        assert db2.estimate(1.0, *e[:6]).match == B.PS_MATCH_EXACT
+    # the same key again replaces the measurement; bad entries are refused
+    db2.add(*ent2[0][:6], 9.0)
+    assert db2.estimate(1.0, *ent2[0][:6]).ms == 9.0 and len(db2.entries()) == len(ent2)
+    for bad in ((7, 4, 0, 16, 128, 1, 1.0), (0, 4, 0, 0, 128, 1, 1.0), (0, 4, 0, 16, 128, 1, 0.0)):
+        with pytest.raises(B.PshardError):
+            db2.add(*bad)
+
+
+def test_profile_db_file_round_trip(tmp_path):
+    db, ent, _ = _golden_db()
+    path = tmp_path / "profile.txt"
+    db.save(path)
+    other = B.ProfileDB()
+    other.load(path)
+    assert other.entries() == ent
+    (tmp_path / "bad.txt").write_text("0 4 0 16 not-a-number\n")
+    with pytest.raises(B.PshardError):
+        other.load(tmp_path / "bad.txt")
+    with pytest.raises(B.PshardError):
+        other.load(tmp_path / "missing.txt")
+
+
+def test_plans_priced_from_a_profile_database():
+    cfg = _kv_cfg(n_layers=2, ctx=0)
+    cfg = dict(cfg, kv_context=0)
+    H, I = cfg["hidden"], cfg["ffn_inter"]
+    full = B.Plan(cfg, 1 << 40, 1).summary()
+    budget = full.workspace_bytes + full.weight_bytes // 2
+    prof = _cpu_prof(cpu_sync_us=0.0, launch_us=0.0)
+    db = B.ProfileDB()
+    # every matrix of the model as a one-token GPU kernel, 1 ms each: an all-resident plan sums them
+    qkv_rows = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    for n, k in ((qkv_rows, H), (H, cfg["n_q_heads"] * cfg["head_dim"]), (2 * I, H), (H, I)):
+        db.add(B.PS_OPK_GEMV, 4, 0, n, k, 1, 1.0)
+    roomy = B.Plan(cfg, 1 << 40, 1, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=db).summary()
+    assert roomy.est_step_ms == pytest.approx(4.0 * cfg["n_layers"])
+    base = B.Plan(cfg, 1 << 40, 1, profile=prof).summary()
+    assert base.est_step_ms != pytest.approx(roomy.est_step_ms)
+    # a CPU that the database shows to be very slow keeps HeuristicSplit on the GPU; a fast one does not
+    for cpu_ms, want_gpu in ((1000.0, True), (1e-4, False)):
+        d2 = B.ProfileDB()
+        for e in db.entries():
+            d2.add(*e)
+        for n, k in ((2 * I, H), (H, I)):
+            d2.add(B.PS_OPK_CPU, 4, 16, n, k, 1, cpu_ms)
+        auto = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_AUTO, db=d2).summary()
+        assert (auto.plan_kind == B.PS_PLAN_GPU_ONLY) == want_gpu
+    # copies priced from H2D entries: a streamed plan's estimate follows the database's copy rate
+    slow_copy, fast_copy = B.ProfileDB(), B.ProfileDB()
+    slow_copy.add(B.PS_OPK_H2D, 0, 0, 1 << 20, 1, 1, 1.0)       # 1 GB/s
+    fast_copy.add(B.PS_OPK_H2D, 0, 0, 1 << 20, 1, 1, 0.001)     # 1 TB/s
+    a = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=slow_copy).summary()
+    b = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=fast_copy).summary()
+    assert a.est_step_ms == pytest.approx(a.streamed_bytes / (1 << 20) * 1.0, rel=0.05) and b.est_step_ms < a.est_step_ms / 50
