@@ -9,6 +9,12 @@
  * stream into a double-buffered VRAM scratch while the compute stream runs the
  * dequantising matmul kernels on the previous shard.  The method is lossless:
  * outputs do not depend on the budget or on where a shard lives.
+ * Around that core: the token-tier table with PickTier, the KV cache as a shard
+ * class with decode attention, the output head as the lowest priority class,
+ * the two plans that run unpinned low-priority shards on the CPU ("Plan Two",
+ * "Plan Three") with HeuristicSplit choosing among the three, and the profile
+ * database the time estimates can be drawn from.  Plan One is what every entry
+ * point does unless a plan kind is asked for; nothing falls back to the CPU.
  *
  * Conventions
  *  - every function returns 0 (PS_OK) or a negative PS_E_* code; nothing throws
