@@ -718,9 +718,9 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // block 4*sb + c of row i, dword kk supplies k-slots c*8 .. c*8+7 of MFMA step kk, which
 // this kernel maps to k = 32*(4*sb + c) + 8*kk + t; the B operand follows the same map.
 // Scales are folded into the fp16 A operand ((q - 8) * d rounded to fp16).
-// 256 threads = 4 waves, each wave owns AT row-tiles and all MT tokens of the workgroup;
-// the activation tile of one super-block (MT x 128 k) is staged in LDS, 16-byte chunks
-// XOR-swizzled by token so that operand reads are conflict-free.
+// NW waves (4, or 8 for the many-token shape), each wave owns AT row-tiles and all MT tokens of
+// the workgroup; the activation tile of one super-block (MT x 128 k) is staged in LDS, 16-byte
+// chunks XOR-swizzled by token so that operand reads are conflict-free.
 // ------------------------------------------------------------------------------------
 // LDS column of activation chunk u (k = 8u .. 8u+7 of a super-block) within its token's 16-chunk
 // row, before the XOR with the token index: MFMA step kk of lane group c consumes chunk 4c + kk,
@@ -728,14 +728,17 @@ hipError_t launch_combine(const __half *h, const float *y, const float *w, uint3
 // the 4c + kk order costs 1.5x the LDS cycles of this one)
 __device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) | (u >> 2); }
 
-// super-blocks of lookahead of the GEMM's prefetch ring (see the kernel): 2 for the few-token tiles
-constexpr int gemm_depth(int MT) { return MT <= 64 ? 2 : 1; }
+// super-blocks of lookahead of the GEMM's prefetch ring (see the kernel): 2 for the few-token tiles;
+// the 8-wave workgroup (one per CU, its activation stages shared by twice the row-tiles) has the
+// LDS for 3
+constexpr int gemm_depth(int MT, int NW = 4) { return NW == 8 ? 3 : MT <= 64 ? 2 : 1; }
 
-template <int MODE, int AT, int MT, bool GROUPED>
-__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
-    extern __shared__ uint4 lds[];                 // gemm_depth(MT) + 1 stages of MT x 16 chunks
+template <int MODE, int AT, int MT, bool GROUPED, int NW = 4>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmArgs a) {
+    extern __shared__ uint4 lds[];                 // gemm_depth(MT, NW) + 1 stages of MT x 16 chunks
     constexpr int NMT = MT / 16;
-    constexpr int NFILL = MT / 16;                 // 16-byte chunks each thread moves per stage
+    constexpr int NFILL = MT / (4 * NW);           // 16-byte chunks each thread moves per stage
+    static_assert(MT % (4 * NW) == 0, "a fill round covers 4 * NW tokens");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, c = lane >> 4;
 
@@ -750,11 +753,11 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     }
     const uint32_t m0 = blockIdx.y * MT;
     if (m0 >= ntok) return;
-    const uint32_t tile_base = (blockIdx.x * 4 + wave) * AT;
+    const uint32_t tile_base = (blockIdx.x * NW + wave) * AT;
 
     // activation fill, global memory straight into LDS (buffer_load ... lds): round r of a wave
     // writes 64 consecutive 16-byte slots, i.e. thread tid fills slot tid & 15 of token
-    // tok0 + 16 r, tok0 = tid >> 4, and therefore fetches the chunk that belongs there,
+    // tok0 + 4 NW r, tok0 = tid >> 4, and therefore fetches the chunk that belongs there,
     // u = lds_col(slot ^ (tok0 & 15)) (lds_col is its own inverse).
     // xoff: byte offset of that chunk in the token's row (grouped launches look the row up);
     // tokens past the end re-read the last valid row: their MFMA columns are never stored, and the
@@ -764,7 +767,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     uint32_t xoff[NFILL];
 #pragma unroll
     for (int r = 0; r < NFILL; ++r) {
-        const uint32_t tok = min(m0 + tok0 + r * 16, ntok - 1);
+        const uint32_t tok = min(m0 + tok0 + r * (4 * NW), ntok - 1);
         size_t rowi = tok;
         if (GROUPED) rowi = (MODE == GEMM_GATE_UP) ? (size_t)(pairs[tok] / (int32_t)a.top_k) : (size_t)pairs[tok];
         xoff[r] = (uint32_t)((rowi * a.x_stride + u * 8) * sizeof(__half));
@@ -790,7 +793,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
     // Prefetch ring: DEPTH super-blocks are in flight ahead of the one being multiplied, in R =
     // DEPTH + 1 weight register sets and LDS stages.  With few tokens an iteration is shorter than
     // the memory latency, so one super-block of lookahead leaves the loop waiting on its loads.
-    constexpr int DEPTH = gemm_depth(MT), R = DEPTH + 1;
+    constexpr int DEPTH = gemm_depth(MT, NW), R = DEPTH + 1;
     constexpr int LPI = NFILL + 2 * AT;          // loads one prefetch issues per lane
     // one super-block of weights of the wave's tiles: the lane's 16 code bytes, and the dword that
     // holds its block's fp16 scale (sh = 0 / 16: which half; the same for the whole workgroup).  The
@@ -802,7 +805,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
         const uint32_t xs = gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half);
 #pragma unroll
         for (int r = 0; r < NFILL; ++r)
-            load_to_lds16(xbuf, (lds_void *)(lds + stage * (MT * 16) + r * 256 + wave_u * 64), xoff[r], xs);
+            load_to_lds16(xbuf, (lds_void *)(lds + stage * (MT * 16) + r * (NW * 64) + wave_u * 64), xoff[r], xs);
     };
 
     // scale group / slot of super-block sb, clamped to the last one (a prefetch past the end
@@ -926,10 +929,14 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
         step(sb, std::integral_constant<int, 0>{});
         step(sb + 1, std::integral_constant<int, 1>{});
         if constexpr (R > 2) step(sb + 2, std::integral_constant<int, 2>{});
+        if constexpr (R > 3) step(sb + 3, std::integral_constant<int, 3>{});
     }
     if (sb < sb_end) step(sb, std::integral_constant<int, 0>{});
     if constexpr (R > 2) {
         if (sb + 1 < sb_end) step(sb + 1, std::integral_constant<int, 1>{});
+    }
+    if constexpr (R > 3) {
+        if (sb + 2 < sb_end) step(sb + 2, std::integral_constant<int, 2>{});
     }
 
     // epilogue: lane holds token j = lane & 15 of each token tile and rows 4*(lane >> 4) + r
@@ -990,6 +997,26 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(GemmArgs a) {
 template <int MODE, int AT, int MT>
 static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st) {
     const uint32_t parts = (!ntasks && a.sb_per_part) ? (a.nsb + a.sb_per_part - 1) / a.sb_per_part : 1;
+    if constexpr (MT == 128) {
+        // Many-token launches of a whole matrix or slab: 8 waves per workgroup, one workgroup per CU.
+        // Its activation stages serve twice the row-tiles, which leaves LDS for three super-blocks of
+        // lookahead instead of one (measured: gate/up and down +10 %, O +6 %).  Both shapes multiply
+        // in the same order, so the choice never changes a result; it goes by how evenly each
+        // shape's workgroups fill the 256 CUs (a 6144-row QKV fills 1.5 rounds either way and runs
+        // 8 % slower in the wide shape).
+        const uint32_t ty = (max_tok + MT - 1) / MT;
+        const uint32_t wg8 = (a.ntiles + 8 * AT - 1) / (8 * AT) * ty, wg4 = (a.ntiles + 4 * AT - 1) / (4 * AT) * ty;
+        const double eff8 = (double)wg8 / ((wg8 + 255) / 256 * 256), eff4 = (double)wg4 / ((wg4 + 511) / 512 * 512);
+        if (!ntasks && parts == 1 && (eff8 >= 0.9 || eff8 > eff4 + 0.05)) {
+            dim3 grid8((a.ntiles + 8 * AT - 1) / (8 * AT), ty, 1);
+            const size_t lds8 = (size_t)MT * 256 * (gemm_depth(MT, 8) + 1);
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4_kernel<MODE, AT, MT, false, 8>),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8);
+            if (attr != hipSuccess) return attr;
+            hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, false, 8>), grid8, dim3(512), lds8, st, a);
+            return hipGetLastError();
+        }
+    }
     dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : parts);
     const size_t lds = (size_t)MT * 256 * (gemm_depth(MT) + 1);
     if (ntasks) hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, true>), grid, dim3(256), lds, st, a);
