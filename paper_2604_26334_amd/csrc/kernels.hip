@@ -867,8 +867,19 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     h8_t Acur[AT], Anxt[AT];
     arrive_w(wr[0]);
     if (PIPE) dequant_a(Acur, wr[0], 0);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LPI) : "memory");   // the first LDS fill has landed
+    // EARLY (three or more super-blocks of lookahead): a stage is required one step before it is
+    // multiplied, so the barrier that ends step sb already covers the fills of stage sb + 2.  A wave
+    // can then fetch the first B operands of step sb + 1 while step sb's last MFMAs run, instead
+    // of every wave of the workgroup meeting the LDS latency together right after the barrier.
+    constexpr bool EARLY = DEPTH >= 3;
+    constexpr int kLand = EARLY ? DEPTH - 2 : DEPTH - 1;   // prefetches that may still be in flight at a barrier
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLand * LPI) : "memory");   // the first LDS fill(s) have landed
     __builtin_amdgcn_s_barrier();
+    h8_t Bc[NMT], Bn[NMT];
+    if (EARLY) {
+#pragma unroll
+        for (int n = 0; n < NMT; ++n) Bc[n] = __builtin_bit_cast(h8_t, lds[i * 16 + n * 256 + (c ^ i)]);
+    }
 
     // one super-block: U = its position in the ring (compile-time, so every register set and LDS
     // stage below is addressed statically and nothing is copied when the ring turns)
@@ -881,16 +892,22 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         load_w(sb + DEPTH, wr[up]);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
         const uint4 *ls = lds + u * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
+        const uint4 *lsn = lds + un * (MT * 16) + i * 16;  // the next super-block's stage
         // B operands are read one MFMA step ahead, so the LDS latency hides behind a step's MFMAs
-        h8_t Bc[NMT], Bn[NMT];
+        if (!EARLY) {
 #pragma unroll
-        for (int n = 0; n < NMT; ++n) Bc[n] = __builtin_bit_cast(h8_t, ls[n * 256 + (c ^ i)]);
+            for (int n = 0; n < NMT; ++n) Bc[n] = __builtin_bit_cast(h8_t, ls[n * 256 + (c ^ i)]);
+        }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) {
 #pragma unroll
                 for (int n = 0; n < NMT; ++n) Bn[n] = __builtin_bit_cast(h8_t, ls[n * 256 + ((c + (kk + 1) * 4) ^ i)]);
                 __builtin_amdgcn_sched_barrier(0);   // or the scheduler sinks each read next to its MFMA
+            } else if (EARLY) {
+#pragma unroll
+                for (int n = 0; n < NMT; ++n) Bn[n] = __builtin_bit_cast(h8_t, lsn[n * 256 + (c ^ i)]);
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (!PIPE) dequant_a(Acur, wr[u], kk);
             else if (kk < 3) dequant_a(Anxt, wr[u], kk + 1);
@@ -908,7 +925,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 #pragma unroll
                 for (int t = 0; t < AT; ++t) Acur[t] = Anxt[t];
             }
-            if (kk < 3) {
+            if (kk < 3 || EARLY) {
 #pragma unroll
                 for (int n = 0; n < NMT; ++n) Bc[n] = Bn[n];
             }
@@ -919,7 +936,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         // here is ordered by hand: this wave's fill of the next stage is complete (vmcnt), and
         // its LDS reads of the current stage, which the next step's fill overwrites, have
         // returned (lgkmcnt).
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DEPTH - 1) * LPI) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLand * LPI) : "memory");
         __builtin_amdgcn_s_barrier();
     };
     // whole turns of the ring, then the remaining steps (no exit from inside a turn: the ring is back
