@@ -355,7 +355,13 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_
 
 template <int MODE, bool FULLG>
 static hipError_t launch_gemv_f(const GemvArgs &a, uint32_t ks, uint32_t ntasks, hipStream_t st) {
-    const uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4, units = nw / ks;
+    // waves per workgroup: at least the K split; two units per workgroup (8 waves) when that still
+    // leaves about one workgroup per CU -- fewer, larger workgroups start sooner (measured on the
+    // 8B shapes: QKV 6.6 -> 5.4 us, gate/up 13.4 -> 13.0 us; O, with 256 units, is best left at one
+    // unit per workgroup).  The result does not depend on the shape.
+    uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4;
+    if (nw < 8 && (a.nunits + 2 * nw / ks - 1) / (2 * nw / ks) >= 192) nw = 8;
+    const uint32_t units = nw / ks;
     dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
     if (nw == 16) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 16, FULLG>), grid, dim3(1024), 0, st, a, ks);
     else if (nw == 8) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 8, FULLG>), grid, dim3(512), 0, st, a, ks);
