@@ -343,7 +343,8 @@ def main():
     ap.add_argument("--measure-profile", type=int, default=1)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--decode-mode", type=int, default=0, help="0 launch per shard, 1 HIP-graph replay")
+    ap.add_argument("--decode-mode", type=int, default=1,
+                    help="0 launch per shard, 1 HIP-graph replay where every shard is resident (others fall back to 0)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -471,7 +472,8 @@ def main():
                 higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f16",
                 data="synthetic",
                 config=dict(workload="dense 8B-shaped stack, %d layers, decode batch 1, budget %g GB" % (
-                    cfg["n_layers"], budgets[0] / 1e9), hidden=4096, ffn=14336, weight_bytes=plans[0].summary().weight_bytes),
+                    cfg["n_layers"], budgets[0] / 1e9), hidden=4096, ffn=14336, weight_bytes=plans[0].summary().weight_bytes,
+                    decode_mode="hip graph replay of the resident forward" if args.decode_mode == 1 else "one launch per shard"),
                 roofline=roof, cpu_baseline=cpu, budgets=results, prefill=prefill, extra=extra,
                 profile=None if prof is None else dict(h2d_gbps=prof.h2d_gbps, gemv_gbps=prof.gemv_gbps,
                                                        launch_us=prof.launch_us, gemm_tflops=list(prof.gemm_tflops),

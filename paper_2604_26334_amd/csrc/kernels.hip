@@ -360,7 +360,7 @@ static hipError_t launch_gemv_f(const GemvArgs &a, uint32_t ks, uint32_t ntasks,
     // 8B shapes: QKV 6.6 -> 5.4 us, gate/up 13.4 -> 13.0 us; O, with 256 units, is best left at one
     // unit per workgroup).  The result does not depend on the shape.
     uint32_t nw = ks > 8 ? 16 : ks > 4 ? 8 : 4;
-    if (nw < 8 && (a.nunits + 2 * nw / ks - 1) / (2 * nw / ks) >= 192) nw = 8;
+    if (ks == 4 && (a.nunits + 1) / 2 >= 192) nw = 8;   // (with one wave per unit, ks < 4, the larger workgroup measured slower)
     const uint32_t units = nw / ks;
     dim3 grid((a.nunits + units - 1) / units, ntasks ? ntasks : 1);
     if (nw == 16) hipLaunchKernelGGL((gemv_w4_kernel<MODE, 16, FULLG>), grid, dim3(1024), 0, st, a, ks);

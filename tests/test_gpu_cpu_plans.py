@@ -152,3 +152,59 @@ def test_moe_experts_on_the_cpu_match_the_oracle(M):
                 assert s.cpu_bytes > 0 and cpu_seen > 0
             st.close()
             plan.close()
+
+
+def test_cpu_plans_beside_a_streamed_kv_cache():
+    """Decode attention over a KV cache whose shards are partly streamed, with the FFN on the CPU:
+    the cache and the attention matrices never leave the GPU side of the plan, the static plan keeps
+    its two slots for the cache shards that do not fit."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    ctx0, steps = 300, 2
+    cfg = dict(Hn.small_dense_cfg(3), kv_context=ctx0 + steps + 3)
+    W = Hn.WeightCache(cfg, 31)
+    n_kv, hd, L = cfg["n_kv_heads"], cfg["head_dim"], cfg["n_layers"]
+    caches = [S.kv_cache(31, l, n_kv, ctx0, hd) for l in range(L)]
+    xs = [S.activations(31, t, 1, cfg["hidden"]) for t in range(steps)]
+    oK = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    oV = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    for l in range(L):
+        oK[l][:, :ctx0], oV[l][:, :ctx0] = caches[l]
+    refs = []
+    for t in range(steps):
+        rows = []
+        refs.append(O.stack_forward(xs[t], cfg, W, mirror=True, kv=lambda l: (oK[l], oV[l]), ctx=ctx0 + t, new_rows=rows))
+        for l, (kn, vn) in enumerate(rows):
+            oK[l][:, ctx0 + t], oV[l][:, ctx0 + t] = kn.astype(np.float16), vn.astype(np.float16)
+    full = B.Plan(cfg, 1 << 40, 1)
+    sh = full.shards()
+    attn_b = sum(s.bytes for s in sh if s.kind in (B.PS_SHARD_QKV, B.PS_SHARD_O))
+    kv_b = sum(s.bytes for s in sh if s.kind == B.PS_SHARD_KV)
+    ws = full.summary().workspace_bytes
+    # budgets: attention + the whole cache pinned (FFN elsewhere); attention + about half the cache
+    for budget in (ws + attn_b + kv_b + (1 << 18), ws + attn_b + kv_b // 2 + (1 << 20)):
+        for kind in (B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC):
+            plan = B.Plan(cfg, budget, 1, profile=_prof(B), kind=kind)
+            s = plan.summary()
+            shards = plan.shards()
+            assert all(x.resident != 2 for x in shards if x.kind in (B.PS_SHARD_QKV, B.PS_SHARD_O, B.PS_SHARD_KV))
+            kv_streamed = sum(1 for x in shards if x.kind == B.PS_SHARD_KV and x.resident == 0)
+            st = B.Stack(plan)
+            for layer in range(L):
+                for k, e, N, K in S.matrix_shapes(cfg):
+                    st.load_matrix(layer, k, e, *W(layer, k, e))
+                for g in range(n_kv):
+                    st.load_kv(layer, g, caches[layer][0][g], caches[layer][1][g])
+            for t in range(steps):
+                st.set_context(ctx0 + t)
+                xin = torch.from_numpy(xs[t]).to(st.device)
+                xout = torch.empty_like(xin)
+                st.forward(xin, xout)
+                st.synchronize()
+                e = Hn.rel_err(xout.cpu().numpy(), refs[t])
+                assert e <= TOL, (budget, kind, t, e)
+            _say("  budget %d kind %d: slots %d, cache shards streamed %d, cpu %d B, streamed %d B, last err %.3e" % (
+                budget, kind, s.n_slots, kv_streamed, s.cpu_bytes, s.streamed_bytes, e))
+            assert s.cpu_bytes > 0
+            st.close()
+            plan.close()
