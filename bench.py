@@ -198,6 +198,14 @@ def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps):
     (pinned after the attention weights, before the FFN), attention is real softmax attention."""
     kcfg = dict(cfg, kv_context=context + 64)
     plans = [B.Plan(kcfg, int(b), 1, profile=prof) for b in budgets]
+    tags = ["%g" % (b / 1e9) for b in budgets]
+    budgets = list(budgets)
+    if prof is not None and prof.cpu_gbps > 0:   # the tightest budget again, planned by HeuristicSplit
+        auto = B.Plan(kcfg, int(budgets[-1]), 1, profile=prof, kind=B.PS_PLAN_AUTO)
+        if auto.summary().plan_kind != B.PS_PLAN_GPU_ONLY:
+            plans.append(auto)
+            tags.append("%g_heuristic_split" % (budgets[-1] / 1e9))
+            budgets.append(budgets[-1])
     stacks = [B.Stack(p) for p in plans]
     B.load_synthetic(stacks, kcfg, seed, threads=min(16, os.cpu_count() or 8))
     K, V = S.kv_cache(seed, 0, kcfg["n_kv_heads"], context, kcfg["head_dim"])   # same contents in every layer
@@ -210,7 +218,7 @@ def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps):
     xo = torch.empty_like(xs[0])
     kv_bytes_layer = context * kcfg["n_kv_heads"] * kcfg["head_dim"] * 2 * 2
     out = {}
-    for b, plan, st in zip(budgets, plans, stacks):
+    for b, tag, plan, st in zip(budgets, tags, plans, stacks):
         s = plan.summary()
         st.set_context(context)            # every timed step attends over the same `context` positions
         n = steps if s.streamed_bytes == 0 else max(3, min(steps, 10))
@@ -220,15 +228,17 @@ def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps):
         kv_res = sum(sh.bytes for sh in plan.shards() if sh.kind == B.PS_SHARD_KV and sh.resident)
         r = dict(budget_bytes=int(b), context=context, ms_per_token=ms, tokens_per_s=1e3 / ms,
                  resident_bytes=s.resident_bytes, kv_cache_bytes=kv_bytes_layer * kcfg["n_layers"],
-                 kv_cache_resident_bytes=kv_res, streamed_bytes_per_token=stats.streamed_bytes_step, est_ms=s.est_step_ms)
+                 kv_cache_resident_bytes=kv_res, streamed_bytes_per_token=stats.streamed_bytes_step, est_ms=s.est_step_ms,
+                 plan=["gpu_only", "static", "dynamic"][s.plan_kind], cpu_bytes_per_token=stats.cpu_bytes_step)
         if at:   # launches of one layer cover all its kv heads when they sit together
             per_layer_ms = at["avg_ms"] * at["launches"] / kcfg["n_layers"]
             r["attn_ms_per_layer"] = per_layer_ms
             r["attn_kv_gbps"] = kv_bytes_layer / (per_layer_ms * 1e-3) / 1e9
             r["attn_frac_of_hbm_peak"] = r["attn_kv_gbps"] / HBM_PEAK_GBS
-        out["%g" % (b / 1e9)] = r
-        log("context %d, budget %.0f GB: %.3f ms/token, %.1f tok/s, cache %.2f of %.2f GB pinned, %.2f GB streamed/token%s" % (
-            context, b / 1e9, ms, 1e3 / ms, kv_res / 1e9, r["kv_cache_bytes"] / 1e9, stats.streamed_bytes_step / 1e9,
+        out[tag] = r
+        log("context %d, budget %.0f GB, plan %s: %.3f ms/token, %.1f tok/s, cache %.2f of %.2f GB pinned, %.2f GB streamed/token, %.2f GB/token on the CPU%s" % (
+            context, b / 1e9, r["plan"], ms, 1e3 / ms, kv_res / 1e9, r["kv_cache_bytes"] / 1e9, stats.streamed_bytes_step / 1e9,
+            stats.cpu_bytes_step / 1e9,
             (", attention %.1f us/layer = %.0f GB/s" % (r["attn_ms_per_layer"] * 1e3, r["attn_kv_gbps"])) if at else ""))
         st.close()
     return out

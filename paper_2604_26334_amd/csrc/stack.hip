@@ -392,10 +392,10 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     const double t0 = now_ms();
     for (int phase = 0; phase < 2; ++phase) {
         std::vector<CpuMatArgs> &mats = phase ? dn : gu;
-        // units of all experts in one job list; about two jobs per thread
+        // units of all experts in one job list
         uint32_t total = 0;
         for (auto &a : mats) { cpu_prepare(a, st->cpu_scratch.data() + scr[&a - mats.data()]); total += cpu_units(a); }
-        const uint32_t per = std::max(1u, total / (st->pool->size() * 2u));
+        const uint32_t per = std::max(1u, total / (st->pool->size() * 4u));   // ~4 jobs per thread: a short tail
         struct Job { uint32_t mat, u0, u1; };
         std::vector<Job> jobs;
         for (uint32_t k = 0; k < mats.size(); ++k)
