@@ -109,12 +109,21 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
     out = {}
     names = ["gpu_only", "static", "dynamic"]
     plans, tags = [], []
+    db = None
+    if prof is not None and prof.cpu_gbps > 0:
+        db = B.ProfileDB()
+        db.measure(cfg)
+    db_est = {}
     for m in token_counts:
         plans.append(B.Plan(cfg, int(budget), m, profile=prof))
         tags.append((m, "batch_%d" % m))
         if prof is not None and prof.cpu_gbps > 0:   # HeuristicSplit's pick, if it is not Plan One again
             auto = B.Plan(cfg, int(budget), m, profile=prof, kind=B.PS_PLAN_AUTO)
-            log("MoE batch %d: HeuristicSplit estimates %s -> %s" % (m, ["%.1f" % e for e in auto.summary().est_kind_ms], names[auto.summary().plan_kind]))
+            auto_db = B.Plan(cfg, int(budget), m, profile=prof, kind=B.PS_PLAN_AUTO, db=db).summary()
+            db_est[m] = dict(picked=names[auto_db.plan_kind], est_ms={names[k]: auto_db.est_kind_ms[k] for k in range(3)})
+            log("MoE batch %d: HeuristicSplit estimates %s -> %s; priced from the profile database %s -> %s" % (
+                m, ["%.1f" % e for e in auto.summary().est_kind_ms], names[auto.summary().plan_kind],
+                ["%.1f" % e for e in auto_db.est_kind_ms], names[auto_db.plan_kind]))
             if auto.summary().plan_kind != B.PS_PLAN_GPU_ONLY:
                 plans.append(auto)
                 tags.append((m, "batch_%d_%s" % (m, names[auto.summary().plan_kind])))
@@ -148,7 +157,7 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
                         cpu_bytes_per_step=on_cpu / steps, cpu_ms_per_step=cpu_ms / steps,
                         pcie_gbps_whole_step=streamed / steps / (ms * 1e-3) / 1e9,
                         frac_of_measured_h2d=(streamed / steps / (ms * 1e-3) / 1e9 / prof.h2d_gbps) if prof else None,
-                        est_ms=s.est_step_ms)
+                        est_ms=s.est_step_ms, heuristic_split_with_database=db_est.get(m))
         log("MoE batch %d, budget %.0f GB, plan %s: %.2f ms/step (estimate %.2f), %.1f tok/s, %.2f GB streamed/step, %.2f GB/step on the CPU in %.2f ms" % (
             m, budget / 1e9, names[s.plan_kind], ms, s.est_step_ms, m * 1e3 / ms, streamed / steps / 1e9, on_cpu / steps / 1e9, cpu_ms / steps))
         st.close()

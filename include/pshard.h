@@ -388,7 +388,8 @@ int32_t ps_profile_db_load(ps_profile_db *db, const char *path);
  * every weight matrix of the model (QKV, O, gate/up, down or the expert pair, output head) as a
  * GEMV at one token and as a GEMM at the tiers up to 2048 tokens, each timed as ten asynchronous
  * launches together; pinned H2D copies of 1 to 64 MiB; and, where the CPU back-end is supported,
- * the FFN / expert / head matrices on it at 1, 4, 16 and 64 tokens (threads = the worker count
+ * the FFN / expert / head matrices on it at 1, 2, 4, 8, 16 and 64 tokens (matrices under 8 MB, i.e.
+ * experts, eight at a time in one pass over the worker pool, as the executor runs them; threads = the worker count
  * used, min(hardware threads, 16)).  scratch, streams: as for ps_profile_measure, scratch at least
  * 768 MiB. */
 int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc *model, void *scratch_dev,

@@ -242,6 +242,20 @@ void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch) {
     });
 }
 
+void cpu_matmul_many(const std::vector<CpuMatArgs> &mats, CpuPool &pool, float *scratch, const std::vector<size_t> &scr) {
+    uint32_t total = 0;
+    for (size_t k = 0; k < mats.size(); ++k) { cpu_prepare(mats[k], scratch + scr[k]); total += cpu_units(mats[k]); }
+    if (!total) return;
+    const uint32_t per = std::max(1u, total / (pool.size() * 4u));
+    struct Job { uint32_t mat, u0, u1; };
+    std::vector<Job> jobs;
+    for (uint32_t k = 0; k < mats.size(); ++k)
+        for (uint32_t u = 0, n = cpu_units(mats[k]); u < n; u += per) jobs.push_back(Job{k, u, std::min(n, u + per)});
+    pool.run((uint32_t)jobs.size(), [&](uint32_t j) {
+        cpu_run_units(mats[jobs[j].mat], jobs[j].u0, jobs[j].u1, scratch + scr[jobs[j].mat]);
+    });
+}
+
 }  // namespace ps
 
 extern "C" int32_t ps_cpu_matmul(const uint8_t *packed, uint32_t rows, uint32_t K, int32_t mode, const uint16_t *x,

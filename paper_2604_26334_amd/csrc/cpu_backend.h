@@ -67,5 +67,8 @@ void cpu_matmul_w4(const CpuMatArgs &a, CpuPool &pool, float *scratch);
 uint32_t cpu_units(const CpuMatArgs &a);
 void cpu_prepare(const CpuMatArgs &a, float *scratch);
 void cpu_run_units(const CpuMatArgs &a, uint32_t u0, uint32_t u1, const float *scratch);
+// Several (small) matrices in one pass over the pool: the units of all of them form one job list,
+// about four jobs per thread.  Matrix k uses scratch + scr[k] (cpu_scratch_floats of its own).
+void cpu_matmul_many(const std::vector<CpuMatArgs> &mats, CpuPool &pool, float *scratch, const std::vector<size_t> &scr);
 
 }  // namespace ps

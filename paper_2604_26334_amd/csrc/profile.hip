@@ -293,24 +293,36 @@ extern "C" int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc 
         const unsigned hw = std::thread::hardware_concurrency();
         std::unique_ptr<CpuPool> pool(new CpuPool(std::min(hw ? hw : 4u, 16u)));
         std::vector<float> scratch(cpu_scratch_floats(64, 16384));
-        std::vector<uint16_t> xh((size_t)64 * 16384, 0x1111), yh((size_t)64 * kMaxRows);
+        std::vector<uint16_t> xh((size_t)64 * 16384, 0x1111), yh((size_t)8 * 64 * kMaxRows);   // an output block per batched matrix
         for (const Mat &mt : mats) {
             if (!mt.cpu) continue;
             const MatGeom mg = make_geom(mt.rows, mt.K, false);
             const uint32_t fit = (uint32_t)std::max<uint64_t>(1, kImage / mg.bytes);
-            for (uint32_t T : {1u, 4u, 16u, 64u}) {
+            for (uint32_t T : {1u, 2u, 4u, 8u, 16u, 64u}) {
                 CpuMatArgs a;
                 a.ntiles = mg.ntiles; a.tile_bytes = mg.tile_bytes; a.nsb = mg.nsb; a.ngroups = mg.ngroups; a.K = mg.K;
                 a.M = T; a.x = xh.data(); a.x_stride = mt.K; a.mode = CPU_PLAIN; a.eps = 1e-6f; a.out = yh.data();
                 a.out_stride = mt.rows; a.out_col0 = 0;
                 const int reps = T <= 4 ? 4 : 2;
-                double t0 = 0;
-                for (int r = -1; r < reps; ++r) {          // pass -1 warms up; each pass reads another copy of the matrix
-                    if (r == 0) t0 = now();
-                    a.W = static_cast<const uint8_t *>(cpu_img) + (uint64_t)((r + 1) % fit) * mg.bytes;
-                    cpu_matmul_w4(a, *pool, scratch.data());
+                // a matrix too small to keep the threads busy on its own (an expert) is run the way the
+                // executor runs such matrices: several of them in one pass over the pool
+                const uint32_t batch = mg.bytes < (8ull << 20) ? std::min(fit, 8u) : 1u;
+                std::vector<CpuMatArgs> many(batch, a);
+                std::vector<size_t> scr(batch);
+                if (scratch.size() < batch * cpu_scratch_floats(T, mt.K)) scratch.resize(batch * cpu_scratch_floats(T, mt.K));
+                for (uint32_t b = 0; b < batch; ++b) {
+                    scr[b] = b * cpu_scratch_floats(T, mt.K);
+                    many[b].out = yh.data() + (size_t)b * 64 * kMaxRows;
                 }
-                rc = add(PS_OPK_CPU, pool->size(), mt.rows, mt.K, T, (now() - t0) / reps);
+                double t0 = 0;
+                for (int r = -1; r < reps; ++r) {          // pass -1 warms up; each pass reads other copies of the matrix
+                    if (r == 0) t0 = now();
+                    for (uint32_t b = 0; b < batch; ++b)
+                        many[b].W = static_cast<const uint8_t *>(cpu_img) + (uint64_t)(((r + 1) * batch + b) % fit) * mg.bytes;
+                    if (batch == 1) cpu_matmul_w4(many[0], *pool, scratch.data());
+                    else cpu_matmul_many(many, *pool, scratch.data(), scr);
+                }
+                rc = add(PS_OPK_CPU, pool->size(), mt.rows, mt.K, T, (now() - t0) / reps / batch);
                 if (rc) goto done;
             }
         }

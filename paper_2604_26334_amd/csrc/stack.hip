@@ -390,20 +390,9 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     }
     if (st->cpu_scratch.size() < scr[op.ntasks]) st->cpu_scratch.resize(scr[op.ntasks]);
     const double t0 = now_ms();
-    for (int phase = 0; phase < 2; ++phase) {
-        std::vector<CpuMatArgs> &mats = phase ? dn : gu;
-        // units of all experts in one job list
-        uint32_t total = 0;
-        for (auto &a : mats) { cpu_prepare(a, st->cpu_scratch.data() + scr[&a - mats.data()]); total += cpu_units(a); }
-        const uint32_t per = std::max(1u, total / (st->pool->size() * 4u));   // ~4 jobs per thread: a short tail
-        struct Job { uint32_t mat, u0, u1; };
-        std::vector<Job> jobs;
-        for (uint32_t k = 0; k < mats.size(); ++k)
-            for (uint32_t u = 0, n = cpu_units(mats[k]); u < n; u += per) jobs.push_back(Job{k, u, std::min(n, u + per)});
-        st->pool->run((uint32_t)jobs.size(), [&](uint32_t j) {
-            cpu_run_units(mats[jobs[j].mat], jobs[j].u0, jobs[j].u1, st->cpu_scratch.data() + scr[jobs[j].mat]);
-        });
-    }
+    scr.pop_back();
+    cpu_matmul_many(gu, *st->pool, st->cpu_scratch.data(), scr);   // gate/up + SwiGLU of every expert
+    cpu_matmul_many(dn, *st->pool, st->cpu_scratch.data(), scr);   // then the down projections
     st->stats.cpu_ms += now_ms() - t0;
     st->stats.cpu_bytes_step += bytes;
     // rows, then (at the fixed offset P * H floats) their pair numbers

@@ -34,7 +34,7 @@ def test_benchmark_suite_fills_the_database_and_prices_a_plan():
     cpu = [e for e in ent if e[0] == B.PS_OPK_CPU]
     if cpu:   # hosts with AVX-512: the FFN and head matrices at four token counts, one thread count
         assert {(e[3], e[4]) for e in cpu} == {(2 * I, H), (H, I), (2064, H)} and len({e[2] for e in cpu}) == 1
-        assert sorted({e[5] for e in cpu}) == [1, 4, 16, 64]
+        assert sorted({e[5] for e in cpu}) == [1, 2, 4, 8, 16, 64]
     # larger copies are not slower per byte; the 64 MiB copy runs at a plausible PCIe rate
     h2d = {e[3]: e[6] for e in ent if e[0] == B.PS_OPK_H2D}
     rate = (64 << 20) / (h2d[64 << 20] * 1e-3) / 1e9
