@@ -347,8 +347,6 @@ int32_t issue_fetch(ps_stack *st, const Op &op, const __half *x_in, __half *x_ou
     return PS_OK;
 }
 
-// CPU: one shard on the CPU back-end, straight from its packed image in the pinned host pool; the
-// finished columns are uploaded on the compute stream, in order with the GPU's work on them.
 // The CPU's experts of one MoE layer: for every such expert its routed (token, rank) pairs go
 // through gate/up + SwiGLU and the down projection on the host; all experts share two passes over
 // the worker pool.  The fp32 result rows travel in one upload, followed by their pair numbers, and
@@ -405,6 +403,8 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     return PS_OK;
 }
 
+// CPU: one shard on the CPU back-end, straight from its packed image in the pinned host pool; the
+// finished columns are uploaded on the compute stream, in order with the GPU's work on them.
 int32_t issue_cpu(ps_stack *st, const ps_schedule &sc, const Op &op, __half *x_out) {
     if (op.info.kernel == PS_K_EXPERT_GATE_UP) return issue_cpu_experts(st, sc, op);
     const ps_plan &p = st->plan;
