@@ -879,7 +879,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // of every wave of the workgroup meeting the LDS latency together right after the barrier.
     constexpr bool EARLY = DEPTH >= 3;
     constexpr int kLand = EARLY ? DEPTH - 2 : DEPTH - 1;   // prefetches that may still be in flight at a barrier
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLand * LPI) : "memory");   // the first LDS fill(s) have landed
+    // a prefetch issues its LDS fills before its weight loads and loads return in order, so the
+    // barrier of the EARLY shape needs only the fills of the stage it covers: that stage's weight
+    // loads (from HBM, the slow ones; consumed a step later) may stay in flight as well
+    constexpr int kInFlight = kLand * LPI + (EARLY ? 2 * AT : 0);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");   // the first LDS fill(s) have landed
     __builtin_amdgcn_s_barrier();
     h8_t Bc[NMT], Bn[NMT];
     if (EARLY) {
@@ -942,7 +946,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         // here is ordered by hand: this wave's fill of the next stage is complete (vmcnt), and
         // its LDS reads of the current stage, which the next step's fill overwrites, have
         // returned (lgkmcnt).
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLand * LPI) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kInFlight) : "memory");
         __builtin_amdgcn_s_barrier();
     };
     // whole turns of the ring, then the remaining steps (no exit from inside a turn: the ring is back
