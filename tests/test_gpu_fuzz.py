@@ -1,0 +1,81 @@
+"""Seeded sweep on the GPU: random small models (dense / MoE, with or without attention, residual,
+output head), budgets, token counts and plan kinds, each forward against the CPU oracle at
+max|err| / max|ref| <= 5e-3."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+def _random_cfg(rng):
+    moe = rng.random() < 0.4
+    attn = rng.random() < 0.8
+    n_kv = int(rng.choice([1, 2]))
+    cfg = dict(n_layers=int(rng.integers(1, 4)), hidden=int(rng.choice([128, 256, 512])),
+               n_q_heads=n_kv * int(rng.choice([1, 2, 4])) if attn else 0, n_kv_heads=n_kv if attn else 0,
+               head_dim=128 if attn else 0, ffn_inter=0 if moe else 128 * int(rng.integers(1, 9)),
+               n_experts=int(rng.choice([4, 8])) if moe else 0, top_k=0,
+               expert_inter=128 * int(rng.integers(1, 3)) if moe else 0, rms_eps=1e-6, no_attn=not attn,
+               no_residual=bool(rng.random() < 0.2))
+    if moe:
+        cfg["top_k"] = int(rng.integers(1, 4))
+    if rng.random() < 0.5:
+        cfg["vocab"] = 16 * int(rng.integers(4, 120))
+    return cfg
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_models_match_the_oracle(seed):
+    import torch
+    from paper_2604_26334_amd import binding as B
+    rng = np.random.default_rng(4000 + seed)
+    prof = B.make_profile(h2d_gbps=50.0, gemv_gbps=4000.0, cpu_gbps=150.0, cpu_gbps_busy=120.0, h2d_gbps_busy=45.0,
+                          cpu_tokens_free=3.0, cpu_sync_us=0.5)
+    for case in range(8):
+        cfg = _random_cfg(rng)
+        M = int(rng.choice([1, 1, 2, 5, 16, 33, 64, 130]))
+        wseed = int(rng.integers(1 << 20))
+        W = Hn.WeightCache(cfg, wseed)
+        head = S.head_matrix(wseed, cfg) if cfg.get("vocab") else None
+        x = S.activations(wseed, 0, M, cfg["hidden"])
+        lg = S.router_logits(wseed, 0, cfg["n_layers"], M, cfg["n_experts"]) if cfg["n_experts"] else None
+        ref_x = O.stack_forward(x, cfg, W, logits=lg, mirror=True)
+        ref_l = O.output_head(ref_x, cfg, head, mirror=True) if head else None
+        full = B.Plan(cfg, 1 << 40, M).summary()
+        frac = float(rng.choice([0.1, 0.3, 0.6, 1.1]))
+        budget = full.workspace_bytes + int(full.weight_bytes * frac) + (1 << 16)
+        kinds = [B.PS_PLAN_GPU_ONLY] + ([B.PS_PLAN_STATIC, B.PS_PLAN_DYNAMIC] if M <= 64 else [])
+        for kind in kinds:
+            try:
+                plan = B.Plan(cfg, budget, M, profile=prof, kind=kind)
+            except B.PshardError as e:
+                assert e.code == B.PS_E_BUDGET
+                continue
+            st = B.Stack(plan)
+            for layer in range(cfg["n_layers"]):
+                for k, e, N, K in S.matrix_shapes(cfg):
+                    st.load_matrix(layer, k, e, *W(layer, k, e))
+            lo = None
+            if head:
+                st.load_matrix(cfg["n_layers"], S.MAT_OUT, None, *head)
+                lo = torch.zeros((M, cfg["vocab"]), dtype=torch.float16, device=st.device)
+                st.set_logits_out(lo, 0, M)
+            xin = torch.from_numpy(x).to(st.device)
+            xout = torch.empty_like(xin)
+            torch.cuda.synchronize()
+            st.forward(xin, xout, lg)
+            st.synchronize()
+            s = plan.summary()
+            e_x = Hn.rel_err(xout.cpu().numpy(), ref_x)
+            e_l = Hn.rel_err(lo.cpu().numpy(), ref_l) if head else 0.0
+            print("  seed %d case %d kind %d: L%d H%d %s M%d frac %.1f pinned %d streamed %d cpu %d  err %.2e %.2e" % (
+                seed, case, kind, cfg["n_layers"], cfg["hidden"], "moe" if cfg["n_experts"] else "dense", M, frac,
+                s.resident_bytes, s.streamed_bytes, s.cpu_bytes, e_x, e_l), flush=True)
+            assert e_x <= TOL and e_l <= TOL, (cfg, M, budget, kind)
+            st.close()
+            plan.close()
