@@ -471,8 +471,10 @@ hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t to
 // sum of p and p-weighted V sums.  Chunks are merged by attn_combine_kernel in chunk order, so the
 // result does not depend on where the cache shard lives.
 // ------------------------------------------------------------------------------------
-constexpr int kAttnPos = kAttnChunk;      // positions per workgroup: 4 waves x kAttnIts steps x 4 positions
-constexpr int kAttnIts = kAttnPos / 16;
+constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 16K context: 4 -> 1.88, 8 -> 1.68, 16 -> 1.74 ms per token)
+constexpr int kAttnIts = 8;               // steps of 4 positions per wave
+constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
+static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
 
 // sum over each row of 16 lanes, result in every lane of the row (DPP: no LDS traffic)
 __device__ __forceinline__ float row16_sum(float v) {
@@ -484,9 +486,9 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 template <int G>
-__global__ __launch_bounds__(256, 4) void attn_decode_kernel(AttnArgs a) {
-    __shared__ float red[4][G][128];
-    __shared__ float redm[4][G], redl[4][G];
+__global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_kernel(AttnArgs a) {
+    __shared__ float red[kAttnWaves][G][128];
+    __shared__ float redm[kAttnWaves][G], redl[kAttnWaves][G];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int dl = lane & 15, pg = lane >> 4;
     const uint32_t chunk = blockIdx.x, hk = blockIdx.y;               // kv head within this launch
@@ -504,7 +506,7 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(AttnArgs a) {
     // the V rows stream in while the scores are computed
     // Buffer loads bounded to the ctx valid rows: a row past the end reads as zeros, so the loads
     // need no branch (a branch per load would also make the compiler wait for each load at once)
-    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / 4);
+    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / kAttnWaves);
     const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)(a.ctx * 256u), 0x00020000);
     const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)(a.ctx * 256u), 0x00020000);
     const uint32_t voff = (uint32_t)pg * 256u + (uint32_t)dl * 16u;
@@ -568,8 +570,8 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(AttnArgs a) {
             for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
         }
     }
-    // the 4 position groups of a wave meet; then the 4 waves through LDS, rescaled to the chunk
-    // maximum, in fixed order
+    // the 4 position groups of a wave meet; then the workgroup's waves through LDS, rescaled to the
+    // chunk maximum, in fixed order
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         l[h] += __shfl_xor(l[h], 16, 64);
@@ -586,18 +588,24 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    for (int t = tid; t < G * 128; t += 256) {
+    for (int t = tid; t < G * 128; t += kAttnWaves * 64) {
         const int h = t >> 7, d = t & 127;
         // wave 0's first position is always valid in a launched chunk, so the chunk maximum is finite
-        const float m = fmaxf(fmaxf(redm[0][h], redm[1][h]), fmaxf(redm[2][h], redm[3][h]));
-        float w[4];
+        float m = redm[0][h];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = redm[k][h] == -INFINITY ? 0.f : __expf(redm[k][h] - m);
+        for (int k = 1; k < kAttnWaves; ++k) m = fmaxf(m, redm[k][h]);
+        float od = 0.f, ld = 0.f;   // waves in ascending order
+#pragma unroll
+        for (int k = 0; k < kAttnWaves; ++k) {
+            const float w = redm[k][h] == -INFINITY ? 0.f : __expf(redm[k][h] - m);
+            od = fmaf(w, red[k][h][d], od);
+            ld = fmaf(w, redl[k][h], ld);
+        }
         float *dst = a.part + ((size_t)(q0 + h) * a.chunk_cap + chunk) * 130;
-        dst[2 + d] = fmaf(w[3], red[3][h][d], fmaf(w[2], red[2][h][d], fmaf(w[1], red[1][h][d], w[0] * red[0][h][d])));
+        dst[2 + d] = od;
         if (d == 0) {
             dst[0] = m;
-            dst[1] = fmaf(w[3], redl[3][h], fmaf(w[2], redl[2][h], fmaf(w[1], redl[1][h], w[0] * redl[0][h])));
+            dst[1] = ld;
         }
     }
 }
@@ -607,10 +615,10 @@ hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
     dim3 grid((a.ctx + kAttnPos - 1) / kAttnPos, a.nheads);
     if (grid.x > a.chunk_cap) return hipErrorInvalidValue;
     switch (a.group) {
-        case 1: hipLaunchKernelGGL(attn_decode_kernel<1>, grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(attn_decode_kernel<2>, grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL(attn_decode_kernel<4>, grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL(attn_decode_kernel<8>, grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL(attn_decode_kernel<1>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 2: hipLaunchKernelGGL(attn_decode_kernel<2>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 4: hipLaunchKernelGGL(attn_decode_kernel<4>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 8: hipLaunchKernelGGL(attn_decode_kernel<8>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
