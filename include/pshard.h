@@ -454,10 +454,13 @@ int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads);
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
 /* Decode execution mode.  0 (default): one launch per shard.  1: applies when the plan is dense,
- * one token, no KV cache and every shard resident (otherwise mode 0 runs): the launch-per-shard
- * kernel sequence is captured once per (x_in, x_out) pair into a HIP graph (kernel nodes only) and
- * replayed.  Order and arithmetic are unchanged (Algorithm 1's RunInTopologicalOrder); both modes
- * give bit-identical results.  Not to be called while a forward is in flight. */
+ * one token and every shard (KV-cache shards included) resident (otherwise mode 0 runs): the
+ * launch-per-shard kernel sequence is captured once per (x_in, x_out, logits) triple into a HIP
+ * graph (kernel nodes only) and replayed; with a KV cache the context length then travels in a
+ * device word set before each replay, and the attention launch covers every chunk the cache can
+ * hold (workgroups past the context leave at once).  Order and arithmetic are unchanged
+ * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  Not to be called
+ * while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
 /* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
  * the copy stream pulls all of them from the pinned pool (one launch per slot fill);

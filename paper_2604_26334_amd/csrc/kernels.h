@@ -82,7 +82,12 @@ struct AttnArgs {
     uint32_t cap, ctx, head0, nheads, group, chunk_cap;
     const __half *q;      // the token's QKV row: query head h at [h * 128]
     float *part;
+    const uint32_t *ctx_dev;   // not null: the context length is read from here (device) instead of ctx, and
+                               // the launch covers every chunk the cache can hold (a captured graph is
+                               // replayed at any context); workgroups past the context leave at once
 };
+// *dst = v (device word), in stream order
+hipError_t launch_set_u32(uint32_t *dst, uint32_t v, hipStream_t st);
 // dst[idx[r]][0..H) = src[r][0..H) for r < n (fp32 rows; H a multiple of 4; idx values are row numbers of dst)
 hipError_t launch_scatter_rows(const float *src, const int32_t *idx, uint32_t n, uint32_t H, float *dst, hipStream_t st);
 hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st);
@@ -90,8 +95,8 @@ hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st);
 // q.k_new / sqrt(128), value v_new), write the attention output (fp16 [n_q * 128]) and append the
 // token's K and V rows at position ctx of each kv head's cache home (home[g] = address of that
 // head's K row 0, device memory or device-visible pinned host memory).
-hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
-                               uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st);
+hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, const uint32_t *ctx_dev, uint32_t cap,
+                               const __half *qkv, uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st);
 hipError_t launch_combine(const __half *h, const float *y, const float *w, uint32_t M, uint32_t H, uint32_t top_k,
                           int residual, __half *out, hipStream_t st);
 hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st);

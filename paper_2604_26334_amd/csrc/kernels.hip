@@ -471,7 +471,7 @@ hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t to
 // sum of p and p-weighted V sums.  Chunks are merged by attn_combine_kernel in chunk order, so the
 // result does not depend on where the cache shard lives.
 // ------------------------------------------------------------------------------------
-constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 16K context: 4 -> 1.88, 8 -> 1.68, 16 -> 1.74 ms per token)
+constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 16K context: 4 -> 1.716, 8 -> 1.680, 16 -> 1.744 ms per token)
 constexpr int kAttnIts = 8;               // steps of 4 positions per wave
 constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
 static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
@@ -492,6 +492,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int dl = lane & 15, pg = lane >> 4;
     const uint32_t chunk = blockIdx.x, hk = blockIdx.y;               // kv head within this launch
+    const uint32_t ctx = a.ctx_dev ? *a.ctx_dev : a.ctx;              // the same for the whole grid
+    if (chunk * kAttnPos >= ctx) return;                              // (launches sized for the whole cache)
     const __half *K = reinterpret_cast<const __half *>(reinterpret_cast<const char *>(a.kv) + (size_t)hk * a.head_stride);
     const __half *V = K + (size_t)a.cap * 128;
     const uint32_t q0 = (a.head0 + hk) * G;                           // first query head of this kv head
@@ -507,8 +509,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
     // Buffer loads bounded to the ctx valid rows: a row past the end reads as zeros, so the loads
     // need no branch (a branch per load would also make the compiler wait for each load at once)
     const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / kAttnWaves);
-    const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)(a.ctx * 256u), 0x00020000);
-    const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)(a.ctx * 256u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)(ctx * 256u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)(ctx * 256u), 0x00020000);
     const uint32_t voff = (uint32_t)pg * 256u + (uint32_t)dl * 16u;
     const uint32_t soff = __builtin_amdgcn_readfirstlane(base * 256u);
     uint4 kq[kAttnIts], vq[kAttnIts];
@@ -535,7 +537,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
             d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kq[it].z), d, false);
             d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kq[it].w), d, false);
             const float r = row16_sum(d) * scale;      // outside any branch: every lane takes part
-            sc[it][h] = j < a.ctx ? r : -INFINITY;
+            sc[it][h] = j < ctx ? r : -INFINITY;
             mx[h] = fmaxf(mx[h], sc[it][h]);
         }
     }
@@ -610,9 +612,19 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
     }
 }
 
+__global__ void set_u32_kernel(uint32_t *dst, uint32_t v) { *dst = v; }
+
+hipError_t launch_set_u32(uint32_t *dst, uint32_t v, hipStream_t st) {
+    hipLaunchKernelGGL(set_u32_kernel, dim3(1), dim3(1), 0, st, dst, v);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
-    if (a.ctx == 0 || a.nheads == 0) return hipSuccess;
-    dim3 grid((a.ctx + kAttnPos - 1) / kAttnPos, a.nheads);
+    if ((!a.ctx_dev && a.ctx == 0) || a.nheads == 0) return hipSuccess;
+    // context read on the device: cover every chunk a cache of cap positions can hold (ctx < cap)
+    const uint32_t span = a.ctx_dev ? a.cap - 1 : a.ctx;
+    if (span == 0) return hipSuccess;
+    dim3 grid((span + kAttnPos - 1) / kAttnPos, a.nheads);
     if (grid.x > a.chunk_cap) return hipErrorInvalidValue;
     switch (a.group) {
         case 1: hipLaunchKernelGGL(attn_decode_kernel<1>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
@@ -645,9 +657,10 @@ __device__ __forceinline__ float block512_reduce(float v, float *scratch, bool i
     return r;
 }
 
-__global__ __launch_bounds__(512) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx,
-                                                           uint32_t cap, const __half *qkv, uint32_t n_q, uint32_t n_kv,
-                                                           const uint64_t *home, __half *out) {
+__global__ __launch_bounds__(512) void attn_combine_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx_arg,
+                                                           const uint32_t *ctx_dev, uint32_t cap, const __half *qkv,
+                                                           uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out) {
+    const uint32_t ctx = ctx_dev ? *ctx_dev : ctx_arg;
     __shared__ float scratch[8];
     __shared__ float wbuf[kAttnMaxChunks];
     __shared__ float osum[4][128];
@@ -695,10 +708,12 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const float *part, ui
     }
 }
 
-hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
-                               uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st) {
-    if (ctx >= cap || n_kv == 0 || n_q % n_kv || (ctx + kAttnPos - 1) / kAttnPos > kAttnMaxChunks) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(512), 0, st, part, chunk_cap, ctx, cap, qkv, n_q, n_kv, home, out);
+hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t ctx, const uint32_t *ctx_dev, uint32_t cap,
+                               const __half *qkv, uint32_t n_q, uint32_t n_kv, const uint64_t *home, __half *out, hipStream_t st) {
+    // (with the context on the device the caller has checked it against cap; the chunk bound then goes by cap)
+    const uint32_t span = ctx_dev ? cap - 1 : ctx;
+    if (ctx >= cap || n_kv == 0 || n_q % n_kv || (span + kAttnPos - 1) / kAttnPos > kAttnMaxChunks) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(n_q), dim3(512), 0, st, part, chunk_cap, ctx, ctx_dev, cap, qkv, n_q, n_kv, home, out);
     return hipGetLastError();
 }
 

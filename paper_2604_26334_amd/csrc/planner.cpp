@@ -149,6 +149,7 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M, bool cpu_experts) {
         const uint64_t chunks = (g.m.kv_context + kAttnChunk - 1) / kAttnChunk;
         w.apart = take((uint64_t)g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
         w.kvhome = take((uint64_t)g.m.n_layers * g.m.n_kv_heads * 8);
+        w.ctx = take(4);   // context length as the kernels of a replayed graph read it
     }
     w.total = off;
     return w;

@@ -47,7 +47,7 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out);
 struct Workspace {
     uint64_t x0 = 0, x1 = 0, h = 0, qkv = 0, s = 0, y = 0, rinv = 0, ridx = 0, rw = 0,
              logits = 0, tasks = 0, pairs = 0, partial = 0,
-             attn = 0, apart = 0, kvhome = 0, cpu_y = 0, total = 0;   // attention output, chunk partials, cache home table, CPU experts' results
+             attn = 0, apart = 0, kvhome = 0, ctx = 0, cpu_y = 0, total = 0;   // attention output, chunk partials, cache home table, CPU experts' results
     uint64_t qkv_bytes = 0, h_bytes = 0, s_bytes = 0, tasks_bytes = 0, pairs_bytes = 0, logits_bytes = 0;
 };
 Workspace make_workspace(const ModelGeom &g, uint32_t M, bool cpu_experts = false);

@@ -66,6 +66,7 @@ struct ps_stack {
     uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
     hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
     bool step_pending = false;
+    bool kv_copied = false;                   // some kv shard is not resident: the copy stream reads appended rows
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
     std::vector<uint8_t> prof_is_copy;
@@ -268,12 +269,14 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             a.head0 = s.expert; a.nheads = op.info.nshards; a.group = m.n_q_heads / m.n_kv_heads;
             a.chunk_cap = (m.kv_context + kAttnChunk - 1) / kAttnChunk;
             a.q = qkv; a.part = reinterpret_cast<float *>(A + p.ws.apart);
+            a.ctx_dev = st->use_graph ? reinterpret_cast<const uint32_t *>(A + p.ws.ctx) : nullptr;
             PS_HIP(launch_attn_decode(a, cs));
             return PS_OK;
         }
         case PS_K_ATTN_COMBINE:
             PS_HIP(launch_attn_combine(reinterpret_cast<const float *>(A + p.ws.apart),
-                                       (m.kv_context + kAttnChunk - 1) / kAttnChunk, st->ctx, m.kv_context, qkv,
+                                       (m.kv_context + kAttnChunk - 1) / kAttnChunk, st->ctx,
+                                       st->use_graph ? reinterpret_cast<const uint32_t *>(A + p.ws.ctx) : nullptr, m.kv_context, qkv,
                                        m.n_q_heads, m.n_kv_heads,
                                        reinterpret_cast<const uint64_t *>(A + p.ws.kvhome) + (size_t)l * m.n_kv_heads,
                                        reinterpret_cast<__half *>(A + p.ws.attn), cs));
@@ -475,6 +478,9 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     st->prof_valid = false;
     ps_stats &ss = st->stats;
     ss = ps_stats{};
+    // graph mode with a KV cache: the context length travels in device memory, where the attention
+    // kernels of this mode read it (set here, outside any capture, so a replay sees this step's value)
+    if (st->use_graph && p.g.kv) PS_HIP(launch_set_u32(reinterpret_cast<uint32_t *>(st->arena + p.ws.ctx), st->ctx, st->compute));
     if (st->use_graph && !prof) {
         // Launch-bound case (every shard resident, one token): the kernel sequence is captured
         // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
@@ -685,6 +691,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         for (size_t i = 0; i < p.shards.size(); ++i) {
             const ps::Shard &s = p.shards[i];
             if (s.kind != PS_SHARD_KV) continue;
+            if (!s.resident) st->kv_copied = true;
             home[(size_t)s.layer * m.n_kv_heads + s.expert] =
                 (uint64_t)(uintptr_t)(s.resident ? st->arena + s.offset : st->shard_host[i]);
         }
@@ -847,11 +854,11 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     if (p.g.kv) {
         if (st->ctx >= p.g.m.kv_context) { ps::set_error("context %u leaves no room in a cache of %u positions", st->ctx, p.g.m.kv_context); return PS_E_STATE; }
         // this step's cache copies read rows the previous step appended from the compute stream
-        if (st->step_pending) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_step, 0));
+        if (st->kv_copied && st->step_pending) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_step, 0));
     }
     if (!p.g.moe) {
         const int32_t rc = run_schedule(st, st->dense_sched, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
-        if (rc == PS_OK && p.g.kv) { PS_HIP(hipEventRecord(st->ev_step, st->compute)); st->step_pending = true; }
+        if (rc == PS_OK && st->kv_copied) { PS_HIP(hipEventRecord(st->ev_step, st->compute)); st->step_pending = true; }
         return rc;
     }
 
@@ -901,7 +908,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (mode < 0 || mode > 1) { ps::set_error("decode mode must be 0 or 1"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
-    st->use_graph = mode == 1 && !p.g.moe && !p.g.kv && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
+    st->use_graph = mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
     return PS_OK;
 }
 

@@ -302,3 +302,44 @@ def test_error_paths_return_codes_and_leave_the_stack_usable():
     with pytest.raises(B.PshardError):
         kst.load_kv(0, 5, np.zeros((4, 128), np.float16), np.zeros((4, 128), np.float16))
     kst.close()
+
+
+def test_kv_decode_graph_replay_matches_launch_per_shard():
+    """Decode over a resident KV cache replayed from a HIP graph: the context length is read from device
+    memory, so one captured graph serves every step; bits must equal the launch-per-shard mode at each
+    of several consecutive steps, after a jump back to a shorter context, and at an empty cache."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    ctx0, cap = 300, 700
+    cfg = _kv_cfg(3, cap)
+    W = Hn.WeightCache(cfg, 19)
+    n_kv, hd, L = cfg["n_kv_heads"], cfg["head_dim"], cfg["n_layers"]
+    caches = [S.kv_cache(19, l, n_kv, ctx0, hd) for l in range(L)]
+    xs = [S.activations(19, t, 1, cfg["hidden"]) for t in range(8)]
+    contexts = [ctx0, ctx0 + 1, ctx0 + 2, ctx0 + 3, 5, 6, 0, 1]      # rows appended by earlier steps are reused
+    outs = {}
+    for mode in (0, 1):
+        plan = B.Plan(cfg, 1 << 30, 1)
+        assert plan.summary().streamed_bytes == 0
+        st = B.Stack(plan)
+        st.set_decode_mode(mode)
+        for layer in range(L):
+            for k, e, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, e, *W(layer, k, e))
+            for g in range(n_kv):
+                st.load_kv(layer, g, caches[layer][0][g], caches[layer][1][g])
+        xin = [torch.from_numpy(x).to(st.device) for x in xs]
+        xout = torch.empty_like(xin[0])
+        res = []
+        for t, c in enumerate(contexts):
+            st.set_context(c)
+            torch.cuda.synchronize()
+            st.forward(xin[t % 2], xout)          # two input buffers: two captured graphs, each replayed
+            st.synchronize()
+            res.append(xout.cpu().numpy().copy())
+        outs[mode] = res
+        st.close()
+        plan.close()
+    for t, (a, b) in enumerate(zip(outs[0], outs[1])):
+        assert np.isfinite(a.astype(np.float64)).all()
+        np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16), err_msg="step %d" % t)
