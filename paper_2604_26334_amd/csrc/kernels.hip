@@ -396,20 +396,35 @@ hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t nt
 }
 
 // ------------------------------------------------------------------------------------
-// rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one wave per token (used when M > 1)
+// rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one workgroup per token (used when M > 1): thread t adds
+// the 8-column chunks t, t + 256, ... in that order, the 64 lanes of a wave are summed by the
+// butterfly, the four waves in order.  All of a thread's loads (up to four per round) are issued
+// before the first is used; chunks past the row's end count as zeros.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rinv_kernel(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv) {
-    const uint32_t m = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (m >= M) return;
+    __shared__ float part[4];
+    const uint32_t m = blockIdx.x;
+    const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)m * H);
+    const uint32_t nq = H / 8;
     float ss = 0.f;
-    for (uint32_t q = lane; q < H / 8; q += 64) ss += sumsq8(*reinterpret_cast<const uint4 *>(x + (size_t)m * H + q * 8));
+    for (uint32_t q0 = 0; q0 < nq; q0 += 1024) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = q0 + u * 256 + threadIdx.x;
+            v[u] = q < nq ? row[q] : uint4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ss += sumsq8(v[u]);
+    }
     ss = wave_sum(ss);
-    if (lane == 0) rinv[m] = rsqrtf(ss / (float)H + eps);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) rinv[m] = rsqrtf((((part[0] + part[1]) + part[2]) + part[3]) / (float)H + eps);
 }
 
 hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st) {
-    hipLaunchKernelGGL(rinv_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, H, eps, rinv);
+    hipLaunchKernelGGL(rinv_kernel, dim3(M), dim3(256), 0, st, x, M, H, eps, rinv);
     return hipGetLastError();
 }
 
@@ -1152,29 +1167,53 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float *parti
                                                               uint32_t M, uint32_t ncols_phys, const float *rinv,
                                                               const __half *res, __half *out, uint32_t out_stride,
                                                               uint32_t out_row0) {
+    // one thread per four adjacent output columns (a 16-column tile is never straddled)
     const uint32_t ncols = MODE == GEMM_GATE_UP ? ncols_phys / 2 : ncols_phys;
-    const size_t n = (size_t)M * ncols;
+    const uint32_t nq = ncols / 4;
+    const size_t n = (size_t)M * nq;
     for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n; q += (size_t)gridDim.x * 256) {
-        const uint32_t m = (uint32_t)(q / ncols), j = (uint32_t)(q % ncols);
+        const uint32_t m = (uint32_t)(q / nq), j = (uint32_t)(q % nq) * 4;
         const uint32_t c0 = MODE == GEMM_GATE_UP ? (j >> 4) * 32 + (j & 15) : j;
         const float *p0 = partial + (size_t)m * ncols_phys + c0;
-        float v = 0.f, u = 0.f;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f), u = v;
         for (uint32_t p = 0; p < parts; ++p) {
-            v += p0[(size_t)p * part_stride];
-            if (MODE == GEMM_GATE_UP) u += p0[(size_t)p * part_stride + 16];
+            const float4 a = *reinterpret_cast<const float4 *>(p0 + (size_t)p * part_stride);
+            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+            if (MODE == GEMM_GATE_UP) {
+                const float4 b = *reinterpret_cast<const float4 *>(p0 + (size_t)p * part_stride + 16);
+                u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+            }
         }
-        float r;
-        if (MODE == GEMM_PLAIN) r = rinv[m] * v;
-        else if (MODE == GEMM_RESID) r = (res ? __half2float(res[(size_t)m * out_stride + out_row0 + j]) : 0.f) + v;
-        else { const float ri = rinv[m]; r = silu(ri * v) * (ri * u); }
-        out[(size_t)m * out_stride + out_row0 + j] = to_half(r);
+        float r[4] = {v.x, v.y, v.z, v.w};
+        if (MODE == GEMM_PLAIN) {
+            const float ri = rinv[m];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = ri * r[e];
+        } else if (MODE == GEMM_RESID) {
+            if (res) {
+                const __half2 *rs = reinterpret_cast<const __half2 *>(res + (size_t)m * out_stride + out_row0 + j);
+                const float2 r01 = __half22float2(rs[0]), r23 = __half22float2(rs[1]);
+                r[0] = r01.x + r[0]; r[1] = r01.y + r[1]; r[2] = r23.x + r[2]; r[3] = r23.y + r[3];
+            }
+        } else {
+            const float ri = rinv[m];
+            const float g[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = silu(ri * r[e]) * (ri * g[e]);
+        }
+        __half2 *d2 = reinterpret_cast<__half2 *>(out + (size_t)m * out_stride + out_row0 + j);
+        d2[0] = __half2{to_half(r[0]), to_half(r[1])};
+        d2[1] = __half2{to_half(r[2]), to_half(r[3])};
     }
 }
 
 hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
                                   uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,
                                   uint32_t out_stride, uint32_t out_row0, hipStream_t st) {
-    const size_t n = (size_t)M * ncols_phys;
+    // four columns per thread: 16-byte plane reads, 8-byte stores (columns come in tiles of 16 and
+    // out_row0 / out_stride are multiples of 16, so both stay aligned)
+    if (ncols_phys % 16 || out_row0 % 4 || out_stride % 4 || part_stride % 4) return hipErrorInvalidValue;
+    const size_t n = (size_t)M * (ncols_phys / 4);
     const uint32_t blocks = (uint32_t)std::min<size_t>((n + 255) / 256, 2048);
     switch (mode) {
         case GEMM_PLAIN:
