@@ -871,13 +871,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     auto arrive_w = [&](Wset &w) {
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
-            uint4 q;
-            uint32_t d;
-            asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8\n\tv_mov_b32 %4, %9"
-                         : "=&v"(q.x), "=&v"(q.y), "=&v"(q.z), "=&v"(q.w), "=&v"(d)
-                         : "v"(w.q[t].x), "v"(w.q[t].y), "v"(w.q[t].z), "v"(w.q[t].w), "v"(w.d[t]));
-            w.q[t] = q;
-            w.d[t] = d;
+            // (an empty statement the compiler cannot see through: no instruction is issued)
+            asm volatile("" : "+v"(w.q[t].x), "+v"(w.q[t].y), "+v"(w.q[t].z), "+v"(w.q[t].w), "+v"(w.d[t]));
+            // the block's scale, once per super-block rather than once per MFMA step
+            w.d[t] >>= w.sh;
         }
     };
     // A operands of MFMA step kk from raw dwords + scale: (q - 8) * d rounded to fp16
@@ -885,7 +882,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
             const uint32_t q = kk == 0 ? ws.q[t].x : kk == 1 ? ws.q[t].y : kk == 2 ? ws.q[t].z : ws.q[t].w;
-            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(ws.d[t] >> ws.sh));
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)ws.d[t]);
             const h2_t dd = {d, d};
             h2_t w[4];
             dequant8(q, w);
