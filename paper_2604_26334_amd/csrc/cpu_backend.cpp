@@ -202,20 +202,34 @@ size_t cpu_scratch_floats(uint32_t M, uint32_t K) { return (size_t)M * K + M + 6
 
 uint32_t cpu_units(const CpuMatArgs &a) { return a.mode == CPU_GATE_UP ? a.ntiles / 2 : a.ntiles; }
 
-// activations once per call: fp32, in the order the kernel dequantises a block; RMS factors
+// activations once per call: fp32, in the order the kernel dequantises a block; RMS factors.
+// A block of 32 fp16 values is converted and permuted in registers (small expert matrices are
+// prepared once per expert and token, which a scalar loop made a visible share of their time);
+// the squares are summed in double precision, eight partial sums per half block.
 PS_AVX512 void cpu_prepare(const CpuMatArgs &a, float *scratch) {
     float *xp = scratch, *rinv = scratch + (size_t)a.M * a.K;
     const bool norm = a.mode == CPU_PLAIN || a.mode == CPU_GATE_UP;
+    alignas(64) int32_t il[16], ih[16];
+    for (uint32_t j = 0; j < 16; ++j) { il[j] = (int32_t)block_k(j); ih[j] = (int32_t)block_k(16 + j); }
+    const __m512i idx_lo = _mm512_load_si512(il), idx_hi = _mm512_load_si512(ih);
+    const __m512 sixteenth = _mm512_set1_ps(0.0625f);   // high-nibble weights come out as 16 (q - 8)
     for (uint32_t m = 0; m < a.M; ++m) {
         const uint16_t *x = a.x + (size_t)m * a.x_stride;
         float *o = xp + (size_t)m * a.K;
-        double ss = 0;
-        for (uint32_t b = 0; b < a.K / 32; ++b)
-            for (uint32_t j = 0; j < 32; ++j) {
-                const float v = half_to_float(x[b * 32 + block_k(j)]);
-                o[b * 32 + j] = j < 16 ? v : v * 0.0625f;   // high-nibble weights come out as 16 (q - 8)
-                ss += (double)v * v;
+        __m512d s0 = _mm512_setzero_pd(), s1 = _mm512_setzero_pd();
+        for (uint32_t b = 0; b < a.K / 32; ++b) {
+            const __m512 v0 = _mm512_cvtph_ps(_mm256_loadu_si256(reinterpret_cast<const __m256i *>(x + b * 32)));
+            const __m512 v1 = _mm512_cvtph_ps(_mm256_loadu_si256(reinterpret_cast<const __m256i *>(x + b * 32 + 16)));
+            _mm512_storeu_ps(o + b * 32, _mm512_permutex2var_ps(v0, idx_lo, v1));
+            _mm512_storeu_ps(o + b * 32 + 16, _mm512_mul_ps(_mm512_permutex2var_ps(v0, idx_hi, v1), sixteenth));
+            if (norm) {
+                const __m512d a0 = _mm512_cvtps_pd(_mm512_castps512_ps256(v0)), a1 = _mm512_cvtps_pd(_mm512_extractf32x8_ps(v0, 1));
+                const __m512d b0 = _mm512_cvtps_pd(_mm512_castps512_ps256(v1)), b1 = _mm512_cvtps_pd(_mm512_extractf32x8_ps(v1, 1));
+                s0 = _mm512_fmadd_pd(a0, a0, s0); s1 = _mm512_fmadd_pd(a1, a1, s1);
+                s0 = _mm512_fmadd_pd(b0, b0, s0); s1 = _mm512_fmadd_pd(b1, b1, s1);
             }
+        }
+        const double ss = _mm512_reduce_add_pd(_mm512_add_pd(s0, s1));
         rinv[m] = norm ? 1.0f / std::sqrt((float)(ss / a.K) + a.eps) : 1.0f;
     }
 }
