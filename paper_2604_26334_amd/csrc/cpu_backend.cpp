@@ -174,6 +174,50 @@ PS_AVX512 void tile_dot(const uint8_t *tile, uint32_t nsb, uint32_t ngroups, con
     }
 }
 
+// One token, short rows: all 16 rows of the tile in a single pass, so the tile is read front to
+// back (the four-pass form above touches every fourth cache line per pass).  Per row the blocks are
+// added in the same order as there, so both forms give the same bits.
+PS_AVX512 void tile_dot_one(const uint8_t *tile, uint32_t nsb, uint32_t ngroups, const float *xp, float *acc_out /* [16] */) {
+    const __m512i nib_lo = _mm512_set1_epi32(0x0F), nib_hi = _mm512_set1_epi32(0xF0);
+    const __m512i magic = _mm512_set1_epi32(0x4B000000);
+    const __m512 bias_lo = _mm512_set1_ps(8388608.0f + 8.0f), bias_hi = _mm512_set1_ps(8388608.0f + 128.0f);
+    alignas(64) float scf[64 * 8];
+    __m512 acc[16];
+    for (int i = 0; i < 16; ++i) acc[i] = _mm512_setzero_ps();
+    for (uint32_t g = 0; g < ngroups; ++g) {
+        const uint32_t nsb_g = std::min(8u, nsb - g * 8u);
+        const uint8_t *gbase = tile + (size_t)g * 9u * 1024u;
+        const uint16_t *sc = reinterpret_cast<const uint16_t *>(gbase + (size_t)nsb_g * 1024u);
+        for (int q = 0; q < 32; ++q)
+            _mm512_store_ps(scf + q * 16, _mm512_cvtph_ps(_mm256_loadu_si256(reinterpret_cast<const __m256i *>(sc + q * 16))));
+        for (uint32_t s = 0; s < nsb_g; ++s) {
+            const uint8_t *sbp = gbase + (size_t)s * 1024u;
+            for (int c = 0; c < 4; ++c) {
+                const float *xk = xp + ((size_t)(g * 8u + s) * 4u + c) * 32u;
+                const __m512 xlo = _mm512_loadu_ps(xk), xhi = _mm512_loadu_ps(xk + 16);
+#pragma GCC unroll 16
+                for (int i = 0; i < 16; ++i) {
+                    const int lane = c * 16 + i;
+                    const __m512i v = _mm512_cvtepu8_epi32(_mm_loadu_si128(reinterpret_cast<const __m128i *>(sbp + lane * 16)));
+                    const __m512 wl = _mm512_sub_ps(_mm512_castsi512_ps(_mm512_ternarylogic_epi32(v, nib_lo, magic, 0xEA)), bias_lo);
+                    const __m512 wh = _mm512_sub_ps(_mm512_castsi512_ps(_mm512_ternarylogic_epi32(v, nib_hi, magic, 0xEA)), bias_hi);
+                    const __m512 d = _mm512_set1_ps(scf[lane * 8 + s]);
+                    acc[i] = _mm512_fmadd_ps(_mm512_fmadd_ps(wh, xhi, _mm512_mul_ps(wl, xlo)), d, acc[i]);
+                }
+            }
+        }
+    }
+    for (int i = 0; i < 16; ++i) acc_out[i] = _mm512_reduce_add_ps(acc[i]);
+}
+
+template <int TOK>
+PS_AVX512 inline void tile_dot_any(const uint8_t *tile, uint32_t nsb, uint32_t ngroups, const float *xp, size_t xp_stride, float *acc_out) {
+    // measured on a 16-thread host, one token: K = 2048 tiles (MoE experts) 96 -> 113 GB/s in the
+    // single pass, K = 4096 and 14336 tiles (dense FFN) 180 -> 158 GB/s; K = 768 the same either way
+    if (TOK == 1 && nsb <= 16) tile_dot_one(tile, nsb, ngroups, xp, acc_out);
+    else tile_dot<TOK>(tile, nsb, ngroups, xp, xp_stride, acc_out);
+}
+
 inline float silu(float v) { return v / (1.0f + std::exp(-v)); }
 
 template <int TOK>
@@ -181,8 +225,8 @@ PS_AVX512 void run_unit(const CpuMatArgs &a, uint32_t u, uint32_t m0, const floa
     const bool gu = a.mode == CPU_GATE_UP;
     float g[16 * TOK], up[16 * TOK];
     const uint8_t *t0 = a.W + (size_t)u * (gu ? 2 : 1) * a.tile_bytes;
-    tile_dot<TOK>(t0, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, g);
-    if (gu) tile_dot<TOK>(t0 + a.tile_bytes, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, up);
+    tile_dot_any<TOK>(t0, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, g);
+    if (gu) tile_dot_any<TOK>(t0 + a.tile_bytes, a.nsb, a.ngroups, xp + (size_t)m0 * a.K, a.K, up);
     for (int m = 0; m < TOK; ++m) {
         const size_t row = (size_t)(m0 + m) * a.out_stride + a.out_col0 + (size_t)u * 16u;
         for (int i = 0; i < 16; ++i) {

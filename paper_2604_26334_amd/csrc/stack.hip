@@ -363,16 +363,19 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     std::vector<CpuMatArgs> gu(op.ntasks), dn(op.ntasks);
     std::vector<size_t> scr(op.ntasks + 1, 0);
     float *yrows = reinterpret_cast<float *>(st->host_out);
-    uint32_t row = 0;
+    uint32_t row = 0, nrows = 0;
     uint64_t bytes = 0;
+    for (uint32_t k = 0; k < op.ntasks; ++k) nrows += sc.tasks[op.task0 + k].npairs;
+    if (nrows > P) { set_error("internal: CPU expert pairs exceed the workspace"); return PS_E_STATE; }
+    // result rows [nrows][H] fp32, directly followed by their pair numbers: one upload
+    int32_t *ypairs = reinterpret_cast<int32_t *>(yrows + (size_t)nrows * H);
     for (uint32_t k = 0; k < op.ntasks; ++k) {
         const TaskHost &t = sc.tasks[op.task0 + k];
-        if (row + t.npairs > P) { set_error("internal: CPU expert pairs exceed the workspace"); return PS_E_STATE; }
         for (uint32_t q = 0; q < t.npairs; ++q) {
             const int32_t pair = sc.pairs[t.pair0 + q];
             if (pair < 0 || (uint32_t)pair >= P) { set_error("internal: pair index out of range"); return PS_E_STATE; }
             std::memcpy(st->cpu_xg.data() + (size_t)(row + q) * H, st->host_h + (size_t)(pair / m.top_k) * H, (size_t)H * 2);
-            reinterpret_cast<int32_t *>(yrows + (size_t)P * H)[row + q] = pair;
+            ypairs[row + q] = pair;
         }
         CpuMatArgs a;
         a.W = st->shard_host[t.shard]; a.ntiles = g.gate_up.ntiles; a.tile_bytes = g.gate_up.tile_bytes;
@@ -396,11 +399,9 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     cpu_matmul_many(dn, *st->pool, st->cpu_scratch.data(), scr);   // then the down projections
     st->stats.cpu_ms += now_ms() - t0;
     st->stats.cpu_bytes_step += bytes;
-    // rows, then (at the fixed offset P * H floats) their pair numbers
     uint8_t *land = st->arena + p.ws.cpu_y;
-    PS_HIP(hipMemcpyAsync(land, yrows, (size_t)row * H * 4, hipMemcpyHostToDevice, st->compute));
-    PS_HIP(hipMemcpyAsync(land + (size_t)P * H * 4, yrows + (size_t)P * H, (size_t)row * 4, hipMemcpyHostToDevice, st->compute));
-    PS_HIP(launch_scatter_rows(reinterpret_cast<const float *>(land), reinterpret_cast<const int32_t *>(land + (size_t)P * H * 4), row, H,
+    PS_HIP(hipMemcpyAsync(land, yrows, (size_t)row * H * 4 + (size_t)row * 4, hipMemcpyHostToDevice, st->compute));
+    PS_HIP(launch_scatter_rows(reinterpret_cast<const float *>(land), reinterpret_cast<const int32_t *>(land + (size_t)row * H * 4), row, H,
                                reinterpret_cast<float *>(st->arena + p.ws.y), st->compute));
     st->out_upload_pending = true;
     return PS_OK;

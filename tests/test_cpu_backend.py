@@ -78,3 +78,17 @@ def test_cpu_matmul_argument_checks():
     assert L.ps_cpu_matmul(p, 16, 128, 0, p, 0, 1e-6, None, p, 1) == B.PS_E_ARG
     assert L.ps_cpu_matmul(p, 16, 128, 0, p, 1, 1e-6, None, p, 0) == B.PS_E_ARG
     assert L.ps_cpu_matmul(None, 16, 128, 0, p, 1, 1e-6, None, p, 1) == B.PS_E_ARG
+
+
+@pytest.mark.parametrize("rows,K", [(48, 1024), (32, 2048), (32, 4096)])
+def test_one_token_forms_agree_bit_for_bit(rows, K):
+    """One token takes a single pass over a tile when rows are short (K <= 2048) and the four-pass
+    form otherwise; a token's result must not depend on which form computed it, nor on whether it
+    was computed alone or as one of two tokens (per row the blocks are added in one fixed order)."""
+    sc, cd = S.weight_matrix(95, 0, 0, None, rows, K)
+    packed = B.pack_matrix(sc, cd)
+    x = S.activations(96, 3, 2, K)
+    both = _cpu(packed, rows, K, 1, x, 1e-6, None, 2)
+    for t in range(2):
+        alone = _cpu(packed, rows, K, 1, x[t:t + 1], 1e-6, None, 3)
+        np.testing.assert_array_equal(alone.view(np.uint16)[0], both.view(np.uint16)[t])
