@@ -183,6 +183,8 @@ typedef struct ps_stats {
     uint64_t cpu_bytes_step; /* weight bytes read by the CPU back-end in the last forward           */
     double cpu_ms;      /* host time inside the CPU kernel in the last forward (always valid)       */
     double cpu_wait_ms; /* host time waiting for activations to arrive from the GPU (always valid)  */
+    uint32_t graph_replay; /* 1 if the last forward was one HIP-graph launch (decode mode 1), else 0  */
+    uint32_t reserved;
 } ps_stats;
 
 /* one operation of an executor schedule, as plain data (see ps_schedule_*) */

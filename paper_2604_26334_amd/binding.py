@@ -79,7 +79,8 @@ class ps_stats(C.Structure):
     _fields_ = [("resident_bytes_step", C.c_uint64), ("streamed_bytes_step", C.c_uint64),
                 ("n_copies", C.c_uint32), ("n_kernels", C.c_uint32)] + \
                [(n, C.c_double) for n in ("copy_ms", "compute_ms", "wall_ms", "overlap", "h2d_gbps")] + \
-               [("cpu_bytes_step", C.c_uint64), ("cpu_ms", C.c_double), ("cpu_wait_ms", C.c_double)]
+               [("cpu_bytes_step", C.c_uint64), ("cpu_ms", C.c_double), ("cpu_wait_ms", C.c_double),
+                ("graph_replay", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ps_op_info(C.Structure):

@@ -511,6 +511,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             it = st->graphs.emplace(key, exec).first;
         }
         PS_HIP(hipGraphLaunch(it->second, st->compute));
+        ss.graph_replay = 1;
         for (const Op &op : sc.ops)
             if (!skip_head_op(st, op)) { ss.resident_bytes_step += op.info.bytes; ss.n_kernels++; }
         return PS_OK;

@@ -121,6 +121,7 @@ def test_graph_replay_matches_eager_on_every_replay():
             torch.cuda.synchronize()
             st.forward(x, y)
             st.synchronize()
+            assert st.stats().graph_replay == 1    # the graph path, not a silent launch-per-shard run
             np.testing.assert_array_equal(y.cpu().numpy().view(np.uint16), ref)
         (torch.ones(1 << 20, device="cuda") * 2).sum().item()
     st.close()
@@ -336,6 +337,7 @@ def test_kv_decode_graph_replay_matches_launch_per_shard():
             torch.cuda.synchronize()
             st.forward(xin[t % 2], xout)          # two input buffers: two captured graphs, each replayed
             st.synchronize()
+            assert st.stats().graph_replay == mode    # mode 1 really is the graph path on this stack
             res.append(xout.cpu().numpy().copy())
         outs[mode] = res
         st.close()

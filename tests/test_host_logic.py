@@ -29,6 +29,7 @@ def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.ps_profile) == 8 * (3 + B.PS_NTIERS + 5)
     assert C.sizeof(B.ps_shard_info) == 48
     assert C.sizeof(B.ps_op_info) == 48
+    assert C.sizeof(B.ps_stats) == 96
 
 
 def test_tiers_are_the_papers_set():
