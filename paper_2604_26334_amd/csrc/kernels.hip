@@ -432,15 +432,42 @@ hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float
 // MoE routing: per token the top_k largest fp32 logits (ties to the lower index, listed
 // in descending order) and the softmax over the selected logits.  One wave per token.
 // ------------------------------------------------------------------------------------
+// Wave-wide maximum / minimum, the same value in every lane: the 16 lanes of a row meet through DPP
+// row operations (no LDS traffic), the four rows through four lane reads.
+__device__ __forceinline__ int dpp_i(int v, int ctrl) {
+    switch (ctrl) {
+        case 0: return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm 1,0,3,2
+        case 1: return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm 2,3,0,1
+        case 2: return __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);   // row_half_mirror
+        default: return __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);  // row_mirror
+    }
+}
+__device__ __forceinline__ float wave_max_all(float v) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v = fmaxf(v, __builtin_bit_cast(float, dpp_i(__builtin_bit_cast(int, v), c)));
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ uint32_t wave_min_all(uint32_t v) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v = min(v, (uint32_t)dpp_i((int)v, c));
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    return min(min(r0, r1), min(r2, r3));
+}
+
+template <int NR>   // 64 * NR >= E
 __global__ __launch_bounds__(256) void route_kernel(const float *logits, uint32_t M, uint32_t E, uint32_t top_k,
                                                     int32_t *idx, float *w) {
     const uint32_t m = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (m >= M) return;
     const float *l = logits + (size_t)m * E;
-    float v[16];  // E <= 1024
+    float v[NR];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
+    for (int r = 0; r < NR; ++r) {
         const uint32_t e = r * 64 + lane;
         v[r] = e < E ? l[e] : -INFINITY;
     }
@@ -450,17 +477,15 @@ __global__ __launch_bounds__(256) void route_kernel(const float *logits, uint32_
         float best = -INFINITY;
         uint32_t be = 0xFFFFFFFFu;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < NR; ++r) {
             const uint32_t e = r * 64 + lane;
             if (e < E && !((taken >> r) & 1u) && (be == 0xFFFFFFFFu || v[r] > best)) { best = v[r]; be = e; }
         }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            const float ob = __shfl_xor(best, o, 64);
-            const uint32_t oe = __shfl_xor(be, o, 64);
-            const bool take = (oe != 0xFFFFFFFFu) && (be == 0xFFFFFFFFu || ob > best || (ob == best && oe < be));
-            if (take) { best = ob; be = oe; }
-        }
+        // the largest value in the wave, then the lowest index among the lanes that hold it
+        // (a lane with nothing left holds -inf and the index 0xFFFFFFFF, which never wins)
+        const float top = wave_max_all(best);
+        be = wave_min_all(best == top ? be : 0xFFFFFFFFu);
+        best = top;
         if ((be & 63u) == (uint32_t)lane) taken |= 1u << (be >> 6);
         if (j == 0) lmax = best;
         if ((uint32_t)lane == j) sel = best;
@@ -473,7 +498,10 @@ __global__ __launch_bounds__(256) void route_kernel(const float *logits, uint32_
 
 hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
                         hipStream_t st) {
-    hipLaunchKernelGGL(route_kernel, dim3((M + 3) / 4), dim3(256), 0, st, logits, M, E, top_k, idx, w);
+    if (E > 1024 || top_k == 0 || top_k > 64 || top_k > E) return hipErrorInvalidValue;
+    if (E <= 128) hipLaunchKernelGGL(route_kernel<2>, dim3((M + 3) / 4), dim3(256), 0, st, logits, M, E, top_k, idx, w);
+    else if (E <= 256) hipLaunchKernelGGL(route_kernel<4>, dim3((M + 3) / 4), dim3(256), 0, st, logits, M, E, top_k, idx, w);
+    else hipLaunchKernelGGL(route_kernel<16>, dim3((M + 3) / 4), dim3(256), 0, st, logits, M, E, top_k, idx, w);
     return hipGetLastError();
 }
 

@@ -278,8 +278,7 @@ static void estimate(ps_plan &p, const float *freq) {
             if (!p.shards[j].resident) streamed += (double)p.shards[j].bytes * prob[j];
             ++j;
         }
-        // (two passes over the worker pool per layer: every expert's gate/up, then every down)
-        if (experts && t_cpu > 0) t_cpu += 2.0 * p.prof.cpu_sync_us * 1e-3;
+        if (experts && t_cpu > 0) t_cpu += p.prof.cpu_sync_us * 1e-3;
         t += std::max(t_gpu, t_cpu);
         i = j;
     }
