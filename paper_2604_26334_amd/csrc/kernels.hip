@@ -79,10 +79,41 @@ __device__ __forceinline__ float sumsq8(uint4 v) {
     return s;
 }
 
+// sum over the wave, the same value in every lane: the 16 lanes of a row meet through DPP row
+// operations, the four rows through four lane reads (no LDS permutes, whose six dependent round
+// trips cost a wave several hundred cycles)
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));   // quad_perm 1,0,3,2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));   // quad_perm 2,3,0,1
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));  // row_mirror
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// Lanes l, l ^ 16, l ^ 32, l ^ 48 (one column of the wave's four rows) meet, the result in all four:
+// (row 0 + row 1) + (row 2 + row 3), by the row-swap instructions of gfx950 (vector ALU, no LDS
+// permute).  v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its
+// second, v_permlane32_swap the upper half of the first with the lower half of the second; with both
+// operands the same value, the two results are the two partners of every lane (lane layout checked
+// on the hardware with lane numbers as data).
+template <bool MAX = false>
+__device__ __forceinline__ float rows4_meet(float v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // written as instructions: the two operands are exchanged in place, so they are two registers
+    // holding the same value (this compiler's builtin for the swap loses its second result when
+    // the two results are combined, checked on the hardware); s_nop covers the write-to-swap
+    // hazard the compiler would otherwise pad
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    float y = MAX ? fmaxf(a, b) : a + b, z = y;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(y), "+v"(z));
+    return MAX ? fmaxf(y, z) : y + z;
+#else
     return v;
+#endif
 }
 
 // fp32 -> fp16 with the rounding kept as its own step: the value passes through an opaque
@@ -279,8 +310,7 @@ __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, con
             // the 4 lanes of a row (c = 0..3) meet; then the group partial joins the others in group order
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                gacc[t] += __shfl_xor(gacc[t], 16, 64);
-                gacc[t] += __shfl_xor(gacc[t], 32, 64);
+                gacc[t] = rows4_meet<false>(gacc[t]);
             }
             float gss = 0.f;
             if (NORM) gss = wave_sum(sumsq8(cur.xa) + sumsq8(cur.xb));
@@ -615,8 +645,9 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
             for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
         }
     }
-    // the 4 position groups of a wave meet; then the workgroup's waves through LDS, rescaled to the
-    // chunk maximum, in fixed order
+    // the 4 position groups of a wave meet (36 independent values: LDS permutes, which pipeline, measured
+    // faster here than the in-register row swaps the one-token GEMV uses for its one or two values);
+    // then the workgroup's waves through LDS, rescaled to the chunk maximum, in fixed order
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         l[h] += __shfl_xor(l[h], 16, 64);
