@@ -717,11 +717,7 @@ hipError_t launch_attn_decode(const AttnArgs &a, hipStream_t st) {
 constexpr uint32_t kAttnMaxChunks = 8192;   // 1M positions
 
 __device__ __forceinline__ float block512_reduce(float v, float *scratch, bool is_max) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        const float u = __shfl_xor(v, o, 64);
-        v = is_max ? fmaxf(v, u) : v + u;
-    }
+    v = is_max ? wave_max_all(v) : wave_sum(v);
     __syncthreads();                       // scratch may still be read from the previous reduction
     if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
