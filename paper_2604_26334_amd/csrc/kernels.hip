@@ -736,28 +736,48 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const float *part, ui
     __shared__ float osum[4][128];
     const uint32_t h = blockIdx.x, tid = threadIdx.x, d = tid & 127, grp = tid >> 7;
     const uint32_t group = n_q / n_kv, g = h / group;
-    const float kn = __half2float(qkv[(size_t)(n_q + g) * 128 + d]);
-    const float vn = __half2float(qkv[(size_t)(n_q + n_kv + g) * 128 + d]);
-    // the token's own score (every group of 128 threads holds the 128 products once)
-    const float s_self = block512_reduce(grp == 0 ? __half2float(qkv[(size_t)h * 128 + d]) * kn : 0.f, scratch, false) *
-                         0.08838834764831845f;
     const uint32_t nchunks = (ctx + kAttnPos - 1) / kAttnPos;
     const float *ph = part + (size_t)h * chunk_cap * 130;
-    float mloc = s_self;
-    for (uint32_t c = tid; c < nchunks; c += 512) mloc = fmaxf(mloc, ph[(size_t)c * 130]);
-    const float mx = block512_reduce(mloc, scratch, true);
-    float lloc = 0.f;
-    for (uint32_t c = tid; c < nchunks; c += 512) {
-        const float w = __expf(ph[(size_t)c * 130] - mx);
-        wbuf[c] = w;
-        lloc = fmaf(w, ph[(size_t)c * 130 + 1], lloc);
-    }
-    const float w_self = __expf(s_self - mx);
-    const float L = block512_reduce(lloc, scratch, false) + w_self;   // also publishes wbuf
     // quarter q of the chunks: [q * per, min((q + 1) * per, nchunks))
     const uint32_t per = (nchunks + 3) / 4, c1 = min(nchunks, (grp + 1) * per);
     uint32_t c = min(nchunks, grp * per);
+    // Everything that does not depend on a reduction is requested now, in one round trip: the
+    // token's own rows, this thread's first chunk maximum and weight sum, and the first 16 partial
+    // sums of its quarter (the partials were written by other XCDs a moment ago, so each dependent
+    // read is a trip to the memory-side cache; the order of the arithmetic below is unchanged).
+    const float kn = __half2float(qkv[(size_t)(n_q + g) * 128 + d]);
+    const float vn = __half2float(qkv[(size_t)(n_q + n_kv + g) * 128 + d]);
+    const float qd = grp == 0 ? __half2float(qkv[(size_t)h * 128 + d]) : 0.f;
+    const bool mine = tid < nchunks, first16 = c + 16 <= c1;
+    float m0 = 0.f, l0 = 0.f, v0[16];
+    if (mine) { m0 = ph[(size_t)tid * 130]; l0 = ph[(size_t)tid * 130 + 1]; }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v0[u] = first16 ? ph[(size_t)(c + u) * 130 + 2 + d] : 0.f;
+    // the token's own score (every group of 128 threads holds the 128 products once)
+    const float s_self = block512_reduce(grp == 0 ? qd * kn : 0.f, scratch, false) * 0.08838834764831845f;
+    float mloc = s_self;
+    if (mine) mloc = fmaxf(mloc, m0);
+    for (uint32_t cc = tid + 512; cc < nchunks; cc += 512) mloc = fmaxf(mloc, ph[(size_t)cc * 130]);
+    const float mx = block512_reduce(mloc, scratch, true);
+    float lloc = 0.f;
+    if (mine) {
+        const float w = __expf(m0 - mx);
+        wbuf[tid] = w;
+        lloc = fmaf(w, l0, lloc);
+    }
+    for (uint32_t cc = tid + 512; cc < nchunks; cc += 512) {
+        const float w = __expf(ph[(size_t)cc * 130] - mx);
+        wbuf[cc] = w;
+        lloc = fmaf(w, ph[(size_t)cc * 130 + 1], lloc);
+    }
+    const float w_self = __expf(s_self - mx);
+    const float L = block512_reduce(lloc, scratch, false) + w_self;   // also publishes wbuf
     float o = 0.f;
+    if (first16) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) o = fmaf(wbuf[c + u], v0[u], o);
+        c += 16;
+    }
     for (; c + 16 <= c1; c += 16) {
         float v[16];
 #pragma unroll
