@@ -345,3 +345,39 @@ def test_kv_decode_graph_replay_matches_launch_per_shard():
     for t, (a, b) in enumerate(zip(outs[0], outs[1])):
         assert np.isfinite(a.astype(np.float64)).all()
         np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16), err_msg="step %d" % t)
+
+
+@pytest.mark.parametrize("n_experts,top_k", [(48, 6), (200, 8), (1024, 8)])
+def test_routing_kernel_indices_and_weights_with_ties(n_experts, top_k):
+    """The routing step on its own, read back from the workspace after a one-layer MoE forward: the
+    top_k largest logits per token, ties to the lower expert index, listed in descending order,
+    and the softmax over them.  Logits are drawn from a handful of values, so ties are everywhere;
+    the three expert counts take the three register shapes of the kernel (up to 128, 256, 1024)."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    M = 5
+    cfg = dict(Hn.small_moe_cfg(1), hidden=128, n_q_heads=1, n_kv_heads=1, n_experts=n_experts, top_k=top_k, expert_inter=128)
+    W = Hn.WeightCache(cfg, 23, keep=False)
+    rng = np.random.default_rng(n_experts)
+    lg = rng.integers(-3, 4, size=(1, M, n_experts)).astype(np.float32) * 0.5
+    lg[0, 1, :] = 0.25                    # one token with every logit equal: experts 0 .. top_k-1
+    lg[0, 2, -1] = 9.0                    # the largest in the last position
+    wb, ws = Hn.total_weight_bytes(cfg)
+    plan = B.Plan(cfg, wb + ws + (4 << 20), M)
+    st = B.Stack(plan)
+    for kind, expert, N, K in S.matrix_shapes(cfg):
+        st.load_matrix(0, kind, expert, *W(0, kind, expert))
+    x = torch.from_numpy(S.activations(23, 0, M, cfg["hidden"])).to(st.device)
+    y = torch.empty_like(x)
+    st.forward(x, y, lg)
+    st.synchronize()
+    idx = st.debug_buffer(3, np.int32, (M, top_k)).copy()
+    w = st.debug_buffer(4, np.float32, (M, top_k)).copy()
+    st.close()
+    plan.close()
+    ref_idx, ref_w = O.route_topk(lg[0], top_k)
+    np.testing.assert_array_equal(idx, ref_idx)
+    np.testing.assert_array_equal(idx[1], np.arange(top_k))
+    assert idx[2, 0] == n_experts - 1
+    np.testing.assert_allclose(w, ref_w, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(w.sum(1), 1.0, rtol=1e-6)
