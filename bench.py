@@ -358,7 +358,7 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
     ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv,head,plans",
-                    help="further legs: batch64 (config 5), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
+                    help="further legs: batch64 (config 5, plus 4 and 16 tokens), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
                          "kv (decode over a 16K-position KV cache), head (decode with a 128256-row output head), "
                          "plans (GPU-only / static / dynamic plan and HeuristicSplit's pick at 2 GB)")
     ap.add_argument("--measure-profile", type=int, default=1)
@@ -476,6 +476,11 @@ def main():
     fresh()
     if "batch64" in args.extra and args.layers == 32:
         extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128)
+        fresh()
+        # the other batch sizes of the paper's batching table (1 is the headline leg)
+        extra["batched_decode_4"] = batched_leg(B, S, torch, cfg, seed, prof, 4, [4e9], 128)
+        fresh()
+        extra["batched_decode_16"] = batched_leg(B, S, torch, cfg, seed, prof, 16, [4e9], 128)
     fresh()
     if "tiers" in args.extra and args.layers == 32:
         extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
