@@ -461,8 +461,11 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
  * graph (kernel nodes only) and replayed; with a KV cache the context length then travels in a
  * device word set before each replay, and the attention launch covers every chunk the cache can
  * hold (workgroups past the context leave at once).  Order and arithmetic are unchanged
- * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  Not to be called
- * while a forward is in flight. */
+ * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  2: mode 0, except
+ * that in a forward of 2..64 tokens the RMS factor of a hidden-state row always comes from a launch
+ * of its own; in modes 0 and 1 the epilogue of an O or down matrix that one launch covers whole
+ * and that is summed from split-K planes leaves the factor itself (same bits: the test of that
+ * claim is what mode 2 is for).  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
 /* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
  * the copy stream pulls all of them from the pinned pool (one launch per slot fill);

@@ -527,7 +527,7 @@ class Stack:
         _check(lib().ps_stack_set_copy_mode(self.h, 1 if gather else 0))
 
     def set_decode_mode(self, mode):
-        """0: launch per shard, 1: HIP-graph replay (see pshard.h)."""
+        """0: launch per shard, 1: HIP-graph replay, 2: mode 0 with every RMS factor from a launch of its own (see pshard.h)."""
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_set_decode_mode(self.h, int(mode)))
 

@@ -68,6 +68,12 @@ hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts
                                   uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,
                                   uint32_t out_stride, uint32_t out_row0, hipStream_t st);
 hipError_t launch_rinv(const __half *x, uint32_t M, uint32_t H, float eps, float *rinv, hipStream_t st);
+// residual epilogue over whole rows of the hidden state (ncols == out_stride == H, first column 0,
+// at most 8 planes) that also writes the RMS factor of each row it stores, bit-identical to
+// launch_splitk_epilogue(GEMM_RESID, ...) followed by launch_rinv(out, ...)
+hipError_t launch_splitk_epilogue_resid_rinv(const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
+                                             uint32_t H, const __half *res, __half *out, float eps, float *rinv,
+                                             hipStream_t st);
 hipError_t launch_route(const float *logits, uint32_t M, uint32_t E, uint32_t top_k, int32_t *idx, float *w,
                         hipStream_t st);
 // Decode attention over a KV cache, one new token.  A cache shard of one kv head is K rows

@@ -1303,6 +1303,73 @@ hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts
 }
 
 // ------------------------------------------------------------------------------------
+// Split-K epilogue of a residual matrix whose launch covers whole rows of the hidden state
+// (out = res + sum of the planes), with the RMS factor of the row it has just written: one
+// workgroup per token.  Thread t owns the 8-column chunks t, t + 256, ... exactly as in
+// rinv_kernel, squares the fp16 values it stores and reduces in the same order, so rinv[m] has the
+// bits rinv_kernel would give on the stored row, and the separate launch can be left out.
+// Planes past `parts` are not read (the load is redirected to the last plane and discarded by a
+// select, so the loads carry no branch).
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void splitk_epilogue_resid_rinv_kernel(const float *partial, uint32_t parts,
+                                                                         uint32_t part_stride, uint32_t H,
+                                                                         const __half *res, __half *out, float eps,
+                                                                         float *rinv) {
+    __shared__ float part[4];
+    const uint32_t m = blockIdx.x, nq = H / 8;
+    const float *prow = partial + (size_t)m * H;
+    float ss = 0.f;
+    for (uint32_t q = threadIdx.x; q < nq; q += 256) {
+        float4 a[8][2];
+#pragma unroll
+        for (uint32_t p = 0; p < 8; ++p) {
+            const float *src = prow + (size_t)(p < parts ? p : parts - 1) * part_stride + q * 8;
+            a[p][0] = *reinterpret_cast<const float4 *>(src);
+            a[p][1] = *reinterpret_cast<const float4 *>(src + 4);
+        }
+        uint4 rv = uint4{0u, 0u, 0u, 0u};
+        if (res) rv = *reinterpret_cast<const uint4 *>(res + (size_t)m * H + q * 8);
+        float r[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (uint32_t p = 0; p < 8; ++p) {
+            const bool on = p < parts;   // adding +0 leaves a sum that started at +0 unchanged
+            r[0] += on ? a[p][0].x : 0.f; r[1] += on ? a[p][0].y : 0.f;
+            r[2] += on ? a[p][0].z : 0.f; r[3] += on ? a[p][0].w : 0.f;
+            r[4] += on ? a[p][1].x : 0.f; r[5] += on ? a[p][1].y : 0.f;
+            r[6] += on ? a[p][1].z : 0.f; r[7] += on ? a[p][1].w : 0.f;
+        }
+        if (res) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = half_of(rv, e) + r[e];
+        }
+        uint32_t d[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint16_t lo = __builtin_bit_cast(uint16_t, to_half(r[2 * e]));
+            const uint16_t hi = __builtin_bit_cast(uint16_t, to_half(r[2 * e + 1]));
+            d[e] = (uint32_t)lo | ((uint32_t)hi << 16);
+        }
+        const uint4 o = uint4{d[0], d[1], d[2], d[3]};
+        *reinterpret_cast<uint4 *>(out + (size_t)m * H + q * 8) = o;
+        ss += sumsq8(o);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) rinv[m] = rsqrtf((((part[0] + part[1]) + part[2]) + part[3]) / (float)H + eps);
+}
+
+hipError_t launch_splitk_epilogue_resid_rinv(const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
+                                             uint32_t H, const __half *res, __half *out, float eps, float *rinv,
+                                             hipStream_t st) {
+    if (M == 0) return hipSuccess;
+    if (parts == 0 || parts > 8 || H % 8 || part_stride % 4 || !partial || !out || !rinv) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(splitk_epilogue_resid_rinv_kernel, dim3(M), dim3(256), 0, st, partial, parts, part_stride, H, res,
+                       out, eps, rinv);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
 // Lane-layout probe for v_mfma_f32_16x16x32_f16 (in-bounds, integer-valued inputs):
 // A[i][k] = 1 if (i, k) == (pi, pk) else 0, B[k][j] = 1 if (k, j) == (pk, pj): the single
 // non-zero of C tells which lane/register holds C[pi][pj] under the layout assumed above.

@@ -68,6 +68,8 @@ struct ps_stack {
     bool step_pending = false;
     bool kv_copied = false;                   // some kv shard is not resident: the copy stream reads appended rows
     bool profiling = false;
+    bool own_rinv_launch = false;             // decode mode 2: RMS factors always from rinv_kernel
+    const void *rinv_of = nullptr;            // rows whose RMS factors the last residual epilogue left in the workspace
     std::vector<hipEvent_t> prof_ev;          // 2 per op of the last profiled forward
     std::vector<uint8_t> prof_is_copy;
     std::vector<double> prof_start, prof_dur;
@@ -216,15 +218,26 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         pa.out_f32 = partial; pa.out = nullptr; pa.out_stride = ncols; pa.out_row0 = 0;
         pa.sb_per_part = per; pa.part_stride = M * ncols;
         PS_HIP(launch_gemm(GEMM_F32, pa, 0, M, cs));
+        if (mode == GEMM_RESID && ncols == H && a.out_row0 == 0 && a.out_stride == H && !st->own_rinv_launch) {
+            // the launch covers whole rows of the hidden state: its epilogue also leaves their RMS
+            // factors (the bits rinv_kernel gives), and the PS_K_RINV op that follows is skipped
+            PS_HIP(launch_splitk_epilogue_resid_rinv(partial, (mg.nsb + per - 1) / per, pa.part_stride, M, H, a.res, a.out,
+                                                     m.rms_eps, rinv, cs));
+            st->rinv_of = a.out;
+            return PS_OK;
+        }
         PS_HIP(launch_splitk_epilogue(mode, partial, (mg.nsb + per - 1) / per, pa.part_stride, M, ncols, rinv, a.res,
                                       a.out, a.out_stride, a.out_row0, cs));
         return PS_OK;
     };
     switch (op.info.kernel) {
-        case PS_K_RINV:
-            if (op.info.shard0 == 2) PS_HIP(launch_rinv(x_out, M, H, m.rms_eps, rinv, cs));   // output head
-            else PS_HIP(launch_rinv(op.info.shard0 == 0 && g.has_attn ? xin : hbuf, M, H, m.rms_eps, rinv, cs));
+        case PS_K_RINV: {
+            const __half *rows = op.info.shard0 == 2 ? x_out : op.info.shard0 == 0 && g.has_attn ? xin : hbuf;   // 2: output head
+            const bool have = st->rinv_of == rows;
+            st->rinv_of = nullptr;
+            if (!have) PS_HIP(launch_rinv(rows, M, H, m.rms_eps, rinv, cs));
             return PS_OK;
+        }
         case PS_K_OUT: {   // every token's logits (head_rows == M > 1)
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.head);
@@ -477,6 +490,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
         st->prof_is_copy.assign(sc.ops.size(), 0);
     }
     st->prof_valid = false;
+    st->rinv_of = nullptr;
     ps_stats &ss = st->stats;
     ss = ps_stats{};
     // graph mode with a KV cache: the context length travels in device memory, where the attention
@@ -567,6 +581,8 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
         } else {
             if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
             if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->compute));
+            // RMS factors left by a residual epilogue are good only for the PS_K_RINV op right behind it
+            if (!(o.type == PS_OP_KERNEL && o.kernel == PS_K_RINV)) st->rinv_of = nullptr;
             int32_t rc = o.type == PS_OP_FETCH ? issue_fetch(st, op, x_in, x_out)
                          : o.type == PS_OP_CPU ? issue_cpu(st, sc, op, x_out) : issue_kernel(st, sc, op, x_in, x_out);
             if (rc) return rc;
@@ -907,10 +923,11 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
 
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
-    if (mode < 0 || mode > 1) { ps::set_error("decode mode must be 0 or 1"); return PS_E_ARG; }
+    if (mode < 0 || mode > 2) { ps::set_error("decode mode must be 0, 1 or 2"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
     st->use_graph = mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
+    st->own_rinv_launch = mode == 2;
     return PS_OK;
 }
 

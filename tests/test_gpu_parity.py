@@ -92,6 +92,41 @@ def test_small_moe(M):
     _check(cfg, 3, M, _budgets(cfg, M, [1.0, 0.6, 0.35]), logits=lg)
 
 
+@pytest.mark.parametrize("M", [2, 16, 37, 64])
+@pytest.mark.parametrize("moe", [False, True])
+def test_rms_factor_left_by_the_residual_epilogue_matches_its_own_launch(M, moe):
+    """2..64 tokens, every shard resident: the split-K epilogue of O and down leaves the RMS factor of
+    the rows it stores (modes 0/1) instead of a launch of its own (mode 2).  Same bits, fewer launches,
+    and the second forward in a row (a smaller activation scale) agrees as well."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = Hn.small_moe_cfg(2) if moe else Hn.small_dense_cfg(2)
+    W = Hn.WeightCache(cfg, 11)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    plan = B.Plan(cfg, wb + B.Plan(cfg, 1 << 62, M).summary().workspace_bytes + (1 << 20), M)
+    st = B.Stack(plan)
+    for layer in range(cfg["n_layers"]):
+        for kind, expert, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, kind, expert, *W(layer, kind, expert))
+    lg = S.router_logits(11, 0, cfg["n_layers"], M, cfg["n_experts"]) if moe else None
+    xs = [torch.from_numpy(S.activations(11, 0, M, cfg["hidden"])).cuda()]
+    xs.append((xs[0] * 0.25).contiguous())
+    res, launches = {}, {}
+    for mode in (2, 0):
+        st.set_decode_mode(mode)
+        outs = []
+        for x in xs:
+            y = torch.empty_like(x)
+            st.forward(x, y, lg)
+            st.synchronize()
+            outs.append(y.cpu().numpy().view(np.uint16))
+        res[mode], launches[mode] = outs, st.stats().n_kernels
+    _say("M", M, "moe", moe, "kernel ops", launches)
+    for a, b in zip(res[0], res[2]):
+        np.testing.assert_array_equal(a, b)
+    st.close()
+
+
 def test_graph_replay_matches_eager_on_every_replay():
     """HIP-graph decode mode: several replays, with eager work and synchronisation in between,
     each compared bit for bit with the eager launch-per-shard result."""
