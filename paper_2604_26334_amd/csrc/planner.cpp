@@ -95,15 +95,17 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
 uint32_t gemm_sb_per_part(const MatGeom &mg, uint32_t M) {
     if (M < 2 || M > 64) return 0;
     // batched decode: with few tokens a matrix has too few 8-tile workgroups to fill 256 CUs, so K is
-    // split into at most 8 parts.  Measured on the 8B shapes: a matrix whose workgroups already fill
-    // 7/8 of the CUs is faster unsplit (gate/up, 224 workgroups: one launch instead of GEMM + plane
-    // sum, 64 tokens 2.74 -> 2.48 ms/step); the others are split until about 256 workgroups exist,
-    // 192 above 32 tokens, where a workgroup's step is long enough that the planes' traffic costs
-    // more than the idle CUs (2.48 -> 2.43 ms/step; at 4 and 16 tokens 192 is 3 % and 1 % slower)
+    // split into at most 8 parts.  Measured on the 8B shapes at 4, 16 and 64 tokens: a matrix whose
+    // workgroups already fill 7/8 of the CUs is faster unsplit (gate/up, 224 workgroups: one launch
+    // instead of GEMM + plane sum); the others take as many parts as still give at most one
+    // workgroup per CU, and parts of equal length win over one part more (QKV, 48 workgroups x 32
+    // super-blocks: 4 x 8 beats 5 parts of 7,7,7,7,4 and 6 of 6,..,2; O and down: 8 even parts)
     const uint32_t wgs = (mg.ntiles + 7) / 8;
     if (wgs * 8 >= 256 * 7) return 0;
-    const uint32_t target = M > 32 ? 192u : 256u;
-    const uint32_t parts = std::min(std::min(mg.nsb, 8u), (target + wgs - 1) / wgs);
+    const uint32_t pmax = std::min(std::min(mg.nsb, 8u), std::max(1u, 256u / wgs));
+    uint32_t parts = pmax;
+    for (uint32_t d = pmax; 2 * d > pmax; --d)
+        if (mg.nsb % d == 0) { parts = d; break; }
     if (parts <= 1) return 0;
     return (mg.nsb + parts - 1) / parts;
 }
