@@ -1005,11 +1005,13 @@ int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, doubl
         if (r == 1) { if (hipEventRecord(e0, st->compute) != hipSuccess) rc = PS_E_HIP; n = 0; }
         for (const ps::Op &op : st->dense_sched.ops) {
             if (op.info.type != PS_OP_KERNEL || op.info.kernel != kernel || op.info.slot >= 0) continue;
+            st->rinv_of = nullptr;   // timed in isolation: every launch is issued
             rc = issue_kernel(st, st->dense_sched, op, xin, xout);
             if (rc) break;
             ++n;
         }
     }
+    st->rinv_of = nullptr;
     float ms = 0;
     if (rc == PS_OK && (hipEventRecord(e1, st->compute) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
                         hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) {
