@@ -1,6 +1,6 @@
 """Seeded sweep on the GPU: random small models (dense / MoE, with or without attention, residual,
 output head), budgets, token counts and plan kinds, each forward against the CPU oracle at
-max|err| / max|ref| <= 5e-3."""
+max|err| / max|ref| <= 5e-3, both the oracle that rounds where the GPU stores fp16 and the pure fp64 one."""
 import numpy as np
 import pytest
 
@@ -46,6 +46,8 @@ def test_random_models_match_the_oracle(seed):
         lg = S.router_logits(wseed, 0, cfg["n_layers"], M, cfg["n_experts"]) if cfg["n_experts"] else None
         ref_x = O.stack_forward(x, cfg, W, logits=lg, mirror=True)
         ref_l = O.output_head(ref_x, cfg, head, mirror=True) if head else None
+        pure_x = O.stack_forward(x, cfg, W, logits=lg, mirror=False)      # the plain fp64 definition
+        pure_l = O.output_head(pure_x, cfg, head, mirror=False) if head else None
         full = B.Plan(cfg, 1 << 40, M).summary()
         frac = float(rng.choice([0.1, 0.3, 0.6, 1.1]))
         budget = full.workspace_bytes + int(full.weight_bytes * frac) + (1 << 16)
@@ -73,9 +75,12 @@ def test_random_models_match_the_oracle(seed):
             s = plan.summary()
             e_x = Hn.rel_err(xout.cpu().numpy(), ref_x)
             e_l = Hn.rel_err(lo.cpu().numpy(), ref_l) if head else 0.0
+            p_x = Hn.rel_err(xout.cpu().numpy(), pure_x)
+            p_l = Hn.rel_err(lo.cpu().numpy(), pure_l) if head else 0.0
             print("  seed %d case %d kind %d: L%d H%d %s M%d frac %.1f pinned %d streamed %d cpu %d  err %.2e %.2e" % (
                 seed, case, kind, cfg["n_layers"], cfg["hidden"], "moe" if cfg["n_experts"] else "dense", M, frac,
                 s.resident_bytes, s.streamed_bytes, s.cpu_bytes, e_x, e_l), flush=True)
             assert e_x <= TOL and e_l <= TOL, (cfg, M, budget, kind)
+            assert p_x <= TOL and p_l <= TOL, (cfg, M, budget, kind, p_x, p_l)
             st.close()
             plan.close()

@@ -77,6 +77,8 @@ def test_output_head_logits_match_the_oracle(case):
     x = S.activations(seed, 0, M, cfg["hidden"])
     ref_x = O.stack_forward(x, cfg, W, logits=lg, mirror=True)
     ref_l = O.output_head(ref_x, cfg, head, mirror=True)
+    pure_x = O.stack_forward(x, cfg, W, logits=lg, mirror=False)         # the plain fp64 definition
+    pure_l = O.output_head(pure_x, cfg, head, mirror=False)
     requests = [(0, M), (M - 1, 1), (M // 2, 1), (0, 0)] if M > 1 else [(0, 1), (0, 0)]
     first = None
     ran = 0
@@ -89,7 +91,7 @@ def test_output_head_logits_match_the_oracle(case):
         ran += 1
         _say("  %s budget %d head tiles pinned %d streamed %d" % (case, budget, kinds.get(True, 0), kinds.get(False, 0)))
         for (tok, rows), (xo, lo) in zip(requests, res):
-            assert Hn.rel_err(xo, ref_x) <= TOL
+            assert Hn.rel_err(xo, ref_x) <= TOL and Hn.rel_err(xo, pure_x) <= TOL
             if rows == 0:
                 assert (lo == np.float16(7.0)).all()      # the head was left out
                 continue
@@ -99,6 +101,7 @@ def test_output_head_logits_match_the_oracle(case):
             e2e, e1 = Hn.rel_err(lo, want), Hn.rel_err(lo, alone)
             _say("    tokens %d+%d  err end-to-end %.3e  head alone %.3e" % (tok, rows, e2e, e1))
             assert e2e <= TOL and e1 <= TOL, (case, budget, tok, rows, e2e, e1)
+            assert Hn.rel_err(lo, pure_l[tok:tok + rows]) <= TOL
         if first is None:
             first = res
         else:

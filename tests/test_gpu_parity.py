@@ -1,8 +1,9 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the
 same seeded inputs, plus bit-exact invariance of the output to shard placement.
 
-Tolerance (fp16 activations, fp32 accumulation): max|err| / max|ref| <= 5e-3 against the oracle
-that rounds to fp16 where the GPU stores fp16; the pure fp64 oracle is reported alongside."""
+Tolerance (fp16 activations, fp32 accumulation): max|err| / max|ref| <= 5e-3, asserted against BOTH
+forms of the oracle on these few-layer stacks: the pure fp64 definition (no rounding anywhere) and the
+one that rounds to fp16 where the GPU stores fp16."""
 import numpy as np
 import pytest
 
@@ -50,6 +51,7 @@ def _check(cfg, seed, M, budgets, logits=None, tol=TOL):
             info["resident"], info["streamed"], info["stats"].n_copies, info["stats"].n_kernels, e_m, e_p))
         assert np.isfinite(y.astype(np.float64)).all()
         assert e_m <= tol, (b, e_m)
+        assert e_p <= tol, (b, e_p)        # the plain fp64 definition, no rounding anywhere
         outs.append(y)
         if M == 1 and info["streamed"] == 0 and not cfg["n_experts"]:
             # the HIP-graph replay of the same launch sequence must agree bit for bit

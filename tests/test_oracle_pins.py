@@ -276,6 +276,94 @@ def test_mirror_mode_rounds_only_to_fp16_grid_and_stays_close():
     assert np.abs(mir - pure).max() > 0
 
 
+def _r16(v):
+    return v.astype(np.float16).astype(np.float64)
+
+
+def _mirror_rebuild(x, cfg, W, logits=None, drop=None):
+    """The stack with an explicit fp16 store at each point where the device path stores fp16 (after the
+    QKV projection, after O + residual, after SwiGLU, after down + residual or the expert combine) and
+    nowhere else; the point named by `drop` is left unrounded.  Every arithmetic step is one of the
+    separately pinned pieces, called in the order of the definition."""
+    r = lambda name, v: v if name == drop else _r16(v)
+    eps, H = cfg["rms_eps"], cfg["hidden"]
+    x = np.asarray(x, dtype=np.float64)
+    for l in range(cfg["n_layers"]):
+        qkv = r("qkv", O.linear(O.rmsnorm(x, eps), *W(l, S.MAT_QKV, None)))
+        A = O.attn_identity_v(qkv, cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"])
+        h = r("h", O.linear(A, *W(l, S.MAT_O, None)) + x)
+        n = O.rmsnorm(h, eps)
+        if cfg["n_experts"] == 0:
+            s = r("s", O.swiglu(O.linear(n, *W(l, S.MAT_GATE, None)), O.linear(n, *W(l, S.MAT_UP, None))))
+            x = r("out", O.linear(s, *W(l, S.MAT_DOWN, None)) + h)
+            continue
+        idx, w = O.route_topk(logits[l], cfg["top_k"])
+        out = np.zeros_like(h)
+        for m in range(h.shape[0]):
+            for j in range(cfg["top_k"]):
+                e = int(idx[m, j])
+                s = r("s", O.swiglu(O.linear(n[m:m + 1], *W(l, S.MAT_GATE, e)), O.linear(n[m:m + 1], *W(l, S.MAT_UP, e))))
+                out[m] += w[m, j] * O.linear(s, *W(l, S.MAT_DOWN, e))[0]      # expert outputs are not rounded
+            out[m] += h[m]
+        x = r("out", out)
+    return x
+
+
+@pytest.mark.parametrize("kind", ["dense", "moe"])
+def test_mirror_mode_rounds_at_exactly_the_documented_points(kind):
+    """Mirror mode = fp16 stores after QKV, after O + residual, after SwiGLU and after down + residual /
+    the expert combine.  The rebuild with numpy's own fp16 conversion at those points must equal the
+    oracle bit for bit, and leaving any single point out must change the result: so a rounding that the
+    oracle dropped, moved or added would fail here."""
+    if kind == "dense":
+        cfg, lg = dict(_tiny_dense_cfg(), n_layers=2), None
+    else:
+        cfg = dict(_tiny_moe_cfg(), n_layers=1)
+        lg = S.router_logits(24, 0, 1, 3, cfg["n_experts"])
+    W = _weights(24, cfg)
+    x0 = S.activations(24, 0, 3, cfg["hidden"])
+    mir = O.stack_forward(x0, cfg, W, logits=lg, mirror=True)
+    np.testing.assert_array_equal(mir, _mirror_rebuild(x0, cfg, W, lg))
+    for point in ("qkv", "h", "s", "out"):
+        other = _mirror_rebuild(x0, cfg, W, lg, drop=point)
+        assert np.any(other != mir), "dropping the fp16 store after %r changes nothing" % point
+    # and pure mode rounds nowhere
+    pure = O.stack_forward(x0, cfg, W, logits=lg, mirror=False)
+    assert np.any(pure != _r16(pure))
+
+
+def test_mirror_mode_rounding_points_of_the_cached_attention_half():
+    """With a KV cache the stored tensors are the QKV row (hence the appended K and V rows), the
+    attention output and O + residual."""
+    cfg = dict(n_layers=1, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_inter=256, n_experts=0,
+               top_k=0, expert_inter=0, rms_eps=1e-6, no_attn=False, no_residual=False)
+    H, n_q, n_kv, hd = 256, 4, 2, 128
+    qkv_w = S.weight_matrix(5, 0, S.MAT_QKV, None, (n_q + 2 * n_kv) * hd, H)
+    o_w = S.weight_matrix(5, 0, S.MAT_O, None, H, n_q * hd)
+    x = S.activations(5, 0, 1, H)
+    rng = np.random.default_rng(17)
+    cap, ctx = 12, 9
+    Kc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    Vc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    h, kn, vn = O.attn_kv_half(x, cfg, qkv_w, o_w, Kc, Vc, ctx, True)
+
+    def rebuild(drop=None):
+        r = lambda name, v: v if name == drop else _r16(v)
+        y = r("qkv", O.linear(O.rmsnorm(x, cfg["rms_eps"]), *qkv_w))[0]
+        k_new, v_new = y[n_q * hd:(n_q + n_kv) * hd].reshape(n_kv, hd), y[(n_q + n_kv) * hd:].reshape(n_kv, hd)
+        K = np.concatenate([Kc[:, :ctx].astype(np.float64), k_new[:, None, :]], axis=1)
+        V = np.concatenate([Vc[:, :ctx].astype(np.float64), v_new[:, None, :]], axis=1)
+        A = r("attn", O.attn_decode(y[:n_q * hd], K, V, n_q, n_kv, hd))
+        return r("h", O.linear(A[None, :], *o_w) + x.astype(np.float64)), k_new, v_new
+
+    h2, k2, v2 = rebuild()
+    np.testing.assert_array_equal(h, h2)
+    np.testing.assert_array_equal(kn, k2)
+    np.testing.assert_array_equal(vn, v2)
+    for point in ("qkv", "attn", "h"):
+        assert np.any(rebuild(point)[0] != h), point
+
+
 def _tiny_moe_cfg():
     return dict(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn_inter=0,
                 n_experts=8, top_k=3, expert_inter=32, rms_eps=1e-6, no_attn=False, no_residual=False)
@@ -532,3 +620,15 @@ def test_profile_estimate_properties():
     assert t4 == t1
     # work of an operation: one multiply-add per weight and token; 4.5 bits per weight
     assert O.op_work(O.OPK_GEMV, 4, 4096, 4096, 1) == (2.0 * 4096 * 4096, 4096 * 4096 * 0.5625 + 2 * 8192)
+
+
+def test_golden_files_are_what_the_oracle_writes():
+    """tests/golden/make_golden.py (which calls only oracle/) regenerates the stored expected values:
+    the committed files must be exactly its output."""
+    import importlib.util
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    for name, make in mod.FILES.items():
+        assert open(os.path.join(here, name)).read() == make(), name
