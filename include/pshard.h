@@ -244,15 +244,6 @@ uint32_t ps_tier_for_tokens(uint32_t n_tokens);
 /* packed bytes of a [rows][K] matrix in the private device layout (host only) */
 uint64_t ps_packed_bytes(uint32_t rows, uint32_t K);
 
-/* Pack a whole logical matrix (host scales fp16 [rows][K/32], host codes u8 [rows][K]) into
- * the private layout, rows in natural order; out: host, ps_packed_bytes(rows, K) bytes.
- * Layout: 16-row tiles, each a run of scale groups of up to 8 super-blocks (128 k); a
- * super-block is 64 lanes x 16 B, lane c*16+i = block 4*sb+c of row i, dword kk = weights
- * 8*kk..8*kk+7 of the block, weight t in nibble (t>>1) + 4*(t&1); after a group's
- * super-blocks come 64 lanes x 8 fp16 scales (lane c*16+i, entry s = block 4*(8g+s)+c). */
-int32_t ps_pack_matrix(const uint16_t *scales, const uint8_t *codes, uint32_t rows, uint32_t K,
-                       uint8_t *out);
-
 /* Planning phase for one token count (Algorithm 1, PlanningPhase and
  * PinShardsToGPU; GPU-only plan).  Host only, no GPU needed.
  *  model, profile: host, copied.  expert_freq: host [n_layers*n_experts]
@@ -265,16 +256,22 @@ int32_t ps_plan_create(const ps_model_desc *model, uint64_t vram_budget_bytes,
 /* The same for one of the three schedule plans of Section 3 (kind = PS_PLAN_*), or, with
  * PS_PLAN_AUTO, HeuristicSplit: all three are built and the one with the lowest estimated time
  * is returned (its summary lists the three estimates).  Plans Two and Three place the unpinned
- * parts of dense FFN matrices and of the output head on the CPU back-end (attention matrices, KV
- * caches and MoE experts always run on the GPU); Plan Three chooses the CPU share of each such
- * matrix, one value for the whole plan, that minimises the estimate.  They need a profile with
+ * parts of dense FFN matrices and of the output head, and unpinned MoE experts (whole), on the CPU
+ * back-end; attention matrices and KV caches always run on the GPU.  Plan Three chooses the CPU
+ * share (of each such matrix, and of the unpinned experts counted from the cold end of the priority
+ * order), one value for the whole plan, that minimises the estimate.  They need a profile with
  * cpu_gbps > 0 and a host CPU the back-end supports (PS_E_STATE otherwise; PS_PLAN_AUTO then
  * returns Plan One). */
 int32_t ps_plan_create_kind(const ps_model_desc *model, uint64_t vram_budget_bytes,
                             const ps_profile *profile, uint32_t n_tokens,
                             const float *expert_freq, uint32_t kind, ps_plan **out);
+/* What the planning phase decided (Algorithm 1, PlanningPhase: the split of the budget into pinned
+ * region and scratch, DecideScratchVRAMBudget; and Section 3, timing estimation: est_step_ms). */
 int32_t ps_plan_summary(const ps_plan *plan, ps_plan_summary_t *out);
-/* shards are listed in execution (topological) order */
+/* The schedule's shards with their residency marks (Algorithm 1: every sub-layer is added to the
+ * schedule marked Residency = VRAM or SysMem), in execution (topological) order: *n of them,
+ * i < *n. */
+int32_t ps_plan_num_shards(const ps_plan *plan, uint32_t *n);
 int32_t ps_plan_get_shard(const ps_plan *plan, uint32_t i, ps_shard_info *out);
 void ps_plan_destroy(ps_plan *plan);
 
@@ -405,14 +402,16 @@ int32_t ps_plan_create_db(const ps_model_desc *model, uint64_t vram_budget_bytes
                           const ps_profile_db *db, uint32_t n_tokens, const float *expert_freq, uint32_t kind,
                           ps_plan **out);
 
-/* Bind a plan to a VRAM arena (device, 256-byte aligned, arena_bytes >= the
- * plan's budget) and two streams.  Allocates pinned host memory for the
- * streamed shards.  The plan is copied; the arena and streams must outlive the stack. */
+/* Algorithm 1, SetupForSched: install one schedule.  Binds a plan to a VRAM arena (device, 256-byte
+ * aligned, arena_bytes >= the plan's budget: the arena IS the VRAM budget of Section 3, nothing else
+ * is allocated on the device) and two streams.  Allocates pinned host memory for the shards the plan
+ * left in system memory.  The plan is copied; the arena and streams must outlive the stack. */
 int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes,
                         void *compute_stream, void *copy_stream, ps_stack **out);
-/* Pack one logical matrix (host scales fp16 [N][K/32], host codes u8 [N][K]) into
- * every shard that covers it: resident slabs are copied to the arena
- * (synchronous), streamed slabs into the pinned pool.  expert: id or 0xFFFFFFFF. */
+/* Put one logical matrix where the plan placed it (Algorithm 1, PinShardsToGPU: Residency = VRAM
+ * for pinned shards, SysMem for the rest): host scales fp16 [N][K/32] and host codes u8 [N][K] are
+ * packed into every shard that covers the matrix; resident slabs are copied to the arena
+ * (synchronous), the others into the pinned host pool.  expert: id or 0xFFFFFFFF. */
 int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_t expert,
                              const uint16_t *scales, const uint8_t *codes);
 /* KV cache (priority class "KV cache", Section 3 planning phase; only with kv_context > 0).
@@ -439,7 +438,7 @@ int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
  * rows / first_token. */
 int32_t ps_stack_set_logits_out(ps_stack *st, void *logits_dev, uint32_t first_token, uint32_t rows);
 /* The CPU back-end's matrix kernel on its own (host pointers only; for tests and for measuring
- * the CPU rate): `packed` is ps_pack_matrix's image of a [rows][K] matrix; x fp16 [n_tokens][K];
+ * the CPU rate): `packed` is the image ps_pack_matrix (pshard_test.h) makes of a [rows][K] matrix; x fp16 [n_tokens][K];
  * out fp16 [n_tokens][rows] (mode 2: [n_tokens][rows / 2]).  mode 0: out = W RMSNorm(x);
  * mode 1: out = W x + res (res fp16 [n_tokens][rows] or NULL); mode 2: the matrix holds gate and
  * up row-tiles alternately (16 gate rows, 16 up rows, ...) and out = SiLU(g) * u of
@@ -451,52 +450,57 @@ int32_t ps_cpu_matmul(const uint8_t *packed, uint32_t rows, uint32_t K, int32_t 
  * threads, 16).  PS_E_STATE if the plan has no CPU shard. */
 int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads);
 /* One pass over the whole stack (Algorithm 1, RunInTopologicalOrder).
- *  x_in, x_out: device fp16 [n_tokens][hidden], caller-owned, may not alias.
- *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE), NULL for dense.
+ *  x_in, x_out: device fp16 [n_tokens][hidden] (n_tokens = the plan's), caller-owned, may not alias.
+ *  router_logits: host fp32 [n_layers][n_tokens][n_experts] (MoE: required, the host routes with the
+ *  device's rule to know which experts to copy and to build the per-expert token lists), NULL for dense.
+ *  router_logits_dev: NULL, or a device copy of the same array: the routing kernel then reads it in
+ *  place and nothing is uploaded (the two copies must hold the same values; the device copy must stay
+ *  unchanged until the forward has completed).
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
-int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits);
+int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits,
+                         const float *router_logits_dev);
+/* Chunked prefill (Section 3, inference phase: the picked tier's size is the chunk size): n_tokens
+ * rows go through the plan's schedule in ceil(n_tokens / T) trips of T = the plan's token count.  A
+ * last chunk shorter than T runs the same schedule with the same launch shapes over its rows only
+ * (a row's result does not depend on how many rows share its trip; rows past the end are neither
+ * read nor written), so each trip costs at most what the tier's estimate prices.
+ *  x_in, x_out: device fp16 [n_tokens][hidden].  router_logits / router_logits_dev: as for
+ *  ps_stack_forward with [n_layers][n_tokens][n_experts].  last_logits_dev: NULL, or device fp16
+ *  [vocab], 16-byte aligned: the output head runs on the last trip only, for the prompt's last token
+ *  (its copies and kernels are left out of the other trips); the setting of ps_stack_set_logits_out
+ *  is not used and is left as it was.  *trips (may be NULL) receives the number of trips.
+ *  PS_E_STATE for a stack with a KV cache (one token per forward).  Asynchronous like ps_stack_forward. */
+int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, uint32_t n_tokens,
+                                 const float *router_logits, const float *router_logits_dev,
+                                 void *last_logits_dev, uint32_t *trips);
 /* Decode execution mode.  0 (default): one launch per shard.  1: applies when the plan is dense,
  * one token and every shard (KV-cache shards included) resident (otherwise mode 0 runs): the
  * launch-per-shard kernel sequence is captured once per (x_in, x_out, logits) triple into a HIP
  * graph (kernel nodes only) and replayed; with a KV cache the context length then travels in a
  * device word set before each replay, and the attention launch covers every chunk the cache can
  * hold (workgroups past the context leave at once).  Order and arithmetic are unchanged
- * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  2: mode 0, except
- * that in a forward of 2..64 tokens the RMS factor of a hidden-state row always comes from a launch
- * of its own; in modes 0 and 1 the epilogue of an O or down matrix that one launch covers whole
- * and that is summed from split-K planes leaves the factor itself (same bits: the test of that
- * claim is what mode 2 is for).  Not to be called while a forward is in flight. */
+ * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  (A third value
+ * exists for tests only, see pshard_test.h.)  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
 /* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
  * the copy stream pulls all of them from the pinned pool (one launch per slot fill);
  * gather = 0: one hipMemcpyAsync per expert.  Dense slabs always use hipMemcpyAsync. */
 int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather);
-/* Block until both streams are idle; PS_E_HIP if either reports an error. */
+/* Block until both streams are idle, i.e. until the schedule's last shard has run (Algorithm 1,
+ * RunInTopologicalOrder, seen from the caller); PS_E_HIP if either stream reports an error. */
 int32_t ps_stack_sync_check(ps_stack *st);
 /* record per-op timing events in the next forwards (adds event overhead) */
 int32_t ps_stack_set_profiling(ps_stack *st, int32_t on);
-/* blocks until both streams are idle when profiling is on */
+/* Counters of the last forward: bytes read in place, bytes copied H2D, bytes read by the CPU, and,
+ * with profiling on, copy time, compute time and their overlap -- the quantities Section 3's timing
+ * estimation models (a shard's time is the larger of its compute and the concurrent PCIe copy), so
+ * that an estimate can be set beside a measurement.  Blocks until both streams are idle when
+ * profiling is on. */
 int32_t ps_stack_stats(ps_stack *st, ps_stats *out);
 /* start (relative to the first op) and duration in ms of op i of the last profiled forward;
  * ops are numbered as in the schedule of the same plan.  Blocks like ps_stack_stats. */
 int32_t ps_stack_op_time(ps_stack *st, uint32_t i, double *start_ms, double *dur_ms);
-/* Time one kernel kind in isolation (measurement aid): every resident op of kind `kernel`
- * (PS_K_*) of a dense stack is launched back to back, `reps` passes after one warm-up pass,
- * between two events on the compute stream; *avg_launch_ms = elapsed / launches.  The
- * activations are whatever the workspace holds, the outputs go to the workspace.  Blocks. */
-int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, double *avg_launch_ms,
-                             uint32_t *launches);
-/* device pointers into the workspace for inspection by tests (fp16 unless noted):
- * which = 0: QKV [M][qkv_w], 1: h [M][H], 2: s [M][I] or [M*top_k][I_e],
- * 3: route idx int32 [M][top_k], 4: route weights fp32 [M][top_k] */
-int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint64_t *bytes);
 void ps_stack_destroy(ps_stack *st);
-
-/* Diagnostic: one v_mfma_f32_16x16x32_f16 with A = unit at (row pi, k pk) and B = unit at
- * (k pk, column pj); out_dev: device fp32 [64 lanes][4 registers] receives the accumulator.
- * Used by a GPU test to confirm the operand lane layout the GEMM kernel relies on.
- * pi, pj in 0..15, pk in 0..31; asynchronous on stream. */
-int32_t ps_mfma_probe(int32_t pi, int32_t pk, int32_t pj, float *out_dev, void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,5 @@
-"""ctypes binding of libpshard.so: same names as include/pshard.h, argument marshalling only.
+"""ctypes binding of libpshard.so: same names as include/pshard.h (and include/pshard_test.h for the
+test-only entry points), argument marshalling only.
 
 The library must have been built (python -m paper_2604_26334_amd.build, or
 __graft_entry__.build()); loading fails loudly otherwise -- there is no CPU fallback.
@@ -89,7 +90,7 @@ class ps_op_info(C.Structure):
                 ("slot_offset", C.c_uint64), ("bytes", C.c_uint64)]
 
 
-EXPORTS = ["ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
+EXPORTS = ["ps_plan_num_shards", "ps_stack_forward_chunked", "ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
@@ -129,6 +130,8 @@ def lib():
             "ps_stack_set_cpu_threads": [vp, u32],
             "ps_plan_summary": [vp, C.POINTER(ps_plan_summary_t)],
             "ps_plan_get_shard": [vp, u32, C.POINTER(ps_shard_info)],
+            "ps_plan_num_shards": [vp, C.POINTER(u32)],
+            "ps_stack_forward_chunked": [vp, vp, vp, u32, vp, vp, vp, C.POINTER(u32)],
             "ps_schedule_create": [vp, vp, C.POINTER(vp)],
             "ps_schedule_num_ops": [vp, C.POINTER(u32)],
             "ps_schedule_get_op": [vp, u32, C.POINTER(ps_op_info)],
@@ -137,7 +140,7 @@ def lib():
             "ps_profile_measure": [vp, u64, vp, vp, C.POINTER(ps_profile)],
             "ps_stack_create": [vp, vp, u64, vp, vp, C.POINTER(vp)],
             "ps_stack_load_matrix": [vp, u32, u32, u32, vp, vp],
-            "ps_stack_forward": [vp, vp, vp, vp],
+            "ps_stack_forward": [vp, vp, vp, vp, vp],
             "ps_stack_set_profiling": [vp, i32],
             "ps_stack_set_decode_mode": [vp, i32],
             "ps_stack_sync_check": [vp],
@@ -242,9 +245,10 @@ class Plan:
         return s
 
     def shards(self):
-        n = self.summary().n_shards
+        n = C.c_uint32()
+        _check(lib().ps_plan_num_shards(self.h, C.byref(n)))
         out = []
-        for i in range(n):
+        for i in range(n.value):
             s = ps_shard_info()
             _check(lib().ps_plan_get_shard(self.h, i, C.byref(s)))
             out.append(s)
@@ -428,37 +432,27 @@ class TierTable:
             pass
 
 
-def chunked_forward(stack, x_in, x_out, router_logits=None, logits_out=None):
-    """Run n = x_in.shape[0] tokens through a stack planned for T = stack.M tokens as ceil(n / T)
-    trips through its schedule (chunked prefill with the tier size as chunk size).  Only slices and
-    pads: full chunks are passed in place, the last partial chunk goes through zero-padded T-row
-    buffers.  logits_out (fp16 [vocab], models with an output head): the head runs on the last trip
-    only, for the last real token.  Asynchronous on stack.compute like Stack.forward."""
-    torch = stack.torch
-    n, T = int(x_in.shape[0]), stack.M
+def chunked_forward(stack, x_in, x_out, router_logits=None, logits_out=None, router_logits_dev=None):
+    """ps_stack_forward_chunked: n = x_in.shape[0] tokens through a stack planned for T = stack.M tokens
+    in ceil(n / T) trips (chunked prefill with the tier size as chunk size).  logits_out (fp16 [vocab],
+    models with an output head): the head runs on the last trip only, for the last token.
+    Asynchronous on stack.compute like Stack.forward; returns the number of trips."""
+    n = int(x_in.shape[0])
+    assert x_in.dtype == stack.torch.float16 and x_out.dtype == stack.torch.float16
+    assert x_in.is_contiguous() and x_out.is_contiguous()
     assert tuple(x_in.shape) == (n, stack.H) and tuple(x_out.shape) == (n, stack.H)
     lg = None if router_logits is None else np.ascontiguousarray(router_logits, dtype=np.float32)
-    for r0 in range(0, n, T):
-        r1 = min(r0 + T, n)
-        l = None
-        if lg is not None:
-            l = np.zeros((lg.shape[0], T, lg.shape[2]), dtype=np.float32)
-            l[:, :r1 - r0] = lg[:, r0:r1]
-        if logits_out is not None:
-            stack.set_logits_out(logits_out if r1 == n else None, n - 1 - r0 if r1 == n else 0, 1 if r1 == n else 0)
-        if r1 - r0 == T:
-            stack.forward(x_in[r0:r1], x_out[r0:r1], l)
-            continue
-        with torch.cuda.stream(stack.compute):
-            xi = torch.zeros((T, stack.H), dtype=torch.float16, device=stack.device)
-            xo = torch.empty_like(xi)
-            xi[:r1 - r0].copy_(x_in[r0:r1])
-        stack.forward(xi, xo, l)
-        with torch.cuda.stream(stack.compute):
-            x_out[r0:r1].copy_(xo[:r1 - r0])
-            xi.record_stream(stack.compute)
-            xo.record_stream(stack.compute)
-    return (n + T - 1) // T
+    if lg is not None:
+        assert lg.shape[1] == n
+    if logits_out is not None:
+        assert logits_out.dtype == stack.torch.float16 and logits_out.is_contiguous()
+        assert logits_out.numel() == stack.plan.cfg["vocab"]
+    trips = C.c_uint32()
+    with stack.torch.cuda.device(stack.device):
+        _check(lib().ps_stack_forward_chunked(stack.h, x_in.data_ptr(), x_out.data_ptr(), n, _ptr(lg),
+                                              None if router_logits_dev is None else router_logits_dev.data_ptr(),
+                                              None if logits_out is None else logits_out.data_ptr(), C.byref(trips)))
+    return trips.value
 
 
 class Stack:
@@ -510,14 +504,20 @@ class Stack:
             assert logits.numel() == rows * self.plan.cfg["vocab"]
         _check(lib().ps_stack_set_logits_out(self.h, logits.data_ptr() if rows else None, int(first_token), int(rows)))
 
-    def forward(self, x_in, x_out, router_logits=None):
-        """x_in, x_out: torch fp16 CUDA tensors [M][H]; asynchronous on self.compute."""
+    def forward(self, x_in, x_out, router_logits=None, router_logits_dev=None):
+        """x_in, x_out: torch fp16 CUDA tensors [M][H]; asynchronous on self.compute.
+        router_logits_dev: optional torch fp32 CUDA tensor holding the same values as router_logits."""
         assert x_in.dtype == self.torch.float16 and x_out.dtype == self.torch.float16
         assert x_in.is_contiguous() and x_out.is_contiguous()
         assert tuple(x_in.shape) == (self.M, self.H) and tuple(x_out.shape) == (self.M, self.H)
         lg = None if router_logits is None else np.ascontiguousarray(router_logits, dtype=np.float32)
+        ld = None
+        if router_logits_dev is not None:
+            assert router_logits_dev.dtype == self.torch.float32 and router_logits_dev.is_contiguous()
+            assert lg is not None and tuple(router_logits_dev.shape) == lg.shape
+            ld = router_logits_dev.data_ptr()
         with self.torch.cuda.device(self.device):
-            _check(lib().ps_stack_forward(self.h, x_in.data_ptr(), x_out.data_ptr(), _ptr(lg)))
+            _check(lib().ps_stack_forward(self.h, x_in.data_ptr(), x_out.data_ptr(), _ptr(lg), ld))
 
     def synchronize(self):
         with self.torch.cuda.device(self.device):
@@ -527,7 +527,7 @@ class Stack:
         _check(lib().ps_stack_set_copy_mode(self.h, 1 if gather else 0))
 
     def set_decode_mode(self, mode):
-        """0: launch per shard, 1: HIP-graph replay, 2: mode 0 with every RMS factor from a launch of its own (see pshard.h)."""
+        """0: launch per shard, 1: HIP-graph replay, 2: mode 0 with every RMS factor from a launch of its own (see pshard_test.h)."""
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_set_decode_mode(self.h, int(mode)))
 

@@ -621,6 +621,12 @@ int32_t ps_plan_summary(const ps_plan *p, ps_plan_summary_t *o) {
     return PS_OK;
 }
 
+int32_t ps_plan_num_shards(const ps_plan *p, uint32_t *n) {
+    if (!p || !n) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    *n = (uint32_t)p->shards.size();
+    return PS_OK;
+}
+
 int32_t ps_plan_get_shard(const ps_plan *p, uint32_t i, ps_shard_info *o) {
     if (!p || !o || i >= p->shards.size()) { ps::set_error("shard index out of range"); return PS_E_ARG; }
     const ps::Shard &s = p->shards[i];

@@ -123,7 +123,10 @@ namespace ps {
 void op_work(uint32_t op, uint32_t quant, uint64_t n, uint64_t k, uint64_t m, double *flops, double *bytes);
 int32_t db_estimate(const ps_profile_db *db, double bandwidth_gbps, uint32_t op, uint32_t quant, uint32_t threads,
                     uint64_t n, uint64_t k, uint64_t m, ps_prof_estimate *out);
-int32_t build_schedule(const ps_plan *plan, const float *router_logits, ps_schedule *out);
+// router_logits: token t of layer l at [l * layer_stride + t * n_experts] (layer_stride 0: the plan's
+// M * n_experts); n_valid: token rows that carry data, 1..M (0: all M)
+int32_t build_schedule(const ps_plan *plan, const float *router_logits, ps_schedule *out, uint64_t layer_stride = 0,
+                       uint32_t n_valid = 0);
 int32_t validate_schedule(const ps_schedule *s);
 void route_host(const float *logits, uint32_t M, uint32_t E, uint32_t k, int32_t *idx);
 // pack logical rows [16*logical_tile, +16) of a [N][K] matrix (scales fp16 [N][K/32],

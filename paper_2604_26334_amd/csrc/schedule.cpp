@@ -189,12 +189,16 @@ struct Builder {
         }
     }
 
-    int32_t run(const float *logits) {
+    // logits: token t of layer l at logits[l * layer_stride + t * n_experts]; only the first n_valid of
+    // the plan's M token rows are routed (a last prefill chunk shorter than the tier): the op list keeps
+    // the plan's shape, the expert task lists hold the valid tokens' pairs only
+    int32_t run(const float *logits, uint64_t layer_stride, uint32_t n_valid) {
         const ModelGeom &g = p->g;
         const auto &m = g.m;
         const uint32_t M = p->M;
         if (g.moe && !logits) { set_error("MoE schedule needs host router logits"); return PS_E_ARG; }
-        std::vector<int32_t> idx((size_t)M * std::max(1u, m.top_k));
+        if (n_valid == 0 || n_valid > M) { set_error("%u valid token rows in a plan of %u", n_valid, M); return PS_E_ARG; }
+        std::vector<int32_t> idx((size_t)n_valid * std::max(1u, m.top_k));
         size_t si = 0;
         for (uint32_t l = 0; l < m.n_layers; ++l) {
             host_has_h = false;
@@ -215,7 +219,7 @@ struct Builder {
             }
             add_plain(PS_K_ROUTE, l, PS_OPF_RECORD_ROUTER);
             batch_open = false;  // expert batches never share a slot fill with other layers
-            route_host(logits + (size_t)l * M * m.n_experts, M, m.n_experts, m.top_k, idx.data());
+            route_host(logits + (size_t)l * layer_stride, n_valid, m.n_experts, m.top_k, idx.data());
             // shards of this layer's experts are consecutive: si + e
             const size_t e0 = si;
             si += m.n_experts;
@@ -223,7 +227,7 @@ struct Builder {
             for (uint32_t e = 0; e < m.n_experts; ++e) {
                 TaskHost t;
                 t.shard = (uint32_t)(e0 + e); t.expert = e; t.pair0 = (uint32_t)out->pairs.size();
-                for (uint32_t q = 0; q < M * m.top_k; ++q)
+                for (uint32_t q = 0; q < n_valid * m.top_k; ++q)
                     if (idx[q] == (int32_t)e) out->pairs.push_back((int32_t)q);
                 t.npairs = (uint32_t)out->pairs.size() - t.pair0;
                 if (!t.npairs) continue;
@@ -318,11 +322,13 @@ struct Builder {
 
 }  // namespace
 
-int32_t build_schedule(const ps_plan *plan, const float *router_logits, ps_schedule *out) {
+int32_t build_schedule(const ps_plan *plan, const float *router_logits, ps_schedule *out, uint64_t layer_stride,
+                       uint32_t n_valid) {
     Builder b{};
     b.p = plan;
     b.out = out;
-    return b.run(router_logits);
+    return b.run(router_logits, layer_stride ? layer_stride : (uint64_t)plan->M * plan->g.m.n_experts,
+                 n_valid ? n_valid : plan->M);
 }
 
 // Vector-clock check over the two in-order streams.  An event wait refers to the latest

@@ -63,6 +63,9 @@ struct ps_stack {
     bool out_upload_pending = false;          // host_out is still being read by an upload
     __half *logits = nullptr;                 // output head: caller's logits buffer
     uint32_t head_rows = 0, head_row0 = 0;    // 0: head skipped, 1: token head_row0 only, n_tokens: every token
+    uint32_t n_valid = 0;                     // token rows of the current forward that carry data (<= plan.M)
+    const float *route_logits = nullptr;      // device: router logits the routing kernel of this forward reads
+    uint64_t route_layer_stride = 0;          // elements between two layers' logits there
     uint32_t ctx = 0;                         // cached positions the next forward attends over (KV stacks)
     hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
     bool step_pending = false;
@@ -161,7 +164,10 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
     const auto &m = g.m;
-    const uint32_t M = p.M, H = m.hidden, l = op.info.layer;
+    // M: token rows that carry data in this forward (the last chunk of a chunked prefill has fewer
+    // than the plan's MP).  Launch shapes, tile sizes and the K split go by MP alone, so a row's bits
+    // do not depend on how many rows came with it; rows past M are neither read nor written.
+    const uint32_t M = st->n_valid, MP = p.M, H = m.hidden, l = op.info.layer;
     uint8_t *A = st->arena;
     const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
     __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
@@ -199,7 +205,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         PS_HIP(launch_gemv(GEMV_PLAIN, gemv_ksplit(g.head.ngroups, g.head.ntiles), a, 0, cs));
         return PS_OK;
     }
-    if (M == 1 && op.info.kernel >= PS_K_QKV && op.info.kernel <= PS_K_DOWN) {
+    if (MP == 1 && op.info.kernel >= PS_K_QKV && op.info.kernel <= PS_K_DOWN) {
         GemvArgs a;
         int mode;
         uint32_t ks;
@@ -210,14 +216,14 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     // batched decode (2..64 tokens) of a narrow matrix: split K over blockIdx.z into fp32 partial
     // planes, then one epilogue kernel sums them in order and applies the mode's epilogue
     auto run_gemm = [&](int mode, GemmArgs a, const MatGeom &mg) -> int32_t {
-        const uint32_t per = gemm_sb_per_part(mg, M);
-        if (!per) { PS_HIP(launch_gemm(mode, a, 0, M, cs)); return PS_OK; }
+        const uint32_t per = gemm_sb_per_part(mg, MP);
+        if (!per) { PS_HIP(launch_gemm(mode, a, 0, MP, cs)); return PS_OK; }
         GemmArgs pa = a;
         float *partial = reinterpret_cast<float *>(A + p.ws.partial);
         const uint32_t ncols = a.ntiles * 16;
         pa.out_f32 = partial; pa.out = nullptr; pa.out_stride = ncols; pa.out_row0 = 0;
-        pa.sb_per_part = per; pa.part_stride = M * ncols;
-        PS_HIP(launch_gemm(GEMM_F32, pa, 0, M, cs));
+        pa.sb_per_part = per; pa.part_stride = MP * ncols;
+        PS_HIP(launch_gemm(GEMM_F32, pa, 0, MP, cs));
         if (mode == GEMM_RESID && ncols == H && a.out_row0 == 0 && a.out_stride == H && !st->own_rinv_launch) {
             // the launch covers whole rows of the hidden state: its epilogue also leaves their RMS
             // factors (the bits rinv_kernel gives), and the PS_K_RINV op that follows is skipped
@@ -238,7 +244,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             if (!have) PS_HIP(launch_rinv(rows, M, H, m.rms_eps, rinv, cs));
             return PS_OK;
         }
-        case PS_K_OUT: {   // every token's logits (head_rows == M > 1)
+        case PS_K_OUT: {   // every token's logits (head_rows == MP > 1)
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.head);
             a.W = wptr(op); a.ntiles = s.ntiles; a.x = x_out; a.x_stride = H; a.out = st->logits;
@@ -295,7 +301,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
                                        reinterpret_cast<__half *>(A + p.ws.attn), cs));
             return PS_OK;
         case PS_K_ROUTE:
-            PS_HIP(launch_route(reinterpret_cast<const float *>(A + p.ws.logits) + (size_t)l * M * m.n_experts, M,
+            PS_HIP(launch_route(st->route_logits + (size_t)l * st->route_layer_stride, M,
                                 m.n_experts, m.top_k, reinterpret_cast<int32_t *>(A + p.ws.ridx),
                                 reinterpret_cast<float *>(A + p.ws.rw), cs));
             return PS_OK;
@@ -308,7 +314,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             uint32_t max_tok = 0;
             for (uint32_t t = op.task0; t < op.task0 + op.ntasks; ++t) max_tok = std::max(max_tok, sc.tasks[t].npairs);
             const MatGeom &mg = gu ? g.gate_up : g.down;
-            if (M == 1) {
+            if (MP == 1) {
                 GemvArgs a = gemv_base(mg);
                 a.tasks = tasks; a.pairs = pairs;
                 if (gu) { a.nunits = mg.ntiles / 2; a.x = hbuf; a.x_stride = H; a.out = sbuf; a.out_stride = g.ffn_i; }
@@ -342,7 +348,7 @@ double now_ms() {
 int32_t issue_fetch(ps_stack *st, const Op &op, const __half *x_in, __half *x_out) {
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
-    const uint32_t M = p.M, H = g.m.hidden, l = op.info.layer;
+    const uint32_t M = st->n_valid, H = g.m.hidden, l = op.info.layer;
     uint8_t *A = st->arena;
     const double t0 = now_ms();
     if (op.info.buffers & PS_BUF_H) {
@@ -427,7 +433,7 @@ int32_t issue_cpu(ps_stack *st, const ps_schedule &sc, const Op &op, __half *x_o
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
     const auto &m = g.m;
-    const uint32_t M = p.M, H = m.hidden, l = op.info.layer;
+    const uint32_t M = st->n_valid, H = m.hidden, l = op.info.layer;
     uint8_t *A = st->arena;
     const Shard &s = p.shards[op.info.shard0];
     if (st->out_upload_pending) { PS_HIP(hipStreamSynchronize(st->compute)); st->out_upload_pending = false; }
@@ -504,6 +510,9 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
         auto it = st->graphs.find(key);
         if (it == st->graphs.end()) {
             if (st->graphs.size() >= 32) {
+                // forward is asynchronous: the latest replays may still be running, and an executable
+                // graph must not be destroyed while it is in flight
+                PS_HIP(hipStreamSynchronize(st->compute));
                 for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
                 st->graphs.clear();
             }
@@ -619,6 +628,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     ps_stack *st = new (std::nothrow) ps_stack();
     if (!st) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
     st->plan = *plan;
+    st->n_valid = plan->M;
     st->arena = static_cast<uint8_t *>(vram_arena);
     st->arena_bytes = arena_bytes;
     st->compute = static_cast<hipStream_t>(compute_stream);
@@ -860,15 +870,12 @@ int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads) {
     return PS_OK;
 }
 
-int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits) {
-    if (!st || !x_in || !x_out) { ps::set_error("NULL argument"); return PS_E_ARG; }
-    if (x_in == x_out) { ps::set_error("x_in and x_out may not alias"); return PS_E_ARG; }
-    if (st->n_loaded != st->n_expected) {
-        ps::set_error("forward before all matrices were loaded (%llu of %llu)", (unsigned long long)st->n_loaded,
-                      (unsigned long long)st->n_expected);
-        return PS_E_STATE;
-    }
+// One trip through the plan's schedule over the first n_valid of its M token rows.
+// router_logits (host) / logits_dev (device, optional): token t of layer l at [l * layer_stride + t * n_experts].
+static int32_t forward_impl(ps_stack *st, const void *x_in, void *x_out, const float *router_logits,
+                            const float *logits_dev, uint64_t layer_stride, uint32_t n_valid) {
     const ps_plan &p = st->plan;
+    st->n_valid = n_valid;
     if (p.g.kv) {
         if (st->ctx >= p.g.m.kv_context) { ps::set_error("context %u leaves no room in a cache of %u positions", st->ctx, p.g.m.kv_context); return PS_E_STATE; }
         // this step's cache copies read rows the previous step appended from the compute stream
@@ -881,8 +888,9 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     }
 
     if (!router_logits) { ps::set_error("MoE forward needs host router logits"); return PS_E_ARG; }
+    const uint32_t E = p.g.m.n_experts, L = p.g.m.n_layers;
     ps_schedule sc;
-    int32_t rc = ps::build_schedule(&st->plan, router_logits, &sc);
+    int32_t rc = ps::build_schedule(&st->plan, router_logits, &sc, layer_stride, n_valid);
     if (rc) return rc;
     // device tables: logits | tasks | pairs, staged in pinned memory and uploaded on the compute stream
     // two table buffers alternate, so the host can prepare a forward while the previous one runs
@@ -891,7 +899,6 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     if (st->upload_pending[tb]) { PS_HIP(hipEventSynchronize(st->ev_upload[tb])); st->upload_pending[tb] = false; }
     st->n_descs = 0;
     uint8_t *th = static_cast<uint8_t *>(st->tables_host[tb]);
-    std::memcpy(th, router_logits, p.ws.logits_bytes);
     ps::DeviceTask *dt = reinterpret_cast<ps::DeviceTask *>(th + p.ws.logits_bytes);
     if (sc.tasks.size() * sizeof(ps::DeviceTask) > p.ws.tasks_bytes || sc.pairs.size() * 4 > p.ws.pairs_bytes) {
         ps::set_error("internal: routing tables exceed the workspace"); return PS_E_STATE;
@@ -906,7 +913,17 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
         dt[t].pair0 = h.pair0; dt[t].npairs = h.npairs; dt[t].expert = h.expert; dt[t].pad = 0;
     }
     std::memcpy(th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.data(), sc.pairs.size() * 4);
-    PS_HIP(hipMemcpyAsync(st->arena + p.ws.logits, th, p.ws.logits_bytes, hipMemcpyHostToDevice, st->compute));
+    if (logits_dev) {   // the routing kernel reads the caller's device copy in place: nothing to upload
+        st->route_logits = logits_dev;
+        st->route_layer_stride = layer_stride;
+    } else {            // the workspace copy: [layer][M][E], the first n_valid rows of each layer filled
+        float *lh = reinterpret_cast<float *>(th);
+        for (uint32_t l = 0; l < L; ++l)
+            std::memcpy(lh + (size_t)l * p.M * E, router_logits + (size_t)l * layer_stride, (size_t)n_valid * E * 4);
+        PS_HIP(hipMemcpyAsync(st->arena + p.ws.logits, th, p.ws.logits_bytes, hipMemcpyHostToDevice, st->compute));
+        st->route_logits = reinterpret_cast<const float *>(st->arena + p.ws.logits);
+        st->route_layer_stride = (uint64_t)p.M * E;
+    }
     if (!sc.tasks.empty())
         PS_HIP(hipMemcpyAsync(st->arena + p.ws.tasks, dt, sc.tasks.size() * sizeof(ps::DeviceTask), hipMemcpyHostToDevice, st->compute));
     if (!sc.pairs.empty())
@@ -918,6 +935,56 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[1], 0));
     PS_HIP(hipEventRecord(st->ev_upload[tb], st->compute));
     st->upload_pending[tb] = true;
+    return rc;
+}
+
+static int32_t forward_checks(ps_stack *st, const void *x_in, void *x_out) {
+    if (!st || !x_in || !x_out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (x_in == x_out) { ps::set_error("x_in and x_out may not alias"); return PS_E_ARG; }
+    if (st->n_loaded != st->n_expected) {
+        ps::set_error("forward before all matrices were loaded (%llu of %llu)", (unsigned long long)st->n_loaded,
+                      (unsigned long long)st->n_expected);
+        return PS_E_STATE;
+    }
+    return PS_OK;
+}
+
+int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits,
+                         const float *router_logits_dev) {
+    const int32_t rc = forward_checks(st, x_in, x_out);
+    if (rc) return rc;
+    const ps_plan &p = st->plan;
+    return forward_impl(st, x_in, x_out, router_logits, router_logits_dev, (uint64_t)p.M * p.g.m.n_experts, p.M);
+}
+
+int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, uint32_t n_tokens,
+                                 const float *router_logits, const float *router_logits_dev, void *last_logits_dev,
+                                 uint32_t *trips) {
+    int32_t rc = forward_checks(st, x_in, x_out);
+    if (rc) return rc;
+    if (n_tokens == 0) { ps::set_error("n_tokens is 0"); return PS_E_ARG; }
+    const ps_plan &p = st->plan;
+    if (p.g.kv) { ps::set_error("a stack with a KV cache takes one token per forward"); return PS_E_STATE; }
+    if (last_logits_dev && !p.g.m.vocab) { ps::set_error("this stack has no output head (vocab is 0)"); return PS_E_STATE; }
+    if (last_logits_dev && (uintptr_t)last_logits_dev % 16) { ps::set_error("logits buffer must be 16-byte aligned"); return PS_E_ARG; }
+    const uint32_t T = p.M, H = p.g.m.hidden, E = p.g.m.n_experts;
+    // the head setting of plain forwards is put back afterwards
+    __half *const saved_logits = st->logits;
+    const uint32_t saved_rows = st->head_rows, saved_row0 = st->head_row0;
+    uint32_t n_trips = 0;
+    for (uint32_t r0 = 0; r0 < n_tokens && rc == PS_OK; r0 += T, ++n_trips) {
+        const uint32_t nv = std::min(T, n_tokens - r0);
+        const bool last = r0 + nv == n_tokens;
+        // the head runs on the last trip only, for the prompt's last token
+        st->logits = last && last_logits_dev ? static_cast<__half *>(last_logits_dev) : nullptr;
+        st->head_rows = st->logits ? 1 : 0;
+        st->head_row0 = st->logits ? nv - 1 : 0;
+        rc = forward_impl(st, static_cast<const __half *>(x_in) + (size_t)r0 * H, static_cast<__half *>(x_out) + (size_t)r0 * H,
+                          router_logits ? router_logits + (size_t)r0 * E : nullptr,
+                          router_logits_dev ? router_logits_dev + (size_t)r0 * E : nullptr, (uint64_t)n_tokens * E, nv);
+    }
+    st->logits = saved_logits; st->head_rows = saved_rows; st->head_row0 = saved_row0;
+    if (trips) *trips = n_trips;
     return rc;
 }
 
@@ -993,6 +1060,7 @@ int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, doubl
     if (!st->have_dense_sched || st->n_loaded != st->n_expected) { ps::set_error("needs a loaded dense stack"); return PS_E_STATE; }
     if (kernel == PS_K_OUT && !st->head_rows) { ps::set_error("timing the output head needs a logits buffer"); return PS_E_STATE; }
     const ps_plan &p = st->plan;
+    st->n_valid = p.M;
     // activations: the workspace ping-pong buffers stand in for the caller's tensors
     const __half *xin = reinterpret_cast<const __half *>(st->arena + p.ws.x0);
     __half *xout = reinterpret_cast<__half *>(st->arena + p.ws.x1);

@@ -165,7 +165,7 @@ def test_output_head_error_paths():
     for layer in range(cfg["n_layers"]):
         for kind, expert, N, K in S.matrix_shapes(cfg):
             st.load_matrix(layer, kind, expert, *W(layer, kind, expert))
-    assert L.ps_stack_forward(st.h, x.data_ptr(), y.data_ptr(), None) == B.PS_E_STATE   # head not loaded yet
+    assert L.ps_stack_forward(st.h, x.data_ptr(), y.data_ptr(), None, None) == B.PS_E_STATE   # head not loaded yet
     sc, cd = head
     assert L.ps_stack_load_matrix(st.h, 0, B.PS_MAT_OUT, B.NO_EXPERT, sc.ctypes.data, cd.ctypes.data) == B.PS_E_ARG
     assert L.ps_stack_load_matrix(st.h, 1, B.PS_MAT_OUT, 0, sc.ctypes.data, cd.ctypes.data) == B.PS_E_ARG

@@ -205,6 +205,27 @@ def test_chunked_prefill_through_the_tier_table(kind):
         err = Hn.rel_err(got, ref)
         _say("tier", e.tier_tokens, "trips", trips, "rel err %.2e" % err)
         assert np.isfinite(got).all() and err <= TOL
+        # a last chunk shorter than the tier: the bits of the same rows in a zero-padded full trip
+        T, H = e.tier_tokens, cfg["hidden"]
+        r0 = (n // T) * T
+        if r0 < n:
+            xi = torch.zeros((T, H), dtype=torch.float16, device=st.device)
+            xi[:n - r0] = xin[r0:]
+            xo = torch.empty_like(xi)
+            lp = None
+            if logits is not None:
+                lp = np.zeros((cfg["n_layers"], T, cfg["n_experts"]), np.float32)
+                lp[:, :n - r0] = logits[:, r0:]
+            st.forward(xi, xo, lp)
+            st.synchronize()
+            np.testing.assert_array_equal(xo[:n - r0].cpu().numpy().view(np.uint16), got[r0:].view(np.uint16))
+        if logits is not None:   # routing kernel reading the caller's device copy of the logits: same bits
+            ld = torch.from_numpy(np.ascontiguousarray(logits)).to(st.device)
+            xo2 = torch.zeros_like(xin)
+            torch.cuda.synchronize()
+            B.chunked_forward(st, xin, xo2, logits, router_logits_dev=ld)
+            st.synchronize()
+            np.testing.assert_array_equal(xo2.cpu().numpy().view(np.uint16), got.view(np.uint16))
         st.close()
     # the larger tier's workspace displaces pinned shards, the smaller tier pins more (or all)
     assert streamed[-1] > 0 and streamed == sorted(streamed)
@@ -315,8 +336,8 @@ def test_error_paths_return_codes_and_leave_the_stack_usable():
         with pytest.raises(B.PshardError) as e:
             st.load_matrix(bad[0], bad[1], None, sc, cd)
         assert e.value.code == B.PS_E_ARG
-    assert L.ps_stack_forward(st.h, x.data_ptr(), x.data_ptr(), None) == B.PS_E_ARG      # aliasing
-    assert L.ps_stack_forward(st.h, None, y.data_ptr(), None) == B.PS_E_ARG
+    assert L.ps_stack_forward(st.h, x.data_ptr(), x.data_ptr(), None, None) == B.PS_E_ARG      # aliasing
+    assert L.ps_stack_forward(st.h, None, y.data_ptr(), None, None) == B.PS_E_ARG
     with pytest.raises(B.PshardError) as e:            # no KV cache in this stack
         st.set_context(3)
     assert e.value.code == B.PS_E_STATE
