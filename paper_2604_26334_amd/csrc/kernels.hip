@@ -231,7 +231,7 @@ struct GemvLds {
 // waves per unit.
 // DBUF: a wave with several scale groups issues the next group's loads before computing the
 // current one (costs a second register buffer; the one-tile modes can afford it).
-template <int MODE, int NW, bool DBUF = ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), bool FULLG = false>
+template <int MODE, int NW, bool DBUF = false, bool FULLG = false>
 __device__ __forceinline__ void gemv_item(const GemvArgs &a, const uint4 *W, const __half *x, __half *out,
                                           float *out_f32, uint32_t item, uint32_t ks, GemvLds<NW> &lds) {
     constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
@@ -380,7 +380,10 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_w4_kernel(GemvArgs a, uint32_
             out_f32 = a.out_f32 + (size_t)pair * a.out_stride;
         }
     }
-    gemv_item<MODE, NW, ((MODE == GEMV_RESID || MODE == GEMV_F32) && NW < 16), FULLG>(a, W, x, out, out_f32, blockIdx.x, ks, lds);
+    // second register buffer for the one-tile modes (the residual mode with ragged scale groups would
+    // spill a register with it)
+    constexpr bool DBUF = (MODE == GEMV_F32 || (MODE == GEMV_RESID && FULLG)) && NW < 16;
+    gemv_item<MODE, NW, DBUF, FULLG>(a, W, x, out, out_f32, blockIdx.x, ks, lds);
 }
 
 template <int MODE, bool FULLG>
@@ -966,6 +969,18 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         }
     };
 
+    // One prefetch = the stage's NFILL LDS fills, THEN the 2 AT weight loads, in that order in the
+    // instruction stream: the hand-counted waits below rely on it (loads complete in issue order, so
+    // "all but the newest n" is a statement about which loads have landed).  The fence keeps the
+    // compiler from moving the weight loads, which depend on nothing, above fills whose addresses do
+    // (in grouped launches the fill offsets come from a load of the pair list).
+    auto prefetch = [&](uint32_t sb_fill, uint32_t stage, uint32_t sb_w, Wset &w) {
+        fill_x(sb_fill, stage);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(sb_w, w);
+    };
+
     // split-K: this workgroup covers super-blocks [sb_begin, sb_end) and writes an fp32 partial plane
     uint32_t sb_begin = 0, sb_end = a.nsb;
     if (!GROUPED && a.sb_per_part) {
@@ -973,10 +988,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         sb_end = min(a.nsb, sb_begin + a.sb_per_part);
     }
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        fill_x(min(sb_begin + d, sb_end - 1), d);
-        load_w(sb_begin + d, wr[d]);
-    }
+    for (int d = 0; d < DEPTH; ++d) prefetch(min(sb_begin + d, sb_end - 1), d, sb_begin + d, wr[d]);
     // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
     // (one more operand set in registers; the 4-tile shape has no room for it)
     constexpr bool PIPE = (AT <= 2);
@@ -993,7 +1005,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // barrier of the EARLY shape needs only the fills of the stage it covers: that stage's weight
     // loads (from HBM, the slow ones; consumed a step later) may stay in flight as well
     constexpr int kInFlight = kLand * LPI + (EARLY ? 2 * AT : 0);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");   // the first LDS fill(s) have landed
+    // Before the first step: everything issued so far has landed.  No count is assumed here, because
+    // nothing orders the DEPTH opening prefetches among themselves: the compiler hoists the weight
+    // loads of all of them above fills that wait for the pair list, and merges the scale loads of two
+    // super-blocks that share a dword, so "all but the newest kInFlight" would not name the fills of
+    // stage 0 (a build in which it happened not to gave wrong results now and then).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     h8_t Bc[NMT], Bn[NMT];
     if (EARLY) {
@@ -1003,13 +1020,16 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 
     // one super-block: U = its position in the ring (compile-time, so every register set and LDS
     // stage below is addressed statically and nothing is copied when the ring turns)
-    auto step = [&](uint32_t sb, auto U) {
+    // TAIL: one of the at most R - 1 steps after the last whole turn of the ring.  Their prefetched
+    // weights are never used and the compiler drops those loads, so fewer than LPI loads are issued
+    // and the counted wait would name less than it should: they wait for everything instead.
+    auto step = [&](uint32_t sb, auto U, auto TAIL) {
         constexpr int u = decltype(U)::value;
+        constexpr bool tail = decltype(TAIL)::value;
         constexpr int un = (u + 1) % R, up = (u + DEPTH) % R;   // next super-block's slot, the slot to refill
         // prefetch super-block sb + DEPTH: activations into the stage every wave left at the
         // barrier that ended the previous step, weights into the register set used then
-        fill_x(min(sb + DEPTH, sb_end - 1), up);
-        load_w(sb + DEPTH, wr[up]);
+        prefetch(min(sb + DEPTH, sb_end - 1), up, sb + DEPTH, wr[up]);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
         const uint4 *ls = lds + u * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
         const uint4 *lsn = lds + un * (MT * 16) + i * 16;  // the next super-block's stage
@@ -1056,24 +1076,24 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         // here is ordered by hand: this wave's fill of the next stage is complete (vmcnt), and
         // its LDS reads of the current stage, which the next step's fill overwrites, have
         // returned (lgkmcnt).
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kInFlight) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(tail ? 0 : kInFlight) : "memory");
         __builtin_amdgcn_s_barrier();
     };
     // whole turns of the ring, then the remaining steps (no exit from inside a turn: the ring is back
     // in phase at the loop's back edge, so no register set is live across it in another slot)
     uint32_t sb = sb_begin;
     for (; sb + R <= sb_end; sb += R) {
-        step(sb, std::integral_constant<int, 0>{});
-        step(sb + 1, std::integral_constant<int, 1>{});
-        if constexpr (R > 2) step(sb + 2, std::integral_constant<int, 2>{});
-        if constexpr (R > 3) step(sb + 3, std::integral_constant<int, 3>{});
+        step(sb, std::integral_constant<int, 0>{}, std::false_type{});
+        step(sb + 1, std::integral_constant<int, 1>{}, std::false_type{});
+        if constexpr (R > 2) step(sb + 2, std::integral_constant<int, 2>{}, std::false_type{});
+        if constexpr (R > 3) step(sb + 3, std::integral_constant<int, 3>{}, std::false_type{});
     }
-    if (sb < sb_end) step(sb, std::integral_constant<int, 0>{});
+    if (sb < sb_end) step(sb, std::integral_constant<int, 0>{}, std::true_type{});
     if constexpr (R > 2) {
-        if (sb + 1 < sb_end) step(sb + 1, std::integral_constant<int, 1>{});
+        if (sb + 1 < sb_end) step(sb + 1, std::integral_constant<int, 1>{}, std::true_type{});
     }
     if constexpr (R > 3) {
-        if (sb + 2 < sb_end) step(sb + 2, std::integral_constant<int, 2>{});
+        if (sb + 2 < sb_end) step(sb + 2, std::integral_constant<int, 2>{}, std::true_type{});
     }
 
     // epilogue: lane holds token j = lane & 15 of each token tile and rows 4*(lane >> 4) + r

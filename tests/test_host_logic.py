@@ -741,3 +741,41 @@ def test_plans_priced_from_a_profile_database():
     a = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=slow_copy).summary()
     b = B.Plan(cfg, budget, 1, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=fast_copy).summary()
     assert a.est_step_ms == pytest.approx(a.streamed_bytes / (1 << 20) * 1.0, rel=0.05) and b.est_step_ms < a.est_step_ms / 50
+
+
+# ------------------------------------------------------------------ build-time checks
+
+def _fake_gemm_isa(prologue_wait, step_loads, step_wait):
+    lds = "\tbuffer_load_dwordx4 v1, s[4:7], 0 offen lds\n"
+    w4, w1 = "\tbuffer_load_dwordx4 v[2:5], v1, s[4:7], 0 offen\n", "\tbuffer_load_dword v6, v1, s[4:7], 0 offen\n"
+    kinds = {"lds": lds, "w4": w4, "w1": w1, "g": "\tglobal_load_dword v7, v[8:9], off\n"}
+    step = "".join(kinds[k] for k in step_loads) + "\ts_waitcnt vmcnt(%d) lgkmcnt(0)\n\ts_barrier\n" % step_wait
+    return ("_ZN2ps14gemm_w4_kernelILi0ELi2ELi16ELb0ELi4EEEvNS_8GemmArgsE: ; @x\n" + lds + w4 + w1 + w4 + w1 +
+            "\ts_waitcnt vmcnt(%d)\n\ts_barrier\n" % prologue_wait + step + step +
+            "\tglobal_store_dword v[8:9], v7, off\n\ts_endpgm\n.Lfunc_end0:\n")
+
+
+def test_build_check_of_the_gemm_wait_counts(tmp_path):
+    """The build refuses generated code in which the GEMM's hand-counted waits would not name the loads
+    they are meant to: an opening wait that is not vmcnt(0), a counted step with a load too few or too
+    many, fills that do not come first, or a foreign memory operation inside the ring."""
+    from paper_2604_26334_amd import build as Bd
+    assert Bd.gemm_wait_counts(16, 4) == (5, 1, 5)        # 1 fill + 4 weight loads, one prefetch may be in flight
+    assert Bd.gemm_wait_counts(64, 4) == (8, 4, 8)
+    assert Bd.gemm_wait_counts(128, 4) == (12, 8, 0)      # one super-block of lookahead: every step waits for all
+    assert Bd.gemm_wait_counts(128, 8) == (8, 4, 12)      # three of lookahead: one prefetch and the next one's weights
+    good = ["lds", "w4", "w1", "w4", "w1"]
+    cases = [(0, good, 5, True), (5, good, 5, False), (0, good[:-1], 5, False), (0, good + ["w1"], 5, False),
+             (0, ["w4", "lds", "w1", "w4", "w1"], 5, False), (0, good, 4, False), (0, ["lds", "w4", "w1", "w4", "g"], 5, False),
+             (0, good[:1], 0, True)]                       # a tail step: fewer loads, but it waits for everything
+    for i, (pw, loads, sw, ok) in enumerate(cases):
+        p = tmp_path / ("k%d.s" % i)
+        p.write_text(_fake_gemm_isa(pw, loads, sw))
+        if ok:
+            assert Bd.check_gemm_isa(str(p)) == 1
+        else:
+            with pytest.raises(RuntimeError):
+                Bd.check_gemm_isa(str(p))
+    with pytest.raises(RuntimeError):
+        Bd.check_resource_usage("remark: Function Name: _ZN2ps14gemm_w4_kernelILi0EEE\nremark:     ScratchSize [bytes/lane]: 8 [-R]\n")
+    Bd.check_resource_usage("remark: Function Name: _ZN2ps14gemm_w4_kernelILi0EEE\nremark:     ScratchSize [bytes/lane]: 0 [-R]\n")
