@@ -103,8 +103,25 @@ def batched_leg(B, S, torch, cfg, seed, prof, tokens, budgets, steps):
     return out
 
 
-def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
-    """MoE stack (config 4): 48 layers, 128 experts, top-8; decode at each token count."""
+def expert_frequencies(B, S, cfg, seed, bias_seed, tokens=1024):
+    """Selection frequency of every (layer, expert) over a host warm-up of `tokens` tokens routed with
+    the library's own rule (ps_route_host): the share of tokens that select the expert."""
+    import numpy as np
+    lg = S.router_logits(seed, 999, cfg["n_layers"], tokens, cfg["n_experts"], bias_seed=bias_seed)
+    freq = np.zeros((cfg["n_layers"], cfg["n_experts"]), dtype=np.float32)
+    for l in range(cfg["n_layers"]):
+        idx = B.route_host(lg[l], cfg["top_k"])
+        freq[l] = np.bincount(idx.reshape(-1), minlength=cfg["n_experts"]) / float(tokens)
+    return freq
+
+
+def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps, bias_seed=7):
+    """MoE stack (config 4): 48 layers, 128 experts, top-8; decode at each token count.  Three runs per
+    token count: the config's own router logits (i.i.d. N(0,1): every expert equally hot) on the plan
+    without frequencies; and, as this build's variant of "hot experts", logits with a fixed
+    per-(layer, expert) N(0,1) bias on that same plan and on a plan whose experts are ranked by the
+    selection frequencies of a 1024-token host warm-up."""
+    import numpy as np
     cfg = S.cfg_moe()
     out = {}
     names = ["gpu_only", "static", "dynamic"]
@@ -114,9 +131,15 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
         db = B.ProfileDB()
         db.measure(cfg)
     db_est = {}
+    freq = expert_frequencies(B, S, cfg, seed, bias_seed) if bias_seed is not None else None
     for m in token_counts:
         plans.append(B.Plan(cfg, int(budget), m, profile=prof))
-        tags.append((m, "batch_%d" % m))
+        tags.append((m, "batch_%d" % m, None))
+        if freq is not None:
+            tags.append((m, "batch_%d_hot_experts_unranked" % m, bias_seed))     # same plan, biased logits
+            plans.append(plans[-1])
+            plans.append(B.Plan(cfg, int(budget), m, profile=prof, expert_freq=freq))
+            tags.append((m, "batch_%d_hot_experts_ranked" % m, bias_seed))
         if prof is not None and prof.cpu_gbps > 0:   # HeuristicSplit's pick, if it is not Plan One again
             auto = B.Plan(cfg, int(budget), m, profile=prof, kind=B.PS_PLAN_AUTO)
             auto_db = B.Plan(cfg, int(budget), m, profile=prof, kind=B.PS_PLAN_AUTO, db=db).summary()
@@ -126,16 +149,32 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
                 ["%.1f" % e for e in auto_db.est_kind_ms], names[auto_db.plan_kind]))
             if auto.summary().plan_kind != B.PS_PLAN_GPU_ONLY:
                 plans.append(auto)
-                tags.append((m, "batch_%d_%s" % (m, names[auto.summary().plan_kind])))
-    stacks = [B.Stack(p) for p in plans]
+                tags.append((m, "batch_%d_%s" % (m, names[auto.summary().plan_kind]), None))
+    uniq = []
+    for p in plans:
+        if not any(p is q for q in uniq):
+            uniq.append(p)
+    stacks = {id(p): B.Stack(p) for p in uniq}
     t0 = time.perf_counter()
-    B.load_synthetic(stacks, cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
-    log("loaded MoE stacks in %.1f s" % (time.perf_counter() - t0))
-    dev = stacks[0].device
-    for (m, tag), plan, st in zip(tags, plans, stacks):
+    B.load_synthetic(list(stacks.values()), cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
+    log("loaded %d MoE stacks in %.1f s" % (len(stacks), time.perf_counter() - t0))
+    dev = next(iter(stacks.values())).device
+    for (m, tag, bias), plan in zip(tags, plans):
+        st = stacks[id(plan)]
         s = plan.summary()
         xs = [torch.from_numpy(S.activations(seed, 300 + t, m, cfg["hidden"])).to(dev) for t in range(4)]
-        lgs = [S.router_logits(seed, 300 + t, cfg["n_layers"], m, cfg["n_experts"]) for t in range(4)]
+        lgs = [S.router_logits(seed, 300 + t, cfg["n_layers"], m, cfg["n_experts"], bias_seed=bias) for t in range(4)]
+        # share of the routed (token, expert) pairs whose expert is pinned in VRAM
+        res = np.zeros((cfg["n_layers"], cfg["n_experts"]), dtype=bool)
+        for sh in plan.shards():
+            if sh.kind == B.PS_SHARD_EXPERT:
+                res[sh.layer, sh.expert] = sh.resident == 1
+        hits = pairs = 0
+        for lg in lgs:
+            for l in range(cfg["n_layers"]):
+                idx = B.route_host(lg[l], cfg["top_k"])
+                hits += int(res[l][idx.reshape(-1)].sum())
+                pairs += idx.size
         xo = torch.empty_like(xs[0])
         torch.cuda.synchronize()
         for i in range(2):
@@ -157,9 +196,13 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps):
                         cpu_bytes_per_step=on_cpu / steps, cpu_ms_per_step=cpu_ms / steps,
                         pcie_gbps_whole_step=streamed / steps / (ms * 1e-3) / 1e9,
                         frac_of_measured_h2d=(streamed / steps / (ms * 1e-3) / 1e9 / prof.h2d_gbps) if prof else None,
-                        est_ms=s.est_step_ms, heuristic_split_with_database=db_est.get(m))
-        log("MoE batch %d, budget %.0f GB, plan %s: %.2f ms/step (estimate %.2f), %.1f tok/s, %.2f GB streamed/step, %.2f GB/step on the CPU in %.2f ms" % (
-            m, budget / 1e9, names[s.plan_kind], ms, s.est_step_ms, m * 1e3 / ms, streamed / steps / 1e9, on_cpu / steps / 1e9, cpu_ms / steps))
+                        est_ms=s.est_step_ms, heuristic_split_with_database=db_est.get(m),
+                        router_logits="N(0,1)" if bias is None else "N(0,1) + fixed per-(layer, expert) N(0,1) bias (this build's hot-expert variant)",
+                        resident_hit_rate=hits / max(1, pairs))
+        log("MoE batch %d (%s), budget %.0f GB, plan %s: %.2f ms/step (estimate %.2f), %.1f tok/s, resident hit rate %.3f, %.2f GB streamed/step, %.2f GB/step on the CPU in %.2f ms" % (
+            m, tag, budget / 1e9, names[s.plan_kind], ms, s.est_step_ms, m * 1e3 / ms, hits / max(1, pairs), streamed / steps / 1e9,
+            on_cpu / steps / 1e9, cpu_ms / steps))
+    for st in stacks.values():
         st.close()
     return out
 

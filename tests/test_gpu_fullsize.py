@@ -37,18 +37,22 @@ def _pick_step(cfg, seed, M, logits_fn, rows):
     raise AssertionError("no activation draw with a finite oracle row")
 
 
-def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, threads=16, kinds=None, graph=()):
+def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, threads=16, kinds=None, graph=(),
+         expert_freqs=None):
     """kinds: one schedule-plan kind per budget (None: Plan One everywhere).  Plans with CPU shards
     sum some rows in another order, so they are held to the tolerance, not to identical bits.
     graph: budgets whose stack is run a second time in decode mode 1 (HIP-graph replay, the mode the
     benchmark times its resident one-token legs in); that run must really be a replay and must give
-    the bits of the launch-per-shard run."""
+    the bits of the launch-per-shard run.
+    expert_freqs: one expert-frequency table (or None) per budget, handed to the planner.
+    Returns the bytes each stack copied over PCIe in its step."""
     import torch
     from paper_2604_26334_amd import binding as B
     rows = np.arange(M) if sample_rows is None else np.asarray(sample_rows)
     step, logits, ref = _pick_step(cfg, seed, M, logits_fn, rows)
     if kinds is None:
-        plans = [B.Plan(cfg, int(b), M) for b in budgets]
+        freqs = expert_freqs if expert_freqs is not None else [None] * len(budgets)
+        plans = [B.Plan(cfg, int(b), M, expert_freq=f) for b, f in zip(budgets, freqs)]
     else:
         prof = B.make_profile(h2d_gbps=55.0, gemv_gbps=5000.0, cpu_gbps=150.0, cpu_gbps_busy=150.0, h2d_gbps_busy=55.0,
                               cpu_tokens_free=2.5, cpu_sync_us=45.0)
@@ -59,7 +63,7 @@ def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, t
     _say("  loaded %d stacks in %.1f s" % (len(stacks), time.time() - t0))
     x = S.activations(seed, step, M, cfg["hidden"])
     xin = torch.from_numpy(x).to(stacks[0].device)
-    outs = []
+    outs, streamed = [], []
     for p, st in zip(plans, stacks):
         xout = torch.empty_like(xin)
         torch.cuda.synchronize()
@@ -67,6 +71,7 @@ def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, t
         st.forward(xin, xout, logits)
         st.synchronize()
         s = p.summary()
+        streamed.append(st.stats().streamed_bytes_step)
         _say("  budget %.1f GB, plan %d: resident %.3f GB, streamed/step %.3f GB, on the CPU %.3f GB, %d copies, %d kernels, first step %.1f ms" % (
             s.budget_bytes / 1e9, s.plan_kind, s.resident_bytes / 1e9, st.stats().streamed_bytes_step / 1e9,
             st.stats().cpu_bytes_step / 1e9, st.stats().n_copies, st.stats().n_kernels, (time.time() - t0) * 1e3))
@@ -86,6 +91,7 @@ def _run(cfg, seed, M, budgets, logits_fn=lambda step: None, sample_rows=None, t
         st.close()
     for y in outs:
         _compare(y, ref, rows, exact_to=outs[0] if kinds is None else None)
+    return streamed
 
 
 def _compare(out, ref, rows, exact_to=None):
@@ -184,6 +190,24 @@ def test_moe_decode_at_6gb(M):
     _say()
     cfg = S.cfg_moe()
     _run(cfg, 0, M, [6e9], logits_fn=lambda step: S.router_logits(0, step, cfg["n_layers"], M, cfg["n_experts"]))
+
+
+@pytest.mark.parametrize("M", [1, 16])
+def test_moe_decode_hot_experts_ranked_by_frequency_at_6gb(M):
+    """Config 4's "hot experts", as this build reads it: router logits with a fixed per-(layer, expert)
+    bias; the planner gets the selection frequencies of a 1024-token host warm-up and pins the hot
+    experts first.  Same bits as the plan without frequencies (placement never changes a result), the
+    oracle's values, and fewer bytes over PCIe."""
+    from paper_2604_26334_amd import binding as B
+    _say()
+    cfg = S.cfg_moe()
+    L, E, k = cfg["n_layers"], cfg["n_experts"], cfg["top_k"]
+    warm = S.router_logits(0, 999, L, 1024, E, bias_seed=7)
+    freq = np.stack([np.bincount(B.route_host(warm[l], k).reshape(-1), minlength=E) / 1024.0 for l in range(L)]).astype(np.float32)
+    streamed = _run(cfg, 0, M, [6e9, 6e9], logits_fn=lambda step: S.router_logits(0, step, L, M, E, bias_seed=7),
+                    expert_freqs=[None, freq])
+    _say("  streamed per step: %.3f GB without frequencies, %.3f GB with" % (streamed[0] / 1e9, streamed[1] / 1e9))
+    assert streamed[1] < streamed[0]
 
 
 @pytest.mark.parametrize("M", [1, 16])
