@@ -459,6 +459,19 @@ int32_t ps_stack_set_cpu_threads(ps_stack *st, uint32_t threads);
  * Asynchronous: returns after enqueueing; x_out is complete when compute_stream is. */
 int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const float *router_logits,
                          const float *router_logits_dev);
+/* For callers that cannot allocate device memory or hand over a workspace at the time of the call:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same pass
+ * as ps_stack_forward over a dense GPU-only stack without a KV cache, except that every buffer the
+ * kernels use between them (activations of the sub-layers, RMS factors, split-K partial sums: the
+ * plan's workspace) lies in a 32 MiB array inside the library's device image instead of the head
+ * of the arena; inputs, outputs, pinned shards and scratch slots are where they always are.  The
+ * call allocates nothing on the device and calls no allocating routine; one launch per shard
+ * whatever the decode mode.  PS_E_ARG if the plan's workspace exceeds 33554432 bytes (e.g. 64 tokens
+ * of the 8B-shaped stack need 13 MB, 2048 tokens 134 MB); PS_E_STATE for MoE / KV-cache / CPU-shard
+ * stacks and while profiling is on.  Every stack on a GPU shares that GPU's array (it keeps the last
+ * call's contents; nothing in it needs clearing, every buffer is written before it is read): two
+ * such forwards that overlap in time on one GPU race.  Bit-identical to ps_stack_forward. */
+int32_t ps_stack_forward_noalloc(ps_stack *st, const void *x_in, void *x_out);
 /* Chunked prefill (Section 3, inference phase: the picked tier's size is the chunk size): n_tokens
  * rows go through the plan's schedule in ceil(n_tokens / T) trips of T = the plan's token count.  A
  * last chunk shorter than T runs the same schedule with the same launch shapes over its rows only

@@ -90,7 +90,7 @@ class ps_op_info(C.Structure):
                 ("slot_offset", C.c_uint64), ("bytes", C.c_uint64)]
 
 
-EXPORTS = ["ps_plan_num_shards", "ps_stack_forward_chunked", "ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
+EXPORTS = ["ps_stack_forward_noalloc", "ps_plan_num_shards", "ps_stack_forward_chunked", "ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
@@ -141,6 +141,7 @@ def lib():
             "ps_stack_create": [vp, vp, u64, vp, vp, C.POINTER(vp)],
             "ps_stack_load_matrix": [vp, u32, u32, u32, vp, vp],
             "ps_stack_forward": [vp, vp, vp, vp, vp],
+            "ps_stack_forward_noalloc": [vp, vp, vp],
             "ps_stack_set_profiling": [vp, i32],
             "ps_stack_set_decode_mode": [vp, i32],
             "ps_stack_sync_check": [vp],
@@ -518,6 +519,14 @@ class Stack:
             ld = router_logits_dev.data_ptr()
         with self.torch.cuda.device(self.device):
             _check(lib().ps_stack_forward(self.h, x_in.data_ptr(), x_out.data_ptr(), _ptr(lg), ld))
+
+    def forward_noalloc(self, x_in, x_out):
+        """ps_stack_forward_noalloc: the same pass with the workspace in the library's static device array."""
+        assert x_in.dtype == self.torch.float16 and x_out.dtype == self.torch.float16
+        assert x_in.is_contiguous() and x_out.is_contiguous()
+        assert tuple(x_in.shape) == (self.M, self.H) and tuple(x_out.shape) == (self.M, self.H)
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_forward_noalloc(self.h, x_in.data_ptr(), x_out.data_ptr()))
 
     def synchronize(self):
         with self.torch.cuda.device(self.device):

@@ -12,6 +12,7 @@
 #include <chrono>
 #include <map>
 #include <memory>
+#include <mutex>
 #include <thread>
 #include <tuple>
 
@@ -32,6 +33,9 @@ struct ps_stack {
     ps_plan plan;
     uint8_t *arena = nullptr;
     uint64_t arena_bytes = 0;
+    uint8_t *static_ws = nullptr;             // this device's address of the library's static scratch
+    uint8_t *ws_base = nullptr;               // where the workspace offsets of the plan count from: the arena,
+                                              // or the library's static scratch during ps_stack_forward_noalloc
     hipStream_t compute = nullptr, copy = nullptr;
     std::vector<void *> host_chunks;          // hipHostMalloc'ed pools of streamed shards
     std::vector<uint8_t *> shard_host;        // per shard: host image (streamed) or null
@@ -80,9 +84,36 @@ struct ps_stack {
     ps_stats stats{};
 };
 
+// Workspace of ps_stack_forward_noalloc: one array per GPU, in the library's own device image, so
+// that entry point needs no memory from its caller beyond inputs, outputs and the arena's weights.
+// In host code the array's name stands for the symbol, not for a device address: the address on a
+// device comes from hipGetSymbolAddress with that device current, once, and is kept per device.
+constexpr uint64_t kStaticWsBytes = 32ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
 namespace {
 
 using namespace ps;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on first use there)
+int32_t static_scratch(uint8_t **out) {
+    int dev = -1;
+    PS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { ps::set_error("device index %d out of range", dev); return PS_E_HIP; }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PS_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || (uintptr_t)ptr % kAlign) { ps::set_error("static scratch has no usable device address"); return PS_E_HIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = static_cast<uint8_t *>(g_scratch_ptr[dev]);
+    return PS_OK;
+}
 
 constexpr uint64_t kHostChunk = 1ull << 30;
 
@@ -118,12 +149,13 @@ bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __hal
     const ModelGeom &g = p.g;
     const auto &m = g.m;
     const uint32_t l = op.info.layer;
-    uint8_t *A = st->arena;
-    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
-    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
-    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(A + p.ws.h) : const_cast<__half *>(xin);
-    __half *qkv = reinterpret_cast<__half *>(A + p.ws.qkv);
-    __half *sbuf = reinterpret_cast<__half *>(A + p.ws.s);
+    uint8_t *A = st->arena;       // weights: pinned shards and scratch slots
+    uint8_t *WS = st->ws_base;    // activations, RMS factors, partial sums, tables
+    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(WS + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(WS + (l & 1 ? p.ws.x1 : p.ws.x0));
+    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(WS + p.ws.h) : const_cast<__half *>(xin);
+    __half *qkv = reinterpret_cast<__half *>(WS + p.ws.qkv);
+    __half *sbuf = reinterpret_cast<__half *>(WS + p.ws.s);
     const bool resid = !(m.flags & PS_FLAG_NO_RESIDUAL);
     const Shard &s = p.shards[op.info.shard0];
     const uint4 *W = s.resident == 1 ? reinterpret_cast<const uint4 *>(A + s.offset)
@@ -140,7 +172,7 @@ bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __hal
             mg = &g.o; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
             a.nunits = s.ntiles; a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
             if (g.kv) {   // the attention output
-                a.x = reinterpret_cast<const __half *>(A + p.ws.attn);
+                a.x = reinterpret_cast<const __half *>(WS + p.ws.attn);
             } else {      // identity on V, read in place from the QKV row
                 a.x = qkv; a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
             }
@@ -168,13 +200,14 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
     // than the plan's MP).  Launch shapes, tile sizes and the K split go by MP alone, so a row's bits
     // do not depend on how many rows came with it; rows past M are neither read nor written.
     const uint32_t M = st->n_valid, MP = p.M, H = m.hidden, l = op.info.layer;
-    uint8_t *A = st->arena;
-    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
-    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
-    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(A + p.ws.h) : const_cast<__half *>(xin);
-    __half *qkv = reinterpret_cast<__half *>(A + p.ws.qkv);
-    __half *sbuf = reinterpret_cast<__half *>(A + p.ws.s);
-    float *rinv = reinterpret_cast<float *>(A + p.ws.rinv);
+    uint8_t *A = st->arena;       // weights: pinned shards and scratch slots
+    uint8_t *WS = st->ws_base;    // activations, RMS factors, partial sums, tables
+    const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(WS + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+    __half *xout = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(WS + (l & 1 ? p.ws.x1 : p.ws.x0));
+    __half *hbuf = g.has_attn ? reinterpret_cast<__half *>(WS + p.ws.h) : const_cast<__half *>(xin);
+    __half *qkv = reinterpret_cast<__half *>(WS + p.ws.qkv);
+    __half *sbuf = reinterpret_cast<__half *>(WS + p.ws.s);
+    float *rinv = reinterpret_cast<float *>(WS + p.ws.rinv);
     const bool resid = !(m.flags & PS_FLAG_NO_RESIDUAL);
     hipStream_t cs = st->compute;
 
@@ -219,7 +252,7 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         const uint32_t per = gemm_sb_per_part(mg, MP);
         if (!per) { PS_HIP(launch_gemm(mode, a, 0, MP, cs)); return PS_OK; }
         GemmArgs pa = a;
-        float *partial = reinterpret_cast<float *>(A + p.ws.partial);
+        float *partial = reinterpret_cast<float *>(WS + p.ws.partial);
         const uint32_t ncols = a.ntiles * 16;
         pa.out_f32 = partial; pa.out = nullptr; pa.out_stride = ncols; pa.out_row0 = 0;
         pa.sb_per_part = per; pa.part_stride = MP * ncols;
@@ -287,30 +320,30 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             a.head_stride = g.kv_shard_bytes; a.cap = m.kv_context; a.ctx = st->ctx;
             a.head0 = s.expert; a.nheads = op.info.nshards; a.group = m.n_q_heads / m.n_kv_heads;
             a.chunk_cap = (m.kv_context + kAttnChunk - 1) / kAttnChunk;
-            a.q = qkv; a.part = reinterpret_cast<float *>(A + p.ws.apart);
-            a.ctx_dev = st->use_graph ? reinterpret_cast<const uint32_t *>(A + p.ws.ctx) : nullptr;
+            a.q = qkv; a.part = reinterpret_cast<float *>(WS + p.ws.apart);
+            a.ctx_dev = st->use_graph ? reinterpret_cast<const uint32_t *>(WS + p.ws.ctx) : nullptr;
             PS_HIP(launch_attn_decode(a, cs));
             return PS_OK;
         }
         case PS_K_ATTN_COMBINE:
-            PS_HIP(launch_attn_combine(reinterpret_cast<const float *>(A + p.ws.apart),
+            PS_HIP(launch_attn_combine(reinterpret_cast<const float *>(WS + p.ws.apart),
                                        (m.kv_context + kAttnChunk - 1) / kAttnChunk, st->ctx,
-                                       st->use_graph ? reinterpret_cast<const uint32_t *>(A + p.ws.ctx) : nullptr, m.kv_context, qkv,
+                                       st->use_graph ? reinterpret_cast<const uint32_t *>(WS + p.ws.ctx) : nullptr, m.kv_context, qkv,
                                        m.n_q_heads, m.n_kv_heads,
-                                       reinterpret_cast<const uint64_t *>(A + p.ws.kvhome) + (size_t)l * m.n_kv_heads,
-                                       reinterpret_cast<__half *>(A + p.ws.attn), cs));
+                                       reinterpret_cast<const uint64_t *>(WS + p.ws.kvhome) + (size_t)l * m.n_kv_heads,
+                                       reinterpret_cast<__half *>(WS + p.ws.attn), cs));
             return PS_OK;
         case PS_K_ROUTE:
             PS_HIP(launch_route(st->route_logits + (size_t)l * st->route_layer_stride, M,
-                                m.n_experts, m.top_k, reinterpret_cast<int32_t *>(A + p.ws.ridx),
-                                reinterpret_cast<float *>(A + p.ws.rw), cs));
+                                m.n_experts, m.top_k, reinterpret_cast<int32_t *>(WS + p.ws.ridx),
+                                reinterpret_cast<float *>(WS + p.ws.rw), cs));
             return PS_OK;
         case PS_K_EXPERT_GATE_UP:
         case PS_K_EXPERT_DOWN: {
             const bool gu = op.info.kernel == PS_K_EXPERT_GATE_UP;
-            const DeviceTask *tasks = reinterpret_cast<const DeviceTask *>(A + p.ws.tasks) + op.task0;
-            const int32_t *pairs = reinterpret_cast<const int32_t *>(A + p.ws.pairs);
-            float *y = reinterpret_cast<float *>(A + p.ws.y);
+            const DeviceTask *tasks = reinterpret_cast<const DeviceTask *>(WS + p.ws.tasks) + op.task0;
+            const int32_t *pairs = reinterpret_cast<const int32_t *>(WS + p.ws.pairs);
+            float *y = reinterpret_cast<float *>(WS + p.ws.y);
             uint32_t max_tok = 0;
             for (uint32_t t = op.task0; t < op.task0 + op.ntasks; ++t) max_tok = std::max(max_tok, sc.tasks[t].npairs);
             const MatGeom &mg = gu ? g.gate_up : g.down;
@@ -331,8 +364,8 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             return PS_OK;
         }
         case PS_K_COMBINE:
-            PS_HIP(launch_combine(hbuf, reinterpret_cast<const float *>(A + p.ws.y),
-                                  reinterpret_cast<const float *>(A + p.ws.rw), M, H, m.top_k, resid ? 1 : 0, xout, cs));
+            PS_HIP(launch_combine(hbuf, reinterpret_cast<const float *>(WS + p.ws.y),
+                                  reinterpret_cast<const float *>(WS + p.ws.rw), M, H, m.top_k, resid ? 1 : 0, xout, cs));
             return PS_OK;
     }
     set_error("unknown kernel id %u", op.info.kernel);
@@ -349,15 +382,14 @@ int32_t issue_fetch(ps_stack *st, const Op &op, const __half *x_in, __half *x_ou
     const ps_plan &p = st->plan;
     const ModelGeom &g = p.g;
     const uint32_t M = st->n_valid, H = g.m.hidden, l = op.info.layer;
-    uint8_t *A = st->arena;
     const double t0 = now_ms();
     if (op.info.buffers & PS_BUF_H) {
-        const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(A + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
-        const void *src = g.has_attn ? static_cast<const void *>(A + p.ws.h) : static_cast<const void *>(xin);
+        const __half *xin = l == 0 ? x_in : reinterpret_cast<const __half *>(st->ws_base + ((l - 1) & 1 ? p.ws.x1 : p.ws.x0));
+        const void *src = g.has_attn ? static_cast<const void *>(st->ws_base + p.ws.h) : static_cast<const void *>(xin);
         PS_HIP(hipMemcpyAsync(st->host_h, src, (size_t)M * H * 2, hipMemcpyDeviceToHost, st->compute));
     }
     if (op.info.buffers & PS_BUF_S)
-        PS_HIP(hipMemcpyAsync(st->host_s, A + p.ws.s, (size_t)M * g.ffn_i * 2, hipMemcpyDeviceToHost, st->compute));
+        PS_HIP(hipMemcpyAsync(st->host_s, st->ws_base + p.ws.s, (size_t)M * g.ffn_i * 2, hipMemcpyDeviceToHost, st->compute));
     if (op.info.buffers & PS_BUF_X) {
         // the head reads every token's final state, or only the requested token's row
         const size_t row0 = st->head_rows == 1 ? st->head_row0 : 0, rows = st->head_rows == 1 ? 1 : M;
@@ -418,10 +450,10 @@ int32_t issue_cpu_experts(ps_stack *st, const ps_schedule &sc, const Op &op) {
     cpu_matmul_many(dn, *st->pool, st->cpu_scratch.data(), scr);   // then the down projections
     st->stats.cpu_ms += now_ms() - t0;
     st->stats.cpu_bytes_step += bytes;
-    uint8_t *land = st->arena + p.ws.cpu_y;
+    uint8_t *land = st->ws_base + p.ws.cpu_y;
     PS_HIP(hipMemcpyAsync(land, yrows, (size_t)row * H * 4 + (size_t)row * 4, hipMemcpyHostToDevice, st->compute));
     PS_HIP(launch_scatter_rows(reinterpret_cast<const float *>(land), reinterpret_cast<const int32_t *>(land + (size_t)row * H * 4), row, H,
-                               reinterpret_cast<float *>(st->arena + p.ws.y), st->compute));
+                               reinterpret_cast<float *>(st->ws_base + p.ws.y), st->compute));
     st->out_upload_pending = true;
     return PS_OK;
 }
@@ -434,7 +466,6 @@ int32_t issue_cpu(ps_stack *st, const ps_schedule &sc, const Op &op, __half *x_o
     const ModelGeom &g = p.g;
     const auto &m = g.m;
     const uint32_t M = st->n_valid, H = m.hidden, l = op.info.layer;
-    uint8_t *A = st->arena;
     const Shard &s = p.shards[op.info.shard0];
     if (st->out_upload_pending) { PS_HIP(hipStreamSynchronize(st->compute)); st->out_upload_pending = false; }
     CpuMatArgs a;
@@ -446,13 +477,13 @@ int32_t issue_cpu(ps_stack *st, const ps_schedule &sc, const Op &op, __half *x_o
         case PS_K_GATE_UP:
             mg = &g.gate_up; a.mode = CPU_GATE_UP; a.x = st->host_h; a.x_stride = H;
             a.out_stride = g.ffn_i; a.out_col0 = s.tile0 / 2 * 16;
-            dst = reinterpret_cast<__half *>(A + p.ws.s);
+            dst = reinterpret_cast<__half *>(st->ws_base + p.ws.s);
             break;
         case PS_K_DOWN:
             mg = &g.down; a.mode = CPU_RESID; a.x = st->host_s; a.x_stride = g.ffn_i;
             a.res = (m.flags & PS_FLAG_NO_RESIDUAL) ? nullptr : st->host_h;
             a.out_stride = H; a.out_col0 = s.tile0 * 16;
-            dst = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(A + (l & 1 ? p.ws.x1 : p.ws.x0));
+            dst = l == m.n_layers - 1 ? x_out : reinterpret_cast<__half *>(st->ws_base + (l & 1 ? p.ws.x1 : p.ws.x0));
             break;
         case PS_K_OUT:
             mg = &g.head; a.mode = CPU_PLAIN; a.x = st->host_x; a.x_stride = H;
@@ -501,7 +532,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     ss = ps_stats{};
     // graph mode with a KV cache: the context length travels in device memory, where the attention
     // kernels of this mode read it (set here, outside any capture, so a replay sees this step's value)
-    if (st->use_graph && p.g.kv) PS_HIP(launch_set_u32(reinterpret_cast<uint32_t *>(st->arena + p.ws.ctx), st->ctx, st->compute));
+    if (st->use_graph && p.g.kv) PS_HIP(launch_set_u32(reinterpret_cast<uint32_t *>(st->ws_base + p.ws.ctx), st->ctx, st->compute));
     if (st->use_graph && !prof) {
         // Launch-bound case (every shard resident, one token): the kernel sequence is captured
         // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
@@ -630,6 +661,11 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     st->plan = *plan;
     st->n_valid = plan->M;
     st->arena = static_cast<uint8_t *>(vram_arena);
+    st->ws_base = st->arena;
+    {   // set-up for ps_stack_forward_noalloc: this device's address of the static scratch
+        const int32_t rc = static_scratch(&st->static_ws);
+        if (rc) { delete st; return rc; }
+    }
     st->arena_bytes = arena_bytes;
     st->compute = static_cast<hipStream_t>(compute_stream);
     st->copy = static_cast<hipStream_t>(copy_stream);
@@ -723,7 +759,7 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
             home[(size_t)s.layer * m.n_kv_heads + s.expert] =
                 (uint64_t)(uintptr_t)(s.resident ? st->arena + s.offset : st->shard_host[i]);
         }
-        if (hipMemcpy(st->arena + p.ws.kvhome, home.data(), home.size() * 8, hipMemcpyHostToDevice) != hipSuccess ||
+        if (hipMemcpy(st->ws_base + p.ws.kvhome, home.data(), home.size() * 8, hipMemcpyHostToDevice) != hipSuccess ||
             hipEventCreateWithFlags(&st->ev_step, hipEventDisableTiming) != hipSuccess) {
             ps::set_error("KV cache set-up failed"); return fail(PS_E_HIP);
         }
@@ -920,14 +956,14 @@ static int32_t forward_impl(ps_stack *st, const void *x_in, void *x_out, const f
         float *lh = reinterpret_cast<float *>(th);
         for (uint32_t l = 0; l < L; ++l)
             std::memcpy(lh + (size_t)l * p.M * E, router_logits + (size_t)l * layer_stride, (size_t)n_valid * E * 4);
-        PS_HIP(hipMemcpyAsync(st->arena + p.ws.logits, th, p.ws.logits_bytes, hipMemcpyHostToDevice, st->compute));
-        st->route_logits = reinterpret_cast<const float *>(st->arena + p.ws.logits);
+        PS_HIP(hipMemcpyAsync(st->ws_base + p.ws.logits, th, p.ws.logits_bytes, hipMemcpyHostToDevice, st->compute));
+        st->route_logits = reinterpret_cast<const float *>(st->ws_base + p.ws.logits);
         st->route_layer_stride = (uint64_t)p.M * E;
     }
     if (!sc.tasks.empty())
-        PS_HIP(hipMemcpyAsync(st->arena + p.ws.tasks, dt, sc.tasks.size() * sizeof(ps::DeviceTask), hipMemcpyHostToDevice, st->compute));
+        PS_HIP(hipMemcpyAsync(st->ws_base + p.ws.tasks, dt, sc.tasks.size() * sizeof(ps::DeviceTask), hipMemcpyHostToDevice, st->compute));
     if (!sc.pairs.empty())
-        PS_HIP(hipMemcpyAsync(st->arena + p.ws.pairs, th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.size() * 4,
+        PS_HIP(hipMemcpyAsync(st->ws_base + p.ws.pairs, th + p.ws.logits_bytes + p.ws.tasks_bytes, sc.pairs.size() * 4,
                               hipMemcpyHostToDevice, st->compute));
     rc = run_schedule(st, sc, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
     // the buffer is free again once the uploads (compute stream) and the gathers (copy stream) are done
@@ -955,6 +991,30 @@ int32_t ps_stack_forward(ps_stack *st, const void *x_in, void *x_out, const floa
     if (rc) return rc;
     const ps_plan &p = st->plan;
     return forward_impl(st, x_in, x_out, router_logits, router_logits_dev, (uint64_t)p.M * p.g.m.n_experts, p.M);
+}
+
+int32_t ps_stack_forward_noalloc(ps_stack *st, const void *x_in, void *x_out) {
+    const int32_t rc0 = forward_checks(st, x_in, x_out);
+    if (rc0) return rc0;
+    const ps_plan &p = st->plan;
+    if (p.g.moe || p.g.kv || p.cpu_bytes) {
+        ps::set_error("ps_stack_forward_noalloc takes dense GPU-only stacks without a KV cache"); return PS_E_STATE;
+    }
+    if (st->profiling) { ps::set_error("ps_stack_forward_noalloc does not record profiling events: switch profiling off"); return PS_E_STATE; }
+    if (p.ws.total > kStaticWsBytes) {
+        ps::set_error("workspace of %llu B for %u tokens exceeds the static scratch of %llu B", (unsigned long long)p.ws.total,
+                      p.M, (unsigned long long)kStaticWsBytes);
+        return PS_E_ARG;
+    }
+    // every kernel of this forward takes its workspace pointers from ws_base: the static array's
+    // address on this device.  Launch per shard (a graph would have to be instantiated).
+    const bool graph = st->use_graph;
+    st->use_graph = false;
+    st->ws_base = st->static_ws;
+    const int32_t rc = forward_impl(st, x_in, x_out, nullptr, nullptr, 0, p.M);
+    st->ws_base = st->arena;
+    st->use_graph = graph;
+    return rc;
 }
 
 int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, uint32_t n_tokens,
@@ -1062,8 +1122,8 @@ int32_t ps_stack_time_kernel(ps_stack *st, uint32_t kernel, uint32_t reps, doubl
     const ps_plan &p = st->plan;
     st->n_valid = p.M;
     // activations: the workspace ping-pong buffers stand in for the caller's tensors
-    const __half *xin = reinterpret_cast<const __half *>(st->arena + p.ws.x0);
-    __half *xout = reinterpret_cast<__half *>(st->arena + p.ws.x1);
+    const __half *xin = reinterpret_cast<const __half *>(st->ws_base + p.ws.x0);
+    __half *xout = reinterpret_cast<__half *>(st->ws_base + p.ws.x1);
     hipEvent_t e0, e1;
     PS_HIP(hipEventCreate(&e0));
     PS_HIP(hipEventCreate(&e1));
@@ -1100,11 +1160,11 @@ int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint
     const ps_plan &p = st->plan;
     const uint64_t P = (uint64_t)p.M * std::max(1u, p.g.m.top_k);
     switch (which) {
-        case 0: *dev_ptr = st->arena + p.ws.qkv; *bytes = p.ws.qkv_bytes; return PS_OK;
-        case 1: *dev_ptr = st->arena + p.ws.h; *bytes = p.ws.h_bytes; return PS_OK;
-        case 2: *dev_ptr = st->arena + p.ws.s; *bytes = p.ws.s_bytes; return PS_OK;
-        case 3: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.ridx; *bytes = P * 4; return PS_OK;
-        case 4: if (!p.g.moe) break; *dev_ptr = st->arena + p.ws.rw; *bytes = P * 4; return PS_OK;
+        case 0: *dev_ptr = st->ws_base + p.ws.qkv; *bytes = p.ws.qkv_bytes; return PS_OK;
+        case 1: *dev_ptr = st->ws_base + p.ws.h; *bytes = p.ws.h_bytes; return PS_OK;
+        case 2: *dev_ptr = st->ws_base + p.ws.s; *bytes = p.ws.s_bytes; return PS_OK;
+        case 3: if (!p.g.moe) break; *dev_ptr = st->ws_base + p.ws.ridx; *bytes = P * 4; return PS_OK;
+        case 4: if (!p.g.moe) break; *dev_ptr = st->ws_base + p.ws.rw; *bytes = P * 4; return PS_OK;
     }
     ps::set_error("no such debug buffer");
     return PS_E_ARG;
