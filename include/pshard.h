@@ -143,7 +143,8 @@ typedef struct ps_shard_info {
                                scratch before each use; 2 = in pinned host memory, run on the CPU */
     uint32_t priority_rank; /* position in the priority order (0 = first)        */
     uint64_t bytes;         /* packed bytes of this shard                        */
-    uint64_t offset;        /* resident: byte offset in the arena; streamed:
+    uint64_t offset;        /* resident: byte offset in the arena (pinned shards fill it from 0 in
+                               priority order; scratch slots and workspace end it); streamed:
                                byte offset in the library's host shard pool      */
 } ps_shard_info;
 
@@ -408,6 +409,23 @@ int32_t ps_plan_create_db(const ps_model_desc *model, uint64_t vram_budget_bytes
  * left in system memory.  The plan is copied; the arena and streams must outlive the stack. */
 int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes,
                         void *compute_stream, void *copy_stream, ps_stack **out);
+/* One stack for every token tier of a budget (Algorithm 1: the planning phase leaves one schedule
+ * per tier; at inference PickTier chooses one, SetupForSched installs it, and the schedule runs).
+ * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans, no KV cache) to one
+ * arena of the table's budget and installs the lowest feasible tier (it pins the most).  Every
+ * tier's arena is laid out [pinned shards in priority order | scratch slots | workspace], so a shard
+ * that two tiers pin lies at the same place in both, and the library keeps a packed image of every
+ * matrix in pinned host memory (the whole model, host side).  ps_stack_set_tier installs another
+ * tier's schedule without reloading or repacking anything: shards the new tier pins and whose bytes
+ * are still in place stay; those that the previous tier's larger workspace or slots overwrote are
+ * copied from the host images again (*uploaded_bytes, may be NULL, receives how much).  It waits
+ * for both streams first; PS_E_STATE before every matrix is loaded or on a single-plan stack,
+ * PS_E_ARG for an infeasible tier.  Outputs do not depend on which tiers ran before.
+ * ps_stack_tier reports the installed tier and its token count (for a single-plan stack: the plan's). */
+int32_t ps_stack_create_tiers(const ps_tier_table *table, void *vram_arena, uint64_t arena_bytes,
+                              void *compute_stream, void *copy_stream, ps_stack **out);
+int32_t ps_stack_set_tier(ps_stack *st, uint32_t tier, uint64_t *uploaded_bytes);
+int32_t ps_stack_tier(const ps_stack *st, uint32_t *tier, uint32_t *n_tokens);
 /* Put one logical matrix where the plan placed it (Algorithm 1, PinShardsToGPU: Residency = VRAM
  * for pinned shards, SysMem for the rest): host scales fp16 [N][K/32] and host codes u8 [N][K] are
  * packed into every shard that covers the matrix; resident slabs are copied to the arena

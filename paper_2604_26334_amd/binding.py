@@ -90,7 +90,7 @@ class ps_op_info(C.Structure):
                 ("slot_offset", C.c_uint64), ("bytes", C.c_uint64)]
 
 
-EXPORTS = ["ps_stack_forward_noalloc", "ps_plan_num_shards", "ps_stack_forward_chunked", "ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
+EXPORTS = ["ps_stack_create_tiers", "ps_stack_set_tier", "ps_stack_tier", "ps_stack_forward_noalloc", "ps_plan_num_shards", "ps_stack_forward_chunked", "ps_last_error", "ps_tier_tokens", "ps_tier_for_tokens", "ps_packed_bytes", "ps_plan_create",
            "ps_plan_summary", "ps_plan_get_shard", "ps_plan_destroy", "ps_schedule_create",
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
@@ -142,6 +142,9 @@ def lib():
             "ps_stack_load_matrix": [vp, u32, u32, u32, vp, vp],
             "ps_stack_forward": [vp, vp, vp, vp, vp],
             "ps_stack_forward_noalloc": [vp, vp, vp],
+            "ps_stack_create_tiers": [vp, vp, u64, vp, vp, C.POINTER(vp)],
+            "ps_stack_set_tier": [vp, u32, C.POINTER(u64)],
+            "ps_stack_tier": [vp, C.POINTER(u32), C.POINTER(u32)],
             "ps_stack_set_profiling": [vp, i32],
             "ps_stack_set_decode_mode": [vp, i32],
             "ps_stack_sync_check": [vp],
@@ -460,10 +463,15 @@ class Stack:
     """ps_stack_*: binds a plan to a torch-owned VRAM arena and two torch streams."""
 
     def __init__(self, plan, device="cuda:0"):
+        """plan: a Plan (ps_stack_create), or a TierTable (ps_stack_create_tiers: every feasible tier of
+        the table on one arena; the lowest feasible tier is installed, set_tier installs another)."""
         import torch
         self.torch = torch
-        self.plan = plan
         self.device = torch.device(device)
+        self.table = plan if isinstance(plan, TierTable) else None
+        if self.table is not None:
+            plan = self.table.plan(next(t for t in range(PS_NTIERS) if self.table.entry(t).feasible))
+        self.plan = plan
         s = plan.summary()
         self.M = s.n_tokens
         self.H = plan.cfg["hidden"]
@@ -472,8 +480,26 @@ class Stack:
         self.copy = torch.cuda.Stream(device=self.device)
         self.h = C.c_void_p()
         with torch.cuda.device(self.device):
-            _check(lib().ps_stack_create(plan.h, self.arena.data_ptr(), self.arena.numel(),
-                                         self.compute.cuda_stream, self.copy.cuda_stream, C.byref(self.h)))
+            if self.table is not None:
+                _check(lib().ps_stack_create_tiers(self.table.h, self.arena.data_ptr(), self.arena.numel(),
+                                                   self.compute.cuda_stream, self.copy.cuda_stream, C.byref(self.h)))
+            else:
+                _check(lib().ps_stack_create(plan.h, self.arena.data_ptr(), self.arena.numel(),
+                                             self.compute.cuda_stream, self.copy.cuda_stream, C.byref(self.h)))
+
+    def set_tier(self, tier):
+        """ps_stack_set_tier: install another tier's schedule; returns the bytes pinned again from the host."""
+        up = C.c_uint64()
+        with self.torch.cuda.device(self.device):
+            _check(lib().ps_stack_set_tier(self.h, int(tier), C.byref(up)))
+        self.plan = self.table.plan(tier)
+        self.M = self.plan.summary().n_tokens
+        return up.value
+
+    def tier(self):
+        t, n = C.c_uint32(), C.c_uint32()
+        _check(lib().ps_stack_tier(self.h, C.byref(t), C.byref(n)))
+        return t.value, n.value
 
     def load_matrix(self, layer, mat, expert, scales, codes):
         s = np.ascontiguousarray(scales)

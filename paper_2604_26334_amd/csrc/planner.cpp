@@ -402,29 +402,32 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
 
     // DecideScratchVRAMBudget: none if everything fits, else a double buffer.  Plan Two gives the
     // scratch to the pinned region when every shard that must run on the GPU can be pinned.
-    bool need_slots = p->ws.total + p->weight_bytes > budget;
+    // the workspace ends the arena, the two slots lie in front of it, the pinned region starts at 0
+    p->ws_off = (budget - p->ws.total) / kAlign * kAlign;
+    bool need_slots = p->weight_bytes > p->ws_off;
     if (need_slots && kind == PS_PLAN_STATIC) {
-        pin(budget - p->ws.total);
+        pin(p->ws_off);
         need_slots = false;
         for (size_t i = 0; i < cands.size(); ++i) need_slots |= !fully_pinned(i) && !cpu_eligible(cands[i].s);
     }
     if (!need_slots) {
         p->n_slots = 0; p->slot_bytes = 0;
-        pin(budget - p->ws.total);
+        p->scratch_off = p->ws_off;
+        pin(p->scratch_off);
     } else {
         uint64_t lo = std::min<uint64_t>(1ull << 20, budget / 8), hi = 64ull << 20;
         uint64_t slot = std::min(std::max(budget / 16, lo), hi) / kAlign * kAlign;
         if (slot < max_unit) slot = align_up(max_unit, kAlign);
         p->slot_bytes = slot; p->n_slots = 2;
-        if (p->ws.total + 2 * slot > budget) {
+        if (p->ws.total + 2 * slot > budget || p->ws_off < 2 * slot) {
             set_error("budget %llu B < workspace %llu B + 2 scratch slots of %llu B",
                       (unsigned long long)budget, (unsigned long long)p->ws.total, (unsigned long long)slot);
             return PS_E_BUDGET;
         }
-        pin(budget - p->ws.total - 2 * slot);
+        p->scratch_off = p->ws_off - 2 * slot;
+        pin(p->scratch_off);
     }
-    p->scratch_off = p->ws.total;
-    p->pinned_off = p->scratch_off + (uint64_t)p->n_slots * p->slot_bytes;
+    p->pinned_off = 0;
 
     // Emit shards in execution order; streamed remainders are cut into slabs that fit a slot; the
     // CPU's part of a matrix is its tail, one shard.  Arena offsets of resident shards follow
@@ -439,7 +442,7 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
             res_off[order[r]] = off;
             off += b;
         }
-        if (off > budget) { set_error("internal: pinned region overflows the budget"); return PS_E_STATE; }
+        if (off > p->scratch_off) { set_error("internal: pinned region overflows the budget"); return PS_E_STATE; }
     }
     // unpinned experts: the share cpu_frac at the cold end of the priority order stays on the CPU
     std::vector<char> expert_on_cpu(cands.size(), 0);

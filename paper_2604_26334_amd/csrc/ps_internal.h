@@ -89,7 +89,10 @@ struct ps_plan {
     uint64_t budget = 0;
     uint32_t M = 0, tier = 0;
     ps::Workspace ws;
-    uint64_t slot_bytes = 0, scratch_off = 0, pinned_off = 0;
+    // arena layout: [pinned shards in priority order from 0 | (free) | slot 0 | slot 1 | workspace]:
+    // the workspace and the slots sit at the END, so that a shard pinned in two token tiers' plans
+    // under one budget has the same arena offset in both (the tiers differ in workspace size only)
+    uint64_t slot_bytes = 0, scratch_off = 0, pinned_off = 0, ws_off = 0;
     uint32_t n_slots = 0;
     std::vector<ps::Shard> shards;  // execution order
     uint64_t weight_bytes = 0, resident_bytes = 0, streamed_bytes = 0, cpu_bytes = 0;

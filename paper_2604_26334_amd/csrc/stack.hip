@@ -33,6 +33,14 @@ struct ps_stack {
     ps_plan plan;
     uint8_t *arena = nullptr;
     uint64_t arena_bytes = 0;
+    // several token tiers on one arena (ps_stack_create_tiers): every tier's plan, the packed image of
+    // every matrix in pinned host memory, and what each stretch of the pinned region holds right now
+    bool multi = false;
+    std::vector<ps_plan> tiers;               // by tier index; a plan with M == 0 marks an infeasible tier
+    uint32_t active_tier = 0;
+    std::map<std::tuple<uint32_t, uint32_t, uint32_t>, uint8_t *> image;   // (layer, shard kind, expert) -> whole matrix
+    struct Content { uint64_t off, bytes, tile_bytes; uint32_t layer, kind, expert, tile0; };
+    std::vector<Content> content;
     uint8_t *static_ws = nullptr;             // this device's address of the library's static scratch
     uint8_t *ws_base = nullptr;               // where the workspace offsets of the plan count from: the arena,
                                               // or the library's static scratch during ps_stack_forward_noalloc
@@ -643,25 +651,91 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
 
 extern "C" {
 
-int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes, void *compute_stream,
-                        void *copy_stream, ps_stack **out) {
-    if (!plan || !vram_arena || !out) { ps::set_error("NULL argument"); return PS_E_ARG; }
-    *out = nullptr;
+}  // extern "C"
+
+namespace {
+
+// tile size of the matrix a shard is cut from (0: whole shards, never split)
+uint64_t shard_tile_bytes(const ps::ModelGeom &g, uint32_t kind) {
+    switch (kind) {
+        case PS_SHARD_QKV: return g.qkv.tile_bytes;
+        case PS_SHARD_O: return g.o.tile_bytes;
+        case PS_SHARD_GATE_UP: return g.gate_up.tile_bytes;
+        case PS_SHARD_DOWN: return g.down.tile_bytes;
+        case PS_SHARD_OUT: return g.head.tile_bytes;
+    }
+    return 0;
+}
+
+// Everything a stack derives from its current plan (Algorithm 1, SetupForSched): where the workspace
+// lies, where each shard's host copy is, which shards cover which matrix, the dense schedule.
+int32_t bind_plan(ps_stack *st) {
+    const ps_plan &p = st->plan;
+    st->n_valid = p.M;
+    st->ws_base = st->arena + p.ws_off;
+    st->cover.clear();
+    for (size_t i = 0; i < p.shards.size(); ++i)
+        st->cover[std::make_tuple(p.shards[i].layer, p.shards[i].kind, p.shards[i].expert)].push_back((uint32_t)i);
+    if (st->multi) {   // every shard is a run of tiles of its matrix's image
+        st->shard_host.assign(p.shards.size(), nullptr);
+        for (size_t i = 0; i < p.shards.size(); ++i) {
+            const ps::Shard &sh = p.shards[i];
+            auto it = st->image.find(std::make_tuple(sh.layer, sh.kind, sh.expert));
+            if (it == st->image.end()) { ps::set_error("internal: shard without a matrix image"); return PS_E_STATE; }
+            st->shard_host[i] = it->second + (uint64_t)sh.tile0 * shard_tile_bytes(p.g, sh.kind);
+        }
+    }
+    if (p.g.moe) {
+        st->descs_off = ps::align_up(p.ws.logits_bytes + p.ws.tasks_bytes + p.ws.pairs_bytes, 256);
+    } else {
+        st->dense_sched = ps_schedule();
+        int32_t rc = ps::build_schedule(&st->plan, nullptr, &st->dense_sched);
+        if (rc) return rc;
+        rc = ps::validate_schedule(&st->dense_sched);
+        if (rc) return rc;
+        st->have_dense_sched = true;
+    }
+    return PS_OK;
+}
+
+// plans: one plan (ps_stack_create), or the PS_NTIERS plans of a tier table (null where infeasible)
+int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi, void *vram_arena, uint64_t arena_bytes,
+                          void *compute_stream, void *copy_stream, ps_stack **out) {
+    const ps_plan *plan = nullptr;       // the plan installed first: the lowest feasible tier (it pins the most)
+    uint32_t first = 0;
+    for (uint32_t t = 0; t < plans.size() && !plan; ++t)
+        if (plans[t]) { plan = plans[t]; first = t; }
+    if (!plan) { ps::set_error("no feasible tier"); return PS_E_BUDGET; }
     if (arena_bytes < plan->budget) {
         ps::set_error("arena of %llu B is smaller than the plan's budget %llu B", (unsigned long long)arena_bytes,
                       (unsigned long long)plan->budget);
         return PS_E_ARG;
     }
     if ((uintptr_t)vram_arena % ps::kAlign) { ps::set_error("arena must be 256-byte aligned"); return PS_E_ARG; }
-    if (compute_stream == copy_stream && plan->n_slots) {
+    bool any_slots = false;
+    for (const ps_plan *q : plans) {
+        if (!q) continue;
+        any_slots |= q->n_slots != 0;
+        if (multi && (q->cpu_bytes || q->g.kv)) {
+            ps::set_error("a stack of several tiers takes GPU-only plans without a KV cache"); return PS_E_ARG;
+        }
+    }
+    if (compute_stream == copy_stream && any_slots) {
         ps::set_error("streamed shards need distinct compute and copy streams"); return PS_E_ARG;
     }
     ps_stack *st = new (std::nothrow) ps_stack();
     if (!st) { ps::set_error("out of host memory"); return PS_E_NOMEM; }
     st->plan = *plan;
+    st->multi = multi;
+    if (multi) {
+        st->tiers.resize(plans.size());
+        for (size_t t = 0; t < plans.size(); ++t)
+            if (plans[t]) st->tiers[t] = *plans[t];
+        st->active_tier = first;
+    }
     st->n_valid = plan->M;
     st->arena = static_cast<uint8_t *>(vram_arena);
-    st->ws_base = st->arena;
+    st->ws_base = st->arena + plan->ws_off;
     {   // set-up for ps_stack_forward_noalloc: this device's address of the static scratch
         const int32_t rc = static_scratch(&st->static_ws);
         if (rc) { delete st; return rc; }
@@ -675,7 +749,39 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     const auto &m = p.g.m;
     // host pools for streamed shards: chunks of at most 1 GiB, a shard never straddles chunks
     st->shard_host.assign(p.shards.size(), nullptr);
-    {
+    if (multi) {
+        // one image per matrix (per expert), whatever the tiers do with it: any tier's shard is a run
+        // of its tiles, and a shard that another tier's workspace displaced can be pinned again from it
+        std::vector<std::pair<std::tuple<uint32_t, uint32_t, uint32_t>, uint64_t>> mats;
+        for (uint32_t l = 0; l < m.n_layers; ++l) {
+            if (p.g.has_attn) {
+                mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_QKV, ps::kNoExpert), p.g.qkv.bytes});
+                mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_O, ps::kNoExpert), p.g.o.bytes});
+            }
+            if (!p.g.moe) {
+                mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_GATE_UP, ps::kNoExpert), p.g.gate_up.bytes});
+                mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_DOWN, ps::kNoExpert), p.g.down.bytes});
+            } else {
+                for (uint32_t e = 0; e < m.n_experts; ++e) mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_EXPERT, e), p.g.expert_bytes});
+            }
+        }
+        if (m.vocab) mats.push_back({std::make_tuple(m.n_layers, (uint32_t)PS_SHARD_OUT, ps::kNoExpert), p.g.head.bytes});
+        std::vector<uint64_t> chunk_bytes;
+        std::vector<std::pair<size_t, uint64_t>> place(mats.size());
+        for (size_t i = 0; i < mats.size(); ++i) {
+            if (chunk_bytes.empty() || chunk_bytes.back() + mats[i].second > kHostChunk) chunk_bytes.push_back(0);
+            place[i] = {chunk_bytes.size() - 1, chunk_bytes.back()};
+            chunk_bytes.back() += mats[i].second;
+        }
+        for (uint64_t b : chunk_bytes) {
+            void *ptr = nullptr;
+            hipError_t e = hipHostMalloc(&ptr, b, hipHostMallocDefault);
+            if (e != hipSuccess) { ps::set_error("hipHostMalloc(%llu) failed: %s", (unsigned long long)b, hipGetErrorString(e)); return fail(PS_E_HIP); }
+            st->host_chunks.push_back(ptr);
+        }
+        for (size_t i = 0; i < mats.size(); ++i)
+            st->image[mats[i].first] = static_cast<uint8_t *>(st->host_chunks[place[i].first]) + place[i].second;
+    } else {
         std::vector<std::pair<size_t, uint64_t>> place(p.shards.size());  // chunk, offset
         std::vector<uint64_t> chunk_bytes;
         for (size_t i = 0; i < p.shards.size(); ++i) {
@@ -693,8 +799,6 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         for (size_t i = 0; i < p.shards.size(); ++i)
             if (p.shards[i].resident != 1) st->shard_host[i] = static_cast<uint8_t *>(st->host_chunks[place[i].first]) + place[i].second;
     }
-    for (size_t i = 0; i < p.shards.size(); ++i)
-        st->cover[std::make_tuple(p.shards[i].layer, p.shards[i].kind, p.shards[i].expert)].push_back((uint32_t)i);
     const uint32_t per_layer = (p.g.has_attn ? 2 : 0) + 3 * (p.g.moe ? m.n_experts : 1);
     st->n_expected = (uint64_t)per_layer * m.n_layers + (m.vocab ? 1 : 0);
     st->loaded.assign(st->n_expected, 0);
@@ -709,20 +813,21 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
         st->ev_router.resize(m.n_layers);
         for (auto &e : st->ev_router)
             if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
-        st->descs_off = ps::align_up(p.ws.logits_bytes + p.ws.tasks_bytes + p.ws.pairs_bytes, 256);
-        st->tables_bytes = st->descs_off + (p.ws.tasks_bytes / sizeof(ps::DeviceTask)) * sizeof(ps::CopyDesc);
+        for (const ps_plan *q : plans) {   // room for the largest tier's tables
+            if (!q) continue;
+            const uint64_t d = ps::align_up(q->ws.logits_bytes + q->ws.tasks_bytes + q->ws.pairs_bytes, 256);
+            st->tables_bytes = std::max(st->tables_bytes, d + (q->ws.tasks_bytes / sizeof(ps::DeviceTask)) * sizeof(ps::CopyDesc));
+        }
         for (int b = 0; b < 2; ++b) {
             if (hipEventCreateWithFlags(&st->ev_upload[b], hipEventDisableTiming) != hipSuccess) { ps::set_error("hipEventCreate failed"); return fail(PS_E_HIP); }
             if (hipHostMalloc(&st->tables_host[b], st->tables_bytes, hipHostMallocDefault) != hipSuccess) {
                 ps::set_error("hipHostMalloc for routing tables failed"); return fail(PS_E_HIP);
             }
         }
-    } else {
-        int32_t rc = ps::build_schedule(&st->plan, nullptr, &st->dense_sched);
+    }
+    {
+        const int32_t rc = bind_plan(st);
         if (rc) return fail(rc);
-        rc = ps::validate_schedule(&st->dense_sched);
-        if (rc) return fail(rc);
-        st->have_dense_sched = true;
     }
     if (p.cpu_bytes) {
         if (!ps::cpu_backend_supported()) { ps::set_error("the CPU back-end needs AVX-512 (F, BW, VL, DQ) and F16C"); return fail(PS_E_STATE); }
@@ -768,6 +873,99 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
     return PS_OK;
 }
 
+// [C, end of arena) is about to be, or has been, used as scratch and workspace: what was pinned there is gone
+void clobber_from(ps_stack *st, uint64_t C) {
+    std::vector<ps_stack::Content> keep;
+    for (ps_stack::Content r : st->content) {
+        if (r.off + r.bytes <= C) { keep.push_back(r); continue; }
+        if (r.off >= C || !r.tile_bytes) continue;
+        const uint64_t nt = (C - r.off) / r.tile_bytes;      // whole tiles in front of C survive
+        if (!nt) continue;
+        r.bytes = nt * r.tile_bytes;
+        keep.push_back(r);
+    }
+    st->content.swap(keep);
+}
+
+void note_content(ps_stack *st, const ps::Shard &sh) {
+    const uint64_t tb = shard_tile_bytes(st->plan.g, sh.kind);
+    for (const ps_stack::Content &r : st->content)
+        if (r.off == sh.offset && r.bytes == sh.bytes && r.layer == sh.layer && r.kind == sh.kind && r.expert == sh.expert && r.tile0 == sh.tile0) return;
+    std::vector<ps_stack::Content> keep;
+    for (const ps_stack::Content &r : st->content)
+        if (r.off + r.bytes <= sh.offset || r.off >= sh.offset + sh.bytes) keep.push_back(r);
+    keep.push_back(ps_stack::Content{sh.offset, sh.bytes, tb, sh.layer, sh.kind, sh.expert, sh.tile0});
+    st->content.swap(keep);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_bytes, void *compute_stream,
+                        void *copy_stream, ps_stack **out) {
+    if (!plan || !vram_arena || !out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    *out = nullptr;
+    return stack_create_impl({plan}, false, vram_arena, arena_bytes, compute_stream, copy_stream, out);
+}
+
+int32_t ps_stack_create_tiers(const ps_tier_table *table, void *vram_arena, uint64_t arena_bytes, void *compute_stream,
+                              void *copy_stream, ps_stack **out) {
+    if (!table || !vram_arena || !out) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    *out = nullptr;
+    std::vector<const ps_plan *> plans(table->plans, table->plans + PS_NTIERS);
+    return stack_create_impl(plans, true, vram_arena, arena_bytes, compute_stream, copy_stream, out);
+}
+
+int32_t ps_stack_tier(const ps_stack *st, uint32_t *tier, uint32_t *n_tokens) {
+    if (!st || !tier || !n_tokens) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    *tier = st->multi ? st->active_tier : st->plan.tier;
+    *n_tokens = st->plan.M;
+    return PS_OK;
+}
+
+int32_t ps_stack_set_tier(ps_stack *st, uint32_t tier, uint64_t *uploaded_bytes) {
+    if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (uploaded_bytes) *uploaded_bytes = 0;
+    if (!st->multi) { ps::set_error("this stack was created for one plan (use ps_stack_create_tiers)"); return PS_E_STATE; }
+    if (tier >= st->tiers.size() || st->tiers[tier].M == 0) { ps::set_error("tier %u has no plan under this budget", tier); return PS_E_ARG; }
+    if (st->n_loaded != st->n_expected) { ps::set_error("set the tier once all matrices are loaded"); return PS_E_STATE; }
+    // no forward of the old tier may be in flight while its workspace moves and shards are pinned again
+    PS_HIP(hipStreamSynchronize(st->copy));
+    PS_HIP(hipStreamSynchronize(st->compute));
+    if (tier == st->active_tier) return PS_OK;
+    for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
+    st->graphs.clear();
+    // the tier that ran until now used the tail of the arena from its slots on; so will the new one
+    clobber_from(st, std::min(st->plan.scratch_off, st->tiers[tier].scratch_off));
+    st->plan = st->tiers[tier];
+    st->active_tier = tier;
+    const int32_t rc = bind_plan(st);
+    if (rc) return rc;
+    const ps_plan &p = st->plan;
+    uint64_t up = 0;
+    for (size_t i = 0; i < p.shards.size(); ++i) {
+        const ps::Shard &sh = p.shards[i];
+        if (sh.resident != 1) continue;
+        // bytes of the shard already in place: a record of the same matrix under the same tile -> address map
+        uint64_t have = 0;
+        const uint64_t tb = shard_tile_bytes(p.g, sh.kind);
+        for (const ps_stack::Content &r : st->content) {
+            if (r.layer != sh.layer || r.kind != sh.kind || r.expert != sh.expert) continue;
+            if (r.off - (uint64_t)r.tile0 * tb != sh.offset - (uint64_t)sh.tile0 * tb) continue;
+            if (r.off <= sh.offset && r.off + r.bytes > sh.offset) have = std::max(have, std::min(sh.bytes, r.off + r.bytes - sh.offset));
+        }
+        if (have < sh.bytes) {
+            PS_HIP(hipMemcpyAsync(st->arena + sh.offset + have, st->shard_host[i] + have, sh.bytes - have, hipMemcpyHostToDevice, st->compute));
+            up += sh.bytes - have;
+        }
+        note_content(st, sh);
+    }
+    PS_HIP(hipStreamSynchronize(st->compute));
+    if (uploaded_bytes) *uploaded_bytes = up;
+    return PS_OK;
+}
+
 int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_t expert,
                              const uint16_t *scales, const uint8_t *codes) {
     if (!st || !scales || !codes) { ps::set_error("NULL argument"); return PS_E_ARG; }
@@ -798,6 +996,30 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
     const uint32_t step = paired ? 2 : 1;
     const uint64_t pitch = mg.tile_bytes * step;
 
+    if (st->multi) {
+        // the whole matrix goes into its host image; what the installed tier pinned of it is copied
+        // from there to the arena and noted as that stretch's content
+        auto im = st->image.find(std::make_tuple(layer, kind, kind == PS_SHARD_EXPERT ? expert : ps::kNoExpert));
+        if (im == st->image.end()) { ps::set_error("internal: no image for this matrix"); return PS_E_STATE; }
+        const bool ex = kind == PS_SHARD_EXPERT;
+        const uint32_t nt_all = ex ? (mat == PS_MAT_DOWN ? g.down.ntiles : g.gate_up.ntiles) : mg.ntiles;
+        const uint64_t base_off = ex && mat == PS_MAT_DOWN ? g.gate_up.bytes : 0;
+        uint8_t *img = im->second + base_off;
+        const uint32_t count_all = (nt_all + step - 1 - parity) / step;
+        parallel_for(count_all, [&](uint32_t j) {
+            const uint32_t pt = parity + j * step;
+            ps::pack_tile(mg, scales, codes, paired ? pt / 2 : pt, img + (uint64_t)pt * mg.tile_bytes);
+        });
+        for (uint32_t si : it->second) {
+            const ps::Shard &s = p.shards[si];
+            if (s.resident != 1) continue;
+            const uint32_t t0 = ex ? 0 : s.tile0, nt = ex ? nt_all : s.ntiles;
+            const uint32_t n = (nt + step - 1 - parity) / step;
+            PS_HIP(hipMemcpy2D(st->arena + s.offset + base_off + (uint64_t)parity * mg.tile_bytes, pitch,
+                               img + (uint64_t)(t0 + parity) * mg.tile_bytes, pitch, mg.tile_bytes, n, hipMemcpyHostToDevice));
+            note_content(st, s);
+        }
+    } else
     for (uint32_t si : it->second) {
         const ps::Shard &s = p.shards[si];
         uint32_t t0 = s.tile0, nt = s.ntiles;
@@ -1012,7 +1234,7 @@ int32_t ps_stack_forward_noalloc(ps_stack *st, const void *x_in, void *x_out) {
     st->use_graph = false;
     st->ws_base = st->static_ws;
     const int32_t rc = forward_impl(st, x_in, x_out, nullptr, nullptr, 0, p.M);
-    st->ws_base = st->arena;
+    st->ws_base = st->arena + p.ws_off;
     st->use_graph = graph;
     return rc;
 }

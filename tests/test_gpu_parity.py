@@ -272,6 +272,85 @@ def test_chunked_prefill_through_the_tier_table(kind):
     assert streamed[-1] > 0 and streamed == sorted(streamed)
 
 
+@pytest.mark.parametrize("kind", ["dense", "moe"])
+def test_one_stack_serves_the_prefill_tier_and_the_decode_tier(kind):
+    """Algorithm 1's inference phase on ONE stack and one arena: SetupForSched for the prefill tier,
+    a chunked prefill, SetupForSched for the one-token tier (shards that the larger workspace had
+    displaced are pinned again from the host images), decode steps, and back again.  Every result
+    against the oracle and bit-identical to a stack built for that tier alone."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    n, steps = 150, 4
+    if kind == "dense":
+        cfg = Hn.small_dense_cfg(3)
+        lg_p, lg_d = None, [None] * steps
+    else:
+        cfg = Hn.small_moe_cfg(3)
+        lg_p = S.router_logits(21, 0, cfg["n_layers"], n, cfg["n_experts"])
+        lg_d = [S.router_logits(21, 1 + t, cfg["n_layers"], 1, cfg["n_experts"]) for t in range(steps)]
+    W = Hn.WeightCache(cfg, 21)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    ws64 = B.Plan(cfg, 1 << 62, 64).summary().workspace_bytes
+    budget = int(wb * 0.7) + ws64
+    table = B.TierTable(cfg, budget)
+    t_pre, t_dec = 4, 0                                   # 64 tokens per trip; one token
+    e_pre, e_dec = table.entry(t_pre), table.entry(t_dec)
+    assert e_pre.feasible and e_dec.feasible and e_dec.summary.resident_bytes > e_pre.summary.resident_bytes
+    x = S.activations(21, 0, n, cfg["hidden"])
+    xd = [S.activations(21, 1 + t, 1, cfg["hidden"]) for t in range(steps)]
+    ref_p = O.stack_forward(x, cfg, W, logits=lg_p, mirror=True)
+    ref_d = [O.stack_forward(xd[t], cfg, W, logits=lg_d[t], mirror=True) for t in range(steps)]
+
+    def load(st):
+        for layer in range(cfg["n_layers"]):
+            for k, ex, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, ex, *W(layer, k, ex))
+
+    def prefill(st):
+        xin = torch.from_numpy(x).to(st.device)
+        xout = torch.zeros_like(xin)
+        torch.cuda.synchronize()
+        B.chunked_forward(st, xin, xout, lg_p)
+        st.synchronize()
+        return xout.cpu().numpy()
+
+    def decode(st):
+        outs = []
+        for t in range(steps):
+            xin = torch.from_numpy(xd[t]).to(st.device)
+            xout = torch.zeros_like(xin)
+            st.forward(xin, xout, lg_d[t])
+            st.synchronize()
+            outs.append(xout.cpu().numpy())
+        return outs
+
+    alone = {}
+    for t, run in ((t_pre, prefill), (t_dec, decode)):    # the per-tier stacks
+        st = B.Stack(table.plan(t))
+        load(st)
+        alone[t] = run(st)
+        st.close()
+    st = B.Stack(table)
+    load(st)
+    assert st.tier() == (0, 1)                            # the lowest tier is installed first
+    for rnd in range(2):
+        up = st.set_tier(t_pre)
+        assert st.tier() == (t_pre, 64)
+        got = prefill(st)
+        np.testing.assert_array_equal(got.view(np.uint16), alone[t_pre].view(np.uint16))
+        assert Hn.rel_err(got, ref_p) <= TOL
+        up = st.set_tier(t_dec)
+        _say(kind, "round", rnd, "back to the one-token tier: %d B pinned again (tier pins %d B, prefill tier %d B)" % (
+            up, e_dec.summary.resident_bytes, e_pre.summary.resident_bytes))
+        assert 0 < up <= e_dec.summary.resident_bytes     # only what the prefill tier's workspace displaced
+        for a, b, r in zip(decode(st), alone[t_dec], ref_d):
+            np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
+            assert Hn.rel_err(a, r) <= TOL
+    with pytest.raises(B.PshardError):
+        st.set_tier(10)                                   # 16384 tokens: no plan under this budget
+    st.close()
+
+
 def _kv_cfg(n_layers, cap):
     return dict(Hn.small_dense_cfg(n_layers), kv_context=cap)
 

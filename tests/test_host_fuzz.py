@@ -49,12 +49,14 @@ def _check_plan(cfg, plan, M, logits):
             if y.resident == 2:
                 assert kind in (B.PS_SHARD_GATE_UP, B.PS_SHARD_DOWN, B.PS_SHARD_OUT, B.PS_SHARD_EXPERT)
                 assert s.plan_kind != B.PS_PLAN_GPU_ONLY
-    # pinned shards do not overlap and lie behind workspace and scratch
+    # pinned shards do not overlap, start the arena in priority order, and end before scratch and workspace
     res = sorted((x.offset, x.bytes) for x in sh if x.resident == 1)
     for (o0, b0), (o1, _) in zip(res, res[1:]):
         assert o0 + b0 <= o1
     if res:
-        assert res[0][0] >= s.workspace_bytes + s.scratch_bytes and res[-1][0] + res[-1][1] <= s.budget_bytes
+        assert res[0][0] == 0 and res[-1][0] + res[-1][1] + s.scratch_bytes + s.workspace_bytes <= s.budget_bytes
+        by_rank = sorted((x.priority_rank, x.offset) for x in sh if x.resident == 1)
+        assert [o for _, o in by_rank] == sorted(o for _, o in by_rank)
     sched = plan.schedule(logits)
     assert sched.validate() is None
     ops = sched.ops()
