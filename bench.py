@@ -150,16 +150,21 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps, bias_seed=7):
             if auto.summary().plan_kind != B.PS_PLAN_GPU_ONLY:
                 plans.append(auto)
                 tags.append((m, "batch_%d_%s" % (m, names[auto.summary().plan_kind]), None))
-    uniq = []
-    for p in plans:
-        if not any(p is q for q in uniq):
-            uniq.append(p)
-    stacks = {id(p): B.Stack(p) for p in uniq}
-    t0 = time.perf_counter()
-    B.load_synthetic(list(stacks.values()), cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
-    log("loaded %d MoE stacks in %.1f s" % (len(stacks), time.perf_counter() - t0))
-    dev = next(iter(stacks.values())).device
+    stacks, cur_m = {}, None
     for (m, tag, bias), plan in zip(tags, plans):
+        if m != cur_m:      # one token count at a time: each stack keeps its unpinned experts (11 GB) in pinned host memory
+            for st in stacks.values():
+                st.close()
+            uniq = []
+            for (m2, _t, _b), p2 in zip(tags, plans):
+                if m2 == m and not any(p2 is q for q in uniq):
+                    uniq.append(p2)
+            stacks = {id(p2): B.Stack(p2) for p2 in uniq}
+            t0 = time.perf_counter()
+            B.load_synthetic(list(stacks.values()), cfg, seed, threads=min(16, os.cpu_count() or 8), progress=6000)
+            log("loaded %d MoE stacks (%d token(s) per step) in %.1f s" % (len(stacks), m, time.perf_counter() - t0))
+            dev = next(iter(stacks.values())).device
+            cur_m = m
         st = stacks[id(plan)]
         s = plan.summary()
         xs = [torch.from_numpy(S.activations(seed, 300 + t, m, cfg["hidden"])).to(dev) for t in range(4)]
@@ -243,6 +248,52 @@ def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
     best = min(out["tiers"], key=lambda k: out["tiers"][k]["ttft_ms"])
     out["measured_best_tier_tokens"] = int(best)
     return out
+
+
+def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, decode_mode):
+    """The paper's operating mode under ONE budget on ONE stack: the tier table is planned once,
+    PickTier chooses the prefill tier for a prompt of `prompt` tokens, the chunked prefill runs (TTFT),
+    the one-token tier is installed (SetupForSched: shards that the prefill tier's workspace displaced
+    are pinned again from the host images) and `decode_steps` tokens are decoded (TPS)."""
+    table = B.TierTable(cfg, int(budget), profile=prof)
+    choice = table.pick(prompt)
+    st = B.Stack(table)
+    st.set_decode_mode(decode_mode)
+    B.load_synthetic([st], cfg, seed, threads=min(16, os.cpu_count() or 8))
+    dev = st.device
+    x = torch.from_numpy(S.activations(seed, 600, prompt, cfg["hidden"])).to(dev)
+    y = torch.empty_like(x)
+    xs = [torch.from_numpy(S.activations(seed, 601 + t, 1, cfg["hidden"])).to(dev) for t in range(4)]
+    yo = torch.empty_like(xs[0])
+    res = []
+    for rep in range(3):                      # the first round warms up (graph capture, first touches)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        up_pre = st.set_tier(choice.tier)
+        t1 = time.perf_counter()
+        trips = B.chunked_forward(st, x, y)
+        st.synchronize()
+        t2 = time.perf_counter()
+        up_dec = st.set_tier(0)
+        t3 = time.perf_counter()
+        for i in range(decode_steps):
+            st.forward(xs[i % 4], yo)
+        st.synchronize()
+        t4 = time.perf_counter()
+        res.append(dict(setup_prefill_ms=(t1 - t0) * 1e3, ttft_ms=(t2 - t1) * 1e3, setup_decode_ms=(t3 - t2) * 1e3,
+                        decode_ms_per_token=(t4 - t3) * 1e3 / decode_steps, pinned_again_bytes_prefill=up_pre,
+                        pinned_again_bytes_decode=up_dec, trips=trips))
+    r = res[-1]
+    e_pre, e_dec = table.entry(choice.tier), table.entry(0)
+    r.update(budget_bytes=int(budget), prompt_tokens=prompt, picked_tier_tokens=choice.tier_tokens, decode_steps=decode_steps,
+             tokens_per_s=1e3 / r["decode_ms_per_token"], est_ttft_ms=choice.est_total_ms, est_decode_ms=e_dec.summary.est_step_ms,
+             resident_bytes_prefill_tier=e_pre.summary.resident_bytes, resident_bytes_decode_tier=e_dec.summary.resident_bytes,
+             e2el_ms_100_tokens=r["ttft_ms"] + r["setup_decode_ms"] + 100 * r["decode_ms_per_token"])
+    log("one stack, budget %.0f GB: prefill %d tokens in tier %d x %d trips: TTFT %.1f ms; switch to the one-token tier %.2f ms (%.1f MB pinned again); decode %.3f ms/token = %.1f tok/s" % (
+        budget / 1e9, prompt, choice.tier_tokens, r["trips"], r["ttft_ms"], r["setup_decode_ms"], r["pinned_again_bytes_decode"] / 1e6,
+        r["decode_ms_per_token"], r["tokens_per_s"]))
+    st.close()
+    return r
 
 
 def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps, decode_mode=1):
@@ -400,8 +451,9 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="0 skips the TTFT leg")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle baseline runs, 0 skips")
     ap.add_argument("--cpu-reps", type=int, default=4, help="tokens the oracle baseline runs")
-    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,kv,head,plans",
-                    help="further legs: batch64 (config 5, plus 4 and 16 tokens), moe (config 4), tiers (tier table + chunked prefill at 2 GB), "
+    ap.add_argument("--extra", type=str, default="batch64,moe,tiers,session,kv,head,plans",
+                    help="further legs: batch64 (config 5, plus 4 and 16 tokens), moe (config 4, with the hot-expert variant), tiers (tier table + chunked prefill at 2 GB), "
+                         "session (prefill then decode on one stack: tier table, PickTier, tier switch), "
                          "kv (decode over a 16K-position KV cache), head (decode with a 128256-row output head), "
                          "plans (GPU-only / static / dynamic plan and HeuristicSplit's pick at 2 GB)")
     ap.add_argument("--measure-profile", type=int, default=1)
@@ -476,6 +528,14 @@ def main():
         results["%g" % (b / 1e9)] = r
         log("budget %.0f GB: %.3f ms/token, %.1f tok/s" % (b / 1e9, ms, 1e3 / ms), {k: round(v["avg_ms"] * 1e3, 2) for k, v in r["kernels"].items()})
 
+    # which of the cycled activation draws keep the fp16 residual stream finite through all layers (the
+    # prescribed weights have a non-zero mean; the others end in inf/NaN rows, on the GPU as in the oracle)
+    finite_draws = []
+    for i, x in enumerate(xs):
+        stacks[0].forward(x, xout)
+        stacks[0].synchronize()
+        if bool(torch.isfinite(xout).all().item()):
+            finite_draws.append(i)
     head = results["%g" % (budgets[0] / 1e9)]
     # dominant kernel of the headline run: the fused gate/up + SwiGLU GEMV (54% of the bytes)
     gu = head["kernels"].get("kernel_%d" % B.PS_K_GATE_UP)
@@ -486,10 +546,19 @@ def main():
         iso_ms, iso_n = stacks[0].time_kernel(B.PS_K_GATE_UP, 10)
         gu = dict(gu, avg_ms=iso_ms, bracketed_avg_ms=gu["avg_ms"])
         ach = gu["bytes_per_launch"] / (gu["avg_ms"] * 1e-3) / 1e9
+        ach_in_step = gu["bytes_per_launch"] / (gu["bracketed_avg_ms"] * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel="gemv_w4_kernel<GATE_UP>", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=ach / HBM_PEAK_GBS, traffic=measured_traffic("gemv_gate_up"),
-                    bytes_per_launch=gu["bytes_per_launch"], bracketed_launch_us=gu["bracketed_avg_ms"] * 1e3,
-                    avg_launch_us=gu["avg_ms"] * 1e3)
+                    traffic_source="profiles/dense8b_decode_prefill_pmc_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                   "command, committed with the kernels they measure; not re-measured in this run)",
+                    bytes_per_launch=gu["bytes_per_launch"],
+                    # two timings of the same launches: `frac` uses the kernel's 32 launches (one per layer)
+                    # back to back between two events; the in-step figure brackets each launch inside a
+                    # whole forward and includes the gap to its neighbours
+                    avg_launch_us=gu["avg_ms"] * 1e3, timing="32 launches back to back between two HIP events on the compute stream",
+                    bracketed_launch_us=gu["bracketed_avg_ms"] * 1e3, achieved_in_step=ach_in_step,
+                    frac_in_step=ach_in_step / HBM_PEAK_GBS,
+                    whole_step_frac=head.get("frac_of_hbm_peak"))
 
     prefill = None
     if args.prefill_tokens:
@@ -528,6 +597,10 @@ def main():
     if "tiers" in args.extra and args.layers == 32:
         extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
     fresh()
+    if "session" in args.extra and args.layers == 32:
+        extra["prefill_then_decode_one_stack"] = {"%g" % (b / 1e9): session_leg(B, S, torch, cfg, seed, prof, b, 2048, 64 if b > 3e9 else 8, args.decode_mode)
+                                                  for b in (4e9, 2e9)}
+    fresh()
     if "kv" in args.extra and args.layers == 32:
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50, args.decode_mode)
     fresh()
@@ -555,7 +628,8 @@ def main():
                 data="synthetic",
                 config=dict(workload="dense 8B-shaped stack, %d layers, decode batch 1, budget %g GB" % (
                     cfg["n_layers"], budgets[0] / 1e9), hidden=4096, ffn=14336, weight_bytes=plans[0].summary().weight_bytes,
-                    decode_mode="hip graph replay of the resident forward" if args.decode_mode == 1 else "one launch per shard"),
+                    decode_mode="hip graph replay of the resident forward" if args.decode_mode == 1 else "one launch per shard",
+                    activation_draws=len(xs), finite_activation_draws=finite_draws),
                 roofline=roof, cpu_baseline=cpu, budgets=results, prefill=prefill, extra=extra,
                 profile=None if prof is None else dict(h2d_gbps=prof.h2d_gbps, gemv_gbps=prof.gemv_gbps,
                                                        launch_us=prof.launch_us, gemm_tflops=list(prof.gemm_tflops),

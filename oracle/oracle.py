@@ -153,6 +153,26 @@ def attn_kv_half(x, cfg, qkv, o, Kc, Vc, ctx, mirror):
     return h, k_new, v_new
 
 
+def attn_kv_chunk_half(x, cfg, qkv, o, Kc, Vc, ctx, mirror):
+    """Attention half for a chunk of M new tokens over ctx cached positions (causal inside the chunk).
+    Kc, Vc: float16 [n_kv][cap][hd], cap >= ctx + M, left as they were; returns (h [M][H],
+    k_new [M][n_kv][hd], v_new [M][n_kv][hd]): the chunk's rows as stored."""
+    x = _f64(x)
+    M, H = x.shape
+    n_q, n_kv, hd = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    (qs, qc), (os_, oc) = _sc(*qkv), _sc(*o)
+    Kb = np.ascontiguousarray(Kc, dtype=np.float16).view(np.uint16)
+    Vb = np.ascontiguousarray(Vc, dtype=np.float16).view(np.uint16)
+    cap = Kb.shape[1]
+    assert Kb.shape == (n_kv, cap, hd) and Vb.shape == Kb.shape and 0 <= ctx and ctx + M <= cap
+    h = np.empty_like(x)
+    k_new = np.empty((M, n_kv, hd), dtype=np.float64)
+    v_new = np.empty((M, n_kv, hd), dtype=np.float64)
+    lib().orc_attn_kv_chunk_half(_p(x), C.c_int64(M), H, n_q, n_kv, hd, C.c_double(cfg["rms_eps"]), _p(qs), _p(qc), _p(os_), _p(oc),
+                                 _p(Kb), _p(Vb), C.c_int64(cap), C.c_int64(ctx), int(mirror), _p(k_new), _p(v_new), _p(h))
+    return h, k_new, v_new
+
+
 def dense_ffn_half(h, cfg, gate, up, down, mirror):
     h = _f64(h)
     M, H = h.shape
@@ -194,15 +214,19 @@ def stack_forward(x, cfg, weights, logits=None, mirror=True, per_layer=None, kv=
     on demand so the full model never has to be resident).  logits: fp32 [L][M][E]
     for MoE stacks.  per_layer, if a list, receives each layer's output.
     kv: None (attention = identity on V) or kv(layer) -> (K, V) float16 [n_kv][cap][hd] caches holding
-    ctx earlier positions: one new token attends over them and itself; new_rows, if a list, receives
-    each layer's (k_new, v_new).
+    ctx earlier positions: the new tokens (one, or a chunk with causal attention inside it) attend over
+    them and themselves; new_rows, if a list, receives each layer's (k_new, v_new) ([n_kv][hd] for one
+    token, [M][n_kv][hd] for a chunk).
     """
     x = _f64(x)
     for l in range(cfg["n_layers"]):
         h = x
         if not cfg["no_attn"] and kv is not None:
             Kc, Vc = kv(l)
-            h, kn, vn = attn_kv_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), Kc, Vc, ctx, mirror)
+            if x.shape[0] == 1:
+                h, kn, vn = attn_kv_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), Kc, Vc, ctx, mirror)
+            else:   # a chunk of new tokens: causal inside the chunk; rows come back as [M][n_kv][hd]
+                h, kn, vn = attn_kv_chunk_half(x, cfg, weights(l, MAT_QKV, None), weights(l, MAT_O, None), Kc, Vc, ctx, mirror)
             if new_rows is not None:
                 new_rows.append((kn, vn))
         elif not cfg["no_attn"]:

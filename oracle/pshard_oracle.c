@@ -232,6 +232,61 @@ void orc_attn_kv_half(const double *x, int H, int n_q, int n_kv, int hd, double 
     free(n); free(qkv); free(A); free(K); free(V);
 }
 
+/* attention half for a CHUNK of M new tokens with a KV cache of C earlier positions (chunked
+ * prefill over the cache; Section 3 lists the KV cache as a shard class and the tier size as the
+ * chunk size).  Causal softmax attention, written out from its definition: token m of the chunk
+ * sits at position C + m and attends over positions 0 .. C + m, i.e. the C cached rows and the
+ * chunk's own tokens 0 .. m; the chunk tokens' K and V rows are their QKV projections (as stored:
+ * fp16 when mirror) and join the cache as positions C .. C + M - 1.
+ * x [M][H]; Kc, Vc fp16 bits [n_kv][cap][hd], cap >= C + M (rows from C on are not read);
+ * k_new, v_new [M][n_kv][hd] receive the chunk's rows; h [M][H] = x + Linear_O(Attention). */
+
+void orc_attn_kv_chunk_half(const double *x, int64_t M, int H, int n_q, int n_kv, int hd, double eps,
+                            const uint16_t *qkv_s, const uint8_t *qkv_c,
+                            const uint16_t *o_s, const uint8_t *o_c,
+                            const uint16_t *Kc, const uint16_t *Vc, int64_t cap, int64_t C, int mirror,
+                            double *k_new, double *v_new, double *h) {
+    int64_t qkv_w = (int64_t)(n_q + 2 * n_kv) * hd, a_w = (int64_t)n_q * hd;
+    double *n = (double *)malloc(sizeof(double) * (size_t)(M * H));
+    double *qkv = (double *)malloc(sizeof(double) * (size_t)(M * qkv_w));
+    double *A = (double *)malloc(sizeof(double) * (size_t)(M * a_w));
+    orc_rmsnorm(x, M, H, eps, n);
+    orc_linear(n, M, qkv_s, qkv_c, qkv_w, H, qkv);
+    round_all(qkv, M * qkv_w, mirror);
+    for (int64_t m = 0; m < M; ++m)
+        for (int g = 0; g < n_kv; ++g)
+            for (int e = 0; e < hd; ++e) {
+                k_new[(m * n_kv + g) * hd + e] = qkv[m * qkv_w + (int64_t)(n_q + g) * hd + e];
+                v_new[(m * n_kv + g) * hd + e] = qkv[m * qkv_w + (int64_t)(n_q + n_kv + g) * hd + e];
+            }
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t T = C + m + 1;          /* positions token m sees */
+        double *K = (double *)malloc(sizeof(double) * (size_t)(n_kv * T * hd));
+        double *V = (double *)malloc(sizeof(double) * (size_t)(n_kv * T * hd));
+        for (int g = 0; g < n_kv; ++g)
+            for (int64_t j = 0; j < T; ++j)
+                for (int e = 0; e < hd; ++e) {
+                    double kv, vv;
+                    if (j < C) {
+                        kv = orc_half_to_double(Kc[((int64_t)g * cap + j) * hd + e]);
+                        vv = orc_half_to_double(Vc[((int64_t)g * cap + j) * hd + e]);
+                    } else {
+                        kv = k_new[((j - C) * n_kv + g) * hd + e];
+                        vv = v_new[((j - C) * n_kv + g) * hd + e];
+                    }
+                    K[((int64_t)g * T + j) * hd + e] = kv;
+                    V[((int64_t)g * T + j) * hd + e] = vv;
+                }
+        orc_attn_decode(qkv + m * qkv_w, K, V, T, n_q, n_kv, hd, A + m * a_w);
+        free(K); free(V);
+    }
+    round_all(A, M * a_w, mirror);
+    orc_linear(A, M, o_s, o_c, H, a_w, h);
+    for (int64_t i = 0; i < M * H; ++i) h[i] += x[i];
+    round_all(h, M * H, mirror);
+    free(n); free(qkv); free(A);
+}
+
 /* ---- one gated FFN on already-normalised input n [M][H] --------------------
  * y = Linear_down(SwiGLU(Linear_gate(n), Linear_up(n))), y [M][H] not rounded */
 

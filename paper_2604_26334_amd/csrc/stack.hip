@@ -64,6 +64,7 @@ struct ps_stack {
     uint64_t stage_bytes = 0;
     void *tables_host[2] = {nullptr, nullptr};   // pinned: logits | tasks | pairs | copy descriptors of one forward (MoE)
     uint64_t tables_bytes = 0;
+    int32_t decode_mode = 0;                  // as set by ps_stack_set_decode_mode (re-evaluated when a tier is installed)
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
     std::map<std::tuple<const void *, void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out, logits)
     // CPU back-end (plans with shards left in system memory): worker threads, pinned host copies of
@@ -695,6 +696,7 @@ int32_t bind_plan(ps_stack *st) {
         if (rc) return rc;
         st->have_dense_sched = true;
     }
+    st->use_graph = st->decode_mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
     return PS_OK;
 }
 
@@ -1275,6 +1277,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     if (mode < 0 || mode > 2) { ps::set_error("decode mode must be 0, 1 or 2"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
+    st->decode_mode = mode;
     st->use_graph = mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
     st->own_rinv_launch = mode == 2;
     return PS_OK;

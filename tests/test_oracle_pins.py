@@ -536,6 +536,66 @@ def test_attn_kv_half_composition_and_empty_cache():
     np.testing.assert_array_equal(h2, h)
 
 
+def test_attn_kv_chunk_equals_token_by_token_decode_and_is_causal():
+    """A chunk of M new tokens over the cache, by the definition of causal attention, is what M
+    one-token steps give when each step's rows join the cache before the next: pinned against the
+    separately pinned one-token half.  Also: a one-token chunk is that half; a later token's input
+    never changes an earlier token's output; rows past ctx + M are never read."""
+    cfg = dict(n_layers=1, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_inter=256, n_experts=0,
+               top_k=0, expert_inter=0, rms_eps=1e-6, no_attn=False, no_residual=False)
+    H, n_q, n_kv, hd = 256, 4, 2, 128
+    qkv = S.weight_matrix(6, 0, S.MAT_QKV, None, (n_q + 2 * n_kv) * hd, H)
+    o = S.weight_matrix(6, 0, S.MAT_O, None, H, n_q * hd)
+    rng = np.random.default_rng(19)
+    cap, ctx, M = 20, 6, 5
+    Kc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    Vc = rng.standard_normal((n_kv, cap, hd)).astype(np.float16)
+    x = S.activations(6, 0, M, H)
+    for mirror in (False, True):
+        h, kn, vn = O.attn_kv_chunk_half(x, cfg, qkv, o, Kc, Vc, ctx, mirror)
+        K2, V2 = Kc.copy(), Vc.copy()
+        for m in range(M):
+            hm, k1, v1 = O.attn_kv_half(x[m:m + 1], cfg, qkv, o, K2, V2, ctx + m, mirror)
+            if mirror:      # rows are stored as fp16: the running cache holds exactly what the chunk call used
+                np.testing.assert_array_equal(h[m], hm[0])
+                np.testing.assert_array_equal(kn[m], k1)
+                K2[:, ctx + m], V2[:, ctx + m] = k1.astype(np.float16), v1.astype(np.float16)
+            else:           # pure mode keeps the chunk's rows in fp64; a fp16 cache would round them
+                np.testing.assert_array_equal(kn[m], k1)
+                if m == 0:
+                    np.testing.assert_array_equal(h[0], hm[0])
+        # one-token chunk
+        h1, k1, v1 = O.attn_kv_chunk_half(x[:1], cfg, qkv, o, Kc, Vc, ctx, mirror)
+        h0, k0, v0 = O.attn_kv_half(x[:1], cfg, qkv, o, Kc, Vc, ctx, mirror)
+        np.testing.assert_array_equal(h1, h0)
+        np.testing.assert_array_equal(k1[0], k0)
+        np.testing.assert_array_equal(v1[0], v0)
+        # causal: perturbing the last token leaves the earlier ones alone
+        x2 = x.copy()
+        x2[M - 1] = -x2[M - 1]
+        hp, _, _ = O.attn_kv_chunk_half(x2, cfg, qkv, o, Kc, Vc, ctx, mirror)
+        np.testing.assert_array_equal(hp[:M - 1], h[:M - 1])
+        assert np.any(hp[M - 1] != h[M - 1])
+        # cache rows at and beyond ctx are not read
+        Kd, Vd = Kc.copy(), Vc.copy()
+        Kd[:, ctx:] = 7.0; Vd[:, ctx:] = -7.0
+        hd2, _, _ = O.attn_kv_chunk_half(x, cfg, qkv, o, Kd, Vd, ctx, mirror)
+        np.testing.assert_array_equal(hd2, h)
+    # pure mode against brute force softmax attention for the middle token of the chunk
+    h, kn, vn = O.attn_kv_chunk_half(x, cfg, qkv, o, Kc, Vc, ctx, False)
+    y = O.linear(O.rmsnorm(x, cfg["rms_eps"]), *qkv)
+    m = 2
+    A = np.zeros(n_q * hd)
+    for hq in range(n_q):
+        g = hq // (n_q // n_kv)
+        Ks = np.concatenate([Kc[g, :ctx].astype(np.float64), y[:m + 1, (n_q + g) * hd:(n_q + g + 1) * hd]])
+        Vs = np.concatenate([Vc[g, :ctx].astype(np.float64), y[:m + 1, (n_q + n_kv + g) * hd:(n_q + n_kv + g + 1) * hd]])
+        sc = Ks @ y[m, hq * hd:(hq + 1) * hd] / math.sqrt(hd)
+        p = np.exp(sc - sc.max()); p /= p.sum()
+        A[hq * hd:(hq + 1) * hd] = p @ Vs
+    np.testing.assert_allclose(h[m], x[m].astype(np.float64) + O.linear(A[None, :], *o)[0], rtol=1e-12, atol=1e-12)
+
+
 # ---------------------------------------------------------------- output head
 
 def test_output_head_closed_forms():
