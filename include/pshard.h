@@ -103,9 +103,10 @@ typedef struct ps_model_desc {
     uint32_t expert_inter; /* per-expert FFN width                               */
     uint32_t flags;        /* PS_FLAG_*                                          */
     float rms_eps;
-    uint32_t kv_context;   /* 0: attention is the identity on V (no cache).  > 0: decode attention over
-                              a KV cache with room for kv_context positions per kv head (one new
-                              token per forward; plans for more than one token are rejected)        */
+    uint32_t kv_context;   /* 0: attention is the identity on V (no cache).  > 0: causal softmax attention over
+                              a KV cache with room for kv_context positions per kv head; a forward takes
+                              one new token, or a chunk of new tokens (a plan's token count must be below
+                              kv_context; chunks take the GPU-only plan)                             */
     uint32_t vocab;        /* 0: no output head.  > 0 (multiple of 16): after the last layer the final
                               hidden state is RMS-normalised and projected to `vocab` logits by one
                               more 4-bit matrix, whose shards form the lowest priority class
@@ -411,7 +412,8 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
                         void *compute_stream, void *copy_stream, ps_stack **out);
 /* One stack for every token tier of a budget (Algorithm 1: the planning phase leaves one schedule
  * per tier; at inference PickTier chooses one, SetupForSched installs it, and the schedule runs).
- * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans, no KV cache) to one
+ * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans, no KV cache: a cache is
+ * state that a tier switch would have to move) to one
  * arena of the table's budget and installs the lowest feasible tier (it pins the most).  Every
  * tier's arena is laid out [pinned shards in priority order | scratch slots | workspace], so a shard
  * that two tiers pin lies at the same place in both, and the library keeps a packed image of every
@@ -436,10 +438,13 @@ int32_t ps_stack_load_matrix(ps_stack *st, uint32_t layer, uint32_t mat, uint32_
  * ps_stack_load_kv fills positions [0, n_pos) of one kv head of one layer from host fp16
  * K, V [n_pos][head_dim] (copied; synchronous) into that shard's home: the arena if the plan pinned
  * it, the pinned host pool otherwise.  ps_stack_set_context sets how many cached positions the next
- * forward attends over (context < kv_context); that forward appends the new token's K and V rows at
- * position `context` of every head's home, so consecutive decode steps pass context, context + 1, ...
- * Attention (no positional encoding): scores q.K_j / sqrt(head_dim) over the cached positions and the
- * token itself, softmax, weighted sum of V; query head h uses kv head h / (n_q / n_kv). */
+ * forward attends over; that forward appends its tokens' K and V rows at positions context,
+ * context + 1, ... of every head's home (context + tokens <= kv_context), so consecutive decode
+ * steps pass context, context + 1, ... (ps_stack_forward_chunked advances the context by itself).
+ * Attention (no positional encoding): the token at position p attends over positions 0 .. p -- the
+ * cached ones and, in a chunk of several new tokens, the chunk's earlier tokens and itself: scores
+ * q.K_j / sqrt(head_dim), softmax, weighted sum of V; query head h uses kv head h / (n_q / n_kv).
+ * A streamed cache shard crosses PCIe with its `context` valid rows only. */
 int32_t ps_stack_load_kv(ps_stack *st, uint32_t layer, uint32_t kv_head, const uint16_t *k_rows,
                          const uint16_t *v_rows, uint32_t n_pos);
 int32_t ps_stack_set_context(ps_stack *st, uint32_t context);
@@ -500,7 +505,10 @@ int32_t ps_stack_forward_noalloc(ps_stack *st, const void *x_in, void *x_out);
  *  [vocab], 16-byte aligned: the output head runs on the last trip only, for the prompt's last token
  *  (its copies and kernels are left out of the other trips); the setting of ps_stack_set_logits_out
  *  is not used and is left as it was.  *trips (may be NULL) receives the number of trips.
- *  PS_E_STATE for a stack with a KV cache (one token per forward).  Asynchronous like ps_stack_forward. */
+ *  With a KV cache every trip attends over the cache and the rows the earlier trips appended, starting
+ *  at the context set by ps_stack_set_context; afterwards the context stands at that value + n_tokens
+ *  (PS_E_ARG if that exceeds kv_context), so decode steps can follow without setting it.
+ *  Asynchronous like ps_stack_forward. */
 int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, uint32_t n_tokens,
                                  const float *router_logits, const float *router_logits_dev,
                                  void *last_logits_dev, uint32_t *trips);

@@ -92,6 +92,28 @@ struct AttnArgs {
                                // the launch covers every chunk the cache can hold (a captured graph is
                                // replayed at any context); workgroups past the context leave at once
 };
+// Attention of a chunk of `ntok` new tokens (rows of q, q_stride elements apart) over one kind of rows:
+//  causal == 0: the cache shards of kv heads head0 .. head0 + nheads - 1 (k_base = first shard; shards
+//   head_stride bytes apart, K rows [cap][128] then V rows; row_stride = 128); every token sees the ctx
+//   cached positions;
+//  causal == 1: the chunk's own K / V rows, read in place from the tokens' QKV rows (k_base / v_base =
+//   kv head 0 of token 0, row_stride = the QKV row width; head0 .. as above): token t sees rows 0 .. t.
+// Partials go to part[((t * n_q + q_head) * chunk_cap + chunk0 + chunk) * 130] (maximum, weight sum, 128 sums).
+struct AttnChunkArgs {
+    const __half *k_base, *v_base;
+    uint64_t head_stride;
+    uint32_t cap, ctx, head0, nheads, group, n_q;
+    uint32_t row_stride, causal, ntok, q_stride, chunk0, chunk_cap;
+    const __half *q;
+    float *part;
+};
+hipError_t launch_attn_chunk(const AttnChunkArgs &a, hipStream_t st);
+// merges every token's chunks (cache chunks below ctx, then the chunk's own) in ascending order, writes the
+// attention rows out[t][n_q * 128] (out_stride elements apart) and appends the tokens' K / V rows at
+// positions ctx .. ctx + ntok - 1 of each kv head's cache home
+hipError_t launch_attn_combine_chunk(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
+                                     uint32_t qkv_w, uint32_t n_q, uint32_t n_kv, uint32_t ntok, const uint64_t *home, __half *out,
+                                     uint32_t out_stride, hipStream_t st);
 // *dst = v (device word), in stream order
 hipError_t launch_set_u32(uint32_t *dst, uint32_t v, hipStream_t st);
 // dst[idx[r]][0..H) = src[r][0..H) for r < n (fp32 rows; H a multiple of 4; idx values are row numbers of dst)

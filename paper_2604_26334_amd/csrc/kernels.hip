@@ -551,6 +551,7 @@ constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 
 constexpr int kAttnIts = 8;               // steps of 4 positions per wave
 constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
 static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
+static_assert(kAttnPos == kAttnPosPerWg, "the executor numbers the chunk's own partials behind ceil(ctx / kAttnPosPerWg) cache chunks");
 
 // sum over each row of 16 lanes, result in every lane of the row (DPP: no LDS traffic)
 __device__ __forceinline__ float row16_sum(float v) {
@@ -687,6 +688,195 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_decode_
             dst[1] = ld;
         }
     }
+}
+
+// ------------------------------------------------------------------------------------
+// Attention for a CHUNK of new tokens (chunked prefill over the cache): the same streaming scheme with
+// a loop over the chunk's tokens.  A workgroup holds 256 positions of one kv head in registers (cache
+// rows, or the chunk's own K / V rows read in place from the QKV buffer: row stride and base differ,
+// nothing else) and serves every token of the chunk in turn: token t sees positions below limit(t) =
+// ctx for cache rows, t + 1 for the chunk's rows (causal).  Per (token, query head, position chunk) it
+// writes the chunk maximum, weight sum and 128 weighted sums; attn_combine_chunk_kernel merges a
+// token's chunks in ascending order, so the result does not depend on where a cache shard lives.
+// ------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_kernel(AttnChunkArgs a) {
+    __shared__ float red[kAttnWaves][G][128];
+    __shared__ float redm[kAttnWaves][G], redl[kAttnWaves][G];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dl = lane & 15, pg = lane >> 4;
+    const uint32_t chunk = blockIdx.x, hk = blockIdx.y;
+    const uint32_t kv_head = a.head0 + hk;
+    const __half *K = a.causal ? a.k_base + (size_t)kv_head * 128 : reinterpret_cast<const __half *>(reinterpret_cast<const char *>(a.k_base) + (size_t)hk * a.head_stride);
+    const __half *V = a.causal ? a.v_base + (size_t)kv_head * 128 : K + (size_t)a.cap * 128;
+    const uint32_t q0 = kv_head * G;
+    const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+    const uint32_t row_b = a.row_stride * 2u;   // bytes between two positions' rows
+    const uint32_t npos = a.causal ? a.ntok : a.ctx;                        // rows that exist
+    const uint32_t range = npos ? (npos - 1) * row_b + 256u : 0u;          // a row past the end reads as zeros
+    const uint32_t base = chunk * kAttnPos + wave * (kAttnPos / kAttnWaves);
+    const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
+    const uint32_t voff = (uint32_t)pg * row_b + (uint32_t)dl * 16u;
+    const uint32_t soff = __builtin_amdgcn_readfirstlane(base * row_b);
+    uint4 kq[kAttnIts], vq[kAttnIts];
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it)
+        kq[it] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(kb, voff, soff + it * 4 * row_b, 0));
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it)
+        vq[it] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, voff, soff + it * 4 * row_b, 0));
+    float vf[kAttnIts][8];
+#pragma unroll
+    for (int it = 0; it < kAttnIts; ++it) {
+        const uint32_t vd[4] = {vq[it].x, vq[it].y, vq[it].z, vq[it].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const h2_t pr = as_h2(vd[e]);
+            vf[it][2 * e] = (float)pr.x;
+            vf[it][2 * e + 1] = (float)pr.y;
+        }
+    }
+    // first token that sees any position of this chunk (causal: token chunk * kAttnPos)
+    const uint32_t t_first = a.causal ? chunk * kAttnPos : 0;
+#pragma unroll 1
+    for (uint32_t t = t_first; t < a.ntok; ++t) {
+        const uint32_t limit = a.causal ? t + 1 : a.ctx;
+        uint4 qv[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) qv[h] = *reinterpret_cast<const uint4 *>(a.q + (size_t)t * a.q_stride + (size_t)(q0 + h) * 128 + dl * 8);
+        float sc[kAttnIts][G], mx[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) mx[h] = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < kAttnIts; ++it) {
+            const uint32_t j = base + it * 4 + pg;
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                float d = 0.f;
+                d = __builtin_amdgcn_fdot2(as_h2(qv[h].x), as_h2(kq[it].x), d, false);
+                d = __builtin_amdgcn_fdot2(as_h2(qv[h].y), as_h2(kq[it].y), d, false);
+                d = __builtin_amdgcn_fdot2(as_h2(qv[h].z), as_h2(kq[it].z), d, false);
+                d = __builtin_amdgcn_fdot2(as_h2(qv[h].w), as_h2(kq[it].w), d, false);
+                const float r = row16_sum(d) * scale;
+                sc[it][h] = j < limit ? r : -INFINITY;
+                mx[h] = fmaxf(mx[h], sc[it][h]);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            mx[h] = fmaxf(mx[h], __shfl_xor(mx[h], 16, 64));
+            mx[h] = fmaxf(mx[h], __shfl_xor(mx[h], 32, 64));
+        }
+        float l[G], o[G][8];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            l[h] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
+        }
+#pragma unroll
+        for (int it = 0; it < kAttnIts; ++it) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float p = sc[it][h] == -INFINITY ? 0.f : __expf(sc[it][h] - mx[h]);
+                l[h] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vf[it][e], o[h][e]);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            l[h] += __shfl_xor(l[h], 16, 64);
+            l[h] += __shfl_xor(l[h], 32, 64);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                o[h][e] += __shfl_xor(o[h][e], 16, 64);
+                o[h][e] += __shfl_xor(o[h][e], 32, 64);
+            }
+            if (pg == 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) red[wave][h][dl * 8 + e] = o[h][e];
+                if (dl == 0) { redl[wave][h] = l[h]; redm[wave][h] = mx[h]; }
+            }
+        }
+        __syncthreads();
+        for (int u = tid; u < G * 128; u += kAttnWaves * 64) {
+            const int h = u >> 7, d = u & 127;
+            // the chunk's first position is below the limit (t >= t_first), so wave 0's maximum is finite
+            float m = redm[0][h];
+#pragma unroll
+            for (int k = 1; k < kAttnWaves; ++k) m = fmaxf(m, redm[k][h]);
+            float od = 0.f, ld = 0.f;   // waves in ascending order
+#pragma unroll
+            for (int k = 0; k < kAttnWaves; ++k) {
+                const float w = redm[k][h] == -INFINITY ? 0.f : __expf(redm[k][h] - m);
+                od = fmaf(w, red[k][h][d], od);
+                ld = fmaf(w, redl[k][h], ld);
+            }
+            float *dst = a.part + (((size_t)t * a.n_q + q0 + h) * a.chunk_cap + a.chunk0 + chunk) * 130;
+            dst[2 + d] = od;
+            if (d == 0) {
+                dst[0] = m;
+                dst[1] = ld;
+            }
+        }
+        __syncthreads();   // the next token reuses the reduction buffers
+    }
+}
+
+hipError_t launch_attn_chunk(const AttnChunkArgs &a, hipStream_t st) {
+    const uint32_t npos = a.causal ? a.ntok : a.ctx;
+    if (npos == 0 || a.nheads == 0 || a.ntok == 0) return hipSuccess;
+    dim3 grid((npos + kAttnPos - 1) / kAttnPos, a.nheads);
+    if (a.chunk0 + grid.x > a.chunk_cap) return hipErrorInvalidValue;
+    if ((uint64_t)npos * a.row_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;   // 32-bit buffer offsets
+    switch (a.group) {
+        case 1: hipLaunchKernelGGL(attn_chunk_kernel<1>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 2: hipLaunchKernelGGL(attn_chunk_kernel<2>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 4: hipLaunchKernelGGL(attn_chunk_kernel<4>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 8: hipLaunchKernelGGL(attn_chunk_kernel<8>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// One workgroup of 128 threads per (query head, token): thread d merges dimension d over the token's
+// chunks in ascending order -- the cache's chunks below ctx, then the chunk's own rows up to the token
+// itself -- writes the attention output row (the O projection's input) and, for the first query head
+// of each kv group, appends the token's K and V rows at position ctx + t of that head's cache home.
+__global__ __launch_bounds__(128) void attn_combine_chunk_kernel(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap,
+                                                                 const __half *qkv, uint32_t qkv_w, uint32_t n_q, uint32_t n_kv,
+                                                                 const uint64_t *home, __half *out, uint32_t out_stride) {
+    const uint32_t h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
+    const uint32_t group = n_q / n_kv, g = h / group;
+    const uint32_t nc_cache = (ctx + kAttnPos - 1) / kAttnPos, nc_own = t / kAttnPos + 1;
+    const float *ph = part + ((size_t)t * n_q + h) * chunk_cap * 130;
+    float mx = -INFINITY;
+    for (uint32_t c = 0; c < nc_cache + nc_own; ++c) mx = fmaxf(mx, ph[(size_t)c * 130]);
+    float L = 0.f, o = 0.f;
+    for (uint32_t c = 0; c < nc_cache + nc_own; ++c) {
+        const float w = __expf(ph[(size_t)c * 130] - mx);
+        L = fmaf(w, ph[(size_t)c * 130 + 1], L);
+        o = fmaf(w, ph[(size_t)c * 130 + 2 + d], o);
+    }
+    out[(size_t)t * out_stride + (size_t)h * 128 + d] = to_half(o / L);
+    if (h % group == 0) {
+        __half *Kh = reinterpret_cast<__half *>(home[g]);
+        Kh[((size_t)ctx + t) * 128 + d] = qkv[(size_t)t * qkv_w + (size_t)(n_q + g) * 128 + d];
+        Kh[((size_t)cap + ctx + t) * 128 + d] = qkv[(size_t)t * qkv_w + (size_t)(n_q + n_kv + g) * 128 + d];
+    }
+}
+
+hipError_t launch_attn_combine_chunk(const float *part, uint32_t chunk_cap, uint32_t ctx, uint32_t cap, const __half *qkv,
+                                     uint32_t qkv_w, uint32_t n_q, uint32_t n_kv, uint32_t ntok, const uint64_t *home, __half *out,
+                                     uint32_t out_stride, hipStream_t st) {
+    if (ntok == 0) return hipSuccess;
+    if (n_kv == 0 || n_q % n_kv || (uint64_t)ctx + ntok > cap || ntok > 65535) return hipErrorInvalidValue;
+    if ((ctx + kAttnPos - 1) / kAttnPos + (ntok + kAttnPos - 1) / kAttnPos > chunk_cap) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_combine_chunk_kernel, dim3(n_q, ntok), dim3(128), 0, st, part, chunk_cap, ctx, cap, qkv, qkv_w, n_q, n_kv, home,
+                       out, out_stride);
+    return hipGetLastError();
 }
 
 __global__ void set_u32_kernel(uint32_t *dst, uint32_t v) { *dst = v; }

@@ -150,10 +150,11 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M, bool cpu_experts) {
     }
     if (pb) w.partial = take(pb);
     if (g.kv) {
-        w.attn = take((uint64_t)g.attn_w * 2);
-        // per query head and 256-position chunk: running maximum, sum of weights, 128 weighted sums
-        const uint64_t chunks = (g.m.kv_context + kAttnChunk - 1) / kAttnChunk;
-        w.apart = take((uint64_t)g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
+        w.attn = take((uint64_t)M * g.attn_w * 2);
+        // per token, query head and position chunk: running maximum, sum of weights, 128 weighted sums;
+        // a chunk of several tokens adds the chunks of its own rows behind the cache's
+        const uint64_t chunks = (g.m.kv_context + kAttnChunk - 1) / kAttnChunk + (M > 1 ? (M + kAttnChunk - 1) / kAttnChunk : 0);
+        w.apart = take((uint64_t)M * g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
         w.kvhome = take((uint64_t)g.m.n_layers * g.m.n_kv_heads * 8);
         w.ctx = take(4);   // context length as the kernels of a replayed graph read it
     }
@@ -305,7 +306,8 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
     p->db_threads = 0;
     if (p->db) for (const ps_prof_entry &e : p->db->entries) if (e.op == PS_OPK_CPU) p->db_threads = std::max(p->db_threads, e.threads);
     if (M == 0 || M > kTiers[PS_NTIERS - 1]) { set_error("n_tokens=%u out of range 1..16384", M); return PS_E_ARG; }
-    if (p->g.kv && M != 1) { set_error("attention over a KV cache is built for one token per step (got %u)", M); return PS_E_ARG; }
+    if (p->g.kv && M >= p->g.m.kv_context) { set_error("a chunk of %u tokens does not fit a cache of %u positions", M, p->g.m.kv_context); return PS_E_BUDGET; }
+    if (p->g.kv && M > 1 && kind != PS_PLAN_GPU_ONLY) { set_error("chunks of several tokens over a KV cache take the GPU-only plan"); return PS_E_ARG; }
     if (prof) p->prof = *prof;
     if (kind != PS_PLAN_GPU_ONLY && !(p->prof.cpu_gbps > 0)) {
         set_error("plans with CPU shards need a profile with cpu_gbps > 0"); return PS_E_STATE;
@@ -656,10 +658,9 @@ int32_t ps_tier_table_create_kind(const ps_model_desc *model, uint64_t budget, c
     for (uint32_t t = 0; t < PS_NTIERS; ++t) {
         ps_plan *p = new (std::nothrow) ps_plan();
         if (!p) { delete tb; ps::set_error("out of host memory"); return PS_E_NOMEM; }
-        // attention over a KV cache is built for one token per step: only that tier has a schedule
-        if (model && model->kv_context && t > 0) { delete p; continue; }
-        // the CPU back-end takes at most 64 tokens: larger tiers keep Plan One whatever was asked for
-        const uint32_t k = ps::kTiers[t] > 64 ? (uint32_t)PS_PLAN_GPU_ONLY : kind;
+        // the CPU back-end takes at most 64 tokens, and one token per step over a KV cache: other tiers
+        // keep Plan One whatever was asked for
+        const uint32_t k = (ps::kTiers[t] > 64 || (model && model->kv_context && t > 0)) ? (uint32_t)PS_PLAN_GPU_ONLY : kind;
         const int32_t rc = ps::plan_impl(model, budget, prof, ps::kTiers[t], expert_freq, k, p);
         if (rc == PS_OK) { tb->plans[t] = p; continue; }
         delete p;

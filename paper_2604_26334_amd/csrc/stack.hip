@@ -303,8 +303,13 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         case PS_K_O: {
             const Shard &s = p.shards[op.info.shard0];
             GemmArgs a = gemm_base(g.o);
-            a.W = wptr(op); a.ntiles = s.ntiles; a.x = qkv; a.x_stride = g.qkv_w;
-            a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
+            a.W = wptr(op); a.ntiles = s.ntiles;
+            if (g.kv) {   // the attention output rows
+                a.x = reinterpret_cast<const __half *>(WS + p.ws.attn); a.x_stride = g.attn_w;
+            } else {      // identity on V, read in place from the QKV rows
+                a.x = qkv; a.x_stride = g.qkv_w;
+                a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
+            }
             a.res = xin; a.out = hbuf; a.out_stride = H; a.out_row0 = s.tile0 * 16;
             return run_gemm(GEMM_RESID, a, g.o);
         }
@@ -324,6 +329,17 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         }
         case PS_K_ATTN: {
             const Shard &s = p.shards[op.info.shard0];
+            const uint32_t ccap = (m.kv_context + kAttnChunk - 1) / kAttnChunk + (MP > 1 ? (MP + kAttnChunk - 1) / kAttnChunk : 0);
+            if (MP > 1) {   // a chunk of tokens over the cached positions of this run of kv heads
+                AttnChunkArgs c{};
+                c.k_base = reinterpret_cast<const __half *>(wptr(op)); c.head_stride = g.kv_shard_bytes;
+                c.cap = m.kv_context; c.ctx = st->ctx; c.head0 = s.expert; c.nheads = op.info.nshards;
+                c.group = m.n_q_heads / m.n_kv_heads; c.n_q = m.n_q_heads; c.row_stride = m.head_dim; c.causal = 0;
+                c.ntok = M; c.q_stride = g.qkv_w; c.chunk0 = 0; c.chunk_cap = ccap; c.q = qkv;
+                c.part = reinterpret_cast<float *>(WS + p.ws.apart);
+                PS_HIP(launch_attn_chunk(c, cs));
+                return PS_OK;
+            }
             AttnArgs a{};
             a.kv = reinterpret_cast<const __half *>(wptr(op));
             a.head_stride = g.kv_shard_bytes; a.cap = m.kv_context; a.ctx = st->ctx;
@@ -335,6 +351,20 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             return PS_OK;
         }
         case PS_K_ATTN_COMBINE:
+            if (MP > 1) {   // the chunk's own rows (causal), then every token's chunks merged and its rows appended
+                const uint32_t ccap = (m.kv_context + kAttnChunk - 1) / kAttnChunk + (MP + kAttnChunk - 1) / kAttnChunk;
+                AttnChunkArgs c{};
+                c.k_base = qkv + (size_t)m.n_q_heads * m.head_dim; c.v_base = qkv + (size_t)(m.n_q_heads + m.n_kv_heads) * m.head_dim;
+                c.cap = m.kv_context; c.ctx = st->ctx; c.head0 = 0; c.nheads = m.n_kv_heads;
+                c.group = m.n_q_heads / m.n_kv_heads; c.n_q = m.n_q_heads; c.row_stride = g.qkv_w; c.causal = 1;
+                c.ntok = M; c.q_stride = g.qkv_w; c.chunk0 = (st->ctx + kAttnPosPerWg - 1) / kAttnPosPerWg; c.chunk_cap = ccap; c.q = qkv;
+                c.part = reinterpret_cast<float *>(WS + p.ws.apart);
+                PS_HIP(launch_attn_chunk(c, cs));
+                PS_HIP(launch_attn_combine_chunk(c.part, ccap, st->ctx, m.kv_context, qkv, g.qkv_w, m.n_q_heads, m.n_kv_heads, M,
+                                                 reinterpret_cast<const uint64_t *>(WS + p.ws.kvhome) + (size_t)l * m.n_kv_heads,
+                                                 reinterpret_cast<__half *>(WS + p.ws.attn), g.attn_w, cs));
+                return PS_OK;
+            }
             PS_HIP(launch_attn_combine(reinterpret_cast<const float *>(WS + p.ws.apart),
                                        (m.kv_context + kAttnChunk - 1) / kAttnChunk, st->ctx,
                                        st->use_graph ? reinterpret_cast<const uint32_t *>(WS + p.ws.ctx) : nullptr, m.kv_context, qkv,
@@ -618,6 +648,16 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
                 }
                 st->n_descs += n;
                 PS_HIP(launch_h2d_gather(descs, n, st->copy));
+            } else if (p.shards[o.shard0].kind == PS_SHARD_KV) {
+                // a cache shard: only the rows the step attends over cross PCIe (K rows, then V rows)
+                const uint64_t rows_b = (uint64_t)st->ctx * p.g.m.head_dim * 2, vbase = (uint64_t)p.g.m.kv_context * p.g.m.head_dim * 2;
+                if (rows_b) {
+                    uint8_t *dst = slot_ptr(st, o.slot) + o.slot_offset;
+                    PS_HIP(hipMemcpyAsync(dst, st->shard_host[o.shard0], rows_b, hipMemcpyHostToDevice, st->copy));
+                    PS_HIP(hipMemcpyAsync(dst + vbase, st->shard_host[o.shard0] + vbase, rows_b, hipMemcpyHostToDevice, st->copy));
+                    ss.streamed_bytes_step += 2 * rows_b;
+                    ss.n_copies += 2;
+                }
             } else {
                 PS_HIP(hipMemcpyAsync(slot_ptr(st, o.slot) + o.slot_offset, st->shard_host[o.shard0], o.bytes,
                                       hipMemcpyHostToDevice, st->copy));
@@ -1137,7 +1177,10 @@ static int32_t forward_impl(ps_stack *st, const void *x_in, void *x_out, const f
     const ps_plan &p = st->plan;
     st->n_valid = n_valid;
     if (p.g.kv) {
-        if (st->ctx >= p.g.m.kv_context) { ps::set_error("context %u leaves no room in a cache of %u positions", st->ctx, p.g.m.kv_context); return PS_E_STATE; }
+        if ((uint64_t)st->ctx + n_valid > p.g.m.kv_context) {
+            ps::set_error("context %u and %u new token(s) leave no room in a cache of %u positions", st->ctx, n_valid, p.g.m.kv_context);
+            return PS_E_STATE;
+        }
         // this step's cache copies read rows the previous step appended from the compute stream
         if (st->kv_copied && st->step_pending) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_step, 0));
     }
@@ -1248,7 +1291,6 @@ int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, ui
     if (rc) return rc;
     if (n_tokens == 0) { ps::set_error("n_tokens is 0"); return PS_E_ARG; }
     const ps_plan &p = st->plan;
-    if (p.g.kv) { ps::set_error("a stack with a KV cache takes one token per forward"); return PS_E_STATE; }
     if (last_logits_dev && !p.g.m.vocab) { ps::set_error("this stack has no output head (vocab is 0)"); return PS_E_STATE; }
     if (last_logits_dev && (uintptr_t)last_logits_dev % 16) { ps::set_error("logits buffer must be 16-byte aligned"); return PS_E_ARG; }
     const uint32_t T = p.M, H = p.g.m.hidden, E = p.g.m.n_experts;
@@ -1256,6 +1298,11 @@ int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, ui
     __half *const saved_logits = st->logits;
     const uint32_t saved_rows = st->head_rows, saved_row0 = st->head_row0;
     uint32_t n_trips = 0;
+    const uint32_t ctx0 = st->ctx;
+    if (p.g.kv && (uint64_t)ctx0 + n_tokens > p.g.m.kv_context) {
+        ps::set_error("context %u and %u new tokens do not fit a cache of %u positions", ctx0, n_tokens, p.g.m.kv_context);
+        return PS_E_ARG;
+    }
     for (uint32_t r0 = 0; r0 < n_tokens && rc == PS_OK; r0 += T, ++n_trips) {
         const uint32_t nv = std::min(T, n_tokens - r0);
         const bool last = r0 + nv == n_tokens;
@@ -1263,11 +1310,13 @@ int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, ui
         st->logits = last && last_logits_dev ? static_cast<__half *>(last_logits_dev) : nullptr;
         st->head_rows = st->logits ? 1 : 0;
         st->head_row0 = st->logits ? nv - 1 : 0;
+        if (p.g.kv) st->ctx = ctx0 + r0;      // each trip attends over the cache and the rows the earlier trips appended
         rc = forward_impl(st, static_cast<const __half *>(x_in) + (size_t)r0 * H, static_cast<__half *>(x_out) + (size_t)r0 * H,
                           router_logits ? router_logits + (size_t)r0 * E : nullptr,
                           router_logits_dev ? router_logits_dev + (size_t)r0 * E : nullptr, (uint64_t)n_tokens * E, nv);
     }
     st->logits = saved_logits; st->head_rows = saved_rows; st->head_row0 = saved_row0;
+    if (p.g.kv && rc == PS_OK) st->ctx = ctx0 + n_tokens;   // the prompt's rows are in the cache now
     if (trips) *trips = n_trips;
     return rc;
 }

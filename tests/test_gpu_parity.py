@@ -426,6 +426,143 @@ def test_decode_attention_over_kv_cache(ctx0):
             np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
 
 
+@pytest.mark.parametrize("ctx0,M", [(0, 5), (3, 37), (300, 64), (250, 16), (10, 300)])
+def test_chunk_of_new_tokens_attends_over_the_kv_cache(ctx0, M):
+    """Chunked prefill over the cache: a forward of M new tokens at context ctx0 (causal attention inside
+    the chunk, rows appended at ctx0 .. ctx0 + M - 1), then a one-token step at ctx0 + M that attends over
+    what the chunk appended.
+    Oracle parity is taken layer by layer, each layer fed the GPU's own output of the layer before (softmax
+    over scores of this size is sharp: a rounding-sized difference in one layer's rows can move weight
+    between positions in the next, so the end-to-end error of a deeper stack says little about a kernel);
+    the two-layer stack must then give exactly the bits of that chain, on every cache placement."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    L = 2
+    cfg = _kv_cfg(L, ctx0 + M + 9)
+    one = dict(cfg, n_layers=1)
+    Wall = Hn.WeightCache(cfg, 29)
+    n_kv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    caches = [S.kv_cache(29, l, n_kv, ctx0, hd) for l in range(L)]
+    x = S.activations(29, 0, M, cfg["hidden"])
+    xd = S.activations(29, 1, 1, cfg["hidden"])
+
+    def load(st, layers, weights):
+        for layer in layers:
+            for k, ex, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, k, ex, *weights(layer, k, ex))
+
+    def run(st, kv_of_layer, n_layers, xin_np, xd_np):
+        for layer in range(n_layers):
+            for g in range(n_kv):
+                st.load_kv(layer, g, kv_of_layer(layer)[0][g], kv_of_layer(layer)[1][g])
+        xin = torch.from_numpy(xin_np).to(st.device)
+        xout = torch.zeros_like(xin)
+        st.set_context(ctx0)
+        st.forward(xin, xout)
+        st.synchronize()
+        streamed = st.stats().streamed_bytes_step
+        xdi = torch.from_numpy(xd_np).to(st.device)
+        xdo = torch.zeros_like(xdi)
+        st.set_context(ctx0 + M)
+        B.chunked_forward(st, xdi, xdo)          # one token through the chunk plan's schedule
+        st.synchronize()
+        return xout.cpu().numpy(), xdo.cpu().numpy(), streamed
+
+    # layer by layer on one-layer stacks, against the oracle on the same inputs
+    cur, cur_d = x, xd
+    for l in range(L):
+        Wl = lambda layer, k, e, l=l: Wall(l, k, e)
+        oK = np.zeros((n_kv, cfg["kv_context"], hd), np.float16)
+        oV = np.zeros_like(oK)
+        oK[:, :ctx0], oV[:, :ctx0] = caches[l]
+        rows = []
+        ref = O.stack_forward(cur, one, Wl, mirror=True, kv=lambda _l: (oK, oV), ctx=ctx0, new_rows=rows)
+        ref_pure = O.stack_forward(cur, one, Wl, mirror=False, kv=lambda _l: (oK, oV), ctx=ctx0)
+        oK[:, ctx0:ctx0 + M] = rows[0][0].transpose(1, 0, 2).astype(np.float16)     # [M][n_kv][hd] -> positions
+        oV[:, ctx0:ctx0 + M] = rows[0][1].transpose(1, 0, 2).astype(np.float16)
+        ref_d = O.stack_forward(cur_d, one, Wl, mirror=True, kv=lambda _l: (oK, oV), ctx=ctx0 + M)
+        st = B.Stack(B.Plan(one, 1 << 30, M))
+        load(st, [0], Wl)
+        got, got_d, _ = run(st, lambda _l: caches[l], 1, cur, cur_d)
+        st.close()
+        e, ep, ed = Hn.rel_err(got, ref), Hn.rel_err(got, ref_pure), Hn.rel_err(got_d, ref_d)
+        _say("ctx", ctx0, "M", M, "layer", l, "err %.2e (pure %.2e)  next token %.2e" % (e, ep, ed))
+        assert np.isfinite(got).all() and e <= TOL and ep <= TOL and ed <= TOL
+        cur, cur_d = got, got_d
+    # the whole stack, three placements of the cache: the chain's bits
+    full = B.Plan(cfg, 1 << 40, M).summary()
+    slot = B.Plan(cfg, full.workspace_bytes + full.weight_bytes - 4096, M).summary().slot_bytes
+    budgets = [full.workspace_bytes + full.weight_bytes + 4096,
+               full.workspace_bytes + (full.weight_bytes + 2 * slot) // 2 + 4096,
+               full.workspace_bytes + 2 * slot + 4096]
+    for b in budgets:
+        plan = B.Plan(cfg, b, M)
+        kvs = [s for s in plan.shards() if s.kind == B.PS_SHARD_KV]
+        st = B.Stack(plan)
+        load(st, range(L), Wall)
+        got, got_d, streamed = run(st, lambda l: caches[l], L, x, xd)
+        _say("  budget", b, "cache shards pinned", sum(s.resident for s in kvs), "of", len(kvs), "streamed %d B" % streamed)
+        np.testing.assert_array_equal(got.view(np.uint16), cur.view(np.uint16))
+        np.testing.assert_array_equal(got_d.view(np.uint16), cur_d.view(np.uint16))
+        st.close()
+        plan.close()
+
+
+def test_chunked_prefill_fills_the_cache_it_then_decodes_over():
+    """150 prompt tokens through a 64-token tier of a stack with a KV cache (three trips, each attending
+    over the cache and the rows the earlier trips appended), then decode steps over the filled cache.
+    Causal attention does not depend on how the prompt is chunked: the oracle takes it in one piece."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    ctx0, n, steps = 40, 150, 3
+    cfg = _kv_cfg(1, ctx0 + n + steps + 4)      # one layer: this is about chunking and the context, not depth
+    W = Hn.WeightCache(cfg, 37)
+    n_kv, hd, L = cfg["n_kv_heads"], cfg["head_dim"], cfg["n_layers"]
+    caches = [S.kv_cache(37, l, n_kv, ctx0, hd) for l in range(L)]
+    x = S.activations(37, 0, n, cfg["hidden"])
+    xs = [S.activations(37, 1 + t, 1, cfg["hidden"]) for t in range(steps)]
+    oK = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    oV = [np.zeros((n_kv, cfg["kv_context"], hd), np.float16) for _ in range(L)]
+    for l in range(L):
+        oK[l][:, :ctx0], oV[l][:, :ctx0] = caches[l]
+    rows = []
+    ref = O.stack_forward(x, cfg, W, mirror=True, kv=lambda l: (oK[l], oV[l]), ctx=ctx0, new_rows=rows)
+    for l, (kn, vn) in enumerate(rows):
+        oK[l][:, ctx0:ctx0 + n] = kn.transpose(1, 0, 2).astype(np.float16)
+        oV[l][:, ctx0:ctx0 + n] = vn.transpose(1, 0, 2).astype(np.float16)
+    refs_d = []
+    for t in range(steps):
+        rows = []
+        refs_d.append(O.stack_forward(xs[t], cfg, W, mirror=True, kv=lambda l: (oK[l], oV[l]), ctx=ctx0 + n + t, new_rows=rows))
+        for l, (kn, vn) in enumerate(rows):
+            oK[l][:, ctx0 + n + t], oV[l][:, ctx0 + n + t] = kn.astype(np.float16), vn.astype(np.float16)
+    table = B.TierTable(cfg, 1 << 30)
+    assert table.entry(4).feasible and table.entry(0).feasible
+    st = B.Stack(table.plan(4))                   # the 64-token tier
+    for layer in range(L):
+        for k, ex, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, k, ex, *W(layer, k, ex))
+        for g in range(n_kv):
+            st.load_kv(layer, g, caches[layer][0][g], caches[layer][1][g])
+    xin = torch.from_numpy(x).to(st.device)
+    xout = torch.zeros_like(xin)
+    st.set_context(ctx0)
+    assert B.chunked_forward(st, xin, xout) == 3
+    st.synchronize()
+    e = Hn.rel_err(xout.cpu().numpy(), ref)
+    _say("chunked prefill over the cache: err %.2e" % e)
+    assert e <= TOL
+    for t in range(steps):                        # the context has advanced past the prompt by itself
+        xi = torch.from_numpy(xs[t]).to(st.device)
+        xo = torch.zeros_like(xi)
+        B.chunked_forward(st, xi, xo)
+        st.synchronize()
+        ed = Hn.rel_err(xo.cpu().numpy(), refs_d[t])
+        _say("  decode step", t, "err %.2e" % ed)
+        assert ed <= TOL
+    st.close()
+
+
 def test_error_paths_return_codes_and_leave_the_stack_usable():
     """Misuse through the C ABI: every case returns an error code with a text, none faults, and the
     stack still computes the right result afterwards."""

@@ -373,13 +373,24 @@ def test_kv_cache_shards_rank_between_attention_and_ffn():
     assert sorted(copied) == [i for i, s in enumerate(got) if not s.resident]
 
 
-def test_kv_cache_plans_are_one_token_only():
+def test_kv_cache_plans_take_chunks_that_fit_the_cache():
+    """With a KV cache a plan takes one token, or a chunk of new tokens (chunked prefill over the cache);
+    the chunk must leave room in the cache, and its attention partials count as workspace, so the
+    tier table has a schedule for every tier that fits."""
     cfg = _kv_cfg()
-    with pytest.raises(B.PshardError):
-        B.Plan(cfg, 1 << 40, 16)
+    cap = cfg["kv_context"]
+    p1, p16 = B.Plan(cfg, 1 << 40, 1).summary(), B.Plan(cfg, 1 << 40, 16).summary()
+    assert p16.workspace_bytes > p1.workspace_bytes
+    with pytest.raises(B.PshardError) as e:
+        B.Plan(cfg, 1 << 40, cap)               # a chunk as long as the cache leaves no room
+    assert e.value.code == B.PS_E_BUDGET
     tb = B.TierTable(cfg, 1 << 40)
-    assert [e.feasible for e in tb.entries()] == [1] + [0] * (B.PS_NTIERS - 1)
+    feas = [bool(x.feasible) for x in tb.entries()]
+    assert feas == [B.lib().ps_tier_tokens(t) < cap for t in range(B.PS_NTIERS)] and feas[0] and feas[2]
     assert tb.pick(1).tier == 0
+    prof = B.make_profile(cpu_gbps=150.0)
+    with pytest.raises(B.PshardError):          # chunks over a cache keep the GPU-only plan
+        B.Plan(cfg, 1 << 40, 16, profile=prof, kind=B.PS_PLAN_STATIC)
     bad = dict(cfg, no_attn=True)
     with pytest.raises(B.PshardError):
         B.Plan(bad, 1 << 40, 1)
