@@ -412,15 +412,16 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
                         void *compute_stream, void *copy_stream, ps_stack **out);
 /* One stack for every token tier of a budget (Algorithm 1: the planning phase leaves one schedule
  * per tier; at inference PickTier chooses one, SetupForSched installs it, and the schedule runs).
- * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans, no KV cache: a cache is
- * state that a tier switch would have to move) to one
+ * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans) to one
  * arena of the table's budget and installs the lowest feasible tier (it pins the most).  Every
  * tier's arena is laid out [pinned shards in priority order | scratch slots | workspace], so a shard
  * that two tiers pin lies at the same place in both, and the library keeps a packed image of every
  * matrix in pinned host memory (the whole model, host side).  ps_stack_set_tier installs another
  * tier's schedule without reloading or repacking anything: shards the new tier pins and whose bytes
  * are still in place stay; those that the previous tier's larger workspace or slots overwrote are
- * copied from the host images again (*uploaded_bytes, may be NULL, receives how much).  It waits
+ * copied from the host images again (*uploaded_bytes, may be NULL, receives how much).  KV caches
+ * are state, not copies: a cache shard that the two tiers place differently (pinned in one, in the
+ * host pool in the other) moves with the rows written so far (counted in *uploaded_bytes).  It waits
  * for both streams first; PS_E_STATE before every matrix is loaded or on a single-plan stack,
  * PS_E_ARG for an infeasible tier.  Outputs do not depend on which tiers ran before.
  * ps_stack_tier reports the installed tier and its token count (for a single-plan stack: the plan's). */

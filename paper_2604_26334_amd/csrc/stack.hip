@@ -83,6 +83,7 @@ struct ps_stack {
     hipEvent_t ev_step = nullptr;             // KV stacks: end of the previous forward's compute
     bool step_pending = false;
     bool kv_copied = false;                   // some kv shard is not resident: the copy stream reads appended rows
+    uint32_t kv_rows = 0;                     // cache positions written so far (loaded or appended): what a tier switch moves
     bool profiling = false;
     bool own_rinv_launch = false;             // decode mode 2: RMS factors always from rinv_kernel
     const void *rinv_of = nullptr;            // rows whose RMS factors the last residual epilogue left in the workspace
@@ -737,6 +738,20 @@ int32_t bind_plan(ps_stack *st) {
         st->have_dense_sched = true;
     }
     st->use_graph = st->decode_mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
+    if (p.g.kv) {
+        // home of every kv head's cache: where its rows live between steps (arena or pinned pool)
+        const auto &m = p.g.m;
+        std::vector<uint64_t> home((size_t)m.n_layers * m.n_kv_heads, 0);
+        st->kv_copied = false;
+        for (size_t i = 0; i < p.shards.size(); ++i) {
+            const ps::Shard &s = p.shards[i];
+            if (s.kind != PS_SHARD_KV) continue;
+            if (!s.resident) st->kv_copied = true;
+            home[(size_t)s.layer * m.n_kv_heads + s.expert] =
+                (uint64_t)(uintptr_t)(s.resident ? st->arena + s.offset : st->shard_host[i]);
+        }
+        PS_HIP(hipMemcpy(st->ws_base + p.ws.kvhome, home.data(), home.size() * 8, hipMemcpyHostToDevice));
+    }
     return PS_OK;
 }
 
@@ -758,8 +773,8 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
     for (const ps_plan *q : plans) {
         if (!q) continue;
         any_slots |= q->n_slots != 0;
-        if (multi && (q->cpu_bytes || q->g.kv)) {
-            ps::set_error("a stack of several tiers takes GPU-only plans without a KV cache"); return PS_E_ARG;
+        if (multi && q->cpu_bytes) {
+            ps::set_error("a stack of several tiers takes GPU-only plans"); return PS_E_ARG;
         }
     }
     if (compute_stream == copy_stream && any_slots) {
@@ -799,6 +814,8 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
             if (p.g.has_attn) {
                 mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_QKV, ps::kNoExpert), p.g.qkv.bytes});
                 mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_O, ps::kNoExpert), p.g.o.bytes});
+                // a cache shard's host home, used by the tiers that do not pin it
+                if (p.g.kv) for (uint32_t h = 0; h < m.n_kv_heads; ++h) mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_KV, h), p.g.kv_shard_bytes});
             }
             if (!p.g.moe) {
                 mats.push_back({std::make_tuple(l, (uint32_t)PS_SHARD_GATE_UP, ps::kNoExpert), p.g.gate_up.bytes});
@@ -896,20 +913,8 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
     if (hipHostMalloc(&st->stage, st->stage_bytes, hipHostMallocDefault) != hipSuccess) {
         ps::set_error("hipHostMalloc for staging failed"); return fail(PS_E_HIP);
     }
-    if (p.g.kv) {
-        // home of every kv head's cache: where its rows live between steps (arena or pinned pool)
-        std::vector<uint64_t> home((size_t)m.n_layers * m.n_kv_heads, 0);
-        for (size_t i = 0; i < p.shards.size(); ++i) {
-            const ps::Shard &s = p.shards[i];
-            if (s.kind != PS_SHARD_KV) continue;
-            if (!s.resident) st->kv_copied = true;
-            home[(size_t)s.layer * m.n_kv_heads + s.expert] =
-                (uint64_t)(uintptr_t)(s.resident ? st->arena + s.offset : st->shard_host[i]);
-        }
-        if (hipMemcpy(st->ws_base + p.ws.kvhome, home.data(), home.size() * 8, hipMemcpyHostToDevice) != hipSuccess ||
-            hipEventCreateWithFlags(&st->ev_step, hipEventDisableTiming) != hipSuccess) {
-            ps::set_error("KV cache set-up failed"); return fail(PS_E_HIP);
-        }
+    if (p.g.kv && hipEventCreateWithFlags(&st->ev_step, hipEventDisableTiming) != hipSuccess) {
+        ps::set_error("KV cache set-up failed"); return fail(PS_E_HIP);
     }
     *out = st;
     return PS_OK;
@@ -978,6 +983,29 @@ int32_t ps_stack_set_tier(ps_stack *st, uint32_t tier, uint64_t *uploaded_bytes)
     if (tier == st->active_tier) return PS_OK;
     for (auto &g : st->graphs) (void)hipGraphExecDestroy(g.second);
     st->graphs.clear();
+    // KV caches are state, not copies of something on the host: a cache shard whose home changes
+    // with the tier (pinned in one, streamed in the other) moves with its rows, through its host home
+    std::map<std::pair<uint32_t, uint32_t>, std::pair<uint32_t, uint64_t>> old_kv;   // (layer, head) -> (resident, offset)
+    const uint64_t kv_rows_b = (uint64_t)st->kv_rows * st->plan.g.m.head_dim * 2;
+    const uint64_t kv_vbase = (uint64_t)st->plan.g.m.kv_context * st->plan.g.m.head_dim * 2;
+    uint64_t moved = 0;
+    if (st->plan.g.kv) {
+        const ps_plan &np = st->tiers[tier];
+        std::map<std::pair<uint32_t, uint32_t>, std::pair<uint32_t, uint64_t>> new_kv;
+        for (const ps::Shard &sh : np.shards)
+            if (sh.kind == PS_SHARD_KV) new_kv[{sh.layer, sh.expert}] = {sh.resident, sh.offset};
+        for (size_t i = 0; i < st->plan.shards.size(); ++i) {
+            const ps::Shard &sh = st->plan.shards[i];
+            if (sh.kind != PS_SHARD_KV) continue;
+            old_kv[{sh.layer, sh.expert}] = {sh.resident, sh.offset};
+            const auto nk = new_kv[{sh.layer, sh.expert}];
+            if (sh.resident == 1 && kv_rows_b && (nk.first != 1 || nk.second != sh.offset)) {
+                PS_HIP(hipMemcpy(st->shard_host[i], st->arena + sh.offset, kv_rows_b, hipMemcpyDeviceToHost));
+                PS_HIP(hipMemcpy(st->shard_host[i] + kv_vbase, st->arena + sh.offset + kv_vbase, kv_rows_b, hipMemcpyDeviceToHost));
+                moved += 2 * kv_rows_b;
+            }
+        }
+    }
     // the tier that ran until now used the tail of the arena from its slots on; so will the new one
     clobber_from(st, std::min(st->plan.scratch_off, st->tiers[tier].scratch_off));
     st->plan = st->tiers[tier];
@@ -985,10 +1013,20 @@ int32_t ps_stack_set_tier(ps_stack *st, uint32_t tier, uint64_t *uploaded_bytes)
     const int32_t rc = bind_plan(st);
     if (rc) return rc;
     const ps_plan &p = st->plan;
-    uint64_t up = 0;
+    uint64_t up = moved;
     for (size_t i = 0; i < p.shards.size(); ++i) {
         const ps::Shard &sh = p.shards[i];
         if (sh.resident != 1) continue;
+        if (sh.kind == PS_SHARD_KV) {   // back into the arena if it was not there, or not at this place
+            const auto ok = old_kv[{sh.layer, sh.expert}];
+            if (kv_rows_b && (ok.first != 1 || ok.second != sh.offset)) {
+                PS_HIP(hipMemcpyAsync(st->arena + sh.offset, st->shard_host[i], kv_rows_b, hipMemcpyHostToDevice, st->compute));
+                PS_HIP(hipMemcpyAsync(st->arena + sh.offset + kv_vbase, st->shard_host[i] + kv_vbase, kv_rows_b, hipMemcpyHostToDevice, st->compute));
+                up += 2 * kv_rows_b;
+            }
+            note_content(st, sh);
+            continue;
+        }
         // bytes of the shard already in place: a record of the same matrix under the same tile -> address map
         uint64_t have = 0;
         const uint64_t tb = shard_tile_bytes(p.g, sh.kind);
@@ -1120,6 +1158,7 @@ int32_t ps_stack_load_kv(ps_stack *st, uint32_t layer, uint32_t kv_head, const u
     const ps::Shard &s = p.shards[si];
     const size_t row_bytes = (size_t)m.head_dim * 2, vbase = (size_t)m.kv_context * row_bytes;
     if (n_pos == 0) return PS_OK;
+    st->kv_rows = std::max(st->kv_rows, n_pos);
     PS_HIP(hipStreamSynchronize(st->compute));
     if (st->copy) PS_HIP(hipStreamSynchronize(st->copy));
     if (s.resident) {
@@ -1184,6 +1223,7 @@ static int32_t forward_impl(ps_stack *st, const void *x_in, void *x_out, const f
         // this step's cache copies read rows the previous step appended from the compute stream
         if (st->kv_copied && st->step_pending) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_step, 0));
     }
+    if (p.g.kv) st->kv_rows = std::max(st->kv_rows, st->ctx + n_valid);   // rows this forward appends
     if (!p.g.moe) {
         const int32_t rc = run_schedule(st, st->dense_sched, static_cast<const __half *>(x_in), static_cast<__half *>(x_out));
         if (rc == PS_OK && st->kv_copied) { PS_HIP(hipEventRecord(st->ev_step, st->compute)); st->step_pending = true; }

@@ -563,6 +563,75 @@ def test_chunked_prefill_fills_the_cache_it_then_decodes_over():
     st.close()
 
 
+def test_one_stack_prefills_into_the_cache_and_decodes_in_the_one_token_tier():
+    """The whole inference phase with a KV cache on ONE stack: the 64-token tier is installed, the prompt
+    is prefilled in chunks (its rows go into the cache, part of which this tier streams), the one-token
+    tier is installed (cache shards it pins move into the arena with their rows) and decode steps attend
+    over everything; then back to the chunk tier for more prompt tokens.  One layer at a time against the
+    oracle would repeat the tests above: here a one-layer stack, end to end."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    ctx0, n, steps, n2 = 40, 150, 3, 20
+    cfg = _kv_cfg(1, ctx0 + n + steps + n2 + 4)
+    W = Hn.WeightCache(cfg, 41)
+    n_kv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    cache = S.kv_cache(41, 0, n_kv, ctx0, hd)
+    oK = np.zeros((n_kv, cfg["kv_context"], hd), np.float16)
+    oV = np.zeros_like(oK)
+    oK[:, :ctx0], oV[:, :ctx0] = cache
+    kvf = lambda _l: (oK, oV)
+
+    def oracle(x, ctx):
+        rows = []
+        ref = O.stack_forward(x, cfg, W, mirror=True, kv=kvf, ctx=ctx, new_rows=rows)
+        kn, vn = rows[0]
+        if x.shape[0] == 1:
+            oK[:, ctx], oV[:, ctx] = kn.astype(np.float16), vn.astype(np.float16)
+        else:
+            oK[:, ctx:ctx + x.shape[0]] = kn.transpose(1, 0, 2).astype(np.float16)
+            oV[:, ctx:ctx + x.shape[0]] = vn.transpose(1, 0, 2).astype(np.float16)
+        return ref
+
+    x = S.activations(41, 0, n, cfg["hidden"])
+    xs = [S.activations(41, 1 + t, 1, cfg["hidden"]) for t in range(steps)]
+    x2 = S.activations(41, 9, n2, cfg["hidden"])
+    full64 = B.Plan(cfg, 1 << 40, 64).summary()
+    table = B.TierTable(cfg, full64.workspace_bytes + int(full64.weight_bytes * 0.7))
+    pinned = {t: sum(s.resident for s in table.plan(t).shards() if s.kind == B.PS_SHARD_KV) for t in (0, 4)}
+    _say("cache shards pinned: one-token tier %d, 64-token tier %d of %d" % (pinned[0], pinned[4], n_kv))
+    assert pinned[0] == n_kv and pinned[4] < n_kv
+    st = B.Stack(table)
+    for k, ex, N, K in S.matrix_shapes(cfg):
+        st.load_matrix(0, k, ex, *W(0, k, ex))
+    for g in range(n_kv):
+        st.load_kv(0, g, cache[0][g], cache[1][g])
+
+    def gpu(xnp):
+        xin = torch.from_numpy(xnp).to(st.device)
+        xout = torch.zeros_like(xin)
+        B.chunked_forward(st, xin, xout)
+        st.synchronize()
+        return xout.cpu().numpy()
+
+    st.set_tier(4)
+    st.set_context(ctx0)
+    e = Hn.rel_err(gpu(x), oracle(x, ctx0))
+    _say("prefill of %d tokens in the 64-token tier: err %.2e" % (n, e))
+    assert e <= TOL
+    up = st.set_tier(0)
+    _say("switch to the one-token tier moved / pinned again %d B" % up)
+    assert up > 0
+    for t in range(steps):
+        e = Hn.rel_err(gpu(xs[t]), oracle(xs[t], ctx0 + n + t))
+        _say("  decode step %d: err %.2e" % (t, e))
+        assert e <= TOL
+    st.set_tier(4)                               # more prompt tokens: the cache moves back with its new rows
+    e = Hn.rel_err(gpu(x2), oracle(x2, ctx0 + n + steps))
+    _say("second prompt piece of %d tokens: err %.2e" % (n2, e))
+    assert e <= TOL
+    st.close()
+
+
 def test_error_paths_return_codes_and_leave_the_stack_usable():
     """Misuse through the C ABI: every case returns an error code with a text, none faults, and the
     stack still computes the right result afterwards."""
