@@ -349,6 +349,48 @@ def kv_leg(B, S, torch, cfg, seed, prof, context, budgets, steps, decode_mode=1)
     return out
 
 
+def kv_prefill_leg(B, S, torch, cfg, seed, prof, context, prompt, tier_tokens, budget):
+    """Chunked prefill OVER a KV cache: `prompt` new tokens at a context of `context` cached positions,
+    in chunks of `tier_tokens` (causal attention inside a chunk, rows appended to the cache), then decode
+    steps over the filled cache through the same schedule."""
+    kcfg = dict(cfg, kv_context=context + prompt + 64)
+    plan = B.Plan(kcfg, int(budget), tier_tokens, profile=prof)
+    st = B.Stack(plan)
+    B.load_synthetic([st], kcfg, seed, threads=min(16, os.cpu_count() or 8))
+    K, V = S.kv_cache(seed, 0, kcfg["n_kv_heads"], context, kcfg["head_dim"])
+    for layer in range(kcfg["n_layers"]):
+        for g in range(kcfg["n_kv_heads"]):
+            st.load_kv(layer, g, K[g], V[g])
+    dev = st.device
+    x = torch.from_numpy(S.activations(seed, 800, prompt, kcfg["hidden"])).to(dev)
+    y = torch.empty_like(x)
+    xd = torch.from_numpy(S.activations(seed, 801, 1, kcfg["hidden"])).to(dev)
+    yd = torch.empty_like(xd)
+    times = []
+    for rep in range(3):
+        st.set_context(context)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        trips = B.chunked_forward(st, x, y)
+        st.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3)
+    t0 = time.perf_counter()
+    nd = 8
+    for i in range(nd):
+        B.chunked_forward(st, xd, yd)
+    st.synchronize()
+    dec = (time.perf_counter() - t0) * 1e3 / nd
+    s = plan.summary()
+    r = dict(budget_bytes=int(budget), context=context, prompt_tokens=prompt, chunk_tokens=tier_tokens, trips=trips,
+             ttft_ms=min(times[1:]), ms_per_chunk=min(times[1:]) / trips, decode_ms_per_token_in_this_tier=dec,
+             resident_bytes=s.resident_bytes, workspace_bytes=s.workspace_bytes, streamed_bytes=s.streamed_bytes,
+             kv_cache_bytes=context * kcfg["n_kv_heads"] * kcfg["head_dim"] * 4 * kcfg["n_layers"])
+    log("prefill over a cache of %d positions: %d tokens in chunks of %d: %.1f ms (%.2f ms per chunk); decode in the same tier %.2f ms/token" % (
+        context, prompt, tier_tokens, r["ttft_ms"], r["ms_per_chunk"], dec))
+    st.close()
+    return r
+
+
 def head_leg(B, S, torch, cfg, seed, prof, vocab, budgets, steps):
     """Decode with the output head (final RMSNorm + projection to `vocab` logits, lowest priority
     class): at a budget that holds everything it is one more resident GEMV, at a tight one it is the
@@ -603,6 +645,9 @@ def main():
     fresh()
     if "kv" in args.extra and args.layers == 32:
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50, args.decode_mode)
+    fresh()
+    if "kv" in args.extra and args.layers == 32:
+        extra["prefill_over_cache_4k"] = kv_prefill_leg(B, S, torch, cfg, seed, prof, 4096, 256, 64, 8e9)
     fresh()
     if "head" in args.extra and args.layers == 32:
         extra["decode_output_head_128k"] = head_leg(B, S, torch, cfg, seed, prof, 128256, [8e9, 4e9], 100)

@@ -75,3 +75,22 @@ def rel_err(got, ref):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     return float(np.abs(got - ref).max() / np.abs(ref).max())
+
+
+def kv_token_reference_from_gpu_qkv(cfg, weights, x_row, qkv_row, Kc, Vc, ctx):
+    """One-layer reference for ONE new token at context ctx that takes the token's QKV row as the GPU
+    stored it (fp16) instead of projecting it again: h = x + Linear_O(fp16(Attention(q, cache rows +
+    own k, v))), out = FFN half of h, rounding where the GPU stores fp16.  Softmax over scores of the
+    size this stack produces is sharp: a last-bit difference in q or k moves weight between positions,
+    so the attention kernel is checked on the very q, k, v it read (the projection that made them is
+    checked on its own).  Kc, Vc: float16 [n_kv][cap][hd] with rows 0 .. ctx - 1 valid."""
+    n_q, n_kv, hd = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    y = np.asarray(qkv_row, dtype=np.float16).astype(np.float64).reshape(-1)
+    k_new = y[n_q * hd:(n_q + n_kv) * hd].reshape(n_kv, 1, hd)
+    v_new = y[(n_q + n_kv) * hd:].reshape(n_kv, 1, hd)
+    K = np.concatenate([np.asarray(Kc)[:, :ctx].astype(np.float64), k_new], axis=1)
+    V = np.concatenate([np.asarray(Vc)[:, :ctx].astype(np.float64), v_new], axis=1)
+    A = O.attn_decode(y[:n_q * hd], K, V, n_q, n_kv, hd).astype(np.float16).astype(np.float64)
+    h = O.linear(A[None, :], *weights(0, S.MAT_O, None)) + np.asarray(x_row, dtype=np.float64).reshape(1, -1)
+    h = h.astype(np.float16).astype(np.float64)
+    return O.dense_ffn_half(h, cfg, weights(0, S.MAT_GATE, None), weights(0, S.MAT_UP, None), weights(0, S.MAT_DOWN, None), True)

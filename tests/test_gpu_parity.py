@@ -461,12 +461,14 @@ def test_chunk_of_new_tokens_attends_over_the_kv_cache(ctx0, M):
         st.forward(xin, xout)
         st.synchronize()
         streamed = st.stats().streamed_bytes_step
+        qkv = st.debug_buffer(0, np.float16, (M, (cfg["n_q_heads"] + 2 * n_kv) * hd)).copy()    # last layer's QKV rows
         xdi = torch.from_numpy(xd_np).to(st.device)
         xdo = torch.zeros_like(xdi)
         st.set_context(ctx0 + M)
         B.chunked_forward(st, xdi, xdo)          # one token through the chunk plan's schedule
         st.synchronize()
-        return xout.cpu().numpy(), xdo.cpu().numpy(), streamed
+        qkv_d = st.debug_buffer(0, np.float16, (M, (cfg["n_q_heads"] + 2 * n_kv) * hd))[0].copy()   # the token's own QKV row
+        return xout.cpu().numpy(), xdo.cpu().numpy(), streamed, (qkv, qkv_d)
 
     # layer by layer on one-layer stacks, against the oracle on the same inputs
     cur, cur_d = x, xd
@@ -478,13 +480,21 @@ def test_chunk_of_new_tokens_attends_over_the_kv_cache(ctx0, M):
         rows = []
         ref = O.stack_forward(cur, one, Wl, mirror=True, kv=lambda _l: (oK, oV), ctx=ctx0, new_rows=rows)
         ref_pure = O.stack_forward(cur, one, Wl, mirror=False, kv=lambda _l: (oK, oV), ctx=ctx0)
-        oK[:, ctx0:ctx0 + M] = rows[0][0].transpose(1, 0, 2).astype(np.float16)     # [M][n_kv][hd] -> positions
-        oV[:, ctx0:ctx0 + M] = rows[0][1].transpose(1, 0, 2).astype(np.float16)
-        ref_d = O.stack_forward(cur_d, one, Wl, mirror=True, kv=lambda _l: (oK, oV), ctx=ctx0 + M)
         st = B.Stack(B.Plan(one, 1 << 30, M))
         load(st, [0], Wl)
-        got, got_d, _ = run(st, lambda _l: caches[l], 1, cur, cur_d)
+        got, got_d, _, (qkv, qkv_d) = run(st, lambda _l: caches[l], 1, cur, cur_d)
         st.close()
+        # the next token attends over the rows the GPU appended: the oracle gets exactly those rows (a
+        # last-bit difference in a row can move softmax weight between positions; the chunk's rows
+        # themselves are checked here and, through `ref`, by the chunk's own attention)
+        nq = cfg["n_q_heads"]
+        assert Hn.rel_err(qkv[:, nq * hd:], np.concatenate([rows[0][0].reshape(M, -1), rows[0][1].reshape(M, -1)], axis=1)) <= TOL
+        oK[:, ctx0:ctx0 + M] = qkv[:, nq * hd:(nq + n_kv) * hd].reshape(M, n_kv, hd).transpose(1, 0, 2)
+        oV[:, ctx0:ctx0 + M] = qkv[:, (nq + n_kv) * hd:].reshape(M, n_kv, hd).transpose(1, 0, 2)
+        # ... and its own QKV row: the projection against the oracle's, the rest of the layer on the GPU's row
+        y_d = O.linear(O.rmsnorm(cur_d, cfg["rms_eps"]), *Wl(0, S.MAT_QKV, None))
+        assert Hn.rel_err(qkv_d[None, :], y_d) <= TOL
+        ref_d = Hn.kv_token_reference_from_gpu_qkv(one, Wl, cur_d, qkv_d, oK, oV, ctx0 + M)
         e, ep, ed = Hn.rel_err(got, ref), Hn.rel_err(got, ref_pure), Hn.rel_err(got_d, ref_d)
         _say("ctx", ctx0, "M", M, "layer", l, "err %.2e (pure %.2e)  next token %.2e" % (e, ep, ed))
         assert np.isfinite(got).all() and e <= TOL and ep <= TOL and ed <= TOL
@@ -500,7 +510,7 @@ def test_chunk_of_new_tokens_attends_over_the_kv_cache(ctx0, M):
         kvs = [s for s in plan.shards() if s.kind == B.PS_SHARD_KV]
         st = B.Stack(plan)
         load(st, range(L), Wall)
-        got, got_d, streamed = run(st, lambda l: caches[l], L, x, xd)
+        got, got_d, streamed, _ = run(st, lambda l: caches[l], L, x, xd)
         _say("  budget", b, "cache shards pinned", sum(s.resident for s in kvs), "of", len(kvs), "streamed %d B" % streamed)
         np.testing.assert_array_equal(got.view(np.uint16), cur.view(np.uint16))
         np.testing.assert_array_equal(got_d.view(np.uint16), cur_d.view(np.uint16))
