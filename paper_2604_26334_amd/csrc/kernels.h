@@ -104,6 +104,7 @@ struct AttnChunkArgs {
     uint64_t head_stride;
     uint32_t cap, ctx, head0, nheads, group, n_q;
     uint32_t row_stride, causal, ntok, q_stride, chunk0, chunk_cap;
+    uint32_t tok_per_wg;   // set by the launch: tokens one workgroup serves
     const __half *q;
     float *part;
 };

@@ -737,10 +737,12 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_k
             vf[it][2 * e + 1] = (float)pr.y;
         }
     }
-    // first token that sees any position of this chunk (causal: token chunk * kAttnPos)
-    const uint32_t t_first = a.causal ? chunk * kAttnPos : 0;
+    // this workgroup's share of the tokens (blockIdx.z), from the first token that sees any position of
+    // this chunk (causal: token chunk * kAttnPos)
+    const uint32_t t_lo = blockIdx.z * a.tok_per_wg, t_hi = min(a.ntok, t_lo + a.tok_per_wg);
+    const uint32_t t_first = max(t_lo, a.causal ? chunk * kAttnPos : 0u);
 #pragma unroll 1
-    for (uint32_t t = t_first; t < a.ntok; ++t) {
+    for (uint32_t t = t_first; t < t_hi; ++t) {
         const uint32_t limit = a.causal ? t + 1 : a.ctx;
         uint4 qv[G];
 #pragma unroll
@@ -825,10 +827,16 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_k
     }
 }
 
-hipError_t launch_attn_chunk(const AttnChunkArgs &a, hipStream_t st) {
+hipError_t launch_attn_chunk(const AttnChunkArgs &a_in, hipStream_t st) {
+    AttnChunkArgs a = a_in;
     const uint32_t npos = a.causal ? a.ntok : a.ctx;
     if (npos == 0 || a.nheads == 0 || a.ntok == 0) return hipSuccess;
-    dim3 grid((npos + kAttnPos - 1) / kAttnPos, a.nheads);
+    // the tokens are shared out over blockIdx.z until the launch has about four workgroups per CU (each
+    // re-reads its 256 positions, from the caches after the first); at least four tokens per workgroup
+    const uint32_t wg_xy = (npos + kAttnPos - 1) / kAttnPos * a.nheads;
+    const uint32_t zmax = std::max(1u, 1024u / wg_xy);
+    a.tok_per_wg = std::max(4u, (a.ntok + zmax - 1) / zmax);
+    dim3 grid((npos + kAttnPos - 1) / kAttnPos, a.nheads, (a.ntok + a.tok_per_wg - 1) / a.tok_per_wg);
     if (a.chunk0 + grid.x > a.chunk_cap) return hipErrorInvalidValue;
     if ((uint64_t)npos * a.row_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;   // 32-bit buffer offsets
     switch (a.group) {
