@@ -827,25 +827,167 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_k
     }
 }
 
+// ------------------------------------------------------------------------------------
+// The same partials on the matrix cores.  Rows of the score matrix are (token, query head of the
+// kv group) pairs, 16 per wave, 64 per workgroup; a workgroup covers 256 positions of one kv head in
+// 8 steps of 32.
+//  scores, transposed: S^T = K Q^T by v_mfma_f32_16x16x32_f16 with A = 16 positions x 32 dims of K
+//   (lane (p, c) loads 16 bytes of a K row straight from memory) and B = the wave's 16 query rows
+//   (registers, loaded once): the accumulator then holds, in lane (row j, rg), four positions of row j;
+//  weights x values, transposed: O^T = V^T P^T with B = the weights exactly as the score
+//   accumulators hold them (the two 16-position tiles of a step are numbered so that lane group c
+//   owns 8 consecutive positions: 4 from each tile) and A = 16 dims x 32 positions of V, read
+//   column-wise (8 two-byte reads) from the chunk's V rows staged in LDS once per workgroup.
+// Two passes over the chunk's 8 steps: all scores (64 registers) and the row maximum, then weights,
+// weight sum and O^T; per (row, chunk) the same (maximum, weight sum, 128 weighted sums) record as
+// the vector-ALU kernel writes, merged by attn_combine_chunk_kernel in chunk order.
+// ------------------------------------------------------------------------------------
+constexpr uint32_t kVRowBytes = 264;   // LDS pitch of a staged V row: 256 + 8 (8-byte writes stay aligned; column reads spread over the banks)
+
+__global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a) {
+    extern __shared__ uint4 lds_v4[];
+    unsigned char *ldsv = reinterpret_cast<unsigned char *>(lds_v4);   // [256 positions][kVRowBytes]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, c = lane >> 4;
+    const uint32_t chunk = blockIdx.x, hk = blockIdx.y, G = a.group;
+    const uint32_t kv_head = a.head0 + hk;
+    const __half *K = a.causal ? a.k_base + (size_t)kv_head * 128 : reinterpret_cast<const __half *>(reinterpret_cast<const char *>(a.k_base) + (size_t)hk * a.head_stride);
+    const __half *V = a.causal ? a.v_base + (size_t)kv_head * 128 : K + (size_t)a.cap * 128;
+    const uint32_t q0 = kv_head * G;
+    const uint32_t row_b = a.row_stride * 2u;
+    const uint32_t npos = a.causal ? a.ntok : a.ctx;
+    const uint32_t range = npos ? (npos - 1) * row_b + 256u : 0u;   // a row past the end reads as zeros
+    const uint32_t P0 = chunk * kAttnPos;
+    const uint32_t R = a.ntok * G;                                   // score rows of this kv head
+    const uint32_t row0 = blockIdx.z * 64;
+    if (row0 >= R) return;
+    // causal: the workgroup's last token sees nothing of this chunk -> nothing to write (uniform)
+    if (a.causal && min(a.ntok - 1, (row0 + 63) / G) < P0) return;
+    const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
+
+    // V rows of the chunk -> LDS (all 256 threads; 16 bytes each, 16 rounds)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+        const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
+        uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
+        dst[0] = make_uint2(v.x, v.y);
+        dst[1] = make_uint2(v.z, v.w);
+    }
+    // this wave's 16 query rows (B operand of the score MFMAs): row rho = (token, head of the group)
+    const uint32_t rho = min(row0 + wave * 16 + i, R - 1);
+    const uint32_t tok = rho / G, hq = rho % G;
+    const bool row_ok = row0 + wave * 16 + i < R;
+    const uint32_t limit = a.causal ? tok + 1 : a.ctx;               // positions below it are visible to this lane's row
+    h8_t qreg[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        qreg[kk] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(a.q + (size_t)tok * a.q_stride + (size_t)(q0 + hq) * 128 + kk * 32 + c * 8));
+
+    const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+    // pass 1: scores of the 8 steps.  Tile T of a step holds positions base + 8 (p >> 2) + 4 T + (p & 3), p = 0..15
+    f4_t S[8][2];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            const uint32_t pos = P0 + 32 * s + 8 * (i >> 2) + 4 * T + (i & 3);        // the K row this lane supplies (A operand)
+            h8_t kreg[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                kreg[kk] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(kb, pos * row_b + kk * 64 + c * 16, 0, 0));
+            f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kreg[kk], qreg[kk], acc, 0, 0, 0);
+            // lane (row i, group c) now holds positions P0 + 32 s + 8 c + 4 T + r of its row
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t pj = P0 + 32 * s + 8 * c + 4 * T + r;
+                acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
+                mx = fmaxf(mx, acc[r]);
+            }
+            S[s][T] = acc;
+        }
+    }
+    mx = rows4_meet<true>(mx);      // the row's four lanes (one per lane group) meet
+    __syncthreads();                // the staged V rows are complete
+
+    // pass 2: weights, their sum, and O^T += V^T P^T
+    f4_t O[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) O[dt] = f4_t{0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        float pv[8];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float sc = S[s][T][r];
+                pv[4 * T + r] = sc == -INFINITY ? 0.f : __expf(sc - mx);
+                l += pv[4 * T + r];
+            }
+        const h8_t Bp = {(_Float16)pv[0], (_Float16)pv[1], (_Float16)pv[2], (_Float16)pv[3],
+                         (_Float16)pv[4], (_Float16)pv[5], (_Float16)pv[6], (_Float16)pv[7]};
+        // A operand: dim 16 dt + i of the 8 positions 32 s + 8 c .. + 7 (a column of the staged rows)
+        const unsigned char *col = ldsv + (32 * s + 8 * c) * kVRowBytes + i * 2;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            h8_t Av;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Av[e] = *reinterpret_cast<const _Float16 *>(col + e * kVRowBytes + dt * 32);
+            O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Av, Bp, O[dt], 0, 0, 0);
+        }
+    }
+    l = rows4_meet<false>(l);
+    // lane (row i, group c) holds dims 16 dt + 4 c + r of its row
+    if (!row_ok || mx == -INFINITY) return;      // no such row, or a row that sees nothing of this chunk
+    float *dst = a.part + (((size_t)tok * a.n_q + q0 + hq) * a.chunk_cap + a.chunk0 + chunk) * 130;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        float2 *d2 = reinterpret_cast<float2 *>(dst + 2 + 16 * dt + 4 * c);
+        d2[0] = make_float2(O[dt][0], O[dt][1]);
+        d2[1] = make_float2(O[dt][2], O[dt][3]);
+    }
+    if (c == 0) {
+        dst[0] = mx;
+        dst[1] = l;
+    }
+}
+
 hipError_t launch_attn_chunk(const AttnChunkArgs &a_in, hipStream_t st) {
     AttnChunkArgs a = a_in;
     const uint32_t npos = a.causal ? a.ntok : a.ctx;
     if (npos == 0 || a.nheads == 0 || a.ntok == 0) return hipSuccess;
-    // the tokens are shared out over blockIdx.z until the launch has about four workgroups per CU (each
-    // re-reads its 256 positions, from the caches after the first); at least four tokens per workgroup
-    const uint32_t wg_xy = (npos + kAttnPos - 1) / kAttnPos * a.nheads;
-    const uint32_t zmax = std::max(1u, 1024u / wg_xy);
-    a.tok_per_wg = std::max(4u, (a.ntok + zmax - 1) / zmax);
-    dim3 grid((npos + kAttnPos - 1) / kAttnPos, a.nheads, (a.ntok + a.tok_per_wg - 1) / a.tok_per_wg);
-    if (a.chunk0 + grid.x > a.chunk_cap) return hipErrorInvalidValue;
-    if ((uint64_t)npos * a.row_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;   // 32-bit buffer offsets
-    switch (a.group) {
-        case 1: hipLaunchKernelGGL(attn_chunk_kernel<1>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(attn_chunk_kernel<2>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        case 4: hipLaunchKernelGGL(attn_chunk_kernel<4>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        case 8: hipLaunchKernelGGL(attn_chunk_kernel<8>, grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        default: return hipErrorInvalidValue;
+    if (a.group == 0 || a.group > 16) return hipErrorInvalidValue;
+    if (a.ntok * a.group < 16) {
+        // fewer score rows than one MFMA tile (a last chunk of one or two tokens): the vector-ALU form,
+        // the tokens shared out over blockIdx.z.  Same records; which form runs depends on the token
+        // count only, never on the placement.
+        const uint32_t wg_xy = (npos + kAttnPos - 1) / kAttnPos * a.nheads;
+        a.tok_per_wg = std::max(1u, (a.ntok + std::max(1u, 1024u / wg_xy) - 1) / std::max(1u, 1024u / wg_xy));
+        dim3 gv((npos + kAttnPos - 1) / kAttnPos, a.nheads, (a.ntok + a.tok_per_wg - 1) / a.tok_per_wg);
+        if (a.chunk0 + gv.x > a.chunk_cap || (uint64_t)npos * a.row_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        switch (a.group) {
+            case 1: hipLaunchKernelGGL(attn_chunk_kernel<1>, gv, dim3(kAttnWaves * 64), 0, st, a); break;
+            case 2: hipLaunchKernelGGL(attn_chunk_kernel<2>, gv, dim3(kAttnWaves * 64), 0, st, a); break;
+            case 4: hipLaunchKernelGGL(attn_chunk_kernel<4>, gv, dim3(kAttnWaves * 64), 0, st, a); break;
+            case 8: hipLaunchKernelGGL(attn_chunk_kernel<8>, gv, dim3(kAttnWaves * 64), 0, st, a); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
     }
+    dim3 grid((npos + kAttnPos - 1) / kAttnPos, a.nheads, (a.ntok * a.group + 63) / 64);
+    if (a.chunk0 + grid.x > a.chunk_cap) return hipErrorInvalidValue;
+    if (((uint64_t)npos + kAttnPos) * a.row_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;   // 32-bit buffer offsets
+    const size_t ldsb = (size_t)kAttnPos * kVRowBytes;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_chunk_mfma_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(attn_chunk_mfma_kernel, grid, dim3(256), ldsb, st, a);
     return hipGetLastError();
 }
 
