@@ -551,6 +551,7 @@ constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 
 constexpr int kAttnIts = 8;               // steps of 4 positions per wave
 constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
 static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
+constexpr uint32_t kVRowBytes = 264;   // LDS pitch of a staged V row: 256 + 8 (8-byte writes stay aligned; column reads spread over the banks)
 static_assert(kAttnPos == kAttnPosPerWg, "the executor numbers the chunk's own partials behind ceil(ctx / kAttnPosPerWg) cache chunks");
 
 // sum over each row of 16 lanes, result in every lane of the row (DPP: no LDS traffic)
@@ -842,7 +843,6 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_k
 // weight sum and O^T; per (row, chunk) the same (maximum, weight sum, 128 weighted sums) record as
 // the vector-ALU kernel writes, merged by attn_combine_chunk_kernel in chunk order.
 // ------------------------------------------------------------------------------------
-constexpr uint32_t kVRowBytes = 264;   // LDS pitch of a staged V row: 256 + 8 (8-byte writes stay aligned; column reads spread over the banks)
 
 __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a) {
     extern __shared__ uint4 lds_v4[];
