@@ -647,7 +647,9 @@ def main():
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50, args.decode_mode)
     fresh()
     if "kv" in args.extra and args.layers == 32:
-        extra["prefill_over_cache_4k"] = kv_prefill_leg(B, S, torch, cfg, seed, prof, 4096, 256, 64, 8e9)
+        extra["prefill_over_cache_4k"] = {"chunks_of_64": kv_prefill_leg(B, S, torch, cfg, seed, prof, 4096, 256, 64, 8e9)}
+        fresh()
+        extra["prefill_over_cache_4k"]["chunks_of_512"] = kv_prefill_leg(B, S, torch, cfg, seed, prof, 4096, 1024, 512, 8e9)
     fresh()
     if "head" in args.extra and args.layers == 32:
         extra["decode_output_head_128k"] = head_leg(B, S, torch, cfg, seed, prof, 128256, [8e9, 4e9], 100)

@@ -105,10 +105,22 @@ struct AttnChunkArgs {
     uint32_t cap, ctx, head0, nheads, group, n_q;
     uint32_t row_stride, causal, ntok, q_stride, chunk0, chunk_cap;
     uint32_t tok_per_wg;   // set by the launch: tokens one workgroup serves
+    // the one-pass form only (launch_attn_chunk_onepass): it walks the cache shards at k_base (row_stride 128,
+    // ctx positions) AND the chunk's own rows in one launch, and writes finished attention rows
+    const __half *k_own, *v_own;   // kv head 0 of token 0 in the QKV rows
+    uint32_t own_stride;           // elements between two tokens' QKV rows
+    __half *out;                   // attention rows [ntok][n_q * 128], out_stride elements apart
+    uint32_t out_stride;
     const __half *q;
     float *part;
 };
 hipError_t launch_attn_chunk(const AttnChunkArgs &a, hipStream_t st);
+// Chunks of many tokens: one launch per run of cache shards walks the cached positions and then the chunk's own
+// rows with running softmax statistics and writes out[t][q_head * 128 ..] directly (no partial records)
+hipError_t launch_attn_chunk_onepass(const AttnChunkArgs &a, hipStream_t st);
+// appends ntok tokens' K / V rows (from their QKV rows) at positions ctx .. of every kv head's cache home
+hipError_t launch_kv_append_rows(uint32_t ctx, uint32_t cap, const __half *qkv, uint32_t qkv_w, uint32_t n_q, uint32_t n_kv, uint32_t ntok,
+                                 const uint64_t *home, hipStream_t st);
 // merges every token's chunks (cache chunks below ctx, then the chunk's own) in ascending order, writes the
 // attention rows out[t][n_q * 128] (out_stride elements apart) and appends the tokens' K / V rows at
 // positions ctx .. ctx + ntok - 1 of each kv head's cache home

@@ -958,6 +958,161 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Many-token chunks (plans of kAttnOnePassTokens tokens and more): the same two products, but one
+// workgroup walks ALL positions of its 64 score rows -- the cache's chunks, then the chunk's own rows up
+// to its last token -- keeping a running maximum, weight sum and O^T per row and rescaling them when a
+// chunk raises the maximum, and writes the finished attention rows.  No partial records: their size
+// (tokens x heads x chunks) is what makes the record form unusable for long chunks over long contexts.
+// The order of the chunks is fixed, so the result does not depend on where a cache shard lives.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArgs a) {
+    extern __shared__ uint4 lds_v4[];
+    unsigned char *ldsv = reinterpret_cast<unsigned char *>(lds_v4);   // [256 positions][kVRowBytes]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, c = lane >> 4;
+    const uint32_t hk = blockIdx.x, G = a.group;
+    const uint32_t kv_head = a.head0 + hk;
+    const uint32_t q0 = kv_head * G;
+    const uint32_t R = a.ntok * G;
+    const uint32_t row0 = blockIdx.y * 64;
+    if (row0 >= R) return;
+    const uint32_t rho = min(row0 + wave * 16 + i, R - 1);
+    const uint32_t tok = rho / G, hq = rho % G;
+    const bool row_ok = row0 + wave * 16 + i < R;
+    const uint32_t last_tok = min(a.ntok - 1, (row0 + 63) / G);      // the workgroup's last token
+    h8_t qreg[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        qreg[kk] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(a.q + (size_t)tok * a.q_stride + (size_t)(q0 + hq) * 128 + kk * 32 + c * 8));
+    const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+    float m_run = -INFINITY, l_run = 0.f;
+    f4_t O[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) O[dt] = f4_t{0.f, 0.f, 0.f, 0.f};
+
+    const uint32_t nc_cache = (a.ctx + kAttnPos - 1) / kAttnPos, nc_own = last_tok / kAttnPos + 1;
+#pragma unroll 1
+    for (uint32_t cc = 0; cc < nc_cache + nc_own; ++cc) {
+        const bool own = cc >= nc_cache;                  // the same for the whole workgroup
+        const uint32_t chunk = own ? cc - nc_cache : cc;
+        const __half *K = own ? a.k_own + (size_t)kv_head * 128 : reinterpret_cast<const __half *>(reinterpret_cast<const char *>(a.k_base) + (size_t)hk * a.head_stride);
+        const __half *V = own ? a.v_own + (size_t)kv_head * 128 : K + (size_t)a.cap * 128;
+        const uint32_t row_b = (own ? a.own_stride : 128u) * 2u;
+        const uint32_t npos = own ? a.ntok : a.ctx;
+        const uint32_t range = (npos - 1) * row_b + 256u;
+        const uint32_t limit = own ? tok + 1 : a.ctx;
+        const uint32_t P0 = chunk * kAttnPos;
+        const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
+        const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
+        __syncthreads();     // every wave has left the previous chunk's staged rows
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+            const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
+            uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
+            dst[0] = make_uint2(v.x, v.y);
+            dst[1] = make_uint2(v.z, v.w);
+        }
+        f4_t S[8][2];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                const uint32_t pos = P0 + 32 * s + 8 * (i >> 2) + 4 * T + (i & 3);
+                h8_t kreg[4];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    kreg[kk] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(kb, pos * row_b + kk * 64 + c * 16, 0, 0));
+                f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kreg[kk], qreg[kk], acc, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t pj = P0 + 32 * s + 8 * c + 4 * T + r;
+                    acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
+                    mx = fmaxf(mx, acc[r]);
+                }
+                S[s][T] = acc;
+            }
+        }
+        mx = rows4_meet<true>(mx);
+        const float m_new = fmaxf(m_run, mx);
+        // a row that has seen nothing yet keeps zeros (the difference of two -inf is not a number)
+        const float resc = m_run == -INFINITY ? 0.f : __expf(m_run - m_new);
+        m_run = m_new;
+        l_run *= resc;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) O[dt] = O[dt] * resc;
+        __syncthreads();     // the staged V rows are complete
+        float l = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            float pv[8];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float sc = S[s][T][r];
+                    pv[4 * T + r] = sc == -INFINITY ? 0.f : __expf(sc - m_new);
+                    l += pv[4 * T + r];
+                }
+            const h8_t Bp = {(_Float16)pv[0], (_Float16)pv[1], (_Float16)pv[2], (_Float16)pv[3],
+                             (_Float16)pv[4], (_Float16)pv[5], (_Float16)pv[6], (_Float16)pv[7]};
+            const unsigned char *col = ldsv + (32 * s + 8 * c) * kVRowBytes + i * 2;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                h8_t Av;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) Av[e] = *reinterpret_cast<const _Float16 *>(col + e * kVRowBytes + dt * 32);
+                O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Av, Bp, O[dt], 0, 0, 0);
+            }
+        }
+        l_run += rows4_meet<false>(l);
+    }
+    if (!row_ok) return;
+    // every row sees at least its own token, so l_run > 0; lane (row i, group c) holds dims 16 dt + 4 c + r
+    const float inv = 1.0f / l_run;
+    __half *dst = a.out + (size_t)tok * a.out_stride + (size_t)(q0 + hq) * 128;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        __half2 *d2 = reinterpret_cast<__half2 *>(dst + 16 * dt + 4 * c);
+        d2[0] = __half2{to_half(O[dt][0] * inv), to_half(O[dt][1] * inv)};
+        d2[1] = __half2{to_half(O[dt][2] * inv), to_half(O[dt][3] * inv)};
+    }
+}
+
+hipError_t launch_attn_chunk_onepass(const AttnChunkArgs &a, hipStream_t st) {
+    if (a.nheads == 0 || a.ntok == 0) return hipSuccess;
+    if (a.group == 0 || a.group > 16 || !a.out || !a.k_own || !a.v_own) return hipErrorInvalidValue;
+    if (((uint64_t)a.ctx + kAttnPos) * 256u > 0x7FFFFFFFull || ((uint64_t)a.ntok + kAttnPos) * a.own_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    dim3 grid(a.nheads, (a.ntok * a.group + 63) / 64);
+    const size_t ldsb = (size_t)kAttnPos * kVRowBytes;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_chunk_onepass_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(attn_chunk_onepass_kernel, grid, dim3(256), ldsb, st, a);
+    return hipGetLastError();
+}
+
+// the tokens' K and V rows go to positions ctx .. ctx + ntok - 1 of each kv head's cache home
+__global__ __launch_bounds__(128) void kv_append_rows_kernel(uint32_t ctx, uint32_t cap, const __half *qkv, uint32_t qkv_w, uint32_t n_q,
+                                                             uint32_t n_kv, const uint64_t *home) {
+    const uint32_t g = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
+    __half *Kh = reinterpret_cast<__half *>(home[g]);
+    Kh[((size_t)ctx + t) * 128 + d] = qkv[(size_t)t * qkv_w + (size_t)(n_q + g) * 128 + d];
+    Kh[((size_t)cap + ctx + t) * 128 + d] = qkv[(size_t)t * qkv_w + (size_t)(n_q + n_kv + g) * 128 + d];
+}
+
+hipError_t launch_kv_append_rows(uint32_t ctx, uint32_t cap, const __half *qkv, uint32_t qkv_w, uint32_t n_q, uint32_t n_kv, uint32_t ntok,
+                                 const uint64_t *home, hipStream_t st) {
+    if (ntok == 0) return hipSuccess;
+    if (n_kv == 0 || (uint64_t)ctx + ntok > cap || ntok > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kv_append_rows_kernel, dim3(n_kv, ntok), dim3(128), 0, st, ctx, cap, qkv, qkv_w, n_q, n_kv, home);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_chunk(const AttnChunkArgs &a_in, hipStream_t st) {
     AttnChunkArgs a = a_in;
     const uint32_t npos = a.causal ? a.ntok : a.ctx;

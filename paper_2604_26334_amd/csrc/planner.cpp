@@ -153,8 +153,9 @@ Workspace make_workspace(const ModelGeom &g, uint32_t M, bool cpu_experts) {
         w.attn = take((uint64_t)M * g.attn_w * 2);
         // per token, query head and position chunk: running maximum, sum of weights, 128 weighted sums;
         // a chunk of several tokens adds the chunks of its own rows behind the cache's
+        // (chunks of kAttnOnePassTokens tokens and more keep running statistics in the kernel instead)
         const uint64_t chunks = (g.m.kv_context + kAttnChunk - 1) / kAttnChunk + (M > 1 ? (M + kAttnChunk - 1) / kAttnChunk : 0);
-        w.apart = take((uint64_t)M * g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
+        w.apart = take(M >= kAttnOnePassTokens ? kAlign : (uint64_t)M * g.m.n_q_heads * chunks * (g.m.head_dim + 2) * 4);
         w.kvhome = take((uint64_t)g.m.n_layers * g.m.n_kv_heads * 8);
         w.ctx = take(4);   // context length as the kernels of a replayed graph read it
     }

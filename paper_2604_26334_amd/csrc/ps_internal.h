@@ -19,6 +19,7 @@ constexpr uint32_t kGroupSb = 8;         // super-blocks per scale group
 constexpr uint64_t kSbBytes = 1024;      // 16 rows x 128 k x 4 bit
 constexpr uint64_t kAlign = 256;
 constexpr uint32_t kAttnChunk = 128;    // granule the attention partials are sized by (multiple of 64)
+constexpr uint32_t kAttnOnePassTokens = 256;   // plans of this many tokens and more: attention without partial records
 constexpr uint32_t kAttnPosPerWg = 256; // positions one attention workgroup covers (a multiple of kAttnChunk)
 
 void set_error(const char *fmt, ...);

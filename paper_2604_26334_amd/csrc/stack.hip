@@ -331,6 +331,17 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         case PS_K_ATTN: {
             const Shard &s = p.shards[op.info.shard0];
             const uint32_t ccap = (m.kv_context + kAttnChunk - 1) / kAttnChunk + (MP > 1 ? (MP + kAttnChunk - 1) / kAttnChunk : 0);
+            if (MP >= kAttnOnePassTokens) {   // many tokens: cache and own rows in one walk, finished rows out
+                AttnChunkArgs c{};
+                c.k_base = reinterpret_cast<const __half *>(wptr(op)); c.head_stride = g.kv_shard_bytes;
+                c.cap = m.kv_context; c.ctx = st->ctx; c.head0 = s.expert; c.nheads = op.info.nshards;
+                c.group = m.n_q_heads / m.n_kv_heads; c.n_q = m.n_q_heads; c.row_stride = m.head_dim;
+                c.ntok = M; c.q_stride = g.qkv_w; c.q = qkv;
+                c.k_own = qkv + (size_t)m.n_q_heads * m.head_dim; c.v_own = qkv + (size_t)(m.n_q_heads + m.n_kv_heads) * m.head_dim;
+                c.own_stride = g.qkv_w; c.out = reinterpret_cast<__half *>(WS + p.ws.attn); c.out_stride = g.attn_w;
+                PS_HIP(launch_attn_chunk_onepass(c, cs));
+                return PS_OK;
+            }
             if (MP > 1) {   // a chunk of tokens over the cached positions of this run of kv heads
                 AttnChunkArgs c{};
                 c.k_base = reinterpret_cast<const __half *>(wptr(op)); c.head_stride = g.kv_shard_bytes;
@@ -352,6 +363,11 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             return PS_OK;
         }
         case PS_K_ATTN_COMBINE:
+            if (MP >= kAttnOnePassTokens) {   // the attention rows are finished: only the chunk's rows remain to be appended
+                PS_HIP(launch_kv_append_rows(st->ctx, m.kv_context, qkv, g.qkv_w, m.n_q_heads, m.n_kv_heads, M,
+                                             reinterpret_cast<const uint64_t *>(WS + p.ws.kvhome) + (size_t)l * m.n_kv_heads, cs));
+                return PS_OK;
+            }
             if (MP > 1) {   // the chunk's own rows (causal), then every token's chunks merged and its rows appended
                 const uint32_t ccap = (m.kv_context + kAttnChunk - 1) / kAttnChunk + (MP + kAttnChunk - 1) / kAttnChunk;
                 AttnChunkArgs c{};

@@ -426,7 +426,7 @@ def test_decode_attention_over_kv_cache(ctx0):
             np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
 
 
-@pytest.mark.parametrize("ctx0,M", [(0, 5), (3, 37), (300, 64), (250, 16), (10, 300)])
+@pytest.mark.parametrize("ctx0,M", [(0, 5), (3, 37), (300, 64), (250, 16), (10, 300), (0, 256), (300, 520)])
 def test_chunk_of_new_tokens_attends_over_the_kv_cache(ctx0, M):
     """Chunked prefill over the cache: a forward of M new tokens at context ctx0 (causal attention inside
     the chunk, rows appended at ctx0 .. ctx0 + M - 1), then a one-token step at ctx0 + M that attends over
