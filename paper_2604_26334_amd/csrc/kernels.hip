@@ -1349,10 +1349,12 @@ __device__ __forceinline__ uint32_t lds_col(uint32_t u) { return ((u & 3) << 2) 
 // the 8-wave workgroup (one per CU, its activation stages shared by twice the row-tiles) has the
 // LDS for 3
 constexpr int gemm_depth(int MT, int NW = 4) { return NW == 8 ? 3 : MT <= 64 ? 2 : 1; }
+// LDS of a workgroup: the activation stages, then per wave two scale buffers of 1 KB per row-tile
+constexpr size_t gemm_lds_bytes(int MT, int AT, int NW) { return (size_t)MT * 256 * (gemm_depth(MT, NW) + 1) + (size_t)NW * 2 * AT * 1024; }
 
 template <int MODE, int AT, int MT, bool GROUPED, int NW = 4>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmArgs a) {
-    extern __shared__ uint4 lds[];                 // gemm_depth(MT, NW) + 1 stages of MT x 16 chunks
+    extern __shared__ uint4 lds[];                 // gemm_depth(MT, NW) + 1 stages of MT x 16 chunks, then 2 AT KB of scales per wave
     constexpr int NMT = MT / 16;
     constexpr int NFILL = MT / (4 * NW);           // 16-byte chunks each thread moves per stage
     static_assert(MT % (4 * NW) == 0, "a fill round covers 4 * NW tokens");
@@ -1411,15 +1413,23 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // DEPTH + 1 weight register sets and LDS stages.  With few tokens an iteration is shorter than
     // the memory latency, so one super-block of lookahead leaves the loop waiting on its loads.
     constexpr int DEPTH = gemm_depth(MT, NW), R = DEPTH + 1;
-    constexpr int LPI = NFILL + 2 * AT;          // loads one prefetch issues per lane
-    // one super-block of weights of the wave's tiles: the lane's 16 code bytes, and the dword that
-    // holds its block's fp16 scale (sh = 0 / 16: which half; the same for the whole workgroup).  The
-    // scale is fetched as a whole dword so that no 16-bit zero-extension is applied to the load's
-    // result the moment it is issued (which would wait for it there).
-    struct Wset { uint4 q[AT]; uint32_t d[AT]; uint32_t sh; };
+    static_assert(AT <= 2, "the dequantisation is pipelined one MFMA step ahead; more tiles per wave do not fit the registers");
+    constexpr int LPI = NFILL + AT;              // loads every prefetch issues per lane (scale fills, when it has them: AT more)
+    // one super-block of weights of the wave's tiles: the lane's 16 code bytes
+    struct Wset { uint4 q[AT]; };
     Wset wr[R];
+    // The fp16 scales come once per scale group (8 super-blocks), not once per super-block: a lane's
+    // 16 bytes of a group's scale area hold the scales of its block column for all 8 super-blocks,
+    // and they go from global memory straight into a wave-private LDS window (two buffers per tile,
+    // by group parity), from where each step picks the two bytes it needs.  (One 4-byte load per
+    // super-block instead touched the same eight cache lines eight times over, between which the
+    // activation fills had pushed them out of the vector cache: a timing probe without scale loads
+    // ran the 64-token gate/up launch 14 % faster.)  Like the activation fills these loads are not
+    // register writes the compiler could wait for; the counted waits below cover them.
+    uint4 *const sc_lds = lds + R * (MT * 16) + __builtin_amdgcn_readfirstlane(wave) * (2 * AT * 64);
     auto fill_x = [&](uint32_t sb, uint32_t stage) {
-        const uint32_t xs = gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half);
+        // (wave-uniform; said so explicitly, or the fill's scalar offset is taken in a lane loop)
+        const uint32_t xs = __builtin_amdgcn_readfirstlane(gather_col(sb * 128, a.x_off, a.x_group) * (uint32_t)sizeof(__half));
 #pragma unroll
         for (int r = 0; r < NFILL; ++r)
             load_to_lds16(xbuf, (lds_void *)(lds + stage * (MT * 16) + r * (NW * 64) + wave_u * 64), xoff[r], xs);
@@ -1430,14 +1440,24 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     auto load_w = [&](uint32_t sbn, Wset &w) {
         sbn = min(sbn, a.nsb - 1);
         const uint32_t gn = sbn >> 3, sn = sbn & 7;
-        const uint32_t nsb_n = min(8u, a.nsb - gn * 8u);
         const uint32_t gb = gn * (9 * 1024);
-        w.sh = (sn & 1) * 16;
 #pragma unroll
-        for (int t = 0; t < AT; ++t) {
+        for (int t = 0; t < AT; ++t)
             w.q[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, woff[t], gb + sn * 1024, kAuxNt));
-            w.d[t] = __builtin_amdgcn_raw_buffer_load_b32(wbuf, woff[t], gb + nsb_n * 1024 + (sn >> 1) * 4, 0);
-        }
+    };
+    // scale area of group g of the wave's tiles -> the window's buffer of parity g & 1
+    auto fill_scales = [&](uint32_t g) {
+        const uint32_t so = g * (9 * 1024) + min(8u, a.nsb - g * 8u) * 1024;
+#pragma unroll
+        for (int t = 0; t < AT; ++t) load_to_lds16(wbuf, (lds_void *)(sc_lds + ((g & 1) * AT + t) * 64), woff[t], so);
+    };
+    // the scales the next dequantisation uses (dsc): the lane's fp16 number sbx & 7 of its group
+    uint32_t dsc[AT];
+    auto scales_of = [&](uint32_t sbx) {
+        const uint32_t g = sbx >> 3, sn = sbx & 7;
+#pragma unroll
+        for (int t = 0; t < AT; ++t)
+            dsc[t] = *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(sc_lds + ((g & 1) * AT + t) * 64) + lane * 16 + sn * 2);
     };
     // prefetched weights become visible to the compiler only where this is called, so nothing
     // derived from them is scheduled (and waited for) earlier
@@ -1445,9 +1465,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
             // (an empty statement the compiler cannot see through: no instruction is issued)
-            asm volatile("" : "+v"(w.q[t].x), "+v"(w.q[t].y), "+v"(w.q[t].z), "+v"(w.q[t].w), "+v"(w.d[t]));
-            // the block's scale, once per super-block rather than once per MFMA step
-            w.d[t] >>= w.sh;
+            asm volatile("" : "+v"(w.q[t].x), "+v"(w.q[t].y), "+v"(w.q[t].z), "+v"(w.q[t].w));
         }
     };
     // A operands of MFMA step kk from raw dwords + scale: (q - 8) * d rounded to fp16
@@ -1455,7 +1473,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 #pragma unroll
         for (int t = 0; t < AT; ++t) {
             const uint32_t q = kk == 0 ? ws.q[t].x : kk == 1 ? ws.q[t].y : kk == 2 ? ws.q[t].z : ws.q[t].w;
-            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)ws.d[t]);
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)dsc[t]);
             const h2_t dd = {d, d};
             h2_t w[4];
             dequant8(q, w);
@@ -1469,7 +1487,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // "all but the newest n" is a statement about which loads have landed).  The fence keeps the
     // compiler from moving the weight loads, which depend on nothing, above fills whose addresses do
     // (in grouped launches the fill offsets come from a load of the pair list).
-    auto prefetch = [&](uint32_t sb_fill, uint32_t stage, uint32_t sb_w, Wset &w) {
+    // Scale fills come first of all.  A group's scales travel with the prefetch of the super-block
+    // BEFORE the group (the dequantisation of a step's first operands runs at the end of the step
+    // before, ahead of the wait that covers the step's own prefetch), and with the walk's opening
+    // prefetch (FIRST) for the group it starts in.  The buffer they overwrite was last read nine
+    // steps earlier.
+    auto prefetch = [&](uint32_t sb_fill, uint32_t stage, uint32_t sb_w, Wset &w, auto FIRST) {
+        const uint32_t sbc = min(sb_w, a.nsb - 1);
+        if constexpr (decltype(FIRST)::value) fill_scales(sbc >> 3);
+        if ((sbc & 7) == 7 && sbc + 1 < a.nsb) fill_scales((sbc >> 3) + 1);
         fill_x(sb_fill, stage);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
@@ -1482,14 +1508,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
         sb_begin = blockIdx.z * a.sb_per_part;
         sb_end = min(a.nsb, sb_begin + a.sb_per_part);
     }
+    prefetch(sb_begin, 0, sb_begin, wr[0], std::true_type{});
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) prefetch(min(sb_begin + d, sb_end - 1), d, sb_begin + d, wr[d]);
-    // PIPE: the A operands of the next MFMA step are dequantised while this step's MFMAs run
-    // (one more operand set in registers; the 4-tile shape has no room for it)
-    constexpr bool PIPE = (AT <= 2);
+    for (int d = 1; d < DEPTH; ++d) prefetch(min(sb_begin + d, sb_end - 1), d, sb_begin + d, wr[d], std::false_type{});
+    // the A operands of the next MFMA step are dequantised while this step's MFMAs run
     h8_t Acur[AT], Anxt[AT];
     arrive_w(wr[0]);
-    if (PIPE) dequant_a(Acur, wr[0], 0);
     // EARLY (three or more super-blocks of lookahead): a stage is required one step before it is
     // multiplied, so the barrier that ends step sb already covers the fills of stage sb + 2.  A wave
     // can then fetch the first B operands of step sb + 1 while step sb's last MFMAs run, instead
@@ -1499,7 +1523,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // a prefetch issues its LDS fills before its weight loads and loads return in order, so the
     // barrier of the EARLY shape needs only the fills of the stage it covers: that stage's weight
     // loads (from HBM, the slow ones; consumed a step later) may stay in flight as well
-    constexpr int kInFlight = kLand * LPI + (EARLY ? 2 * AT : 0);
+    // (counted without the scale fills that one prefetch in eight carries: with one of those among
+    // the newest the wait asks for a little more than it needs, never for less)
+    constexpr int kInFlight = kLand * LPI + (EARLY ? AT : 0);
     // Before the first step: everything issued so far has landed.  No count is assumed here, because
     // nothing orders the DEPTH opening prefetches among themselves: the compiler hoists the weight
     // loads of all of them above fills that wait for the pair list, and merges the scale loads of two
@@ -1507,6 +1533,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
     // stage 0 (a build in which it happened not to gave wrong results now and then).
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    scales_of(sb_begin);
+    dequant_a(Acur, wr[0], 0);
     h8_t Bc[NMT], Bn[NMT];
     if (EARLY) {
 #pragma unroll
@@ -1515,16 +1543,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
 
     // one super-block: U = its position in the ring (compile-time, so every register set and LDS
     // stage below is addressed statically and nothing is copied when the ring turns)
-    // TAIL: one of the at most R - 1 steps after the last whole turn of the ring.  Their prefetched
-    // weights are never used and the compiler drops those loads, so fewer than LPI loads are issued
-    // and the counted wait would name less than it should: they wait for everything instead.
+    // TAIL: one of the at most R - 1 steps after the last whole turn of the ring.  What they would
+    // prefetch lies past the end of the walk, so they issue nothing and wait for everything.
     auto step = [&](uint32_t sb, auto U, auto TAIL) {
         constexpr int u = decltype(U)::value;
         constexpr bool tail = decltype(TAIL)::value;
         constexpr int un = (u + 1) % R, up = (u + DEPTH) % R;   // next super-block's slot, the slot to refill
         // prefetch super-block sb + DEPTH: activations into the stage every wave left at the
         // barrier that ended the previous step, weights into the register set used then
-        prefetch(min(sb + DEPTH, sb_end - 1), up, sb + DEPTH, wr[up]);
+        if (!tail) prefetch(min(sb + DEPTH, sb_end - 1), up, sb + DEPTH, wr[up], std::false_type{});
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch up here: its latency hides behind the MFMAs
         const uint4 *ls = lds + u * (MT * 16) + i * 16;   // + n * 256: token n*16 + i
         const uint4 *lsn = lds + un * (MT * 16) + i * 16;  // the next super-block's stage
@@ -1544,10 +1571,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
                 for (int n = 0; n < NMT; ++n) Bn[n] = __builtin_bit_cast(h8_t, lsn[n * 256 + (c ^ i)]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (!PIPE) dequant_a(Acur, wr[u], kk);
-            else if (kk < 3) dequant_a(Anxt, wr[u], kk + 1);
+            if (kk < 3) dequant_a(Anxt, wr[u], kk + 1);
             else {
                 arrive_w(wr[un]);
+                scales_of(sb + 1);
                 dequant_a(Anxt, wr[un], 0);
             }
 #pragma unroll
@@ -1556,10 +1583,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void gemm_w4_kernel(GemmA
                 for (int t = 0; t < AT; ++t)
                     acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Acur[t], Bc[n], acc[t][n], 0, 0, 0);
             }
-            if (PIPE) {
 #pragma unroll
-                for (int t = 0; t < AT; ++t) Acur[t] = Anxt[t];
-            }
+            for (int t = 0; t < AT; ++t) Acur[t] = Anxt[t];
             if (kk < 3 || EARLY) {
 #pragma unroll
                 for (int n = 0; n < NMT; ++n) Bc[n] = Bn[n];
@@ -1661,7 +1686,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max
         const double eff8 = (double)wg8 / ((wg8 + 255) / 256 * 256), eff4 = (double)wg4 / ((wg4 + 511) / 512 * 512);
         if (!ntasks && parts == 1 && (eff8 >= 0.9 || eff8 > eff4 + 0.05)) {
             dim3 grid8((a.ntiles + 8 * AT - 1) / (8 * AT), ty, 1);
-            const size_t lds8 = (size_t)MT * 256 * (gemm_depth(MT, 8) + 1);
+            const size_t lds8 = gemm_lds_bytes(MT, AT, 8);
             static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4_kernel<MODE, AT, MT, false, 8>),
                                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8);
             if (attr != hipSuccess) return attr;
@@ -1670,7 +1695,15 @@ static hipError_t launch_gemm_t(const GemmArgs &a, uint32_t ntasks, uint32_t max
         }
     }
     dim3 grid((a.ntiles + 4 * AT - 1) / (4 * AT), (max_tok + MT - 1) / MT, ntasks ? ntasks : parts);
-    const size_t lds = (size_t)MT * 256 * (gemm_depth(MT) + 1);
+    const size_t lds = gemm_lds_bytes(MT, AT, 4);
+    if (lds > 64 * 1024) {
+        static const hipError_t attr_g = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4_kernel<MODE, AT, MT, true>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static const hipError_t attr_u = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4_kernel<MODE, AT, MT, false>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (attr_g != hipSuccess) return attr_g;
+        if (attr_u != hipSuccess) return attr_u;
+    }
     if (ntasks) hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, true>), grid, dim3(256), lds, st, a);
     else hipLaunchKernelGGL((gemm_w4_kernel<MODE, AT, MT, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
