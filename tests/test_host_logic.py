@@ -761,7 +761,7 @@ def _fake_gemm_isa(prologue_wait, step_loads, step_wait):
     w4, w1 = "\tbuffer_load_dwordx4 v[2:5], v1, s[4:7], 0 offen\n", "\tbuffer_load_dword v6, v1, s[4:7], 0 offen\n"
     kinds = {"lds": lds, "w4": w4, "w1": w1, "g": "\tglobal_load_dword v7, v[8:9], off\n"}
     step = "".join(kinds[k] for k in step_loads) + "\ts_waitcnt vmcnt(%d) lgkmcnt(0)\n\ts_barrier\n" % step_wait
-    return ("_ZN2ps14gemm_w4_kernelILi0ELi2ELi16ELb0ELi4EEEvNS_8GemmArgsE: ; @x\n" + lds + w4 + w1 + w4 + w1 +
+    return ("_ZN2ps14gemm_w4_kernelILi0ELi2ELi16ELb0ELi4EEEvNS_8GemmArgsE: ; @x\n" + lds + lds + lds + w4 + w4 +
             "\ts_waitcnt vmcnt(%d)\n\ts_barrier\n" % prologue_wait + step + step +
             "\tglobal_store_dword v[8:9], v7, off\n\ts_endpgm\n.Lfunc_end0:\n")
 
@@ -771,14 +771,16 @@ def test_build_check_of_the_gemm_wait_counts(tmp_path):
     they are meant to: an opening wait that is not vmcnt(0), a counted step with a load too few or too
     many, fills that do not come first, or a foreign memory operation inside the ring."""
     from paper_2604_26334_amd import build as Bd
-    assert Bd.gemm_wait_counts(16, 4) == (5, 1, 5)        # 1 fill + 4 weight loads, one prefetch may be in flight
-    assert Bd.gemm_wait_counts(64, 4) == (8, 4, 8)
-    assert Bd.gemm_wait_counts(128, 4) == (12, 8, 0)      # one super-block of lookahead: every step waits for all
-    assert Bd.gemm_wait_counts(128, 8) == (8, 4, 12)      # three of lookahead: one prefetch and the next one's weights
-    good = ["lds", "w4", "w1", "w4", "w1"]
-    cases = [(0, good, 5, True), (5, good, 5, False), (0, good[:-1], 5, False), (0, good + ["w1"], 5, False),
-             (0, ["w4", "lds", "w1", "w4", "w1"], 5, False), (0, good, 4, False), (0, ["lds", "w4", "w1", "w4", "g"], 5, False),
-             (0, good[:1], 0, True)]                       # a tail step: fewer loads, but it waits for everything
+    assert Bd.gemm_wait_counts(16, 4) == (3, 1, 3)        # 1 fill + 2 weight loads, one prefetch may be in flight
+    assert Bd.gemm_wait_counts(64, 4) == (6, 4, 6)
+    assert Bd.gemm_wait_counts(128, 4) == (10, 8, 0)      # one super-block of lookahead: every step waits for all
+    assert Bd.gemm_wait_counts(128, 8) == (6, 4, 8)       # three of lookahead: one prefetch and the next one's weights
+    good = ["lds", "w4", "w4"]
+    scales = ["lds", "lds"] + good                         # the prefetch that carries a scale fill per tile
+    cases = [(0, good, 3, True), (0, scales, 3, True), (3, good, 3, False), (0, good[:-1], 3, False), (0, good + ["w4"], 3, False),
+             (0, ["w4", "lds", "w4"], 3, False), (0, good, 2, False), (0, good, 5, False), (0, ["lds", "w4", "g"], 3, False),
+             (0, ["lds"] + good, 3, False),                # one scale fill for two tiles
+             (0, good[:1], 0, True)]                       # a step that waits for everything may issue anything
     for i, (pw, loads, sw, ok) in enumerate(cases):
         p = tmp_path / ("k%d.s" % i)
         p.write_text(_fake_gemm_isa(pw, loads, sw))
