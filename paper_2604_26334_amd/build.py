@@ -29,7 +29,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-ffp-c
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("PS_EXTRA_FLAGS", "").split()
 CHECKED = "kernels.hip"      # the source whose kernels are checked
-NO_SCRATCH = ("gemm_w4_kernel", "gemv_w4_kernel", "attn_decode_kernel", "attn_combine_kernel", "attn_chunk_kernel", "attn_chunk_mfma_kernel", "attn_chunk_onepass_kernel", "attn_combine_chunk_kernel")
+NO_SCRATCH = ("gemm_w4_kernel", "gemv_w4_kernel", "gemv_mt_kernel", "attn_decode_kernel", "attn_combine_kernel", "attn_chunk_kernel", "attn_chunk_mfma_kernel", "attn_chunk_onepass_kernel", "attn_combine_chunk_kernel")
 
 
 def _run(cmd):

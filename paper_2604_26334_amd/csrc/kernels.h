@@ -63,6 +63,11 @@ hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st);
 uint32_t gemv_ksplit(uint32_t ngroups, uint32_t total_units);
 hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntasks, hipStream_t st);
 hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t max_tok, hipStream_t st);
+// Two to kGemvMtTokens tokens of a dense sub-layer whose K is a multiple of 1024 (rows of x x_stride
+// elements apart, rows of out and res out_stride apart): the one-token kernel's launch shape with the dot
+// products on the matrix cores; PLAIN, RESID and GATE_UP, the RMS factors computed from the activations
+constexpr int kGemvMtTokens = 4;
+hipError_t launch_gemv_mt(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntok, hipStream_t st);
 // sums `parts` fp32 partial planes [M][ncols_phys] in ascending order and applies the mode's epilogue
 hipError_t launch_splitk_epilogue(int mode, const float *partial, uint32_t parts, uint32_t part_stride, uint32_t M,
                                   uint32_t ncols_phys, const float *rinv, const __half *res, __half *out,

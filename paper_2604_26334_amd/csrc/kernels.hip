@@ -429,6 +429,184 @@ hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t nt
 }
 
 // ------------------------------------------------------------------------------------
+// Two to kGemvMtTokens tokens: the decode kernel's structure -- units, K split over the waves of a
+// unit, a whole scale group of weights requested at once, wave-private activation windows, no
+// barrier before the last reduction -- with the dot products on the matrix cores.  A wave's lanes
+// hold a row-tile's weights exactly as the GEMM's do (lane (i, c): block 4 sb + c of row i, dword kk
+// the A operand of MFMA step kk, the scale folded in); the B operand of a step is one 16-byte chunk
+// of a token's window, MFMA column j serving token j % kGemvMtTokens.  Against the one-token kernel
+// the weight stream is the same and the vector ALU does a third more per weight (the exact
+// (q - 8) d instead of the raw patterns), whatever the token count; against the MFMA GEMM at these
+// token counts there are no partial planes, no plane-sum launches and no separate RMS-factor
+// launch (four launches per layer instead of seven).  K must be a multiple of 1024.
+// The windows are filled from global memory straight into LDS; chunk q of token t sits in slot
+// q ^ t, so the 16 lanes x 4 lane groups of an operand read touch 16 different slots.
+// A row's result is the sum of its scale-group partials in ascending group order, as in the
+// one-token kernel: it depends neither on the K split nor on the workgroup shape.
+// ------------------------------------------------------------------------------------
+template <int MODE, int NW>
+__global__ __launch_bounds__(NW * 64, 4) void gemv_mt_kernel(GemvArgs a, uint32_t ks, uint32_t ntok) {
+    extern __shared__ uint4 mt_lds[];
+    // a wave works on ONE row-tile (two tiles' weights of a scale group do not fit the registers beside the
+    // operands): a gate/up unit takes 2 ks waves, the gate tile's and the up tile's, which meet in the epilogue
+    constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
+    constexpr int TK = kGemvMtTokens;
+    constexpr bool NORM = (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP);
+    static_assert(MODE != GEMV_F32, "dense sub-layers only");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, c = lane >> 4;
+    const uint32_t wpu = ks * NT;               // waves per unit
+    const uint32_t units = NW / wpu;
+    const uint32_t unit = blockIdx.x * units + wave / wpu;
+    const uint32_t tsel = (wave % wpu) / ks;    // which tile of the unit
+    const uint32_t kpart = wave % ks;
+    const bool active = unit < a.nunits;
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint4 *win = mt_lds + wave_u * (TK * 128);                                   // [token][128 chunks of 8]
+    float *red = reinterpret_cast<float *>(mt_lds + NW * (TK * 128));            // [(unit, group)][tile][token][16 rows]
+    float *red_ss = red + units * a.ngroups * (NT * TK * 16);                    // [(unit, group)][token]
+    const uint32_t tb = j & (TK - 1);                                            // the token this lane's MFMA column serves
+    const __amdgpu_buffer_rsrc_t xbuf = make_rsrc(a.x);
+
+    if (active && kpart < a.ngroups) {
+        for (uint32_t g = kpart; g < a.ngroups; g += ks) {
+            // activations of the group for every token first (they are needed first), then the weights
+            // slot r * 64 + lane of token t's window holds chunk (r * 64 + lane) ^ t: the same 128-column
+            // stretch (one input head) for every t, so the column map is worked out once per r
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const uint32_t col0 = gather_col(g * 1024u + (uint32_t)(r * 64 + (lane & 48)) * 8u, a.x_off, a.x_group);
+#pragma unroll
+                for (int t = 0; t < TK; ++t) {
+                    const uint32_t tokc = min((uint32_t)t, ntok - 1);   // windows past the last token repeat it (never stored)
+                    const uint32_t voff = (tokc * a.x_stride + col0 + (((uint32_t)lane & 15u) ^ (uint32_t)t) * 8u) * (uint32_t)sizeof(__half);
+                    load_to_lds16(xbuf, (lds_void *)(win + t * 128 + r * 64), voff, 0);
+                }
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            GemvBuf<1> cur;
+            gemv_issue_w<1, true>(cur, a.W, unit * NT + tsel, a.tile_u4, g, 8u, lane);
+            // the window fills are the oldest loads in flight: all but the 9 weight loads behind them
+            // (the compiler does not know of loads into LDS; later loads only make this wait stricter)
+            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+            const uint32_t slot = (wave / wpu) * a.ngroups + g;
+            if (NORM && tsel == 0) {
+#pragma unroll
+                for (int t = 0; t < TK; ++t) {
+                    const uint4 xa = win[t * 128 + lane], xb = win[t * 128 + 64 + lane];
+                    float sq = 0.f;
+                    sq = __builtin_amdgcn_fdot2(as_h2(xa.x), as_h2(xa.x), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xa.y), as_h2(xa.y), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xa.z), as_h2(xa.z), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xa.w), as_h2(xa.w), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xb.x), as_h2(xb.x), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xb.y), as_h2(xb.y), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xb.z), as_h2(xb.z), sq, false);
+                    sq = __builtin_amdgcn_fdot2(as_h2(xb.w), as_h2(xb.w), sq, false);
+                    const float gss = wave_sum(sq);
+                    if (lane == 0) red_ss[slot * TK + t] = gss;
+                }
+            }
+            f4_t gacc = f4_t{0.f, 0.f, 0.f, 0.f};
+            const uint4 *wb = win + tb * 128;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const h8_t B = __builtin_bit_cast(h8_t, wb[(uint32_t)(s * 16 + c * 4 + kk) ^ tb]);
+                    const uint4 wq = cur.wq[0][s];
+                    const uint32_t q = kk == 0 ? wq.x : kk == 1 ? wq.y : kk == 2 ? wq.z : wq.w;
+                    const uint32_t dw = (s < 2) ? cur.sc[0].x : (s < 4) ? cur.sc[0].y : (s < 6) ? cur.sc[0].z : cur.sc[0].w;
+                    const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
+                    const h2_t dd = {d, d};
+                    h2_t w[4];
+                    dequant8(q, w);
+                    w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+                    const h8_t A = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+                    gacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, gacc, 0, 0, 0);
+                }
+            }
+            // lane (j, c) holds rows 4c .. 4c + 3 of token column j
+            if (j < TK)
+                *reinterpret_cast<float4 *>(red + ((slot * NT + tsel) * TK + j) * 16 + c * 4) = make_float4(gacc[0], gacc[1], gacc[2], gacc[3]);
+            asm volatile("" ::: "memory");   // the window's reads are behind us before the next group's fills are issued
+        }
+    }
+    __syncthreads();
+    if (!(active && kpart == 0 && tsel == 0 && (uint32_t)j < ntok)) return;
+    const uint32_t slot0 = (wave / wpu) * a.ngroups;
+    float acc[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] = 0.f;
+    float ss = 0.f;
+    for (uint32_t g = 0; g < a.ngroups; ++g) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float4 v = *reinterpret_cast<const float4 *>(red + (((slot0 + g) * NT + t) * TK + j) * 16 + c * 4);
+            acc[t][0] += v.x; acc[t][1] += v.y; acc[t][2] += v.z; acc[t][3] += v.w;
+        }
+        if (NORM) ss += red_ss[(slot0 + g) * TK + j];
+    }
+    const float rinv = NORM ? rsqrtf(ss / (float)a.K + a.eps) : 1.f;
+    const size_t o = (size_t)j * a.out_stride + a.out_row0 + unit * 16 + c * 4;
+    float v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (MODE == GEMV_PLAIN) v[r] = rinv * acc[0][r];
+        else if (MODE == GEMV_RESID) v[r] = (a.res ? __half2float(a.res[o + r]) : 0.f) + acc[0][r];
+        else v[r] = silu(rinv * acc[0][r]) * (rinv * acc[NT - 1][r]);
+    }
+    __half2 *dst = reinterpret_cast<__half2 *>(a.out + o);
+    dst[0] = __halves2half2(to_half(v[0]), to_half(v[1]));
+    dst[1] = __halves2half2(to_half(v[2]), to_half(v[3]));
+}
+
+size_t gemv_mt_lds_bytes(uint32_t nw, uint32_t units, uint32_t ngroups, uint32_t nt) {
+    return (size_t)nw * kGemvMtTokens * 2048 + (size_t)units * ngroups * (nt * kGemvMtTokens * 64 + kGemvMtTokens * 4);
+}
+
+template <int MODE>
+static hipError_t launch_gemv_mt_t(const GemvArgs &a, uint32_t ks, uint32_t ntok, hipStream_t st) {   // ks by value: adjusted below
+    constexpr uint32_t NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
+    // workgroup shapes as for one token (launch_gemv_f), in waves per unit (a gate/up unit: 2 ks)
+    while (ks * NT > 16) ks /= 2;
+    const uint32_t wpu = ks * NT;
+    uint32_t nw = wpu > 8 ? 16 : wpu > 4 ? 8 : 4;
+    if (wpu == 4 && (a.nunits + 1) / 2 >= 192) nw = 8;
+    const uint32_t units = nw / wpu;
+    const size_t lds = gemv_mt_lds_bytes(nw, units, a.ngroups, NT);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    dim3 grid((a.nunits + units - 1) / units);
+    static const hipError_t attr16 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mt_kernel<MODE, 16>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static const hipError_t attr8 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mt_kernel<MODE, 8>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr16 != hipSuccess) return attr16;
+    if (attr8 != hipSuccess) return attr8;
+    if (nw == 16) hipLaunchKernelGGL((gemv_mt_kernel<MODE, 16>), grid, dim3(1024), lds, st, a, ks, ntok);
+    else if (nw == 8) hipLaunchKernelGGL((gemv_mt_kernel<MODE, 8>), grid, dim3(512), lds, st, a, ks, ntok);
+    else hipLaunchKernelGGL((gemv_mt_kernel<MODE, 4>), grid, dim3(256), lds, st, a, ks, ntok);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_mt(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t ntok, hipStream_t st) {
+    if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8 && ksplit != 16) return hipErrorInvalidValue;
+    if (ntok < 1 || ntok > (uint32_t)kGemvMtTokens || a.nsb % 8 != 0 || a.tasks) return hipErrorInvalidValue;
+    // weights and activations are addressed as a uniform base plus 32-bit byte offsets
+    if ((uint64_t)a.nunits * (mode == GEMV_GATE_UP ? 2u : 1u) * a.tile_u4 * 16u > 0xFFFFFFFFull) return hipErrorInvalidValue;
+    if ((uint64_t)ntok * a.x_stride * 2u > 0xFFFFFFFFull) return hipErrorInvalidValue;
+    switch (mode) {
+        case GEMV_PLAIN: return launch_gemv_mt_t<GEMV_PLAIN>(a, ksplit, ntok, st);
+        case GEMV_RESID: return launch_gemv_mt_t<GEMV_RESID>(a, ksplit, ntok, st);
+        case GEMV_GATE_UP: return launch_gemv_mt_t<GEMV_GATE_UP>(a, ksplit, ntok, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps), one workgroup per token (used when M > 1): thread t adds
 // the 8-column chunks t, t + 256, ... in that order, the 64 lanes of a wave are summed by the
 // butterfly, the four waves in order.  All of a thread's loads (up to four per round) are issued

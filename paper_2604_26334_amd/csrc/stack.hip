@@ -152,7 +152,13 @@ const MatGeom &geom_of(const ModelGeom &g, uint32_t mat) {
     }
 }
 
-// GEMV launch description of a dense one-token matmul op (QKV, O, GATE_UP, DOWN)
+// A dense matmul op of a plan of two to kGemvMtTokens tokens runs in the few-token form of the decode
+// kernel when the matrix's K is a multiple of 1024 (whole scale groups); it computes its own RMS factors
+static bool few_token_gemv(const ps_plan &p, const MatGeom &mg) {
+    return p.M >= 2 && p.M <= (uint32_t)kGemvMtTokens && mg.ntiles && mg.nsb % 8 == 0;
+}
+
+// GEMV launch description of a dense matmul op (QKV, O, GATE_UP, DOWN) of one or a few tokens
 bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __half *x_out, GemvArgs *out, int *mode,
                      uint32_t *ks) {
     const ps_plan &p = st->plan;
@@ -177,23 +183,28 @@ bool dense_gemv_args(const ps_stack *st, const Op &op, const __half *x_in, __hal
         case PS_K_QKV:
             mg = &g.qkv; *mode = GEMV_PLAIN; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
             a.nunits = s.ntiles; a.x = xin; a.out = qkv; a.out_row0 = s.tile0 * 16;
+            a.x_stride = m.hidden; a.out_stride = g.qkv_w;
             break;
         case PS_K_O:
             mg = &g.o; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
             a.nunits = s.ntiles; a.res = xin; a.out = hbuf; a.out_row0 = s.tile0 * 16;
             if (g.kv) {   // the attention output
-                a.x = reinterpret_cast<const __half *>(WS + p.ws.attn);
+                a.x = reinterpret_cast<const __half *>(WS + p.ws.attn); a.x_stride = g.attn_w;
             } else {      // identity on V, read in place from the QKV row
                 a.x = qkv; a.x_off = (m.n_q_heads + m.n_kv_heads) * m.head_dim; a.x_group = m.n_q_heads / m.n_kv_heads;
+                a.x_stride = g.qkv_w;
             }
+            a.out_stride = m.hidden;
             break;
         case PS_K_GATE_UP:
             mg = &g.gate_up; *mode = GEMV_GATE_UP; *ks = gemv_ksplit(mg->ngroups, mg->ntiles / 2);
             a.nunits = s.ntiles / 2; a.x = hbuf; a.out = sbuf; a.out_row0 = s.tile0 / 2 * 16;
+            a.x_stride = m.hidden; a.out_stride = g.ffn_i;
             break;
         case PS_K_DOWN:
             mg = &g.down; *mode = GEMV_RESID; *ks = gemv_ksplit(mg->ngroups, mg->ntiles);
             a.nunits = s.ntiles; a.x = sbuf; a.res = resid ? hbuf : nullptr; a.out = xout; a.out_row0 = s.tile0 * 16;
+            a.x_stride = g.ffn_i; a.out_stride = m.hidden;
             break;
         default: return false;
     }
@@ -256,6 +267,15 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
         PS_HIP(launch_gemv(mode, ks, a, 0, cs));
         return PS_OK;
     }
+    if (op.info.kernel >= PS_K_QKV && op.info.kernel <= PS_K_DOWN &&
+        few_token_gemv(p, op.info.kernel == PS_K_QKV ? g.qkv : op.info.kernel == PS_K_O ? g.o : op.info.kernel == PS_K_GATE_UP ? g.gate_up : g.down)) {
+        GemvArgs a;
+        int mode;
+        uint32_t ks;
+        dense_gemv_args(st, op, x_in, x_out, &a, &mode, &ks);
+        PS_HIP(launch_gemv_mt(mode, ks, a, M, cs));
+        return PS_OK;
+    }
     // batched decode (2..64 tokens) of a narrow matrix: split K over blockIdx.z into fp32 partial
     // planes, then one epilogue kernel sums them in order and applies the mode's epilogue
     auto run_gemm = [&](int mode, GemmArgs a, const MatGeom &mg) -> int32_t {
@@ -284,6 +304,9 @@ int32_t issue_kernel(ps_stack *st, const ps_schedule &sc, const Op &op, const __
             const __half *rows = op.info.shard0 == 2 ? x_out : op.info.shard0 == 0 && g.has_attn ? xin : hbuf;   // 2: output head
             const bool have = st->rinv_of == rows;
             st->rinv_of = nullptr;
+            // the few-token kernels of QKV (factors of kind 0) and of a dense gate/up (kind 1) compute their own
+            if (op.info.shard0 == 0 && few_token_gemv(p, g.qkv)) return PS_OK;
+            if (op.info.shard0 == 1 && !g.moe && few_token_gemv(p, g.gate_up)) return PS_OK;
             if (!have) PS_HIP(launch_rinv(rows, M, H, m.rms_eps, rinv, cs));
             return PS_OK;
         }

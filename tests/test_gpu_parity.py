@@ -87,6 +87,26 @@ def test_small_dense_batched_and_prefill(M):
     _check(cfg, 2, M, _budgets(cfg, M, [1.0, 0.5]))
 
 
+@pytest.mark.parametrize("M", [2, 3, 4])
+@pytest.mark.parametrize("ffn", [2048, 1408])
+def test_few_token_decode_kernel(M, ffn):
+    """Two to four tokens through matrices whose K is a multiple of 1024 take the few-token form of the decode
+    kernel (MFMA dot products in the one-token kernel's launch shape, RMS factors computed in the kernel);
+    with ffn 1408 the down projection (K = 1408) stays on the GEMM path and the two forms alternate inside a layer.
+    Against the oracle, and bit-identical across placements."""
+    cfg = dict(Hn.small_dense_cfg(2), hidden=1024, n_q_heads=8, n_kv_heads=2, ffn_inter=ffn)
+    _check(cfg, 11, M, _budgets(cfg, M, [1.0, 0.6, 0.35]))
+
+
+def test_few_token_decode_kernel_under_moe_layers():
+    """The attention matrices of an MoE stack take the few-token kernel too; the experts' grouped GEMM still gets
+    its RMS factors from their own launch."""
+    cfg = dict(Hn.small_moe_cfg(2), hidden=1024, n_q_heads=8, n_kv_heads=2)
+    M = 3
+    lg = S.router_logits(5, 0, cfg["n_layers"], M, cfg["n_experts"])
+    _check(cfg, 5, M, _budgets(cfg, M, [1.0, 0.5]), logits=lg)
+
+
 @pytest.mark.parametrize("M", [1, 5, 16])
 def test_small_moe(M):
     cfg = Hn.small_moe_cfg(2)
