@@ -78,8 +78,9 @@ def cpu_baseline(cfg, seed, layers, reps, S, O):
     return dt, min(threads, os.cpu_count() or threads)
 
 
-def batched_leg(B, S, torch, cfg, seed, prof, tokens, budgets, steps):
-    """Batched decode (config 5): `tokens` tokens per step, `steps` steps of fresh activations."""
+def batched_leg(B, S, torch, cfg, seed, prof, tokens, budgets, steps, decode_mode=1):
+    """Batched decode (config 5): `tokens` tokens per step, `steps` steps of fresh activations (decode mode 1:
+    the step's launches replayed from a HIP graph where every shard is resident)."""
     out = {}
     plans = [B.Plan(cfg, int(b), tokens, profile=prof) for b in budgets]
     stacks = [B.Stack(p) for p in plans]
@@ -90,9 +91,11 @@ def batched_leg(B, S, torch, cfg, seed, prof, tokens, budgets, steps):
     torch.cuda.synchronize()
     for b, plan, st in zip(budgets, plans, stacks):
         s = plan.summary()
+        st.set_decode_mode(decode_mode)
         ms = time_steps(torch, st, xs, xo, steps, 3)
         flops = 2.0 * tokens * (s.weight_bytes / 0.5625)
         out["%g" % (b / 1e9)] = dict(budget_bytes=int(b), tokens_per_step=tokens, steps=steps, ms_per_step=ms,
+                                     graph_replay=int(st.stats().graph_replay),
                                      tokens_per_s=tokens * 1e3 / ms, resident_bytes=s.resident_bytes,
                                      streamed_bytes_per_step=st.stats().streamed_bytes_step,
                                      hbm_gbps=s.weight_bytes / (ms * 1e-3) / 1e9,
@@ -629,12 +632,12 @@ def main():
         torch.cuda.empty_cache()
     fresh()
     if "batch64" in args.extra and args.layers == 32:
-        extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128)
+        extra["batched_decode_64"] = batched_leg(B, S, torch, cfg, seed, prof, 64, [4e9, 12e9], 128, args.decode_mode)
         fresh()
         # the other batch sizes of the paper's batching table (1 is the headline leg)
-        extra["batched_decode_4"] = batched_leg(B, S, torch, cfg, seed, prof, 4, [4e9], 128)
+        extra["batched_decode_4"] = batched_leg(B, S, torch, cfg, seed, prof, 4, [4e9], 128, args.decode_mode)
         fresh()
-        extra["batched_decode_16"] = batched_leg(B, S, torch, cfg, seed, prof, 16, [4e9], 128)
+        extra["batched_decode_16"] = batched_leg(B, S, torch, cfg, seed, prof, 16, [4e9], 128, args.decode_mode)
     fresh()
     if "tiers" in args.extra and args.layers == 32:
         extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)

@@ -513,10 +513,11 @@ int32_t ps_stack_forward_noalloc(ps_stack *st, const void *x_in, void *x_out);
 int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, uint32_t n_tokens,
                                  const float *router_logits, const float *router_logits_dev,
                                  void *last_logits_dev, uint32_t *trips);
-/* Decode execution mode.  0 (default): one launch per shard.  1: applies when the plan is dense,
- * one token and every shard (KV-cache shards included) resident (otherwise mode 0 runs): the
- * launch-per-shard kernel sequence is captured once per (x_in, x_out, logits) triple into a HIP
- * graph (kernel nodes only) and replayed; with a KV cache the context length then travels in a
+/* Decode execution mode.  0 (default): one launch per shard.  1: applies when the plan is dense with
+ * every shard (KV-cache shards included) resident and no CPU share, for one token or, without a KV
+ * cache, for a batched-decode step of up to 64 tokens (otherwise mode 0 runs): the launch-per-shard
+ * kernel sequence is captured once per (x_in, x_out, logits, valid rows) into a HIP graph (kernel
+ * nodes only) and replayed; with a KV cache the context length then travels in a
  * device word set before each replay, and the attention launch covers every chunk the cache can
  * hold (workgroups past the context leave at once).  Order and arithmetic are unchanged
  * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  (A third value

@@ -66,7 +66,7 @@ struct ps_stack {
     uint64_t tables_bytes = 0;
     int32_t decode_mode = 0;                  // as set by ps_stack_set_decode_mode (re-evaluated when a tier is installed)
     bool use_graph = false;                   // all-resident one-token forward replayed from a HIP graph
-    std::map<std::tuple<const void *, void *, void *>, hipGraphExec_t> graphs;   // per (x_in, x_out, logits)
+    std::map<std::tuple<const void *, void *, void *, uint32_t>, hipGraphExec_t> graphs;   // per (x_in, x_out, logits, valid rows and head rows)
     // CPU back-end (plans with shards left in system memory): worker threads, pinned host copies of
     // the activations it reads (FFN input, SwiGLU output, final hidden state) and of what it writes
     std::unique_ptr<ps::CpuPool> pool;
@@ -594,6 +594,13 @@ bool skip_head_op(const ps_stack *st, const Op &op) {
     return st->head_rows == 1 && op.info.type == PS_OP_KERNEL && op.info.kernel == PS_K_RINV;
 }
 
+// Plans whose forward is a fixed sequence of kernels and nothing else: dense, every shard resident, no CPU
+// share; one token (with or without a KV cache) or a batched-decode step of up to 64 tokens without one
+// (a chunk's attention takes its context as a launch argument)
+static bool graph_eligible(const ps_plan &p) {
+    return !p.g.moe && p.n_slots == 0 && p.cpu_bytes == 0 && (p.M == 1 || (p.M <= 64 && !p.g.kv));
+}
+
 int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __half *x_out) {
     const ps_plan &p = st->plan;
     const bool prof = st->profiling;
@@ -613,10 +620,11 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
     // kernels of this mode read it (set here, outside any capture, so a replay sees this step's value)
     if (st->use_graph && p.g.kv) PS_HIP(launch_set_u32(reinterpret_cast<uint32_t *>(st->ws_base + p.ws.ctx), st->ctx, st->compute));
     if (st->use_graph && !prof) {
-        // Launch-bound case (every shard resident, one token): the kernel sequence is captured
-        // once per (x_in, x_out) pair and replayed.  The graph holds kernel nodes only.
+        // Launch-bound case (every shard resident; one token or a batched-decode step): the kernel
+        // sequence is captured once per (x_in, x_out, logits, rows) and replayed.  Kernel nodes only.
         auto key = std::make_tuple(static_cast<const void *>(x_in), static_cast<void *>(x_out),
-                                   static_cast<void *>(st->head_rows ? st->logits : nullptr));
+                                   static_cast<void *>(st->head_rows ? st->logits : nullptr),
+                                   st->n_valid | (st->head_rows << 8) | (st->head_row0 << 16));
         auto it = st->graphs.find(key);
         if (it == st->graphs.end()) {
             if (st->graphs.size() >= 32) {
@@ -776,7 +784,7 @@ int32_t bind_plan(ps_stack *st) {
         if (rc) return rc;
         st->have_dense_sched = true;
     }
-    st->use_graph = st->decode_mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
+    st->use_graph = st->decode_mode == 1 && graph_eligible(p) && st->have_dense_sched;
     if (p.g.kv) {
         // home of every kv head's cache: where its rows live between steps (arena or pinned pool)
         const auto &m = p.g.m;
@@ -1406,7 +1414,7 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
     const ps_plan &p = st->plan;
     // eligible: dense, one token, every shard resident (nothing to wait for but the previous kernel)
     st->decode_mode = mode;
-    st->use_graph = mode == 1 && !p.g.moe && p.M == 1 && p.n_slots == 0 && p.cpu_bytes == 0 && st->have_dense_sched;
+    st->use_graph = mode == 1 && graph_eligible(p) && st->have_dense_sched;
     st->own_rinv_launch = mode == 2;
     return PS_OK;
 }

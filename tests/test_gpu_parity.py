@@ -190,20 +190,22 @@ def test_rms_factor_left_by_the_residual_epilogue_matches_its_own_launch(M, moe)
     st.close()
 
 
-def test_graph_replay_matches_eager_on_every_replay():
-    """HIP-graph decode mode: several replays, with eager work and synchronisation in between,
-    each compared bit for bit with the eager launch-per-shard result."""
+@pytest.mark.parametrize("M,hidden", [(1, 512), (4, 1024), (16, 512)])
+def test_graph_replay_matches_eager_on_every_replay(M, hidden):
+    """HIP-graph decode mode (one token; batched-decode steps of a few tokens, in the few-token kernel and in
+    the GEMM form): several replays, with eager work and synchronisation in between, each compared bit for
+    bit with the eager launch-per-shard result."""
     import torch
     from paper_2604_26334_amd import binding as B
-    cfg = Hn.small_dense_cfg(3)
+    cfg = dict(Hn.small_dense_cfg(3), hidden=hidden)
     W = Hn.WeightCache(cfg, 5)
     wb, _ = Hn.total_weight_bytes(cfg)
-    plan = B.Plan(cfg, wb + (1 << 20), 1)
+    plan = B.Plan(cfg, wb + (4 << 20), M)
     st = B.Stack(plan)
     for layer in range(cfg["n_layers"]):
         for kind, expert, N, K in S.matrix_shapes(cfg):
             st.load_matrix(layer, kind, expert, *W(layer, kind, expert))
-    xs = [torch.from_numpy(S.activations(5, t, 1, cfg["hidden"])).cuda() for t in range(3)]
+    xs = [torch.from_numpy(S.activations(5, t, M, cfg["hidden"])).cuda() for t in range(3)]
     eager = []
     st.set_decode_mode(0)
     for x in xs:
