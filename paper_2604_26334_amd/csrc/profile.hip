@@ -102,9 +102,17 @@ extern "C" int32_t ps_profile_measure(void *scratch_dev, uint64_t scratch_bytes,
         a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = 4096; a.x_group = 1; a.rinv = rinv; a.out = y;
         a.out_stride = 8192; a.top_k = 1;
         PS_HIP(launch_rinv(x, T, 4096, 1e-6f, rinv, cs));
+        // the executor runs two to kGemvMtTokens tokens in the few-token form of the decode kernel
+        const bool few = T <= (uint32_t)kGemvMtTokens && mg.nsb % 8 == 0;
+        GemvArgs fa{};
+        fa.W = a.W; fa.nunits = mg.ntiles; fa.tile_u4 = a.tile_u4; fa.nsb = mg.nsb; fa.ngroups = mg.ngroups; fa.K = mg.K;
+        fa.x = x; fa.x_group = 1; fa.x_stride = 4096; fa.eps = 1e-6f; fa.out = y; fa.out_stride = 8192; fa.top_k = 1;
         for (int rep = 0; rep < 2; ++rep) {
             PS_HIP(hipEventRecord(e0, cs));
-            for (int i = 0; i < kLaunches; ++i) PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
+            for (int i = 0; i < kLaunches; ++i) {
+                if (few) PS_HIP(launch_gemv_mt(GEMV_PLAIN, gemv_ksplit(mg.ngroups, mg.ntiles), fa, T, cs));
+                else PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
+            }
             PS_HIP(hipEventRecord(e1, cs));
             PS_HIP(hipEventSynchronize(e1));
         }
@@ -271,11 +279,18 @@ extern "C" int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc 
             a.nsb = mg.nsb; a.M = T; a.x = x; a.x_stride = mt.K; a.x_group = 1; a.rinv = rinv; a.out = y;
             a.out_stride = mt.rows; a.top_k = 1;
             PS_HIP(launch_rinv(x, T, mt.K, 1e-6f, rinv, cs));
+            // (two to kGemvMtTokens tokens: the few-token form of the decode kernel, as in the executor)
+            const bool few = T <= (uint32_t)kGemvMtTokens && mg.nsb % 8 == 0;
+            GemvArgs fa{};
+            fa.nunits = mg.ntiles; fa.tile_u4 = a.tile_u4; fa.nsb = mg.nsb; fa.ngroups = mg.ngroups; fa.K = mg.K;
+            fa.x = x; fa.x_group = 1; fa.x_stride = mt.K; fa.eps = 1e-6f; fa.out = y; fa.out_stride = mt.rows; fa.top_k = 1;
             for (int rep = 0; rep < 2; ++rep) {
                 PS_HIP(hipEventRecord(e0, cs));
                 for (int i = 0; i < kLaunches; ++i) {
                     a.W = reinterpret_cast<const uint4 *>(wts + (uint64_t)(i % fit) * mg.bytes);
-                    PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
+                    fa.W = a.W;
+                    if (few) PS_HIP(launch_gemv_mt(GEMV_PLAIN, gemv_ksplit(mg.ngroups, mg.ntiles), fa, T, cs));
+                    else PS_HIP(launch_gemm(GEMM_PLAIN, a, 0, T, cs));
                 }
                 PS_HIP(hipEventRecord(e1, cs));
                 PS_HIP(hipEventSynchronize(e1));

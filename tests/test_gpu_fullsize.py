@@ -132,10 +132,17 @@ def test_dense8b_prefill_2048_at_4gb():
 
 
 def test_dense8b_batch64_at_4_and_12_gb():
-    """Config 5 at both of its budgets."""
+    """Config 5 at both of its budgets, also in the graph-replay mode the benchmark times its batched legs in."""
     _say()
     rows = np.random.default_rng(1).choice(64, 10, replace=False)
-    _run(S.cfg_dense8b(), 0, 64, [4e9, 12e9], sample_rows=np.sort(rows))
+    _run(S.cfg_dense8b(), 0, 64, [4e9, 12e9], sample_rows=np.sort(rows), graph=[4e9, 12e9])
+
+
+def test_dense8b_batch4_few_token_kernel_at_4_and_2_gb():
+    """Four tokens per step on the full stack: every matrix runs in the few-token form of the decode kernel;
+    every row against the oracle, resident and streamed placements bit-identical, graph replay where resident."""
+    _say()
+    _run(S.cfg_dense8b(), 0, 4, [4e9, 2e9], graph=[4e9])
 
 
 def test_one_8b_layer_many_tokens_every_row_three_placements():
