@@ -85,7 +85,8 @@ extern "C" {
 #define PS_PLAN_AUTO 3     /* HeuristicSplit: build all three, keep the one with the lowest estimate  */
 
 #define PS_FLAG_NO_ATTN 1u     /* layers have no attention sub-layer (FFN block only) */
-#define PS_FLAG_NO_RESIDUAL 2u /* FFN output is not added to its input                */
+#define PS_FLAG_NO_RESIDUAL 2u /* dense FFN output is not added to its input (the bare FFN block of
+                                  benchmark config 1); PS_E_ARG together with MoE layers */
 
 /* token tiers of the paper's tier table (Section 3, inference phase) */
 #define PS_NTIERS 11

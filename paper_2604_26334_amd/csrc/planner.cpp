@@ -72,6 +72,12 @@ int32_t make_model_geom(const ps_model_desc *m, ModelGeom *out) {
             set_error("MoE needs ffn_inter 0, 0 < top_k <= min(n_experts, 32), n_experts <= 1024");
             return PS_E_ARG;
         }
+        if (m->flags & PS_FLAG_NO_RESIDUAL) {
+            // the flag describes the bare dense FFN block (RMSNorm -> gate/up -> SwiGLU -> down); an MoE layer's
+            // combine is defined with its residual
+            set_error("PS_FLAG_NO_RESIDUAL applies to dense FFN layers only");
+            return PS_E_ARG;
+        }
         g.ffn_i = m->expert_inter;
     } else {
         g.ffn_i = m->ffn_inter;

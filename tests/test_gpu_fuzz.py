@@ -12,16 +12,16 @@ pytestmark = pytest.mark.gpu
 TOL = 5e-3
 
 
-def _random_cfg(rng):
+def _random_cfg(rng, hiddens=(128, 256, 512), max_layers=3):
     moe = rng.random() < 0.4
     attn = rng.random() < 0.8
     n_kv = int(rng.choice([1, 2]))
-    cfg = dict(n_layers=int(rng.integers(1, 4)), hidden=int(rng.choice([128, 256, 512])),
+    cfg = dict(n_layers=int(rng.integers(1, max_layers + 1)), hidden=int(rng.choice(list(hiddens))),
                n_q_heads=n_kv * int(rng.choice([1, 2, 4])) if attn else 0, n_kv_heads=n_kv if attn else 0,
                head_dim=128 if attn else 0, ffn_inter=0 if moe else 128 * int(rng.integers(1, 9)),
                n_experts=int(rng.choice([4, 8])) if moe else 0, top_k=0,
                expert_inter=128 * int(rng.integers(1, 3)) if moe else 0, rms_eps=1e-6, no_attn=not attn,
-               no_residual=bool(rng.random() < 0.2))
+               no_residual=bool(rng.random() < 0.2) and not moe)     # (the flag is the bare dense FFN block's)
     if moe:
         cfg["top_k"] = int(rng.integers(1, 4))
     if rng.random() < 0.5:
@@ -31,14 +31,27 @@ def _random_cfg(rng):
 
 @pytest.mark.parametrize("seed", range(4))
 def test_random_models_match_the_oracle(seed):
+    _sweep(4000 + seed, 8, (128, 256, 512), 3, [1, 1, 2, 5, 16, 33, 64, 130])
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_random_models_of_whole_scale_groups_and_few_tokens(seed):
+    """Hidden sizes that are multiples of 1024 with two to four tokens: the few-token form of the decode kernel
+    on the attention matrices and the dense gate/up (and on the down projection where the intermediate size is a
+    multiple of 1024 too), next to the GEMM path, the CPU plans and the output head."""
+    _sweep(5000 + seed, 6, (1024, 2048), 2, [2, 3, 4, 4])
+
+
+def _sweep(seed0, cases, hiddens, max_layers, token_counts):
     import torch
     from paper_2604_26334_amd import binding as B
-    rng = np.random.default_rng(4000 + seed)
+    seed = seed0
+    rng = np.random.default_rng(seed0)
     prof = B.make_profile(h2d_gbps=50.0, gemv_gbps=4000.0, cpu_gbps=150.0, cpu_gbps_busy=120.0, h2d_gbps_busy=45.0,
                           cpu_tokens_free=3.0, cpu_sync_us=0.5)
-    for case in range(8):
-        cfg = _random_cfg(rng)
-        M = int(rng.choice([1, 1, 2, 5, 16, 33, 64, 130]))
+    for case in range(cases):
+        cfg = _random_cfg(rng, hiddens, max_layers)
+        M = int(rng.choice(token_counts))
         wseed = int(rng.integers(1 << 20))
         W = Hn.WeightCache(cfg, wseed)
         head = S.head_matrix(wseed, cfg) if cfg.get("vocab") else None

@@ -17,7 +17,7 @@ def _random_cfg(rng):
                n_kv_heads=n_kv if attn else 0, head_dim=128 if attn else 0,
                ffn_inter=0 if moe else 128 * int(rng.integers(1, 12)), n_experts=int(rng.choice([4, 8, 16])) if moe else 0,
                top_k=0, expert_inter=128 * int(rng.integers(1, 4)) if moe else 0, rms_eps=1e-6,
-               no_attn=not attn, no_residual=bool(rng.random() < 0.2))
+               no_attn=not attn, no_residual=bool(rng.random() < 0.2) and not moe)   # (the flag is the bare dense FFN block's)
     if moe:
         cfg["top_k"] = int(rng.integers(1, min(4, cfg["n_experts"]) + 1))
     if rng.random() < 0.4:

@@ -161,6 +161,10 @@ def test_budget_too_small_is_an_error_not_a_crash():
     assert e.value.code == B.PS_E_ARG
     with pytest.raises(B.PshardError):
         B.Plan(S.cfg_dense8b(), 10 ** 9, 0)
+    # the no-residual flag is the bare dense FFN block's (benchmark config 1): an MoE layer's combine keeps its residual
+    with pytest.raises(B.PshardError) as e:
+        B.Plan(dict(S.cfg_moe(2), no_residual=True), 10 ** 10, 1)
+    assert e.value.code == B.PS_E_ARG
 
 
 def test_expert_frequency_ranks_hot_experts_first():
