@@ -54,6 +54,31 @@ def test_noalloc_forward_matches_the_arena_forward_twice_in_a_row():
         plan.close()
 
 
+def test_noalloc_forward_with_the_few_token_kernel():
+    """Four tokens through matrices of whole scale groups (the few-token form of the decode kernel: no RMS-factor
+    buffer, no partial planes; its activations in the static array), then three: same bits as the arena forward."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = dict(Hn.small_dense_cfg(2), hidden=1024, n_q_heads=8, n_kv_heads=2, ffn_inter=2048)
+    W = Hn.WeightCache(cfg, 34)
+    for M, frac in ((4, 0.6), (3, 1.0)):
+        plan, st = _stack(B, cfg, W, M, frac)
+        x = S.activations(34, M, M, cfg["hidden"])
+        ref = O.stack_forward(x, cfg, W, mirror=True)
+        xin = torch.from_numpy(x).to(st.device)
+        y_arena, y_static = torch.zeros_like(xin), torch.zeros_like(xin)
+        st.forward(xin, y_arena)
+        st.synchronize()
+        for rep in range(2):
+            y_static.zero_()
+            st.forward_noalloc(xin, y_static)
+            st.synchronize()
+            np.testing.assert_array_equal(y_static.cpu().numpy().view(np.uint16), y_arena.cpu().numpy().view(np.uint16))
+        assert Hn.rel_err(y_static.cpu().numpy(), ref) <= TOL
+        st.close()
+        plan.close()
+
+
 def test_noalloc_forward_refuses_what_it_cannot_hold():
     import torch
     from paper_2604_26334_amd import binding as B
