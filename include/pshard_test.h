@@ -45,6 +45,12 @@ int32_t ps_stack_debug_buffer(ps_stack *st, uint32_t which, void **dev_ptr, uint
  * Used by a GPU test to confirm the operand lane layout the GEMM kernel relies on.
  * pi, pj in 0..15, pk in 0..31; asynchronous on stream. */
 int32_t ps_mfma_probe(int32_t pi, int32_t pk, int32_t pj, float *out_dev, void *stream);
+/* Diagnostic: one LDS transpose read (ds_read_b64_tr_b16) by a wave over a table of the 16-bit numbers
+ * 0 .. 2047 stored at their own index.  addr_dev: device uint32 [64], lane l's byte address into the
+ * table (rounded down to a multiple of 8 and clamped inside it); out_dev: device uint16 [64][4], the
+ * four numbers each lane received.  Used by a GPU test to confirm the lane layout the chunk-attention
+ * kernels rely on for their V operand.  Asynchronous on stream. */
+int32_t ps_lds_tr_probe(const uint32_t *addr_dev, uint16_t *out_dev, void *stream);
 
 #ifdef __cplusplus
 }

@@ -95,7 +95,7 @@ EXPORTS = ["ps_stack_create_tiers", "ps_stack_set_tier", "ps_stack_tier", "ps_st
            "ps_schedule_num_ops", "ps_schedule_get_op", "ps_schedule_validate", "ps_schedule_destroy",
            "ps_route_host", "ps_profile_measure", "ps_stack_create", "ps_stack_load_matrix",
            "ps_stack_forward", "ps_stack_set_decode_mode", "ps_stack_set_copy_mode", "ps_stack_sync_check", "ps_stack_set_profiling", "ps_stack_stats", "ps_stack_op_time", "ps_stack_time_kernel", "ps_stack_debug_buffer",
-           "ps_stack_destroy", "ps_mfma_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
+           "ps_stack_destroy", "ps_mfma_probe", "ps_lds_tr_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
            "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
            "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads",
            "ps_tier_table_create_kind", "ps_profile_db_create", "ps_profile_db_destroy", "ps_profile_db_add",
@@ -154,6 +154,7 @@ def lib():
             "ps_stack_time_kernel": [vp, u32, u32, C.POINTER(C.c_double), C.POINTER(u32)],
             "ps_stack_debug_buffer": [vp, u32, C.POINTER(vp), C.POINTER(u64)],
             "ps_mfma_probe": [i32, i32, i32, vp, vp],
+            "ps_lds_tr_probe": [vp, vp, vp],
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
             "ps_tier_table_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, C.POINTER(vp)],
             "ps_tier_table_create_kind": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, u32, C.POINTER(vp)],

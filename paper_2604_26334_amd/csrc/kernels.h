@@ -146,5 +146,6 @@ hipError_t launch_attn_combine(const float *part, uint32_t chunk_cap, uint32_t c
 hipError_t launch_combine(const __half *h, const float *y, const float *w, uint32_t M, uint32_t H, uint32_t top_k,
                           int residual, __half *out, hipStream_t st);
 hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st);
+hipError_t launch_lds_tr_probe(const uint32_t *addr, uint16_t *out, hipStream_t st);
 
 }  // namespace ps

@@ -729,7 +729,27 @@ constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 
 constexpr int kAttnIts = 8;               // steps of 4 positions per wave
 constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
 static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
-constexpr uint32_t kVRowBytes = 264;   // LDS pitch of a staged V row: 256 + 8 (8-byte writes stay aligned; column reads spread over the banks)
+constexpr uint32_t kVRowBytes = 288;   // LDS pitch of a staged V row: 256 + 32, so that the four rows of a transpose read lie 8 banks apart
+// A operand of O^T += V^T P^T for MFMA step s of a staged chunk and dim tile dt: lane (i, c) needs dim
+// 16 dt + i of the 8 positions 32 s + 8 c .. + 7, i.e. a COLUMN of the staged rows.  The LDS transpose read
+// of gfx950 (ds_read_b64_tr_b16) does that within each group of 16 lanes: lane L of a group names 8 bytes
+// (4 numbers), lane m receives number m % 4 of lanes m / 4, m / 4 + 4, m / 4 + 8, m / 4 + 12 (checked on the
+// hardware with index numbers as data).  With lane L naming row L / 4, dims 4 (L % 4) .. + 3 of the tile,
+// lane i receives dim i of four consecutive positions; two reads make the operand.
+// lane_base = staged rows + (8 c + i / 4) * kVRowBytes + (i % 4) * 8.
+__device__ __forceinline__ h8_t v_operand(const unsigned char *lane_base, int s, int dt) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(__fp16)))) __fp16 fp16x4_t;
+    typedef __attribute__((address_space(3))) fp16x4_t lds_fp16x4_t;
+    const unsigned char *p = lane_base + (32 * s) * kVRowBytes + dt * 32;
+    const fp16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_fp16x4_t *)(p));
+    const fp16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_fp16x4_t *)(p + 4 * kVRowBytes));
+    const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+    return __builtin_bit_cast(h8_t, make_uint4(a.x, a.y, b.x, b.y));
+#else
+    return h8_t{};
+#endif
+}
 static_assert(kAttnPos == kAttnPosPerWg, "the executor numbers the chunk's own partials behind ceil(ctx / kAttnPosPerWg) cache chunks");
 
 // sum over each row of 16 lanes, result in every lane of the row (DPP: no LDS traffic)
@@ -1022,6 +1042,45 @@ __global__ __launch_bounds__(kAttnWaves * 64, 16 / kAttnWaves) void attn_chunk_k
 // the vector-ALU kernel writes, merged by attn_combine_chunk_kernel in chunk order.
 // ------------------------------------------------------------------------------------
 
+// Score pass of the chunk kernels: S^T = K Q^T for the 16 position tiles of a 256-position chunk (tile t: step
+// t / 2, tile t % 2 of the step: positions P0 + 32 (t / 2) + 8 (p / 4) + 4 (t % 2) + p % 4, p = 0 .. 15).  The K
+// rows are A operands straight from memory, so their loads have to be under way well before the MFMAs that
+// take them: kKAhead tiles (4 loads each) stay in flight, a tile's registers refilled as soon as its MFMAs have
+// read them.  (Left to the scheduler, every load sat right in front of its MFMA: 64 exposed round trips to
+// the L2 per chunk.)
+constexpr int kKAhead = 4;
+struct KTiles { h8_t k[kKAhead][4]; };
+__device__ __forceinline__ void k_tile_load(__amdgpu_buffer_rsrc_t kb, uint32_t P0, uint32_t row_b, int t, int i, int c, h8_t (&dst)[4]) {
+    const uint32_t pos = P0 + 32 * (t >> 1) + 8 * (i >> 2) + 4 * (t & 1) + (i & 3);        // the K row this lane supplies
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        dst[kk] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(kb, pos * row_b + kk * 64 + c * 16, 0, 0));
+}
+__device__ __forceinline__ void k_tiles_open(__amdgpu_buffer_rsrc_t kb, uint32_t P0, uint32_t row_b, int i, int c, KTiles &kt) {
+#pragma unroll
+    for (int t = 0; t < kKAhead; ++t) k_tile_load(kb, P0, row_b, t, i, c, kt.k[t]);
+}
+// scores (scaled, -inf where the lane's row does not see the position) and their maximum over the lane's registers
+__device__ __forceinline__ void attn_scores(__amdgpu_buffer_rsrc_t kb, uint32_t P0, uint32_t row_b, int i, int c, KTiles &kt,
+                                            const h8_t (&qreg)[4], float scale, uint32_t limit, f4_t (&S)[8][2], float &mx) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        __builtin_amdgcn_sched_barrier(0);
+        f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kt.k[t % kKAhead][kk], qreg[kk], acc, 0, 0, 0);
+        if (t + kKAhead < 16) k_tile_load(kb, P0, row_b, t + kKAhead, i, c, kt.k[t % kKAhead]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t pj = P0 + 32 * (t >> 1) + 8 * c + 4 * (t & 1) + r;
+            acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
+            mx = fmaxf(mx, acc[r]);
+        }
+        S[t >> 1][t & 1] = acc;
+    }
+}
+
 __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a) {
     extern __shared__ uint4 lds_v4[];
     unsigned char *ldsv = reinterpret_cast<unsigned char *>(lds_v4);   // [256 positions][kVRowBytes]
@@ -1044,6 +1103,9 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
     const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
     const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
 
+    KTiles kt;
+    k_tiles_open(kb, P0, row_b, i, c, kt);      // the first K tiles set out ahead of everything else
+    __builtin_amdgcn_sched_barrier(0);
     // V rows of the chunk -> LDS (all 256 threads; 16 bytes each, 16 rounds)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -1067,28 +1129,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
     // pass 1: scores of the 8 steps.  Tile T of a step holds positions base + 8 (p >> 2) + 4 T + (p & 3), p = 0..15
     f4_t S[8][2];
     float mx = -INFINITY;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-#pragma unroll
-        for (int T = 0; T < 2; ++T) {
-            const uint32_t pos = P0 + 32 * s + 8 * (i >> 2) + 4 * T + (i & 3);        // the K row this lane supplies (A operand)
-            h8_t kreg[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                kreg[kk] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(kb, pos * row_b + kk * 64 + c * 16, 0, 0));
-            f4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kreg[kk], qreg[kk], acc, 0, 0, 0);
-            // lane (row i, group c) now holds positions P0 + 32 s + 8 c + 4 T + r of its row
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t pj = P0 + 32 * s + 8 * c + 4 * T + r;
-                acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
-                mx = fmaxf(mx, acc[r]);
-            }
-            S[s][T] = acc;
-        }
-    }
+    attn_scores(kb, P0, row_b, i, c, kt, qreg, scale, limit, S, mx);
     mx = rows4_meet<true>(mx);      // the row's four lanes (one per lane group) meet
     __syncthreads();                // the staged V rows are complete
 
@@ -1111,14 +1152,9 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
         const h8_t Bp = {(_Float16)pv[0], (_Float16)pv[1], (_Float16)pv[2], (_Float16)pv[3],
                          (_Float16)pv[4], (_Float16)pv[5], (_Float16)pv[6], (_Float16)pv[7]};
         // A operand: dim 16 dt + i of the 8 positions 32 s + 8 c .. + 7 (a column of the staged rows)
-        const unsigned char *col = ldsv + (32 * s + 8 * c) * kVRowBytes + i * 2;
+        const unsigned char *vbase = ldsv + (8 * c + (i >> 2)) * kVRowBytes + (i & 3) * 8;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            h8_t Av;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) Av[e] = *reinterpret_cast<const _Float16 *>(col + e * kVRowBytes + dt * 32);
-            O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Av, Bp, O[dt], 0, 0, 0);
-        }
+        for (int dt = 0; dt < 8; ++dt) O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(v_operand(vbase, s, dt), Bp, O[dt], 0, 0, 0);
     }
     l = rows4_meet<false>(l);
     // lane (row i, group c) holds dims 16 dt + 4 c + r of its row
@@ -1183,6 +1219,9 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArg
         const uint32_t P0 = chunk * kAttnPos;
         const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
         const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
+        KTiles kt;
+        k_tiles_open(kb, P0, row_b, i, c, kt);      // the first K tiles set out ahead of everything else
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();     // every wave has left the previous chunk's staged rows
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -1194,27 +1233,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArg
         }
         f4_t S[8][2];
         float mx = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                const uint32_t pos = P0 + 32 * s + 8 * (i >> 2) + 4 * T + (i & 3);
-                h8_t kreg[4];
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    kreg[kk] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(kb, pos * row_b + kk * 64 + c * 16, 0, 0));
-                f4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kreg[kk], qreg[kk], acc, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t pj = P0 + 32 * s + 8 * c + 4 * T + r;
-                    acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
-                    mx = fmaxf(mx, acc[r]);
-                }
-                S[s][T] = acc;
-            }
-        }
+        attn_scores(kb, P0, row_b, i, c, kt, qreg, scale, limit, S, mx);
         mx = rows4_meet<true>(mx);
         const float m_new = fmaxf(m_run, mx);
         // a row that has seen nothing yet keeps zeros (the difference of two -inf is not a number)
@@ -1238,14 +1257,9 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArg
                 }
             const h8_t Bp = {(_Float16)pv[0], (_Float16)pv[1], (_Float16)pv[2], (_Float16)pv[3],
                              (_Float16)pv[4], (_Float16)pv[5], (_Float16)pv[6], (_Float16)pv[7]};
-            const unsigned char *col = ldsv + (32 * s + 8 * c) * kVRowBytes + i * 2;
+            const unsigned char *vbase = ldsv + (8 * c + (i >> 2)) * kVRowBytes + (i & 3) * 8;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                h8_t Av;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) Av[e] = *reinterpret_cast<const _Float16 *>(col + e * kVRowBytes + dt * 32);
-                O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Av, Bp, O[dt], 0, 0, 0);
-            }
+            for (int dt = 0; dt < 8; ++dt) O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(v_operand(vbase, s, dt), Bp, O[dt], 0, 0, 0);
         }
         l_run += rows4_meet<false>(l);
     }
@@ -2109,6 +2123,31 @@ __global__ void mfma_probe_kernel(int pi, int pk, int pj, float *out /*[64][4]*/
     C = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, C, 0, 0, 0);
 #pragma unroll
     for (int r = 0; r < 4; ++r) out[lane * 4 + r] = C[r];
+}
+
+// LDS transpose read (ds_read_b64_tr_b16): LDS holds the 16-bit numbers 0 .. 2047 at their own index; lane l
+// reads at byte address addr[l] (forced to a multiple of 8 inside the table) and stores its four results.
+__global__ void lds_tr_probe_kernel(const uint32_t *addr, uint16_t *out /*[64][4]*/) {
+    __shared__ __attribute__((aligned(16))) uint16_t tab[2048];
+    const int lane = threadIdx.x & 63;
+    for (int k = lane; k < 2048; k += 64) tab[k] = (uint16_t)k;
+    __syncthreads();
+    const uint32_t off = min(addr[lane] & ~7u, 4088u);
+    typedef __attribute__((__vector_size__(4 * sizeof(__fp16)))) __fp16 fp16x4_t;
+    typedef __attribute__((address_space(3))) fp16x4_t lds_fp16x4_t;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const fp16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_fp16x4_t *)(reinterpret_cast<unsigned char *>(tab) + off));
+    const uint2 bits = __builtin_bit_cast(uint2, v);
+    out[lane * 4 + 0] = (uint16_t)(bits.x & 0xFFFFu);
+    out[lane * 4 + 1] = (uint16_t)(bits.x >> 16);
+    out[lane * 4 + 2] = (uint16_t)(bits.y & 0xFFFFu);
+    out[lane * 4 + 3] = (uint16_t)(bits.y >> 16);
+#endif
+}
+
+hipError_t launch_lds_tr_probe(const uint32_t *addr, uint16_t *out, hipStream_t st) {
+    hipLaunchKernelGGL(lds_tr_probe_kernel, dim3(1), dim3(64), 0, st, addr, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_mfma_probe(int pi, int pk, int pj, float *out, hipStream_t st) {

@@ -1553,6 +1553,12 @@ void ps_stack_destroy(ps_stack *st) {
     delete st;
 }
 
+int32_t ps_lds_tr_probe(const uint32_t *addr_dev, uint16_t *out_dev, void *stream) {
+    if (!addr_dev || !out_dev) { ps::set_error("probe buffers missing"); return PS_E_ARG; }
+    PS_HIP(ps::launch_lds_tr_probe(addr_dev, out_dev, static_cast<hipStream_t>(stream)));
+    return PS_OK;
+}
+
 int32_t ps_mfma_probe(int32_t pi, int32_t pk, int32_t pj, float *out_dev, void *stream) {
     if (pi < 0 || pi > 15 || pj < 0 || pj > 15 || pk < 0 || pk > 31 || !out_dev) { ps::set_error("probe index out of range"); return PS_E_ARG; }
     PS_HIP(ps::launch_mfma_probe(pi, pk, pj, out_dev, static_cast<hipStream_t>(stream)));

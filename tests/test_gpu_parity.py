@@ -37,6 +37,31 @@ def test_mfma_operand_layout_probe():
         assert c[pj + 16 * (pi // 4), pi % 4] == 1.0
 
 
+def test_lds_transpose_read_lane_layout():
+    """The LDS transpose read the chunk-attention kernels build their V operand with: within each group of 16
+    lanes, lane L names 4 consecutive 16-bit numbers and lane m receives number m % 4 of lanes m / 4 + 4 e,
+    e = 0 .. 3.  Checked with index numbers as data, for rows of the staged-V pitch and for packed chunks."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    for pitch in (8, 288):                      # bytes between the rows the four lanes of a column name
+        addr = np.zeros(64, dtype=np.uint32)
+        for l in range(64):
+            g, L = divmod(l, 16)
+            addr[l] = (3 * g + L // 4) * pitch + (L % 4) * 8 if pitch > 8 else 8 * l    # (inside the 4 KB table)
+        a = torch.from_numpy(addr.view(np.int32)).cuda()
+        out = torch.zeros(256, dtype=torch.int16, device="cuda")
+        assert B.lib().ps_lds_tr_probe(a.data_ptr(), out.data_ptr(), None) == 0
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint16).reshape(64, 4)
+        want = np.zeros((64, 4), dtype=np.uint16)
+        for l in range(64):
+            g, m = divmod(l, 16)
+            for e in range(4):
+                src = 16 * g + 4 * e + m // 4               # the lane whose 8 bytes hold the number
+                want[l, e] = addr[src] // 2 + m % 4
+        np.testing.assert_array_equal(got, want)
+
+
 def _check(cfg, seed, M, budgets, logits=None, tol=TOL):
     W = Hn.WeightCache(cfg, seed)
     x = S.activations(seed, 0, M, cfg["hidden"])
