@@ -729,6 +729,7 @@ constexpr int kAttnWaves = 8;             // waves per workgroup (measured at a 
 constexpr int kAttnIts = 8;               // steps of 4 positions per wave
 constexpr int kAttnPos = kAttnWaves * kAttnIts * 4;   // positions per workgroup (a multiple of kAttnChunk, which sizes the partials)
 static_assert(kAttnPos % kAttnChunk == 0, "the workspace is sized for one partial per kAttnChunk positions");
+constexpr uint32_t kKRowBytes = 272;   // LDS pitch of a staged K row: the 16 rows of an operand read lie 4 banks apart
 constexpr uint32_t kVRowBytes = 288;   // LDS pitch of a staged V row: 256 + 32, so that the four rows of a transpose read lie 8 banks apart
 // A operand of O^T += V^T P^T for MFMA step s of a staged chunk and dim tile dt: lane (i, c) needs dim
 // 16 dt + i of the 8 positions 32 s + 8 c .. + 7, i.e. a COLUMN of the staged rows.  The LDS transpose read
@@ -1180,9 +1181,10 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
 // (tokens x heads x chunks) is what makes the record form unusable for long chunks over long contexts.
 // The order of the chunks is fixed, so the result does not depend on where a cache shard lives.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArgs a) {
+__global__ __launch_bounds__(256, 1) void attn_chunk_onepass_kernel(AttnChunkArgs a) {
     extern __shared__ uint4 lds_v4[];
-    unsigned char *ldsv = reinterpret_cast<unsigned char *>(lds_v4);   // [256 positions][kVRowBytes]
+    unsigned char *ldsv = reinterpret_cast<unsigned char *>(lds_v4);   // V rows [256 positions][kVRowBytes]
+    unsigned char *ldsk = ldsv + kAttnPos * kVRowBytes;                 // K rows [256 positions][kKRowBytes]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, c = lane >> 4;
     const uint32_t hk = blockIdx.x, G = a.group;
@@ -1219,21 +1221,58 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArg
         const uint32_t P0 = chunk * kAttnPos;
         const __amdgpu_buffer_rsrc_t kb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(K), 0, (int)range, 0x00020000);
         const __amdgpu_buffer_rsrc_t vb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(V), 0, (int)range, 0x00020000);
-        KTiles kt;
-        k_tiles_open(kb, P0, row_b, i, c, kt);      // the first K tiles set out ahead of everything else
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();     // every wave has left the previous chunk's staged rows
+        // the chunk's K and V rows -> LDS: every thread requests its 32 pieces (16 bytes each) at once, so the
+        // whole 128 KB is under way together (the four waves share the K rows instead of each reading them all)
+        {
+            uint4 kq[16], vq[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
-            const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
-            uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
-            dst[0] = make_uint2(v.x, v.y);
-            dst[1] = make_uint2(v.z, v.w);
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+                kq[r] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(kb, (P0 + pos) * row_b + seg * 16, 0, 0));
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+                vq[r] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
+            }
+            __syncthreads();     // every wave has left the previous chunk's staged rows
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+                *reinterpret_cast<uint4 *>(ldsk + pos * kKRowBytes + seg * 16) = kq[r];
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+                uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
+                dst[0] = make_uint2(vq[r].x, vq[r].y);
+                dst[1] = make_uint2(vq[r].z, vq[r].w);
+            }
         }
+        __syncthreads();     // the staged rows are complete
         f4_t S[8][2];
         float mx = -INFINITY;
-        attn_scores(kb, P0, row_b, i, c, kt, qreg, scale, limit, S, mx);
+        {
+            // S^T = K Q^T, the K rows as A operands from LDS: lane (i, c) supplies row 8 (i / 4) + i % 4 (+ 4 for
+            // the second tile of a step), bytes 64 kk + 16 c
+            const unsigned char *kbase = ldsk + (8 * (i >> 2) + (i & 3)) * kKRowBytes + c * 16;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const h8_t kreg = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(kbase + (32 * (t >> 1) + 4 * (t & 1)) * kKRowBytes + kk * 64));
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kreg, qreg[kk], acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t pj = P0 + 32 * (t >> 1) + 8 * c + 4 * (t & 1) + r;
+                    acc[r] = pj < limit ? acc[r] * scale : -INFINITY;
+                    mx = fmaxf(mx, acc[r]);
+                }
+                S[t >> 1][t & 1] = acc;
+            }
+        }
         mx = rows4_meet<true>(mx);
         const float m_new = fmaxf(m_run, mx);
         // a row that has seen nothing yet keeps zeros (the difference of two -inf is not a number)
@@ -1242,7 +1281,6 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_onepass_kernel(AttnChunkArg
         l_run *= resc;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) O[dt] = O[dt] * resc;
-        __syncthreads();     // the staged V rows are complete
         float l = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -1280,7 +1318,7 @@ hipError_t launch_attn_chunk_onepass(const AttnChunkArgs &a, hipStream_t st) {
     if (a.group == 0 || a.group > 16 || !a.out || !a.k_own || !a.v_own) return hipErrorInvalidValue;
     if (((uint64_t)a.ctx + kAttnPos) * 256u > 0x7FFFFFFFull || ((uint64_t)a.ntok + kAttnPos) * a.own_stride * 2u > 0x7FFFFFFFull) return hipErrorInvalidValue;
     dim3 grid(a.nheads, (a.ntok * a.group + 63) / 64);
-    const size_t ldsb = (size_t)kAttnPos * kVRowBytes;
+    const size_t ldsb = (size_t)kAttnPos * (kVRowBytes + kKRowBytes);
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_chunk_onepass_kernel),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb);
     if (attr != hipSuccess) return attr;
@@ -1906,6 +1944,13 @@ static hipError_t launch_gemm_m(const GemmArgs &a, uint32_t ntasks, uint32_t max
     if (max_tok <= 16) return launch_gemm_t<MODE, 2, 16>(a, ntasks, max_tok, st);
     if (max_tok <= 32) return launch_gemm_t<MODE, 2, 32>(a, ntasks, max_tok, st);
     if (max_tok <= 64) return launch_gemm_t<MODE, 2, 64>(a, ntasks, max_tok, st);
+    // A few hundred tokens on a narrow matrix (O and down at 512 tokens: 32 eight-tile workgroups x 4 token
+    // tiles) leave half the CUs without a workgroup in 128-token tiles: 64-token tiles double the workgroups.
+    // The tile shape goes by the whole matrix and the plan's token count, never by the slab, and every shape
+    // adds a row's super-blocks in the same order, so the choice does not change a bit of the result.
+    // (measured on the 8B shapes over a 4K cache, per layer: 256 tokens 387 -> 296 us, 512 tokens 462 -> 409 us,
+    // 1024 tokens 714 -> 697 us; from 1.5 workgroups per CU on, the 128-token tile is the faster one)
+    if (!ntasks && (a.total_tiles + 7) / 8 * ((max_tok + 127) / 128) < 384) return launch_gemm_t<MODE, 2, 64>(a, ntasks, max_tok, st);
     // 2 row-tiles per wave leave room for the pipelined dequant at two workgroups per CU; the
     // 4-tile shape (half the LDS operand traffic) does not fit that register budget
     return launch_gemm_t<MODE, 2, 128>(a, ntasks, max_tok, st);
