@@ -1107,14 +1107,23 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnChunkArgs a
     KTiles kt;
     k_tiles_open(kb, P0, row_b, i, c, kt);      // the first K tiles set out ahead of everything else
     __builtin_amdgcn_sched_barrier(0);
-    // V rows of the chunk -> LDS (all 256 threads; 16 bytes each, 16 rounds)
+    // V rows of the chunk -> LDS (all 256 threads; 16 bytes each, 16 rounds): every piece is requested before
+    // the first is written (written one by one, each load was waited for before the next was issued)
+    {
+        uint4 vq[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
-        const uint4 v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
-        uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
-        dst[0] = make_uint2(v.x, v.y);
-        dst[1] = make_uint2(v.z, v.w);
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+            vq[r] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(vb, (P0 + pos) * row_b + seg * 16, 0, 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t idx = r * 256 + tid, pos = idx >> 4, seg = idx & 15;
+            uint2 *dst = reinterpret_cast<uint2 *>(ldsv + pos * kVRowBytes + seg * 16);
+            dst[0] = make_uint2(vq[r].x, vq[r].y);
+            dst[1] = make_uint2(vq[r].z, vq[r].w);
+        }
     }
     // this wave's 16 query rows (B operand of the score MFMAs): row rho = (token, head of the group)
     const uint32_t rho = min(row0 + wave * 16 + i, R - 1);
