@@ -622,8 +622,11 @@ __global__ __launch_bounds__(256) void rinv_kernel(const __half *x, uint32_t M, 
         uint4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            // (a chunk past the row's end re-reads the last one and counts as zeros: no branch around the load,
+            // so the four requests go out together)
             const uint32_t q = q0 + u * 256 + threadIdx.x;
-            v[u] = q < nq ? row[q] : uint4{0u, 0u, 0u, 0u};
+            const uint4 w = row[min(q, nq - 1)];
+            v[u] = q < nq ? w : uint4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) ss += sumsq8(v[u]);
@@ -1396,13 +1399,33 @@ __global__ __launch_bounds__(128) void attn_combine_chunk_kernel(const float *pa
     const uint32_t group = n_q / n_kv, g = h / group;
     const uint32_t nc_cache = (ctx + kAttnPos - 1) / kAttnPos, nc_own = t / kAttnPos + 1;
     const float *ph = part + ((size_t)t * n_q + h) * chunk_cap * 130;
+    // the records are read eight (then four) chunks at a time, every load of a round requested before the first
+    // is used (a chunk past the last re-reads the last one and is left out); the sums stay in chunk order
+    const uint32_t nct = nc_cache + nc_own;
     float mx = -INFINITY;
-    for (uint32_t c = 0; c < nc_cache + nc_own; ++c) mx = fmaxf(mx, ph[(size_t)c * 130]);
+    for (uint32_t c0 = 0; c0 < nct; c0 += 8) {
+        float mv[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) mv[u] = ph[(size_t)min(c0 + u, nct - 1) * 130];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) mx = fmaxf(mx, mv[u]);
+    }
     float L = 0.f, o = 0.f;
-    for (uint32_t c = 0; c < nc_cache + nc_own; ++c) {
-        const float w = __expf(ph[(size_t)c * 130] - mx);
-        L = fmaf(w, ph[(size_t)c * 130 + 1], L);
-        o = fmaf(w, ph[(size_t)c * 130 + 2 + d], o);
+    for (uint32_t c0 = 0; c0 < nct; c0 += 4) {
+        float mv[4], lv[4], ov[4];
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            const float *pc = ph + (size_t)min(c0 + u, nct - 1) * 130;
+            mv[u] = pc[0]; lv[u] = pc[1]; ov[u] = pc[2 + d];
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            if (c0 + u < nct) {
+                const float w = __expf(mv[u] - mx);
+                L = fmaf(w, lv[u], L);
+                o = fmaf(w, ov[u], o);
+            }
+        }
     }
     out[(size_t)t * out_stride + (size_t)h * 128 + d] = to_half(o / L);
     if (h % group == 0) {
