@@ -1576,7 +1576,20 @@ __global__ __launch_bounds__(256) void combine_kernel(const __half *h, const flo
     for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n; q += (size_t)gridDim.x * 256) {
         const uint32_t m = (uint32_t)(q / H), col = (uint32_t)(q % H);
         float s = 0.f;
-        for (uint32_t j = 0; j < top_k; ++j) s += w[(size_t)m * top_k + j] * y[((size_t)m * top_k + j) * H + col];
+        // eight experts' rows and weights are requested before the first is added (a rank past the last re-reads
+        // the last one and is left out); the sum stays in rank order
+        for (uint32_t j0 = 0; j0 < top_k; j0 += 8) {
+            float wv[8], yv[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const size_t pr = (size_t)m * top_k + min(j0 + u, top_k - 1);
+                wv[u] = w[pr];
+                yv[u] = y[pr * H + col];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u)
+                if (j0 + u < top_k) s += wv[u] * yv[u];
+        }
         out[q] = __float2half((residual ? __half2float(h[q]) : 0.f) + s);
     }
 }
