@@ -123,6 +123,42 @@ def test_few_token_decode_kernel(M, ffn):
     _check(cfg, 11, M, _budgets(cfg, M, [1.0, 0.6, 0.35]))
 
 
+def test_few_token_kernel_in_chunked_trips():
+    """Seven tokens through a four-token plan: a full trip and a short last one (three valid rows of four) in the
+    few-token kernel, eager and replayed from a graph; every row against the oracle, and a row's bits do not
+    depend on the trip it rode in (chunks are independent: attention is the identity on V)."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = dict(Hn.small_dense_cfg(2), hidden=1024, n_q_heads=8, n_kv_heads=2, ffn_inter=2048)
+    W = Hn.WeightCache(cfg, 13)
+    x = S.activations(13, 0, 7, cfg["hidden"])
+    ref = O.stack_forward(x, cfg, W, mirror=True)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    outs = []
+    for frac, mode in ((1.0, 0), (1.0, 1), (0.5, 0)):
+        plan = B.Plan(cfg, _budgets(cfg, 4, [frac])[0], 4)
+        st = B.Stack(plan)
+        st.set_decode_mode(mode)
+        for layer in range(cfg["n_layers"]):
+            for kind, expert, N, K in S.matrix_shapes(cfg):
+                st.load_matrix(layer, kind, expert, *W(layer, kind, expert))
+        xin = torch.from_numpy(x).to(st.device)
+        y = torch.zeros_like(xin)
+        assert B.chunked_forward(st, xin, y) == 2
+        st.synchronize()
+        outs.append(y.cpu().numpy())
+        # the last three rows alone, as a trip of their own
+        y3 = torch.zeros_like(xin[4:])
+        B.chunked_forward(st, xin[4:].contiguous(), y3)
+        st.synchronize()
+        np.testing.assert_array_equal(y3.cpu().numpy().view(np.uint16), outs[-1][4:].view(np.uint16))
+        st.close()
+        plan.close()
+    assert Hn.rel_err(outs[0], ref) <= TOL
+    for y in outs[1:]:
+        np.testing.assert_array_equal(y.view(np.uint16), outs[0].view(np.uint16))
+
+
 def test_few_token_decode_kernel_under_moe_layers():
     """The attention matrices of an MoE stack take the few-token kernel too; the experts' grouped GEMM still gets
     its RMS factors from their own launch."""
