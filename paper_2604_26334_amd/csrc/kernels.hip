@@ -447,18 +447,18 @@ hipError_t launch_gemv(int mode, uint32_t ksplit, const GemvArgs &a, uint32_t nt
 template <int MODE, int NW>
 __global__ __launch_bounds__(NW * 64, 4) void gemv_mt_kernel(GemvArgs a, uint32_t ks, uint32_t ntok) {
     extern __shared__ uint4 mt_lds[];
-    // a wave works on ONE row-tile (two tiles' weights of a scale group do not fit the registers beside the
-    // operands): a gate/up unit takes 2 ks waves, the gate tile's and the up tile's, which meet in the epilogue
+    // a wave holds ONE row-tile's weights of a scale group at a time (two tiles' do not fit the registers beside
+    // the operands): of a gate/up unit it takes the gate tile first and, super-block by super-block as the gate
+    // tile's registers are used up, requests the up tile's into them, so one window serves both tiles
     constexpr int NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
     constexpr int TK = kGemvMtTokens;
     constexpr bool NORM = (MODE == GEMV_PLAIN || MODE == GEMV_GATE_UP);
     static_assert(MODE != GEMV_F32, "dense sub-layers only");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, c = lane >> 4;
-    const uint32_t wpu = ks * NT;               // waves per unit
+    const uint32_t wpu = ks;                    // waves per unit
     const uint32_t units = NW / wpu;
     const uint32_t unit = blockIdx.x * units + wave / wpu;
-    const uint32_t tsel = (wave % wpu) / ks;    // which tile of the unit
     const uint32_t kpart = wave % ks;
     const bool active = unit < a.nunits;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -486,12 +486,16 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_mt_kernel(GemvArgs a, uint32_
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
             GemvBuf<1> cur;
-            gemv_issue_w<1, true>(cur, a.W, unit * NT + tsel, a.tile_u4, g, 8u, lane);
-            // the window fills are the oldest loads in flight: all but the 9 weight loads behind them
+            gemv_issue_w<1, true>(cur, a.W, unit * NT, a.tile_u4, g, 8u, lane);
+            const __amdgpu_buffer_rsrc_t wrs = make_rsrc(a.W);
+            const uint32_t up_base = __builtin_amdgcn_readfirstlane((unit * NT + 1) * a.tile_u4 * 16u + g * (9u * 1024u));
+            uint4 sc_up = make_uint4(0, 0, 0, 0);
+            if (NT == 2) sc_up = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wrs, (uint32_t)lane * 16u, up_base + 8u * 1024u, kAuxNt));
+            // the window fills are the oldest loads in flight: all but the weight loads behind them
             // (the compiler does not know of loads into LDS; later loads only make this wait stricter)
-            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(9 + (NT - 1)) : "memory");
             const uint32_t slot = (wave / wpu) * a.ngroups + g;
-            if (NORM && tsel == 0) {
+            if (NORM) {
 #pragma unroll
                 for (int t = 0; t < TK; ++t) {
                     const uint4 xa = win[t * 128 + lane], xb = win[t * 128 + 64 + lane];
@@ -508,33 +512,40 @@ __global__ __launch_bounds__(NW * 64, 4) void gemv_mt_kernel(GemvArgs a, uint32_
                     if (lane == 0) red_ss[slot * TK + t] = gss;
                 }
             }
-            f4_t gacc = f4_t{0.f, 0.f, 0.f, 0.f};
             const uint4 *wb = win + tb * 128;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
+            for (int tile = 0; tile < NT; ++tile) {
+                const uint4 sc = tile == 0 ? cur.sc[0] : sc_up;
+                f4_t gacc = f4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const h8_t B = __builtin_bit_cast(h8_t, wb[(uint32_t)(s * 16 + c * 4 + kk) ^ tb]);
+                for (int s = 0; s < 8; ++s) {
                     const uint4 wq = cur.wq[0][s];
-                    const uint32_t q = kk == 0 ? wq.x : kk == 1 ? wq.y : kk == 2 ? wq.z : wq.w;
-                    const uint32_t dw = (s < 2) ? cur.sc[0].x : (s < 4) ? cur.sc[0].y : (s < 6) ? cur.sc[0].z : cur.sc[0].w;
-                    const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
-                    const h2_t dd = {d, d};
-                    h2_t w[4];
-                    dequant8(q, w);
-                    w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
-                    const h8_t A = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
-                    gacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, gacc, 0, 0, 0);
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        const h8_t B = __builtin_bit_cast(h8_t, wb[(uint32_t)(s * 16 + c * 4 + kk) ^ tb]);
+                        const uint32_t q = kk == 0 ? wq.x : kk == 1 ? wq.y : kk == 2 ? wq.z : wq.w;
+                        const uint32_t dw = (s < 2) ? sc.x : (s < 4) ? sc.y : (s < 6) ? sc.z : sc.w;
+                        const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)((s & 1) ? (dw >> 16) : (dw & 0xFFFFu)));
+                        const h2_t dd = {d, d};
+                        h2_t w[4];
+                        dequant8(q, w);
+                        w[0] *= dd; w[1] *= dd; w[2] *= dd; w[3] *= dd;
+                        const h8_t A = h8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+                        gacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, gacc, 0, 0, 0);
+                    }
+                    // this super-block's registers are free: the next tile's super-block sets out into them
+                    if (tile + 1 < NT)
+                        cur.wq[0][s] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wrs, (uint32_t)lane * 16u, up_base + (uint32_t)s * 1024u, kAuxNt));
                 }
+                // lane (j, c) holds rows 4c .. 4c + 3 of token column j
+                if (j < TK)
+                    *reinterpret_cast<float4 *>(red + ((slot * NT + tile) * TK + j) * 16 + c * 4) = make_float4(gacc[0], gacc[1], gacc[2], gacc[3]);
             }
-            // lane (j, c) holds rows 4c .. 4c + 3 of token column j
-            if (j < TK)
-                *reinterpret_cast<float4 *>(red + ((slot * NT + tsel) * TK + j) * 16 + c * 4) = make_float4(gacc[0], gacc[1], gacc[2], gacc[3]);
             asm volatile("" ::: "memory");   // the window's reads are behind us before the next group's fills are issued
         }
     }
     __syncthreads();
-    if (!(active && kpart == 0 && tsel == 0 && (uint32_t)j < ntok)) return;
+    if (!(active && kpart == 0 && (uint32_t)j < ntok)) return;
     const uint32_t slot0 = (wave / wpu) * a.ngroups;
     float acc[NT][4];
 #pragma unroll
@@ -571,9 +582,8 @@ size_t gemv_mt_lds_bytes(uint32_t nw, uint32_t units, uint32_t ngroups, uint32_t
 template <int MODE>
 static hipError_t launch_gemv_mt_t(const GemvArgs &a, uint32_t ks, uint32_t ntok, hipStream_t st) {   // ks by value: adjusted below
     constexpr uint32_t NT = (MODE == GEMV_GATE_UP) ? 2 : 1;
-    // workgroup shapes as for one token (launch_gemv_f), in waves per unit (a gate/up unit: 2 ks)
-    while (ks * NT > 16) ks /= 2;
-    const uint32_t wpu = ks * NT;
+    // workgroup shapes as for one token (launch_gemv_f)
+    const uint32_t wpu = ks;
     uint32_t nw = wpu > 8 ? 16 : wpu > 4 ? 8 : 4;
     if (wpu == 4 && (a.nunits + 1) / 2 >= 192) nw = 8;
     const uint32_t units = nw / wpu;
