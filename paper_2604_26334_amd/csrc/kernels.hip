@@ -1,6 +1,13 @@
 // CDNA4 (gfx950) kernels of the pipelined-sharding hot path: the dequantising matmuls of
 // the decoder sub-layers with their fused RMSNorm / SwiGLU / residual steps, MoE routing and
-// the expert combine.  Weight layout: see pack.cpp.  wave64 only.
+// the expert combine, and attention over the KV cache.  Weight layout: see pack.cpp.  wave64 only.
+//   matmuls by token count:  1 -> gemv_w4_kernel,  2..4 -> gemv_mt_kernel (whole scale groups),
+//                            otherwise gemm_w4_kernel (+ splitk_epilogue* when K is split)
+//   attention:  one query token -> attn_decode_kernel + attn_combine_kernel,
+//               a long chunk of query tokens -> attn_chunk_onepass_kernel (one walk over the cache and
+//               the chunk's own rows);  a short chunk -> attn_chunk_mfma_kernel over 256-position
+//               pieces of the cache (attn_chunk_kernel when there are fewer than 16 score rows), the
+//               pieces merged by attn_combine_chunk_kernel
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
