@@ -524,9 +524,15 @@ int32_t ps_stack_forward_chunked(ps_stack *st, const void *x_in, void *x_out, ui
  * (Algorithm 1's RunInTopologicalOrder); both modes give bit-identical results.  (A third value
  * exists for tests only, see pshard_test.h.)  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
-/* How the streamed experts of one slot fill cross PCIe.  gather = 1 (default): one kernel on
- * the copy stream pulls all of them from the pinned pool (one launch per slot fill);
- * gather = 0: one hipMemcpyAsync per expert.  Dense slabs always use hipMemcpyAsync. */
+/* How streamed shards cross PCIe (Section 3: the copy of the next shard runs beside the compute of
+ * the current one).  gather = 1 (default): the streamed experts of one slot fill are pulled from
+ * the pinned pool by one kernel on the copy stream (one launch per slot fill), and so are the
+ * dense slabs of a plan whose step is copy time almost alone (copy estimate at least ten times the
+ * kernel estimate, from the plan's profile: the kernel keeps the link busier than back-to-back
+ * hipMemcpyAsync calls but slows kernels that run beside it); other dense slabs and all KV rows
+ * use hipMemcpyAsync.  gather = 0: hipMemcpyAsync for everything, one per expert.  gather = 2:
+ * the kernel for every expert and dense slab.  The bytes that arrive are the same in every mode.
+ * PS_E_ARG for another value.  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather);
 /* Block until both streams are idle, i.e. until the schedule's last shard has run (Algorithm 1,
  * RunInTopologicalOrder, seen from the caller); PS_E_HIP if either stream reports an error. */

@@ -560,7 +560,7 @@ class Stack:
             _check(lib().ps_stack_sync_check(self.h))
 
     def set_copy_mode(self, gather):
-        _check(lib().ps_stack_set_copy_mode(self.h, 1 if gather else 0))
+        _check(lib().ps_stack_set_copy_mode(self.h, int(gather)))
 
     def set_decode_mode(self, mode):
         """0: launch per shard, 1: HIP-graph replay, 2: mode 0 with every RMS factor from a launch of its own (see pshard_test.h)."""

@@ -2032,30 +2032,45 @@ hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t ma
 }
 
 // ------------------------------------------------------------------------------------
-// Gathered host->device copy: blockIdx.y selects the shard, the workgroups of a shard
-// stride through it in 16-byte units (each wave moves 1 KB contiguous per step).
+// Gathered host->device copy.  A fixed, small number of workgroups walks every shard of the list in
+// turn, each taking its share of every shard in 16-byte units (a wave moves 1 KB contiguous per
+// load), eight loads per thread in flight.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs) {
-    const CopyDesc d = descs[blockIdx.y];
-    const u4_t *src = reinterpret_cast<const u4_t *>(d.src);
-    u4_t *dst = reinterpret_cast<u4_t *>(d.dst);
+constexpr uint32_t kGatherDescs = 128;   // descriptors staged in LDS at a time
+constexpr uint32_t kGatherWgs = 16;
+__global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs, uint32_t n) {
+    __shared__ CopyDesc sd[kGatherDescs];
     const uint32_t stride = gridDim.x * 256;
-    uint32_t idx = blockIdx.x * 256 + threadIdx.x;
-    for (; idx + 7 * stride < d.n16; idx += 8 * stride) {
-        u4_t v[8];
+    for (uint32_t base = 0; base < n; base += kGatherDescs) {
+        const uint32_t m = min(kGatherDescs, n - base);
+        __syncthreads();
+        // the list may sit in pinned host memory: one round trip over PCIe for the whole chunk
+        if (threadIdx.x < m) sd[threadIdx.x] = descs[base + threadIdx.x];
+        __syncthreads();
+        for (uint32_t e = 0; e < m; ++e) {
+            const u4_t *src = reinterpret_cast<const u4_t *>(sd[e].src);
+            u4_t *dst = reinterpret_cast<u4_t *>(sd[e].dst);
+            const uint32_t n16 = sd[e].n16;
+            if (n16 == 0) continue;
+            // past the end a load re-reads the last unit and its store is skipped, so the last pass
+            // keeps eight loads in flight like the others
+            for (uint32_t idx = blockIdx.x * 256 + threadIdx.x; idx < n16; idx += 8 * stride) {
+                u4_t v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + idx + u * stride);
+                for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + min(idx + u * stride, n16 - 1));
 #pragma unroll
-        for (int u = 0; u < 8; ++u) dst[idx + u * stride] = v[u];
+                for (int u = 0; u < 8; ++u)
+                    if (idx + u * stride < n16) dst[idx + u * stride] = v[u];
+            }
+        }
     }
-    for (; idx < d.n16; idx += stride) dst[idx] = __builtin_nontemporal_load(src + idx);
 }
 
 hipError_t launch_h2d_gather(const CopyDesc *descs, uint32_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
-    // 8 workgroups per shard: enough outstanding reads to fill the PCIe link, few enough to leave the
-    // CUs to the compute stream
-    hipLaunchKernelGGL(h2d_gather_kernel, dim3(8, n), dim3(256), 0, st, descs);
+    // 16 workgroups keep 512 KB of reads in flight, which fills the PCIe link; more only queue up
+    // ahead of the compute stream's reads from HBM
+    hipLaunchKernelGGL(h2d_gather_kernel, dim3(kGatherWgs), dim3(256), 0, st, descs, n);
     return hipGetLastError();
 }
 

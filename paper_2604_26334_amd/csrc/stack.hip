@@ -56,6 +56,10 @@ struct ps_stack {
     bool upload_pending[2] = {false, false};
     uint32_t table_idx = 0;                   // table buffer of the current forward
     bool gather_copy = true;                  // expert batches: one gather kernel instead of one memcpy each
+    int32_t copy_mode = 1;                    // as set by ps_stack_set_copy_mode
+    bool gather_dense = false;                // this plan's dense slabs go through the gather kernel as well
+    ps::CopyDesc *dense_descs = nullptr;      // pinned: one descriptor per op of the dense schedule (copies use theirs)
+    size_t dense_descs_cap = 0;
     uint64_t descs_off = 0;                   // offset of the copy descriptors in a table buffer
     uint32_t n_descs = 0;                     // descriptors written in the current forward
     ps_schedule dense_sched;
@@ -672,14 +676,19 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
             if (prof) { PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->copy)); st->prof_is_copy[i] = 1; }
             size_t last = i;
-            if (st->gather_copy && p.shards[o.shard0].kind == PS_SHARD_EXPERT && st->tables_host[0]) {
+            const bool expert_gather = st->gather_copy && p.shards[o.shard0].kind == PS_SHARD_EXPERT && st->tables_host[0];
+            const bool dense_gather = st->gather_dense && st->dense_descs && &sc == &st->dense_sched && p.shards[o.shard0].kind != PS_SHARD_KV;
+            if (expert_gather || dense_gather) {
                 // the rest of this slot fill follows in the op list: one gather launch for all of it
-                ps::CopyDesc *descs = reinterpret_cast<ps::CopyDesc *>(
+                // (a dense schedule never changes between forwards: its descriptors sit at the ops' own
+                // indices and are rewritten with the same values)
+                ps::CopyDesc *descs = dense_gather ? st->dense_descs + i : reinterpret_cast<ps::CopyDesc *>(
                     static_cast<uint8_t *>(st->tables_host[st->table_idx]) + st->descs_off) + st->n_descs;
                 uint32_t n = 0;
                 for (size_t j = i; j < sc.ops.size(); ++j) {
                     const ps_op_info &c = sc.ops[j].info;
                     if (c.type != PS_OP_COPY || c.slot != o.slot || (j > i && (c.flags & PS_OPF_WAIT_SLOT_FREE))) break;
+                    if (dense_gather && p.shards[c.shard0].kind == PS_SHARD_KV) break;
                     descs[n].src = (uint64_t)(uintptr_t)st->shard_host[c.shard0];
                     descs[n].dst = (uint64_t)(uintptr_t)(slot_ptr(st, c.slot) + c.slot_offset);
                     descs[n].n16 = (uint32_t)(c.bytes / 16);
@@ -694,7 +703,7 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
                     }
                     if (c.flags & PS_OPF_RECORD_READY) break;
                 }
-                st->n_descs += n;
+                if (!dense_gather) st->n_descs += n;
                 PS_HIP(launch_h2d_gather(descs, n, st->copy));
             } else if (p.shards[o.shard0].kind == PS_SHARD_KV) {
                 // a cache shard: only the rows the step attends over cross PCIe (K rows, then V rows)
@@ -744,6 +753,29 @@ extern "C" {
 
 namespace {
 
+// Whether a dense plan's streamed slabs should cross PCIe through the gather kernel rather than
+// hipMemcpyAsync.  Measured on the 8B-shaped stack: the kernel keeps the link at 98 % of the pinned
+// H2D rate where back-to-back hipMemcpyAsync calls leave about 60 us between copies (90 %), but a
+// kernel that runs beside it is several times slower (its loads queue behind the PCIe reads on the
+// CUs the gather occupies).  So it pays where the step is copy time almost alone: the plan's copy
+// estimate at least ten times its kernel estimate (one-token decode at 2 GB: 36 ms against 1 ms,
+// 40.3 -> 37.0 ms per token; the 295 MB head beside 1 ms of resident decode, ratio 5: 6.4 -> 7.1 ms).
+// mode: 0 never, 1 by this rule, 2 always.
+bool dense_gather_pays(const ps_plan &p, int32_t mode) {
+    if (mode != 1) return mode == 2;
+    if (!(p.prof.h2d_gbps > 0) || !(p.prof.gemv_gbps > 0) || p.streamed_bytes == 0) return false;
+    const double tf = p.prof.gemm_tflops[p.tier];
+    double copy_ms = 0, kernel_ms = 0;
+    for (const ps::Shard &sh : p.shards) {
+        if (sh.resident == 2) continue;
+        const double t_mem = (double)sh.bytes / (p.prof.gemv_gbps * 1e9);
+        const double t_cmp = tf > 0 ? 2.0 * p.M * ((double)sh.bytes / 0.5625) / (tf * 1e12) : 0;
+        kernel_ms += std::max(t_mem, t_cmp) * 1e3;
+        if (!sh.resident) copy_ms += (double)sh.bytes / (p.prof.h2d_gbps * 1e9) * 1e3;
+    }
+    return copy_ms >= 10.0 * kernel_ms;
+}
+
 // tile size of the matrix a shard is cut from (0: whole shards, never split)
 uint64_t shard_tile_bytes(const ps::ModelGeom &g, uint32_t kind) {
     switch (kind) {
@@ -783,6 +815,18 @@ int32_t bind_plan(ps_stack *st) {
         rc = ps::validate_schedule(&st->dense_sched);
         if (rc) return rc;
         st->have_dense_sched = true;
+        st->gather_dense = dense_gather_pays(p, st->copy_mode);
+        if (st->dense_sched.ops.size() > st->dense_descs_cap) {
+            if (st->dense_descs) (void)hipHostFree(st->dense_descs);
+            st->dense_descs = nullptr;
+            st->dense_descs_cap = 0;
+            void *d = nullptr;
+            if (hipHostMalloc(&d, st->dense_sched.ops.size() * sizeof(ps::CopyDesc), hipHostMallocDefault) != hipSuccess) {
+                ps::set_error("hipHostMalloc for copy descriptors failed"); return PS_E_HIP;
+            }
+            st->dense_descs = static_cast<ps::CopyDesc *>(d);
+            st->dense_descs_cap = st->dense_sched.ops.size();
+        }
     }
     st->use_graph = st->decode_mode == 1 && graph_eligible(p) && st->have_dense_sched;
     if (p.g.kv) {
@@ -1421,7 +1465,10 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode) {
 
 int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather) {
     if (!st) { ps::set_error("NULL argument"); return PS_E_ARG; }
+    if (gather < 0 || gather > 2) { ps::set_error("copy mode must be 0, 1 or 2"); return PS_E_ARG; }
+    st->copy_mode = gather;
     st->gather_copy = gather != 0;
+    st->gather_dense = st->have_dense_sched && dense_gather_pays(st->plan, gather);
     return PS_OK;
 }
 
@@ -1541,6 +1588,7 @@ void ps_stack_destroy(ps_stack *st) {
     if (st->stage) (void)hipHostFree(st->stage);
     for (uint16_t *b : {st->host_h, st->host_s, st->host_x, st->host_out}) if (b) (void)hipHostFree(b);
     for (int b = 0; b < 2; ++b) if (st->tables_host[b]) (void)hipHostFree(st->tables_host[b]);
+    if (st->dense_descs) (void)hipHostFree(st->dense_descs);
     for (int s = 0; s < 2; ++s) {
         if (st->ev_ready[s]) (void)hipEventDestroy(st->ev_ready[s]);
         if (st->ev_free[s]) (void)hipEventDestroy(st->ev_free[s]);

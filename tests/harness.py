@@ -41,7 +41,7 @@ def total_weight_bytes(cfg):
     return p.summary().weight_bytes, p.summary().workspace_bytes
 
 
-def run_gpu(cfg, weights, budget, x_np, logits=None, expert_freq=None, steps=1, profile=None, mode=0):
+def run_gpu(cfg, weights, budget, x_np, logits=None, expert_freq=None, steps=1, profile=None, mode=0, copy_mode=None):
     """Plan for budget, load, run one forward per x in x_np (list) -> list of fp16 numpy outputs."""
     import torch
     from paper_2604_26334_amd import binding as B
@@ -50,6 +50,8 @@ def run_gpu(cfg, weights, budget, x_np, logits=None, expert_freq=None, steps=1, 
     plan = B.Plan(cfg, int(budget), M, profile=profile, expert_freq=expert_freq)
     st = B.Stack(plan)
     st.set_decode_mode(mode)
+    if copy_mode is not None:
+        st.set_copy_mode(copy_mode)
     for layer in range(cfg["n_layers"]):
         for kind, expert, N, K in S.matrix_shapes(cfg):
             sc, cd = weights(layer, kind, expert)

@@ -175,6 +175,31 @@ def test_small_moe(M):
     _check(cfg, 3, M, _budgets(cfg, M, [1.0, 0.6, 0.35]), logits=lg)
 
 
+@pytest.mark.parametrize("kind,M", [("dense", 1), ("dense", 4), ("dense", 37), ("moe", 1), ("moe", 5)])
+def test_copy_modes_move_the_same_bytes(kind, M):
+    """Streamed shards cross PCIe by hipMemcpyAsync (mode 0), by the gather kernel where the library's rule
+    picks it (mode 1, the default) or by the gather kernel throughout (mode 2): the outputs are bit-identical,
+    match the oracle, and the same number of bytes is streamed.  Three forwards in a row, so slots are reused
+    and the gather's descriptors are written again."""
+    if kind == "dense":
+        cfg, lgs = Hn.small_dense_cfg(3), None
+    else:
+        cfg = Hn.small_moe_cfg(2)
+        lgs = [S.router_logits(17, t, cfg["n_layers"], M, cfg["n_experts"]) for t in range(3)]
+    W = Hn.WeightCache(cfg, 17)
+    xs = [S.activations(17, t, M, cfg["hidden"]) for t in range(3)]
+    budget = _budgets(cfg, M, [0.4])[0]
+    res = {m: Hn.run_gpu(cfg, W, budget, xs, logits=lgs, copy_mode=m) for m in (0, 1, 2)}
+    assert res[0][1]["streamed"] > 0
+    for t in range(3):
+        ref = O.stack_forward(xs[t], cfg, W, logits=None if lgs is None else lgs[t], mirror=True)
+        assert Hn.rel_err(res[0][0][t], ref) <= TOL
+        for m in (1, 2):
+            np.testing.assert_array_equal(res[0][0][t].view(np.uint16), res[m][0][t].view(np.uint16))
+    for m in (1, 2):
+        assert res[m][1]["stats"].streamed_bytes_step == res[0][1]["stats"].streamed_bytes_step
+
+
 @pytest.mark.parametrize("M", [1, 5])
 def test_small_moe_hot_experts_ranked_by_frequency(M):
     """Planner's expert ranking on the device: biased router logits make some experts hot; with the
@@ -764,6 +789,9 @@ def test_error_paths_return_codes_and_leave_the_stack_usable():
         st.load_kv(0, 0, np.zeros((4, 128), np.float16), np.zeros((4, 128), np.float16))
     with pytest.raises(B.PshardError):
         st.set_decode_mode(7)
+    with pytest.raises(B.PshardError) as e:
+        st.set_copy_mode(3)
+    assert e.value.code == B.PS_E_ARG
     st.forward(x, y)
     st.synchronize()
     ref = O.stack_forward(S.activations(4, 0, 1, cfg["hidden"]), cfg, W, mirror=True)
