@@ -58,6 +58,7 @@ struct ps_stack {
     bool gather_copy = true;                  // expert batches: one gather kernel instead of one memcpy each
     int32_t copy_mode = 1;                    // as set by ps_stack_set_copy_mode
     bool gather_dense = false;                // this plan's dense slabs go through the gather kernel as well
+    bool inline_fill = true;                  // a layer's only expert fill is issued on the compute stream
     ps::CopyDesc *dense_descs = nullptr;      // pinned: one descriptor per op of the dense schedule (copies use theirs)
     size_t dense_descs_cap = 0;
     uint64_t descs_off = 0;                   // offset of the copy descriptors in a table buffer
@@ -605,6 +606,20 @@ static bool graph_eligible(const ps_plan &p) {
     return !p.g.moe && p.n_slots == 0 && p.cpu_bytes == 0 && (p.M == 1 || (p.M <= 64 && !p.g.kv));
 }
 
+// True when the copy op at index i opens the only slot fill of its layer (the schedule lists a layer's
+// expert copies between its routing kernel and the next layer's ops; a fill ends at its ready record).
+bool only_fill_of_layer(const ps_schedule &sc, size_t i) {
+    const uint32_t layer = sc.ops[i].info.layer;
+    bool past_ready = false;
+    for (size_t j = i; j < sc.ops.size() && sc.ops[j].info.layer == layer; ++j) {
+        const ps_op_info &c = sc.ops[j].info;
+        if (c.type != PS_OP_COPY) continue;
+        if (past_ready) return false;
+        if (c.flags & PS_OPF_RECORD_READY) past_ready = true;
+    }
+    return true;
+}
+
 int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __half *x_out) {
     const ps_plan &p = st->plan;
     const bool prof = st->profiling;
@@ -672,9 +687,17 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             continue;
         }
         if (o.type == PS_OP_COPY) {
-            if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
-            if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
-            if (prof) { PS_HIP(hipEventRecord(st->prof_ev[2 * i], st->copy)); st->prof_is_copy[i] = 1; }
+            // A streamed expert fill that is its layer's only one goes out on the compute stream: it
+            // can start only when the router has run and the layer's streamed experts can start only
+            // when it has landed, so the copy stream would add two cross-stream event hand-overs and
+            // nothing it could run ahead of (stream order stands in for both waits).
+            const bool inl = st->inline_fill && (o.flags & PS_OPF_WAIT_ROUTER) && only_fill_of_layer(sc, i);
+            const hipStream_t cps = inl ? st->compute : st->copy;
+            if (!inl) {
+                if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
+                if (o.flags & PS_OPF_WAIT_ROUTER) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_router[o.layer], 0));
+            }
+            if (prof) { PS_HIP(hipEventRecord(st->prof_ev[2 * i], cps)); st->prof_is_copy[i] = 1; }
             size_t last = i;
             const bool expert_gather = st->gather_copy && p.shards[o.shard0].kind == PS_SHARD_EXPERT && st->tables_host[0];
             const bool dense_gather = st->gather_dense && st->dense_descs && &sc == &st->dense_sched && p.shards[o.shard0].kind != PS_SHARD_KV;
@@ -697,32 +720,32 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
                     ss.streamed_bytes_step += c.bytes;
                     ss.n_copies++;
                     if (prof && j > i) {   // the batch's time is booked on its first op
-                        PS_HIP(hipEventRecord(st->prof_ev[2 * j], st->copy));
-                        PS_HIP(hipEventRecord(st->prof_ev[2 * j + 1], st->copy));
+                        PS_HIP(hipEventRecord(st->prof_ev[2 * j], cps));
+                        PS_HIP(hipEventRecord(st->prof_ev[2 * j + 1], cps));
                         st->prof_is_copy[j] = 1;
                     }
                     if (c.flags & PS_OPF_RECORD_READY) break;
                 }
                 if (!dense_gather) st->n_descs += n;
-                PS_HIP(launch_h2d_gather(descs, n, st->copy));
+                PS_HIP(launch_h2d_gather(descs, n, cps));
             } else if (p.shards[o.shard0].kind == PS_SHARD_KV) {
                 // a cache shard: only the rows the step attends over cross PCIe (K rows, then V rows)
                 const uint64_t rows_b = (uint64_t)st->ctx * p.g.m.head_dim * 2, vbase = (uint64_t)p.g.m.kv_context * p.g.m.head_dim * 2;
                 if (rows_b) {
                     uint8_t *dst = slot_ptr(st, o.slot) + o.slot_offset;
-                    PS_HIP(hipMemcpyAsync(dst, st->shard_host[o.shard0], rows_b, hipMemcpyHostToDevice, st->copy));
-                    PS_HIP(hipMemcpyAsync(dst + vbase, st->shard_host[o.shard0] + vbase, rows_b, hipMemcpyHostToDevice, st->copy));
+                    PS_HIP(hipMemcpyAsync(dst, st->shard_host[o.shard0], rows_b, hipMemcpyHostToDevice, cps));
+                    PS_HIP(hipMemcpyAsync(dst + vbase, st->shard_host[o.shard0] + vbase, rows_b, hipMemcpyHostToDevice, cps));
                     ss.streamed_bytes_step += 2 * rows_b;
                     ss.n_copies += 2;
                 }
             } else {
                 PS_HIP(hipMemcpyAsync(slot_ptr(st, o.slot) + o.slot_offset, st->shard_host[o.shard0], o.bytes,
-                                      hipMemcpyHostToDevice, st->copy));
+                                      hipMemcpyHostToDevice, cps));
                 ss.streamed_bytes_step += o.bytes;
                 ss.n_copies++;
             }
-            if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], st->copy));
-            if (sc.ops[last].info.flags & PS_OPF_RECORD_READY) PS_HIP(hipEventRecord(st->ev_ready[o.slot], st->copy));
+            if (prof) PS_HIP(hipEventRecord(st->prof_ev[2 * i + 1], cps));
+            if (sc.ops[last].info.flags & PS_OPF_RECORD_READY) PS_HIP(hipEventRecord(st->ev_ready[o.slot], cps));
             i = last;
         } else {
             if (o.flags & PS_OPF_WAIT_READY) PS_HIP(hipStreamWaitEvent(st->compute, st->ev_ready[o.slot], 0));
@@ -1468,6 +1491,7 @@ int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather) {
     if (gather < 0 || gather > 2) { ps::set_error("copy mode must be 0, 1 or 2"); return PS_E_ARG; }
     st->copy_mode = gather;
     st->gather_copy = gather != 0;
+    st->inline_fill = gather == 1;
     st->gather_dense = st->have_dense_sched && dense_gather_pays(st->plan, gather);
     return PS_OK;
 }
