@@ -378,15 +378,29 @@ static int32_t build_plan(const ps_model_desc *model, uint64_t budget, const ps_
         return PS_E_BUDGET;
     }
 
-    // SortByPriority: class first; inside a class layer order and matrix order, experts by
-    // descending frequency then (layer, expert)
+    // SortByPriority: class first; experts by descending frequency; then the layer's place in a
+    // spread walk over the stack (bit-reversed layer index: 0, L/2, L/4, 3L/4, ...), then matrix
+    // order / expert id.  The paper fixes the order of the classes only.  With the spread walk the
+    // layers a budget pins whole lie evenly between the streamed ones, so a pinned layer's kernels
+    // run while the next streamed layer's first slot fills cross PCIe (in the timing estimate: a
+    // shard costs the larger of its compute and the next shard's copy), where pinning the first
+    // layers of the stack leaves nothing beside the copies of the rest.  The walk does not
+    // depend on the token count, so every tier of a budget ranks the shards alike.
+    uint32_t lbits = 0;
+    while ((1u << lbits) < m.n_layers) ++lbits;
+    auto spread = [&](uint32_t layer) {
+        uint32_t r = 0;
+        for (uint32_t b = 0; b < lbits; ++b) r |= ((layer >> b) & 1u) << (lbits - 1 - b);
+        return r;
+    };
     std::vector<uint32_t> order(cands.size());
     std::iota(order.begin(), order.end(), 0u);
     std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
         const Cand &x = cands[a], &y = cands[b];
         if (x.s.cls != y.s.cls) return x.s.cls < y.s.cls;
         if (x.s.kind == PS_SHARD_EXPERT && y.s.kind == PS_SHARD_EXPERT && x.freq != y.freq) return x.freq > y.freq;
-        return a < b;  // enumeration order = (layer, matrix order / expert id)
+        if (x.s.layer != y.s.layer) return spread(x.s.layer) < spread(y.s.layer);
+        return a < b;  // enumeration order inside a layer = matrix order / expert id
     });
     for (uint32_t r = 0; r < order.size(); ++r) cands[order[r]].s.rank = r;
 
