@@ -2038,8 +2038,15 @@ hipError_t launch_gemm(int mode, const GemmArgs &a, uint32_t ntasks, uint32_t ma
 // ------------------------------------------------------------------------------------
 constexpr uint32_t kGatherDescs = 128;   // descriptors staged in LDS at a time
 constexpr uint32_t kGatherWgs = 16;
+constexpr uint32_t kLdsPerCu = 160 * 1024;   // gfx950
 __global__ __launch_bounds__(256) void h2d_gather_kernel(const CopyDesc *descs, uint32_t n) {
     __shared__ CopyDesc sd[kGatherDescs];
+    // The rest of the CU's LDS is claimed and left unused: no workgroup that needs LDS (every
+    // matmul and attention kernel does) can then be placed on this CU, where its loads would
+    // queue behind half a megabyte of PCIe reads on the CU's one vector-memory path (a one-token
+    // matmul beside a gather: 45 us without the claim, 25 us with it, 13 us alone).
+    __shared__ uint8_t rest[kLdsPerCu - sizeof(CopyDesc) * kGatherDescs];
+    asm volatile("" ::"v"(&rest[threadIdx.x]));
     const uint32_t stride = gridDim.x * 256;
     for (uint32_t base = 0; base < n; base += kGatherDescs) {
         const uint32_t m = min(kGatherDescs, n - base);
