@@ -140,6 +140,31 @@ def test_priority_attention_before_ffn_and_first_fit():
         assert max(ranks) < min(x.priority_rank for x in sh if x.cls == B.PS_CLASS_FFN)
 
 
+def test_pinned_layers_of_a_class_are_spread_over_the_stack():
+    # Algorithm 1 fixes the order of the classes only (SortByPriority).  Inside a class this planner ranks the
+    # layers in a spread walk, so that whatever prefix of the class a budget pins lies evenly between the
+    # streamed layers (their kernels then run beside the next streamed layer's copies), and the ranking does
+    # not depend on the token count (every tier of a budget pins a prefix of the same list).
+    for L in (32, 12, 5):
+        cfg = S.cfg_dense8b(L)
+        per_layer = 122683392
+        rank_by_tokens = []
+        for M in (1, 64, 2048):
+            _, s, sh = _plan(cfg, 0.5 * L * per_layer + 0.35e9, M)   # room for the workspace and the two slots
+            rank_by_tokens.append({(x.layer, x.kind): x.priority_rank for x in sh if x.tile0 == 0 or x.resident == 1})
+            pinned = sorted({x.layer for x in sh if x.kind == B.PS_SHARD_GATE_UP and x.resident == 1 and x.ntiles == 14336 * 2 // 16})
+            assert len(pinned) >= 2
+            # no run of streamed layers longer than twice the even spacing, at the ends included
+            gaps = [b - a for a, b in zip([-1] + pinned, pinned + [L])]
+            assert max(gaps) <= 2 * -(-L // len(pinned)), (L, M, pinned)
+            assert pinned[0] == 0
+        assert rank_by_tokens[0] == rank_by_tokens[1] == rank_by_tokens[2]
+        # a class's ranks: one permutation of the layers, matrices of a layer next to each other
+        ffn = sorted((r, k) for k, r in rank_by_tokens[0].items() if k[1] in (B.PS_SHARD_GATE_UP, B.PS_SHARD_DOWN))
+        layers = [k[0] for _, k in ffn]
+        assert layers[0::2] == layers[1::2] and sorted(layers[0::2]) == list(range(L))
+
+
 def test_streamed_bytes_monotone_in_budget():
     # the paper's evaluation appendix: throughput rises with budget; here: streamed bytes never rise
     cfg = S.cfg_dense8b(8)
