@@ -530,10 +530,10 @@ int32_t ps_stack_set_decode_mode(ps_stack *st, int32_t mode);
  * dense slabs of a plan whose step is copy time almost alone (copy estimate at least ten times the
  * kernel estimate, from the plan's profile: the kernel keeps the link busier than back-to-back
  * hipMemcpyAsync calls but slows kernels that run beside it); other dense slabs and all KV rows
- * use hipMemcpyAsync.  In this mode an expert fill that is its layer's only one is launched on the
- * compute stream, between the router and the experts that wait for it (nothing could run beside
- * it, and two cross-stream hand-overs per layer are saved); modes 0 and 2 keep every copy on the
- * copy stream.  gather = 0: hipMemcpyAsync for everything, one per expert.  gather = 2:
+ * use hipMemcpyAsync.  In this mode, in one-token steps, an expert fill that is its layer's only one
+ * is launched on the compute stream, between the router and the experts that wait for it (two
+ * cross-stream hand-overs per layer are saved, which at one token outweigh running the resident
+ * experts beside the copy); modes 0 and 2 keep every copy on the copy stream.  gather = 0: hipMemcpyAsync for everything, one per expert.  gather = 2:
  * the kernel for every expert and dense slab.  The bytes that arrive are the same in every mode.
  * PS_E_ARG for another value.  Not to be called while a forward is in flight. */
 int32_t ps_stack_set_copy_mode(ps_stack *st, int32_t gather);

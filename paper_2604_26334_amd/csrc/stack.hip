@@ -610,6 +610,8 @@ static bool graph_eligible(const ps_plan &p) {
 // expert copies between its routing kernel and the next layer's ops; a fill ends at its ready record).
 bool only_fill_of_layer(const ps_schedule &sc, size_t i) {
     const uint32_t layer = sc.ops[i].info.layer;
+    for (size_t j = i; j-- > 0 && sc.ops[j].info.layer == layer;)
+        if (sc.ops[j].info.type == PS_OP_COPY) return false;   // an earlier fill of this layer
     bool past_ready = false;
     for (size_t j = i; j < sc.ops.size() && sc.ops[j].info.layer == layer; ++j) {
         const ps_op_info &c = sc.ops[j].info;
@@ -687,11 +689,13 @@ int32_t run_schedule(ps_stack *st, const ps_schedule &sc, const __half *x_in, __
             continue;
         }
         if (o.type == PS_OP_COPY) {
-            // A streamed expert fill that is its layer's only one goes out on the compute stream: it
-            // can start only when the router has run and the layer's streamed experts can start only
-            // when it has landed, so the copy stream would add two cross-stream event hand-overs and
-            // nothing it could run ahead of (stream order stands in for both waits).
-            const bool inl = st->inline_fill && (o.flags & PS_OPF_WAIT_ROUTER) && only_fill_of_layer(sc, i);
+            // One-token steps: a streamed expert fill that is its layer's only one goes out on the
+            // compute stream.  It can start only when the router has run and the layer's streamed
+            // experts can start only when it has landed, so the copy stream would add two cross-stream
+            // event hand-overs and hide only the launch of the resident experts, which at one token is
+            // shorter than the hand-overs (with more tokens it is not, and the copy stream keeps the
+            // fill).  Stream order stands in for both waits.
+            const bool inl = st->inline_fill && st->n_valid == 1 && (o.flags & PS_OPF_WAIT_ROUTER) && only_fill_of_layer(sc, i);
             const hipStream_t cps = inl ? st->compute : st->copy;
             if (!inl) {
                 if (o.flags & PS_OPF_WAIT_SLOT_FREE) PS_HIP(hipStreamWaitEvent(st->copy, st->ev_free[o.slot], 0));
