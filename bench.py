@@ -215,11 +215,11 @@ def moe_leg(B, S, torch, seed, prof, budget, token_counts, steps, bias_seed=7):
     return out
 
 
-def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
-    """Token-tier table + PickTier + chunked prefill: plan every tier under `budget`, pick the tier for a
-    prompt of `tokens` tokens, and time the chunked prefill with the picked tier and its two neighbours
-    (estimate against measurement for each)."""
-    table = B.TierTable(cfg, int(budget), profile=prof)
+def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens, db=None):
+    """Token-tier table + PickTier + chunked prefill: plan every tier under `budget` (priced from the
+    profile database when one is given), pick the tier for a prompt of `tokens` tokens, and time the
+    chunked prefill with the picked tier and its two neighbours (estimate against measurement for each)."""
+    table = B.TierTable(cfg, int(budget), profile=prof, db=db)
     choice = table.pick(tokens)
     ents = table.entries()
     cand = [t for t in (choice.tier - 1, choice.tier, choice.tier + 1)
@@ -230,7 +230,8 @@ def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
     x = torch.from_numpy(S.activations(seed, 400, tokens, cfg["hidden"])).to(dev)
     y = torch.empty_like(x)
     torch.cuda.synchronize()
-    out = dict(budget_bytes=int(budget), tokens=tokens, picked_tier_tokens=choice.tier_tokens, tiers={})
+    out = dict(budget_bytes=int(budget), tokens=tokens, picked_tier_tokens=choice.tier_tokens, tiers={},
+               estimates="profile database" if db is not None else "profile rates")
     for t, st in zip(cand, stacks):
         e = ents[t]
         B.chunked_forward(st, x, y)
@@ -253,13 +254,14 @@ def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens):
     return out
 
 
-def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, decode_mode):
+def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, decode_mode, db=None):
     """The paper's operating mode under ONE budget on ONE stack: the tier table is planned once,
     PickTier chooses the prefill tier for a prompt of `prompt` tokens, the chunked prefill runs (TTFT),
     the one-token tier is installed (SetupForSched: shards that the prefill tier's workspace displaced
     are pinned again from the host images) and `decode_steps` tokens are decoded (TPS)."""
-    table = B.TierTable(cfg, int(budget), profile=prof)
+    table = B.TierTable(cfg, int(budget), profile=prof, db=db)   # the install-time database prices every tier
     choice = table.pick(prompt)
+    by_rates = B.TierTable(cfg, int(budget), profile=prof).pick(prompt)
     st = B.Stack(table)
     st.set_decode_mode(decode_mode)
     B.load_synthetic([st], cfg, seed, threads=min(16, os.cpu_count() or 8))
@@ -291,7 +293,11 @@ def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, deco
     r.update(budget_bytes=int(budget), prompt_tokens=prompt, picked_tier_tokens=choice.tier_tokens, decode_steps=decode_steps,
              tokens_per_s=1e3 / r["decode_ms_per_token"], est_ttft_ms=choice.est_total_ms, est_decode_ms=e_dec.summary.est_step_ms,
              resident_bytes_prefill_tier=e_pre.summary.resident_bytes, resident_bytes_decode_tier=e_dec.summary.resident_bytes,
-             e2el_ms_100_tokens=r["ttft_ms"] + r["setup_decode_ms"] + 100 * r["decode_ms_per_token"])
+             e2el_ms_100_tokens=r["ttft_ms"] + r["setup_decode_ms"] + 100 * r["decode_ms_per_token"],
+             estimates="profile database" if db is not None else "profile rates",
+             pick_from_profile_rates_alone=dict(tier_tokens=by_rates.tier_tokens, trips=by_rates.iterations, est_ttft_ms=by_rates.est_total_ms))
+    log("one stack, budget %.0f GB: PickTier estimate %.1f ms (from the profile's rates alone it picks %d x %d, %.1f ms)" % (
+        budget / 1e9, choice.est_total_ms, by_rates.tier_tokens, by_rates.iterations, by_rates.est_total_ms))
     log("one stack, budget %.0f GB: prefill %d tokens in tier %d x %d trips: TTFT %.1f ms; switch to the one-token tier %.2f ms (%.1f MB pinned again); decode %.3f ms/token = %.1f tok/s" % (
         budget / 1e9, prompt, choice.tier_tokens, r["trips"], r["ttft_ms"], r["setup_decode_ms"], r["pinned_again_bytes_decode"] / 1e6,
         r["decode_ms_per_token"], r["tokens_per_s"]))
@@ -639,11 +645,15 @@ def main():
         fresh()
         extra["batched_decode_16"] = batched_leg(B, S, torch, cfg, seed, prof, 16, [4e9], 128, args.decode_mode)
     fresh()
+    tier_db = None
+    if ("tiers" in args.extra or "session" in args.extra) and args.layers == 32:
+        tier_db = B.ProfileDB()      # the install phase's benchmark suite: every matrix of the model at every tier
+        tier_db.measure(cfg)
     if "tiers" in args.extra and args.layers == 32:
-        extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048)
+        extra["chunked_prefill_2gb"] = tier_leg(B, S, torch, cfg, seed, prof, 2e9, 2048, db=tier_db)
     fresh()
     if "session" in args.extra and args.layers == 32:
-        extra["prefill_then_decode_one_stack"] = {"%g" % (b / 1e9): session_leg(B, S, torch, cfg, seed, prof, b, 2048, 64 if b > 3e9 else 8, args.decode_mode)
+        extra["prefill_then_decode_one_stack"] = {"%g" % (b / 1e9): session_leg(B, S, torch, cfg, seed, prof, b, 2048, 64 if b > 3e9 else 8, args.decode_mode, db=tier_db)
                                                   for b in (4e9, 2e9)}
     fresh()
     if "kv" in args.extra and args.layers == 32:

@@ -404,6 +404,14 @@ int32_t ps_profile_db_measure(ps_profile_db *db, const ps_model_desc *model, voi
 int32_t ps_plan_create_db(const ps_model_desc *model, uint64_t vram_budget_bytes, const ps_profile *profile,
                           const ps_profile_db *db, uint32_t n_tokens, const float *expert_freq, uint32_t kind,
                           ps_plan **out);
+/* ps_tier_table_create_kind with every tier's plan priced from a profile database as in
+ * ps_plan_create_db (the paper's overview: the install-time database feeds the timing estimator
+ * that fills the (token tier, best schedule) table of the planning phase).  PickTier then compares
+ * tiers by times measured on the model's own matrices at each tier's token count.  The database is
+ * copied. */
+int32_t ps_tier_table_create_db(const ps_model_desc *model, uint64_t vram_budget_bytes,
+                                const ps_profile *profile, const ps_profile_db *db,
+                                const float *expert_freq, uint32_t kind, ps_tier_table **out);
 
 /* Algorithm 1, SetupForSched: install one schedule.  Binds a plan to a VRAM arena (device, 256-byte
  * aligned, arena_bytes >= the plan's budget: the arena IS the VRAM budget of Section 3, nothing else

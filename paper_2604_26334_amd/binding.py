@@ -98,7 +98,7 @@ EXPORTS = ["ps_stack_create_tiers", "ps_stack_set_tier", "ps_stack_tier", "ps_st
            "ps_stack_destroy", "ps_mfma_probe", "ps_lds_tr_probe", "ps_pack_matrix", "ps_tier_table_create", "ps_tier_table_entry",
            "ps_tier_table_plan", "ps_tier_pick", "ps_tier_table_destroy", "ps_stack_load_kv", "ps_stack_set_context",
            "ps_stack_set_logits_out", "ps_cpu_matmul", "ps_plan_create_kind", "ps_stack_set_cpu_threads",
-           "ps_tier_table_create_kind", "ps_profile_db_create", "ps_profile_db_destroy", "ps_profile_db_add",
+           "ps_tier_table_create_kind", "ps_tier_table_create_db", "ps_profile_db_create", "ps_profile_db_destroy", "ps_profile_db_add",
            "ps_profile_db_count", "ps_profile_db_get", "ps_profile_db_estimate", "ps_profile_db_save",
            "ps_profile_db_load", "ps_profile_db_measure", "ps_plan_create_db"]
 
@@ -158,6 +158,7 @@ def lib():
             "ps_pack_matrix": [vp, vp, u32, u32, vp],
             "ps_tier_table_create": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, C.POINTER(vp)],
             "ps_tier_table_create_kind": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, u32, C.POINTER(vp)],
+            "ps_tier_table_create_db": [C.POINTER(ps_model_desc), u64, C.POINTER(ps_profile), vp, vp, u32, C.POINTER(vp)],
             "ps_tier_table_entry": [vp, u32, C.POINTER(ps_tier_entry)],
             "ps_profile_db_create": [C.POINTER(vp)],
             "ps_profile_db_add": [vp, C.POINTER(ps_prof_entry)],
@@ -394,13 +395,16 @@ class ProfileDB:
 class TierTable:
     """ps_tier_table_*: one plan per token tier under one budget, and PickTier."""
 
-    def __init__(self, cfg, budget_bytes, profile=None, expert_freq=None, kind=None):
+    def __init__(self, cfg, budget_bytes, profile=None, expert_freq=None, kind=None, db=None):
         self.cfg = cfg
         self.desc = model_desc(cfg)
         self.profile = profile if profile is not None else make_profile()
         self.h = C.c_void_p()
         freq = None if expert_freq is None else np.ascontiguousarray(expert_freq, dtype=np.float32)
-        if kind is None:
+        if db is not None:
+            _check(lib().ps_tier_table_create_db(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), db.h, _ptr(freq),
+                                                 PS_PLAN_GPU_ONLY if kind is None else int(kind), C.byref(self.h)))
+        elif kind is None:
             _check(lib().ps_tier_table_create(C.byref(self.desc), int(budget_bytes), C.byref(self.profile), _ptr(freq),
                                               C.byref(self.h)))
         else:

@@ -691,6 +691,16 @@ int32_t ps_tier_table_create_kind(const ps_model_desc *model, uint64_t budget, c
     return PS_OK;
 }
 
+int32_t ps_tier_table_create_db(const ps_model_desc *model, uint64_t budget, const ps_profile *prof,
+                                const ps_profile_db *db, const float *expert_freq, uint32_t kind,
+                                ps_tier_table **out) {
+    if (!db) { ps::set_error("profile database is NULL"); return PS_E_ARG; }
+    ps::t_db = std::make_shared<const ps_profile_db>(*db);
+    const int32_t rc = ps_tier_table_create_kind(model, budget, prof, expert_freq, kind, out);
+    ps::t_db.reset();
+    return rc;
+}
+
 int32_t ps_tier_table_entry(const ps_tier_table *tb, uint32_t tier, ps_tier_entry *o) {
     if (!tb || !o || tier >= PS_NTIERS) { ps::set_error("bad tier table argument"); return PS_E_ARG; }
     std::memset(o, 0, sizeof *o);

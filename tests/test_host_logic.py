@@ -783,6 +783,42 @@ def test_plans_priced_from_a_profile_database():
     assert a.est_step_ms == pytest.approx(a.streamed_bytes / (1 << 20) * 1.0, rel=0.05) and b.est_step_ms < a.est_step_ms / 50
 
 
+def test_tier_table_priced_from_a_profile_database():
+    # The paper's overview: the install-time profile database feeds the estimator that fills the
+    # (token tier, schedule) table.  Every tier of the table carries the estimate of the plan built for
+    # that tier alone from the same database, and PickTier follows those estimates: with 64-token GEMMs
+    # priced absurdly slow in the database the pick moves off that tier, which the profile alone would take.
+    cfg = dict(_kv_cfg(n_layers=2, ctx=0), kv_context=0)
+    H, I = cfg["hidden"], cfg["ffn_inter"]
+    prof = _cpu_prof(cpu_sync_us=0.0, launch_us=0.0)
+    qkv_rows = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    mats = ((qkv_rows, H), (H, cfg["n_q_heads"] * cfg["head_dim"]), (2 * I, H), (H, I))
+    db = B.ProfileDB()
+    for n, k in mats:
+        db.add(B.PS_OPK_GEMV, 4, 0, n, k, 1, 0.5)
+        for m, ms in ((4, 0.6), (16, 0.7), (32, 0.8), (64, 1000.0), (512, 3.0)):
+            db.add(B.PS_OPK_GEMM, 4, 0, n, k, m, ms)
+    budget = 1 << 34
+    table = B.TierTable(cfg, budget, profile=prof, db=db)
+    plain = B.TierTable(cfg, budget, profile=prof)
+    for e in table.entries():
+        if not e.feasible:
+            continue
+        alone = B.Plan(cfg, budget, e.tier_tokens, profile=prof, kind=B.PS_PLAN_GPU_ONLY, db=db).summary()
+        assert e.summary.est_step_ms == alone.est_step_ms
+    by_tokens = {e.tier_tokens: e.summary.est_step_ms for e in table.entries() if e.feasible}
+    assert by_tokens[1] == pytest.approx(0.5 * 4 * cfg["n_layers"]) and by_tokens[64] == pytest.approx(1000.0 * 4 * cfg["n_layers"])
+    fair = B.ProfileDB()
+    for e in db.entries():
+        fair.add(*e[:6], 0.9 if e[5] == 64 else e[6])
+    assert B.TierTable(cfg, budget, profile=prof, db=fair).pick(64).tier_tokens == 64     # 0.9 x 1 trip < 0.8 x 2 trips
+    assert plain.entry(0).summary.est_step_ms != pytest.approx(by_tokens[1])
+    c = table.pick(64)
+    assert c.tier_tokens == 32 and c.iterations == 2 and c.est_total_ms == pytest.approx(2 * 0.8 * 4 * cfg["n_layers"])
+    with pytest.raises(B.PshardError):     # a NULL database is refused
+        B._check(B.lib().ps_tier_table_create_db(B.C.byref(table.desc), budget, B.C.byref(prof), None, None, 0, B.C.byref(B.C.c_void_p())))
+
+
 # ------------------------------------------------------------------ build-time checks
 
 def _fake_gemm_isa(prologue_wait, step_loads, step_wait):
