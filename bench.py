@@ -254,14 +254,16 @@ def tier_leg(B, S, torch, cfg, seed, prof, budget, tokens, db=None):
     return out
 
 
-def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, decode_mode, db=None):
+def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, decode_mode, db=None, kind=None):
     """The paper's operating mode under ONE budget on ONE stack: the tier table is planned once,
     PickTier chooses the prefill tier for a prompt of `prompt` tokens, the chunked prefill runs (TTFT),
     the one-token tier is installed (SetupForSched: shards that the prefill tier's workspace displaced
     are pinned again from the host images) and `decode_steps` tokens are decoded (TPS)."""
-    table = B.TierTable(cfg, int(budget), profile=prof, db=db)   # the install-time database prices every tier
+    # the install-time database prices every tier; kind = PS_PLAN_AUTO lets HeuristicSplit plan each tier of up to
+    # 64 tokens with a CPU share (prefill then streams through the GPU, decode runs its unpinned FFN on the CPU)
+    table = B.TierTable(cfg, int(budget), profile=prof, db=db, kind=kind)
     choice = table.pick(prompt)
-    by_rates = B.TierTable(cfg, int(budget), profile=prof).pick(prompt)
+    by_rates = B.TierTable(cfg, int(budget), profile=prof, kind=kind).pick(prompt)
     st = B.Stack(table)
     st.set_decode_mode(decode_mode)
     B.load_synthetic([st], cfg, seed, threads=min(16, os.cpu_count() or 8))
@@ -295,11 +297,12 @@ def session_leg(B, S, torch, cfg, seed, prof, budget, prompt, decode_steps, deco
              resident_bytes_prefill_tier=e_pre.summary.resident_bytes, resident_bytes_decode_tier=e_dec.summary.resident_bytes,
              e2el_ms_100_tokens=r["ttft_ms"] + r["setup_decode_ms"] + 100 * r["decode_ms_per_token"],
              estimates="profile database" if db is not None else "profile rates",
+             decode_plan=["gpu_only", "static", "dynamic"][e_dec.summary.plan_kind], decode_cpu_bytes=e_dec.summary.cpu_bytes,
              pick_from_profile_rates_alone=dict(tier_tokens=by_rates.tier_tokens, trips=by_rates.iterations, est_ttft_ms=by_rates.est_total_ms))
     log("one stack, budget %.0f GB: PickTier estimate %.1f ms (from the profile's rates alone it picks %d x %d, %.1f ms)" % (
         budget / 1e9, choice.est_total_ms, by_rates.tier_tokens, by_rates.iterations, by_rates.est_total_ms))
-    log("one stack, budget %.0f GB: prefill %d tokens in tier %d x %d trips: TTFT %.1f ms; switch to the one-token tier %.2f ms (%.1f MB pinned again); decode %.3f ms/token = %.1f tok/s" % (
-        budget / 1e9, prompt, choice.tier_tokens, r["trips"], r["ttft_ms"], r["setup_decode_ms"], r["pinned_again_bytes_decode"] / 1e6,
+    log("one stack, budget %.0f GB: prefill %d tokens in tier %d x %d trips: TTFT %.1f ms; switch to the one-token tier (plan %s) %.2f ms (%.1f MB pinned again); decode %.3f ms/token = %.1f tok/s" % (
+        budget / 1e9, prompt, choice.tier_tokens, r["trips"], r["ttft_ms"], r["decode_plan"], r["setup_decode_ms"], r["pinned_again_bytes_decode"] / 1e6,
         r["decode_ms_per_token"], r["tokens_per_s"]))
     st.close()
     return r
@@ -655,6 +658,9 @@ def main():
     if "session" in args.extra and args.layers == 32:
         extra["prefill_then_decode_one_stack"] = {"%g" % (b / 1e9): session_leg(B, S, torch, cfg, seed, prof, b, 2048, 64 if b > 3e9 else 8, args.decode_mode, db=tier_db)
                                                   for b in (4e9, 2e9)}
+        if prof is not None and prof.cpu_gbps > 0:   # the same at 2 GB with HeuristicSplit planning the low tiers
+            extra["prefill_then_decode_one_stack"]["2_heuristic_split"] = session_leg(B, S, torch, cfg, seed, prof, 2e9, 2048, 16, args.decode_mode,
+                                                                                      db=tier_db, kind=B.PS_PLAN_AUTO)
     fresh()
     if "kv" in args.extra and args.layers == 32:
         extra["decode_context_16k"] = kv_leg(B, S, torch, cfg, seed, prof, 16384, [8e9, 4e9], 50, args.decode_mode)

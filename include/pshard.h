@@ -421,7 +421,9 @@ int32_t ps_stack_create(const ps_plan *plan, void *vram_arena, uint64_t arena_by
                         void *compute_stream, void *copy_stream, ps_stack **out);
 /* One stack for every token tier of a budget (Algorithm 1: the planning phase leaves one schedule
  * per tier; at inference PickTier chooses one, SetupForSched installs it, and the schedule runs).
- * ps_stack_create_tiers binds all feasible tiers of a table (GPU-only plans) to one
+ * ps_stack_create_tiers binds all feasible tiers of a table (any plan kind per tier: a table from
+ * ps_tier_table_create_kind may stream everything through the GPU in its many-token tiers and leave
+ * unpinned shards to the CPU in its low ones; the CPU reads the same host images) to one
  * arena of the table's budget and installs the lowest feasible tier (it pins the most).  Every
  * tier's arena is laid out [pinned shards in priority order | scratch slots | workspace], so a shard
  * that two tiers pin lies at the same place in both, and the library keeps a packed image of every

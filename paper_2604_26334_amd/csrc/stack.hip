@@ -891,9 +891,6 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
     for (const ps_plan *q : plans) {
         if (!q) continue;
         any_slots |= q->n_slots != 0;
-        if (multi && q->cpu_bytes) {
-            ps::set_error("a stack of several tiers takes GPU-only plans"); return PS_E_ARG;
-        }
     }
     if (compute_stream == copy_stream && any_slots) {
         ps::set_error("streamed shards need distinct compute and copy streams"); return PS_E_ARG;
@@ -1006,15 +1003,18 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
         const int32_t rc = bind_plan(st);
         if (rc) return fail(rc);
     }
-    if (p.cpu_bytes) {
+    uint32_t cpu_M = 0;     // most tokens of any plan that leaves shards to the CPU (several tiers: each may)
+    for (const ps_plan *q : plans)
+        if (q && q->cpu_bytes) cpu_M = std::max(cpu_M, q->M);
+    if (cpu_M) {
         if (!ps::cpu_backend_supported()) { ps::set_error("the CPU back-end needs AVX-512 (F, BW, VL, DQ) and F16C"); return fail(PS_E_STATE); }
         const uint32_t H = m.hidden, I = p.g.ffn_i;
         const size_t widest = std::max<size_t>(std::max(H, I), m.vocab);
-        const size_t P = (size_t)p.M * std::max(1u, m.top_k);
+        const size_t P = (size_t)cpu_M * std::max(1u, m.top_k);
         void *bufs[4] = {};
         // host_out doubles as the CPU experts' landing image: fp32 rows [P][H], then P pair numbers
-        const size_t sizes[4] = {(size_t)p.M * H * 2, (size_t)p.M * I * 2, (size_t)p.M * H * 2,
-                                 std::max((size_t)p.M * widest * 2, p.g.moe ? P * H * 4 + P * 4 : 0)};
+        const size_t sizes[4] = {(size_t)cpu_M * H * 2, (size_t)cpu_M * I * 2, (size_t)cpu_M * H * 2,
+                                 std::max((size_t)cpu_M * widest * 2, p.g.moe ? P * H * 4 + P * 4 : 0)};
         if (p.g.moe) { st->cpu_xg.resize(P * H); st->cpu_sg.resize(P * I); }
         for (int b = 0; b < 4; ++b)
             if (hipHostMalloc(&bufs[b], sizes[b], hipHostMallocDefault) != hipSuccess) {
@@ -1023,7 +1023,7 @@ int32_t stack_create_impl(const std::vector<const ps_plan *> &plans, bool multi,
             }
         st->host_h = static_cast<uint16_t *>(bufs[0]); st->host_s = static_cast<uint16_t *>(bufs[1]);
         st->host_x = static_cast<uint16_t *>(bufs[2]); st->host_out = static_cast<uint16_t *>(bufs[3]);
-        st->cpu_scratch.resize(ps::cpu_scratch_floats(p.M, std::max(H, I)));
+        st->cpu_scratch.resize(ps::cpu_scratch_floats(cpu_M, std::max(H, I)));
         const unsigned hw = std::thread::hardware_concurrency();
         st->pool.reset(new ps::CpuPool(std::min(hw ? hw : 4u, 16u)));
     }

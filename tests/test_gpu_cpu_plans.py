@@ -208,3 +208,67 @@ def test_cpu_plans_beside_a_streamed_kv_cache():
             assert s.cpu_bytes > 0
             st.close()
             plan.close()
+
+
+@pytest.mark.parametrize("kind_name", ["static", "dynamic", "auto"])
+def test_one_stack_prefills_on_the_gpu_and_decodes_with_a_cpu_plan(kind_name):
+    """The paper's phase-adaptive use of one budget (Algorithm 1: SetupForSched after PickTier; Section 3,
+    the three plans per tier): a tier table whose low tiers are planned with CPU shares and whose many-token
+    tiers stream everything through the GPU, served by ONE stack.  Prefill runs in a chunk tier (Plan One),
+    the stack switches to the one-token tier (static / dynamic / HeuristicSplit's pick) and decodes; then a
+    second prompt piece goes back through the chunk tier.  Every output against the oracle; the decode steps
+    bit-identical to a stack built for the one-token plan alone."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    kind = {"static": B.PS_PLAN_STATIC, "dynamic": B.PS_PLAN_DYNAMIC, "auto": B.PS_PLAN_AUTO}[kind_name]
+    cfg = Hn.small_dense_cfg(3)
+    W = Hn.WeightCache(cfg, 23)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    full = B.Plan(cfg, 1 << 40, 512).summary()
+    budget = full.workspace_bytes + int(wb * 0.25)     # the 512-token tier streams every matrix; the one-token tier pins most
+    table = B.TierTable(cfg, budget, profile=_prof(B), kind=kind)
+    ents = table.entries()
+    t_dec, t_pre = 0, [e.tier for e in ents if e.feasible and e.tier_tokens == 512][0]
+    assert ents[t_pre].summary.cpu_bytes == 0 and ents[t_pre].summary.streamed_bytes > 0
+    assert ents[t_dec].summary.cpu_bytes > 0 and ents[t_dec].summary.plan_kind == (B.PS_PLAN_STATIC if kind == B.PS_PLAN_AUTO else kind)
+    _say("one-token tier: plan kind %d, %d B on the CPU, %d B streamed; 512-token tier: %d B streamed" % (
+        ents[t_dec].summary.plan_kind, ents[t_dec].summary.cpu_bytes, ents[t_dec].summary.streamed_bytes, ents[t_pre].summary.streamed_bytes))
+    st = B.Stack(table)
+    alone = B.Stack(table.plan(t_dec))
+    for s_ in (st, alone):
+        for layer in range(cfg["n_layers"]):
+            for k, e, N, K in S.matrix_shapes(cfg):
+                s_.load_matrix(layer, k, e, *W(layer, k, e))
+
+    def run(stack, xnp, chunked):
+        xin = torch.from_numpy(np.ascontiguousarray(xnp)).to(stack.device)
+        xout = torch.zeros_like(xin)
+        if chunked:
+            B.chunked_forward(stack, xin, xout)
+        else:
+            stack.forward(xin, xout)
+        stack.synchronize()
+        return xout.cpu().numpy()
+
+    x = S.activations(23, 0, 700, cfg["hidden"])          # two trips, the second ragged
+    st.set_tier(t_pre)
+    e = Hn.rel_err(run(st, x, True), O.stack_forward(x, cfg, W, mirror=True))
+    _say("prefill of 700 tokens in the 512-token tier: err %.2e" % e)
+    assert e <= TOL
+    st.set_tier(t_dec)
+    for t in range(3):
+        xt = S.activations(23, 1 + t, 1, cfg["hidden"])
+        got = run(st, xt, False)
+        e = Hn.rel_err(got, O.stack_forward(xt, cfg, W, mirror=True))
+        _say("  decode step %d in the one-token tier: err %.2e, CPU bytes %d" % (t, e, st.stats().cpu_bytes_step))
+        assert e <= TOL
+        if ents[t_dec].summary.cpu_bytes:
+            assert st.stats().cpu_bytes_step == ents[t_dec].summary.cpu_bytes
+        np.testing.assert_array_equal(got.view(np.uint16), run(alone, xt, False).view(np.uint16))
+    st.set_tier(t_pre)
+    x2 = S.activations(23, 9, 300, cfg["hidden"])
+    e = Hn.rel_err(run(st, x2, True), O.stack_forward(x2, cfg, W, mirror=True))
+    _say("second prompt piece of 300 tokens: err %.2e" % e)
+    assert e <= TOL
+    st.close()
+    alone.close()
