@@ -62,14 +62,18 @@ def _isa(src):
 
 
 def check_resource_usage(remarks):
-    """The compiler's per-kernel resource remarks: matmul and attention kernels use no scratch."""
-    name, bad, seen = None, [], 0
+    """The compiler's per-kernel resource remarks: matmul and attention kernels use no scratch, and the
+    gather copy kernel holds a CU's whole LDS (what keeps matmul workgroups off the CUs it reads PCIe from)."""
+    name, bad, seen, gather_lds = None, [], 0, None
     for ln in remarks.splitlines():
         m = re.search(r"remark: Function Name: (\S+)", ln)
         if m:
             name = m.group(1)
             seen += any(k in name for k in NO_SCRATCH)
             continue
+        m = re.search(r"remark:\s+LDS Size \[bytes/block\]: (\d+)", ln)
+        if m and name and "h2d_gather_kernel" in name:
+            gather_lds = int(m.group(1))
         m = re.search(r"remark:\s+(ScratchSize \[bytes/lane\]|SGPRs Spill|VGPRs Spill): (\d+)", ln)
         if m and name and any(k in name for k in NO_SCRATCH) and int(m.group(2)) != 0:
             bad.append("%s: %s = %s" % (name, m.group(1), m.group(2)))
@@ -77,6 +81,8 @@ def check_resource_usage(remarks):
         raise RuntimeError("build check: no resource-usage remarks for the matmul kernels (compiler flag ignored?)")
     if bad:
         raise RuntimeError("build check: scratch / spills in kernels that must have none:\n  " + "\n  ".join(bad))
+    if gather_lds != 160 * 1024:
+        raise RuntimeError("build check: h2d_gather_kernel allocates %s B of LDS, not the CU's 163840" % gather_lds)
 
 
 def gemm_wait_counts(mt, nw, at=2):

@@ -856,4 +856,11 @@ def test_build_check_of_the_gemm_wait_counts(tmp_path):
                 Bd.check_gemm_isa(str(p))
     with pytest.raises(RuntimeError):
         Bd.check_resource_usage("remark: Function Name: _ZN2ps14gemm_w4_kernelILi0EEE\nremark:     ScratchSize [bytes/lane]: 8 [-R]\n")
-    Bd.check_resource_usage("remark: Function Name: _ZN2ps14gemm_w4_kernelILi0EEE\nremark:     ScratchSize [bytes/lane]: 0 [-R]\n")
+    gather = "remark: Function Name: _ZN2ps17h2d_gather_kernelEPKNS_8CopyDescEj\nremark:     LDS Size [bytes/block]: %d [-R]\n"
+    clean = "remark: Function Name: _ZN2ps14gemm_w4_kernelILi0EEE\nremark:     ScratchSize [bytes/lane]: 0 [-R]\n"
+    Bd.check_resource_usage(clean + gather % 163840)
+    for lds in (3072, 65536):       # the gather kernel no longer holds its CU's whole LDS
+        with pytest.raises(RuntimeError):
+            Bd.check_resource_usage(clean + gather % lds)
+    with pytest.raises(RuntimeError):
+        Bd.check_resource_usage(clean)
