@@ -71,3 +71,54 @@ def test_benchmark_suite_fills_the_database_and_prices_a_plan():
         assert Hn.rel_err(xout.cpu().numpy(), ref) <= 5e-3
         st.close()
         plan.close()
+
+
+def test_tier_table_priced_from_the_measured_database_serves_one_stack():
+    """Overview steps 1-4 in one go: the benchmark suite fills the database, the planning phase prices every
+    tier's schedule from it (HeuristicSplit per tier where the host has the CPU back-end), PickTier chooses
+    the prefill tier from those estimates, and one stack runs the prefill in that tier and a decode step in
+    the one-token tier, each against the oracle."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    cfg = Hn.small_dense_cfg(3)
+    db = B.ProfileDB()
+    db.measure(cfg, scratch_bytes=768 << 20)
+    has_cpu = any(e[0] == B.PS_OPK_CPU for e in db.entries())
+    prof = B.make_profile(h2d_gbps=50.0, gemv_gbps=5000.0, cpu_gbps=150.0 if has_cpu else 0.0, cpu_gbps_busy=140.0 if has_cpu else 0.0,
+                          h2d_gbps_busy=48.0, cpu_sync_us=40.0)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    full = B.Plan(cfg, 1 << 40, 512).summary()
+    budget = full.workspace_bytes + int(wb * 0.25)
+    table = B.TierTable(cfg, budget, profile=prof, db=db, kind=B.PS_PLAN_AUTO if has_cpu else None)
+    ents = [e for e in table.entries() if e.feasible]
+    assert {1, 512} <= {e.tier_tokens for e in ents}
+    for e in ents:   # every tier's estimate is the database-priced plan's
+        alone = B.Plan(cfg, budget, e.tier_tokens, profile=prof, db=db,
+                       kind=B.PS_PLAN_AUTO if (has_cpu and e.tier_tokens <= 64) else B.PS_PLAN_GPU_ONLY).summary()
+        assert e.summary.est_step_ms == alone.est_step_ms and e.summary.est_step_ms > 0
+    n = 600
+    c = table.pick(n)
+    _say("  tiers %s; PickTier for %d tokens: %d x %d trips, estimate %.3f ms" % (
+        [(e.tier_tokens, e.summary.plan_kind, round(e.summary.est_step_ms, 3)) for e in ents], n, c.tier_tokens, c.iterations, c.est_total_ms))
+    best = min(-(-n // e.tier_tokens) * e.summary.est_step_ms for e in ents)
+    assert c.est_total_ms == pytest.approx(best)
+    W = Hn.WeightCache(cfg, 29)
+    st = B.Stack(table)
+    for layer in range(cfg["n_layers"]):
+        for k, e, N, K in S.matrix_shapes(cfg):
+            st.load_matrix(layer, k, e, *W(layer, k, e))
+    x = S.activations(29, 0, n, cfg["hidden"])
+    st.set_tier(c.tier)
+    xin = torch.from_numpy(x).to(st.device)
+    xout = torch.zeros_like(xin)
+    assert B.chunked_forward(st, xin, xout) == c.iterations
+    st.synchronize()
+    assert Hn.rel_err(xout.cpu().numpy(), O.stack_forward(x, cfg, W, mirror=True)) <= 5e-3
+    st.set_tier(0)
+    x1 = S.activations(29, 1, 1, cfg["hidden"])
+    xin = torch.from_numpy(x1).to(st.device)
+    xout = torch.zeros_like(xin)
+    st.forward(xin, xout)
+    st.synchronize()
+    assert Hn.rel_err(xout.cpu().numpy(), O.stack_forward(x1, cfg, W, mirror=True)) <= 5e-3
+    st.close()
