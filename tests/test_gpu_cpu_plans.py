@@ -272,3 +272,60 @@ def test_one_stack_prefills_on_the_gpu_and_decodes_with_a_cpu_plan(kind_name):
     assert e <= TOL
     st.close()
     alone.close()
+
+
+@pytest.mark.parametrize("kind_name", ["static", "dynamic"])
+def test_one_moe_stack_switches_between_tiers_with_cpu_experts(kind_name):
+    """An MoE stack of several tiers whose plans leave experts to the CPU (Plan Two / Plan Three in every tier of
+    up to 64 tokens, each with its own pinned set): a 100-token prompt in the 64-token tier (two trips), decode in
+    the one-token tier, the 16-token tier after that; each against the oracle, decode bit-identical to a stack
+    built for the one-token plan alone."""
+    import torch
+    from paper_2604_26334_amd import binding as B
+    kind = {"static": B.PS_PLAN_STATIC, "dynamic": B.PS_PLAN_DYNAMIC}[kind_name]
+    cfg = Hn.small_moe_cfg(3)
+    L, E = cfg["n_layers"], cfg["n_experts"]
+    W = Hn.WeightCache(cfg, 31)
+    wb, _ = Hn.total_weight_bytes(cfg)
+    budget = B.Plan(cfg, 1 << 40, 64).summary().workspace_bytes + int(wb * 0.3)
+    table = B.TierTable(cfg, budget, profile=_prof(B), kind=kind)
+    ents = {e.tier_tokens: e for e in table.entries() if e.feasible}
+    assert all(ents[t].summary.cpu_bytes > 0 and ents[t].summary.plan_kind == kind for t in (1, 16, 64))
+    assert ents[1].summary.resident_bytes > ents[64].summary.resident_bytes
+    st = B.Stack(table)
+    alone = B.Stack(table.plan(ents[1].tier))
+    for s_ in (st, alone):
+        for layer in range(L):
+            for k, e, N, K in S.matrix_shapes(cfg):
+                s_.load_matrix(layer, k, e, *W(layer, k, e))
+
+    def run(stack, xnp, lg, chunked):
+        xin = torch.from_numpy(np.ascontiguousarray(xnp)).to(stack.device)
+        xout = torch.zeros_like(xin)
+        if chunked:
+            B.chunked_forward(stack, xin, xout, router_logits=lg)
+        else:
+            stack.forward(xin, xout, lg)
+        stack.synchronize()
+        return xout.cpu().numpy()
+
+    x, lg = S.activations(31, 0, 100, cfg["hidden"]), S.router_logits(31, 0, L, 100, E)
+    st.set_tier(ents[64].tier)
+    e = Hn.rel_err(run(st, x, lg, True), O.stack_forward(x, cfg, W, logits=lg, mirror=True))
+    _say("prompt of 100 tokens in the 64-token tier (%d B of experts on the CPU): err %.2e" % (ents[64].summary.cpu_bytes, e))
+    assert e <= TOL
+    st.set_tier(ents[1].tier)
+    for t in range(3):
+        xt, lt = S.activations(31, 1 + t, 1, cfg["hidden"]), S.router_logits(31, 1 + t, L, 1, E)
+        got = run(st, xt, lt, False)
+        e = Hn.rel_err(got, O.stack_forward(xt, cfg, W, logits=lt, mirror=True))
+        _say("  decode step %d in the one-token tier: err %.2e, CPU bytes %d" % (t, e, st.stats().cpu_bytes_step))
+        assert e <= TOL
+        np.testing.assert_array_equal(got.view(np.uint16), run(alone, xt, lt, False).view(np.uint16))
+    st.set_tier(ents[16].tier)
+    x2, l2 = S.activations(31, 9, 16, cfg["hidden"]), S.router_logits(31, 9, L, 16, E)
+    e = Hn.rel_err(run(st, x2, l2, False), O.stack_forward(x2, cfg, W, logits=l2, mirror=True))
+    _say("16 tokens in the 16-token tier: err %.2e" % e)
+    assert e <= TOL
+    st.close()
+    alone.close()
